@@ -1,0 +1,129 @@
+"""CPU oracle for the 2D selective scan (2DMamba Eq. 3, 5, 6; output rule below Eq. 7).
+
+TEST INFRASTRUCTURE ONLY.  The arithmetic lives in ``scan2d_oracle.c`` (plain C loops in
+double precision).  This module compiles it with gcc and wraps it with ctypes on numpy
+arrays.  Nothing here is shared with, or imported by, the GPU library; only tests, the
+smoke check and the benchmark's ``cpu_baseline`` leg may import it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "scan2d_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_scan2d.so")
+
+F32, BF16, F64 = 0, 1, 2
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle (gcc -O2, no fast-math, OpenMP over independent maps)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, ip = ctypes.c_void_p, ctypes.c_int
+        lib.oracle_scan2d_fwd.argtypes = [ip] * 6 + [vp] * 8 + [ip]
+        lib.oracle_scan2d_fwd.restype = ip
+        lib.oracle_scan2d_bwd.argtypes = [ip] * 6 + [vp] * 14 + [ip]
+        lib.oracle_scan2d_bwd.restype = ip
+        lib.oracle_num_procs.restype = ip
+        _lib = lib
+    return _lib
+
+
+def num_procs() -> int:
+    return int(_load().oracle_num_procs())
+
+
+def _storage(dtype: int):
+    if dtype == F32:
+        return np.float32
+    if dtype == BF16:
+        return np.uint16
+    if dtype == F64:
+        return np.float64
+    raise ValueError("dtype must be 0 (fp32), 1 (bf16 bits in uint16) or 2 (double, tests only)")
+
+
+def _chk(a, np_dtype, shape, name, optional=False):
+    if a is None:
+        if optional:
+            return None
+        raise ValueError(f"{name} is required")
+    a = np.ascontiguousarray(a)
+    if a.dtype != np_dtype or tuple(a.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected {np_dtype} {tuple(shape)}, got {a.dtype} {a.shape}")
+    return a
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def scan2d_fwd(x, delta, A, Bm, Cm, Dskip=None, mask=None, dtype=F32, threads=0):
+    """y = 2D selective scan of x.  bf16 tensors are uint16 arrays holding the bf16 bits.
+
+    x, delta: [Bt, Dc, H, W]; A: [Dc, N] fp32; Bm, Cm: [Bt, N, H, W]; Dskip: [Dc] fp32 or None;
+    mask: [Bt, H, W] uint8 (nonzero = background) or None.  Returns y like x.
+    """
+    st = _storage(dtype)
+    x = np.ascontiguousarray(x)
+    Bt, Dc, H, W = x.shape
+    N = np.asarray(A).shape[1]
+    x = _chk(x, st, (Bt, Dc, H, W), "x")
+    delta = _chk(delta, st, (Bt, Dc, H, W), "delta")
+    A = _chk(A, np.float32, (Dc, N), "A")
+    Bm = _chk(Bm, st, (Bt, N, H, W), "Bm")
+    Cm = _chk(Cm, st, (Bt, N, H, W), "Cm")
+    Dskip = _chk(Dskip, np.float32, (Dc,), "Dskip", optional=True)
+    mask = _chk(mask, np.uint8, (Bt, H, W), "mask", optional=True)
+    y = np.empty_like(x)
+    rc = _load().oracle_scan2d_fwd(Bt, Dc, H, W, N, dtype, _ptr(x), _ptr(delta), _ptr(A),
+                                   _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(y),
+                                   int(threads))
+    if rc != 0:
+        raise RuntimeError(f"oracle_scan2d_fwd failed ({rc})")
+    return y
+
+
+def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F32, threads=0):
+    """Gradients (dx, ddelta, dA, dBm, dCm, dDskip) of sum(dy * y); dDskip is None iff Dskip is."""
+    st = _storage(dtype)
+    x = np.ascontiguousarray(x)
+    Bt, Dc, H, W = x.shape
+    N = np.asarray(A).shape[1]
+    x = _chk(x, st, (Bt, Dc, H, W), "x")
+    delta = _chk(delta, st, (Bt, Dc, H, W), "delta")
+    dy = _chk(dy, st, (Bt, Dc, H, W), "dy")
+    A = _chk(A, np.float32, (Dc, N), "A")
+    Bm = _chk(Bm, st, (Bt, N, H, W), "Bm")
+    Cm = _chk(Cm, st, (Bt, N, H, W), "Cm")
+    Dskip = _chk(Dskip, np.float32, (Dc,), "Dskip", optional=True)
+    mask = _chk(mask, np.uint8, (Bt, H, W), "mask", optional=True)
+    dx = np.empty_like(x)
+    ddelta = np.empty_like(x)
+    dA = np.empty((Dc, N), np.float32)
+    dBm = np.empty((Bt, N, H, W), np.float32)
+    dCm = np.empty((Bt, N, H, W), np.float32)
+    dDskip = None if Dskip is None else np.empty((Dc,), np.float32)
+    rc = _load().oracle_scan2d_bwd(Bt, Dc, H, W, N, dtype, _ptr(x), _ptr(delta), _ptr(A),
+                                   _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(dy),
+                                   _ptr(dx), _ptr(ddelta), _ptr(dA), _ptr(dBm), _ptr(dCm),
+                                   _ptr(dDskip), int(threads))
+    if rc != 0:
+        raise RuntimeError(f"oracle_scan2d_bwd failed ({rc})")
+    return dx, ddelta, dA, dBm, dCm, dDskip
