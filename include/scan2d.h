@@ -1,0 +1,119 @@
+/*
+ * scan2d.h -- C ABI of the MI355X (gfx950) 2D selective scan library.
+ *
+ * The operation is the 2D selective scan of 2DMamba (Sec. 3.3, Eq. 3, Eq. 5, Eq. 6 and the
+ * output rule y = C h below Eq. 7; inputs and output as listed at the top of the
+ * supplementary algorithm "2D selective scan": x, Delta, N, A, D, B, C -> y), batched over
+ * Bt batch items and Dc channels.  For every batch item b, channel c and state n:
+ *
+ *     x_eff[i,j] = mask[b,i,j] ? +0 : x[b,c,i,j]
+ *     a[i,j]     = exp(delta[b,c,i,j] * A[c,n])
+ *     u[i,j]     = delta[b,c,i,j] * Bm[b,n,i,j] * x_eff[i,j]
+ *     hhor[i,j]  = a[i,j] * hhor[i,j-1] + u[i,j]          (row scan,    hhor[i,-1] = 0)
+ *     h[i,j]     = a[i,j] * h[i-1,j]   + hhor[i,j]        (column scan, h[-1,j]   = 0)
+ *     y[b,c,i,j] = sum_n Cm[b,n,i,j] * h_n[i,j] + Dskip[c] * x_eff[i,j]
+ *
+ * delta is the already positive step (softplus applied by the caller); A is the negative
+ * real parameter itself.  The N-wide states hhor and h only ever live in registers / LDS.
+ *
+ * ALL POINTERS ARE DEVICE POINTERS owned by the caller.  The library never allocates,
+ * frees or synchronises; every call only enqueues kernels on `stream` (a hipStream_t,
+ * passed as void*; NULL = the default stream) and returns.  Inputs and outputs must not
+ * alias.  Outputs are overwritten, never accumulated into.
+ *
+ * Layouts (dense, row-major, last index fastest):
+ *     x, delta, y, dy, dx, ddelta : [Bt][Dc][H][W]   element type given by desc.dtype
+ *     Bm, Cm                      : [Bt][N][H][W]    element type given by desc.dtype
+ *     dBm, dCm                    : [Bt][N][H][W]    fp32
+ *     A, dA                       : [Dc][N]          fp32
+ *     Dskip, dDskip               : [Dc]             fp32
+ *     mask                        : [Bt][H][W]       uint8, nonzero = background cell
+ * Base pointers must be aligned to 16 bytes.  State, exp and all accumulation are fp32;
+ * bf16 outputs are rounded once, to nearest-even.
+ *
+ * Errors: every entry point returns SCAN2D_OK (0) or a negative code; on error nothing has
+ * been enqueued and no output has been touched.  No exceptions, no abort.
+ * Thread safety: entry points may be called concurrently from several host threads.
+ */
+#ifndef SCAN2D_H_
+#define SCAN2D_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SCAN2D_OK                   =  0,
+    SCAN2D_ERR_NULL_POINTER     = -1,  /* a required pointer is NULL */
+    SCAN2D_ERR_BAD_SHAPE        = -2,  /* a dimension < 1, N > 64, or element count overflow */
+    SCAN2D_ERR_BAD_DTYPE        = -3,
+    SCAN2D_ERR_BAD_FLAGS        = -4,  /* flags must be 0 */
+    SCAN2D_ERR_WORKSPACE_SMALL  = -5,  /* workspace_bytes < scan2d_workspace_bytes() */
+    SCAN2D_ERR_MISALIGNED       = -6,  /* a base pointer is not 16-byte aligned */
+    SCAN2D_ERR_LAUNCH_FAILED    = -7,  /* the HIP runtime refused a launch */
+    SCAN2D_ERR_UNSUPPORTED_DEVICE = -8 /* current device is not gfx950 */
+};
+
+enum { SCAN2D_F32 = 0, SCAN2D_BF16 = 1 };
+enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1 };
+
+typedef struct {
+    int32_t  Bt, Dc, H, W, N;  /* batch, channels, grid height, grid width, states: all >= 1, N <= 64 */
+    int32_t  dtype;            /* SCAN2D_F32 or SCAN2D_BF16: type of x, delta, Bm, Cm, y, dy, dx, ddelta */
+    uint32_t flags;            /* must be 0 */
+} scan2d_desc;
+
+/*
+ * Forward scan (Eq. 5, Eq. 6, y = C h + D x).
+ *   Dskip : may be NULL (no skip term).
+ *   mask  : may be NULL (no background).  A masked cell behaves exactly as x = +0 there,
+ *           whatever is stored in x (a select, so NaN/Inf under the mask cannot leak); the
+ *           decay a still acts on masked cells and y is still produced there.
+ *   workspace : scratch of at least scan2d_workspace_bytes(desc, SCAN2D_PASS_FWD) bytes,
+ *           16-byte aligned; may be NULL when that size is 0.  Contents are undefined after
+ *           the call; two calls that overlap in time must not share a workspace.
+ */
+int scan2d_fwd(const scan2d_desc* desc,
+               const void* x, const void* delta, const float* A,
+               const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+               void* y,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of the forward above for a given dy = dL/dy (Supp. B: two forward scans rebuild
+ * the states, which are never stored by the forward; a reverse column scan and a reverse row
+ * scan carry the gradients).  With g = dL/dh, q = dL/dhhor:
+ *     g[i,j]  = dy[i,j] * Cm[n,i,j] + a[i+1,j] * g[i+1,j]
+ *     q[i,j]  = g[i,j]              + a[i,j+1] * q[i,j+1]
+ *     da[i,j] = g[i,j] * h[i-1,j] + q[i,j] * hhor[i,j-1]
+ *     ddelta  = sum_n (da * a * A[c,n] + q * Bm * x_eff)      dA[c,n] = sum_{b,i,j} da * a * delta
+ *     dBm     = sum_c q * delta * x_eff                       dCm     = sum_c dy * h
+ *     dx      = mask ? +0 : sum_n q * delta * Bm + Dskip[c] * dy
+ *     dDskip  = sum_{b,i,j} dy * x_eff
+ * Gradients are with respect to the arrays as passed.  dDskip must be NULL iff Dskip is NULL.
+ * Reductions use a fixed order: results are bit-reproducible from run to run.
+ */
+int scan2d_bwd(const scan2d_desc* desc,
+               const void* x, const void* delta, const float* A,
+               const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+               const void* dy,
+               void* dx, void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD / _BWD).
+ * Returns 0 for an invalid descriptor (the call itself then reports the error). */
+size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass);
+
+/* Static, never-NULL description of an error code. */
+const char* scan2d_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int scan2d_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCAN2D_H_ */

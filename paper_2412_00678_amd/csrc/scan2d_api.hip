@@ -1,0 +1,215 @@
+// C ABI of the 2D selective scan library: argument validation, variant selection, launches.
+// The operation and every argument are specified in include/scan2d.h.
+#include "../../include/scan2d.h"
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "scan2d_variants.hpp"
+#include "scan2d_bwd.hpp"
+
+namespace scan2d {
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_device_ok[kMaxDevices];   // 0 = unknown, 1 = gfx950, -1 = something else
+
+int check_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SCAN2D_ERR_UNSUPPORTED_DEVICE;
+    if (dev < 0 || dev >= kMaxDevices) return SCAN2D_ERR_UNSUPPORTED_DEVICE;
+    int st = g_device_ok[dev].load(std::memory_order_relaxed);
+    if (st == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return SCAN2D_ERR_UNSUPPORTED_DEVICE;
+        st = (std::strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : -1;
+        g_device_ok[dev].store(st, std::memory_order_relaxed);
+    }
+    return st == 1 ? SCAN2D_OK : SCAN2D_ERR_UNSUPPORTED_DEVICE;
+}
+
+int check_desc(const scan2d_desc* d) {
+    if (d == nullptr) return SCAN2D_ERR_NULL_POINTER;
+    if (d->Bt < 1 || d->Dc < 1 || d->H < 1 || d->W < 1 || d->N < 1 || d->N > 64) return SCAN2D_ERR_BAD_SHAPE;
+    if (d->dtype != SCAN2D_F32 && d->dtype != SCAN2D_BF16) return SCAN2D_ERR_BAD_DTYPE;
+    if (d->flags != 0u) return SCAN2D_ERR_BAD_FLAGS;
+    // element counts must fit 63 bits, and one map's states must be addressable with 32-bit
+    // lane offsets (see fits_offsets below): N * H * W < 2^27 covers every variant
+    const double M = (double)d->Bt * d->Dc * d->H * d->W;
+    const double S = (double)d->Bt * d->N * d->H * d->W;
+    if (M >= 9.0e18 || S >= 9.0e18) return SCAN2D_ERR_BAD_SHAPE;
+    if ((double)d->N * d->H * d->W >= 134217728.0) return SCAN2D_ERR_BAD_SHAPE;
+    return SCAN2D_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ------------------------------------------------------------------ forward variant choice
+struct FwdChoice {
+    int LG = 0, K = 0, NW = 0;
+    bool exact = true, fast = true, multi = false;
+    int NG = 0, MPW = 0, panels = 0;
+    FwdKernel kernel = nullptr;
+};
+
+struct V3 { int LG, K, NW; };
+#define SCAN2D_X(lg, k, nw) {lg, k, nw},
+const V3 kFwdVariants[] = {SCAN2D_FWD_VARIANTS(SCAN2D_X)};
+#undef SCAN2D_X
+
+FwdKernel lookup(int dtype, int LG, int K, int NW, bool exact, bool fast, bool multi) {
+    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, exact, fast, multi)
+                                : fwd_kernel_f32(LG, K, NW, exact, fast, multi);
+}
+
+bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, FwdChoice* out) {
+    const int slots = kThreads / LG;
+    FwdChoice c;
+    c.LG = LG; c.K = K; c.NW = NW;
+    c.exact = (d->N % NW) == 0;
+    c.NG = (d->N + NW - 1) / NW;
+    if (c.NG > slots) return false;
+    c.MPW = slots / c.NG;
+    c.panels = (d->W + LG * K - 1) / (LG * K);
+    c.multi = c.panels > 1;
+    c.fast = !c.multi && (d->W % K) == 0;
+    // 32-bit lane offsets span up to `slots` maps and `slots + 1` batch items of states
+    const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
+    if (span >= 2147483648.0) return false;
+    c.kernel = lookup(d->dtype, LG, K, NW, c.exact, c.fast, c.multi);
+    if (c.kernel == nullptr) return false;
+    *out = c;
+    return true;
+}
+
+// Rough cost in VALU issue slots per (position, channel, state) divided by the fraction of
+// the machine the launch can keep busy; only used to rank variants.
+double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
+    const double maps = (double)d->Bt * d->Dc;
+    const int slots = kThreads / c.LG;
+    const double lane_util = (double)d->W / ((double)c.panels * c.LG * c.K);
+    const double slot_util = (double)(c.MPW * c.NG) / slots * (double)d->N / (c.NG * c.NW);
+    const double steps = c.LG == 64 ? 6.0 : 4.0;
+    double ops = 7.5 + (d->dtype == SCAN2D_BF16 ? 2.0 : 0.0) + 2.0 * (c.K - 1) / c.K + (2.0 * steps + 1.0) / c.K
+               + (6.0 + (c.NG > 1 ? 3.0 : 1.0)) / c.NW;
+    if (!c.fast) ops *= 1.6;
+    if (c.multi) ops += 1.0;
+    const double wgs = std::ceil(maps / c.MPW);
+    const double waves = wgs * 4.0;
+    const double simds = 1024.0;
+    double par;
+    if (waves <= simds) par = waves / simds * 0.8;            // one wave per SIMD hides little latency
+    else if (waves <= 2 * simds) par = 0.8 + 0.2 * (waves - simds) / simds;
+    else par = (waves / (2 * simds)) / std::ceil(waves / (2 * simds));
+    // register pressure of the big variants limits them to one wave per SIMD
+    if (c.K * c.NW > 32 && waves > simds) par = std::min(par, 0.8 * (waves / simds) / std::ceil(waves / simds));
+    return ops / (lane_util * slot_util * par);
+}
+
+int choose_fwd(const scan2d_desc* d, FwdChoice* out) {
+    if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW"
+        int LG = 0, K = 0, NW = 0;
+        if (std::sscanf(env, "%d,%d,%d", &LG, &K, &NW) == 3 && (LG == 16 || LG == 64) && NW >= 1 &&
+            fill_choice(d, LG, K, NW, out))
+            return SCAN2D_OK;
+    }
+    bool found = false;
+    double best = 0.0;
+    for (const V3& v : kFwdVariants) {
+        FwdChoice c;
+        if (!fill_choice(d, v.LG, v.K, v.NW, &c)) continue;
+        const double cost = fwd_cost(d, c);
+        if (!found || cost < best) { best = cost; *out = c; found = true; }
+    }
+    return found ? SCAN2D_OK : SCAN2D_ERR_BAD_SHAPE;
+}
+
+size_t fwd_workspace(const scan2d_desc* d, const FwdChoice& c) {
+    if (!c.multi) return 0;
+    return (size_t)d->Bt * d->Dc * d->N * d->H * sizeof(float);
+}
+
+}  // namespace
+}  // namespace scan2d
+
+using namespace scan2d;
+
+extern "C" int scan2d_fwd(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
+                          const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                          void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!x || !delta || !A || !Bm || !Cm || !y) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(delta) || !aligned16(A) || !aligned16(Bm) || !aligned16(Cm) ||
+        !aligned16(y) || !aligned16(Dskip) || !aligned16(mask) || !aligned16(workspace))
+        return SCAN2D_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    FwdChoice ch;
+    rc = choose_fwd(desc, &ch);
+    if (rc != SCAN2D_OK) return rc;
+    const size_t need = fwd_workspace(desc, ch);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SCAN2D_ERR_WORKSPACE_SMALL;
+
+    FwdArgs a;
+    a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.y = y;
+    a.carry = static_cast<float*>(workspace);
+    a.maps = (long long)desc->Bt * desc->Dc;
+    a.Dc = desc->Dc; a.H = desc->H; a.W = desc->W; a.N = desc->N;
+    a.NG = ch.NG; a.MPW = ch.MPW; a.panels = ch.panels;
+    const long long wgs = (a.maps + ch.MPW - 1) / ch.MPW;
+    if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+extern "C" int scan2d_bwd(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
+                          const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                          const void* dy, void* dx, void* ddelta, float* dA, float* dBm, float* dCm,
+                          float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!x || !delta || !A || !Bm || !Cm || !dy || !dx || !ddelta || !dA || !dBm || !dCm)
+        return SCAN2D_ERR_NULL_POINTER;
+    if ((Dskip == nullptr) != (dDskip == nullptr)) return SCAN2D_ERR_NULL_POINTER;
+    const void* ptrs[] = {x, delta, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, dA, dBm, dCm, dDskip, workspace};
+    for (const void* q : ptrs)
+        if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    return bwd_launch(desc, x, delta, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, dA, dBm, dCm, dDskip,
+                      workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
+    if (check_desc(desc) != SCAN2D_OK) return 0;
+    if (pass == SCAN2D_PASS_FWD) {
+        FwdChoice ch;
+        if (choose_fwd(desc, &ch) != SCAN2D_OK) return 0;
+        return fwd_workspace(desc, ch);
+    }
+    if (pass == SCAN2D_PASS_BWD) return bwd_workspace_bytes(desc);
+    return 0;
+}
+
+extern "C" const char* scan2d_strerror(int code) {
+    switch (code) {
+        case SCAN2D_OK: return "success";
+        case SCAN2D_ERR_NULL_POINTER: return "a required pointer is NULL (or dDskip/Dskip do not match)";
+        case SCAN2D_ERR_BAD_SHAPE: return "bad shape: every dimension must be >= 1, N <= 64, N*H*W < 2^27";
+        case SCAN2D_ERR_BAD_DTYPE: return "dtype must be SCAN2D_F32 or SCAN2D_BF16";
+        case SCAN2D_ERR_BAD_FLAGS: return "flags must be 0";
+        case SCAN2D_ERR_WORKSPACE_SMALL: return "workspace is NULL or smaller than scan2d_workspace_bytes()";
+        case SCAN2D_ERR_MISALIGNED: return "a base pointer is not 16-byte aligned";
+        case SCAN2D_ERR_LAUNCH_FAILED: return "the HIP runtime refused a kernel launch";
+        case SCAN2D_ERR_UNSUPPORTED_DEVICE: return "the current device is not gfx950 (MI355X)";
+        default: return "unknown scan2d error code";
+    }
+}
+
+extern "C" int scan2d_version(void) { return 100; }

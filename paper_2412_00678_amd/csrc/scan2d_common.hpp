@@ -1,0 +1,253 @@
+// Shared device helpers of the gfx950 2D selective scan kernels: storage types, wide loads
+// with 4-byte alignment, bf16 conversion, DPP lane movement and the wave-level scan of
+// (decay-product, state) pairs.  Device code only; nothing here is used by the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace scan2d {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kThreads = 256;   // workgroup size of every scan kernel: 4 wavefronts
+
+struct bf16_t { uint16_t bits; };   // storage tag: upper half of an IEEE fp32
+
+template <typename T> struct Elem;
+template <> struct Elem<float>  { static constexpr int kBytes = 4; };
+template <> struct Elem<bf16_t> { static constexpr int kBytes = 2; };
+
+// 32-bit words that hold K consecutive elements of T (K is a multiple of 4).
+template <typename T, int K> constexpr int words_of() { return K * Elem<T>::kBytes / 4; }
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef u32x4_t u32x4_a4 __attribute__((aligned(4)));
+typedef u32x2_t u32x2_a4 __attribute__((aligned(4)));
+
+// Load WORDS consecutive dwords from a 4-byte aligned address with the widest instructions.
+template <int WORDS>
+__device__ __forceinline__ void load_words(const uint32_t* __restrict__ p, uint32_t* r) {
+    int w = 0;
+#pragma unroll
+    for (; w + 4 <= WORDS; w += 4) {
+        const u32x4_a4 v = *reinterpret_cast<const u32x4_a4*>(p + w);
+        r[w] = v.x; r[w + 1] = v.y; r[w + 2] = v.z; r[w + 3] = v.w;
+    }
+#pragma unroll
+    for (; w + 2 <= WORDS; w += 2) {
+        const u32x2_a4 v = *reinterpret_cast<const u32x2_a4*>(p + w);
+        r[w] = v.x; r[w + 1] = v.y;
+    }
+#pragma unroll
+    for (; w < WORDS; ++w) r[w] = p[w];
+}
+
+template <int WORDS>
+__device__ __forceinline__ void store_words(uint32_t* __restrict__ p, const uint32_t* r) {
+    int w = 0;
+#pragma unroll
+    for (; w + 4 <= WORDS; w += 4) {
+        u32x4_a4 v; v.x = r[w]; v.y = r[w + 1]; v.z = r[w + 2]; v.w = r[w + 3];
+        *reinterpret_cast<u32x4_a4*>(p + w) = v;
+    }
+#pragma unroll
+    for (; w + 2 <= WORDS; w += 2) {
+        u32x2_a4 v; v.x = r[w]; v.y = r[w + 1];
+        *reinterpret_cast<u32x2_a4*>(p + w) = v;
+    }
+#pragma unroll
+    for (; w < WORDS; ++w) p[w] = r[w];
+}
+
+__device__ __forceinline__ uint32_t elem_bits(const float* p)  { return __float_as_uint(*p); }
+__device__ __forceinline__ uint32_t elem_bits(const bf16_t* p) { return p->bits; }
+
+template <typename T, int K>
+__device__ __forceinline__ void put_elem(uint32_t* r, int j, uint32_t bits) {
+    if constexpr (Elem<T>::kBytes == 4) r[j] = bits;
+    else r[j >> 1] |= bits << (16 * (j & 1));
+}
+
+// The K elements [col0, col0+K) of one row; columns >= W read as +0 and are never touched
+// in memory (identity padding: delta = 0 gives a = 1, x = B = C = 0 gives u = 0).
+template <typename T, int K>
+__device__ __forceinline__ void load_row(const T* __restrict__ rowp, int col0, int W, bool vec_ok,
+                                         uint32_t* r) {
+    if (vec_ok && col0 + K <= W) {
+        load_words<words_of<T, K>()>(reinterpret_cast<const uint32_t*>(rowp + col0), r);
+    } else {
+#pragma unroll
+        for (int w = 0; w < words_of<T, K>(); ++w) r[w] = 0u;
+#pragma unroll
+        for (int j = 0; j < K; ++j)
+            if (col0 + j < W) put_elem<T, K>(r, j, elem_bits(rowp + col0 + j));
+    }
+}
+
+// K mask bytes packed 4 per word; columns >= W read as 0 (not background).
+template <int K>
+__device__ __forceinline__ void load_mask(const uint8_t* __restrict__ rowp, int col0, int W, bool vec_ok,
+                                          uint32_t* m) {
+    if (vec_ok && col0 + K <= W) {
+        load_words<K / 4>(reinterpret_cast<const uint32_t*>(rowp + col0), m);
+    } else {
+#pragma unroll
+        for (int w = 0; w < K / 4; ++w) m[w] = 0u;
+#pragma unroll
+        for (int j = 0; j < K; ++j)
+            if (col0 + j < W) m[j >> 2] |= static_cast<uint32_t>(rowp[col0 + j]) << (8 * (j & 3));
+    }
+}
+
+template <int K>
+__device__ __forceinline__ bool mask_bit(const uint32_t* m, int j) {
+    return ((m[j >> 2] >> (8 * (j & 3))) & 0xffu) != 0u;
+}
+
+template <typename T, int K>
+__device__ __forceinline__ float get_elem(const uint32_t* r, int j) {
+    if constexpr (Elem<T>::kBytes == 4) return __uint_as_float(r[j]);
+    else return (j & 1) ? __uint_as_float(r[j >> 1] & 0xffff0000u) : __uint_as_float(r[j >> 1] << 16);
+}
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? ((u >> 16) | 0x40u) : r;
+}
+
+template <typename T> __device__ __forceinline__ uint32_t to_elem_bits(float f) {
+    if constexpr (Elem<T>::kBytes == 4) return __float_as_uint(f);
+    else return f32_to_bf16_bits(f);
+}
+
+__device__ __forceinline__ void store_elem(float* p, float f)  { *p = f; }
+__device__ __forceinline__ void store_elem(bf16_t* p, float f) { p->bits = static_cast<uint16_t>(f32_to_bf16_bits(f)); }
+
+// Write v[0..K) to columns [col0, col0+K) of a row, skipping columns >= W.
+template <typename T, int K>
+__device__ __forceinline__ void store_row(T* __restrict__ rowp, int col0, int W, bool vec_ok, const float* v) {
+    if (vec_ok && col0 + K <= W) {
+        uint32_t r[words_of<T, K>()];
+#pragma unroll
+        for (int w = 0; w < words_of<T, K>(); ++w) r[w] = 0u;
+#pragma unroll
+        for (int j = 0; j < K; ++j) put_elem<T, K>(r, j, to_elem_bits<T>(v[j]));
+        store_words<words_of<T, K>()>(reinterpret_cast<uint32_t*>(rowp + col0), r);
+    } else {
+#pragma unroll
+        for (int j = 0; j < K; ++j)
+            if (col0 + j < W) store_elem(rowp + col0 + j, v[j]);
+    }
+}
+
+// ----------------------------------------------------------------------------- DPP
+// dpp_ctrl names of gfx9 used below: row_shr:n / row_shl:n shift inside a row of 16 lanes,
+// wave_shr:1 / wave_shl:1 shift across the whole wavefront, row_bcast:15 copies lane 15 of
+// each row to the next row, row_bcast:31 copies lane 31 to rows 2 and 3.
+// ------------------------------------------------------------------ group scan (rightwards)
+// Inclusive scan, over the LG lanes of a lane group, of the linear recurrence h <- P*h_in + H.
+// In : per lane, P = product of the decays of its K columns, H = its last local state
+//      computed with zero carry-in.
+// Out: H = state at the lane's last column including everything to its left in the group;
+//      C = that value of the lane to the left (0 for the group's first lane), i.e. the carry
+//      entering this lane.  P is consumed (afterwards: the product of the decays up to and
+//      including this lane inside its DPP row).
+// A lane whose source lane does not exist (or whose row is switched off by row_mask) is not
+// written by a DPP instruction, which is exactly the identity element of the recurrence.
+// Each step is H += P * H[lane-d]; P *= P[lane-d], written as VOP2 instructions with a DPP
+// source so that the lane movement costs no extra instruction.  S independent recurrences
+// are interleaved in one block: that keeps the two wait states the hardware requires between
+// a VALU write of a VGPR and a DPP read of it (explicit s_nop where S is too small).
+#define SCAN2D_SHR(n) " row_shr:" #n " row_mask:0xf bank_mask:0xf\n\t"
+#define SCAN2D_BC15 " row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+#define SCAN2D_BC31 " row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+#define SCAN2D_CIN16 " row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+#define SCAN2D_CIN64 " wave_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+
+#define SCAN2D_S1_STEP(M) "v_fmac_f32_dpp %0, %0, %1" M "v_mul_f32_dpp %1, %1, %1" M "s_nop 0\n\t"
+#define SCAN2D_S1_LAST(M) "v_fmac_f32_dpp %0, %0, %1" M "s_nop 1\n\t"
+#define SCAN2D_S2_STEP(M) "v_fmac_f32_dpp %0, %0, %2" M "v_fmac_f32_dpp %1, %1, %3" M \
+                          "v_mul_f32_dpp %2, %2, %2" M "v_mul_f32_dpp %3, %3, %3" M
+#define SCAN2D_S2_LAST(M) "v_fmac_f32_dpp %0, %0, %2" M "v_fmac_f32_dpp %1, %1, %3" M "s_nop 0\n\t"
+#define SCAN2D_S4_STEP(M) "v_fmac_f32_dpp %0, %0, %4" M "v_fmac_f32_dpp %1, %1, %5" M \
+                          "v_fmac_f32_dpp %2, %2, %6" M "v_fmac_f32_dpp %3, %3, %7" M \
+                          "v_mul_f32_dpp %4, %4, %4" M "v_mul_f32_dpp %5, %5, %5" M   \
+                          "v_mul_f32_dpp %6, %6, %6" M "v_mul_f32_dpp %7, %7, %7" M
+#define SCAN2D_S4_LAST(M) "v_fmac_f32_dpp %0, %0, %4" M "v_fmac_f32_dpp %1, %1, %5" M \
+                          "v_fmac_f32_dpp %2, %2, %6" M "v_fmac_f32_dpp %3, %3, %7" M
+
+template <int LG>
+__device__ __forceinline__ void group_scan1(float& P0, float& H0, float& C0) {
+    C0 = 0.0f;
+    if constexpr (LG == 16) {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_LAST(SCAN2D_SHR(8))
+                     "v_mov_b32_dpp %2, %0" SCAN2D_CIN16
+                     : "+v"(H0), "+v"(P0), "+v"(C0));
+    } else {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_STEP(SCAN2D_SHR(8))
+                     SCAN2D_S1_STEP(SCAN2D_BC15) SCAN2D_S1_LAST(SCAN2D_BC31)
+                     "v_mov_b32_dpp %2, %0" SCAN2D_CIN64
+                     : "+v"(H0), "+v"(P0), "+v"(C0));
+    }
+}
+
+template <int LG>
+__device__ __forceinline__ void group_scan2(float& P0, float& P1, float& H0, float& H1, float& C0, float& C1) {
+    C0 = 0.0f; C1 = 0.0f;
+    if constexpr (LG == 16) {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_LAST(SCAN2D_SHR(8))
+                     "v_mov_b32_dpp %4, %0" SCAN2D_CIN16 "v_mov_b32_dpp %5, %1" SCAN2D_CIN16
+                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "+v"(C0), "+v"(C1));
+    } else {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_STEP(SCAN2D_SHR(8))
+                     SCAN2D_S2_STEP(SCAN2D_BC15) SCAN2D_S2_LAST(SCAN2D_BC31)
+                     "v_mov_b32_dpp %4, %0" SCAN2D_CIN64 "v_mov_b32_dpp %5, %1" SCAN2D_CIN64
+                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "+v"(C0), "+v"(C1));
+    }
+}
+
+template <int LG>
+__device__ __forceinline__ void group_scan4(float& P0, float& P1, float& P2, float& P3,
+                                            float& H0, float& H1, float& H2, float& H3,
+                                            float& C0, float& C1, float& C2, float& C3) {
+    C0 = 0.0f; C1 = 0.0f; C2 = 0.0f; C3 = 0.0f;
+    if constexpr (LG == 16) {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S4_STEP(SCAN2D_SHR(4)) SCAN2D_S4_LAST(SCAN2D_SHR(8))
+                     "v_mov_b32_dpp %8, %0" SCAN2D_CIN16 "v_mov_b32_dpp %9, %1" SCAN2D_CIN16
+                     "v_mov_b32_dpp %10, %2" SCAN2D_CIN16 "v_mov_b32_dpp %11, %3" SCAN2D_CIN16
+                     : "+v"(H0), "+v"(H1), "+v"(H2), "+v"(H3), "+v"(P0), "+v"(P1), "+v"(P2), "+v"(P3),
+                       "+v"(C0), "+v"(C1), "+v"(C2), "+v"(C3));
+    } else {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S4_STEP(SCAN2D_SHR(4)) SCAN2D_S4_STEP(SCAN2D_SHR(8))
+                     SCAN2D_S4_STEP(SCAN2D_BC15) SCAN2D_S4_LAST(SCAN2D_BC31)
+                     "v_mov_b32_dpp %8, %0" SCAN2D_CIN64 "v_mov_b32_dpp %9, %1" SCAN2D_CIN64
+                     "v_mov_b32_dpp %10, %2" SCAN2D_CIN64 "v_mov_b32_dpp %11, %3" SCAN2D_CIN64
+                     : "+v"(H0), "+v"(H1), "+v"(H2), "+v"(H3), "+v"(P0), "+v"(P1), "+v"(P2), "+v"(P3),
+                       "+v"(C0), "+v"(C1), "+v"(C2), "+v"(C3));
+    }
+}
+
+// Scan S (1, 2 or 4) recurrences held in arrays.
+template <int LG, int S>
+__device__ __forceinline__ void group_scan(float* P, float* H, float* C) {
+    if constexpr (S == 1) group_scan1<LG>(P[0], H[0], C[0]);
+    else if constexpr (S == 2) group_scan2<LG>(P[0], P[1], H[0], H[1], C[0], C[1]);
+    else group_scan4<LG>(P[0], P[1], P[2], P[3], H[0], H[1], H[2], H[3], C[0], C[1], C[2], C[3]);
+}
+
+}  // namespace scan2d

@@ -1,0 +1,217 @@
+// Forward 2D selective scan kernel for gfx950 (2DMamba Eq. 3, Eq. 5, Eq. 6, y = C h + D x).
+//
+// Work decomposition (differs from the paper's sequential 2D tiles with carries in HBM):
+//   * a "lane group" of LG lanes (LG = 16: one DPP row, LG = 64: a wavefront) owns a panel of
+//     LG*K consecutive columns; lane l owns the K columns [l*K, l*K+K) and NW of the N states;
+//   * the group walks down the rows.  The column recurrence (Eq. 6) is a plain FMA on
+//     registers that persist from row to row, so the N-wide state never leaves VGPRs;
+//   * the row recurrence (Eq. 5) is a serial chain over the lane's K columns plus one
+//     log-step DPP scan of the per-lane (decay product, state) pairs across the group;
+//   * a map uses NG = N / NW lane groups; their partial sums over states meet in LDS, one
+//     barrier per row, and are summed in a fixed order;
+//   * inputs of row i+1 are requested while row i is computed (a raw register is refilled
+//     as soon as its content has been consumed).
+// Maps wider than one panel are processed panel by panel, left to right; the row-end states
+// of a panel travel to the next one through a small carry buffer (N floats per row).
+#pragma once
+
+#include "scan2d_common.hpp"
+
+namespace scan2d {
+
+struct FwdArgs {
+    const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
+    const float* Dskip; const uint8_t* mask; void* y;
+    float* carry;        // [maps][N][H] row-end states between column panels (panels > 1 only)
+    long long maps;      // Bt * Dc
+    int Dc, H, W, N;
+    int NG;              // lane groups per map = ceil(N / NW)
+    int MPW;             // maps per workgroup = (256 / LG) / NG, >= 1
+    int panels;          // ceil(W / (LG * K))
+};
+
+// FAST: W is a multiple of K and every row starts 4-byte aligned, so a lane is either fully
+// inside the map (one wide load per tensor) or fully outside (it then re-reads the columns of
+// lane 0 and its results are discarded).  Otherwise every element access is guarded.
+// MULTI: the map is wider than one panel (p.panels > 1); single-panel kernels carry no code
+// for the panel hand-over.
+template <typename T, int LG, int K, int NW, bool EXACT, bool FAST, bool MULTI>
+__global__ __launch_bounds__(kThreads) void scan2d_fwd_kernel(const FwdArgs p) {
+    constexpr int SLOTS = kThreads / LG;
+    constexpr int XW = words_of<T, K>();
+    constexpr int PANEL = LG * K;
+    constexpr int SC = (NW < 4 ? NW : (K >= 12 ? 2 : 4));   // states scanned together
+    static_assert(NW % SC == 0, "state chunking");
+    __shared__ float ypart[2][SLOTS][PANEL];
+
+    const int tid = threadIdx.x;
+    const int slot = tid / LG;
+    const int l = tid % LG;
+    const int NG = p.NG;
+    int map_local = slot / NG;
+    const int sg = slot - map_local * NG;
+    const long long map0 = (long long)blockIdx.x * p.MPW;
+    const bool live = (map_local < p.MPW) && (map0 + map_local < p.maps);
+    if (!live) map_local = 0;                     // idle group: valid addresses, no writes
+    const long long map = map0 + map_local;
+
+    const int H = p.H, W = p.W, N = p.N;
+    const size_t HW = (size_t)H * W;
+    const int b0 = (int)(map0 / p.Dc);
+    const int b = (int)(map / p.Dc), c = (int)(map % p.Dc);
+    const int n0 = sg * NW;
+    const int nvalid = EXACT ? NW : min(NW, N - n0);
+
+    // Uniform bases (scalar registers) + 32-bit per-lane element offsets.
+    const T* __restrict__ xu = reinterpret_cast<const T*>(p.x) + (size_t)map0 * HW;
+    const T* __restrict__ du = reinterpret_cast<const T*>(p.delta) + (size_t)map0 * HW;
+    T* __restrict__ yu = reinterpret_cast<T*>(p.y) + (size_t)map0 * HW;
+    const T* __restrict__ Bu = reinterpret_cast<const T*>(p.Bm) + (size_t)b0 * N * HW;
+    const T* __restrict__ Cu = reinterpret_cast<const T*>(p.Cm) + (size_t)b0 * N * HW;
+    const uint8_t* __restrict__ mu = p.mask ? p.mask + (size_t)b0 * HW : nullptr;
+    const uint32_t xlane = (uint32_t)(map_local * HW);
+    const uint32_t slane = (uint32_t)(((size_t)(b - b0) * N + n0) * HW);
+    const uint32_t mlane = (uint32_t)((size_t)(b - b0) * HW);
+
+    float Ap[NW];
+#pragma unroll
+    for (int s = 0; s < NW; ++s) {
+        const int n = (EXACT || s < nvalid) ? n0 + s : n0;
+        Ap[s] = p.A[(size_t)c * N + n] * kLog2e;             // a = exp2(delta * A * log2 e)
+    }
+    const float dsk = (p.Dskip != nullptr && sg == 0) ? p.Dskip[c] : 0.0f;
+    const bool reduce = NG > 1;
+
+    int step = 0;   // rows processed so far: its parity selects the LDS buffer
+    const int panels = MULTI ? p.panels : 1;
+    for (int panel = 0; panel < panels; ++panel) {
+        if (panel > 0) __threadfence();           // row-end states of the previous panel are visible
+        const int col0 = panel * PANEL + l * K;
+        const bool inside = col0 < W;
+        const uint32_t lcol = (FAST && !inside) ? 0u : (uint32_t)col0;   // FAST: idle lanes mirror lane 0
+
+        float h[NW][K];
+#pragma unroll
+        for (int s = 0; s < NW; ++s)
+#pragma unroll
+            for (int j = 0; j < K; ++j) h[s][j] = 0.0f;       // h[-1, j] = 0
+
+        uint32_t rx[XW], rd[XW], rm[K / 4], rB[NW][XW], rC[NW][XW];
+        auto ld = [&](const T* base, uint32_t lane_off, uint32_t* r) {
+            if constexpr (FAST) load_words<XW>(reinterpret_cast<const uint32_t*>(base + (lane_off + lcol)), r);
+            else load_row<T, K>(base + lane_off, col0, W, false, r);
+        };
+        auto ldm = [&](const uint8_t* base, uint32_t* r) {
+            if constexpr (FAST) load_words<K / 4>(reinterpret_cast<const uint32_t*>(base + (mlane + lcol)), r);
+            else load_mask<K>(base + mlane, col0, W, false, r);
+        };
+        ld(xu, xlane, rx);
+        ld(du, xlane, rd);
+#pragma unroll
+        for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
+        if (mu) ldm(mu, rm);
+        // State s of this lane group: uniform offset s*HW when every group is full; otherwise a
+        // per-lane offset, with the idle states of a ragged last group re-reading state n0.
+        auto lds = [&](const T* base, int s, size_t row_off, uint32_t* r) {
+            if constexpr (EXACT) ld(base + (size_t)s * HW + row_off, slane, r);
+            else ld(base + row_off, slane + (uint32_t)((s < nvalid ? s : 0) * HW), r);
+        };
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            lds(Bu, s, 0, rB[s]);
+            lds(Cu, s, 0, rC[s]);
+        }
+
+        for (int i = 0; i < H; ++i, ++step) {
+            const size_t nxt = (size_t)(i + 1 < H ? i + 1 : i) * W;   // the last row re-reads itself
+            float dl[K], dx[K], yacc[K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                dl[j] = get_elem<T, K>(rd, j);
+                const float xv = get_elem<T, K>(rx, j);
+                const float xe = mask_bit<K>(rm, j) ? 0.0f : xv;      // select: nothing under the mask leaks
+                dx[j] = dl[j] * xe;
+                yacc[j] = dsk * xe;
+            }
+            ld(xu + nxt, xlane, rx);
+            ld(du + nxt, xlane, rd);
+            if (mu) ldm(mu + nxt, rm);
+
+#pragma unroll
+            for (int s0 = 0; s0 < NW; s0 += SC) {
+                if (EXACT || s0 < nvalid) {       // a ragged last group idles whole chunks only when SC divides
+                    float a[SC][K], hl[SC][K], pl[SC][K];
+                    float P[SC], Hh[SC], cin[SC];
+#pragma unroll
+                    for (int t = 0; t < SC; ++t) {
+                        const int s = s0 + t;
+#pragma unroll
+                        for (int j = 0; j < K; ++j) a[t][j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
+                        hl[t][0] = dx[0] * get_elem<T, K>(rB[s], 0);
+                        pl[t][0] = a[t][0];
+                        if (MULTI && panel > 0 && l == 0) {   // state entering from the panel to the left
+                            const float* cw = p.carry + ((size_t)map * N + n0 + ((EXACT || s < nvalid) ? s : 0)) * H + i;
+                            hl[t][0] = fmaf(a[t][0], __hip_atomic_load(cw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), hl[t][0]);
+                        }
+#pragma unroll
+                        for (int j = 1; j < K; ++j) {
+                            hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dx[j] * get_elem<T, K>(rB[s], j));
+                            pl[t][j] = pl[t][j - 1] * a[t][j];
+                        }
+                        lds(Bu, s, nxt, rB[s]);
+                        P[t] = pl[t][K - 1];
+                        Hh[t] = hl[t][K - 1];
+                    }
+                    group_scan<LG, SC>(P, Hh, cin);
+#pragma unroll
+                    for (int t = 0; t < SC; ++t) {
+                        const int s = s0 + t;
+                        if (MULTI && panel + 1 < p.panels && l == LG - 1 && live && (EXACT || s < nvalid)) {
+                            float* cw = p.carry + ((size_t)map * N + n0 + s) * H + i;
+                            __hip_atomic_store(cw, Hh[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                        const float cmul = (EXACT || s < nvalid) ? 1.0f : 0.0f;   // idle state adds nothing to y
+#pragma unroll
+                        for (int j = 0; j < K; ++j) {
+                            // Eq. 5; at the lane's last column the scan result is the state itself
+                            const float hh = (j == K - 1) ? Hh[t] : fmaf(pl[t][j], cin[t], hl[t][j]);
+                            h[s][j] = fmaf(a[t][j], h[s][j], hh);                       // Eq. 6
+                            const float cv = EXACT ? get_elem<T, K>(rC[s], j) : cmul * get_elem<T, K>(rC[s], j);
+                            yacc[j] = fmaf(cv, h[s][j], yacc[j]);
+                        }
+                        lds(Cu, s, nxt, rC[s]);
+                    }
+                }
+            }
+
+            T* yrow = yu + (size_t)i * W;
+            if (!reduce) {
+                if (live) {
+                    if constexpr (FAST) {
+                        if (inside) store_row<T, K>(yrow + xlane, col0, col0 + K, true, yacc);
+                    } else {
+                        store_row<T, K>(yrow + xlane, col0, W, false, yacc);
+                    }
+                }
+            } else {
+                float* mine = &ypart[step & 1][slot][l * K];
+#pragma unroll
+                for (int j = 0; j < K; ++j) mine[j] = yacc[j];
+                __syncthreads();
+                if (live) {
+                    const float* base = &ypart[step & 1][slot - sg][0];   // first group of this map
+                    for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
+                        const int gc = panel * PANEL + col;
+                        if (gc < W) {
+                            float acc = base[col];
+                            for (int g = 1; g < NG; ++g) acc += base[g * PANEL + col];
+                            store_elem(yrow + xlane + gc, acc);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace scan2d

@@ -1,0 +1,185 @@
+"""Thin ctypes binding of the C-ABI library `libscan2d.so` (see include/scan2d.h).
+
+Argument marshalling only: every step of the scan runs in the HIP kernels.  PyTorch is used
+for device memory and the current stream, nothing else.  Importing this module loads the
+shared library and raises if it has not been built (there is no fallback path).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libscan2d.so")
+
+F32, BF16 = 0, 1
+PASS_FWD, PASS_BWD = 0, 1
+
+EXPORTS = ("scan2d_fwd", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_strerror", "scan2d_version")
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("Bt", ctypes.c_int32), ("Dc", ctypes.c_int32), ("H", ctypes.c_int32),
+                ("W", ctypes.c_int32), ("N", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+
+class Scan2dError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where} failed with code {code}: {strerror(code)}")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2412_00678_amd.build` "
+            "(there is no CPU or PyTorch fallback for the scan)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp = ctypes.c_void_p
+    lib.scan2d_fwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_fwd.restype = ctypes.c_int
+    lib.scan2d_bwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 14 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_bwd.restype = ctypes.c_int
+    lib.scan2d_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.c_int]
+    lib.scan2d_workspace_bytes.restype = ctypes.c_size_t
+    lib.scan2d_strerror.argtypes = [ctypes.c_int]
+    lib.scan2d_strerror.restype = ctypes.c_char_p
+    lib.scan2d_version.restype = ctypes.c_int
+    return lib
+
+
+lib = _load()
+
+
+def strerror(code: int) -> str:
+    return lib.scan2d_strerror(int(code)).decode()
+
+
+def version() -> int:
+    return int(lib.scan2d_version())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"x must be float32 or bfloat16, got {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _check(t: Optional[torch.Tensor], name: str, dtype, shape, optional=False):
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name} is required")
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+
+
+def make_desc(x: torch.Tensor, A: torch.Tensor) -> Desc:
+    Bt, Dc, H, W = x.shape
+    return Desc(Bt, Dc, H, W, A.shape[1], _dtype_code(x), 0)
+
+
+def workspace_bytes(desc: Desc, which: int) -> int:
+    return int(lib.scan2d_workspace_bytes(ctypes.byref(desc), which))
+
+
+def _workspace(desc: Desc, which: int, device) -> Tuple[Optional[torch.Tensor], int]:
+    n = workspace_bytes(desc, which)
+    if n == 0:
+        return None, 0
+    return torch.empty(n, dtype=torch.uint8, device=device), n
+
+
+def _stream_ptr() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def scan2d_fwd(x, delta, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None):
+    """y = 2D selective scan; enqueued on torch's current stream.  Returns y (allocated if None)."""
+    desc = make_desc(x, A)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(delta, "delta", x.dtype, (Bt, Dc, H, W))
+    _check(A, "A", torch.float32, (Dc, N))
+    _check(Bm, "Bm", x.dtype, (Bt, N, H, W))
+    _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    if y is None:
+        y = torch.empty_like(x)
+    _check(y, "y", x.dtype, (Bt, Dc, H, W))
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_FWD, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    rc = lib.scan2d_fwd(ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm),
+                        _ptr(Dskip), _ptr(mask), _ptr(y), _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_fwd")
+    return y
+
+
+def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None):
+    """Gradients (dx, ddelta, dA, dBm, dCm, dDskip) of sum(dy * y); dDskip is None iff Dskip is."""
+    desc = make_desc(x, A)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(delta, "delta", x.dtype, (Bt, Dc, H, W))
+    _check(dy, "dy", x.dtype, (Bt, Dc, H, W))
+    _check(A, "A", torch.float32, (Dc, N))
+    _check(Bm, "Bm", x.dtype, (Bt, N, H, W))
+    _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    dx = torch.empty_like(x)
+    ddelta = torch.empty_like(x)
+    dA = torch.empty((Dc, N), dtype=torch.float32, device=x.device)
+    dBm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dCm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dDskip = None if Dskip is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_BWD, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    rc = lib.scan2d_bwd(ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm),
+                        _ptr(Dskip), _ptr(mask), _ptr(dy), _ptr(dx), _ptr(ddelta), _ptr(dA),
+                        _ptr(dBm), _ptr(dCm), _ptr(dDskip), _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_bwd")
+    return dx, ddelta, dA, dBm, dCm, dDskip
+
+
+def to_device(arrs: dict, dtype_code: int, device="cuda:0") -> dict:
+    """numpy tensors of a workload (bf16 as uint16 bit patterns) -> device tensors."""
+    import numpy as np
+
+    out = {}
+    for k, v in arrs.items():
+        if v is None:
+            out[k] = None
+        elif v.dtype == np.uint16 and dtype_code == BF16:
+            out[k] = torch.from_numpy(v.view(np.int16)).to(device).view(torch.bfloat16)
+        else:
+            out[k] = torch.from_numpy(v).to(device)
+    return out
+
+
+def to_host(t: torch.Tensor):
+    """Device tensor -> numpy (bf16 comes back as its uint16 bit patterns)."""
+    import numpy as np
+
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()

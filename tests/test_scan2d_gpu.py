@@ -1,0 +1,189 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances (per output tensor): max|gpu - ref| / max|ref| <= 1e-4 for fp32
+storage and <= 2e-2 for bf16 storage; mask and indexing properties are bit-exact."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2412_00678_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {wl.F32: 1e-4, wl.BF16: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def s2d():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2412_00678_amd import scan2d          # raises if the library is not built
+    return scan2d
+
+
+def rel_err(got, ref):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    denom = max(np.abs(ref).max(), 1e-30)
+    return float(np.abs(got - ref).max() / denom)
+
+
+def run_fwd(s2d, inp, dtype, variant=None):
+    import torch
+    d = s2d.to_device(inp, dtype)
+    old = os.environ.pop("SCAN2D_FWD_VARIANT", None)
+    if variant is not None:
+        os.environ["SCAN2D_FWD_VARIANT"] = variant
+    try:
+        y = s2d.scan2d_fwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("SCAN2D_FWD_VARIANT", None)
+        if old is not None:
+            os.environ["SCAN2D_FWD_VARIANT"] = old
+    return s2d.to_host(y)
+
+
+def oracle_fwd(inp, dtype):
+    return oracle.scan2d_fwd(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"],
+                             inp["mask"], dtype=dtype)
+
+
+def check_fwd(s2d, w, seed=0, variant=None, tol=None):
+    inp = wl.make_inputs(w, seed=seed)
+    print(f"fwd case {w.name} Bt={w.Bt} Dc={w.Dc} N={w.N} H={w.H} W={w.W} dtype={w.dtype} variant={variant}", flush=True)
+    y = run_fwd(s2d, inp, w.dtype, variant)
+    ref = oracle_fwd(inp, w.dtype)
+    err = rel_err(wl.to_float(y, w.dtype), wl.to_float(ref, w.dtype))
+    assert np.isfinite(wl.to_float(y, w.dtype)).all()
+    assert err <= (tol or TOL[w.dtype]), f"{w.name}: rel err {err:.3e}"
+    return err
+
+
+# ------------------------------------------------------------------ the benchmark configurations
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_forward_matches_oracle_on_benchmark_configs(s2d, idx):
+    check_fwd(s2d, wl.CONFIGS[idx])
+
+
+# ------------------------------------------------------------------ shapes, tails, degenerate cases
+
+SHAPES = [
+    # Bt, Dc, N, H, W, dtype, mask
+    (1, 3, 4, 1, 1, wl.F32, 0.0),          # single cell
+    (2, 3, 4, 1, 37, wl.F32, 0.3),         # H = 1: the 1D scan
+    (2, 3, 4, 29, 1, wl.BF16, 0.3),        # W = 1
+    (1, 5, 16, 14, 14, wl.BF16, 0.0),      # the paper's typical small map: ragged lanes
+    (3, 7, 16, 56, 56, wl.F32, 0.0),
+    (1, 2, 16, 200, 200, wl.BF16, 0.4),    # the paper's largest timed map
+    (1, 3, 5, 23, 45, wl.F32, 0.2),        # N not divisible by the states per lane
+    (1, 2, 64, 17, 33, wl.BF16, 0.2),      # maximum N
+    (1, 2, 1, 19, 64, wl.F32, 0.0),        # N = 1
+    (2, 2, 8, 9, 260, wl.F32, 0.3),        # one column past a 256-wide panel
+    (1, 2, 4, 5, 1100, wl.BF16, 0.3),      # several panels
+    (1, 1, 16, 300, 12, wl.F32, 0.5),      # tall and narrow
+    (5, 1, 16, 20, 24, wl.BF16, 0.3),      # one channel: every map is another batch item
+    (1, 40, 16, 16, 128, wl.F32, 0.0),
+    (1, 9, 16, 33, 192, wl.F32, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_forward_edge_shapes(s2d, shape):
+    Bt, Dc, N, H, W, dtype, mf = shape
+    check_fwd(s2d, wl.Workload("edge", Bt, Dc, N, H, W, dtype, mask_frac=mf), seed=3)
+
+
+VARIANT_CASES = [
+    # (LG, K, NW) forced on a shape it fits: W multiple of K, N multiple of NW
+    ("16,4,1", (1, 6, 4, 21, 64)), ("16,4,2", (1, 6, 4, 21, 48)), ("16,4,4", (2, 5, 16, 21, 56)),
+    ("16,4,8", (1, 6, 16, 21, 64)), ("16,4,16", (1, 9, 16, 21, 60)),
+    ("16,8,1", (1, 6, 2, 21, 128)), ("16,8,2", (1, 6, 4, 21, 120)), ("16,8,4", (1, 6, 16, 21, 128)),
+    ("16,8,8", (1, 6, 16, 21, 96)),
+    ("16,12,1", (1, 6, 2, 13, 192)), ("16,12,2", (1, 6, 4, 13, 180)), ("16,12,4", (1, 6, 16, 13, 192)),
+    ("16,16,1", (1, 6, 2, 13, 256)), ("16,16,2", (1, 6, 4, 13, 240)), ("16,16,4", (1, 6, 16, 13, 256)),
+    ("64,4,1", (1, 6, 4, 13, 256)), ("64,4,2", (1, 6, 4, 13, 200)), ("64,4,4", (1, 6, 16, 13, 256)),
+    ("64,4,8", (1, 6, 16, 13, 252)), ("64,4,16", (1, 6, 32, 13, 256)),
+    ("64,8,1", (1, 6, 2, 13, 512)), ("64,8,2", (1, 6, 4, 13, 504)), ("64,8,4", (1, 6, 16, 13, 512)),
+    ("64,8,8", (1, 6, 16, 13, 400)),
+    ("64,16,1", (1, 6, 2, 9, 1024)), ("64,16,2", (1, 6, 4, 9, 1008)), ("64,16,4", (1, 6, 16, 9, 1024)),
+    # guarded (ragged W) and multi-panel forms of the K = 4 variants
+    ("16,4,4", (1, 6, 16, 9, 61)), ("64,4,4", (1, 6, 16, 9, 203)), ("64,4,2", (1, 3, 4, 7, 777)),
+    ("16,4,4", (1, 3, 16, 7, 150)), ("16,4,4", (1, 3, 10, 7, 150)), ("16,8,4", (1, 3, 10, 7, 128)),
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("variant,shape", VARIANT_CASES, ids=[f"{v}-{s[4]}-{s[2]}" for v, s in VARIANT_CASES])
+def test_every_kernel_variant(s2d, variant, shape, dtype):
+    Bt, Dc, N, H, W = shape
+    check_fwd(s2d, wl.Workload("var", Bt, Dc, N, H, W, dtype, mask_frac=0.25), seed=5, variant=variant)
+
+
+# ------------------------------------------------------------------ mask / indexing: bit-exact
+
+def test_mask_is_bit_identical_to_prezeroed_x_and_blocks_garbage(s2d):
+    for dtype in (wl.F32, wl.BF16):
+        w = wl.Workload("mask", 2, 6, 16, 40, 72, dtype, mask_frac=0.4)
+        inp = wl.make_inputs(w, seed=7)
+        y_mask = run_fwd(s2d, inp, dtype)
+        nomask = dict(inp, mask=None)                     # x is already +0 under the mask
+        assert np.array_equal(y_mask, run_fwd(s2d, nomask, dtype))
+        for poison in (np.nan, np.inf, 1e30):
+            p = wl.make_inputs(w, seed=7, poison_under_mask=poison)
+            assert np.array_equal(y_mask, run_fwd(s2d, p, dtype)), poison
+        full = dict(inp, mask=np.ones_like(inp["mask"]))
+        assert not wl.to_float(run_fwd(s2d, full, dtype), dtype).any()
+
+
+def test_causality_is_bit_exact(s2d):
+    w = wl.Workload("causal", 1, 4, 16, 48, 80, wl.F32, mask_frac=0.2)
+    inp = wl.make_inputs(w, seed=9)
+    y0 = run_fwd(s2d, inp, wl.F32)
+    i0, j0 = 20, 41
+    rng = np.random.default_rng(1)
+    alt = {k: (None if v is None else v.copy()) for k, v in inp.items()}
+    for k in ("x", "delta", "Bm", "Cm"):
+        alt[k][..., i0 + 1:, :] = np.abs(rng.standard_normal(alt[k][..., i0 + 1:, :].shape)).astype(np.float32)
+        alt[k][..., :, j0 + 1:] = np.abs(rng.standard_normal(alt[k][..., :, j0 + 1:].shape)).astype(np.float32)
+    alt["mask"][..., i0 + 1:, :] = 0
+    alt["mask"][..., :, j0 + 1:] = 0
+    y1 = run_fwd(s2d, alt, wl.F32)
+    assert np.array_equal(y0[..., :i0 + 1, :j0 + 1], y1[..., :i0 + 1, :j0 + 1])
+    assert not np.array_equal(y0, y1)
+
+
+def test_each_map_lands_at_its_own_index_and_runs_are_reproducible(s2d):
+    w = wl.Workload("perm", 3, 10, 16, 24, 56, wl.BF16, mask_frac=0.3)
+    inp = wl.make_inputs(w, seed=11)
+    y = run_fwd(s2d, inp, wl.BF16)
+    assert np.array_equal(y, run_fwd(s2d, inp, wl.BF16))          # same bits on a second run
+    perm_c = np.random.default_rng(2).permutation(w.Dc)
+    perm_b = np.array([2, 0, 1])
+    q = dict(inp)
+    q["x"] = inp["x"][perm_b][:, perm_c].copy()
+    q["delta"] = inp["delta"][perm_b][:, perm_c].copy()
+    q["A"] = inp["A"][perm_c].copy()
+    q["Dskip"] = inp["Dskip"][perm_c].copy()
+    q["Bm"], q["Cm"], q["mask"] = inp["Bm"][perm_b].copy(), inp["Cm"][perm_b].copy(), inp["mask"][perm_b].copy()
+    assert np.array_equal(run_fwd(s2d, q, wl.BF16), y[perm_b][:, perm_c])
+
+
+def test_no_skip_term_and_no_mask(s2d):
+    w = wl.Workload("plain", 1, 6, 16, 30, 64, wl.F32)
+    inp = wl.make_inputs(w, seed=13)
+    inp["Dskip"] = None
+    y = run_fwd(s2d, inp, wl.F32)
+    assert rel_err(y, oracle_fwd(inp, wl.F32)) <= 1e-4
+
+
+def test_unit_decay_and_strong_decay(s2d):
+    """A = 0 (summed-area table, sums grow with H*W) and very negative A (a underflows to 0)."""
+    w = wl.Workload("decay", 1, 4, 4, 64, 64, wl.F32)
+    inp = wl.make_inputs(w, seed=15)
+    inp["A"] = np.zeros_like(inp["A"])
+    assert rel_err(run_fwd(s2d, inp, wl.F32), oracle_fwd(inp, wl.F32)) <= 1e-4
+    inp["A"] = np.full_like(inp["A"], -3000.0)
+    assert rel_err(run_fwd(s2d, inp, wl.F32), oracle_fwd(inp, wl.F32)) <= 1e-4
