@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the 2D selective scan on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--all]
+
+A step is one pass of the scan over one batch of synthetic input (forward; forward + backward
+for the training workload).  Inputs are resident in HBM before the timed region; the steps
+cycle through several independent buffer sets so that consecutive launches do not hit the
+256 MB Infinity Cache.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2412_00678_amd import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+# fp32 vector peak without packed-FP32 instructions (they are disabled in this build):
+# 256 CUs x 4 SIMDs x 16 lanes x 2 flop (FMA) x 2.4 GHz = 78.6 TFLOP/s; the published
+# 157.3 TFLOP/s counts two FMAs per lane per clock through the packed forms.
+ALU_PEAK_TFLOPS = 78.6
+FLOPS_PER_UNIT_FWD = 9.0         # exp + 2 mul + 3 FMA per (position, channel, state)
+FLOPS_PER_UNIT_BWD = 30.0        # two rebuilt forward scans + two reverse scans + local gradients
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
+# None where no counter run has been recorded for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def device_sets(s2d, inp, dtype, nsets, backward):
+    import torch
+    base = s2d.to_device(inp, dtype)
+    sets = [base]
+    for _ in range(nsets - 1):
+        sets.append({k: (None if v is None else v.clone()) for k, v in base.items()})
+    for s in sets:
+        s["y"] = torch.empty_like(s["x"])
+    return sets
+
+
+def time_launches(fn, sets, steps, warmup):
+    """Average duration of one launch in ms, from events on the launch stream."""
+    import torch
+    for i in range(warmup):
+        fn(sets[i % len(sets)])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fn(sets[i % len(sets)])
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def bench_workload(s2d, w, steps, warmup, with_bwd):
+    import torch
+    inp = wl.make_inputs(w, seed=0)
+    set_bytes = w.fwd_bytes() + (w.bwd_bytes() if with_bwd else 0)
+    nsets = int(min(16, max(2, np.ceil(1.2e9 / set_bytes))))
+    free, _ = torch.cuda.mem_get_info()
+    nsets = int(max(1, min(nsets, free // (4 * set_bytes))))
+    sets = device_sets(s2d, inp, w.dtype, nsets, with_bwd)
+    desc = s2d.make_desc(sets[0]["x"], sets[0]["A"])
+    wf = s2d.workspace_bytes(desc, s2d.PASS_FWD)
+    ws_f = torch.empty(max(wf, 16), dtype=torch.uint8, device="cuda:0")
+
+    def fwd(s):
+        s2d.scan2d_fwd(s["x"], s["delta"], s["A"], s["Bm"], s["Cm"], s["Dskip"], s["mask"], y=s["y"], workspace=ws_f)
+
+    ms_f, wall_f = time_launches(fwd, sets, steps, warmup)
+    out = {"workload": w.name, "shape": [w.Bt, w.Dc, w.N, w.H, w.W], "dtype": "bf16" if w.dtype == wl.BF16 else "fp32",
+           "buffer_sets": nsets, "fwd_ms": ms_f, "fwd_gunits_s": w.units / ms_f / 1e6,
+           "fwd_algorithmic_GBs": w.fwd_bytes() / ms_f / 1e6, "fwd_bytes": w.fwd_bytes()}
+    if with_bwd:
+        wb = s2d.workspace_bytes(desc, s2d.PASS_BWD)
+        ws_b = torch.empty(max(wb, 16), dtype=torch.uint8, device="cuda:0")
+
+        def bwd(s):
+            s2d.scan2d_bwd(s["x"], s["delta"], s["A"], s["Bm"], s["Cm"], s["Dskip"], s["mask"], s["dy"], workspace=ws_b)
+
+        ms_b, _ = time_launches(bwd, sets, max(3, steps // 8), max(1, warmup // 8))
+        out.update({"bwd_ms": ms_b, "bwd_gunits_s": w.units / ms_b / 1e6, "bwd_algorithmic_GBs": w.bwd_bytes() / ms_b / 1e6,
+                    "fwd_bwd_gunits_s": w.units / (ms_f + ms_b) / 1e6, "bwd_workspace_bytes": wb})
+    del sets
+    torch.cuda.empty_cache()
+    return out, inp
+
+
+def cpu_baseline(w, inp):
+    """The oracle as it stands, all host cores, on the same workload (bounded by channel count)."""
+    import oracle
+    cores = oracle.num_procs()
+    # bound the sample to roughly 10-30 s: the oracle does ~0.03 G units/s per core
+    budget_units = 20.0 * 0.03e9 * cores
+    frac = min(1.0, budget_units / w.units)
+    dc = max(1, int(w.Dc * frac))
+    sub = {k: v for k, v in inp.items()}
+    sub["x"], sub["delta"] = inp["x"][:, :dc].copy(), inp["delta"][:, :dc].copy()
+    sub["A"], sub["Dskip"] = inp["A"][:dc].copy(), inp["Dskip"][:dc].copy()
+    t0 = time.perf_counter()
+    oracle.scan2d_fwd(sub["x"], sub["delta"], sub["A"], sub["Bm"], sub["Cm"], sub["Dskip"], sub["mask"],
+                      dtype=w.dtype, threads=cores)
+    dt = time.perf_counter() - t0
+    units = w.Bt * dc * w.H * w.W * w.N
+    return {"value": units / dt / 1e9, "unit": "G(pos*ch*state)/s", "cores": cores, "kind": "oracle",
+            "sample": f"forward of {w.name} on the first {dc} of {w.Dc} channels ({units} units) in {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", type=int, default=2, help="index into the five configurations (default: the 256x256 WSI grid)")
+    ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under 'others')")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the scan shards over channels with no exchange in forward; "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    from paper_2412_00678_amd import scan2d as s2d   # raises if the library is missing
+
+    torch.cuda.set_device(0)
+    w = wl.CONFIGS[args.workload]
+    res, inp = bench_workload(s2d, w, args.steps, args.warmup, with_bwd=w.backward)
+    ms = res["fwd_ms"] + res.get("bwd_ms", 0.0)
+    flops = w.units * (FLOPS_PER_UNIT_FWD + (FLOPS_PER_UNIT_BWD if w.backward else 0.0))
+    alu = flops / (ms * 1e-3) / 1e12
+    hbm_bytes = w.fwd_bytes() + (w.bwd_bytes() if w.backward else 0)
+    hbm = hbm_bytes / (ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    line = {
+        "metric": "2D-scan G(pos*ch*state)/s (forward; forward+backward for the training workload)",
+        "value": w.units / ms / 1e6, "unit": "G(pos*ch*state)/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "shape_Bt_Dc_N_H_W": [w.Bt, w.Dc, w.N, w.H, w.W],
+                   "storage": res["dtype"], "pass": "fwd+bwd" if w.backward else "fwd", "buffer_sets": res["buffer_sets"]},
+        # the kernel issues ~15 fp32 VALU instructions per unit against 0.39 algorithmic bytes:
+        # the vector ALU, not HBM, is the roof that binds; both are reported
+        "roofline": {"bound": "alu", "achieved": alu, "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": alu / ALU_PEAK_TFLOPS, "traffic": traffic},
+        "roofline_hbm": {"bound": "hbm", "achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": hbm / HBM_PEAK_GBS, "algorithmic_bytes": hbm_bytes, "traffic": traffic},
+        "detail": res,
+    }
+    if args.all:
+        others = []
+        for k, ow in enumerate(wl.CONFIGS):
+            if k == args.workload:
+                continue
+            r, _ = bench_workload(s2d, ow, max(20, args.steps // 3), max(5, args.warmup // 3), with_bwd=ow.backward)
+            others.append(r)
+        line["others"] = others
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

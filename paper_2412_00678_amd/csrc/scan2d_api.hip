@@ -38,7 +38,7 @@ int check_desc(const scan2d_desc* d) {
     if (d->dtype != SCAN2D_F32 && d->dtype != SCAN2D_BF16) return SCAN2D_ERR_BAD_DTYPE;
     if (d->flags != 0u) return SCAN2D_ERR_BAD_FLAGS;
     // element counts must fit 63 bits, and one map's states must be addressable with 32-bit
-    // lane offsets (see fits_offsets below): N * H * W < 2^27 covers every variant
+    // lane offsets (fill_choice checks the exact span): N * H * W < 2^27 bounds it
     const double M = (double)d->Bt * d->Dc * d->H * d->W;
     const double S = (double)d->Bt * d->N * d->H * d->W;
     if (M >= 9.0e18 || S >= 9.0e18) return SCAN2D_ERR_BAD_SHAPE;
@@ -50,26 +50,26 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // ------------------------------------------------------------------ forward variant choice
 struct FwdChoice {
-    int LG = 0, K = 0, NW = 0;
+    int LG = 0, K = 0, NW = 0, waves = 4;
     bool exact = true, fast = true, multi = false;
     int NG = 0, MPW = 0, panels = 0;
     FwdKernel kernel = nullptr;
 };
 
-struct V3 { int LG, K, NW; };
-#define SCAN2D_X(lg, k, nw) {lg, k, nw},
-const V3 kFwdVariants[] = {SCAN2D_FWD_VARIANTS(SCAN2D_X)};
+struct V4 { int LG, K, NW, waves; };
+#define SCAN2D_X(lg, k, nw, wv) {lg, k, nw, wv},
+const V4 kFwdVariants[] = {SCAN2D_FWD_VARIANTS(SCAN2D_X)};
 #undef SCAN2D_X
 
-FwdKernel lookup(int dtype, int LG, int K, int NW, bool exact, bool fast, bool multi) {
-    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, exact, fast, multi)
-                                : fwd_kernel_f32(LG, K, NW, exact, fast, multi);
+FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {
+    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi)
+                                : fwd_kernel_f32(LG, K, NW, waves, exact, fast, multi);
 }
 
-bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, FwdChoice* out) {
-    const int slots = kThreads / LG;
+bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, FwdChoice* out) {
+    const int slots = waves * 64 / LG;
     FwdChoice c;
-    c.LG = LG; c.K = K; c.NW = NW;
+    c.LG = LG; c.K = K; c.NW = NW; c.waves = waves;
     c.exact = (d->N % NW) == 0;
     c.NG = (d->N + NW - 1) / NW;
     if (c.NG > slots) return false;
@@ -80,7 +80,7 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, FwdChoice* out) {
     // 32-bit lane offsets span up to `slots` maps and `slots + 1` batch items of states
     const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
     if (span >= 2147483648.0) return false;
-    c.kernel = lookup(d->dtype, LG, K, NW, c.exact, c.fast, c.multi);
+    c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi);
     if (c.kernel == nullptr) return false;
     *out = c;
     return true;
@@ -90,38 +90,45 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, FwdChoice* out) {
 // the machine the launch can keep busy; only used to rank variants.
 double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     const double maps = (double)d->Bt * d->Dc;
-    const int slots = kThreads / c.LG;
+    const int slots = c.waves * 64 / c.LG;
     const double lane_util = (double)d->W / ((double)c.panels * c.LG * c.K);
     const double slot_util = (double)(c.MPW * c.NG) / slots * (double)d->N / (c.NG * c.NW);
     const double steps = c.LG == 64 ? 6.0 : 4.0;
-    double ops = 7.5 + (d->dtype == SCAN2D_BF16 ? 2.0 : 0.0) + 2.0 * (c.K - 1) / c.K + (2.0 * steps + 1.0) / c.K
-               + (6.0 + (c.NG > 1 ? 3.0 : 1.0)) / c.NW;
+    const bool bf16 = d->dtype == SCAN2D_BF16;
+    double ops = 7.5 + (bf16 ? 2.0 : 0.0) + 2.0 * (c.K - 1) / c.K + (2.0 * steps) / c.K
+               + ((bf16 ? 7.0 : 5.0) + (c.NG > 1 ? 2.0 + 0.5 * c.NG : 1.0)) / c.NW;
     if (!c.fast) ops *= 1.6;
     if (c.multi) ops += 1.0;
+    // waves per SIMD the launch sustains: limited by the grid and by the registers of the variant
     const double wgs = std::ceil(maps / c.MPW);
-    const double waves = wgs * 4.0;
-    const double simds = 1024.0;
-    double par;
-    if (waves <= simds) par = waves / simds * 0.8;            // one wave per SIMD hides little latency
-    else if (waves <= 2 * simds) par = 0.8 + 0.2 * (waves - simds) / simds;
-    else par = (waves / (2 * simds)) / std::ceil(waves / (2 * simds));
-    // register pressure of the big variants limits them to one wave per SIMD
-    if (c.K * c.NW > 32 && waves > simds) par = std::min(par, 0.8 * (waves / simds) / std::ceil(waves / simds));
-    return ops / (lane_util * slot_util * par);
+    const double regs = 40.0 + (bf16 ? 6.5 : 8.5) * c.K * c.NW;
+    // waves per SIMD by registers (launch bounds force at least waves/4), at most 8
+    const double occ = std::min(8.0, std::max(std::floor(512.0 / regs), c.waves / 4.0));
+    const double resident = 256.0 * std::max(1.0, std::floor(occ * 4.0 / c.waves));   // workgroups on the chip
+    const double rounds = std::ceil(wgs / resident);
+    const double wps = std::min(occ, wgs * c.waves / 1024.0 / rounds);     // average waves per SIMD
+    // issue rate of one SIMD against its number of waves: 1 -> 0.5, 2 -> 0.85, 4 -> 1.0 (measured)
+    double rate;
+    if (wps <= 1.0) rate = 0.5 * wps;
+    else if (wps <= 2.0) rate = 0.5 + 0.35 * (wps - 1.0);
+    else rate = std::min(1.0, 0.85 + 0.075 * (wps - 2.0));
+    const double tail = (wgs / resident) / rounds;                         // last round partly empty
+    return ops / (lane_util * slot_util * rate * std::max(tail, 0.05));
 }
 
 int choose_fwd(const scan2d_desc* d, FwdChoice* out) {
-    if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW"
-        int LG = 0, K = 0, NW = 0;
-        if (std::sscanf(env, "%d,%d,%d", &LG, &K, &NW) == 3 && (LG == 16 || LG == 64) && NW >= 1 &&
-            fill_choice(d, LG, K, NW, out))
+    if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES"
+        int LG = 0, K = 0, NW = 0, waves = 4;
+        const int got = std::sscanf(env, "%d,%d,%d,%d", &LG, &K, &NW, &waves);
+        if (got >= 3 && (LG == 16 || LG == 64) && NW >= 1 && (waves == 4 || waves == 8 || waves == 16) &&
+            fill_choice(d, LG, K, NW, waves, out))
             return SCAN2D_OK;
     }
     bool found = false;
     double best = 0.0;
-    for (const V3& v : kFwdVariants) {
+    for (const V4& v : kFwdVariants) {
         FwdChoice c;
-        if (!fill_choice(d, v.LG, v.K, v.NW, &c)) continue;
+        if (!fill_choice(d, v.LG, v.K, v.NW, v.waves, &c)) continue;
         const double cost = fwd_cost(d, c);
         if (!found || cost < best) { best = cost; *out = c; found = true; }
     }
@@ -164,7 +171,7 @@ extern "C" int scan2d_fwd(const scan2d_desc* desc, const void* x, const void* de
     const long long wgs = (a.maps + ch.MPW - 1) / ch.MPW;
     if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
     (void)hipGetLastError();
-    hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(kThreads), 0, static_cast<hipStream_t>(stream), a);
+    hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(ch.waves * 64), 0, static_cast<hipStream_t>(stream), a);
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
 

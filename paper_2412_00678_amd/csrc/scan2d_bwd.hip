@@ -1,7 +1,168 @@
+// Host side of the backward pass: variant choice, workspace layout, launches.
 #include "scan2d_bwd.hpp"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+
+#include "scan2d_bwd_variants.hpp"
+
 namespace scan2d {
-size_t bwd_workspace_bytes(const scan2d_desc*) { return 0; }
-int bwd_launch(const scan2d_desc*, const void*, const void*, const float*, const void*, const void*,
-               const float*, const uint8_t*, const void*, void*, void*, float*, float*, float*, float*,
-               void*, size_t, hipStream_t) { return SCAN2D_ERR_LAUNCH_FAILED; }
+namespace {
+
+// ------------------------------------------------------------------------------ final sums
+// dBm/dCm[b,n,i,j] = sum over channel groups of the partials; one thread per element.
+__global__ void scan2d_bwd_reduce_groups_kernel(const float* __restrict__ pB, const float* __restrict__ pC,
+                                                float* __restrict__ dBm, float* __restrict__ dCm,
+                                                int Bt, int CG, size_t NHW) {
+    const size_t total = (size_t)Bt * NHW;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t b = e / NHW, r = e - b * NHW;
+        const float* sB = pB + b * CG * NHW + r;
+        const float* sC = pC + b * CG * NHW + r;
+        float aB = 0.0f, aC = 0.0f;
+        for (int g = 0; g < CG; ++g) { aB += sB[(size_t)g * NHW]; aC += sC[(size_t)g * NHW]; }
+        dBm[e] = aB;
+        dCm[e] = aC;
+    }
 }
+
+// dA[c,n] = sum_b pA[b,c,n]; dDskip[c] = sum_b pD[b,c].
+__global__ void scan2d_bwd_reduce_batch_kernel(const float* __restrict__ pA, const float* __restrict__ pD,
+                                               float* __restrict__ dA, float* __restrict__ dDskip,
+                                               int Bt, int Dc, int N) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < Dc * N) {
+        float acc = 0.0f;
+        for (int b = 0; b < Bt; ++b) acc += pA[(size_t)b * Dc * N + e];
+        dA[e] = acc;
+    }
+    if (dDskip != nullptr && e < Dc) {
+        float acc = 0.0f;
+        for (int b = 0; b < Bt; ++b) acc += pD[(size_t)b * Dc + e];
+        dDskip[e] = acc;
+    }
+}
+
+struct BwdPlan {
+    int LG = 0, K = 0, NW = 0, waves = 0, RB = 0;
+    int NG = 0, GS = 0, CG = 0, nb = 0;
+    BwdKernels k;
+    size_t lds_bytes = 0;
+    size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, total = 0;
+};
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool make_plan(const scan2d_desc* d, BwdPlan* out) {
+    BwdPlan pl;
+    const int W = d->W, N = d->N;
+    int LG, K;
+    if (W <= 64) { LG = 16; K = 4; }
+    else if (W <= 128) { LG = 16; K = 8; }
+    else if (W <= 256) { LG = 64; K = 4; }
+    else if (W <= 512) { LG = 64; K = 8; }
+    else if (W <= 1024) { LG = 64; K = 16; }
+    else return false;
+    if (const char* env = std::getenv("SCAN2D_BWD_VARIANT")) {   // tuning aid: "LG,K"
+        int eLG = 0, eK = 0;
+        if (std::sscanf(env, "%d,%d", &eLG, &eK) == 2 && (eLG == 16 || eLG == 64) && eLG * eK >= W) { LG = eLG; K = eK; }
+    }
+    // states per lane and waves per workgroup: 16 lane groups of one DPP row with one state each,
+    // or 8 wavefront-wide lane groups with two states each; four states per lane beyond N = 16
+    int waves, NW;
+    if (LG == 16) { waves = 4; NW = N <= 16 ? 1 : 4; }
+    else if (N <= 16) { waves = 8; NW = 2; }
+    else { waves = 16; NW = 4; }
+    const int slots = waves * 64 / LG;
+    if ((N + NW - 1) / NW > slots) return false;
+    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves) : bwd_kernels_f32(LG, K, NW, waves);
+    if (pl.k.main == nullptr) return false;
+    pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
+    pl.NG = (N + NW - 1) / NW;
+    pl.nb = (d->H + pl.RB - 1) / pl.RB;
+    // channels per workgroup: bounded by LDS (150 KB) and by keeping at least 2048 waves in flight
+    const size_t T = (size_t)waves * 64;
+    const size_t fixed = 2 * T * K, per = T * ((size_t)NW * K + NW + 1);
+    int gs_lds = (int)std::max<size_t>(1, (38400 - std::min<size_t>(fixed, 38400)) / per);
+    const int JPW = slots / pl.NG;
+    int gs = std::min({gs_lds, 8, d->Dc});
+    while (gs > 1) {
+        const long long jobs = (long long)d->Bt * ((d->Dc + gs - 1) / gs);
+        if (((jobs + JPW - 1) / JPW) * waves >= 2048) break;
+        --gs;
+    }
+    pl.GS = gs;
+    pl.CG = (d->Dc + gs - 1) / gs;
+    pl.lds_bytes = (fixed + (size_t)gs * per) * sizeof(float);
+    if (pl.lds_bytes > 160 * 1024) return false;
+    const size_t maps = (size_t)d->Bt * d->Dc;
+    const size_t NHW = (size_t)N * d->H * W;
+    size_t o = 0;
+    pl.off_ck = o; o += align_up(maps * pl.nb * N * W * sizeof(float));
+    pl.off_pB = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * NHW * sizeof(float)) : 0;
+    pl.off_pC = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * NHW * sizeof(float)) : 0;
+    pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
+    pl.off_pD = o; o += d->Bt > 1 ? align_up(maps * sizeof(float)) : 0;
+    pl.total = o;
+    *out = pl;
+    return true;
+}
+
+}  // namespace
+
+size_t bwd_workspace_bytes(const scan2d_desc* d) {
+    BwdPlan pl;
+    return make_plan(d, &pl) ? pl.total : 0;
+}
+
+int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const float* A, const void* Bm,
+               const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
+               void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
+               size_t workspace_bytes, hipStream_t stream) {
+    BwdPlan pl;
+    if (!make_plan(d, &pl)) return SCAN2D_ERR_BAD_SHAPE;
+    if (pl.total > 0 && (workspace == nullptr || workspace_bytes < pl.total)) return SCAN2D_ERR_WORKSPACE_SMALL;
+    char* ws = static_cast<char*>(workspace);
+    BwdArgs a;
+    a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.dy = dy;
+    a.dx = dx; a.ddelta = ddelta;
+    a.ck = reinterpret_cast<float*>(ws + pl.off_ck);
+    a.pB = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pB) : dBm;   // one group: the partial is the result
+    a.pC = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pC) : dCm;
+    a.pA = d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pA) : dA;
+    a.pD = dDskip == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pD) : dDskip);
+    a.Bt = d->Bt; a.Dc = d->Dc; a.H = d->H; a.W = d->W; a.N = d->N;
+    a.NG = pl.NG; a.GS = pl.GS; a.CG = pl.CG; a.nb = pl.nb;
+    a.fast = ((d->W * (d->dtype == SCAN2D_BF16 ? 2 : 4)) % 4 == 0 && d->W % 4 == 0) ? 1 : 0;
+
+    const int slots = pl.waves * 64 / pl.LG;
+    const long long maps = (long long)d->Bt * d->Dc;
+    const int MPW = slots / pl.NG;
+    const long long wg1 = (maps + MPW - 1) / MPW;
+    const long long jobs = (long long)d->Bt * pl.CG;
+    const long long wg2 = (jobs + MPW - 1) / MPW;
+    if (wg1 > 2147483647LL || wg2 > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    (void)hipGetLastError();
+    if (pl.nb > 1)
+        hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.waves * 64), 0, stream, a);
+    if (pl.lds_bytes > 65536)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(pl.k.main),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes);
+    hipLaunchKernelGGL(pl.k.main, dim3((unsigned)wg2), dim3(pl.waves * 64), pl.lds_bytes, stream, a);
+    if (pl.CG > 1) {
+        const size_t NHW = (size_t)d->N * d->H * d->W;
+        const size_t total = (size_t)d->Bt * NHW;
+        const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 16384);
+        hipLaunchKernelGGL(scan2d_bwd_reduce_groups_kernel, dim3(blocks), dim3(256), 0, stream,
+                           a.pB, a.pC, dBm, dCm, d->Bt, pl.CG, NHW);
+    }
+    if (d->Bt > 1) {
+        const int n = d->Dc * d->N;
+        hipLaunchKernelGGL(scan2d_bwd_reduce_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
+                           a.pA, a.pD, dA, dDskip, d->Bt, d->Dc, d->N);
+    }
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+}  // namespace scan2d

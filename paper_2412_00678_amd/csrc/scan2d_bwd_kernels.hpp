@@ -1,0 +1,420 @@
+// Backward 2D selective scan kernels for gfx950 (2DMamba Supp. B: two forward scans rebuild the
+// states, a reverse column scan and a reverse row scan carry the gradients).
+//
+// The forward pass stores nothing N-wide, so the backward works in bands of RB rows:
+//   1. a checkpoint kernel repeats the forward recurrences and keeps only the column state h
+//      at the top of every band (N*W floats per band and map);
+//   2. the main kernel walks the bands from the bottom up.  Per band and channel it rebuilds
+//      h[i-1,j] and hhor[i,j-1] for the band's rows into registers (scans 1 and 2), then walks
+//      the band's rows upwards with the reverse column recurrence g (a plain FMA on a register
+//      that persists from row to row) and the reverse row recurrence q (serial over the lane's
+//      K columns plus a leftward lane-group scan), and forms the local gradients;
+//   3. sums over channels (dBm, dCm) are accumulated in registers over the GS channels a
+//      workgroup handles one after the other, written once per band as partial sums, and added
+//      up over the channel groups by a reduction kernel in a fixed order; dA and dDskip are
+//      reduced over lanes in a fixed order and over batch items by the same kernel.
+// Lane mapping is that of the forward kernel: a lane group of LG lanes owns LG*K columns, lane l
+// the columns [l*K, l*K+K) and NW states; NG = ceil(N/NW) lane groups share a map and meet in
+// LDS once per row for the sums over states (ddelta, dx).
+#pragma once
+
+#include "scan2d_common.hpp"
+
+namespace scan2d {
+
+struct BwdArgs {
+    const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
+    const float* Dskip; const uint8_t* mask; const void* dy;
+    void* dx; void* ddelta;
+    float* ck;           // [maps][nb][N][W]   column state entering each band (band 0 unused)
+    float* pB; float* pC; // [Bt][CG][N][H][W] partial sums over the channels of one group
+    float* pA;           // [Bt][Dc][N]
+    float* pD;           // [Bt][Dc]
+    int Bt, Dc, H, W, N;
+    int NG;              // lane groups per map
+    int GS;              // channels a workgroup handles one after the other
+    int CG;              // channel groups = ceil(Dc / GS)
+    int nb;              // bands = ceil(H / RB)
+    int fast;            // rows start 4-byte aligned: wide loads allowed for full lanes
+};
+
+// ---------------------------------------------------------------------------- checkpoint sweep
+template <typename T, int LG, int K, int NW, int WAVES, int RB>
+__global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdArgs p) {
+    constexpr int SLOTS = WAVES * 64 / LG;
+    constexpr int XW = words_of<T, K>();
+    const int tid = threadIdx.x, slot = tid / LG, l = tid % LG;
+    const int NG = p.NG, MPW = SLOTS / NG;
+    const int map_local = slot / NG, sg = slot - map_local * NG;
+    const long long maps = (long long)p.Bt * p.Dc;
+    const long long map = (long long)blockIdx.x * MPW + map_local;
+    if (map_local >= MPW || map >= maps) return;             // no barriers in this kernel
+    const int H = p.H, W = p.W, N = p.N;
+    const size_t HW = (size_t)H * W;
+    const int b = (int)(map / p.Dc), c = (int)(map % p.Dc);
+    const int n0 = sg * NW, nvalid = min(NW, N - n0);
+    const int col0 = l * K;
+    const bool fast = p.fast != 0;
+    const T* xm = reinterpret_cast<const T*>(p.x) + (size_t)map * HW;
+    const T* dm = reinterpret_cast<const T*>(p.delta) + (size_t)map * HW;
+    const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
+    const T* Bs[NW];
+    float Ap[NW], h[NW][K];
+#pragma unroll
+    for (int s = 0; s < NW; ++s) {
+        const int n = n0 + (s < nvalid ? s : 0);
+        Bs[s] = reinterpret_cast<const T*>(p.Bm) + ((size_t)b * N + n) * HW;
+        Ap[s] = p.A[(size_t)c * N + n] * kLog2e;
+#pragma unroll
+        for (int j = 0; j < K; ++j) h[s][j] = 0.0f;
+    }
+    for (int i = 0; i < H; ++i) {
+        const size_t ro = (size_t)i * W;
+        uint32_t rx[XW], rd[XW], rm[K / 4];
+        load_row<T, K>(xm + ro, col0, W, fast, rx);
+        load_row<T, K>(dm + ro, col0, W, fast, rd);
+#pragma unroll
+        for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
+        if (mm) load_mask<K>(mm + ro, col0, W, fast, rm);
+        float dl[K], dxe[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            dl[j] = get_elem<T, K>(rd, j);
+            const float xe = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
+            dxe[j] = dl[j] * xe;
+        }
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            uint32_t rB[XW];
+            load_row<T, K>(Bs[s] + ro, col0, W, fast, rB);
+            float a[K], hl[K], pl[K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
+            hl[0] = dxe[0] * get_elem<T, K>(rB, 0);
+            pl[0] = a[0];
+#pragma unroll
+            for (int j = 1; j < K; ++j) {
+                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(rB, j));
+                pl[j] = pl[j - 1] * a[j];
+            }
+            float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
+            group_scan<LG, 1>(P, Hh, cin);
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
+                h[s][j] = fmaf(a[j], h[s][j], hh);
+            }
+        }
+        if ((i + 1) % RB == 0 && i + 1 < H) {                 // h[i] enters band (i+1)/RB
+            const int band = (i + 1) / RB;
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+                if (s < nvalid) {
+                    float* dst = p.ck + (((size_t)map * p.nb + band) * N + n0 + s) * W;
+#pragma unroll
+                    for (int j = 0; j < K; ++j)
+                        if (col0 + j < W) dst[col0 + j] = h[s][j];
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------- main sweep
+// Dynamic LDS layout (floats), T = workgroup threads:
+//   part [2][T*K]      per-thread partial sums over its states of ddelta and dx for one row
+//   gaL  [GS][T*NW*K]  a[i+1,j]*g[i+1,j] of every channel, kept between bands
+//   dAL  [GS][T*NW]    per-lane partial of dA
+//   dDL  [GS][T]       per-lane partial of dDskip (first lane group of a map only)
+template <typename T, int LG, int K, int NW, int WAVES, int RB>
+__global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdArgs p) {
+    constexpr int THREADS = WAVES * 64;
+    constexpr int SLOTS = THREADS / LG;
+    constexpr int XW = words_of<T, K>();
+    constexpr int PANEL = LG * K;
+    extern __shared__ float lds[];
+    const int GS = p.GS;
+    float* part = lds;                                   // [2][SLOTS][PANEL]
+    float* gaL = part + 2 * THREADS * K;                 // [GS][THREADS][NW*K]
+    float* dAL = gaL + (size_t)GS * THREADS * NW * K;    // [GS][THREADS][NW]
+    float* dDL = dAL + (size_t)GS * THREADS * NW;        // [GS][THREADS]
+
+    const int tid = threadIdx.x, slot = tid / LG, l = tid % LG;
+    const int NG = p.NG, JPW = SLOTS / NG;               // jobs (batch item, channel group) per workgroup
+    int job_local = slot / NG;
+    const int sg = slot - job_local * NG;
+    const long long jobs = (long long)p.Bt * p.CG;
+    const long long job0 = (long long)blockIdx.x * JPW;
+    const bool live = (job_local < JPW) && (job0 + job_local < jobs);
+    if (!live) job_local = 0;
+    const long long job = job0 + job_local;
+    const int b = (int)(job / p.CG), cg = (int)(job % p.CG);
+    const int c_first = cg * GS;
+    const int nch = live ? min(GS, p.Dc - c_first) : 0;
+
+    const int H = p.H, W = p.W, N = p.N;
+    const size_t HW = (size_t)H * W;
+    const int n0 = sg * NW, nvalid = min(NW, N - n0);
+    const int col0 = l * K;
+    const bool fast = p.fast != 0;
+    const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
+    const T* Bs[NW];
+    const T* Cs[NW];
+#pragma unroll
+    for (int s = 0; s < NW; ++s) {
+        const int n = n0 + (s < nvalid ? s : 0);
+        Bs[s] = reinterpret_cast<const T*>(p.Bm) + ((size_t)b * N + n) * HW;
+        Cs[s] = reinterpret_cast<const T*>(p.Cm) + ((size_t)b * N + n) * HW;
+    }
+
+    for (int ch = 0; ch < GS; ++ch) {
+#pragma unroll
+        for (int e = 0; e < NW * K; ++e) gaL[((size_t)ch * THREADS + tid) * (NW * K) + e] = 0.0f;   // g below the map is 0
+#pragma unroll
+        for (int s = 0; s < NW; ++s) dAL[((size_t)ch * THREADS + tid) * NW + s] = 0.0f;
+        dDL[(size_t)ch * THREADS + tid] = 0.0f;
+    }
+    // every thread only ever touches its own gaL / dAL / dDL entries: no barrier needed for them
+
+    for (int band = p.nb - 1; band >= 0; --band) {
+        const int r0 = band * RB;
+        float dBacc[RB][NW][K], dCacc[RB][NW][K];
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int s = 0; s < NW; ++s)
+#pragma unroll
+                for (int j = 0; j < K; ++j) { dBacc[r][s][j] = 0.0f; dCacc[r][s][j] = 0.0f; }
+
+        for (int ch = 0; ch < GS; ++ch) {
+            const bool act = ch < nch;
+            const int c = act ? c_first + ch : c_first;      // idle iterations re-read a valid channel
+            const size_t map = (size_t)b * p.Dc + c;
+            const T* xm = reinterpret_cast<const T*>(p.x) + map * HW;
+            const T* dm = reinterpret_cast<const T*>(p.delta) + map * HW;
+            const T* dym = reinterpret_cast<const T*>(p.dy) + map * HW;
+            T* dxm = reinterpret_cast<T*>(p.dx) + map * HW;
+            T* ddm = reinterpret_cast<T*>(p.ddelta) + map * HW;
+            float An[NW], Ap[NW];
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+                An[s] = p.A[(size_t)c * N + n0 + (s < nvalid ? s : 0)];
+                Ap[s] = An[s] * kLog2e;
+            }
+            const float dsk = (p.Dskip != nullptr && sg == 0) ? p.Dskip[c] : 0.0f;
+
+            // ---- scans 1 and 2: rebuild h[i-1,j] and hhor[i,j-1] for the rows of the band
+            float hprev[RB][NW][K], hhl[RB][NW][K];
+            {
+                float hcur[NW][K];
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    const float* src = p.ck + ((map * p.nb + band) * N + n0 + (s < nvalid ? s : 0)) * W;
+#pragma unroll
+                    for (int j = 0; j < K; ++j)
+                        hcur[s][j] = (band > 0 && col0 + j < W) ? src[col0 + j] : 0.0f;
+                }
+#pragma unroll
+                for (int r = 0; r < RB; ++r) {
+                    const int i = r0 + r;
+                    if (i < H && act) {
+                        const size_t ro = (size_t)i * W;
+                        uint32_t rx[XW], rd[XW], rm[K / 4];
+                        load_row<T, K>(xm + ro, col0, W, fast, rx);
+                        load_row<T, K>(dm + ro, col0, W, fast, rd);
+#pragma unroll
+                        for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
+                        if (mm) load_mask<K>(mm + ro, col0, W, fast, rm);
+                        float dl[K], dxe[K];
+#pragma unroll
+                        for (int j = 0; j < K; ++j) {
+                            dl[j] = get_elem<T, K>(rd, j);
+                            const float xe = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
+                            dxe[j] = dl[j] * xe;
+                        }
+#pragma unroll
+                        for (int s = 0; s < NW; ++s) {
+                            uint32_t rB[XW];
+                            load_row<T, K>(Bs[s] + ro, col0, W, fast, rB);
+                            float a[K], hl[K], pl[K];
+#pragma unroll
+                            for (int j = 0; j < K; ++j) a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
+                            hl[0] = dxe[0] * get_elem<T, K>(rB, 0);
+                            pl[0] = a[0];
+#pragma unroll
+                            for (int j = 1; j < K; ++j) {
+                                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(rB, j));
+                                pl[j] = pl[j - 1] * a[j];
+                            }
+                            float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
+                            group_scan<LG, 1>(P, Hh, cin);
+                            float left = cin[0];                          // hhor[i, j-1]
+#pragma unroll
+                            for (int j = 0; j < K; ++j) {
+                                const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
+                                hhl[r][s][j] = left;
+                                hprev[r][s][j] = hcur[s][j];
+                                hcur[s][j] = fmaf(a[j], hcur[s][j], hh);
+                                left = hh;
+                            }
+                        }
+                    }
+                }
+            }
+
+            // ---- scans 3 and 4, bottom row of the band first
+            float ga[NW][K], dAb[NW], dDb = 0.0f;
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+                dAb[s] = 0.0f;
+#pragma unroll
+                for (int j = 0; j < K; ++j) ga[s][j] = gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j];
+            }
+#pragma unroll
+            for (int r = RB - 1; r >= 0; --r) {
+                const int i = r0 + r;
+                if (i < H) {                                               // uniform over the workgroup
+                    const size_t ro = (size_t)i * W;
+                    uint32_t rx[XW], rd[XW], ry[XW], rm[K / 4];
+                    load_row<T, K>(xm + ro, col0, W, fast, rx);
+                    load_row<T, K>(dm + ro, col0, W, fast, rd);
+                    load_row<T, K>(dym + ro, col0, W, fast, ry);
+#pragma unroll
+                    for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
+                    if (mm) load_mask<K>(mm + ro, col0, W, fast, rm);
+                    float dl[K], xe[K], dxe[K], dyv[K], ddl[K], dxl[K];
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        dl[j] = get_elem<T, K>(rd, j);
+                        xe[j] = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
+                        dxe[j] = dl[j] * xe[j];
+                        dyv[j] = get_elem<T, K>(ry, j);
+                        ddl[j] = 0.0f;
+                        dxl[j] = dsk * dyv[j];
+                        dDb = fmaf(dyv[j], xe[j], dDb);
+                    }
+#pragma unroll
+                    for (int s = 0; s < NW; ++s) {
+                        if (act && s < nvalid) {
+                            uint32_t rB[XW], rC[XW];
+                            load_row<T, K>(Bs[s] + ro, col0, W, fast, rB);
+                            load_row<T, K>(Cs[s] + ro, col0, W, fast, rC);
+                            float a[K], Bv[K], g[K];
+#pragma unroll
+                            for (int j = 0; j < K; ++j) {
+                                a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
+                                Bv[j] = get_elem<T, K>(rB, j);
+                                const float hh = fmaf(a[j], hhl[r][s][j], dxe[j] * Bv[j]);   // hhor[i,j]
+                                const float hv = fmaf(a[j], hprev[r][s][j], hh);             // h[i,j]
+                                dCacc[r][s][j] = fmaf(dyv[j], hv, dCacc[r][s][j]);
+                                g[j] = fmaf(dyv[j], get_elem<T, K>(rC, j), ga[s][j]);        // scan 3
+                                ga[s][j] = a[j] * g[j];
+                            }
+                            // scan 4: q[j] = g[j] + a[j+1] * q[j+1]
+                            float ar[K], ql[K], pr[K];
+#pragma unroll
+                            for (int j = 0; j + 1 < K; ++j) ar[j] = a[j + 1];
+                            ar[K - 1] = from_right<LG>(a[0]);
+                            ql[K - 1] = g[K - 1];
+                            pr[K - 1] = ar[K - 1];
+#pragma unroll
+                            for (int j = K - 2; j >= 0; --j) {
+                                ql[j] = fmaf(ar[j], ql[j + 1], g[j]);
+                                pr[j] = ar[j] * pr[j + 1];
+                            }
+                            float P[1] = {pr[0]}, Q[1] = {ql[0]}, qin[1];
+                            group_scan_left<LG, 1>(P, Q, qin);
+#pragma unroll
+                            for (int j = 0; j < K; ++j) {
+                                const float q = fmaf(pr[j], qin[0], ql[j]);
+                                const float da = fmaf(g[j], hprev[r][s][j], q * hhl[r][s][j]);
+                                const float t = da * a[j];
+                                dAb[s] = fmaf(t, dl[j], dAb[s]);
+                                ddl[j] = fmaf(t, An[s], fmaf(q * Bv[j], xe[j], ddl[j]));
+                                dxl[j] = fmaf(q * dl[j], Bv[j], dxl[j]);
+                                dBacc[r][s][j] = fmaf(q, dxe[j], dBacc[r][s][j]);
+                            }
+                        }
+                    }
+                    // sums over the states held by the other lane groups of this map
+                    float* mine = part + (size_t)tid * K;
+                    __syncthreads();                                       // previous row's sums are consumed
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        mine[j] = ddl[j];
+                        mine[THREADS * K + j] = mask_bit<K>(rm, j) ? 0.0f : dxl[j];
+                    }
+                    __syncthreads();
+                    if (act) {
+                        const float* base = part + (size_t)(slot - sg) * PANEL;
+                        for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
+                            if (col < W) {
+                                float sd = base[col], sx = base[THREADS * K + col];
+                                for (int gq = 1; gq < NG; ++gq) {
+                                    sd += base[gq * PANEL + col];
+                                    sx += base[THREADS * K + gq * PANEL + col];
+                                }
+                                store_elem(ddm + ro + col, sd);
+                                store_elem(dxm + ro + col, sx);
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+#pragma unroll
+                for (int j = 0; j < K; ++j) gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j] = ga[s][j];
+                dAL[((size_t)ch * THREADS + tid) * NW + s] += dAb[s];
+            }
+            dDL[(size_t)ch * THREADS + tid] += dDb;
+        }
+
+        // partial sums over this workgroup's channels, one write per band
+        if (live) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const int i = r0 + r;
+                if (i < H) {
+#pragma unroll
+                    for (int s = 0; s < NW; ++s) {
+                        if (s < nvalid) {
+                            const size_t o = ((((size_t)b * p.CG + cg) * N + n0 + s) * H + i) * W;
+#pragma unroll
+                            for (int j = 0; j < K; ++j)
+                                if (col0 + j < W) { p.pB[o + col0 + j] = dBacc[r][s][j]; p.pC[o + col0 + j] = dCacc[r][s][j]; }
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    // dA[b,c,n] and dDskip[b,c]: sum the per-lane partials over the lane group in a fixed order
+    for (int ch = 0; ch < GS; ++ch) {                 // uniform trip count: the sums use DPP
+        const bool act = ch < nch;
+        const int c = c_first + ch;
+#pragma unroll
+        for (int s = 0; s <= NW; ++s) {               // s == NW: the dDskip partial
+            float v = (s < NW) ? dAL[((size_t)ch * THREADS + tid) * NW + (s < NW ? s : 0)]
+                               : dDL[(size_t)ch * THREADS + tid];
+            v = row_sum16(v);
+            if constexpr (LG == 64) {
+                const int vi = __builtin_bit_cast(int, v);
+                v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 0)) +
+                    __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 16)) +
+                    __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 32)) +
+                    __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 48));
+            }
+            if (act && l == 0) {
+                if (s < NW) {
+                    if (s < nvalid) p.pA[((size_t)b * p.Dc + c) * N + n0 + s] = v;
+                } else if (sg == 0 && p.pD != nullptr) {
+                    p.pD[(size_t)b * p.Dc + c] = v;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace scan2d

@@ -9,7 +9,7 @@
 namespace scan2d {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kThreads = 256;   // workgroup size of every scan kernel: 4 wavefronts
+
 
 struct bf16_t { uint16_t bits; };   // storage tag: upper half of an IEEE fp32
 
@@ -248,6 +248,85 @@ __device__ __forceinline__ void group_scan(float* P, float* H, float* C) {
     if constexpr (S == 1) group_scan1<LG>(P[0], H[0], C[0]);
     else if constexpr (S == 2) group_scan2<LG>(P[0], P[1], H[0], H[1], C[0], C[1]);
     else group_scan4<LG>(P[0], P[1], P[2], P[3], H[0], H[1], H[2], H[3], C[0], C[1], C[2], C[3]);
+}
+
+// ------------------------------------------------------------------ group scan (leftwards)
+// Mirror image for the reverse row scan of the backward pass: q <- Q + P * q_in where q_in
+// comes from the lane to the RIGHT.  Out: C = the value at the first column of the lane to the
+// right, including everything further right in the group (0 for the group's last lane), i.e.
+// the carry entering this lane.  P and Q are consumed.  Inside a DPP row the steps use row_shl.  A wavefront has no leftward
+// counterpart of row_bcast, so for LG = 64 the pairs are mirrored across the wave with
+// ds_bpermute (LDS crossbar, no VALU slot), scanned rightwards, and the carry mirrored back.
+#define SCAN2D_SHL(n) " row_shl:" #n " row_mask:0xf bank_mask:0xf\n\t"
+
+__device__ __forceinline__ void row_scan_left1(float& P0, float& H0, float& C0) {
+    C0 = 0.0f;
+    asm volatile("s_nop 1\n\t"
+                 SCAN2D_S1_STEP(SCAN2D_SHL(1)) SCAN2D_S1_STEP(SCAN2D_SHL(2))
+                 SCAN2D_S1_STEP(SCAN2D_SHL(4)) SCAN2D_S1_LAST(SCAN2D_SHL(8))
+                 "v_mov_b32_dpp %2, %0" SCAN2D_SHL(1)
+                 : "+v"(H0), "+v"(P0), "+v"(C0));
+}
+__device__ __forceinline__ void row_scan_left2(float& P0, float& P1, float& H0, float& H1, float& C0, float& C1) {
+    C0 = 0.0f; C1 = 0.0f;
+    asm volatile("s_nop 1\n\t"
+                 SCAN2D_S2_STEP(SCAN2D_SHL(1)) SCAN2D_S2_STEP(SCAN2D_SHL(2))
+                 SCAN2D_S2_STEP(SCAN2D_SHL(4)) SCAN2D_S2_LAST(SCAN2D_SHL(8))
+                 "v_mov_b32_dpp %4, %0" SCAN2D_SHL(1) "v_mov_b32_dpp %5, %1" SCAN2D_SHL(1)
+                 : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "+v"(C0), "+v"(C1));
+}
+__device__ __forceinline__ void row_scan_left4(float& P0, float& P1, float& P2, float& P3,
+                                               float& H0, float& H1, float& H2, float& H3,
+                                               float& C0, float& C1, float& C2, float& C3) {
+    C0 = 0.0f; C1 = 0.0f; C2 = 0.0f; C3 = 0.0f;
+    asm volatile("s_nop 1\n\t"
+                 SCAN2D_S4_STEP(SCAN2D_SHL(1)) SCAN2D_S4_STEP(SCAN2D_SHL(2))
+                 SCAN2D_S4_STEP(SCAN2D_SHL(4)) SCAN2D_S4_LAST(SCAN2D_SHL(8))
+                 "v_mov_b32_dpp %8, %0" SCAN2D_SHL(1) "v_mov_b32_dpp %9, %1" SCAN2D_SHL(1)
+                 "v_mov_b32_dpp %10, %2" SCAN2D_SHL(1) "v_mov_b32_dpp %11, %3" SCAN2D_SHL(1)
+                 : "+v"(H0), "+v"(H1), "+v"(H2), "+v"(H3), "+v"(P0), "+v"(P1), "+v"(P2), "+v"(P3),
+                   "+v"(C0), "+v"(C1), "+v"(C2), "+v"(C3));
+}
+
+__device__ __forceinline__ float wave_mirror(float v) {
+    const int lane = (int)(threadIdx.x & 63u);
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((63 - lane) << 2, __builtin_bit_cast(int, v)));
+}
+
+template <int LG, int S>
+__device__ __forceinline__ void group_scan_left(float* P, float* Q, float* C) {
+    if constexpr (LG == 16) {
+        if constexpr (S == 1) row_scan_left1(P[0], Q[0], C[0]);
+        else if constexpr (S == 2) row_scan_left2(P[0], P[1], Q[0], Q[1], C[0], C[1]);
+        else row_scan_left4(P[0], P[1], P[2], P[3], Q[0], Q[1], Q[2], Q[3], C[0], C[1], C[2], C[3]);
+    } else {
+        float Pm[S], Qm[S], Cm[S];
+#pragma unroll
+        for (int t = 0; t < S; ++t) { Pm[t] = wave_mirror(P[t]); Qm[t] = wave_mirror(Q[t]); }
+        group_scan<64, S>(Pm, Qm, Cm);
+#pragma unroll
+        for (int t = 0; t < S; ++t) C[t] = wave_mirror(Cm[t]);
+    }
+}
+
+// Value held by the lane to the right inside the lane group (0 for the group's last lane).
+template <int LG>
+__device__ __forceinline__ float from_right(float v) {
+    float r = 0.0f;
+    if constexpr (LG == 64) asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 wave_shl:1 row_mask:0xf bank_mask:0xf" : "+v"(r) : "v"(v));
+    else asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 row_shl:1 row_mask:0xf bank_mask:0xf" : "+v"(r) : "v"(v));
+    return r;
+}
+
+// Sum over the 16 lanes of a DPP row (every lane of the row gets the total).
+__device__ __forceinline__ float row_sum16(float v) {
+    asm volatile("s_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_ror:1 row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_ror:2 row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_ror:4 row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+                 : "+v"(v));
+    return v;
 }
 
 }  // namespace scan2d

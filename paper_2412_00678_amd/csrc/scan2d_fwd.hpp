@@ -26,7 +26,7 @@ struct FwdArgs {
     long long maps;      // Bt * Dc
     int Dc, H, W, N;
     int NG;              // lane groups per map = ceil(N / NW)
-    int MPW;             // maps per workgroup = (256 / LG) / NG, >= 1
+    int MPW;             // maps per workgroup = (lane groups per workgroup) / NG, >= 1
     int panels;          // ceil(W / (LG * K))
 };
 
@@ -35,9 +35,12 @@ struct FwdArgs {
 // lane 0 and its results are discarded).  Otherwise every element access is guarded.
 // MULTI: the map is wider than one panel (p.panels > 1); single-panel kernels carry no code
 // for the panel hand-over.
-template <typename T, int LG, int K, int NW, bool EXACT, bool FAST, bool MULTI>
-__global__ __launch_bounds__(kThreads) void scan2d_fwd_kernel(const FwdArgs p) {
-    constexpr int SLOTS = kThreads / LG;
+// WAVES: wavefronts per workgroup (4, 8 or 16).  One wave per SIMD reaches only about half of
+// the vector issue rate on this chip, so maps that are few but large spread their states over
+// more waves (smaller NW) rather than leaving SIMDs with a single wave.
+template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI>
+__global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p) {
+    constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
     constexpr int PANEL = LG * K;
     constexpr int SC = (NW < 4 ? NW : (K >= 12 ? 2 : 4));   // states scanned together

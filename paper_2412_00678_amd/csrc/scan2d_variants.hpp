@@ -1,60 +1,68 @@
-// The (LG, K, NW) kernel variants that are compiled, and the lookup used by the dispatcher.
-//   LG : lanes per lane group (16 = one DPP row, 64 = a wavefront)
-//   K  : consecutive columns per lane
-//   NW : states per lane
-// K * NW <= 64 bounds the persistent column state held in VGPRs.
+// The (LG, K, NW, WAVES) kernel variants that are compiled, and the lookup used by the dispatcher.
+//   LG    : lanes per lane group (16 = one DPP row, 64 = a wavefront)
+//   K     : consecutive columns per lane
+//   NW    : states per lane
+//   WAVES : wavefronts per workgroup
+// K * NW <= 64 bounds the persistent column state held in VGPRs; the 8- and 16-wave forms are
+// limited to the variants whose register count allows that many waves per SIMD.
 #pragma once
 
 #include "scan2d_fwd.hpp"
 
 namespace scan2d {
 
-#define SCAN2D_FWD_VARIANTS(X)                                   \
-    X(16, 4, 1) X(16, 4, 2) X(16, 4, 4) X(16, 4, 8) X(16, 4, 16) \
-    X(16, 8, 1) X(16, 8, 2) X(16, 8, 4) X(16, 8, 8)              \
-    X(16, 12, 1) X(16, 12, 2) X(16, 12, 4)                       \
-    X(16, 16, 1) X(16, 16, 2) X(16, 16, 4)                       \
-    X(64, 4, 1) X(64, 4, 2) X(64, 4, 4) X(64, 4, 8) X(64, 4, 16) \
-    X(64, 8, 1) X(64, 8, 2) X(64, 8, 4) X(64, 8, 8)              \
-    X(64, 16, 1) X(64, 16, 2) X(64, 16, 4)
+#define SCAN2D_FWD_VARIANTS(X)                                                  \
+    X(16, 4, 1, 4) X(16, 4, 2, 4) X(16, 4, 4, 4) X(16, 4, 8, 4) X(16, 4, 16, 4) \
+    X(16, 8, 1, 4) X(16, 8, 2, 4) X(16, 8, 4, 4) X(16, 8, 8, 4)                 \
+    X(16, 12, 1, 4) X(16, 12, 2, 4) X(16, 12, 4, 4)                             \
+    X(16, 16, 1, 4) X(16, 16, 2, 4) X(16, 16, 4, 4)                             \
+    X(64, 4, 1, 4) X(64, 4, 2, 4) X(64, 4, 4, 4) X(64, 4, 8, 4) X(64, 4, 16, 4) \
+    X(64, 8, 1, 4) X(64, 8, 2, 4) X(64, 8, 4, 4) X(64, 8, 8, 4)                 \
+    X(64, 16, 1, 4) X(64, 16, 2, 4) X(64, 16, 4, 4)                             \
+    X(64, 4, 1, 8) X(64, 4, 2, 8) X(64, 8, 1, 8) X(64, 8, 2, 8) X(64, 16, 1, 8) \
+    X(64, 4, 1, 16) X(64, 8, 1, 16)
 
 // Variants that also exist for N not divisible by NW (the last lane group idles some states).
-#define SCAN2D_FWD_RAGGED_VARIANTS(X) X(16, 4, 4) X(16, 8, 4) X(16, 12, 4) X(16, 16, 4)
+#define SCAN2D_FWD_RAGGED_VARIANTS(X) X(16, 4, 4, 4) X(16, 8, 4, 4) X(16, 12, 4, 4) X(16, 16, 4, 4)
 
 // Variants that also exist with guarded element-wise accesses (W not a multiple of K, or rows
 // that do not start 4-byte aligned).
-#define SCAN2D_FWD_GUARDED_VARIANTS(X) \
-    X(16, 4, 1) X(16, 4, 2) X(16, 4, 4) X(16, 4, 8) X(16, 4, 16) X(64, 4, 1) X(64, 4, 2) X(64, 4, 4) X(64, 4, 8) X(64, 4, 16)
+#define SCAN2D_FWD_GUARDED_VARIANTS(X)                                          \
+    X(16, 4, 1, 4) X(16, 4, 2, 4) X(16, 4, 4, 4) X(16, 4, 8, 4) X(16, 4, 16, 4) \
+    X(64, 4, 1, 4) X(64, 4, 2, 4) X(64, 4, 4, 4) X(64, 4, 8, 4) X(64, 4, 16, 4) \
+    X(64, 4, 1, 8) X(64, 4, 2, 8) X(64, 4, 1, 16)
 
 // Variants that also exist for maps wider than one panel (guarded accesses, any W).
-#define SCAN2D_FWD_MULTI_VARIANTS(X) X(64, 4, 1) X(64, 4, 2) X(64, 4, 4) X(64, 4, 8) X(64, 4, 16) X(16, 4, 4)
+#define SCAN2D_FWD_MULTI_VARIANTS(X)                                            \
+    X(64, 4, 1, 4) X(64, 4, 2, 4) X(64, 4, 4, 4) X(64, 4, 8, 4) X(64, 4, 16, 4) \
+    X(64, 4, 1, 8) X(64, 4, 2, 8) X(64, 4, 1, 16) X(16, 4, 4, 4)
 
 using FwdKernel = void (*)(const FwdArgs);
 
 // Returns nullptr when the variant is not compiled.
-FwdKernel fwd_kernel_f32(int LG, int K, int NW, bool exact, bool fast, bool multi);
-FwdKernel fwd_kernel_bf16(int LG, int K, int NW, bool exact, bool fast, bool multi);
+FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
+FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
 
 template <typename T>
-inline FwdKernel lookup_fwd_kernel(int LG, int K, int NW, bool exact, bool fast, bool multi) {
-#define SCAN2D_X(lg, k, nw) \
-    if (exact && fast && !multi && LG == lg && K == k && NW == nw) return scan2d_fwd_kernel<T, lg, k, nw, true, true, false>;
+inline FwdKernel lookup_fwd_kernel(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {
+#define SCAN2D_X(lg, k, nw, wv) \
+    if (exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, true, false>;
     SCAN2D_FWD_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
-#define SCAN2D_X(lg, k, nw) \
-    if (!exact && fast && !multi && LG == lg && K == k && NW == nw) return scan2d_fwd_kernel<T, lg, k, nw, false, true, false>;
+#define SCAN2D_X(lg, k, nw, wv) \
+    if (!exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, false, true, false>;
     SCAN2D_FWD_RAGGED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
-#define SCAN2D_X(lg, k, nw) \
-    if (exact && !fast && !multi && LG == lg && K == k && NW == nw) return scan2d_fwd_kernel<T, lg, k, nw, true, false, false>;
+#define SCAN2D_X(lg, k, nw, wv) \
+    if (exact && !fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, false>;
     SCAN2D_FWD_GUARDED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
-#define SCAN2D_X(lg, k, nw) \
-    if (exact && !fast && multi && LG == lg && K == k && NW == nw) return scan2d_fwd_kernel<T, lg, k, nw, true, false, true>;
+#define SCAN2D_X(lg, k, nw, wv) \
+    if (exact && !fast && multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, true>;
     SCAN2D_FWD_MULTI_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
-    if (!exact && !fast && LG == 16 && K == 4 && NW == 4)
-        return multi ? scan2d_fwd_kernel<T, 16, 4, 4, false, false, true> : scan2d_fwd_kernel<T, 16, 4, 4, false, false, false>;
+    if (!exact && !fast && LG == 16 && K == 4 && NW == 4 && waves == 4)
+        return multi ? scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, true> : scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, false>;
     return nullptr;
 }
 

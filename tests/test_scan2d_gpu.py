@@ -109,6 +109,12 @@ VARIANT_CASES = [
     ("64,8,1", (1, 6, 2, 13, 512)), ("64,8,2", (1, 6, 4, 13, 504)), ("64,8,4", (1, 6, 16, 13, 512)),
     ("64,8,8", (1, 6, 16, 13, 400)),
     ("64,16,1", (1, 6, 2, 9, 1024)), ("64,16,2", (1, 6, 4, 9, 1008)), ("64,16,4", (1, 6, 16, 9, 1024)),
+    # 8 and 16 waves per workgroup (the states of one map spread over more wavefronts)
+    ("64,4,1,8", (1, 3, 8, 13, 256)), ("64,4,2,8", (1, 3, 16, 13, 256)), ("64,8,1,8", (1, 3, 8, 13, 512)),
+    ("64,8,2,8", (1, 3, 16, 13, 512)), ("64,16,1,8", (1, 3, 8, 9, 1024)),
+    ("64,4,1,16", (2, 3, 16, 13, 256)), ("64,8,1,16", (1, 3, 16, 13, 480)),
+    ("64,4,1,16", (1, 3, 16, 9, 203)), ("64,4,1,16", (1, 2, 16, 5, 777)), ("64,4,2,8", (1, 2, 16, 5, 515)),
+    ("64,4,1,8", (1, 5, 4, 9, 101)),
     # guarded (ragged W) and multi-panel forms of the K = 4 variants
     ("16,4,4", (1, 6, 16, 9, 61)), ("64,4,4", (1, 6, 16, 9, 203)), ("64,4,2", (1, 3, 4, 7, 777)),
     ("16,4,4", (1, 3, 16, 7, 150)), ("16,4,4", (1, 3, 10, 7, 150)), ("16,8,4", (1, 3, 10, 7, 128)),
@@ -187,3 +193,110 @@ def test_unit_decay_and_strong_decay(s2d):
     assert rel_err(run_fwd(s2d, inp, wl.F32), oracle_fwd(inp, wl.F32)) <= 1e-4
     inp["A"] = np.full_like(inp["A"], -3000.0)
     assert rel_err(run_fwd(s2d, inp, wl.F32), oracle_fwd(inp, wl.F32)) <= 1e-4
+
+
+# ====================================================================== backward
+
+GRADS = ("dx", "ddelta", "dA", "dBm", "dCm", "dDskip")
+
+
+def run_bwd(s2d, inp, dtype, variant=None):
+    import torch
+    d = s2d.to_device(inp, dtype)
+    old = os.environ.pop("SCAN2D_BWD_VARIANT", None)
+    if variant is not None:
+        os.environ["SCAN2D_BWD_VARIANT"] = variant
+    try:
+        out = s2d.scan2d_bwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["dy"])
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("SCAN2D_BWD_VARIANT", None)
+        if old is not None:
+            os.environ["SCAN2D_BWD_VARIANT"] = old
+    return [None if t is None else s2d.to_host(t) for t in out]
+
+
+def oracle_bwd(inp, dtype):
+    return oracle.scan2d_bwd(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"],
+                             inp["mask"], inp["dy"], dtype=dtype)
+
+
+def check_bwd(s2d, w, seed=0, variant=None):
+    inp = wl.make_inputs(w, seed=seed)
+    print(f"bwd case {w.name} Bt={w.Bt} Dc={w.Dc} N={w.N} H={w.H} W={w.W} dtype={w.dtype} variant={variant}", flush=True)
+    got = run_bwd(s2d, inp, w.dtype, variant)
+    ref = oracle_bwd(inp, w.dtype)
+    errs = {}
+    for k, (name, g, r) in enumerate(zip(GRADS, got, ref)):
+        if r is None:
+            assert g is None
+            continue
+        gv = wl.to_float(g, w.dtype) if k < 2 else g.astype(np.float64)
+        rv = wl.to_float(r, w.dtype) if k < 2 else r.astype(np.float64)
+        assert np.isfinite(gv).all(), name
+        errs[name] = rel_err(gv, rv)
+        tol = TOL[w.dtype] if k < 2 else (1e-4 if w.dtype == wl.F32 else 2e-2)
+        assert errs[name] <= tol, f"{w.name} {name}: rel err {errs[name]:.3e}"
+    if inp["mask"] is not None:                       # dx under the mask is exactly +0
+        m = np.broadcast_to(inp["mask"][:, None] != 0, got[0].shape)
+        assert not got[0].view(np.uint32 if w.dtype == wl.F32 else np.uint16)[m].any()
+    return errs
+
+
+def test_backward_matches_oracle_on_the_training_config(s2d):
+    check_bwd(s2d, wl.CONFIGS[4])
+
+
+BWD_SHAPES = [
+    # Bt, Dc, N, H, W, dtype, mask
+    (1, 3, 4, 1, 1, wl.F32, 0.0),
+    (2, 3, 4, 1, 37, wl.F32, 0.3),         # H = 1
+    (2, 3, 4, 29, 1, wl.F32, 0.3),         # W = 1
+    (1, 5, 16, 14, 14, wl.F32, 0.0),
+    (2, 7, 16, 56, 56, wl.F32, 0.2),
+    (1, 6, 16, 23, 100, wl.F32, 0.3),      # 8 columns per lane
+    (1, 5, 16, 9, 200, wl.F32, 0.4),       # wave-wide lane groups
+    (1, 3, 5, 11, 45, wl.F32, 0.2),        # N below a full set of lane groups
+    (1, 2, 40, 7, 33, wl.F32, 0.2),        # N > 16: four states per lane
+    (1, 2, 1, 19, 64, wl.F32, 0.0),
+    (1, 9, 16, 6, 300, wl.F32, 0.3),
+    (1, 4, 8, 5, 1000, wl.F32, 0.3),
+    (3, 5, 16, 13, 24, wl.BF16, 0.3),      # bf16 storage
+    (1, 3, 16, 10, 130, wl.BF16, 0.3),
+    (4, 1, 16, 10, 24, wl.F32, 0.3),       # one channel per batch item
+    (2, 21, 16, 10, 40, wl.F32, 0.3),      # ragged last channel group
+]
+
+
+@pytest.mark.parametrize("shape", BWD_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_backward_edge_shapes(s2d, shape):
+    Bt, Dc, N, H, W, dtype, mf = shape
+    check_bwd(s2d, wl.Workload("bedge", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True), seed=4)
+
+
+@pytest.mark.parametrize("variant,W", [("16,4", 60), ("16,8", 60), ("16,12", 190), ("16,16", 250),
+                                       ("64,4", 250), ("64,8", 260), ("64,16", 60)])
+def test_backward_variants(s2d, variant, W):
+    check_bwd(s2d, wl.Workload("bvar", 2, 6, 16, 11, W, wl.F32, mask_frac=0.3, backward=True), seed=6, variant=variant)
+
+
+def test_backward_is_reproducible_and_ignores_garbage_under_the_mask(s2d):
+    w = wl.Workload("brep", 2, 12, 16, 20, 72, wl.F32, mask_frac=0.4, backward=True)
+    inp = wl.make_inputs(w, seed=8)
+    a = run_bwd(s2d, inp, wl.F32)
+    b = run_bwd(s2d, inp, wl.F32)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+    p = wl.make_inputs(w, seed=8, poison_under_mask=np.nan)
+    for u, v in zip(a, run_bwd(s2d, p, wl.F32)):
+        assert np.array_equal(u, v)
+
+
+def test_backward_without_skip_term(s2d):
+    w = wl.Workload("bnoskip", 1, 6, 16, 12, 64, wl.F32, backward=True)
+    inp = wl.make_inputs(w, seed=10)
+    inp["Dskip"] = None
+    got, ref = run_bwd(s2d, inp, wl.F32), oracle_bwd(inp, wl.F32)
+    assert got[5] is None and ref[5] is None
+    for g, r in zip(got[:5], ref[:5]):
+        assert rel_err(g, r) <= 1e-4
