@@ -19,6 +19,33 @@
 
 namespace scan2d {
 
+// Sum of the NG partial sums of one column (stride STRIDE floats), added in index order.  The
+// loads are issued together for the common group counts so that their LDS latencies overlap.
+template <int STRIDE, int G>
+__device__ __forceinline__ float sum_partials_fixed(const float* p) {
+    float v[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) v[g] = p[g * STRIDE];
+    float acc = v[0];
+#pragma unroll
+    for (int g = 1; g < G; ++g) acc += v[g];
+    return acc;
+}
+template <int STRIDE>
+__device__ __forceinline__ float sum_partials(const float* p, int NG) {
+    switch (NG) {
+        case 2: return sum_partials_fixed<STRIDE, 2>(p);
+        case 4: return sum_partials_fixed<STRIDE, 4>(p);
+        case 8: return sum_partials_fixed<STRIDE, 8>(p);
+        case 16: return sum_partials_fixed<STRIDE, 16>(p);
+        default: {
+            float acc = p[0];
+            for (int g = 1; g < NG; ++g) acc += p[g * STRIDE];
+            return acc;
+        }
+    }
+}
+
 struct FwdArgs {
     const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
     const float* Dskip; const uint8_t* mask; void* y;
@@ -205,11 +232,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                     const float* base = &ypart[step & 1][slot - sg][0];   // first group of this map
                     for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
                         const int gc = panel * PANEL + col;
-                        if (gc < W) {
-                            float acc = base[col];
-                            for (int g = 1; g < NG; ++g) acc += base[g * PANEL + col];
-                            store_elem(yrow + xlane + gc, acc);
-                        }
+                        if (gc < W) store_elem(yrow + xlane + gc, sum_partials<PANEL>(base + col, NG));
                     }
                 }
             }
