@@ -60,6 +60,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     int LG, K;
     if (W <= 64) { LG = 16; K = 4; }
     else if (W <= 128) { LG = 16; K = 8; }
+    else if (W <= 192) { LG = 16; K = 12; }
     else if (W <= 256) { LG = 64; K = 4; }
     else if (W <= 512) { LG = 64; K = 8; }
     else if (W <= 1024) { LG = 64; K = 16; }
@@ -72,18 +73,20 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     // or 8 wavefront-wide lane groups with two states each; four states per lane beyond N = 16
     int waves, NW;
     if (LG == 16) { waves = 4; NW = N <= 16 ? 1 : 4; }
+    else if (N <= 16 && K == 16) { waves = 4; NW = 4; }     // widest maps: LDS bounds the workgroup size
     else if (N <= 16) { waves = 8; NW = 2; }
     else { waves = 16; NW = 4; }
     const int slots = waves * 64 / LG;
     if ((N + NW - 1) / NW > slots) return false;
-    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves) : bwd_kernels_f32(LG, K, NW, waves);
+    const bool fast = (W % K) == 0;
+    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast) : bwd_kernels_f32(LG, K, NW, waves, fast);
     if (pl.k.main == nullptr) return false;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
     pl.NG = (N + NW - 1) / NW;
     pl.nb = (d->H + pl.RB - 1) / pl.RB;
     // channels per workgroup: bounded by LDS (150 KB) and by keeping at least 2048 waves in flight
     const size_t T = (size_t)waves * 64;
-    const size_t fixed = 2 * T * K, per = T * ((size_t)NW * K + NW + 1);
+    const size_t fixed = 4 * T * K, per = T * ((size_t)NW * K + NW + 1);
     int gs_lds = (int)std::max<size_t>(1, (38400 - std::min<size_t>(fixed, 38400)) / per);
     const int JPW = slots / pl.NG;
     int gs = std::min({gs_lds, 8, d->Dc});
@@ -134,7 +137,6 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.pD = dDskip == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pD) : dDskip);
     a.Bt = d->Bt; a.Dc = d->Dc; a.H = d->H; a.W = d->W; a.N = d->N;
     a.NG = pl.NG; a.GS = pl.GS; a.CG = pl.CG; a.nb = pl.nb;
-    a.fast = ((d->W * (d->dtype == SCAN2D_BF16 ? 2 : 4)) % 4 == 0 && d->W % 4 == 0) ? 1 : 0;
 
     const int slots = pl.waves * 64 / pl.LG;
     const long long maps = (long long)d->Bt * d->Dc;

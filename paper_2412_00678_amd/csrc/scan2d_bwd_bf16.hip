@@ -1,5 +1,5 @@
 // bf16-storage instantiations of the backward kernels.
 #include "scan2d_bwd_variants.hpp"
 namespace scan2d {
-BwdKernels bwd_kernels_bf16(int LG, int K, int NW, int waves) { return lookup_bwd_kernels<bf16_t>(LG, K, NW, waves); }
+BwdKernels bwd_kernels_bf16(int LG, int K, int NW, int waves, bool fast) { return lookup_bwd_kernels<bf16_t>(LG, K, NW, waves, fast); }
 }

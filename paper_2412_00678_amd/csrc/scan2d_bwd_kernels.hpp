@@ -16,9 +16,14 @@
 // Lane mapping is that of the forward kernel: a lane group of LG lanes owns LG*K columns, lane l
 // the columns [l*K, l*K+K) and NW states; NG = ceil(N/NW) lane groups share a map and meet in
 // LDS once per row for the sums over states (ddelta, dx).
+// FAST (W a multiple of K, rows 4-byte aligned): unguarded wide accesses; a lane past the last
+// column mirrors lane 0 with dy forced to 0, so nothing flows out of it into the reverse scans,
+// and it never stores.  Otherwise every element access is guarded and out-of-range cells read 0.
+// The inputs of the next row are requested before the current row is processed.
 #pragma once
 
 #include "scan2d_common.hpp"
+#include "scan2d_fwd.hpp"   // sum_partials
 
 namespace scan2d {
 
@@ -35,11 +40,43 @@ struct BwdArgs {
     int GS;              // channels a workgroup handles one after the other
     int CG;              // channel groups = ceil(Dc / GS)
     int nb;              // bands = ceil(H / RB)
-    int fast;            // rows start 4-byte aligned: wide loads allowed for full lanes
 };
 
+template <int K>
+__device__ __forceinline__ void load_f32s(const float* __restrict__ p, float* v) {
+    uint32_t r[K];
+    load_words<K>(reinterpret_cast<const uint32_t*>(p), r);
+#pragma unroll
+    for (int j = 0; j < K; ++j) v[j] = __uint_as_float(r[j]);
+}
+template <int K>
+__device__ __forceinline__ void store_f32s(float* __restrict__ p, const float* v) {
+    uint32_t r[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) r[j] = __float_as_uint(v[j]);
+    store_words<K>(reinterpret_cast<uint32_t*>(p), r);
+}
+
+// K elements of one row for this lane (see FAST above).
+template <typename T, int K, bool FAST>
+__device__ __forceinline__ void ld_elems(const T* __restrict__ rowp, int col0, uint32_t lcol, int W, uint32_t* r) {
+    if constexpr (FAST) load_words<words_of<T, K>()>(reinterpret_cast<const uint32_t*>(rowp + lcol), r);
+    else load_row<T, K>(rowp, col0, W, false, r);
+}
+template <int K, bool FAST>
+__device__ __forceinline__ void ld_mask(const uint8_t* __restrict__ rowp, int col0, uint32_t lcol, int W, uint32_t* r) {
+    if (rowp == nullptr) {
+#pragma unroll
+        for (int w = 0; w < K / 4; ++w) r[w] = 0u;
+    } else if constexpr (FAST) {
+        load_words<K / 4>(reinterpret_cast<const uint32_t*>(rowp + lcol), r);
+    } else {
+        load_mask<K>(rowp, col0, W, false, r);
+    }
+}
+
 // ---------------------------------------------------------------------------- checkpoint sweep
-template <typename T, int LG, int K, int NW, int WAVES, int RB>
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdArgs p) {
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
@@ -54,7 +91,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
     const int b = (int)(map / p.Dc), c = (int)(map % p.Dc);
     const int n0 = sg * NW, nvalid = min(NW, N - n0);
     const int col0 = l * K;
-    const bool fast = p.fast != 0;
+    const bool inside = col0 < W;
+    const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
     const T* xm = reinterpret_cast<const T*>(p.x) + (size_t)map * HW;
     const T* dm = reinterpret_cast<const T*>(p.delta) + (size_t)map * HW;
     const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
@@ -68,14 +106,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 #pragma unroll
         for (int j = 0; j < K; ++j) h[s][j] = 0.0f;
     }
-    for (int i = 0; i < H; ++i) {
-        const size_t ro = (size_t)i * W;
-        uint32_t rx[XW], rd[XW], rm[K / 4];
-        load_row<T, K>(xm + ro, col0, W, fast, rx);
-        load_row<T, K>(dm + ro, col0, W, fast, rd);
+    uint32_t rx[XW], rd[XW], rm[K / 4], rB[NW][XW];
+    ld_elems<T, K, FAST>(xm, col0, lcol, W, rx);
+    ld_elems<T, K, FAST>(dm, col0, lcol, W, rd);
+    ld_mask<K, FAST>(mm, col0, lcol, W, rm);
 #pragma unroll
-        for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
-        if (mm) load_mask<K>(mm + ro, col0, W, fast, rm);
+    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s], col0, lcol, W, rB[s]);
+
+    for (int i = 0; i + 1 < H; ++i) {                         // the last row's state is never needed
+        const size_t nxt = (size_t)(i + 1) * W;
         float dl[K], dxe[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) {
@@ -83,20 +122,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
             const float xe = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
             dxe[j] = dl[j] * xe;
         }
+        ld_elems<T, K, FAST>(xm + nxt, col0, lcol, W, rx);
+        ld_elems<T, K, FAST>(dm + nxt, col0, lcol, W, rd);
+        ld_mask<K, FAST>(mm ? mm + nxt : nullptr, col0, lcol, W, rm);
 #pragma unroll
         for (int s = 0; s < NW; ++s) {
-            uint32_t rB[XW];
-            load_row<T, K>(Bs[s] + ro, col0, W, fast, rB);
             float a[K], hl[K], pl[K];
 #pragma unroll
             for (int j = 0; j < K; ++j) a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
-            hl[0] = dxe[0] * get_elem<T, K>(rB, 0);
+            hl[0] = dxe[0] * get_elem<T, K>(rB[s], 0);
             pl[0] = a[0];
 #pragma unroll
             for (int j = 1; j < K; ++j) {
-                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(rB, j));
+                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(rB[s], j));
                 pl[j] = pl[j - 1] * a[j];
             }
+            ld_elems<T, K, FAST>(Bs[s] + nxt, col0, lcol, W, rB[s]);
             float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
             group_scan<LG, 1>(P, Hh, cin);
 #pragma unroll
@@ -105,15 +146,19 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
                 h[s][j] = fmaf(a[j], h[s][j], hh);
             }
         }
-        if ((i + 1) % RB == 0 && i + 1 < H) {                 // h[i] enters band (i+1)/RB
+        if ((i + 1) % RB == 0) {                              // h[i] enters band (i+1)/RB
             const int band = (i + 1) / RB;
 #pragma unroll
             for (int s = 0; s < NW; ++s) {
                 if (s < nvalid) {
                     float* dst = p.ck + (((size_t)map * p.nb + band) * N + n0 + s) * W;
+                    if constexpr (FAST) {
+                        if (inside) store_f32s<K>(dst + col0, h[s]);
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < K; ++j)
-                        if (col0 + j < W) dst[col0 + j] = h[s][j];
+                        for (int j = 0; j < K; ++j)
+                            if (col0 + j < W) dst[col0 + j] = h[s][j];
+                    }
                 }
             }
         }
@@ -122,11 +167,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 
 // ---------------------------------------------------------------------------------- main sweep
 // Dynamic LDS layout (floats), T = workgroup threads:
-//   part [2][T*K]      per-thread partial sums over its states of ddelta and dx for one row
+//   part [2][2][T*K]   per-thread partial sums over its states of ddelta and dx (double buffered)
 //   gaL  [GS][T*NW*K]  a[i+1,j]*g[i+1,j] of every channel, kept between bands
 //   dAL  [GS][T*NW]    per-lane partial of dA
 //   dDL  [GS][T]       per-lane partial of dDskip (first lane group of a map only)
-template <typename T, int LG, int K, int NW, int WAVES, int RB>
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdArgs p) {
     constexpr int THREADS = WAVES * 64;
     constexpr int SLOTS = THREADS / LG;
@@ -134,8 +179,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     constexpr int PANEL = LG * K;
     extern __shared__ float lds[];
     const int GS = p.GS;
-    float* part = lds;                                   // [2][SLOTS][PANEL]
-    float* gaL = part + 2 * THREADS * K;                 // [GS][THREADS][NW*K]
+    float* part = lds;                                   // [2][2][SLOTS][PANEL]
+    float* gaL = part + 4 * THREADS * K;                 // [GS][THREADS][NW*K]
     float* dAL = gaL + (size_t)GS * THREADS * NW * K;    // [GS][THREADS][NW]
     float* dDL = dAL + (size_t)GS * THREADS * NW;        // [GS][THREADS]
 
@@ -156,7 +201,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     const size_t HW = (size_t)H * W;
     const int n0 = sg * NW, nvalid = min(NW, N - n0);
     const int col0 = l * K;
-    const bool fast = p.fast != 0;
+    const bool inside = col0 < W;
+    const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
     const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
     const T* Bs[NW];
     const T* Cs[NW];
@@ -176,8 +222,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     }
     // every thread only ever touches its own gaL / dAL / dDL entries: no barrier needed for them
 
+    int step = 0;                                         // rows reduced so far: parity picks the LDS buffer
     for (int band = p.nb - 1; band >= 0; --band) {
         const int r0 = band * RB;
+        const int ilast = min(r0 + RB, H) - 1;            // bottom row of the band
         float dBacc[RB][NW][K], dCacc[RB][NW][K];
 #pragma unroll
         for (int r = 0; r < RB; ++r)
@@ -205,45 +253,53 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 
             // ---- scans 1 and 2: rebuild h[i-1,j] and hhor[i,j-1] for the rows of the band
             float hprev[RB][NW][K], hhl[RB][NW][K];
-            {
+            if (act) {
+                uint32_t fx[2][XW], fd[2][XW], fm[2][K / 4], fB[2][NW][XW];
+                auto issue = [&](int buf, int i) {
+                    const size_t ro = (size_t)i * W;
+                    ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, fx[buf]);
+                    ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, fd[buf]);
+                    ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, fm[buf]);
+#pragma unroll
+                    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, fB[buf][s]);
+                };
+                issue(0, r0);
                 float hcur[NW][K];
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
                     const float* src = p.ck + ((map * p.nb + band) * N + n0 + (s < nvalid ? s : 0)) * W;
+                    if (band == 0) {
 #pragma unroll
-                    for (int j = 0; j < K; ++j)
-                        hcur[s][j] = (band > 0 && col0 + j < W) ? src[col0 + j] : 0.0f;
+                        for (int j = 0; j < K; ++j) hcur[s][j] = 0.0f;
+                    } else if constexpr (FAST) {
+                        load_f32s<K>(src + lcol, hcur[s]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < K; ++j) hcur[s][j] = (col0 + j < W) ? src[col0 + j] : 0.0f;
+                    }
                 }
 #pragma unroll
                 for (int r = 0; r < RB; ++r) {
                     const int i = r0 + r;
-                    if (i < H && act) {
-                        const size_t ro = (size_t)i * W;
-                        uint32_t rx[XW], rd[XW], rm[K / 4];
-                        load_row<T, K>(xm + ro, col0, W, fast, rx);
-                        load_row<T, K>(dm + ro, col0, W, fast, rd);
-#pragma unroll
-                        for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
-                        if (mm) load_mask<K>(mm + ro, col0, W, fast, rm);
+                    if (i < H) {
+                        if (r + 1 < RB && i + 1 < H) issue((r + 1) & 1, i + 1);
                         float dl[K], dxe[K];
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
-                            dl[j] = get_elem<T, K>(rd, j);
-                            const float xe = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
+                            dl[j] = get_elem<T, K>(fd[r & 1], j);
+                            const float xe = mask_bit<K>(fm[r & 1], j) ? 0.0f : get_elem<T, K>(fx[r & 1], j);
                             dxe[j] = dl[j] * xe;
                         }
 #pragma unroll
                         for (int s = 0; s < NW; ++s) {
-                            uint32_t rB[XW];
-                            load_row<T, K>(Bs[s] + ro, col0, W, fast, rB);
                             float a[K], hl[K], pl[K];
 #pragma unroll
                             for (int j = 0; j < K; ++j) a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
-                            hl[0] = dxe[0] * get_elem<T, K>(rB, 0);
+                            hl[0] = dxe[0] * get_elem<T, K>(fB[r & 1][s], 0);
                             pl[0] = a[0];
 #pragma unroll
                             for (int j = 1; j < K; ++j) {
-                                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(rB, j));
+                                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(fB[r & 1][s], j));
                                 pl[j] = pl[j - 1] * a[j];
                             }
                             float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
@@ -270,25 +326,34 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                 for (int j = 0; j < K; ++j) ga[s][j] = gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j];
             }
+            uint32_t bx[2][XW], bd[2][XW], by[2][XW], bm[2][K / 4], bB[2][NW][XW], bC[2][NW][XW];
+            auto issue_r = [&](int buf, int i) {
+                const size_t ro = (size_t)i * W;
+                ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, bx[buf]);
+                ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, bd[buf]);
+                ld_elems<T, K, FAST>(dym + ro, col0, lcol, W, by[buf]);
+                ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, bm[buf]);
+#pragma unroll
+                for (int s = 0; s < NW; ++s) {
+                    ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, bB[buf][s]);
+                    ld_elems<T, K, FAST>(Cs[s] + ro, col0, lcol, W, bC[buf][s]);
+                }
+            };
 #pragma unroll
             for (int r = RB - 1; r >= 0; --r) {
                 const int i = r0 + r;
                 if (i < H) {                                               // uniform over the workgroup
+                    if (i == ilast) issue_r(r & 1, i);
+                    if (r > 0) issue_r((r - 1) & 1, i - 1);
                     const size_t ro = (size_t)i * W;
-                    uint32_t rx[XW], rd[XW], ry[XW], rm[K / 4];
-                    load_row<T, K>(xm + ro, col0, W, fast, rx);
-                    load_row<T, K>(dm + ro, col0, W, fast, rd);
-                    load_row<T, K>(dym + ro, col0, W, fast, ry);
-#pragma unroll
-                    for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
-                    if (mm) load_mask<K>(mm + ro, col0, W, fast, rm);
                     float dl[K], xe[K], dxe[K], dyv[K], ddl[K], dxl[K];
 #pragma unroll
                     for (int j = 0; j < K; ++j) {
-                        dl[j] = get_elem<T, K>(rd, j);
-                        xe[j] = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
+                        dl[j] = get_elem<T, K>(bd[r & 1], j);
+                        xe[j] = mask_bit<K>(bm[r & 1], j) ? 0.0f : get_elem<T, K>(bx[r & 1], j);
                         dxe[j] = dl[j] * xe[j];
-                        dyv[j] = get_elem<T, K>(ry, j);
+                        dyv[j] = get_elem<T, K>(by[r & 1], j);
+                        if (FAST && !inside) dyv[j] = 0.0f;               // nothing flows out of a lane past the map
                         ddl[j] = 0.0f;
                         dxl[j] = dsk * dyv[j];
                         dDb = fmaf(dyv[j], xe[j], dDb);
@@ -296,18 +361,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                     for (int s = 0; s < NW; ++s) {
                         if (act && s < nvalid) {
-                            uint32_t rB[XW], rC[XW];
-                            load_row<T, K>(Bs[s] + ro, col0, W, fast, rB);
-                            load_row<T, K>(Cs[s] + ro, col0, W, fast, rC);
                             float a[K], Bv[K], g[K];
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
-                                Bv[j] = get_elem<T, K>(rB, j);
+                                Bv[j] = get_elem<T, K>(bB[r & 1][s], j);
                                 const float hh = fmaf(a[j], hhl[r][s][j], dxe[j] * Bv[j]);   // hhor[i,j]
                                 const float hv = fmaf(a[j], hprev[r][s][j], hh);             // h[i,j]
                                 dCacc[r][s][j] = fmaf(dyv[j], hv, dCacc[r][s][j]);
-                                g[j] = fmaf(dyv[j], get_elem<T, K>(rC, j), ga[s][j]);        // scan 3
+                                g[j] = fmaf(dyv[j], get_elem<T, K>(bC[r & 1][s], j), ga[s][j]);   // scan 3
                                 ga[s][j] = a[j] * g[j];
                             }
                             // scan 4: q[j] = g[j] + a[j+1] * q[j+1]
@@ -337,35 +399,30 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                         }
                     }
                     // sums over the states held by the other lane groups of this map
-                    float* mine = part + (size_t)tid * K;
-                    __syncthreads();                                       // previous row's sums are consumed
+                    float* mine = part + (size_t)(step & 1) * 2 * THREADS * K + (size_t)tid * K;
 #pragma unroll
                     for (int j = 0; j < K; ++j) {
                         mine[j] = ddl[j];
-                        mine[THREADS * K + j] = mask_bit<K>(rm, j) ? 0.0f : dxl[j];
+                        mine[THREADS * K + j] = mask_bit<K>(bm[r & 1], j) ? 0.0f : dxl[j];
                     }
                     __syncthreads();
                     if (act) {
-                        const float* base = part + (size_t)(slot - sg) * PANEL;
+                        const float* base = part + (size_t)(step & 1) * 2 * THREADS * K + (size_t)(slot - sg) * PANEL;
                         for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
                             if (col < W) {
-                                float sd = base[col], sx = base[THREADS * K + col];
-                                for (int gq = 1; gq < NG; ++gq) {
-                                    sd += base[gq * PANEL + col];
-                                    sx += base[THREADS * K + gq * PANEL + col];
-                                }
-                                store_elem(ddm + ro + col, sd);
-                                store_elem(dxm + ro + col, sx);
+                                store_elem(ddm + ro + col, sum_partials<PANEL>(base + col, NG));
+                                store_elem(dxm + ro + col, sum_partials<PANEL>(base + THREADS * K + col, NG));
                             }
                         }
                     }
+                    ++step;
                 }
             }
 #pragma unroll
             for (int s = 0; s < NW; ++s) {
 #pragma unroll
                 for (int j = 0; j < K; ++j) gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j] = ga[s][j];
-                dAL[((size_t)ch * THREADS + tid) * NW + s] += dAb[s];
+                dAL[((size_t)ch * THREADS + tid) * NW + s] += (FAST && !inside) ? 0.0f : dAb[s];
             }
             dDL[(size_t)ch * THREADS + tid] += dDb;
         }
@@ -380,9 +437,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                     for (int s = 0; s < NW; ++s) {
                         if (s < nvalid) {
                             const size_t o = ((((size_t)b * p.CG + cg) * N + n0 + s) * H + i) * W;
+                            if constexpr (FAST) {
+                                if (inside) { store_f32s<K>(p.pB + o + col0, dBacc[r][s]); store_f32s<K>(p.pC + o + col0, dCacc[r][s]); }
+                            } else {
 #pragma unroll
-                            for (int j = 0; j < K; ++j)
-                                if (col0 + j < W) { p.pB[o + col0 + j] = dBacc[r][s][j]; p.pC[o + col0 + j] = dCacc[r][s][j]; }
+                                for (int j = 0; j < K; ++j)
+                                    if (col0 + j < W) { p.pB[o + col0 + j] = dBacc[r][s][j]; p.pC[o + col0 + j] = dCacc[r][s][j]; }
+                            }
                         }
                     }
                 }

@@ -9,23 +9,23 @@ namespace scan2d {
 #define SCAN2D_BWD_VARIANTS(X)                                             \
     X(16, 4, 1, 4, 4) X(16, 8, 1, 4, 4) X(16, 12, 1, 4, 2) X(16, 16, 1, 4, 2) \
     X(16, 4, 4, 4, 2) X(16, 8, 4, 4, 1)                                       \
-    X(64, 4, 2, 8, 4) X(64, 8, 2, 8, 2) X(64, 16, 2, 8, 1)                    \
+    X(64, 4, 2, 8, 4) X(64, 8, 2, 8, 2) X(64, 16, 4, 4, 1)                     \
     X(64, 4, 4, 16, 2) X(64, 8, 4, 16, 1)
 
 using BwdKernel = void (*)(const BwdArgs);
 struct BwdKernels { BwdKernel ckpt = nullptr; BwdKernel main = nullptr; int RB = 0; };
 
-BwdKernels bwd_kernels_f32(int LG, int K, int NW, int waves);
-BwdKernels bwd_kernels_bf16(int LG, int K, int NW, int waves);
+BwdKernels bwd_kernels_f32(int LG, int K, int NW, int waves, bool fast);
+BwdKernels bwd_kernels_bf16(int LG, int K, int NW, int waves, bool fast);
 
 template <typename T>
-inline BwdKernels lookup_bwd_kernels(int LG, int K, int NW, int waves) {
+inline BwdKernels lookup_bwd_kernels(int LG, int K, int NW, int waves, bool fast) {
     BwdKernels r;
-#define SCAN2D_X(lg, k, nw, wv, rb)                                    \
-    if (LG == lg && K == k && NW == nw && waves == wv) {               \
-        r.ckpt = scan2d_bwd_ckpt_kernel<T, lg, k, nw, wv, rb>;         \
-        r.main = scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb>;         \
-        r.RB = rb;                                                     \
+#define SCAN2D_X(lg, k, nw, wv, rb)                                                                     \
+    if (LG == lg && K == k && NW == nw && waves == wv) {                                                \
+        r.ckpt = fast ? scan2d_bwd_ckpt_kernel<T, lg, k, nw, wv, rb, true> : scan2d_bwd_ckpt_kernel<T, lg, k, nw, wv, rb, false>; \
+        r.main = fast ? scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, true> : scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, false>; \
+        r.RB = rb;                                                                                      \
     }
     SCAN2D_BWD_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
