@@ -52,6 +52,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 struct FwdChoice {
     int LG = 0, K = 0, NW = 0, waves = 4;
     bool exact = true, fast = true, multi = false;
+    int RPB = 1;
+    size_t lds_bytes = 0;
     int NG = 0, MPW = 0, panels = 0;
     FwdKernel kernel = nullptr;
 };
@@ -66,7 +68,8 @@ FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool f
                                 : fwd_kernel_f32(LG, K, NW, waves, exact, fast, multi);
 }
 
-bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, FwdChoice* out) {
+// rpb: rows between two barriers; 0 = decide here
+bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb, FwdChoice* out) {
     const int slots = waves * 64 / LG;
     FwdChoice c;
     c.LG = LG; c.K = K; c.NW = NW; c.waves = waves;
@@ -82,53 +85,67 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, FwdChoi
     if (span >= 2147483648.0) return false;
     c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi);
     if (c.kernel == nullptr) return false;
+    // LDS for the partial sums: 2 buffers x RPB rows x (threads * K) floats.  Few large maps (one
+    // workgroup per CU at most) can afford 64 KB; otherwise stay near 24 KB so that several
+    // workgroups fit a CU.
+    const size_t row_bytes = (size_t)waves * 64 * K * sizeof(float);
+    const double wgs = std::ceil((double)d->Bt * d->Dc / c.MPW);
+    const size_t budget = wgs <= 256.0 ? 65536 : 24576;
+    c.RPB = 1;
+    if (c.NG > 1) {
+        if (rpb == 1 || rpb == 2 || rpb == 4) c.RPB = rpb;
+        else if (2 * 4 * row_bytes <= budget) c.RPB = 4;
+        else if (2 * 2 * row_bytes <= budget) c.RPB = 2;
+    }
+    c.lds_bytes = c.NG > 1 ? 2 * (size_t)c.RPB * row_bytes : 0;
+    if (c.lds_bytes > 160 * 1024) return false;
     *out = c;
     return true;
 }
 
-// Rough cost in VALU issue slots per (position, channel, state) divided by the fraction of
-// the machine the launch can keep busy; only used to rank variants.
+// Estimated run time (arbitrary units) of a variant, used only to rank the variants.  Calibrated
+// against measurements on the five benchmark shapes: instructions per workgroup row (core
+// arithmetic, lane-group scans, per-position work, fixed loop overhead, LDS reduction) times
+// rows, divided by the issue efficiency that the number of resident waves per SIMD allows
+// (about 0.40 / 0.55 / 0.70 / 0.85 / 0.95 for 1 / 2 / 3 / 4 / 5+ waves).
 double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
-    const double maps = (double)d->Bt * d->Dc;
-    const int slots = c.waves * 64 / c.LG;
-    const double lane_util = (double)d->W / ((double)c.panels * c.LG * c.K);
-    const double slot_util = (double)(c.MPW * c.NG) / slots * (double)d->N / (c.NG * c.NW);
-    const double steps = c.LG == 64 ? 6.0 : 4.0;
     const bool bf16 = d->dtype == SCAN2D_BF16;
-    double ops = 7.5 + (bf16 ? 2.0 : 0.0) + 2.0 * (c.K - 1) / c.K + (2.0 * steps) / c.K
-               + ((bf16 ? 7.0 : 5.0) + (c.NG > 1 ? 2.0 + 0.5 * c.NG : 1.0)) / c.NW;
-    if (!c.fast) ops *= 1.6;
-    if (c.multi) ops += 1.0;
-    // waves per SIMD the launch sustains: limited by the grid and by the registers of the variant
+    const double maps = (double)d->Bt * d->Dc;
     const double wgs = std::ceil(maps / c.MPW);
+    const double c_core = bf16 ? 10.5 : 8.5;
+    const double c_scan = c.LG == 64 ? 13.0 : (c.LG == 32 ? 12.0 : 9.0);
+    const double c_pos = bf16 ? 9.0 : 6.0;
+    const double cols_t = std::max(1.0, (double)c.K / c.NG);
+    const double c_red = c.NG > 1 ? cols_t * (4.0 + 1.5 * c.NG) + 6.0 : 4.0;
+    double row = c.K * c.NW * c_core + c.NW * c_scan + c_pos * c.K + 35.0 + c_red;
+    if (!c.fast) row *= 1.6;
+    if (c.multi) row += 8.0 * c.NW;
     const double regs = 40.0 + (bf16 ? 6.5 : 8.5) * c.K * c.NW;
-    // waves per SIMD by registers (launch bounds force at least waves/4), at most 8
     const double occ = std::min(8.0, std::max(std::floor(512.0 / regs), c.waves / 4.0));
-    const double resident = 256.0 * std::max(1.0, std::floor(occ * 4.0 / c.waves));   // workgroups on the chip
-    const double rounds = std::ceil(wgs / resident);
-    const double wps = std::min(occ, wgs * c.waves / 1024.0 / rounds);     // average waves per SIMD
-    // issue rate of one SIMD against its number of waves: 1 -> 0.5, 2 -> 0.85, 4 -> 1.0 (measured)
-    double rate;
-    if (wps <= 1.0) rate = 0.5 * wps;
-    else if (wps <= 2.0) rate = 0.5 + 0.35 * (wps - 1.0);
-    else rate = std::min(1.0, 0.85 + 0.075 * (wps - 2.0));
-    const double tail = (wgs / resident) / rounds;                         // last round partly empty
-    return ops / (lane_util * slot_util * rate * std::max(tail, 0.05));
+    const double res_wg = 256.0 * std::max(1.0, std::floor(occ * 4.0 / c.waves));   // workgroups resident on the chip
+    const double rounds = std::ceil(wgs / res_wg);
+    double wps = std::min(occ, wgs * c.waves / 1024.0 / rounds);
+    if (rounds > 1.0) wps = std::max(wps, 1.0);                                      // several rounds: SIMDs are never empty
+    const double steps = (double)d->H * c.panels * row;                              // instructions of one wave
+    if (wps < 1.0) return steps * 8.0;                                               // a lone wave: its own critical path
+    const double eff = std::min(0.95, 0.25 + 0.15 * wps);
+    const double tail = wgs > res_wg ? rounds / (wgs / res_wg) : 1.0;
+    return wgs * c.waves * steps * 4.0 / (1024.0 * eff) * tail;
 }
 
 int choose_fwd(const scan2d_desc* d, FwdChoice* out) {
-    if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES"
-        int LG = 0, K = 0, NW = 0, waves = 4;
-        const int got = std::sscanf(env, "%d,%d,%d,%d", &LG, &K, &NW, &waves);
-        if (got >= 3 && (LG == 16 || LG == 64) && NW >= 1 && (waves == 4 || waves == 8 || waves == 16) &&
-            fill_choice(d, LG, K, NW, waves, out))
+    if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES[,RPB]"
+        int LG = 0, K = 0, NW = 0, waves = 4, rpb = 0;
+        const int got = std::sscanf(env, "%d,%d,%d,%d,%d", &LG, &K, &NW, &waves, &rpb);
+        if (got >= 3 && (LG == 16 || LG == 32 || LG == 64) && NW >= 1 && (waves == 4 || waves == 8 || waves == 16) &&
+            fill_choice(d, LG, K, NW, waves, rpb, out))
             return SCAN2D_OK;
     }
     bool found = false;
     double best = 0.0;
     for (const V4& v : kFwdVariants) {
         FwdChoice c;
-        if (!fill_choice(d, v.LG, v.K, v.NW, v.waves, &c)) continue;
+        if (!fill_choice(d, v.LG, v.K, v.NW, v.waves, 0, &c)) continue;
         const double cost = fwd_cost(d, c);
         if (!found || cost < best) { best = cost; *out = c; found = true; }
     }
@@ -167,11 +184,14 @@ extern "C" int scan2d_fwd(const scan2d_desc* desc, const void* x, const void* de
     a.carry = static_cast<float*>(workspace);
     a.maps = (long long)desc->Bt * desc->Dc;
     a.Dc = desc->Dc; a.H = desc->H; a.W = desc->W; a.N = desc->N;
-    a.NG = ch.NG; a.MPW = ch.MPW; a.panels = ch.panels;
+    a.NG = ch.NG; a.MPW = ch.MPW; a.panels = ch.panels; a.RPB = ch.RPB;
     const long long wgs = (a.maps + ch.MPW - 1) / ch.MPW;
     if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
     (void)hipGetLastError();
-    hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(ch.waves * 64), 0, static_cast<hipStream_t>(stream), a);
+    if (ch.lds_bytes > 65536)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ch.kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)ch.lds_bytes);
+    hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(ch.waves * 64), ch.lds_bytes, static_cast<hipStream_t>(stream), a);
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
 

@@ -65,15 +65,20 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     else if (W <= 512) { LG = 64; K = 8; }
     else if (W <= 1024) { LG = 64; K = 16; }
     else return false;
-    if (const char* env = std::getenv("SCAN2D_BWD_VARIANT")) {   // tuning aid: "LG,K"
-        int eLG = 0, eK = 0;
-        if (std::sscanf(env, "%d,%d", &eLG, &eK) == 2 && (eLG == 16 || eLG == 64) && eLG * eK >= W) { LG = eLG; K = eK; }
+    int force_waves = 0, force_gs = 0;
+    if (const char* env = std::getenv("SCAN2D_BWD_VARIANT")) {   // tuning aid: "LG,K[,WAVES[,GS]]"
+        int eLG = 0, eK = 0, eW = 0, eG = 0;
+        const int got = std::sscanf(env, "%d,%d,%d,%d", &eLG, &eK, &eW, &eG);
+        if (got >= 2 && (eLG == 16 || eLG == 64) && eLG * eK >= W) { LG = eLG; K = eK; }
+        if (got >= 3) force_waves = eW;
+        if (got >= 4) force_gs = eG;
     }
     // states per lane and waves per workgroup: 16 lane groups of one DPP row with one state each,
     // or 8 wavefront-wide lane groups with two states each; four states per lane beyond N = 16
     int waves, NW;
     if (LG == 16) { waves = 4; NW = N <= 16 ? 1 : 4; }
     else if (N <= 16 && K == 16) { waves = 4; NW = 4; }     // widest maps: LDS bounds the workgroup size
+    else if (N <= 16 && force_waves == 16) { waves = 16; NW = 1; }
     else if (N <= 16) { waves = 8; NW = 2; }
     else { waves = 16; NW = 4; }
     const int slots = waves * 64 / LG;
@@ -95,6 +100,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
         if (((jobs + JPW - 1) / JPW) * waves >= 2048) break;
         --gs;
     }
+    if (force_gs >= 1 && force_gs <= gs_lds && force_gs <= d->Dc) gs = force_gs;
     pl.GS = gs;
     pl.CG = (d->Dc + gs - 1) / gs;
     pl.lds_bytes = (fixed + (size_t)gs * per) * sizeof(float);

@@ -19,7 +19,8 @@
 // FAST (W a multiple of K, rows 4-byte aligned): unguarded wide accesses; a lane past the last
 // column mirrors lane 0 with dy forced to 0, so nothing flows out of it into the reverse scans,
 // and it never stores.  Otherwise every element access is guarded and out-of-range cells read 0.
-// The inputs of the next row are requested before the current row is processed.
+// PF: the inputs of the next row are requested before the current row is processed (costs one
+// more row of raw registers); without it the kernel relies on several waves per SIMD.
 #pragma once
 
 #include "scan2d_common.hpp"
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 //   gaL  [GS][T*NW*K]  a[i+1,j]*g[i+1,j] of every channel, kept between bands
 //   dAL  [GS][T*NW]    per-lane partial of dA
 //   dDL  [GS][T]       per-lane partial of dDskip (first lane group of a map only)
-template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST>
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool PF>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdArgs p) {
     constexpr int THREADS = WAVES * 64;
     constexpr int SLOTS = THREADS / LG;
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                     for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, fB[buf][s]);
                 };
-                issue(0, r0);
+                if constexpr (PF) issue(0, r0);
                 float hcur[NW][K];
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
@@ -282,7 +283,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                 for (int r = 0; r < RB; ++r) {
                     const int i = r0 + r;
                     if (i < H) {
-                        if (r + 1 < RB && i + 1 < H) issue((r + 1) & 1, i + 1);
+                        if constexpr (PF) { if (r + 1 < RB && i + 1 < H) issue((r + 1) & 1, i + 1); }
+                        else issue(r & 1, i);
                         float dl[K], dxe[K];
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
@@ -343,8 +345,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             for (int r = RB - 1; r >= 0; --r) {
                 const int i = r0 + r;
                 if (i < H) {                                               // uniform over the workgroup
-                    if (i == ilast) issue_r(r & 1, i);
-                    if (r > 0) issue_r((r - 1) & 1, i - 1);
+                    if constexpr (PF) {
+                        if (i == ilast) issue_r(r & 1, i);
+                        if (r > 0) issue_r((r - 1) & 1, i - 1);
+                    } else {
+                        issue_r(r & 1, i);
+                    }
                     const size_t ro = (size_t)i * W;
                     float dl[K], xe[K], dxe[K], dyv[K], ddl[K], dxl[K];
 #pragma unroll

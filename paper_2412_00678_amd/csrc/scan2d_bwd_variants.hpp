@@ -1,5 +1,6 @@
-// The backward kernel variants that are compiled: (LG, K, NW, WAVES, RB), RB = rows per band.
-// RB * NW * K bounds the rebuilt states and the channel-sum accumulators held in VGPRs.
+// The backward kernel variants that are compiled: (LG, K, NW, WAVES, RB, PF), RB = rows per
+// band, PF = next-row prefetch.  RB * NW * K bounds the rebuilt states and the channel-sum
+// accumulators held in VGPRs.
 #pragma once
 
 #include "scan2d_bwd_kernels.hpp"
@@ -7,10 +8,10 @@
 namespace scan2d {
 
 #define SCAN2D_BWD_VARIANTS(X)                                             \
-    X(16, 4, 1, 4, 4) X(16, 8, 1, 4, 4) X(16, 12, 1, 4, 2) X(16, 16, 1, 4, 2) \
-    X(16, 4, 4, 4, 2) X(16, 8, 4, 4, 1)                                       \
-    X(64, 4, 2, 8, 4) X(64, 8, 2, 8, 2) X(64, 16, 4, 4, 1)                     \
-    X(64, 4, 4, 16, 2) X(64, 8, 4, 16, 1)
+    X(16, 4, 1, 4, 4, true) X(16, 8, 1, 4, 4, true) X(16, 12, 1, 4, 2, true) X(16, 16, 1, 4, 2, true) \
+    X(16, 4, 4, 4, 2, true) X(16, 8, 4, 4, 1, true)                                                   \
+    X(64, 4, 2, 8, 4, false) X(64, 8, 2, 8, 2, true) X(64, 16, 4, 4, 1, true)                           \
+    X(64, 4, 4, 16, 2, false) X(64, 8, 4, 16, 1, false) X(64, 4, 1, 16, 2, false)
 
 using BwdKernel = void (*)(const BwdArgs);
 struct BwdKernels { BwdKernel ckpt = nullptr; BwdKernel main = nullptr; int RB = 0; };
@@ -21,10 +22,10 @@ BwdKernels bwd_kernels_bf16(int LG, int K, int NW, int waves, bool fast);
 template <typename T>
 inline BwdKernels lookup_bwd_kernels(int LG, int K, int NW, int waves, bool fast) {
     BwdKernels r;
-#define SCAN2D_X(lg, k, nw, wv, rb)                                                                     \
+#define SCAN2D_X(lg, k, nw, wv, rb, pf)                                                                 \
     if (LG == lg && K == k && NW == nw && waves == wv) {                                                \
         r.ckpt = fast ? scan2d_bwd_ckpt_kernel<T, lg, k, nw, wv, rb, true> : scan2d_bwd_ckpt_kernel<T, lg, k, nw, wv, rb, false>; \
-        r.main = fast ? scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, true> : scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, false>; \
+        r.main = fast ? scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, true, pf> : scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, false, pf>; \
         r.RB = rb;                                                                                      \
     }
     SCAN2D_BWD_VARIANTS(SCAN2D_X)

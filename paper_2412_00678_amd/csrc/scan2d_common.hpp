@@ -182,7 +182,14 @@ __device__ __forceinline__ void store_row(T* __restrict__ rowp, int col0, int W,
 template <int LG>
 __device__ __forceinline__ void group_scan1(float& P0, float& H0, float& C0) {
     C0 = 0.0f;
-    if constexpr (LG == 16) {
+    if constexpr (LG == 32) {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_STEP(SCAN2D_SHR(8))
+                     SCAN2D_S1_LAST(SCAN2D_BC15)
+                     "v_mov_b32_dpp %2, %0" SCAN2D_CIN64
+                     : "+v"(H0), "+v"(P0), "+v"(C0));
+    } else if constexpr (LG == 16) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
                      SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_LAST(SCAN2D_SHR(8))
@@ -201,7 +208,14 @@ __device__ __forceinline__ void group_scan1(float& P0, float& H0, float& C0) {
 template <int LG>
 __device__ __forceinline__ void group_scan2(float& P0, float& P1, float& H0, float& H1, float& C0, float& C1) {
     C0 = 0.0f; C1 = 0.0f;
-    if constexpr (LG == 16) {
+    if constexpr (LG == 32) {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_STEP(SCAN2D_SHR(8))
+                     SCAN2D_S2_LAST(SCAN2D_BC15)
+                     "v_mov_b32_dpp %4, %0" SCAN2D_CIN64 "v_mov_b32_dpp %5, %1" SCAN2D_CIN64
+                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "+v"(C0), "+v"(C1));
+    } else if constexpr (LG == 16) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
                      SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_LAST(SCAN2D_SHR(8))
@@ -222,7 +236,16 @@ __device__ __forceinline__ void group_scan4(float& P0, float& P1, float& P2, flo
                                             float& H0, float& H1, float& H2, float& H3,
                                             float& C0, float& C1, float& C2, float& C3) {
     C0 = 0.0f; C1 = 0.0f; C2 = 0.0f; C3 = 0.0f;
-    if constexpr (LG == 16) {
+    if constexpr (LG == 32) {
+        asm volatile("s_nop 1\n\t"
+                     SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
+                     SCAN2D_S4_STEP(SCAN2D_SHR(4)) SCAN2D_S4_STEP(SCAN2D_SHR(8))
+                     SCAN2D_S4_LAST(SCAN2D_BC15)
+                     "v_mov_b32_dpp %8, %0" SCAN2D_CIN64 "v_mov_b32_dpp %9, %1" SCAN2D_CIN64
+                     "v_mov_b32_dpp %10, %2" SCAN2D_CIN64 "v_mov_b32_dpp %11, %3" SCAN2D_CIN64
+                     : "+v"(H0), "+v"(H1), "+v"(H2), "+v"(H3), "+v"(P0), "+v"(P1), "+v"(P2), "+v"(P3),
+                       "+v"(C0), "+v"(C1), "+v"(C2), "+v"(C3));
+    } else if constexpr (LG == 16) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
                      SCAN2D_S4_STEP(SCAN2D_SHR(4)) SCAN2D_S4_LAST(SCAN2D_SHR(8))
@@ -242,12 +265,18 @@ __device__ __forceinline__ void group_scan4(float& P0, float& P1, float& P2, flo
     }
 }
 
-// Scan S (1, 2 or 4) recurrences held in arrays.
+// Scan S (1, 2 or 4) recurrences held in arrays.  LG = 32 (half a wavefront): the first lane of
+// the upper half must not take the carry of the lower half.
 template <int LG, int S>
 __device__ __forceinline__ void group_scan(float* P, float* H, float* C) {
     if constexpr (S == 1) group_scan1<LG>(P[0], H[0], C[0]);
     else if constexpr (S == 2) group_scan2<LG>(P[0], P[1], H[0], H[1], C[0], C[1]);
     else group_scan4<LG>(P[0], P[1], P[2], P[3], H[0], H[1], H[2], H[3], C[0], C[1], C[2], C[3]);
+    if constexpr (LG == 32) {
+        const bool first = (threadIdx.x & 31u) == 0u;
+#pragma unroll
+        for (int t = 0; t < S; ++t) C[t] = first ? 0.0f : C[t];
+    }
 }
 
 // ------------------------------------------------------------------ group scan (leftwards)

@@ -55,6 +55,7 @@ struct FwdArgs {
     int NG;              // lane groups per map = ceil(N / NW)
     int MPW;             // maps per workgroup = (lane groups per workgroup) / NG, >= 1
     int panels;          // ceil(W / (LG * K))
+    int RPB;             // rows between two workgroup barriers (1, 2 or 4); sizes the dynamic LDS
 };
 
 // FAST: W is a multiple of K and every row starts 4-byte aligned, so a lane is either fully
@@ -72,7 +73,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
     constexpr int PANEL = LG * K;
     constexpr int SC = (NW < 4 ? NW : (K >= 12 ? 2 : 4));   // states scanned together
     static_assert(NW % SC == 0, "state chunking");
-    __shared__ float ypart[2][SLOTS][PANEL];
+    // partial sums over states: [2 buffers][RPB rows][SLOTS][PANEL]; the lane groups of a map
+    // meet at a barrier once every RPB rows
+    extern __shared__ float ypart[];
+    const int RPB = p.RPB;
 
     const int tid = threadIdx.x;
     const int slot = tid / LG;
@@ -127,12 +131,18 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
             for (int j = 0; j < K; ++j) h[s][j] = 0.0f;       // h[-1, j] = 0
 
         uint32_t rx[XW], rd[XW], rm[K / 4], rB[NW][XW], rC[NW][XW];
+        // FAST: uniform base + 32-bit byte offset per lane (the host bounds the span to 2^31 bytes),
+        // which the hardware adds for free (scalar base, vector offset addressing)
         auto ld = [&](const T* base, uint32_t lane_off, uint32_t* r) {
-            if constexpr (FAST) load_words<XW>(reinterpret_cast<const uint32_t*>(base + (lane_off + lcol)), r);
-            else load_row<T, K>(base + lane_off, col0, W, false, r);
+            if constexpr (FAST) {
+                const uint32_t boff = (lane_off + lcol) * (uint32_t)Elem<T>::kBytes;
+                load_words<XW>(reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(base) + boff), r);
+            } else {
+                load_row<T, K>(base + lane_off, col0, W, false, r);
+            }
         };
         auto ldm = [&](const uint8_t* base, uint32_t* r) {
-            if constexpr (FAST) load_words<K / 4>(reinterpret_cast<const uint32_t*>(base + (mlane + lcol)), r);
+            if constexpr (FAST) load_words<K / 4>(reinterpret_cast<const uint32_t*>(base + (uint32_t)(mlane + lcol)), r);
             else load_mask<K>(base + mlane, col0, W, false, r);
         };
         ld(xu, xlane, rx);
@@ -224,16 +234,24 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                     }
                 }
             } else {
-                float* mine = &ypart[step & 1][slot][l * K];
+                const int batch = step / RPB, rb = step - batch * RPB;     // row inside the current batch
+                float* buf = ypart + (size_t)(batch & 1) * RPB * SLOTS * PANEL;
+                float* mine = buf + ((size_t)rb * SLOTS + slot) * PANEL + l * K;
 #pragma unroll
                 for (int j = 0; j < K; ++j) mine[j] = yacc[j];
-                __syncthreads();
-                if (live) {
-                    const float* base = &ypart[step & 1][slot - sg][0];   // first group of this map
-                    for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
-                        const int gc = panel * PANEL + col;
-                        if (gc < W) store_elem(yrow + xlane + gc, sum_partials<PANEL>(base + col, NG));
+                if (rb == RPB - 1 || i == H - 1) {                         // uniform: batch complete
+                    __syncthreads();
+                    if (live) {
+                        for (int r = 0; r <= rb; ++r) {
+                            const float* base = buf + ((size_t)r * SLOTS + slot - sg) * PANEL;   // first group of this map
+                            T* yr = yrow - (size_t)(rb - r) * W;
+                            for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
+                                const int gc = panel * PANEL + col;
+                                if (gc < W) store_elem(yr + xlane + gc, sum_partials<PANEL>(base + col, NG));
+                            }
+                        }
                     }
+                    step += RPB - 1 - rb;                                  // a short last batch still ends its buffer
                 }
             }
         }

@@ -1,5 +1,5 @@
 // The (LG, K, NW, WAVES) kernel variants that are compiled, and the lookup used by the dispatcher.
-//   LG    : lanes per lane group (16 = one DPP row, 64 = a wavefront)
+//   LG    : lanes per lane group (16 = one DPP row, 32 = half a wavefront, 64 = a wavefront)
 //   K     : consecutive columns per lane
 //   NW    : states per lane
 //   WAVES : wavefronts per workgroup
@@ -20,7 +20,8 @@ namespace scan2d {
     X(64, 8, 1, 4) X(64, 8, 2, 4) X(64, 8, 4, 4) X(64, 8, 8, 4)                 \
     X(64, 16, 1, 4) X(64, 16, 2, 4) X(64, 16, 4, 4)                             \
     X(64, 4, 1, 8) X(64, 4, 2, 8) X(64, 8, 1, 8) X(64, 8, 2, 8) X(64, 16, 1, 8) \
-    X(64, 4, 1, 16) X(64, 8, 1, 16)
+    X(64, 4, 1, 16) X(64, 8, 1, 16)                                             \
+    X(32, 4, 1, 8) X(32, 4, 2, 4) X(32, 4, 4, 4) X(32, 8, 1, 8) X(32, 8, 2, 4) X(32, 8, 2, 8) X(32, 8, 4, 4)
 
 // Variants that also exist for N not divisible by NW (the last lane group idles some states).
 #define SCAN2D_FWD_RAGGED_VARIANTS(X) X(16, 4, 4, 4) X(16, 8, 4, 4) X(16, 12, 4, 4) X(16, 16, 4, 4)
