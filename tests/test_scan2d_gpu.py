@@ -307,3 +307,54 @@ def test_backward_without_skip_term(s2d):
     assert got[5] is None and ref[5] is None
     for g, r in zip(got[:5], ref[:5]):
         assert rel_err(g, r) <= 1e-4
+
+
+# ====================================================================== error paths on the device
+
+def test_workspace_too_small_and_unsupported_shapes_are_reported(s2d):
+    import ctypes
+    import torch
+    w = wl.Workload("err", 1, 2, 4, 6, 1500, wl.F32, backward=True)       # several panels: forward needs a carry buffer
+    d = s2d.to_device(wl.make_inputs(w, seed=1), wl.F32)
+    desc = s2d.make_desc(d["x"], d["A"])
+    need = s2d.workspace_bytes(desc, s2d.PASS_FWD)
+    assert need == 1 * 2 * 4 * 6 * 4
+    y = torch.full_like(d["x"], 7.0)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.scan2d_fwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], None, y=y, workspace=small)
+    assert e.value.code == -5
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())                                          # nothing was written
+    # backward of maps wider than 1024 columns is not available in this version
+    assert s2d.workspace_bytes(desc, s2d.PASS_BWD) == 0
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.scan2d_bwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], None, d["dy"])
+    assert e.value.code == -2
+    # a backward workspace that is too small
+    w2 = wl.Workload("err2", 2, 8, 16, 12, 40, wl.F32, backward=True)
+    d2 = s2d.to_device(wl.make_inputs(w2, seed=1), wl.F32)
+    assert s2d.workspace_bytes(s2d.make_desc(d2["x"], d2["A"]), s2d.PASS_BWD) > 0
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.scan2d_bwd(d2["x"], d2["delta"], d2["A"], d2["Bm"], d2["Cm"], d2["Dskip"], None, d2["dy"], workspace=small)
+    assert e.value.code == -5
+    # Dskip / dDskip must match: checked by the C ABI itself
+    rc = s2d.lib.scan2d_bwd(ctypes.byref(s2d.make_desc(d2["x"], d2["A"])), d2["x"].data_ptr(), d2["delta"].data_ptr(),
+                            d2["A"].data_ptr(), d2["Bm"].data_ptr(), d2["Cm"].data_ptr(), d2["Dskip"].data_ptr(), None,
+                            d2["dy"].data_ptr(), d2["x"].data_ptr(), d2["x"].data_ptr(), d2["A"].data_ptr(),
+                            d2["Bm"].data_ptr(), d2["Cm"].data_ptr(), None, None, 0, None)
+    assert rc == -1
+
+
+def test_runs_on_a_side_stream(s2d):
+    import torch
+    w = wl.Workload("stream", 1, 8, 16, 32, 64, wl.BF16, mask_frac=0.3)
+    inp = wl.make_inputs(w, seed=2)
+    d = s2d.to_device(inp, wl.BF16)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        y = s2d.scan2d_fwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
+    st.synchronize()
+    ref = oracle_fwd(inp, wl.BF16)
+    assert rel_err(wl.to_float(s2d.to_host(y), wl.BF16), wl.to_float(ref, wl.BF16)) <= 2e-2
