@@ -29,11 +29,14 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 # 157.3 TFLOP/s counts two FMAs per lane per clock through the packed forms.
 ALU_PEAK_TFLOPS = 78.6
 FLOPS_PER_UNIT_FWD = 9.0         # exp + 2 mul + 3 FMA per (position, channel, state)
-FLOPS_PER_UNIT_BWD = 30.0        # two rebuilt forward scans + two reverse scans + local gradients
+FLOPS_PER_UNIT_BWD = 32.0        # rebuilt states (7) + two reverse scans and local gradients (25)
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
 # None where no counter run has been recorded for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # forward: FETCH_SIZE 49,475 KiB x 2.00 (copy-kernel scale) + WRITE_SIZE 32,768 KiB x 1.00 per launch
+    "wsi_256x256_bf16_mask50": int((49475 * 2.0 + 32768) * 1024),
+}
 
 
 def device_sets(s2d, inp, dtype, nsets, backward):
@@ -124,6 +127,9 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="index into the five configurations (default: the 256x256 WSI grid)")
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under 'others')")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="also time the grids the paper times (14x14, 56x56, 200x200; N = 16): 128-channel maps and "
+                         "batches of single-channel maps, reported under 'paper_shapes' as feature maps per second")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: the scan shards over channels with no exchange in forward; "
@@ -168,6 +174,15 @@ def main():
             r, _ = bench_workload(s2d, ow, max(20, args.steps // 3), max(5, args.warmup // 3), with_bwd=ow.backward)
             others.append(r)
         line["others"] = others
+    if args.paper_shapes:
+        rows = []
+        for side in (14, 56, 200):
+            for label, Bt, Dc in (("128-channel map, batch 8", 8, 128), ("single-channel maps, batch 4096", 4096, 1)):
+                pw = wl.Workload(f"paper_{side}x{side}_{Dc}ch", Bt, Dc, 16, side, side, wl.F32)
+                r, _ = bench_workload(s2d, pw, max(20, args.steps // 3), max(5, args.warmup // 3), with_bwd=False)
+                rows.append({"grid": side, "what": label, "fwd_ms": r["fwd_ms"], "maps_per_s": Bt / (r["fwd_ms"] * 1e-3),
+                             "gunits_s": r["fwd_gunits_s"]})
+        line["paper_shapes"] = rows
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(line))

@@ -272,6 +272,12 @@ BWD_SHAPES = [
     (1, 3, 16, 10, 130, wl.BF16, 0.3),
     (4, 1, 16, 10, 24, wl.F32, 0.3),       # one channel per batch item
     (2, 21, 16, 10, 40, wl.F32, 0.3),      # ragged last channel group
+    (1, 5, 16, 10, 68, wl.F32, 0.3),       # one lane past a 64-column boundary
+    (1, 5, 16, 9, 129, wl.F32, 0.3),       # ragged width, odd
+    (1, 6, 16, 9, 256, wl.F32, 0.3),       # widest map of the 16-lane groups
+    (1, 6, 16, 9, 255, wl.BF16, 0.3),
+    (1, 3, 24, 7, 132, wl.F32, 0.3),       # four states per lane, 12 columns per lane
+    (1, 3, 40, 6, 250, wl.BF16, 0.2),
 ]
 
 
