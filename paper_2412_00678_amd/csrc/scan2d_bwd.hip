@@ -60,7 +60,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     int LG, K;
     if (W <= 64) { LG = 16; K = 4; }
     else if (W <= 128) { LG = 16; K = 8; }
-    else if (W <= 192) { LG = 16; K = 12; }
+    else if (W <= 192 && N <= 16) { LG = 16; K = 12; }         // 12 columns x 4 states per lane would not fit the registers
     else if (W <= 256) { LG = 64; K = 4; }
     else if (W <= 512) { LG = 64; K = 8; }
     else if (W <= 1024) { LG = 64; K = 16; }
@@ -147,13 +147,16 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     const int slots = pl.waves * 64 / pl.LG;
     const long long maps = (long long)d->Bt * d->Dc;
     const int MPW = slots / pl.NG;
-    const long long wg1 = (maps + MPW - 1) / MPW;
+    BwdArgs ac = a;                                            // the checkpoint sweep may hold more states per lane
+    ac.NG = (d->N + pl.k.ckpt_NW - 1) / pl.k.ckpt_NW;
+    const int MPW1 = slots / ac.NG;
+    const long long wg1 = (maps + MPW1 - 1) / MPW1;
     const long long jobs = (long long)d->Bt * pl.CG;
     const long long wg2 = (jobs + MPW - 1) / MPW;
     if (wg1 > 2147483647LL || wg2 > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
     (void)hipGetLastError();
     if (pl.nb > 1)
-        hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.waves * 64), 0, stream, a);
+        hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.waves * 64), 0, stream, ac);
     if (pl.lds_bytes > 65536)
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(pl.k.main),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes);

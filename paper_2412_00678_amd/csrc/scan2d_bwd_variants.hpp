@@ -14,7 +14,7 @@ namespace scan2d {
     X(64, 4, 4, 16, 2, false) X(64, 8, 4, 16, 1, false) X(64, 4, 1, 16, 2, false)
 
 using BwdKernel = void (*)(const BwdArgs);
-struct BwdKernels { BwdKernel ckpt = nullptr; BwdKernel main = nullptr; int RB = 0; };
+struct BwdKernels { BwdKernel ckpt = nullptr; BwdKernel main = nullptr; int RB = 0; int ckpt_NW = 0; };
 
 BwdKernels bwd_kernels_f32(int LG, int K, int NW, int waves, bool fast);
 BwdKernels bwd_kernels_bf16(int LG, int K, int NW, int waves, bool fast);
@@ -24,7 +24,9 @@ inline BwdKernels lookup_bwd_kernels(int LG, int K, int NW, int waves, bool fast
     BwdKernels r;
 #define SCAN2D_X(lg, k, nw, wv, rb, pf)                                                                 \
     if (LG == lg && K == k && NW == nw && waves == wv) {                                                \
-        r.ckpt = fast ? scan2d_bwd_ckpt_kernel<T, lg, k, nw, wv, rb, true> : scan2d_bwd_ckpt_kernel<T, lg, k, nw, wv, rb, false>; \
+        constexpr int cnw = (lg == 16 && nw == 1) ? 2 : nw;   /* the checkpoint sweep has registers to spare */ \
+        r.ckpt = fast ? scan2d_bwd_ckpt_kernel<T, lg, k, cnw, wv, rb, true> : scan2d_bwd_ckpt_kernel<T, lg, k, cnw, wv, rb, false>; \
+        r.ckpt_NW = cnw;                                                                                \
         r.main = fast ? scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, true, pf> : scan2d_bwd_main_kernel<T, lg, k, nw, wv, rb, false, pf>; \
         r.RB = rb;                                                                                      \
     }
