@@ -103,6 +103,21 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb
     return true;
 }
 
+// Narrow maps: one wavefront per map, its four DPP rows share the states (scan2d_fwd_small.hpp).
+bool fill_small(const scan2d_desc* d, int KS, FwdChoice* out) {
+    if (d->W > 16 * KS) return false;
+    int NW = 1;
+    while (4 * NW < d->N) NW *= 2;
+    FwdChoice c;
+    c.LG = 16; c.K = KS; c.NW = NW; c.waves = 4;
+    c.exact = true; c.fast = false; c.multi = false;
+    c.NG = 4; c.MPW = 4; c.panels = 1; c.RPB = 1; c.lds_bytes = 0;
+    c.kernel = d->dtype == SCAN2D_BF16 ? fwd_small_kernel_bf16(KS, NW) : fwd_small_kernel_f32(KS, NW);
+    if (c.kernel == nullptr) return false;
+    *out = c;
+    return true;
+}
+
 // Estimated run time (arbitrary units) of a variant, used only to rank the variants.  Calibrated
 // against measurements on the five benchmark shapes: instructions per workgroup row (core
 // arithmetic, lane-group scans, per-position work, fixed loop overhead, LDS reduction) times
@@ -137,10 +152,15 @@ int choose_fwd(const scan2d_desc* d, FwdChoice* out) {
     if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES[,RPB]"
         int LG = 0, K = 0, NW = 0, waves = 4, rpb = 0;
         const int got = std::sscanf(env, "%d,%d,%d,%d,%d", &LG, &K, &NW, &waves, &rpb);
+        if (got >= 2 && LG == 16 && (K == 1 || K == 2) && fill_small(d, K, out)) return SCAN2D_OK;
         if (got >= 3 && (LG == 16 || LG == 32 || LG == 64) && NW >= 1 && (waves == 4 || waves == 8 || waves == 16) &&
             fill_choice(d, LG, K, NW, waves, rpb, out))
             return SCAN2D_OK;
     }
+    // narrow maps: one column per lane up to 16 columns; two per lane up to 32 where the width rules out
+    // the unguarded wide loads of the 4-column variants (measured: twice as fast as their guarded form)
+    if (d->W <= 16 && fill_small(d, 1, out)) return SCAN2D_OK;
+    if (d->W <= 32 && d->W % 4 != 0 && fill_small(d, 2, out)) return SCAN2D_OK;
     bool found = false;
     double best = 0.0;
     for (const V4& v : kFwdVariants) {

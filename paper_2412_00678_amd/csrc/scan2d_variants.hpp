@@ -8,6 +8,7 @@
 #pragma once
 
 #include "scan2d_fwd.hpp"
+#include "scan2d_fwd_small.hpp"
 
 namespace scan2d {
 
@@ -43,6 +44,20 @@ using FwdKernel = void (*)(const FwdArgs);
 // Returns nullptr when the variant is not compiled.
 FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
 FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
+
+// Narrow maps (W <= 32): KS columns per lane, NW = states per lane group of the wave's four.
+FwdKernel fwd_small_kernel_f32(int KS, int NW);
+FwdKernel fwd_small_kernel_bf16(int KS, int NW);
+
+template <typename T>
+inline FwdKernel lookup_fwd_small_kernel(int KS, int NW) {
+#define SCAN2D_X(ks, nw, pd) \
+    if (KS == ks && NW == nw) return scan2d_fwd_small_kernel<T, ks, nw, pd>;
+    SCAN2D_X(1, 1, 4) SCAN2D_X(1, 2, 4) SCAN2D_X(1, 4, 4) SCAN2D_X(1, 8, 2) SCAN2D_X(1, 16, 2)
+    SCAN2D_X(2, 1, 4) SCAN2D_X(2, 2, 4) SCAN2D_X(2, 4, 4) SCAN2D_X(2, 8, 2) SCAN2D_X(2, 16, 1)
+#undef SCAN2D_X
+    return nullptr;
+}
 
 template <typename T>
 inline FwdKernel lookup_fwd_kernel(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {

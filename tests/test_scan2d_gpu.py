@@ -87,6 +87,18 @@ SHAPES = [
     (5, 1, 16, 20, 24, wl.BF16, 0.3),      # one channel: every map is another batch item
     (1, 40, 16, 16, 128, wl.F32, 0.0),
     (1, 9, 16, 33, 192, wl.F32, 0.3),
+    # narrow maps: one wavefront per map
+    (2, 9, 16, 14, 14, wl.F32, 0.2),       # 14 of 16 lanes
+    (1, 7, 16, 7, 7, wl.BF16, 0.2),
+    (2, 5, 16, 28, 28, wl.BF16, 0.3),      # two columns per lane
+    (1, 6, 16, 11, 31, wl.F32, 0.3),       # odd width: the last lane holds one column
+    (1, 3, 16, 40, 17, wl.BF16, 0.0),      # odd rows of bf16 start on a 2-byte boundary
+    (1, 5, 4, 9, 16, wl.F32, 0.3),         # one state per lane group
+    (1, 5, 3, 9, 13, wl.F32, 0.3),         # fewer states than lane groups
+    (1, 3, 5, 9, 20, wl.BF16, 0.3),        # N not a multiple of the states per lane
+    (1, 3, 30, 6, 15, wl.F32, 0.2),        # eight states per lane, last group ragged
+    (1, 2, 64, 5, 32, wl.F32, 0.2),        # sixteen states per lane, two columns
+    (3, 1, 16, 14, 14, wl.F32, 0.0),       # a partly filled last workgroup
 ]
 
 
@@ -125,6 +137,8 @@ VARIANT_CASES = [
     # guarded (ragged W) and multi-panel forms of the K = 4 variants
     ("16,4,4", (1, 6, 16, 9, 61)), ("64,4,4", (1, 6, 16, 9, 203)), ("64,4,2", (1, 3, 4, 7, 777)),
     ("16,4,4", (1, 3, 16, 7, 150)), ("16,4,4", (1, 3, 10, 7, 150)), ("16,8,4", (1, 3, 10, 7, 128)),
+    # narrow-map kernel with two columns per lane forced on a map that one column per lane would cover
+    ("16,2", (1, 5, 16, 9, 14)), ("16,1", (2, 3, 8, 9, 16)),
 ]
 
 
