@@ -34,6 +34,11 @@
  * Errors: every entry point returns SCAN2D_OK (0) or a negative code; on error nothing has
  * been enqueued and no output has been touched.  No exceptions, no abort.
  * Thread safety: entry points may be called concurrently from several host threads.
+ *
+ * Limits of this version: 1 <= N <= 64; N*H*W < 2^27 (the kernels address one map's states
+ * with 32-bit lane offsets); any H, W >= 1 in the forward (maps wider than one lane-group
+ * panel need a workspace, see scan2d_workspace_bytes); the backward accepts W <= 1024, and
+ * W <= 512 when N > 16.  Shapes outside these limits return SCAN2D_ERR_BAD_SHAPE.
  */
 #ifndef SCAN2D_H_
 #define SCAN2D_H_
@@ -48,7 +53,8 @@ extern "C" {
 enum {
     SCAN2D_OK                   =  0,
     SCAN2D_ERR_NULL_POINTER     = -1,  /* a required pointer is NULL */
-    SCAN2D_ERR_BAD_SHAPE        = -2,  /* a dimension < 1, N > 64, or element count overflow */
+    SCAN2D_ERR_BAD_SHAPE        = -2,  /* a dimension < 1, N > 64, N*H*W >= 2^27, element count overflow,
+                                          or (backward only) W > 1024, or W > 512 with N > 16 */
     SCAN2D_ERR_BAD_DTYPE        = -3,
     SCAN2D_ERR_BAD_FLAGS        = -4,  /* flags must be 0 */
     SCAN2D_ERR_WORKSPACE_SMALL  = -5,  /* workspace_bytes < scan2d_workspace_bytes() */
