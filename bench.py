@@ -181,7 +181,8 @@ def main():
                 pw = wl.Workload(f"paper_{side}x{side}_{Dc}ch", Bt, Dc, 16, side, side, wl.F32)
                 r, _ = bench_workload(s2d, pw, max(20, args.steps // 3), max(5, args.warmup // 3), with_bwd=False)
                 rows.append({"grid": side, "what": label, "fwd_ms": r["fwd_ms"], "maps_per_s": Bt / (r["fwd_ms"] * 1e-3),
-                             "gunits_s": r["fwd_gunits_s"]})
+                             "gunits_s": r["fwd_gunits_s"], "algorithmic_GBs": r["fwd_algorithmic_GBs"],
+                             "hbm_frac": r["fwd_algorithmic_GBs"] / HBM_PEAK_GBS})
         line["paper_shapes"] = rows
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w, inp)
