@@ -118,11 +118,24 @@ bool fill_small(const scan2d_desc* d, int KS, FwdChoice* out) {
     return true;
 }
 
+// VGPRs of the compiled forward variants by (K, NW) and storage type, as the compiler reports
+// them for this source (300 = more than 256, i.e. one wave per SIMD).  Only used to rank variants.
+int fwd_regs(bool bf16, int K, int NW) {
+    struct R { int K, NW, b, f; };
+    static const R t[] = {{4, 1, 82, 116},  {4, 2, 112, 120}, {4, 4, 153, 153}, {4, 8, 166, 213}, {4, 16, 238, 300},
+                          {8, 1, 127, 124}, {8, 2, 160, 157}, {8, 4, 233, 255}, {8, 8, 300, 300},
+                          {12, 1, 177, 181}, {12, 2, 227, 230}, {12, 4, 255, 300},
+                          {16, 1, 196, 168}, {16, 2, 238, 300}, {16, 4, 300, 300}};
+    for (const R& r : t)
+        if (r.K == K && r.NW == NW) return bf16 ? r.b : r.f;
+    return 300;
+}
+
 // Estimated run time (arbitrary units) of a variant, used only to rank the variants.  Calibrated
-// against measurements on the five benchmark shapes: instructions per workgroup row (core
+// against measurements on the benchmark shapes: instructions per workgroup row (core
 // arithmetic, lane-group scans, per-position work, fixed loop overhead, LDS reduction) times
 // rows, divided by the issue efficiency that the number of resident waves per SIMD allows
-// (about 0.40 / 0.55 / 0.70 / 0.85 / 0.95 for 1 / 2 / 3 / 4 / 5+ waves).
+// (about 0.5 / 0.7 / 0.9 for 1 / 2 / 3 and more waves).
 double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     const bool bf16 = d->dtype == SCAN2D_BF16;
     const double maps = (double)d->Bt * d->Dc;
@@ -135,7 +148,7 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     double row = c.K * c.NW * c_core + c.NW * c_scan + c_pos * c.K + 35.0 + c_red;
     if (!c.fast) row *= 1.6;
     if (c.multi) row += 8.0 * c.NW;
-    const double regs = 40.0 + (bf16 ? 6.5 : 8.5) * c.K * c.NW;
+    const double regs = fwd_regs(bf16, c.K, c.NW);
     const double occ = std::min(8.0, std::max(std::floor(512.0 / regs), c.waves / 4.0));
     const double res_wg = 256.0 * std::max(1.0, std::floor(occ * 4.0 / c.waves));   // workgroups resident on the chip
     const double rounds = std::ceil(wgs / res_wg);
@@ -143,7 +156,7 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     if (rounds > 1.0) wps = std::max(wps, 1.0);                                      // several rounds: SIMDs are never empty
     const double steps = (double)d->H * c.panels * row;                              // instructions of one wave
     if (wps < 1.0) return steps * 8.0;                                               // a lone wave: its own critical path
-    const double eff = std::min(0.95, 0.25 + 0.15 * wps);
+    const double eff = std::min(0.95, 0.30 + 0.20 * wps);
     const double tail = wgs > res_wg ? rounds / (wgs / res_wg) : 1.0;
     return wgs * c.waves * steps * 4.0 / (1024.0 * eff) * tail;
 }

@@ -60,6 +60,30 @@ __device__ __forceinline__ void store_words(uint32_t* __restrict__ p, const uint
     for (; w < WORDS; ++w) p[w] = r[w];
 }
 
+// Buffer addressing: a wave-uniform base in a resource descriptor (scalar registers), a 32-bit
+// byte offset per lane and a 32-bit uniform byte offset (the row), which the memory instruction
+// adds itself - no 64-bit vector address arithmetic per load.  Spans are below 2^31 bytes.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+template <int WORDS>
+__device__ __forceinline__ void buffer_load_words(rsrc_t rs, uint32_t lane_bytes, uint32_t uniform_bytes, uint32_t* r) {
+    int w = 0;
+#pragma unroll
+    for (; w + 4 <= WORDS; w += 4) {
+        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes + 4 * w, uniform_bytes, 0);
+        r[w] = v.x; r[w + 1] = v.y; r[w + 2] = v.z; r[w + 3] = v.w;
+    }
+#pragma unroll
+    for (; w + 2 <= WORDS; w += 2) {
+        const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(rs, lane_bytes + 4 * w, uniform_bytes, 0);
+        r[w] = v.x; r[w + 1] = v.y;
+    }
+#pragma unroll
+    for (; w < WORDS; ++w) r[w] = __builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes + 4 * w, uniform_bytes, 0);
+}
+
 __device__ __forceinline__ uint32_t elem_bits(const float* p)  { return __float_as_uint(*p); }
 __device__ __forceinline__ uint32_t elem_bits(const bf16_t* p) { return p->bits; }
 
@@ -141,6 +165,14 @@ __device__ __forceinline__ void store_row(T* __restrict__ rowp, int col0, int W,
         for (int j = 0; j < K; ++j)
             if (col0 + j < W) store_elem(rowp + col0 + j, v[j]);
     }
+}
+
+// h = a * h + add with h updated in place.  The compiler would pick the two-operand
+// v_fmac_f32, whose destination is the addend, and then move the result back into the register
+// that carries h into the next row: one extra instruction per state and column.  The
+// three-operand form writes h directly.
+__device__ __forceinline__ void fma_inplace(float& h, float a, float add) {
+    asm("v_fma_f32 %0, %1, %0, %2" : "+v"(h) : "v"(a), "v"(add));
 }
 
 // ----------------------------------------------------------------------------- DPP

@@ -15,6 +15,8 @@
 // of a panel travel to the next one through a small carry buffer (N floats per row).
 #pragma once
 
+#include <type_traits>
+
 #include "scan2d_common.hpp"
 
 namespace scan2d {
@@ -66,6 +68,15 @@ struct FwdArgs {
 // WAVES: wavefronts per workgroup (4, 8 or 16).  One wave per SIMD reaches only about half of
 // the vector issue rate on this chip, so maps that are few but large spread their states over
 // more waves (smaller NW) rather than leaving SIMDs with a single wave.
+// VGPRs a kernel may spend on rows of loads in flight, per group of tensors.
+#ifndef SCAN2D_PREFETCH_BUDGET_X
+#define SCAN2D_PREFETCH_BUDGET_X 56
+#endif
+#ifndef SCAN2D_PREFETCH_BUDGET_S
+#define SCAN2D_PREFETCH_BUDGET_S 48
+#endif
+constexpr int kPrefetchBudgetX = SCAN2D_PREFETCH_BUDGET_X, kPrefetchBudgetS = SCAN2D_PREFETCH_BUDGET_S;
+
 template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p) {
     constexpr int SLOTS = WAVES * 64 / LG;
@@ -106,6 +117,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
     const uint32_t xlane = (uint32_t)(map_local * HW);
     const uint32_t slane = (uint32_t)(((size_t)(b - b0) * N + n0) * HW);
     const uint32_t mlane = (uint32_t)((size_t)(b - b0) * HW);
+    const rsrc_t rsx = make_rsrc(xu), rsd = make_rsrc(du), rsB = make_rsrc(Bu), rsC = make_rsrc(Cu), rsm = make_rsrc(mu);
 
     float Ap[NW];
 #pragma unroll
@@ -130,52 +142,70 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
 #pragma unroll
             for (int j = 0; j < K; ++j) h[s][j] = 0.0f;       // h[-1, j] = 0
 
-        uint32_t rx[XW], rd[XW], rm[K / 4], rB[NW][XW], rC[NW][XW];
-        // FAST: uniform base + 32-bit byte offset per lane (the host bounds the span to 2^31 bytes),
-        // which the hardware adds for free (scalar base, vector offset addressing)
-        auto ld = [&](const T* base, uint32_t lane_off, uint32_t* r) {
-            if constexpr (FAST) {
-                const uint32_t boff = (lane_off + lcol) * (uint32_t)Elem<T>::kBytes;
-                load_words<XW>(reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(base) + boff), r);
-            } else {
-                load_row<T, K>(base + lane_off, col0, W, false, r);
-            }
+        // Raw registers of the rows in flight.  The row loop below is written for TRIP rows per
+        // trip; PDX (x, delta, mask: one stream per channel, straight from HBM) and PDS (Bm, Cm: shared
+        // by the channels, mostly L2 hits) say how many rows ahead each group of loads runs.  Every
+        // row of depth costs another set of raw registers, so the depth follows the size of a set.
+        constexpr int XSET = 2 * XW + K / 4, SSET = 2 * NW * XW;
+        constexpr int PDX = 4 * XSET <= kPrefetchBudgetX ? 4 : (2 * XSET <= kPrefetchBudgetX ? 2 : 1);
+        constexpr int PDS = 4 * SSET <= kPrefetchBudgetS ? 4 : (2 * SSET <= kPrefetchBudgetS ? 2 : 1);
+        constexpr int TRIP = PDX > PDS ? PDX : PDS;
+        uint32_t rx[PDX][XW], rd[PDX][XW], rm[PDX][K / 4], rB[PDS][NW][XW], rC[PDS][NW][XW];
+        // FAST: buffer addressing - uniform base and uniform row offset in scalar registers, one
+        // loop-invariant 32-bit byte offset per lane (the host bounds the span to 2^31 bytes)
+        constexpr uint32_t EB = (uint32_t)Elem<T>::kBytes;
+        auto ld = [&](const T* base, rsrc_t rs, uint32_t uni_off, uint32_t lane_off, uint32_t* r) {
+            if constexpr (FAST) buffer_load_words<XW>(rs, (lane_off + lcol) * EB, uni_off * EB, r);
+            else load_row<T, K>(base + uni_off + lane_off, col0, W, false, r);
         };
-        auto ldm = [&](const uint8_t* base, uint32_t* r) {
-            if constexpr (FAST) load_words<K / 4>(reinterpret_cast<const uint32_t*>(base + (uint32_t)(mlane + lcol)), r);
-            else load_mask<K>(base + mlane, col0, W, false, r);
+        auto ldm = [&](uint32_t uni_off, uint32_t* r) {
+            if constexpr (FAST) buffer_load_words<K / 4>(rsm, mlane + lcol, uni_off, r);
+            else load_mask<K>(mu + uni_off + mlane, col0, W, false, r);
         };
-        ld(xu, xlane, rx);
-        ld(du, xlane, rd);
-#pragma unroll
-        for (int w = 0; w < K / 4; ++w) rm[w] = 0u;
-        if (mu) ldm(mu, rm);
         // State s of this lane group: uniform offset s*HW when every group is full; otherwise a
         // per-lane offset, with the idle states of a ragged last group re-reading state n0.
-        auto lds = [&](const T* base, int s, size_t row_off, uint32_t* r) {
-            if constexpr (EXACT) ld(base + (size_t)s * HW + row_off, slane, r);
-            else ld(base + row_off, slane + (uint32_t)((s < nvalid ? s : 0) * HW), r);
+        auto lds = [&](const T* base, rsrc_t rs, int s, uint32_t row_off, uint32_t* r) {
+            if constexpr (EXACT) ld(base, rs, (uint32_t)s * (uint32_t)HW + row_off, slane, r);
+            else ld(base, rs, row_off, slane + (uint32_t)((s < nvalid ? s : 0) * HW), r);
         };
 #pragma unroll
-        for (int s = 0; s < NW; ++s) {
-            lds(Bu, s, 0, rB[s]);
-            lds(Cu, s, 0, rC[s]);
+        for (int d = 0; d < PDX; ++d) {
+            const uint32_t ro = (uint32_t)min(d, H - 1) * (uint32_t)W;
+            ld(xu, rsx, ro, xlane, rx[d]);
+            ld(du, rsd, ro, xlane, rd[d]);
+#pragma unroll
+            for (int w = 0; w < K / 4; ++w) rm[d][w] = 0u;
+            if (mu) ldm(ro, rm[d]);
+        }
+#pragma unroll
+        for (int d = 0; d < PDS; ++d) {
+            const uint32_t ro = (uint32_t)min(d, H - 1) * (uint32_t)W;
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+                lds(Bu, rsB, s, ro, rB[d][s]);
+                lds(Cu, rsC, s, ro, rC[d][s]);
+            }
         }
 
-        for (int i = 0; i < H; ++i, ++step) {
-            const size_t nxt = (size_t)(i + 1 < H ? i + 1 : i) * W;   // the last row re-reads itself
+        // One row; PAR = position of the row inside the trip (selects the raw register sets).
+        auto do_row = [&](const int i, auto par) __attribute__((always_inline)) {
+            constexpr int PAR = decltype(par)::value;
+            constexpr int XS = PAR % PDX, SS = PAR % PDS;
+            // a row past the end re-reads the last row
+            const uint32_t nxt_x = (uint32_t)min(i + PDX, H - 1) * (uint32_t)W;
+            const uint32_t nxt_s = (uint32_t)min(i + PDS, H - 1) * (uint32_t)W;
             float dl[K], dx[K], yacc[K];
 #pragma unroll
             for (int j = 0; j < K; ++j) {
-                dl[j] = get_elem<T, K>(rd, j);
-                const float xv = get_elem<T, K>(rx, j);
-                const float xe = mask_bit<K>(rm, j) ? 0.0f : xv;      // select: nothing under the mask leaks
+                dl[j] = get_elem<T, K>(rd[XS], j);
+                const float xv = get_elem<T, K>(rx[XS], j);
+                const float xe = mask_bit<K>(rm[XS], j) ? 0.0f : xv;      // select: nothing under the mask leaks
                 dx[j] = dl[j] * xe;
                 yacc[j] = dsk * xe;
             }
-            ld(xu + nxt, xlane, rx);
-            ld(du + nxt, xlane, rd);
-            if (mu) ldm(mu + nxt, rm);
+            ld(xu, rsx, nxt_x, xlane, rx[XS]);
+            ld(du, rsd, nxt_x, xlane, rd[XS]);
+            if (mu) ldm(nxt_x, rm[XS]);
 
 #pragma unroll
             for (int s0 = 0; s0 < NW; s0 += SC) {
@@ -187,7 +217,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                         const int s = s0 + t;
 #pragma unroll
                         for (int j = 0; j < K; ++j) a[t][j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
-                        hl[t][0] = dx[0] * get_elem<T, K>(rB[s], 0);
+                        hl[t][0] = dx[0] * get_elem<T, K>(rB[SS][s], 0);
                         pl[t][0] = a[t][0];
                         if (MULTI && panel > 0 && l == 0) {   // state entering from the panel to the left
                             const float* cw = p.carry + ((size_t)map * N + n0 + ((EXACT || s < nvalid) ? s : 0)) * H + i;
@@ -195,10 +225,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                         }
 #pragma unroll
                         for (int j = 1; j < K; ++j) {
-                            hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dx[j] * get_elem<T, K>(rB[s], j));
+                            hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dx[j] * get_elem<T, K>(rB[SS][s], j));
                             pl[t][j] = pl[t][j - 1] * a[t][j];
                         }
-                        lds(Bu, s, nxt, rB[s]);
+                        lds(Bu, rsB, s, nxt_s, rB[SS][s]);
                         P[t] = pl[t][K - 1];
                         Hh[t] = hl[t][K - 1];
                     }
@@ -215,11 +245,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                         for (int j = 0; j < K; ++j) {
                             // Eq. 5; at the lane's last column the scan result is the state itself
                             const float hh = (j == K - 1) ? Hh[t] : fmaf(pl[t][j], cin[t], hl[t][j]);
-                            h[s][j] = fmaf(a[t][j], h[s][j], hh);                       // Eq. 6
-                            const float cv = EXACT ? get_elem<T, K>(rC[s], j) : cmul * get_elem<T, K>(rC[s], j);
+                            fma_inplace(h[s][j], a[t][j], hh);                          // Eq. 6
+                            const float cv = EXACT ? get_elem<T, K>(rC[SS][s], j) : cmul * get_elem<T, K>(rC[SS][s], j);
                             yacc[j] = fmaf(cv, h[s][j], yacc[j]);
                         }
-                        lds(Cu, s, nxt, rC[s]);
+                        lds(Cu, rsC, s, nxt_s, rC[SS][s]);
                     }
                 }
             }
@@ -253,6 +283,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                     }
                     step += RPB - 1 - rb;                                  // a short last batch still ends its buffer
                 }
+            }
+            ++step;
+        };
+        for (int i = 0; i < H; i += TRIP) {
+            do_row(i, std::integral_constant<int, 0>{});
+            if constexpr (TRIP >= 2) { if (i + 1 < H) do_row(i + 1, std::integral_constant<int, 1>{}); }
+            if constexpr (TRIP >= 4) {
+                if (i + 2 < H) do_row(i + 2, std::integral_constant<int, 2>{});
+                if (i + 3 < H) do_row(i + 3, std::integral_constant<int, 3>{});
             }
         }
     }
