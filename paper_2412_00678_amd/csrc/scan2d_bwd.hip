@@ -89,16 +89,30 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
     pl.NG = (N + NW - 1) / NW;
     pl.nb = (d->H + pl.RB - 1) / pl.RB;
-    // channels per workgroup: bounded by LDS (150 KB) and by keeping at least 2048 waves in flight
+    // channels a workgroup handles one after the other: bounded by the 160 KB of LDS; among the
+    // feasible counts take the one with the shortest critical path (rounds of resident workgroups
+    // - the runtime's occupancy figure for the kernel's registers and this much LDS, one per CU
+    // if it cannot be asked - times channels per workgroup), the larger count on a tie (fewer
+    // partial sums to write and add up)
     const size_t T = (size_t)waves * 64;
     const size_t fixed = 4 * T * K, per = T * ((size_t)NW * K + NW + 1);
-    int gs_lds = (int)std::max<size_t>(1, (38400 - std::min<size_t>(fixed, 38400)) / per);
+    const int gs_lds = (int)std::max<size_t>(1, (40960 - std::min<size_t>(fixed, 40960)) / per);
     const int JPW = slots / pl.NG;
-    int gs = std::min({gs_lds, 8, d->Dc});
-    while (gs > 1) {
-        const long long jobs = (long long)d->Bt * ((d->Dc + gs - 1) / gs);
-        if (((jobs + JPW - 1) / JPW) * waves >= 2048) break;
-        --gs;
+    const int gs_max = std::min({gs_lds, 8, d->Dc});
+    int gs = 1;
+    long long best_path = -1;
+    for (int g = 1; g <= gs_max; ++g) {
+        const long long jobs = (long long)d->Bt * ((d->Dc + g - 1) / g);
+        const long long wgs = (jobs + JPW - 1) / JPW;
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(pl.k.main), (int)T,
+                                                         (fixed + (size_t)g * per) * sizeof(float)) != hipSuccess || per_cu < 1) {
+            (void)hipGetLastError();
+            per_cu = 1;
+        }
+        const long long resident = 256LL * per_cu;
+        const long long path = ((wgs + resident - 1) / resident) * g;
+        if (best_path < 0 || path <= best_path) { best_path = path; gs = g; }
     }
     if (force_gs >= 1 && force_gs <= gs_lds && force_gs <= d->Dc) gs = force_gs;
     pl.GS = gs;

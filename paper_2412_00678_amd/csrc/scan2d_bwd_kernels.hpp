@@ -144,7 +144,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
-                h[s][j] = fmaf(a[j], h[s][j], hh);
+                fma_inplace(h[s][j], a[j], hh);
             }
         }
         if ((i + 1) % RB == 0) {                              // h[i] enters band (i+1)/RB
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
                                 hhl[r][s][j] = left;
                                 hprev[r][s][j] = hcur[s][j];
-                                hcur[s][j] = fmaf(a[j], hcur[s][j], hh);
+                                fma_inplace(hcur[s][j], a[j], hh);
                                 left = hh;
                             }
                         }
