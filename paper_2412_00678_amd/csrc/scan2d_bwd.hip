@@ -45,6 +45,7 @@ __global__ void scan2d_bwd_reduce_batch_kernel(const float* __restrict__ pA, con
 }
 
 struct BwdPlan {
+    bool small = false;                                    // one wavefront per map, no bands (scan2d_bwd_small.hpp)
     int LG = 0, K = 0, NW = 0, waves = 0, RB = 0;
     int NG = 0, GS = 0, CG = 0, nb = 0;
     BwdKernels k;
@@ -57,6 +58,25 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     BwdPlan pl;
     const int W = d->W, N = d->N;
+    if (W <= 16 && d->H <= 16 && N <= 16 && !std::getenv("SCAN2D_BWD_VARIANT")) {
+        // small maps: the whole map stays in registers; dBm/dCm partials per channel
+        pl.small = true;
+        pl.LG = 16; pl.K = 1; pl.NW = N <= 4 ? 1 : (N <= 8 ? 2 : 4); pl.waves = 4; pl.RB = d->H;
+        pl.NG = 4; pl.GS = 1; pl.CG = d->Dc; pl.nb = 1; pl.lds_bytes = 0;
+        pl.k.main = d->dtype == SCAN2D_BF16 ? bwd_small_kernel_bf16(pl.NW) : bwd_small_kernel_f32(pl.NW);
+        if (pl.k.main == nullptr) return false;
+        const size_t maps = (size_t)d->Bt * d->Dc;
+        const size_t NHW = (size_t)N * d->H * W;
+        size_t o = 0;
+        pl.off_ck = o;
+        pl.off_pB = o; o += pl.CG > 1 ? align_up(maps * NHW * sizeof(float)) : 0;
+        pl.off_pC = o; o += pl.CG > 1 ? align_up(maps * NHW * sizeof(float)) : 0;
+        pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
+        pl.off_pD = o; o += d->Bt > 1 ? align_up(maps * sizeof(float)) : 0;
+        pl.total = o;
+        *out = pl;
+        return true;
+    }
     int LG, K;
     if (W <= 64) { LG = 16; K = 4; }
     else if (W <= 128) { LG = 16; K = 8; }
@@ -158,8 +178,27 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.Bt = d->Bt; a.Dc = d->Dc; a.H = d->H; a.W = d->W; a.N = d->N;
     a.NG = pl.NG; a.GS = pl.GS; a.CG = pl.CG; a.nb = pl.nb;
 
-    const int slots = pl.waves * 64 / pl.LG;
     const long long maps = (long long)d->Bt * d->Dc;
+    if (pl.small) {
+        const long long wgs = (maps + 3) / 4;
+        if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+        (void)hipGetLastError();
+        hipLaunchKernelGGL(pl.k.main, dim3((unsigned)wgs), dim3(256), 0, stream, a);
+        if (pl.CG > 1) {
+            const size_t NHW = (size_t)d->N * d->H * d->W;
+            const size_t total = (size_t)d->Bt * NHW;
+            const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 16384);
+            hipLaunchKernelGGL(scan2d_bwd_reduce_groups_kernel, dim3(blocks), dim3(256), 0, stream,
+                               a.pB, a.pC, dBm, dCm, d->Bt, pl.CG, NHW);
+        }
+        if (d->Bt > 1) {
+            const int n = d->Dc * d->N;
+            hipLaunchKernelGGL(scan2d_bwd_reduce_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
+                               a.pA, a.pD, dA, dDskip, d->Bt, d->Dc, d->N);
+        }
+        return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+    }
+    const int slots = pl.waves * 64 / pl.LG;
     const int MPW = slots / pl.NG;
     BwdArgs ac = a;                                            // the checkpoint sweep may hold more states per lane
     ac.NG = (d->N + pl.k.ckpt_NW - 1) / pl.k.ckpt_NW;

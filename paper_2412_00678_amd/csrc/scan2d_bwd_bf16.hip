@@ -2,4 +2,5 @@
 #include "scan2d_bwd_variants.hpp"
 namespace scan2d {
 BwdKernels bwd_kernels_bf16(int LG, int K, int NW, int waves, bool fast) { return lookup_bwd_kernels<bf16_t>(LG, K, NW, waves, fast); }
+BwdKernel bwd_small_kernel_bf16(int NW) { return lookup_bwd_small_kernel<bf16_t>(NW); }
 }

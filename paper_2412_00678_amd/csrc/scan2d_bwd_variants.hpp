@@ -4,6 +4,7 @@
 #pragma once
 
 #include "scan2d_bwd_kernels.hpp"
+#include "scan2d_bwd_small.hpp"
 
 namespace scan2d {
 
@@ -33,6 +34,18 @@ inline BwdKernels lookup_bwd_kernels(int LG, int K, int NW, int waves, bool fast
     SCAN2D_BWD_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
     return r;
+}
+
+// Small maps (W, H, N <= 16): one wavefront per map, NW = states per lane group of its four.
+BwdKernel bwd_small_kernel_f32(int NW);
+BwdKernel bwd_small_kernel_bf16(int NW);
+
+template <typename T>
+inline BwdKernel lookup_bwd_small_kernel(int NW) {
+    if (NW == 1) return scan2d_bwd_small_kernel<T, 1>;
+    if (NW == 2) return scan2d_bwd_small_kernel<T, 2>;
+    if (NW == 4) return scan2d_bwd_small_kernel<T, 4>;
+    return nullptr;
 }
 
 }  // namespace scan2d

@@ -292,6 +292,16 @@ BWD_SHAPES = [
     (1, 6, 16, 9, 255, wl.BF16, 0.3),
     (1, 3, 24, 7, 132, wl.F32, 0.3),       # four states per lane, 12 columns per lane
     (1, 3, 40, 6, 250, wl.BF16, 0.2),
+    # small maps: one wavefront per map, the whole map in registers
+    (3, 5, 16, 14, 14, wl.F32, 0.3),
+    (2, 7, 16, 7, 7, wl.BF16, 0.3),
+    (1, 6, 4, 16, 16, wl.F32, 0.2),        # one state per lane group, all 16 rows and columns
+    (2, 3, 8, 14, 14, wl.BF16, 0.0),       # two states per lane group
+    (1, 4, 5, 9, 13, wl.F32, 0.3),         # N not a multiple of the states per lane
+    (1, 4, 3, 16, 1, wl.F32, 0.3),         # W = 1, fewer states than lane groups
+    (5, 1, 16, 14, 14, wl.F32, 0.3),       # one channel: no partial sums over channels
+    (1, 2, 16, 17, 14, wl.F32, 0.3),       # one row too many for the small-map kernel
+    (1, 2, 24, 14, 14, wl.F32, 0.3),       # too many states for it
 ]
 
 
