@@ -286,13 +286,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
             }
             ++step;
         };
-        for (int i = 0; i < H; i += TRIP) {
+        // Full trips run without a test between their rows: every path through the loop body then
+        // issues the same loads, and the compiler's wait counts let all TRIP rows of loads stay in
+        // flight (a skippable row would make it wait for nearly everything at each row).
+        int i = 0;
+        for (; i + TRIP <= H; i += TRIP) {
+            do_row(i, std::integral_constant<int, 0>{});
+            if constexpr (TRIP >= 2) do_row(i + 1, std::integral_constant<int, 1>{});
+            if constexpr (TRIP >= 4) {
+                do_row(i + 2, std::integral_constant<int, 2>{});
+                do_row(i + 3, std::integral_constant<int, 3>{});
+            }
+        }
+        if (i < H) {                                          // the last H % TRIP rows
             do_row(i, std::integral_constant<int, 0>{});
             if constexpr (TRIP >= 2) { if (i + 1 < H) do_row(i + 1, std::integral_constant<int, 1>{}); }
-            if constexpr (TRIP >= 4) {
-                if (i + 2 < H) do_row(i + 2, std::integral_constant<int, 2>{});
-                if (i + 3 < H) do_row(i + 3, std::integral_constant<int, 3>{});
-            }
+            if constexpr (TRIP >= 4) { if (i + 2 < H) do_row(i + 2, std::integral_constant<int, 2>{}); }
         }
     }
 }
