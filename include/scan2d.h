@@ -38,7 +38,7 @@
  * Limits of this version: 1 <= N <= 64; N*H*W < 2^27 (the kernels address one map's states
  * with 32-bit lane offsets); any H, W >= 1 in the forward (maps wider than one lane-group
  * panel need a workspace, see scan2d_workspace_bytes); the backward accepts W <= 1024, and
- * W <= 512 when N > 16.  Shapes outside these limits return SCAN2D_ERR_BAD_SHAPE.
+ * W <= 256 when N > 16.  Shapes outside these limits return SCAN2D_ERR_BAD_SHAPE.
  */
 #ifndef SCAN2D_H_
 #define SCAN2D_H_
@@ -54,7 +54,7 @@ enum {
     SCAN2D_OK                   =  0,
     SCAN2D_ERR_NULL_POINTER     = -1,  /* a required pointer is NULL */
     SCAN2D_ERR_BAD_SHAPE        = -2,  /* a dimension < 1, N > 64, N*H*W >= 2^27, element count overflow,
-                                          or (backward only) W > 1024, or W > 512 with N > 16 */
+                                          or (backward only) W > 1024, or W > 256 with N > 16 */
     SCAN2D_ERR_BAD_DTYPE        = -3,
     SCAN2D_ERR_BAD_FLAGS        = -4,  /* flags must be 0 */
     SCAN2D_ERR_WORKSPACE_SMALL  = -5,  /* workspace_bytes < scan2d_workspace_bytes() */
@@ -112,6 +112,16 @@ int scan2d_bwd(const scan2d_desc* desc,
 /* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD / _BWD).
  * Returns 0 for an invalid descriptor (the call itself then reports the error). */
 size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass);
+
+/*
+ * Diagnostic, not part of the paper's operator: writes a one-line description of the launch plan
+ * the library would use for this descriptor and pass (kernel form, lane-group width LG, columns K
+ * and states NW per lane, wavefronts per workgroup, rows per barrier or per band, channels per
+ * workgroup, workgroups, dynamic LDS bytes, workspace bytes) into `text` (host memory, at most
+ * `text_bytes` bytes including the terminating 0).  Touches no device memory and enqueues nothing.
+ * Returns SCAN2D_OK, or the error code the corresponding call would return for this descriptor.
+ */
+int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* text, size_t text_bytes);
 
 /* Static, never-NULL description of an error code. */
 const char* scan2d_strerror(int code);

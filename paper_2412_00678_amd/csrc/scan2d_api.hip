@@ -6,6 +6,7 @@
 
 #include <atomic>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 
@@ -255,6 +256,25 @@ extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
     }
     if (pass == SCAN2D_PASS_BWD) return bwd_workspace_bytes(desc);
     return 0;
+}
+
+extern "C" int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* text, size_t text_bytes) {
+    if (text == nullptr || text_bytes == 0) return SCAN2D_ERR_NULL_POINTER;
+    text[0] = 0;
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (pass == SCAN2D_PASS_FWD) {
+        FwdChoice ch;
+        rc = choose_fwd(desc, &ch);
+        if (rc != SCAN2D_OK) return rc;
+        const long long maps = (long long)desc->Bt * desc->Dc;
+        std::snprintf(text, text_bytes, "fwd form=%s LG=%d K=%d NW=%d waves=%d RPB=%d NG=%d MPW=%d panels=%d fast=%d exact=%d wgs=%lld lds=%zu workspace=%zu",
+                      ch.K < 4 ? "small" : "general", ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
+                      (int)ch.fast, (int)ch.exact, (maps + ch.MPW - 1) / ch.MPW, ch.lds_bytes, fwd_workspace(desc, ch));
+        return SCAN2D_OK;
+    }
+    if (pass == SCAN2D_PASS_BWD) return bwd_describe(desc, text, text_bytes) ? SCAN2D_OK : SCAN2D_ERR_BAD_SHAPE;
+    return SCAN2D_ERR_BAD_FLAGS;
 }
 
 extern "C" const char* scan2d_strerror(int code) {

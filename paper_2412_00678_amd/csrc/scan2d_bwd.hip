@@ -159,6 +159,19 @@ size_t bwd_workspace_bytes(const scan2d_desc* d) {
     return make_plan(d, &pl) ? pl.total : 0;
 }
 
+bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
+    BwdPlan pl;
+    if (!make_plan(d, &pl)) return false;
+    const long long maps = (long long)d->Bt * d->Dc;
+    long long wgs;
+    if (pl.small) wgs = (maps + 3) / 4;
+    else wgs = ((long long)d->Bt * pl.CG + (pl.waves * 64 / pl.LG) / pl.NG - 1) / ((pl.waves * 64 / pl.LG) / pl.NG);
+    std::snprintf(text, text_bytes, "bwd form=%s LG=%d K=%d NW=%d waves=%d RB=%d GS=%d CG=%d bands=%d wgs=%lld lds=%zu workspace=%zu",
+                  pl.small ? "small" : "banded", pl.LG, pl.K, pl.NW, pl.waves, pl.RB, pl.GS, pl.CG, pl.nb, wgs,
+                  pl.lds_bytes, pl.total);
+    return true;
+}
+
 int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
                void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,

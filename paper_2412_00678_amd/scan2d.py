@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libscan2d.so")
 F32, BF16 = 0, 1
 PASS_FWD, PASS_BWD = 0, 1
 
-EXPORTS = ("scan2d_fwd", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_strerror", "scan2d_version")
+EXPORTS = ("scan2d_fwd", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
+           "scan2d_version")
 
 
 class Desc(ctypes.Structure):
@@ -49,6 +50,8 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_strerror.argtypes = [ctypes.c_int]
     lib.scan2d_strerror.restype = ctypes.c_char_p
     lib.scan2d_version.restype = ctypes.c_int
+    lib.scan2d_describe_plan.argtypes = [ctypes.POINTER(Desc), ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
+    lib.scan2d_describe_plan.restype = ctypes.c_int
     return lib
 
 
@@ -89,6 +92,15 @@ def _check(t: Optional[torch.Tensor], name: str, dtype, shape, optional=False):
 def make_desc(x: torch.Tensor, A: torch.Tensor) -> Desc:
     Bt, Dc, H, W = x.shape
     return Desc(Bt, Dc, H, W, A.shape[1], _dtype_code(x), 0)
+
+
+def describe_plan(desc: Desc, which: int) -> str:
+    """One line naming the kernel form and launch shape the library would use (diagnostic)."""
+    buf = ctypes.create_string_buffer(512)
+    rc = lib.scan2d_describe_plan(ctypes.byref(desc), which, buf, len(buf))
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_describe_plan")
+    return buf.value.decode()
 
 
 def workspace_bytes(desc: Desc, which: int) -> int:

@@ -27,7 +27,8 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted(
-        ["scan2d_fwd", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_strerror", "scan2d_version"])
+        ["scan2d_fwd", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
+         "scan2d_version"])
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -77,3 +78,83 @@ def test_workspace_query(lib):
     assert lib.workspace_bytes(wide, lib.PASS_FWD) == 1 * 2 * 4 * 8 * 4
     assert lib.workspace_bytes(lib.Desc(0, 1, 1, 1, 1, 0, 0), lib.PASS_FWD) == 0
     assert lib.workspace_bytes(small, 5) == 0
+
+
+# ------------------------------------------------------------------ host logic: variant choice and launch plans
+
+def plan(lib, d, which):
+    fields = {}
+    for tok in lib.describe_plan(d, which).split()[1:]:
+        k, v = tok.split("=")
+        fields[k] = v if k == "form" else int(v)
+    return fields
+
+
+SWEEP_W = [1, 2, 3, 7, 13, 14, 15, 16, 17, 20, 28, 30, 31, 32, 33, 56, 60, 63, 64, 65, 100, 127, 128, 129, 132, 190, 192,
+           193, 200, 250, 255, 256, 257, 300, 500, 512, 513, 777, 1000, 1024, 1025, 3000]
+SWEEP_N = [1, 3, 4, 5, 8, 15, 16, 17, 24, 40, 63, 64]
+
+
+def test_every_shape_has_a_forward_plan_within_the_hardware_limits(lib):
+    for dtype in (0, 1):
+        for W in SWEEP_W:
+            for N in SWEEP_N:
+                for (Bt, Dc, H) in ((1, 1, 1), (2, 7, 9), (4, 256, 64)):
+                    d = lib.Desc(Bt, Dc, H, W, N, dtype, 0)
+                    f = plan(lib, d, lib.PASS_FWD)
+                    where = f"dtype {dtype} W {W} N {N} Bt {Bt} Dc {Dc} H {H}: {f}"
+                    assert f["lds"] <= 160 * 1024, where
+                    assert f["waves"] in (4, 8, 16), where
+                    if f["form"] == "small":
+                        assert W <= 16 * f["K"] and 4 * f["NW"] >= N, where
+                        assert f["wgs"] == -(-Bt * Dc // 4), where
+                    else:
+                        assert f["NG"] * f["NW"] >= N and f["NG"] <= f["waves"] * 64 // f["LG"], where
+                        assert f["panels"] * f["LG"] * f["K"] >= W, where
+                        assert f["wgs"] * f["MPW"] >= Bt * Dc, where
+                        assert (f["workspace"] > 0) == (f["panels"] > 1), where
+                        if f["fast"]:
+                            assert W % f["K"] == 0 and f["panels"] == 1, where
+                        if f["exact"]:
+                            assert N % f["NW"] == 0, where
+                    assert f["workspace"] == lib.workspace_bytes(d, lib.PASS_FWD), where
+
+
+def test_backward_plans_cover_the_documented_range_and_nothing_else(lib):
+    for dtype in (0, 1):
+        for W in SWEEP_W:
+            for N in SWEEP_N:
+                for (Bt, Dc, H) in ((1, 1, 1), (2, 7, 9), (4, 512, 128)):
+                    d = lib.Desc(Bt, Dc, H, W, N, dtype, 0)
+                    supported = W <= 1024 and (N <= 16 or W <= 256)
+                    if not supported:
+                        with pytest.raises(lib.Scan2dError):
+                            plan(lib, d, lib.PASS_BWD)
+                        assert lib.workspace_bytes(d, lib.PASS_BWD) == 0
+                        continue
+                    f = plan(lib, d, lib.PASS_BWD)
+                    where = f"dtype {dtype} W {W} N {N} Bt {Bt} Dc {Dc} H {H}: {f}"
+                    assert f["lds"] <= 160 * 1024, where
+                    assert f["workspace"] == lib.workspace_bytes(d, lib.PASS_BWD), where
+                    assert 1 <= f["GS"] <= 8 and f["CG"] == -(-Dc // f["GS"]), where
+                    if f["form"] == "small":
+                        assert W <= 16 and H <= 16 and N <= 16 and 4 * f["NW"] >= N, where
+                    else:
+                        assert f["LG"] * f["K"] >= W, where
+                        assert f["bands"] == -(-H // f["RB"]), where
+                        # checkpoints + partial sums over channel groups + partial sums over batch items
+                        ck = Bt * Dc * f["bands"] * N * W * 4
+                        part = 2 * Bt * f["CG"] * N * H * W * 4 if f["CG"] > 1 else 0
+                        assert f["workspace"] >= ck + part, where
+                        assert f["workspace"] <= ck + part + Bt * Dc * (N + 1) * 4 + 5 * 256, where
+
+
+def test_benchmark_configurations_take_the_intended_forms(lib):
+    f = plan(lib, lib.Desc(1, 256, 256, 256, 16, 1, 0), lib.PASS_FWD)
+    assert (f["LG"], f["K"], f["NW"], f["waves"]) == (64, 4, 2, 8) and f["fast"] and f["wgs"] == 256
+    f = plan(lib, lib.Desc(32, 192, 56, 56, 16, 1, 0), lib.PASS_FWD)
+    assert f["LG"] == 16 and f["K"] == 4 and f["fast"]
+    f = plan(lib, lib.Desc(1, 16, 16, 16, 4, 0, 0), lib.PASS_FWD)
+    assert f["form"] == "small"
+    b = plan(lib, lib.Desc(4, 512, 128, 192, 16, 0, 0), lib.PASS_BWD)
+    assert (b["form"], b["LG"], b["K"], b["NW"]) == ("banded", 16, 12, 1) and b["wgs"] * b["GS"] >= 4 * 512 // 1

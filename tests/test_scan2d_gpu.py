@@ -302,6 +302,7 @@ BWD_SHAPES = [
     (5, 1, 16, 14, 14, wl.F32, 0.3),       # one channel: no partial sums over channels
     (1, 2, 16, 17, 14, wl.F32, 0.3),       # one row too many for the small-map kernel
     (1, 2, 24, 14, 14, wl.F32, 0.3),       # too many states for it
+    (1, 2, 64, 5, 256, wl.F32, 0.2),       # widest map with more than 16 states
 ]
 
 
@@ -388,3 +389,30 @@ def test_runs_on_a_side_stream(s2d):
     st.synchronize()
     ref = oracle_fwd(inp, wl.BF16)
     assert rel_err(wl.to_float(s2d.to_host(y), wl.BF16), wl.to_float(ref, wl.BF16)) <= 2e-2
+
+
+# ------------------------------------------------------------------ shapes nobody chose by hand
+
+def _random_shape(seed, backward):
+    r = np.random.default_rng(1000 + seed)
+    N = int(r.choice([1, 2, 3, 4, 5, 8, 12, 16, 16, 16, 17, 24, 32, 64]))
+    W = int(r.choice([r.integers(1, 17), r.integers(17, 65), r.integers(65, 257), r.integers(257, 700)]))
+    if backward and N > 16:
+        W = min(W, 256)
+    H = int(r.integers(1, 24))
+    Bt, Dc = int(r.integers(1, 4)), int(r.integers(1, 10))
+    dtype = int(r.integers(0, 2))
+    mf = float(r.choice([0.0, 0.3]))
+    return Bt, Dc, N, H, W, dtype, mf
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_forward_random_shapes(s2d, seed):
+    Bt, Dc, N, H, W, dtype, mf = _random_shape(seed, False)
+    check_fwd(s2d, wl.Workload(f"rand{seed}", Bt, Dc, N, H, W, dtype, mask_frac=mf), seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_backward_random_shapes(s2d, seed):
+    Bt, Dc, N, H, W, dtype, mf = _random_shape(seed, True)
+    check_bwd(s2d, wl.Workload(f"brand{seed}", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True), seed=seed)
