@@ -391,6 +391,54 @@ def test_runs_on_a_side_stream(s2d):
     assert rel_err(wl.to_float(s2d.to_host(y), wl.BF16), wl.to_float(ref, wl.BF16)) <= 2e-2
 
 
+def test_forward_and_backward_replay_from_a_hip_graph(s2d):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so its calls can be captured; every replay must equal the eager result bit for
+    bit, also after the inputs changed and eager work ran in between."""
+    import torch
+    w = wl.Workload("graph", 2, 12, 16, 40, 96, wl.F32, mask_frac=0.3, backward=True)
+    sets = [wl.make_inputs(w, seed=k) for k in (11, 12)]
+    static = s2d.to_device(sets[0], wl.F32)
+    desc = s2d.make_desc(static["x"], static["A"])
+    y = torch.empty_like(static["x"])
+    ws_f = torch.empty(max(16, s2d.workspace_bytes(desc, s2d.PASS_FWD)), dtype=torch.uint8, device="cuda:0")
+    ws_b = torch.empty(max(16, s2d.workspace_bytes(desc, s2d.PASS_BWD)), dtype=torch.uint8, device="cuda:0")
+    args = [static[k] for k in ("x", "delta", "A", "Bm", "Cm", "Dskip", "mask")]
+
+    def eager():
+        yy = s2d.scan2d_fwd(*args, workspace=ws_f)
+        gg = s2d.scan2d_bwd(*args, static["dy"], workspace=ws_b)
+        torch.cuda.synchronize()
+        return [s2d.to_host(yy)] + [s2d.to_host(t) for t in gg]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture
+        s2d.scan2d_fwd(*args, y=y, workspace=ws_f)
+        s2d.scan2d_bwd(*args, static["dy"], workspace=ws_b)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s2d.scan2d_fwd(*args, y=y, workspace=ws_f)
+        grads = s2d.scan2d_bwd(*args, static["dy"], workspace=ws_b)
+    for k in (0, 1, 0):
+        new = s2d.to_device(sets[k], wl.F32)
+        for name in ("x", "delta", "A", "Bm", "Cm", "Dskip", "mask", "dy"):
+            static[name].copy_(new[name])
+        y.fill_(float("nan"))
+        for t in grads:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [s2d.to_host(y)] + [s2d.to_host(t) for t in grads]
+        ref = eager()                                   # eager work between the replays
+        for a, b in zip(got, ref):
+            assert np.array_equal(a, b)
+    yo = oracle_fwd(sets[0], wl.F32)
+    assert rel_err(got[0], yo) <= 1e-4
+
+
 # ------------------------------------------------------------------ shapes nobody chose by hand
 
 def _random_shape(seed, backward):
