@@ -41,6 +41,8 @@ def _load():
         lib.oracle_scan2d_bwd.argtypes = [ip] * 6 + [vp] * 14 + [ip]
         lib.oracle_scan2d_bwd.restype = ip
         lib.oracle_num_procs.restype = ip
+        lib.oracle_round_to_bf16.argtypes = [vp, vp, ctypes.c_size_t]
+        lib.oracle_round_to_bf16.restype = None
         _lib = lib
     return _lib
 
@@ -127,3 +129,53 @@ def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F32, threads=0):
     if rc != 0:
         raise RuntimeError(f"oracle_scan2d_bwd failed ({rc})")
     return dx, ddelta, dA, dBm, dCm, dDskip
+
+
+# ----------------------------------------------------------------------------------------------
+# Step fused in front of the scan (2DMamba Eq. 3: the step is softplus of a projection; the
+# supplementary algorithm adds a bias inside the softplus): delta = softplus(raw + bias[c]).
+# Written as a composition: the library routine numpy.logaddexp(0, t) = log(1 + exp(t)) in double,
+# then the plain scan above on double storage, then one rounding to the storage type.  The
+# backward is the chain rule: d softplus(t) / dt = 1 / (1 + exp(-t)).
+
+def _widen(a, dtype):
+    a = np.ascontiguousarray(a)
+    if dtype == BF16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def _narrow(a, dtype):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if dtype == F32:
+        return a.astype(np.float32)
+    if dtype == F64:
+        return a
+    out = np.empty(a.shape, np.uint16)
+    _load().oracle_round_to_bf16(_ptr(a), _ptr(out), a.size)
+    return out
+
+
+def _step(delta_raw, delta_bias, dtype):
+    t = _widen(delta_raw, dtype)
+    if delta_bias is not None:
+        t = t + np.asarray(delta_bias, np.float64)[None, :, None, None]
+    return t, np.logaddexp(0.0, t)
+
+
+def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=None, dtype=F32, threads=0):
+    """y of the scan with delta = softplus(delta_raw + delta_bias[c]) (delta_bias: [Dc] fp32 or None)."""
+    _, delta = _step(delta_raw, delta_bias, dtype)
+    y = scan2d_fwd(_widen(x, dtype), delta, A, _widen(Bm, dtype), _widen(Cm, dtype), Dskip, mask,
+                   dtype=F64, threads=threads)
+    return _narrow(y, dtype)
+
+
+def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, dtype=F32, threads=0):
+    """Gradients (dx, ddelta_raw, ddelta_bias, dA, dBm, dCm, dDskip); ddelta_bias is None iff delta_bias is."""
+    t, delta = _step(delta_raw, delta_bias, dtype)
+    dx, dd, dA, dBm, dCm, dD = scan2d_bwd(_widen(x, dtype), delta, A, _widen(Bm, dtype), _widen(Cm, dtype),
+                                          Dskip, mask, _widen(dy, dtype), dtype=F64, threads=threads)
+    draw = dd / (1.0 + np.exp(-t))
+    dbias = None if delta_bias is None else draw.sum(axis=(0, 2, 3)).astype(np.float32)
+    return _narrow(dx, dtype), _narrow(draw, dtype), dbias, dA, dBm, dCm, dD

@@ -323,3 +323,10 @@ int oracle_num_procs(void)
     return 1;
 #endif
 }
+
+/* Rounds n doubles to bf16 bits with the single nearest-even rounding used for every output of
+ * the oracle (for the Python-level compositions around the two functions above). */
+void oracle_round_to_bf16(const double* in, uint16_t* out, size_t n) {
+    for (size_t k = 0; k < n; ++k) out[k] = round_to_bf16(in[k]);
+}
+

@@ -401,3 +401,87 @@ def test_thread_count_does_not_change_results():
     g4 = oracle.scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F64, threads=4)
     for a, b in zip(g1, g4):
         np.testing.assert_allclose(a, b, rtol=1e-6, atol=1e-9)   # channel sums re-associate
+
+
+# ---------------------------------------------------------------------------- softplus step (Eq. 3)
+
+def test_softplus_step_is_log1p_exp_with_its_asymptotes():
+    """delta = softplus(raw + bias[c]) (Eq. 3; bias as in the supplementary algorithm): against
+    math.log1p(math.exp(t)) element by element, and against its two asymptotes (t for large t,
+    exp(t) for very negative t)."""
+    import math
+    rng = np.random.default_rng(41)
+    Bt, Dc, N, H, W = 1, 2, 2, 3, 4
+    x, _, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    raw = rng.normal(0.0, 3.0, x.shape)
+    bias = np.array([0.25, -1.5], np.float32)
+    delta = np.empty_like(raw)
+    for idx in np.ndindex(raw.shape):
+        delta[idx] = math.log1p(math.exp(raw[idx] + float(bias[idx[1]])))
+    want = oracle.scan2d_fwd(x, delta, A, Bm, Cm, Dskip, mask, dtype=F64)
+    got = oracle.scan2d_fwd_softplus(x, raw, bias, A, Bm, Cm, Dskip, mask, dtype=F64)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-13)
+    # no bias = zero bias
+    np.testing.assert_array_equal(oracle.scan2d_fwd_softplus(x, raw, None, A, Bm, Cm, Dskip, mask, dtype=F64),
+                                  oracle.scan2d_fwd_softplus(x, raw, np.zeros(Dc, np.float32), A, Bm, Cm, Dskip, mask, dtype=F64))
+    # asymptotes: softplus(t) -> t (t = 40: the difference is e^-40), -> exp(t) (t = -40)
+    big = np.full(x.shape, 40.0)
+    np.testing.assert_allclose(oracle.scan2d_fwd_softplus(x, big, None, A, Bm, Cm, Dskip, mask, dtype=F64),
+                               oracle.scan2d_fwd(x, big, A, Bm, Cm, Dskip, mask, dtype=F64), rtol=1e-12, atol=1e-12)
+    small = np.full(x.shape, -40.0)
+    np.testing.assert_allclose(oracle.scan2d_fwd_softplus(x, small, None, A, Bm, Cm, Dskip, mask, dtype=F64),
+                               oracle.scan2d_fwd(x, np.exp(small), A, Bm, Cm, Dskip, mask, dtype=F64), rtol=1e-12, atol=1e-30)
+
+
+def test_softplus_backward_matches_central_differences_and_the_logistic_chain_rule():
+    from scipy.special import expit
+    rng = np.random.default_rng(43)
+    Bt, Dc, N, H, W = 2, 2, 3, 3, 4
+    x, _, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    raw = rng.normal(-0.5, 1.5, x.shape)
+    bias = (np.round(rng.normal(0, 1, Dc) * 64) / 64).astype(np.float32)
+    dy = rng.standard_normal(x.shape)
+
+    def f(r, b):
+        return float(np.sum(dy * oracle.scan2d_fwd_softplus(x, r, b, A, Bm, Cm, Dskip, mask, dtype=F64)))
+
+    dx, draw, dbias, dA, dBm, dCm, dD = oracle.scan2d_bwd_softplus(x, raw, bias, A, Bm, Cm, Dskip, mask, dy, dtype=F64)
+    fd = np.zeros(raw.shape)
+    for idx in np.ndindex(raw.shape):
+        hi, lo = raw.copy(), raw.copy()
+        hi[idx] += 1e-6
+        lo[idx] -= 1e-6
+        fd[idx] = (f(hi, bias) - f(lo, bias)) / 2e-6
+    np.testing.assert_allclose(draw, fd, rtol=1e-7, atol=1e-7 * np.abs(fd).max())
+    eps = 2.0 ** -12
+    for c in range(Dc):
+        hi, lo = bias.copy(), bias.copy()
+        hi[c] += eps
+        lo[c] -= eps
+        assert abs((f(raw, hi) - f(raw, lo)) / (2 * eps) - dbias[c]) <= 2e-6 * max(1.0, abs(dbias[c]))
+    # chain rule with a library logistic function on top of the plain backward
+    t = raw + bias[None, :, None, None].astype(np.float64)
+    plain = oracle.scan2d_bwd(x, np.logaddexp(0.0, t), A, Bm, Cm, Dskip, mask, dy, dtype=F64)
+    np.testing.assert_allclose(draw, plain[1] * expit(t), rtol=1e-12, atol=1e-14)
+    for a, b in zip((dx, dA, dBm, dCm, dD), (plain[0], plain[2], plain[3], plain[4], plain[5])):
+        np.testing.assert_array_equal(a, b)
+    assert oracle.scan2d_bwd_softplus(x, raw, None, A, Bm, Cm, Dskip, mask, dy, dtype=F64)[2] is None
+
+
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_softplus_low_precision_storage_rounds_once(dtype):
+    rng = np.random.default_rng(47)
+    Bt, Dc, N, H, W = 1, 3, 4, 5, 6
+    x, _, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    raw = rng.normal(-1.0, 1.0, x.shape)
+    bias = rng.normal(0, 1, Dc).astype(np.float32)
+    st = lambda a: wl.f32_to_bf16_bits(a.astype(np.float32)) if dtype == oracle.BF16 else a.astype(np.float32)
+    xs, rs, Bs, Cs = st(x), st(raw), st(Bm), st(Cm)
+    wide = lambda a: wl.to_float(a, dtype).astype(np.float64)
+    y = oracle.scan2d_fwd_softplus(xs, rs, bias, A, Bs, Cs, Dskip, mask, dtype=dtype)
+    y64 = oracle.scan2d_fwd_softplus(wide(xs), wide(rs), bias, A, wide(Bs), wide(Cs), Dskip, mask, dtype=F64)
+    want = wl.f32_to_bf16_bits(y64.astype(np.float32)) if dtype == oracle.BF16 else y64.astype(np.float32)
+    if dtype == oracle.F32:
+        np.testing.assert_array_equal(y, want)
+    else:   # double -> fp32 -> bf16 may differ from the single rounding by one unit in rare ties
+        assert np.abs(y.astype(np.int32) - want.astype(np.int32)).max() <= 1
