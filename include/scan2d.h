@@ -89,6 +89,19 @@ int scan2d_fwd(const scan2d_desc* desc,
                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same scan with the step computed inside the kernels (Eq. 3: the step is the softplus of its
+ * projection; the supplementary algorithm adds a bias inside the softplus):
+ *     delta[b,c,i,j] = softplus(delta_raw[b,c,i,j] + delta_bias[c]),   softplus(t) = log(1 + exp(t))
+ * delta_raw has the layout and type of delta; delta_bias is [Dc] fp32 and may be NULL (no bias).
+ * Everything else as in scan2d_fwd.
+ */
+int scan2d_fwd_softplus(const scan2d_desc* desc,
+                        const void* x, const void* delta_raw, const float* delta_bias, const float* A,
+                        const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                        void* y,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Backward of the forward above for a given dy = dL/dy (Supp. B: two forward scans rebuild
  * the states, which are never stored by the forward; a reverse column scan and a reverse row
  * scan carry the gradients).  With g = dL/dh, q = dL/dhhor:

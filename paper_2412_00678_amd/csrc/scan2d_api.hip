@@ -64,13 +64,13 @@ struct V4 { int LG, K, NW, waves; };
 const V4 kFwdVariants[] = {SCAN2D_FWD_VARIANTS(SCAN2D_X)};
 #undef SCAN2D_X
 
-FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {
-    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi)
-                                : fwd_kernel_f32(LG, K, NW, waves, exact, fast, multi);
+FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp) {
+    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi, sp)
+                                : fwd_kernel_f32(LG, K, NW, waves, exact, fast, multi, sp);
 }
 
 // rpb: rows between two barriers; 0 = decide here
-bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb, FwdChoice* out) {
+bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb, bool sp, FwdChoice* out) {
     const int slots = waves * 64 / LG;
     FwdChoice c;
     c.LG = LG; c.K = K; c.NW = NW; c.waves = waves;
@@ -84,7 +84,7 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb
     // 32-bit lane offsets span up to `slots` maps and `slots + 1` batch items of states
     const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
     if (span >= 2147483648.0) return false;
-    c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi);
+    c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi, sp);
     if (c.kernel == nullptr) return false;
     // LDS for the partial sums: 2 buffers x RPB rows x (threads * K) floats.  Few large maps (one
     // workgroup per CU at most) can afford 64 KB; otherwise stay near 24 KB so that several
@@ -105,7 +105,7 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb
 }
 
 // Narrow maps: one wavefront per map, its four DPP rows share the states (scan2d_fwd_small.hpp).
-bool fill_small(const scan2d_desc* d, int KS, FwdChoice* out) {
+bool fill_small(const scan2d_desc* d, int KS, bool sp, FwdChoice* out) {
     if (d->W > 16 * KS) return false;
     int NW = 1;
     while (4 * NW < d->N) NW *= 2;
@@ -113,7 +113,7 @@ bool fill_small(const scan2d_desc* d, int KS, FwdChoice* out) {
     c.LG = 16; c.K = KS; c.NW = NW; c.waves = 4;
     c.exact = true; c.fast = false; c.multi = false;
     c.NG = 4; c.MPW = 4; c.panels = 1; c.RPB = 1; c.lds_bytes = 0;
-    c.kernel = d->dtype == SCAN2D_BF16 ? fwd_small_kernel_bf16(KS, NW) : fwd_small_kernel_f32(KS, NW);
+    c.kernel = d->dtype == SCAN2D_BF16 ? fwd_small_kernel_bf16(KS, NW, sp) : fwd_small_kernel_f32(KS, NW, sp);
     if (c.kernel == nullptr) return false;
     *out = c;
     return true;
@@ -162,24 +162,25 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     return wgs * c.waves * steps * 4.0 / (1024.0 * eff) * tail;
 }
 
-int choose_fwd(const scan2d_desc* d, FwdChoice* out) {
+// sp: pick the instantiation that computes the step itself; the choice of variant does not depend on it
+int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false) {
     if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES[,RPB]"
         int LG = 0, K = 0, NW = 0, waves = 4, rpb = 0;
         const int got = std::sscanf(env, "%d,%d,%d,%d,%d", &LG, &K, &NW, &waves, &rpb);
-        if (got >= 2 && LG == 16 && (K == 1 || K == 2) && fill_small(d, K, out)) return SCAN2D_OK;
+        if (got >= 2 && LG == 16 && (K == 1 || K == 2) && fill_small(d, K, sp, out)) return SCAN2D_OK;
         if (got >= 3 && (LG == 16 || LG == 32 || LG == 64) && NW >= 1 && (waves == 4 || waves == 8 || waves == 16) &&
-            fill_choice(d, LG, K, NW, waves, rpb, out))
+            fill_choice(d, LG, K, NW, waves, rpb, sp, out))
             return SCAN2D_OK;
     }
     // narrow maps: one column per lane up to 16 columns; two per lane up to 32 where the width rules out
     // the unguarded wide loads of the 4-column variants (measured: twice as fast as their guarded form)
-    if (d->W <= 16 && fill_small(d, 1, out)) return SCAN2D_OK;
-    if (d->W <= 32 && d->W % 4 != 0 && fill_small(d, 2, out)) return SCAN2D_OK;
+    if (d->W <= 16 && fill_small(d, 1, sp, out)) return SCAN2D_OK;
+    if (d->W <= 32 && d->W % 4 != 0 && fill_small(d, 2, sp, out)) return SCAN2D_OK;
     bool found = false;
     double best = 0.0;
     for (const V4& v : kFwdVariants) {
         FwdChoice c;
-        if (!fill_choice(d, v.LG, v.K, v.NW, v.waves, 0, &c)) continue;
+        if (!fill_choice(d, v.LG, v.K, v.NW, v.waves, 0, sp, &c)) continue;
         const double cost = fwd_cost(d, c);
         if (!found || cost < best) { best = cost; *out = c; found = true; }
     }
@@ -196,25 +197,27 @@ size_t fwd_workspace(const scan2d_desc* d, const FwdChoice& c) {
 
 using namespace scan2d;
 
-extern "C" int scan2d_fwd(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
-                          const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
-                          void* y, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, int softplus, const float* A,
+             const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+             void* y, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_desc(desc);
     if (rc != SCAN2D_OK) return rc;
     if (!x || !delta || !A || !Bm || !Cm || !y) return SCAN2D_ERR_NULL_POINTER;
     if (!aligned16(x) || !aligned16(delta) || !aligned16(A) || !aligned16(Bm) || !aligned16(Cm) ||
-        !aligned16(y) || !aligned16(Dskip) || !aligned16(mask) || !aligned16(workspace))
+        !aligned16(y) || !aligned16(Dskip) || !aligned16(mask) || !aligned16(workspace) || !aligned16(delta_bias))
         return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
     FwdChoice ch;
-    rc = choose_fwd(desc, &ch);
+    rc = choose_fwd(desc, &ch, softplus != 0);
     if (rc != SCAN2D_OK) return rc;
     const size_t need = fwd_workspace(desc, ch);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SCAN2D_ERR_WORKSPACE_SMALL;
 
     FwdArgs a;
     a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.y = y;
+    a.delta_bias = delta_bias;
     a.carry = static_cast<float*>(workspace);
     a.maps = (long long)desc->Bt * desc->Dc;
     a.Dc = desc->Dc; a.H = desc->H; a.W = desc->W; a.N = desc->N;
@@ -227,6 +230,19 @@ extern "C" int scan2d_fwd(const scan2d_desc* desc, const void* x, const void* de
                                   (int)ch.lds_bytes);
     hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(ch.waves * 64), ch.lds_bytes, static_cast<hipStream_t>(stream), a);
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+}  // namespace
+
+extern "C" int scan2d_fwd(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
+                          const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                          void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    return fwd_impl(desc, x, delta, nullptr, 0, A, Bm, Cm, Dskip, mask, y, workspace, workspace_bytes, stream);
+}
+
+extern "C" int scan2d_fwd_softplus(const scan2d_desc* desc, const void* x, const void* delta_raw, const float* delta_bias,
+                                   const float* A, const void* Bm, const void* Cm, const float* Dskip,
+                                   const uint8_t* mask, void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    return fwd_impl(desc, x, delta_raw, delta_bias, 1, A, Bm, Cm, Dskip, mask, y, workspace, workspace_bytes, stream);
 }
 
 extern "C" int scan2d_bwd(const scan2d_desc* desc, const void* x, const void* delta, const float* A,

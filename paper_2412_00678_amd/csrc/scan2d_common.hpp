@@ -167,6 +167,19 @@ __device__ __forceinline__ void store_row(T* __restrict__ rowp, int col0, int W,
     }
 }
 
+// softplus(t) = log(1 + exp(t)) = max(t, 0) + log1p(exp(-|t|)) (2DMamba Eq. 3: the step is the softplus
+// of its projection).  exp and log through v_exp_f32 / v_log_f32 (base 2); where exp(-|t|) is too small
+// for 1 + z to keep its digits the series z - z^2/2 takes over.
+__device__ __forceinline__ float softplus_f32(float t) {
+    const float z = __builtin_amdgcn_exp2f(-fabsf(t) * kLog2e);
+    const float lp = z < 2.44140625e-4f ? z * fmaf(-0.5f, z, 1.0f) : __builtin_amdgcn_logf(1.0f + z) * 0.6931471805599453f;
+    return fmaxf(t, 0.0f) + lp;
+}
+// d softplus(t) / dt = 1 / (1 + exp(-t))
+__device__ __forceinline__ float logistic_f32(float t) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t * kLog2e));
+}
+
 // h = a * h + add with h updated in place.  The compiler would pick the two-operand
 // v_fmac_f32, whose destination is the addend, and then move the result back into the register
 // that carries h into the next row: one extra instruction per state and column.  The

@@ -51,6 +51,7 @@ __device__ __forceinline__ float sum_partials(const float* p, int NG) {
 struct FwdArgs {
     const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
     const float* Dskip; const uint8_t* mask; void* y;
+    const float* delta_bias;   // [Dc] or null; read by the SP instantiations only (delta then holds the raw projection)
     float* carry;        // [maps][N][H] row-end states between column panels (panels > 1 only)
     long long maps;      // Bt * Dc
     int Dc, H, W, N;
@@ -65,6 +66,8 @@ struct FwdArgs {
 // lane 0 and its results are discarded).  Otherwise every element access is guarded.
 // MULTI: the map is wider than one panel (p.panels > 1); single-panel kernels carry no code
 // for the panel hand-over.
+// SP: the step is computed here, delta = softplus(raw + bias) (a second set of instantiations, so that
+// the plain kernels carry neither the code nor its registers).
 // WAVES: wavefronts per workgroup (4, 8 or 16).  One wave per SIMD reaches only about half of
 // the vector issue rate on this chip, so maps that are few but large spread their states over
 // more waves (smaller NW) rather than leaving SIMDs with a single wave.
@@ -77,7 +80,7 @@ struct FwdArgs {
 #endif
 constexpr int kPrefetchBudgetX = SCAN2D_PREFETCH_BUDGET_X, kPrefetchBudgetS = SCAN2D_PREFETCH_BUDGET_S;
 
-template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI>
+template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI, bool SP = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p) {
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
@@ -126,6 +129,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
         Ap[s] = p.A[(size_t)c * N + n] * kLog2e;             // a = exp2(delta * A * log2 e)
     }
     const float dsk = (p.Dskip != nullptr && sg == 0) ? p.Dskip[c] : 0.0f;
+    // SP: `delta` holds the raw projection and the step is softplus(raw + delta_bias[c]) (Eq. 3)
+    const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;
     const bool reduce = NG > 1;
 
     int step = 0;   // rows processed so far: its parity selects the LDS buffer
@@ -198,6 +203,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 dl[j] = get_elem<T, K>(rd[XS], j);
+                if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
                 const float xv = get_elem<T, K>(rx[XS], j);
                 const float xe = mask_bit<K>(rm[XS], j) ? 0.0f : xv;      // select: nothing under the mask leaks
                 dx[j] = dl[j] * xe;

@@ -19,7 +19,7 @@ namespace scan2d {
 __device__ __forceinline__ float raw_to_float(float, uint32_t bits) { return __uint_as_float(bits); }
 __device__ __forceinline__ float raw_to_float(bf16_t, uint32_t bits) { return __uint_as_float(bits << 16); }
 
-template <typename T, int KS, int NW, int PD>
+template <typename T, int KS, int NW, int PD, bool SP = false>
 __global__ __launch_bounds__(256) void scan2d_fwd_small_kernel(const FwdArgs p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l = lane & 15, g = lane >> 4;
@@ -53,6 +53,7 @@ __global__ __launch_bounds__(256) void scan2d_fwd_small_kernel(const FwdArgs p) 
         for (int k = 0; k < KS; ++k) h[s][k] = 0.0f;
     }
     const float dsk = (g == 0 && p.Dskip != nullptr) ? p.Dskip[c] : 0.0f;
+    const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;   // SP: delta = softplus(raw + bias)
 
     // ring of raw registers: row i waits in slot i % PD
     uint32_t rx[PD][KS], rd[PD][KS], rm[PD][KS], rB[PD][NW][KS], rC[PD][NW][KS];
@@ -85,6 +86,7 @@ __global__ __launch_bounds__(256) void scan2d_fwd_small_kernel(const FwdArgs p) 
 #pragma unroll
                 for (int k = 0; k < KS; ++k) {
                     dl[k] = raw_to_float(T{}, rd[r][k]);
+                    if constexpr (SP) dl[k] = softplus_f32(dl[k] + dbias);
                     xe[k] = rm[r][k] != 0u ? 0.0f : raw_to_float(T{}, rx[r][k]);
                     dxe[k] = dl[k] * xe[k];
                     yacc[k] = dsk * xe[k];

@@ -42,43 +42,44 @@ namespace scan2d {
 using FwdKernel = void (*)(const FwdArgs);
 
 // Returns nullptr when the variant is not compiled.
-FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
-FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
+// sp: the instantiations that compute the step themselves (softplus of the raw projection).
+FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp);
+FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp);
 
 // Narrow maps (W <= 32): KS columns per lane, NW = states per lane group of the wave's four.
-FwdKernel fwd_small_kernel_f32(int KS, int NW);
-FwdKernel fwd_small_kernel_bf16(int KS, int NW);
+FwdKernel fwd_small_kernel_f32(int KS, int NW, bool sp);
+FwdKernel fwd_small_kernel_bf16(int KS, int NW, bool sp);
 
-template <typename T>
+template <typename T, bool SP>
 inline FwdKernel lookup_fwd_small_kernel(int KS, int NW) {
 #define SCAN2D_X(ks, nw, pd) \
-    if (KS == ks && NW == nw) return scan2d_fwd_small_kernel<T, ks, nw, pd>;
+    if (KS == ks && NW == nw) return scan2d_fwd_small_kernel<T, ks, nw, pd, SP>;
     SCAN2D_X(1, 1, 4) SCAN2D_X(1, 2, 4) SCAN2D_X(1, 4, 4) SCAN2D_X(1, 8, 2) SCAN2D_X(1, 16, 2)
     SCAN2D_X(2, 1, 4) SCAN2D_X(2, 2, 4) SCAN2D_X(2, 4, 4) SCAN2D_X(2, 8, 2) SCAN2D_X(2, 16, 1)
 #undef SCAN2D_X
     return nullptr;
 }
 
-template <typename T>
+template <typename T, bool SP>
 inline FwdKernel lookup_fwd_kernel(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {
 #define SCAN2D_X(lg, k, nw, wv) \
-    if (exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, true, false>;
+    if (exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, true, false, SP>;
     SCAN2D_FWD_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
 #define SCAN2D_X(lg, k, nw, wv) \
-    if (!exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, false, true, false>;
+    if (!exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, false, true, false, SP>;
     SCAN2D_FWD_RAGGED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
 #define SCAN2D_X(lg, k, nw, wv) \
-    if (exact && !fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, false>;
+    if (exact && !fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, false, SP>;
     SCAN2D_FWD_GUARDED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
 #define SCAN2D_X(lg, k, nw, wv) \
-    if (exact && !fast && multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, true>;
+    if (exact && !fast && multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, true, SP>;
     SCAN2D_FWD_MULTI_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
     if (!exact && !fast && LG == 16 && K == 4 && NW == 4 && waves == 4)
-        return multi ? scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, true> : scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, false>;
+        return multi ? scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, true, SP> : scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, false, SP>;
     return nullptr;
 }
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libscan2d.so")
 F32, BF16 = 0, 1
 PASS_FWD, PASS_BWD = 0, 1
 
-EXPORTS = ("scan2d_fwd", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
+EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
            "scan2d_version")
 
 
@@ -43,6 +43,8 @@ def _load() -> ctypes.CDLL:
     vp = ctypes.c_void_p
     lib.scan2d_fwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 8 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_fwd.restype = ctypes.c_int
+    lib.scan2d_fwd_softplus.argtypes = [ctypes.POINTER(Desc)] + [vp] * 9 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_fwd_softplus.restype = ctypes.c_int
     lib.scan2d_bwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 14 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_bwd.restype = ctypes.c_int
     lib.scan2d_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.c_int]
@@ -140,6 +142,32 @@ def scan2d_fwd(x, delta, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=Non
                         _ptr(Dskip), _ptr(mask), _ptr(y), _ptr(workspace), wbytes, _stream_ptr())
     if rc != 0:
         raise Scan2dError(rc, "scan2d_fwd")
+    return y
+
+
+def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None):
+    """y of the scan with delta = softplus(delta_raw + delta_bias[c]) computed in the kernels."""
+    desc = make_desc(x, A)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))
+    _check(delta_bias, "delta_bias", torch.float32, (Dc,), optional=True)
+    _check(A, "A", torch.float32, (Dc, N))
+    _check(Bm, "Bm", x.dtype, (Bt, N, H, W))
+    _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    if y is None:
+        y = torch.empty_like(x)
+    _check(y, "y", x.dtype, (Bt, Dc, H, W))
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_FWD, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    rc = lib.scan2d_fwd_softplus(ctypes.byref(desc), _ptr(x), _ptr(delta_raw), _ptr(delta_bias), _ptr(A), _ptr(Bm),
+                                 _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(y), _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_fwd_softplus")
     return y
 
 

@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted(
-        ["scan2d_fwd", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
+        ["scan2d_fwd", "scan2d_fwd_softplus", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
          "scan2d_version"])
 
 

@@ -391,6 +391,56 @@ def test_runs_on_a_side_stream(s2d):
     assert rel_err(wl.to_float(s2d.to_host(y), wl.BF16), wl.to_float(ref, wl.BF16)) <= 2e-2
 
 
+# ------------------------------------------------------------------ step computed in the kernels
+
+def _softplus_inputs(w, seed):
+    """The workload's tensors with `delta` replaced by a raw projection spread over both tails of the
+    softplus (its stored values are rounded to the storage type once) and a per-channel bias."""
+    inp = wl.make_inputs(w, seed=seed)
+    r = np.random.default_rng(500 + seed)
+    raw = r.normal(-2.0, 2.5, (w.Bt, w.Dc, w.H, w.W))
+    raw.reshape(-1)[:: 97] = 30.0                      # far right tail: softplus(t) = t
+    raw.reshape(-1)[5:: 101] = -40.0                   # far left tail: softplus(t) = exp(t)
+    raw = raw.astype(np.float32)
+    inp["delta"] = wl.f32_to_bf16_bits(raw) if w.dtype == wl.BF16 else raw
+    inp["delta_bias"] = r.normal(0.0, 0.5, w.Dc).astype(np.float32)
+    return inp
+
+
+SOFTPLUS_SHAPES = [
+    (1, 6, 16, 21, 64, wl.F32, 0.3), (2, 5, 16, 14, 14, wl.BF16, 0.2), (1, 3, 16, 9, 200, wl.BF16, 0.3),
+    (1, 4, 5, 7, 45, wl.F32, 0.2), (1, 3, 16, 13, 192, wl.F32, 0.0), (1, 2, 8, 5, 600, wl.F32, 0.3),
+    (1, 16, 16, 64, 256, wl.BF16, 0.5), (3, 2, 4, 6, 30, wl.F32, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape", SOFTPLUS_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+@pytest.mark.parametrize("with_bias", [True, False], ids=["bias", "nobias"])
+def test_forward_with_softplus_step_matches_oracle(s2d, shape, with_bias):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("sp", Bt, Dc, N, H, W, dtype, mask_frac=mf)
+    inp = _softplus_inputs(w, seed=9)
+    bias = inp["delta_bias"] if with_bias else None
+    print(f"softplus fwd case Bt={Bt} Dc={Dc} N={N} H={H} W={W} dtype={dtype} bias={with_bias}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    db = torch.from_numpy(bias).cuda() if with_bias else None
+    y = s2d.scan2d_fwd_softplus(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
+    torch.cuda.synchronize()
+    ref = oracle.scan2d_fwd_softplus(inp["x"], inp["delta"], bias, inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"],
+                                     inp["mask"], dtype=dtype)
+    got = wl.to_float(s2d.to_host(y), dtype)
+    assert np.isfinite(got).all()
+    assert rel_err(got, wl.to_float(ref, dtype)) <= TOL[dtype]
+    # the plain entry point on the step computed by a library routine gives the same result to rounding
+    if dtype == wl.F32:
+        t = inp["delta"].astype(np.float64) + (0.0 if bias is None else bias[None, :, None, None])
+        inp2 = dict(inp)
+        inp2["delta"] = np.logaddexp(0.0, t).astype(np.float32)
+        y2 = run_fwd(s2d, inp2, dtype)
+        assert rel_err(got, y2) <= 1e-5
+
+
 def test_forward_and_backward_replay_from_a_hip_graph(s2d):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so its calls can be captured; every replay must equal the eager result bit for
