@@ -122,6 +122,23 @@ int scan2d_bwd(const scan2d_desc* desc,
                void* dx, void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip,
                void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Backward of scan2d_fwd_softplus: as scan2d_bwd, but the step is softplus(delta_raw + delta_bias[c]) and
+ * the gradients are those of the raw projection and of the bias (chain rule: d softplus(t)/dt =
+ * 1/(1 + exp(-t))):
+ *     ddelta_raw[b,c,i,j] = ddelta[b,c,i,j] / (1 + exp(-(delta_raw[b,c,i,j] + delta_bias[c])))
+ *     ddelta_bias[c]      = sum_{b,i,j} ddelta_raw[b,c,i,j]      (summed from the stored ddelta_raw)
+ * ddelta_raw has the layout and type of delta_raw; ddelta_bias is [Dc] fp32 and must be NULL iff
+ * delta_bias is NULL.  Workspace as for scan2d_bwd (scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD)).
+ */
+int scan2d_bwd_softplus(const scan2d_desc* desc,
+                        const void* x, const void* delta_raw, const float* delta_bias, const float* A,
+                        const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                        const void* dy,
+                        void* dx, void* ddelta_raw, float* ddelta_bias, float* dA, float* dBm, float* dCm,
+                        float* dDskip,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD / _BWD).
  * Returns 0 for an invalid descriptor (the call itself then reports the error). */
 size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass);

@@ -245,22 +245,41 @@ extern "C" int scan2d_fwd_softplus(const scan2d_desc* desc, const void* x, const
     return fwd_impl(desc, x, delta_raw, delta_bias, 1, A, Bm, Cm, Dskip, mask, y, workspace, workspace_bytes, stream);
 }
 
-extern "C" int scan2d_bwd(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
-                          const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
-                          const void* dy, void* dx, void* ddelta, float* dA, float* dBm, float* dCm,
-                          float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, bool softplus,
+             const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+             const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
+             float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_desc(desc);
     if (rc != SCAN2D_OK) return rc;
     if (!x || !delta || !A || !Bm || !Cm || !dy || !dx || !ddelta || !dA || !dBm || !dCm)
         return SCAN2D_ERR_NULL_POINTER;
     if ((Dskip == nullptr) != (dDskip == nullptr)) return SCAN2D_ERR_NULL_POINTER;
-    const void* ptrs[] = {x, delta, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, dA, dBm, dCm, dDskip, workspace};
+    if ((delta_bias == nullptr) != (ddelta_bias == nullptr)) return SCAN2D_ERR_NULL_POINTER;
+    const void* ptrs[] = {x, delta, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, dA, dBm, dCm, dDskip, workspace, delta_bias, ddelta_bias};
     for (const void* q : ptrs)
         if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
-    return bwd_launch(desc, x, delta, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, dA, dBm, dCm, dDskip,
-                      workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    return bwd_launch(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
+                      dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+}  // namespace
+
+extern "C" int scan2d_bwd(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
+                          const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                          const void* dy, void* dx, void* ddelta, float* dA, float* dBm, float* dCm,
+                          float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_impl(desc, x, delta, nullptr, false, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, nullptr, dA, dBm, dCm, dDskip,
+                    workspace, workspace_bytes, stream);
+}
+
+extern "C" int scan2d_bwd_softplus(const scan2d_desc* desc, const void* x, const void* delta_raw, const float* delta_bias,
+                                   const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                                   const void* dy, void* dx, void* ddelta_raw, float* ddelta_bias, float* dA, float* dBm,
+                                   float* dCm, float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_impl(desc, x, delta_raw, delta_bias, true, A, Bm, Cm, Dskip, mask, dy, dx, ddelta_raw, ddelta_bias, dA, dBm, dCm,
+                    dDskip, workspace, workspace_bytes, stream);
 }
 
 extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {

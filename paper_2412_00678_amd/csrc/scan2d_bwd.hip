@@ -44,18 +44,47 @@ __global__ void scan2d_bwd_reduce_batch_kernel(const float* __restrict__ pA, con
     }
 }
 
+// ddelta_bias: per map, the sum of the (already chain-ruled) ddelta_raw over positions, in a fixed
+// order (strided partial sums per thread, then a tree over the workgroup); summed over batch items
+// by scan2d_bwd_reduce_bias_batch_kernel.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_bwd_reduce_bias_kernel(const T* __restrict__ ddelta_raw, float* __restrict__ pbias, size_t HW) {
+    __shared__ float sh[256];
+    const T* src = ddelta_raw + (size_t)blockIdx.x * HW;
+    float acc = 0.0f;
+    for (size_t e = threadIdx.x; e < HW; e += 256) {
+        if constexpr (Elem<T>::kBytes == 4) acc += __uint_as_float(elem_bits(src + e));
+        else acc += __uint_as_float(elem_bits(src + e) << 16);
+    }
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) pbias[blockIdx.x] = sh[0];
+}
+__global__ void scan2d_bwd_reduce_bias_batch_kernel(const float* __restrict__ pbias, float* __restrict__ dbias, int Bt, int Dc) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < Dc) {
+        float acc = 0.0f;
+        for (int b = 0; b < Bt; ++b) acc += pbias[(size_t)b * Dc + c];
+        dbias[c] = acc;
+    }
+}
+
 struct BwdPlan {
     bool small = false;                                    // one wavefront per map, no bands (scan2d_bwd_small.hpp)
     int LG = 0, K = 0, NW = 0, waves = 0, RB = 0;
     int NG = 0, GS = 0, CG = 0, nb = 0;
     BwdKernels k;
     size_t lds_bytes = 0;
-    size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, total = 0;
+    size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, off_pb = 0, total = 0;   // pb: bias-gradient partials
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
-bool make_plan(const scan2d_desc* d, BwdPlan* out) {
+bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     BwdPlan pl;
     const int W = d->W, N = d->N;
     if (W <= 16 && d->H <= 16 && N <= 16 && !std::getenv("SCAN2D_BWD_VARIANT")) {
@@ -63,7 +92,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
         pl.small = true;
         pl.LG = 16; pl.K = 1; pl.NW = N <= 4 ? 1 : (N <= 8 ? 2 : 4); pl.waves = 4; pl.RB = d->H;
         pl.NG = 4; pl.GS = 1; pl.CG = d->Dc; pl.nb = 1; pl.lds_bytes = 0;
-        pl.k.main = d->dtype == SCAN2D_BF16 ? bwd_small_kernel_bf16(pl.NW) : bwd_small_kernel_f32(pl.NW);
+        pl.k.main = d->dtype == SCAN2D_BF16 ? bwd_small_kernel_bf16(pl.NW, sp) : bwd_small_kernel_f32(pl.NW, sp);
         if (pl.k.main == nullptr) return false;
         const size_t maps = (size_t)d->Bt * d->Dc;
         const size_t NHW = (size_t)N * d->H * W;
@@ -73,6 +102,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
         pl.off_pC = o; o += pl.CG > 1 ? align_up(maps * NHW * sizeof(float)) : 0;
         pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
         pl.off_pD = o; o += d->Bt > 1 ? align_up(maps * sizeof(float)) : 0;
+        pl.off_pb = o; o += align_up(maps * sizeof(float));
         pl.total = o;
         *out = pl;
         return true;
@@ -104,7 +134,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     const int slots = waves * 64 / LG;
     if ((N + NW - 1) / NW > slots) return false;
     const bool fast = (W % K) == 0;
-    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast) : bwd_kernels_f32(LG, K, NW, waves, fast);
+    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
     if (pl.k.main == nullptr) return false;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
     pl.NG = (N + NW - 1) / NW;
@@ -147,6 +177,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out) {
     pl.off_pC = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * NHW * sizeof(float)) : 0;
     pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
     pl.off_pD = o; o += d->Bt > 1 ? align_up(maps * sizeof(float)) : 0;
+    pl.off_pb = o; o += align_up(maps * sizeof(float));
     pl.total = o;
     *out = pl;
     return true;
@@ -172,17 +203,36 @@ bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
     return true;
 }
 
-int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const float* A, const void* Bm,
+namespace {
+// Sum of ddelta_raw over positions and batch items, per channel (softplus step only).
+void launch_bias_sums(const scan2d_desc* d, const BwdPlan& pl, const void* ddelta_raw, float* dbias, char* ws, hipStream_t stream) {
+    const long long maps = (long long)d->Bt * d->Dc;
+    const size_t HW = (size_t)d->H * d->W;
+    float* pb = d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pb) : dbias;
+    if (d->dtype == SCAN2D_BF16)
+        hipLaunchKernelGGL(scan2d_bwd_reduce_bias_kernel<bf16_t>, dim3((unsigned)maps), dim3(256), 0, stream,
+                           static_cast<const bf16_t*>(ddelta_raw), pb, HW);
+    else
+        hipLaunchKernelGGL(scan2d_bwd_reduce_bias_kernel<float>, dim3((unsigned)maps), dim3(256), 0, stream,
+                           static_cast<const float*>(ddelta_raw), pb, HW);
+    if (d->Bt > 1)
+        hipLaunchKernelGGL(scan2d_bwd_reduce_bias_batch_kernel, dim3((d->Dc + 255) / 256), dim3(256), 0, stream,
+                           pb, dbias, d->Bt, d->Dc);
+}
+}  // namespace
+
+int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const float* delta_bias, bool softplus,
+               const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
-               void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
+               void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
                size_t workspace_bytes, hipStream_t stream) {
     BwdPlan pl;
-    if (!make_plan(d, &pl)) return SCAN2D_ERR_BAD_SHAPE;
+    if (!make_plan(d, &pl, softplus)) return SCAN2D_ERR_BAD_SHAPE;
     if (pl.total > 0 && (workspace == nullptr || workspace_bytes < pl.total)) return SCAN2D_ERR_WORKSPACE_SMALL;
     char* ws = static_cast<char*>(workspace);
     BwdArgs a;
     a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.dy = dy;
-    a.dx = dx; a.ddelta = ddelta;
+    a.dx = dx; a.ddelta = ddelta; a.delta_bias = delta_bias;
     a.ck = reinterpret_cast<float*>(ws + pl.off_ck);
     a.pB = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pB) : dBm;   // one group: the partial is the result
     a.pC = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pC) : dCm;
@@ -209,6 +259,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
             hipLaunchKernelGGL(scan2d_bwd_reduce_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
                                a.pA, a.pD, dA, dDskip, d->Bt, d->Dc, d->N);
         }
+        if (softplus && ddelta_bias != nullptr) launch_bias_sums(d, pl, ddelta, ddelta_bias, ws, stream);
         return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
     }
     const int slots = pl.waves * 64 / pl.LG;
@@ -239,6 +290,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
         hipLaunchKernelGGL(scan2d_bwd_reduce_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
                            a.pA, a.pD, dA, dDskip, d->Bt, d->Dc, d->N);
     }
+    if (softplus && ddelta_bias != nullptr) launch_bias_sums(d, pl, ddelta, ddelta_bias, ws, stream);
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
 

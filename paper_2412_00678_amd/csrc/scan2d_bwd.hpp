@@ -12,9 +12,12 @@ size_t bwd_workspace_bytes(const scan2d_desc* d);
 // One line describing the backward plan; false when the shape has no plan.
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes);
 
-int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const float* A, const void* Bm,
+// softplus: `delta` is the raw projection, the step is softplus(delta + delta_bias[c]); ddelta is then the
+// gradient of the raw projection and ddelta_bias (null iff delta_bias is) that of the bias.
+int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const float* delta_bias, bool softplus,
+               const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
-               void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
+               void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
                size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace scan2d

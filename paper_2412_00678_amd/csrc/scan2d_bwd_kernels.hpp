@@ -19,6 +19,8 @@
 // FAST (W a multiple of K, rows 4-byte aligned): unguarded wide accesses; a lane past the last
 // column mirrors lane 0 with dy forced to 0, so nothing flows out of it into the reverse scans,
 // and it never stores.  Otherwise every element access is guarded and out-of-range cells read 0.
+// SP: `delta` holds the raw projection; the step is softplus(raw + delta_bias[c]) (Eq. 3) and ddelta
+// is the gradient with respect to the raw projection (a second set of instantiations).
 // PF: the inputs of the next row are requested before the current row is processed (costs one
 // more row of raw registers); without it the kernel relies on several waves per SIMD.
 #pragma once
@@ -31,6 +33,7 @@ namespace scan2d {
 struct BwdArgs {
     const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
     const float* Dskip; const uint8_t* mask; const void* dy;
+    const float* delta_bias;   // [Dc] or null; read by the SP instantiations only (delta then holds the raw projection)
     void* dx; void* ddelta;
     float* ck;           // [maps][nb][N][W]   column state entering each band (band 0 unused)
     float* pB; float* pC; // [Bt][CG][N][H][W] partial sums over the channels of one group
@@ -77,7 +80,7 @@ __device__ __forceinline__ void ld_mask(const uint8_t* __restrict__ rowp, int co
 }
 
 // ---------------------------------------------------------------------------- checkpoint sweep
-template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST>
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool SP = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdArgs p) {
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
@@ -107,6 +110,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 #pragma unroll
         for (int j = 0; j < K; ++j) h[s][j] = 0.0f;
     }
+    const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;   // SP: delta = softplus(raw + bias)
     uint32_t rx[XW], rd[XW], rm[K / 4], rB[NW][XW];
     ld_elems<T, K, FAST>(xm, col0, lcol, W, rx);
     ld_elems<T, K, FAST>(dm, col0, lcol, W, rd);
@@ -120,6 +124,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 #pragma unroll
         for (int j = 0; j < K; ++j) {
             dl[j] = get_elem<T, K>(rd, j);
+            if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
             const float xe = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
             dxe[j] = dl[j] * xe;
         }
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 //   gaL  [GS][T*NW*K]  a[i+1,j]*g[i+1,j] of every channel, kept between bands
 //   dAL  [GS][T*NW]    per-lane partial of dA
 //   dDL  [GS][T]       per-lane partial of dDskip (first lane group of a map only)
-template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool PF>
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool PF, bool SP = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdArgs p) {
     constexpr int THREADS = WAVES * 64;
     constexpr int SLOTS = THREADS / LG;
@@ -251,6 +256,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                 Ap[s] = An[s] * kLog2e;
             }
             const float dsk = (p.Dskip != nullptr && sg == 0) ? p.Dskip[c] : 0.0f;
+            const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;   // SP: delta = softplus(raw + bias)
 
             // ---- scans 1 and 2: rebuild h[i-1,j] and hhor[i,j-1] for the rows of the band
             float hprev[RB][NW][K], hhl[RB][NW][K];
@@ -289,6 +295,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
                             dl[j] = get_elem<T, K>(fd[r & 1], j);
+                            if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
                             const float xe = mask_bit<K>(fm[r & 1], j) ? 0.0f : get_elem<T, K>(fx[r & 1], j);
                             dxe[j] = dl[j] * xe;
                         }
@@ -356,6 +363,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                     for (int j = 0; j < K; ++j) {
                         dl[j] = get_elem<T, K>(bd[r & 1], j);
+                        if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
                         xe[j] = mask_bit<K>(bm[r & 1], j) ? 0.0f : get_elem<T, K>(bx[r & 1], j);
                         dxe[j] = dl[j] * xe[j];
                         dyv[j] = get_elem<T, K>(by[r & 1], j);
@@ -416,7 +424,14 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                         const float* base = part + (size_t)(step & 1) * 2 * THREADS * K + (size_t)(slot - sg) * PANEL;
                         for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
                             if (col < W) {
-                                store_elem(ddm + ro + col, sum_partials<PANEL>(base + col, NG));
+                                float dd = sum_partials<PANEL>(base + col, NG);
+                                if constexpr (SP) {                    // chain rule through the softplus
+                                    float traw;
+                                    if constexpr (Elem<T>::kBytes == 4) traw = __uint_as_float(elem_bits(dm + ro + col));
+                                    else traw = __uint_as_float(elem_bits(dm + ro + col) << 16);
+                                    dd *= logistic_f32(traw + dbias);
+                                }
+                                store_elem(ddm + ro + col, dd);
                                 store_elem(dxm + ro + col, sum_partials<PANEL>(base + THREADS * K + col, NG));
                             }
                         }

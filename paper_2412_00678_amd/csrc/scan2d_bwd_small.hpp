@@ -16,7 +16,7 @@
 
 namespace scan2d {
 
-template <typename T, int NW>
+template <typename T, int NW, bool SP = false>
 __global__ __launch_bounds__(256) void scan2d_bwd_small_kernel(const BwdArgs p) {
     constexpr int HM = 16;                                // most rows a map may have
     constexpr int PD = NW >= 4 ? 2 : 4;                   // rows of loads in flight
@@ -55,6 +55,7 @@ __global__ __launch_bounds__(256) void scan2d_bwd_small_kernel(const BwdArgs p) 
         Ap[s] = An[s] * kLog2e;
     }
     const float dsk = (g == 0 && p.Dskip != nullptr) ? p.Dskip[c] : 0.0f;
+    const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;   // SP: delta = softplus(raw + bias)
 
     // ---- scans 1 and 2, top to bottom: h[i-1,j] and hhor[i,j-1] of every row stay in registers
     float hprev[HM][NW], hhl[HM][NW];
@@ -78,7 +79,8 @@ __global__ __launch_bounds__(256) void scan2d_bwd_small_kernel(const BwdArgs p) 
         for (int i = 0; i < HM; ++i) {
             if (i < H) {                                  // uniform
                 const int slot = i % PD;               // a constant once the loop is unrolled
-                const float dl = raw_to_float(T{}, rd[slot]);
+                float dl = raw_to_float(T{}, rd[slot]);
+                if constexpr (SP) dl = softplus_f32(dl + dbias);
                 const float xe = rm[slot] != 0u ? 0.0f : raw_to_float(T{}, rx[slot]);
                 const float dxe = dl * xe;
                 float P[NW], Hh[NW], cin[NW], a[NW];
@@ -125,7 +127,8 @@ __global__ __launch_bounds__(256) void scan2d_bwd_small_kernel(const BwdArgs p) 
         const int i = H - 1 - k;
         if (i >= 0) {                                     // uniform
             const int slot = k % PD;                   // a constant once the loop is unrolled
-            const float dl = raw_to_float(T{}, rd[slot]);
+            const float traw = SP ? raw_to_float(T{}, rd[slot]) + dbias : raw_to_float(T{}, rd[slot]);
+            const float dl = SP ? softplus_f32(traw) : traw;
             const bool masked = rm[slot] != 0u;
             const float xe = masked ? 0.0f : raw_to_float(T{}, rx[slot]);
             const float dyv = in ? raw_to_float(T{}, ry[slot]) : 0.0f;   // nothing flows out of a lane past the map
@@ -184,7 +187,7 @@ __global__ __launch_bounds__(256) void scan2d_bwd_small_kernel(const BwdArgs p) 
             dxl += __shfl_xor(dxl, 16);
             dxl += __shfl_xor(dxl, 32);
             if (g == 0 && in) {
-                store_elem(ddm + (size_t)i * W + l, ddl);
+                store_elem(ddm + (size_t)i * W + l, SP ? ddl * logistic_f32(traw) : ddl);
                 store_elem(dxm + (size_t)i * W + l, masked ? 0.0f : dxl);
             }
         }

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libscan2d.so")
 F32, BF16 = 0, 1
 PASS_FWD, PASS_BWD = 0, 1
 
-EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_bwd", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
+EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_bwd", "scan2d_bwd_softplus", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
            "scan2d_version")
 
 
@@ -47,6 +47,8 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_fwd_softplus.restype = ctypes.c_int
     lib.scan2d_bwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 14 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_bwd.restype = ctypes.c_int
+    lib.scan2d_bwd_softplus.argtypes = [ctypes.POINTER(Desc)] + [vp] * 16 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_bwd_softplus.restype = ctypes.c_int
     lib.scan2d_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.c_int]
     lib.scan2d_workspace_bytes.restype = ctypes.c_size_t
     lib.scan2d_strerror.argtypes = [ctypes.c_int]
@@ -199,6 +201,38 @@ def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None):
     if rc != 0:
         raise Scan2dError(rc, "scan2d_bwd")
     return dx, ddelta, dA, dBm, dCm, dDskip
+
+
+def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, workspace=None):
+    """Gradients (dx, ddelta_raw, ddelta_bias, dA, dBm, dCm, dDskip) with the step computed in the kernels."""
+    desc = make_desc(x, A)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))
+    _check(delta_bias, "delta_bias", torch.float32, (Dc,), optional=True)
+    _check(dy, "dy", x.dtype, (Bt, Dc, H, W))
+    _check(A, "A", torch.float32, (Dc, N))
+    _check(Bm, "Bm", x.dtype, (Bt, N, H, W))
+    _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    dx = torch.empty_like(x)
+    draw = torch.empty_like(x)
+    dbias = None if delta_bias is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    dA = torch.empty((Dc, N), dtype=torch.float32, device=x.device)
+    dBm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dCm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dDskip = None if Dskip is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_BWD, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    rc = lib.scan2d_bwd_softplus(ctypes.byref(desc), _ptr(x), _ptr(delta_raw), _ptr(delta_bias), _ptr(A), _ptr(Bm),
+                                 _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(dy), _ptr(dx), _ptr(draw), _ptr(dbias),
+                                 _ptr(dA), _ptr(dBm), _ptr(dCm), _ptr(dDskip), _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_bwd_softplus")
+    return dx, draw, dbias, dA, dBm, dCm, dDskip
 
 
 def to_device(arrs: dict, dtype_code: int, device="cuda:0") -> dict:

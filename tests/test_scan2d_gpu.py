@@ -441,6 +441,49 @@ def test_forward_with_softplus_step_matches_oracle(s2d, shape, with_bias):
         assert rel_err(got, y2) <= 1e-5
 
 
+SOFTPLUS_BWD_SHAPES = [
+    (2, 5, 16, 14, 14, wl.F32, 0.2), (1, 6, 16, 21, 64, wl.F32, 0.3), (2, 3, 16, 9, 128, wl.BF16, 0.3),
+    (1, 9, 16, 13, 192, wl.F32, 0.3), (1, 3, 16, 6, 250, wl.F32, 0.0), (1, 2, 8, 5, 600, wl.F32, 0.3),
+    (3, 2, 40, 6, 30, wl.F32, 0.3), (1, 4, 5, 9, 13, wl.BF16, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape", SOFTPLUS_BWD_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+@pytest.mark.parametrize("with_bias", [True, False], ids=["bias", "nobias"])
+def test_backward_with_softplus_step_matches_oracle(s2d, shape, with_bias):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("spb", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True)
+    inp = _softplus_inputs(w, seed=10)
+    bias = inp["delta_bias"] if with_bias else None
+    print(f"softplus bwd case Bt={Bt} Dc={Dc} N={N} H={H} W={W} dtype={dtype} bias={with_bias}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    db = torch.from_numpy(bias).cuda() if with_bias else None
+    got = s2d.scan2d_bwd_softplus(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["dy"])
+    torch.cuda.synchronize()
+    ref = oracle.scan2d_bwd_softplus(inp["x"], inp["delta"], bias, inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"],
+                                     inp["mask"], inp["dy"], dtype=dtype)
+    names = ("dx", "ddelta_raw", "ddelta_bias", "dA", "dBm", "dCm", "dDskip")
+    for k, (name, g, r) in enumerate(zip(names, got, ref)):
+        if r is None:
+            assert g is None, name
+            continue
+        g = s2d.to_host(g)
+        gv = wl.to_float(g, dtype) if k < 2 else g.astype(np.float64)
+        rv = wl.to_float(r, dtype) if k < 2 else r.astype(np.float64)
+        assert np.isfinite(gv).all(), name
+        tol = TOL[dtype] if k < 2 else (1e-4 if dtype == wl.F32 else 2e-2)
+        assert rel_err(gv, rv) <= tol, f"{name}: rel err {rel_err(gv, rv):.3e}"
+    # every other gradient is that of the plain entry point on the step a library routine computes
+    if dtype == wl.F32:
+        t = inp["delta"].astype(np.float64) + (0.0 if bias is None else bias[None, :, None, None])
+        inp2 = dict(inp)
+        inp2["delta"] = np.logaddexp(0.0, t).astype(np.float32)
+        plain = run_bwd(s2d, inp2, dtype)
+        for k, j in ((0, 0), (3, 2), (4, 3), (5, 4), (6, 5)):
+            assert rel_err(s2d.to_host(got[k]).astype(np.float64), plain[j].astype(np.float64)) <= 2e-5, names[k]
+
+
 def test_forward_and_backward_replay_from_a_hip_graph(s2d):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so its calls can be captured; every replay must equal the eager result bit for
