@@ -111,45 +111,65 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
         for (int j = 0; j < K; ++j) h[s][j] = 0.0f;
     }
     const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;   // SP: delta = softplus(raw + bias)
-    uint32_t rx[XW], rd[XW], rm[K / 4], rB[NW][XW];
-    ld_elems<T, K, FAST>(xm, col0, lcol, W, rx);
-    ld_elems<T, K, FAST>(dm, col0, lcol, W, rd);
-    ld_mask<K, FAST>(mm, col0, lcol, W, rm);
+    // x, delta, mask (one HBM stream per channel) run PDX rows ahead in a ring of raw registers, Bm one
+    // row ahead; the row loop is written as trips of PDX rows without a test between them, so that
+    // the wait counts the compiler derives let all of them stay in flight.
+    constexpr int PDX = (2 * XW + K / 4 <= 28) ? 2 : 1;
+    constexpr int SC = NW >= 4 ? 4 : NW;                      // states scanned together
+    uint32_t rx[PDX][XW], rd[PDX][XW], rm[PDX][K / 4], rB[NW][XW];
+    const int last = H - 2;                                   // the last row's state is never needed
+#pragma unroll
+    for (int d = 0; d < PDX; ++d) {
+        const size_t ro = (size_t)min(d, H - 1) * W;
+        ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, rx[d]);
+        ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, rd[d]);
+        ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, rm[d]);
+    }
 #pragma unroll
     for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s], col0, lcol, W, rB[s]);
 
-    for (int i = 0; i + 1 < H; ++i) {                         // the last row's state is never needed
-        const size_t nxt = (size_t)(i + 1) * W;
+    auto do_row = [&](const int i, auto par) __attribute__((always_inline)) {
+        constexpr int XS = decltype(par)::value % PDX;
+        const size_t nxt_x = (size_t)min(i + PDX, H - 1) * W;   // a row past the end re-reads the last row
+        const size_t nxt_s = (size_t)min(i + 1, H - 1) * W;
         float dl[K], dxe[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) {
-            dl[j] = get_elem<T, K>(rd, j);
+            dl[j] = get_elem<T, K>(rd[XS], j);
             if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
-            const float xe = mask_bit<K>(rm, j) ? 0.0f : get_elem<T, K>(rx, j);
+            const float xe = mask_bit<K>(rm[XS], j) ? 0.0f : get_elem<T, K>(rx[XS], j);
             dxe[j] = dl[j] * xe;
         }
-        ld_elems<T, K, FAST>(xm + nxt, col0, lcol, W, rx);
-        ld_elems<T, K, FAST>(dm + nxt, col0, lcol, W, rd);
-        ld_mask<K, FAST>(mm ? mm + nxt : nullptr, col0, lcol, W, rm);
+        ld_elems<T, K, FAST>(xm + nxt_x, col0, lcol, W, rx[XS]);
+        ld_elems<T, K, FAST>(dm + nxt_x, col0, lcol, W, rd[XS]);
+        ld_mask<K, FAST>(mm ? mm + nxt_x : nullptr, col0, lcol, W, rm[XS]);
 #pragma unroll
-        for (int s = 0; s < NW; ++s) {
-            float a[K], hl[K], pl[K];
+        for (int s0 = 0; s0 < NW; s0 += SC) {
+            float a[SC][K], hl[SC][K], pl[SC][K], P[SC], Hh[SC], cin[SC];
 #pragma unroll
-            for (int j = 0; j < K; ++j) a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
-            hl[0] = dxe[0] * get_elem<T, K>(rB[s], 0);
-            pl[0] = a[0];
+            for (int t = 0; t < SC; ++t) {
+                const int s = s0 + t;
 #pragma unroll
-            for (int j = 1; j < K; ++j) {
-                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(rB[s], j));
-                pl[j] = pl[j - 1] * a[j];
+                for (int j = 0; j < K; ++j) a[t][j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
+                hl[t][0] = dxe[0] * get_elem<T, K>(rB[s], 0);
+                pl[t][0] = a[t][0];
+#pragma unroll
+                for (int j = 1; j < K; ++j) {
+                    hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dxe[j] * get_elem<T, K>(rB[s], j));
+                    pl[t][j] = pl[t][j - 1] * a[t][j];
+                }
+                ld_elems<T, K, FAST>(Bs[s] + nxt_s, col0, lcol, W, rB[s]);
+                P[t] = pl[t][K - 1];
+                Hh[t] = hl[t][K - 1];
             }
-            ld_elems<T, K, FAST>(Bs[s] + nxt, col0, lcol, W, rB[s]);
-            float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
-            group_scan<LG, 1>(P, Hh, cin);
+            group_scan<LG, SC>(P, Hh, cin);
 #pragma unroll
-            for (int j = 0; j < K; ++j) {
-                const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
-                fma_inplace(h[s][j], a[j], hh);
+            for (int t = 0; t < SC; ++t) {
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    const float hh = (j == K - 1) ? Hh[t] : fmaf(pl[t][j], cin[t], hl[t][j]);
+                    fma_inplace(h[s0 + t][j], a[t][j], hh);
+                }
             }
         }
         if ((i + 1) % RB == 0) {                              // h[i] enters band (i+1)/RB
@@ -168,7 +188,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
                 }
             }
         }
+    };
+    int i = 0;
+    for (; i + PDX - 1 <= last; i += PDX) {
+        do_row(i, std::integral_constant<int, 0>{});
+        if constexpr (PDX == 2) do_row(i + 1, std::integral_constant<int, 1>{});
     }
+    if constexpr (PDX == 2) { if (i <= last) do_row(i, std::integral_constant<int, 0>{}); }
 }
 
 // ---------------------------------------------------------------------------------- main sweep
