@@ -120,13 +120,13 @@ bool fill_small(const scan2d_desc* d, int KS, bool sp, FwdChoice* out) {
 }
 
 // VGPRs of the compiled forward variants by (K, NW) and storage type, as the compiler reports
-// them for this source (300 = more than 256, i.e. one wave per SIMD).  Only used to rank variants.
+// them for this source (VGPRs + AGPRs; more than 256 means one wave per SIMD).  Only used to rank variants.
 int fwd_regs(bool bf16, int K, int NW) {
     struct R { int K, NW, b, f; };
-    static const R t[] = {{4, 1, 82, 116},  {4, 2, 112, 120}, {4, 4, 153, 153}, {4, 8, 166, 213}, {4, 16, 238, 300},
-                          {8, 1, 127, 124}, {8, 2, 160, 157}, {8, 4, 233, 255}, {8, 8, 300, 300},
-                          {12, 1, 177, 181}, {12, 2, 227, 230}, {12, 4, 255, 300},
-                          {16, 1, 196, 168}, {16, 2, 238, 300}, {16, 4, 300, 300}};
+    static const R t[] = {{4, 1, 84, 116},   {4, 2, 116, 131},  {4, 4, 148, 172},  {4, 8, 168, 255}, {4, 16, 247, 336},
+                          {8, 1, 143, 127},  {8, 2, 163, 167},  {8, 4, 243, 258},  {8, 8, 318, 386},
+                          {12, 1, 157, 182}, {12, 2, 228, 253}, {12, 4, 256, 331},
+                          {16, 1, 201, 168}, {16, 2, 252, 265}, {16, 4, 338, 398}};
     for (const R& r : t)
         if (r.K == K && r.NW == NW) return bf16 ? r.b : r.f;
     return 300;
