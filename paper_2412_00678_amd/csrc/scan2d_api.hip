@@ -120,7 +120,8 @@ bool fill_small(const scan2d_desc* d, int KS, bool sp, FwdChoice* out) {
 }
 
 // VGPRs of the compiled forward variants by (K, NW) and storage type, as the compiler reports
-// them for this source (VGPRs + AGPRs; more than 256 means one wave per SIMD).  Only used to rank variants.
+// them for this source (VGPRs + AGPRs; more than 256 means one wave per SIMD).  Only used to rank variants;
+// `python -m paper_2412_00678_amd.fwd_regs_table` prints these rows for the current kernel source.
 int fwd_regs(bool bf16, int K, int NW) {
     struct R { int K, NW, b, f; };
     static const R t[] = {{4, 1, 84, 116},   {4, 2, 116, 131},  {4, 4, 148, 172},  {4, 8, 168, 255}, {4, 16, 247, 336},
