@@ -64,13 +64,14 @@ struct V4 { int LG, K, NW, waves; };
 const V4 kFwdVariants[] = {SCAN2D_FWD_VARIANTS(SCAN2D_X)};
 #undef SCAN2D_X
 
-FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp) {
-    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi, sp)
-                                : fwd_kernel_f32(LG, K, NW, waves, exact, fast, multi, sp);
+FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma) {
+    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi, sp, ma)
+                                : fwd_kernel_f32(LG, K, NW, waves, exact, fast, multi, sp, ma);
 }
 
 // rpb: rows between two barriers; 0 = decide here
-bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb, bool sp, FwdChoice* out) {
+// ma: the mask rows (if any) start on 4-byte boundaries
+bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb, bool sp, bool ma, FwdChoice* out) {
     const int slots = waves * 64 / LG;
     FwdChoice c;
     c.LG = LG; c.K = K; c.NW = NW; c.waves = waves;
@@ -80,11 +81,11 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb
     c.MPW = slots / c.NG;
     c.panels = (d->W + LG * K - 1) / (LG * K);
     c.multi = c.panels > 1;
-    c.fast = !c.multi && (d->W % K) == 0;
+    c.fast = !c.multi && (d->dtype == SCAN2D_F32 || (d->W % 2) == 0) && (ma || !sp);   // rows start on a 4-byte boundary
     // 32-bit lane offsets span up to `slots` maps and `slots + 1` batch items of states
     const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
     if (span >= 2147483648.0) return false;
-    c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi, sp);
+    c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi, sp, ma);
     if (c.kernel == nullptr) return false;
     // LDS for the partial sums: 2 buffers x RPB rows x (threads * K) floats.  Few large maps (one
     // workgroup per CU at most) can afford 64 KB; otherwise stay near 24 KB so that several
@@ -164,13 +165,13 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
 }
 
 // sp: pick the instantiation that computes the step itself; the choice of variant does not depend on it
-int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false) {
+int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = true) {
     if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES[,RPB]"
         int LG = 0, K = 0, NW = 0, waves = 4, rpb = 0;
         const int got = std::sscanf(env, "%d,%d,%d,%d,%d", &LG, &K, &NW, &waves, &rpb);
         if (got >= 2 && LG == 16 && (K == 1 || K == 2) && fill_small(d, K, sp, out)) return SCAN2D_OK;
         if (got >= 3 && (LG == 16 || LG == 32 || LG == 64) && NW >= 1 && (waves == 4 || waves == 8 || waves == 16) &&
-            fill_choice(d, LG, K, NW, waves, rpb, sp, out))
+            fill_choice(d, LG, K, NW, waves, rpb, sp, ma, out))
             return SCAN2D_OK;
     }
     // narrow maps: one column per lane up to 16 columns; two per lane up to 32 where the width rules out
@@ -181,7 +182,7 @@ int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false) {
     double best = 0.0;
     for (const V4& v : kFwdVariants) {
         FwdChoice c;
-        if (!fill_choice(d, v.LG, v.K, v.NW, v.waves, 0, sp, &c)) continue;
+        if (!fill_choice(d, v.LG, v.K, v.NW, v.waves, 0, sp, ma, &c)) continue;
         const double cost = fwd_cost(d, c);
         if (!found || cost < best) { best = cost; *out = c; found = true; }
     }
@@ -211,7 +212,7 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
     FwdChoice ch;
-    rc = choose_fwd(desc, &ch, softplus != 0);
+    rc = choose_fwd(desc, &ch, softplus != 0, mask == nullptr || (desc->W % 4) == 0);
     if (rc != SCAN2D_OK) return rc;
     const size_t need = fwd_workspace(desc, ch);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SCAN2D_ERR_WORKSPACE_SMALL;

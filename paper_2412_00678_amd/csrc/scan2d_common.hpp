@@ -63,9 +63,12 @@ __device__ __forceinline__ void store_words(uint32_t* __restrict__ p, const uint
 // Buffer addressing: a wave-uniform base in a resource descriptor (scalar registers), a 32-bit
 // byte offset per lane and a 32-bit uniform byte offset (the row), which the memory instruction
 // adds itself - no 64-bit vector address arithmetic per load.  Spans are below 2^31 bytes.
+// `bytes` is what remains of the tensor behind `base`: a load that reaches past it returns 0
+// instead of touching memory, so a lane may read its K elements across the end of the last row.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, size_t bytes) {
+    const int records = bytes > (size_t)0x7fffffff ? 0x7fffffff : (int)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, records, 0x00020000);
 }
 template <int WORDS>
 __device__ __forceinline__ void buffer_load_words(rsrc_t rs, uint32_t lane_bytes, uint32_t uniform_bytes, uint32_t* r) {
@@ -82,6 +85,20 @@ __device__ __forceinline__ void buffer_load_words(rsrc_t rs, uint32_t lane_bytes
     }
 #pragma unroll
     for (; w < WORDS; ++w) r[w] = __builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes + 4 * w, uniform_bytes, 0);
+}
+
+// K mask bytes from a byte offset that is not a multiple of 4 (rows of a width that is not): buffer
+// loads of dwords drop the low address bits, so read the K/4 + 1 aligned dwords around the bytes and
+// shift them into place (v_alignbyte_b32).
+template <int K>
+__device__ __forceinline__ void buffer_load_mask_unaligned(rsrc_t rs, uint32_t byte_off, uint32_t* m) {
+    constexpr int NWORD = K / 4;
+    const uint32_t base = byte_off & ~3u, sh = byte_off & 3u;
+    uint32_t w[NWORD + 1];
+#pragma unroll
+    for (int k = 0; k <= NWORD; ++k) w[k] = __builtin_amdgcn_raw_buffer_load_b32(rs, base + 4 * k, 0, 0);
+#pragma unroll
+    for (int k = 0; k < NWORD; ++k) m[k] = __builtin_amdgcn_alignbyte(w[k + 1], w[k], sh);
 }
 
 __device__ __forceinline__ uint32_t elem_bits(const float* p)  { return __float_as_uint(*p); }

@@ -61,9 +61,16 @@ struct FwdArgs {
     int RPB;             // rows between two workgroup barriers (1, 2 or 4); sizes the dynamic LDS
 };
 
-// FAST: W is a multiple of K and every row starts 4-byte aligned, so a lane is either fully
-// inside the map (one wide load per tensor) or fully outside (it then re-reads the columns of
-// lane 0 and its results are discarded).  Otherwise every element access is guarded.
+// FAST (single-panel maps, any W): every lane reads its K columns with one wide buffer load per tensor.
+// A lane that starts past the last column re-reads the columns of lane 0 and its results are
+// discarded.  A lane that straddles the end of the row reads on into the next row (or zeros past the
+// end of the tensor: the buffer descriptors carry the exact size): those cells sit to the right of
+// every real column, so what they hold reaches no output (the row recurrence only runs rightwards,
+// the column recurrence stays in its column), and they are never stored.  Rows must start on a 4-byte
+// boundary (buffer loads of dwords drop the low address bits): always for fp32, even W for bf16; the
+// mask rows start on such a boundary only when W is a multiple of 4 (MA); the instantiations with MA = false
+// read the aligned dwords around a lane's mask bytes and shift them into place.  Without FAST (maps wider than one
+// panel, bf16 rows of odd width) every element access is guarded.
 // MULTI: the map is wider than one panel (p.panels > 1); single-panel kernels carry no code
 // for the panel hand-over.
 // SP: the step is computed here, delta = softplus(raw + bias) (a second set of instantiations, so that
@@ -80,7 +87,7 @@ struct FwdArgs {
 #endif
 constexpr int kPrefetchBudgetX = SCAN2D_PREFETCH_BUDGET_X, kPrefetchBudgetS = SCAN2D_PREFETCH_BUDGET_S;
 
-template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI, bool SP = false>
+template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI, bool SP = false, bool MA = true>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p) {
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
@@ -120,7 +127,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
     const uint32_t xlane = (uint32_t)(map_local * HW);
     const uint32_t slane = (uint32_t)(((size_t)(b - b0) * N + n0) * HW);
     const uint32_t mlane = (uint32_t)((size_t)(b - b0) * HW);
-    const rsrc_t rsx = make_rsrc(xu), rsd = make_rsrc(du), rsB = make_rsrc(Bu), rsC = make_rsrc(Cu), rsm = make_rsrc(mu);
+    constexpr size_t EBY = (size_t)Elem<T>::kBytes;
+    const size_t left_maps = (size_t)(p.maps - map0) * HW, left_items = (size_t)(p.maps / p.Dc - b0) * HW;
+    const rsrc_t rsx = make_rsrc(xu, left_maps * EBY), rsd = make_rsrc(du, left_maps * EBY),
+                 rsB = make_rsrc(Bu, left_items * N * EBY), rsC = make_rsrc(Cu, left_items * N * EBY),
+                 rsm = make_rsrc(mu, left_items);
 
     float Ap[NW];
 #pragma unroll
@@ -164,7 +175,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
             else load_row<T, K>(base + uni_off + lane_off, col0, W, false, r);
         };
         auto ldm = [&](uint32_t uni_off, uint32_t* r) {
-            if constexpr (FAST) buffer_load_words<K / 4>(rsm, mlane + lcol, uni_off, r);
+            if constexpr (FAST) {
+                if constexpr (MA) buffer_load_words<K / 4>(rsm, mlane + lcol, uni_off, r);
+                else buffer_load_mask_unaligned<K>(rsm, mlane + lcol + uni_off, r);
+            }
             else load_mask<K>(mu + uni_off + mlane, col0, W, false, r);
         };
         // State s of this lane group: uniform offset s*HW when every group is full; otherwise a
@@ -264,7 +278,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
             if (!reduce) {
                 if (live) {
                     if constexpr (FAST) {
-                        if (inside) store_row<T, K>(yrow + xlane, col0, col0 + K, true, yacc);
+                        if (inside) store_row<T, K>(yrow + xlane, col0, W, true, yacc);   // wide unless it straddles the row end
                     } else {
                         store_row<T, K>(yrow + xlane, col0, W, false, yacc);
                     }

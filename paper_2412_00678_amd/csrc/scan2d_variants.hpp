@@ -43,8 +43,14 @@ using FwdKernel = void (*)(const FwdArgs);
 
 // Returns nullptr when the variant is not compiled.
 // sp: the instantiations that compute the step themselves (softplus of the raw projection).
-FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp);
-FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp);
+// ma: mask rows start on 4-byte boundaries (no mask, or W a multiple of 4); the instantiations for the
+//     other case exist for the unguarded variants without sp only.
+FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma);
+FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma);
+
+// Unguarded variants for mask rows that do not start on 4-byte boundaries.
+template <typename T>
+inline FwdKernel lookup_fwd_kernel_unaligned_mask(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
 
 // Narrow maps (W <= 32): KS columns per lane, NW = states per lane group of the wave's four.
 FwdKernel fwd_small_kernel_f32(int KS, int NW, bool sp);
@@ -80,6 +86,19 @@ inline FwdKernel lookup_fwd_kernel(int LG, int K, int NW, int waves, bool exact,
 #undef SCAN2D_X
     if (!exact && !fast && LG == 16 && K == 4 && NW == 4 && waves == 4)
         return multi ? scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, true, SP> : scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, false, SP>;
+    return nullptr;
+}
+
+template <typename T>
+inline FwdKernel lookup_fwd_kernel_unaligned_mask(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {
+#define SCAN2D_X(lg, k, nw, wv) \
+    if (exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, true, false, false, false>;
+    SCAN2D_FWD_VARIANTS(SCAN2D_X)
+#undef SCAN2D_X
+#define SCAN2D_X(lg, k, nw, wv) \
+    if (!exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, false, true, false, false, false>;
+    SCAN2D_FWD_RAGGED_VARIANTS(SCAN2D_X)
+#undef SCAN2D_X
     return nullptr;
 }
 

@@ -99,6 +99,15 @@ SHAPES = [
     (1, 3, 30, 6, 15, wl.F32, 0.2),        # eight states per lane, last group ragged
     (1, 2, 64, 5, 32, wl.F32, 0.2),        # sixteen states per lane, two columns
     (3, 1, 16, 14, 14, wl.F32, 0.0),       # a partly filled last workgroup
+    # widths that are not a multiple of the columns per lane: the last lane reads across the row end
+    (2, 5, 16, 19, 57, wl.F32, 0.3),       # mask rows off the 4-byte boundaries
+    (2, 5, 16, 19, 58, wl.BF16, 0.3),      # bf16, even width: rows on 4-byte boundaries, mask rows not
+    (1, 6, 16, 11, 201, wl.F32, 0.4),
+    (1, 6, 16, 11, 250, wl.BF16, 0.4),
+    (1, 3, 16, 9, 55, wl.BF16, 0.3),       # bf16, odd width: guarded accesses
+    (1, 4, 16, 13, 101, wl.F32, 0.0),      # no mask
+    (1, 2, 5, 7, 150, wl.F32, 0.3),        # ragged states and a ragged last lane
+    (1, 1, 16, 3, 255, wl.F32, 0.5),       # the last lane of the last row of the last map reads past the tensor
 ]
 
 
@@ -411,6 +420,7 @@ SOFTPLUS_SHAPES = [
     (1, 6, 16, 21, 64, wl.F32, 0.3), (2, 5, 16, 14, 14, wl.BF16, 0.2), (1, 3, 16, 9, 200, wl.BF16, 0.3),
     (1, 4, 5, 7, 45, wl.F32, 0.2), (1, 3, 16, 13, 192, wl.F32, 0.0), (1, 2, 8, 5, 600, wl.F32, 0.3),
     (1, 16, 16, 64, 256, wl.BF16, 0.5), (3, 2, 4, 6, 30, wl.F32, 0.3),
+    (1, 5, 16, 9, 57, wl.F32, 0.3), (1, 5, 16, 9, 58, wl.BF16, 0.3),   # widths off the lane and mask boundaries
 ]
 
 
