@@ -133,7 +133,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     else { waves = 16; NW = 4; }
     const int slots = waves * 64 / LG;
     if ((N + NW - 1) / NW > slots) return false;
-    const bool fast = (W % K) == 0;
+    const bool fast = (W % K) == 0;                          // otherwise: the instantiations that treat the row end
     pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
     if (pl.k.main == nullptr) return false;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;

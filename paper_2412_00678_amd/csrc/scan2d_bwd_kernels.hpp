@@ -16,9 +16,13 @@
 // Lane mapping is that of the forward kernel: a lane group of LG lanes owns LG*K columns, lane l
 // the columns [l*K, l*K+K) and NW states; NG = ceil(N/NW) lane groups share a map and meet in
 // LDS once per row for the sums over states (ddelta, dx).
-// FAST (W a multiple of K, rows 4-byte aligned): unguarded wide accesses; a lane past the last
-// column mirrors lane 0 with dy forced to 0, so nothing flows out of it into the reverse scans,
-// and it never stores.  Otherwise every element access is guarded and out-of-range cells read 0.
+// All accesses are unguarded and wide.  A lane past the last column mirrors lane 0 with dy
+// forced to 0, so nothing flows out of it into the reverse scans, and it never stores.
+// FAST = W is a multiple of K.  Without it the lane that holds the last column reads on into
+// the next row (only the last row of a map, after which the tensor may end, is read element by
+// element); its cells past the row end get dy = 0 and a zero column state, which makes every
+// gradient they could contribute exactly 0 whatever finite values they hold, and it stores
+// element by element.
 // SP: `delta` holds the raw projection; the step is softplus(raw + delta_bias[c]) (Eq. 3) and ddelta
 // is the gradient with respect to the raw projection (a second set of instantiations).
 // PF: the inputs of the next row are requested before the current row is processed (costs one
@@ -61,19 +65,22 @@ __device__ __forceinline__ void store_f32s(float* __restrict__ p, const float* v
     store_words<K>(reinterpret_cast<uint32_t*>(p), r);
 }
 
-// K elements of one row for this lane (see FAST above).
+// K elements of one row for this lane (see FAST above).  wide = the lane may read K elements
+// starting at its first column even if the row ends before the last of them: true for every row
+// but the last one of a map whose width is not a multiple of K (what follows a row in memory
+// is the next row of the same tensor, except after the very last row).
 template <typename T, int K, bool FAST>
-__device__ __forceinline__ void ld_elems(const T* __restrict__ rowp, int col0, uint32_t lcol, int W, uint32_t* r) {
-    if constexpr (FAST) load_words<words_of<T, K>()>(reinterpret_cast<const uint32_t*>(rowp + lcol), r);
+__device__ __forceinline__ void ld_elems(const T* __restrict__ rowp, int col0, uint32_t lcol, int W, bool wide, uint32_t* r) {
+    if (FAST || wide) load_words_any<words_of<T, K>()>(rowp + lcol, r);
     else load_row<T, K>(rowp, col0, W, false, r);
 }
 template <int K, bool FAST>
-__device__ __forceinline__ void ld_mask(const uint8_t* __restrict__ rowp, int col0, uint32_t lcol, int W, uint32_t* r) {
+__device__ __forceinline__ void ld_mask(const uint8_t* __restrict__ rowp, int col0, uint32_t lcol, int W, bool wide, uint32_t* r) {
     if (rowp == nullptr) {
 #pragma unroll
         for (int w = 0; w < K / 4; ++w) r[w] = 0u;
-    } else if constexpr (FAST) {
-        load_words<K / 4>(reinterpret_cast<const uint32_t*>(rowp + lcol), r);
+    } else if (FAST || wide) {
+        load_words_any<K / 4>(rowp + lcol, r);
     } else {
         load_mask<K>(rowp, col0, W, false, r);
     }
@@ -118,20 +125,23 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
     constexpr int SC = NW >= 4 ? 4 : NW;                      // states scanned together
     uint32_t rx[PDX][XW], rd[PDX][XW], rm[PDX][K / 4], rB[NW][XW];
     const int last = H - 2;                                   // the last row's state is never needed
+    const int wide_rows = H - 1;                              // without FAST: rows that may be read past their end
 #pragma unroll
     for (int d = 0; d < PDX; ++d) {
-        const size_t ro = (size_t)min(d, H - 1) * W;
-        ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, rx[d]);
-        ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, rd[d]);
-        ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, rm[d]);
+        const int row = min(d, H - 1);
+        const size_t ro = (size_t)row * W;
+        ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, row < wide_rows, rx[d]);
+        ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, row < wide_rows, rd[d]);
+        ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, row < wide_rows, rm[d]);
     }
 #pragma unroll
-    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s], col0, lcol, W, rB[s]);
+    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s], col0, lcol, W, 0 < wide_rows, rB[s]);
 
     auto do_row = [&](const int i, auto par) __attribute__((always_inline)) {
         constexpr int XS = decltype(par)::value % PDX;
-        const size_t nxt_x = (size_t)min(i + PDX, H - 1) * W;   // a row past the end re-reads the last row
-        const size_t nxt_s = (size_t)min(i + 1, H - 1) * W;
+        const int row_x = min(i + PDX, H - 1), row_s = min(i + 1, H - 1);   // a row past the end re-reads the last row
+        const size_t nxt_x = (size_t)row_x * W;
+        const size_t nxt_s = (size_t)row_s * W;
         float dl[K], dxe[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) {
@@ -140,9 +150,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
             const float xe = mask_bit<K>(rm[XS], j) ? 0.0f : get_elem<T, K>(rx[XS], j);
             dxe[j] = dl[j] * xe;
         }
-        ld_elems<T, K, FAST>(xm + nxt_x, col0, lcol, W, rx[XS]);
-        ld_elems<T, K, FAST>(dm + nxt_x, col0, lcol, W, rd[XS]);
-        ld_mask<K, FAST>(mm ? mm + nxt_x : nullptr, col0, lcol, W, rm[XS]);
+        ld_elems<T, K, FAST>(xm + nxt_x, col0, lcol, W, row_x < wide_rows, rx[XS]);
+        ld_elems<T, K, FAST>(dm + nxt_x, col0, lcol, W, row_x < wide_rows, rd[XS]);
+        ld_mask<K, FAST>(mm ? mm + nxt_x : nullptr, col0, lcol, W, row_x < wide_rows, rm[XS]);
 #pragma unroll
         for (int s0 = 0; s0 < NW; s0 += SC) {
             float a[SC][K], hl[SC][K], pl[SC][K], P[SC], Hh[SC], cin[SC];
@@ -158,7 +168,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
                     hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dxe[j] * get_elem<T, K>(rB[s], j));
                     pl[t][j] = pl[t][j - 1] * a[t][j];
                 }
-                ld_elems<T, K, FAST>(Bs[s] + nxt_s, col0, lcol, W, rB[s]);
+                ld_elems<T, K, FAST>(Bs[s] + nxt_s, col0, lcol, W, row_s < wide_rows, rB[s]);
                 P[t] = pl[t][K - 1];
                 Hh[t] = hl[t][K - 1];
             }
@@ -178,9 +188,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
             for (int s = 0; s < NW; ++s) {
                 if (s < nvalid) {
                     float* dst = p.ck + (((size_t)map * p.nb + band) * N + n0 + s) * W;
-                    if constexpr (FAST) {
-                        if (inside) store_f32s<K>(dst + col0, h[s]);
-                    } else {
+                    if (FAST ? inside : col0 + K <= W) {
+                        store_f32s<K>(dst + col0, h[s]);
+                    } else if (!FAST) {
 #pragma unroll
                         for (int j = 0; j < K; ++j)
                             if (col0 + j < W) dst[col0 + j] = h[s][j];
@@ -235,6 +245,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     const int col0 = l * K;
     const bool inside = col0 < W;
     const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
+    const int wide_rows = H - 1;                         // without FAST: rows that may be read past their end
+    const int nv = FAST ? (inside ? K : 0) : max(0, min(K, W - col0));   // cells of this lane inside the map
     const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
     const T* Bs[NW];
     const T* Cs[NW];
@@ -290,11 +302,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                 uint32_t fx[2][XW], fd[2][XW], fm[2][K / 4], fB[2][NW][XW];
                 auto issue = [&](int buf, int i) {
                     const size_t ro = (size_t)i * W;
-                    ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, fx[buf]);
-                    ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, fd[buf]);
-                    ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, fm[buf]);
+                    const bool wide = i < wide_rows;
+                    ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, wide, fx[buf]);
+                    ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, wide, fd[buf]);
+                    ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, wide, fm[buf]);
 #pragma unroll
-                    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, fB[buf][s]);
+                    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, wide, fB[buf][s]);
                 };
                 if constexpr (PF) issue(0, r0);
                 float hcur[NW][K];
@@ -304,11 +317,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                     if (band == 0) {
 #pragma unroll
                         for (int j = 0; j < K; ++j) hcur[s][j] = 0.0f;
-                    } else if constexpr (FAST) {
-                        load_f32s<K>(src + lcol, hcur[s]);
                     } else {
+                        load_f32s<K>(src + lcol, hcur[s]);               // past the row end: the next checkpoint row or the region behind
+                        if constexpr (!FAST) {
 #pragma unroll
-                        for (int j = 0; j < K; ++j) hcur[s][j] = (col0 + j < W) ? src[col0 + j] : 0.0f;
+                            for (int j = 0; j < K; ++j)
+                                if (j >= nv) hcur[s][j] = 0.0f;
+                        }
                     }
                 }
 #pragma unroll
@@ -364,14 +379,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             uint32_t bx[2][XW], bd[2][XW], by[2][XW], bm[2][K / 4], bB[2][NW][XW], bC[2][NW][XW];
             auto issue_r = [&](int buf, int i) {
                 const size_t ro = (size_t)i * W;
-                ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, bx[buf]);
-                ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, bd[buf]);
-                ld_elems<T, K, FAST>(dym + ro, col0, lcol, W, by[buf]);
-                ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, bm[buf]);
+                const bool wide = i < wide_rows;
+                ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, wide, bx[buf]);
+                ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, wide, bd[buf]);
+                ld_elems<T, K, FAST>(dym + ro, col0, lcol, W, wide, by[buf]);
+                ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, wide, bm[buf]);
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
-                    ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, bB[buf][s]);
-                    ld_elems<T, K, FAST>(Cs[s] + ro, col0, lcol, W, bC[buf][s]);
+                    ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, wide, bB[buf][s]);
+                    ld_elems<T, K, FAST>(Cs[s] + ro, col0, lcol, W, wide, bC[buf][s]);
                 }
             };
 #pragma unroll
@@ -393,7 +409,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                         xe[j] = mask_bit<K>(bm[r & 1], j) ? 0.0f : get_elem<T, K>(bx[r & 1], j);
                         dxe[j] = dl[j] * xe[j];
                         dyv[j] = get_elem<T, K>(by[r & 1], j);
-                        if (FAST && !inside) dyv[j] = 0.0f;               // nothing flows out of a lane past the map
+                        if (FAST ? !inside : j >= nv) dyv[j] = 0.0f;      // nothing flows out of a cell past the map
                         ddl[j] = 0.0f;
                         dxl[j] = dsk * dyv[j];
                         dDb = fmaf(dyv[j], xe[j], dDb);
@@ -469,7 +485,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             for (int s = 0; s < NW; ++s) {
 #pragma unroll
                 for (int j = 0; j < K; ++j) gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j] = ga[s][j];
-                dAL[((size_t)ch * THREADS + tid) * NW + s] += (FAST && !inside) ? 0.0f : dAb[s];
+                dAL[((size_t)ch * THREADS + tid) * NW + s] += inside ? dAb[s] : 0.0f;
             }
             dDL[(size_t)ch * THREADS + tid] += dDb;
         }
@@ -484,9 +500,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                     for (int s = 0; s < NW; ++s) {
                         if (s < nvalid) {
                             const size_t o = ((((size_t)b * p.CG + cg) * N + n0 + s) * H + i) * W;
-                            if constexpr (FAST) {
-                                if (inside) { store_f32s<K>(p.pB + o + col0, dBacc[r][s]); store_f32s<K>(p.pC + o + col0, dCacc[r][s]); }
-                            } else {
+                            if (nv == K) {
+                                store_f32s<K>(p.pB + o + col0, dBacc[r][s]);
+                                store_f32s<K>(p.pC + o + col0, dCacc[r][s]);
+                            } else if (!FAST) {
 #pragma unroll
                                 for (int j = 0; j < K; ++j)
                                     if (col0 + j < W) { p.pB[o + col0 + j] = dBacc[r][s][j]; p.pC[o + col0 + j] = dCacc[r][s][j]; }

@@ -43,6 +43,29 @@ __device__ __forceinline__ void load_words(const uint32_t* __restrict__ p, uint3
     for (; w < WORDS; ++w) r[w] = p[w];
 }
 
+// The same from any byte address (global memory only: flat and global loads of gfx950 accept
+// unaligned addresses, buffer loads do not).
+typedef u32x4_t u32x4_a1 __attribute__((aligned(1)));
+typedef u32x2_t u32x2_a1 __attribute__((aligned(1)));
+typedef uint32_t u32_a1 __attribute__((aligned(1)));
+template <int WORDS>
+__device__ __forceinline__ void load_words_any(const void* __restrict__ q, uint32_t* r) {
+    const unsigned char* p = static_cast<const unsigned char*>(q);
+    int w = 0;
+#pragma unroll
+    for (; w + 4 <= WORDS; w += 4) {
+        const u32x4_a1 v = *reinterpret_cast<const u32x4_a1*>(p + 4 * w);
+        r[w] = v.x; r[w + 1] = v.y; r[w + 2] = v.z; r[w + 3] = v.w;
+    }
+#pragma unroll
+    for (; w + 2 <= WORDS; w += 2) {
+        const u32x2_a1 v = *reinterpret_cast<const u32x2_a1*>(p + 4 * w);
+        r[w] = v.x; r[w + 1] = v.y;
+    }
+#pragma unroll
+    for (; w < WORDS; ++w) r[w] = *reinterpret_cast<const u32_a1*>(p + 4 * w);
+}
+
 template <int WORDS>
 __device__ __forceinline__ void store_words(uint32_t* __restrict__ p, const uint32_t* r) {
     int w = 0;

@@ -312,6 +312,13 @@ BWD_SHAPES = [
     (1, 2, 16, 17, 14, wl.F32, 0.3),       # one row too many for the small-map kernel
     (1, 2, 24, 14, 14, wl.F32, 0.3),       # too many states for it
     (1, 2, 64, 5, 256, wl.F32, 0.2),       # widest map with more than 16 states
+    # widths that are not a multiple of the columns per lane: the last lane reads into the next row
+    (2, 5, 16, 12, 57, wl.BF16, 0.3),      # rows on odd 2-byte boundaries
+    (1, 4, 16, 9, 191, wl.BF16, 0.3),
+    (1, 3, 16, 1, 190, wl.F32, 0.3),       # a single row: nothing may be read past its end
+    (1, 4, 16, 2, 61, wl.F32, 0.3),
+    (2, 3, 16, 33, 333, wl.F32, 0.3),
+    (1, 2, 32, 9, 250, wl.F32, 0.3),
 ]
 
 
@@ -327,8 +334,9 @@ def test_backward_variants(s2d, variant, W):
     check_bwd(s2d, wl.Workload("bvar", 2, 6, 16, 11, W, wl.F32, mask_frac=0.3, backward=True), seed=6, variant=variant)
 
 
-def test_backward_is_reproducible_and_ignores_garbage_under_the_mask(s2d):
-    w = wl.Workload("brep", 2, 12, 16, 20, 72, wl.F32, mask_frac=0.4, backward=True)
+@pytest.mark.parametrize("W", [72, 75, 190])
+def test_backward_is_reproducible_and_ignores_garbage_under_the_mask(s2d, W):
+    w = wl.Workload("brep", 2, 12, 16, 20, W, wl.F32, mask_frac=0.4, backward=True)
     inp = wl.make_inputs(w, seed=8)
     a = run_bwd(s2d, inp, wl.F32)
     b = run_bwd(s2d, inp, wl.F32)
