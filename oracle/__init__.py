@@ -179,3 +179,38 @@ def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, dt
     draw = dd / (1.0 + np.exp(-t))
     dbias = None if delta_bias is None else draw.sum(axis=(0, 2, 3)).astype(np.float32)
     return _narrow(dx, dtype), _narrow(draw, dtype), dbias, dA, dBm, dCm, dD
+
+
+# ------------------------------------------------------------------ output gate of the block
+# The 2DMamba block is the Mamba block with the scan swapped for the 2D one (Sec. 3.2, Fig. 2):
+# the scan's output is multiplied element-wise by SiLU(z) = z / (1 + exp(-z)) of the block's
+# gate branch z [Bt][Dc][H][W].  The gate acts on the unrounded scan output; the gated output
+# is rounded once to the storage type (the ungated output, which a backward pass needs for
+# dz, is rounded on its own).  d SiLU(z) / dz = s (1 + z (1 - s)) with s = 1 / (1 + exp(-z)).
+
+def _silu(z):
+    s = 1.0 / (1.0 + np.exp(-z))
+    return z * s, s * (1.0 + z * (1.0 - s))
+
+
+def scan2d_fwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, z, dtype=F32, threads=0):
+    """(y_scan, y): the scan output with the softplus step, and y = y_scan * SiLU(z)."""
+    _, delta = _step(delta_raw, delta_bias, dtype)
+    y = scan2d_fwd(_widen(x, dtype), delta, A, _widen(Bm, dtype), _widen(Cm, dtype), Dskip, mask,
+                   dtype=F64, threads=threads)
+    gate, _ = _silu(_widen(z, dtype))
+    return _narrow(y, dtype), _narrow(y * gate, dtype)
+
+
+def scan2d_bwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, z, dy, dtype=F32, threads=0):
+    """Gradients of sum(dy * y) for the gated output y:
+    (dx, ddelta_raw, ddelta_bias, dA, dBm, dCm, dDskip, dz)."""
+    t, delta = _step(delta_raw, delta_bias, dtype)
+    xw, Bw, Cw, zw, dyw = (_widen(a, dtype) for a in (x, Bm, Cm, z, dy))
+    y = scan2d_fwd(xw, delta, A, Bw, Cw, Dskip, mask, dtype=F64, threads=threads)
+    gate, dgate = _silu(zw)
+    dz = dyw * y * dgate
+    dx, dd, dA, dBm, dCm, dD = scan2d_bwd(xw, delta, A, Bw, Cw, Dskip, mask, dyw * gate, dtype=F64, threads=threads)
+    draw = dd / (1.0 + np.exp(-t))
+    dbias = None if delta_bias is None else draw.sum(axis=(0, 2, 3)).astype(np.float32)
+    return _narrow(dx, dtype), _narrow(draw, dtype), dbias, dA, dBm, dCm, dD, _narrow(dz, dtype)

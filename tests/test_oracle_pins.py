@@ -485,3 +485,81 @@ def test_softplus_low_precision_storage_rounds_once(dtype):
         np.testing.assert_array_equal(y, want)
     else:   # double -> fp32 -> bf16 may differ from the single rounding by one unit in rare ties
         assert np.abs(y.astype(np.int32) - want.astype(np.int32)).max() <= 1
+
+
+# ---------------------------------------------------------------------------- output gate (Fig. 2)
+
+def test_output_gate_is_silu_of_z_times_the_scan_output():
+    """y = y_scan * z / (1 + exp(-z)): against math.exp element by element, the values SiLU(1),
+    SiLU(-1) and SiLU(0) = 0, and the asymptote SiLU(z) -> z."""
+    import math
+    rng = np.random.default_rng(51)
+    Bt, Dc, N, H, W = 2, 2, 3, 3, 5
+    x, _, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    raw = rng.normal(-0.5, 1.0, x.shape)
+    z = rng.normal(0.0, 2.0, x.shape)
+    ys, y = oracle.scan2d_fwd_softplus_gated(x, raw, None, A, Bm, Cm, Dskip, mask, z, dtype=F64)
+    np.testing.assert_array_equal(ys, oracle.scan2d_fwd_softplus(x, raw, None, A, Bm, Cm, Dskip, mask, dtype=F64))
+    for idx in np.ndindex(z.shape):
+        assert abs(y[idx] - ys[idx] * z[idx] / (1.0 + math.exp(-z[idx]))) <= 1e-14 * max(1.0, abs(y[idx]))
+    one = np.ones(x.shape)
+    np.testing.assert_allclose(oracle.scan2d_fwd_softplus_gated(x, raw, None, A, Bm, Cm, Dskip, mask, one, dtype=F64)[1],
+                               ys * 0.7310585786300049, rtol=1e-14)
+    np.testing.assert_allclose(oracle.scan2d_fwd_softplus_gated(x, raw, None, A, Bm, Cm, Dskip, mask, -one, dtype=F64)[1],
+                               ys * -0.2689414213699951, rtol=1e-14)
+    assert not oracle.scan2d_fwd_softplus_gated(x, raw, None, A, Bm, Cm, Dskip, mask, 0 * one, dtype=F64)[1].any()
+    np.testing.assert_allclose(oracle.scan2d_fwd_softplus_gated(x, raw, None, A, Bm, Cm, Dskip, mask, 40 * one, dtype=F64)[1],
+                               ys * 40.0, rtol=1e-14)
+
+
+def test_gated_backward_matches_central_differences_in_every_input():
+    rng = np.random.default_rng(53)
+    Bt, Dc, N, H, W = 2, 2, 2, 3, 3
+    x, _, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    raw = rng.normal(-0.5, 1.0, x.shape)
+    bias = (np.round(rng.normal(0, 1, Dc) * 64) / 64).astype(np.float32)
+    z = rng.normal(0.0, 1.5, x.shape)
+    dy = rng.standard_normal(x.shape)
+    A64 = A.astype(np.float64)
+
+    def f(x_=x, raw_=raw, z_=z, Bm_=Bm, Cm_=Cm):
+        return float(np.sum(dy * oracle.scan2d_fwd_softplus_gated(x_, raw_, bias, A, Bm_, Cm_, Dskip, mask, z_, dtype=F64)[1]))
+
+    grads = oracle.scan2d_bwd_softplus_gated(x, raw, bias, A, Bm, Cm, Dskip, mask, z, dy, dtype=F64)
+    dx, draw, dbias, dA, dBm, dCm, dD, dz = grads
+    for name, arr, got in (("x_", x, dx), ("raw_", raw, draw), ("z_", z, dz), ("Bm_", Bm, dBm), ("Cm_", Cm, dCm)):
+        fd = np.zeros(arr.shape)
+        for idx in np.ndindex(arr.shape):
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += 1e-6
+            lo[idx] -= 1e-6
+            fd[idx] = (f(**{name: hi}) - f(**{name: lo})) / 2e-6
+        if name == "x_":
+            fd[np.broadcast_to(mask[:, None] != 0, fd.shape)] = 0.0     # x under the mask does not exist
+        np.testing.assert_allclose(got, fd, rtol=2e-7, atol=2e-7 * max(1e-30, np.abs(fd).max()), err_msg=name)
+    # the gate changes nothing but dy: every other gradient is the ungated backward fed dy * SiLU(z)
+    s = 1.0 / (1.0 + np.exp(-z))
+    plain = oracle.scan2d_bwd_softplus(x, raw, bias, A, Bm, Cm, Dskip, mask, dy * z * s, dtype=F64)
+    for a, b in zip(grads[:7], plain):
+        np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-15)
+    assert A64.shape == dA.shape
+
+
+@pytest.mark.parametrize("dtype", [oracle.F32, oracle.BF16])
+def test_gated_output_is_rounded_once_from_the_unrounded_scan(dtype):
+    rng = np.random.default_rng(57)
+    Bt, Dc, N, H, W = 1, 3, 4, 5, 6
+    x, _, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    raw = rng.normal(-1.0, 1.0, x.shape)
+    z = rng.normal(0.0, 1.5, x.shape)
+    st = lambda a: wl.f32_to_bf16_bits(a.astype(np.float32)) if dtype == oracle.BF16 else a.astype(np.float32)
+    xs, rs, Bs, Cs, zs = st(x), st(raw), st(Bm), st(Cm), st(z)
+    wide = lambda a: wl.to_float(a, dtype).astype(np.float64)
+    ys, y = oracle.scan2d_fwd_softplus_gated(xs, rs, None, A, Bs, Cs, Dskip, mask, zs, dtype=dtype)
+    ys64, y64 = oracle.scan2d_fwd_softplus_gated(wide(xs), wide(rs), None, A, wide(Bs), wide(Cs), Dskip, mask, wide(zs), dtype=F64)
+    for got, ref in ((ys, ys64), (y, y64)):
+        want = wl.f32_to_bf16_bits(ref.astype(np.float32)) if dtype == oracle.BF16 else ref.astype(np.float32)
+        if dtype == oracle.F32:
+            np.testing.assert_array_equal(got, want)
+        else:
+            assert np.abs(got.astype(np.int32) - want.astype(np.int32)).max() <= 1
