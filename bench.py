@@ -128,6 +128,45 @@ def bench_softplus(s2d, w, steps, warmup):
     return out
 
 
+def bench_gated(s2d, w, steps, warmup):
+    """scan2d_fwd_softplus_gated (training form: both outputs written; and scan2d_bwd_softplus_gated for the
+    training workload) on the workload's tensors plus a gate branch z."""
+    import torch
+    inp = wl.make_inputs(w, seed=0)
+    set_bytes = w.fwd_bytes() + (w.bwd_bytes() if w.backward else 0)
+    nsets = int(min(16, max(2, np.ceil(1.2e9 / set_bytes))))
+    sets = device_sets(s2d, inp, w.dtype, nsets, w.backward)
+    g = torch.Generator(device="cuda:0").manual_seed(7)
+    for s in sets:
+        s["z"] = (2.0 * torch.randn(s["x"].shape, device="cuda:0", generator=g)).to(s["x"].dtype)
+        s["y_scan"] = torch.empty_like(s["x"])
+    bias = torch.zeros(w.Dc, dtype=torch.float32, device="cuda:0")
+    desc = s2d.make_desc(sets[0]["x"], sets[0]["A"])
+    ws_f = torch.empty(max(s2d.workspace_bytes(desc, s2d.PASS_FWD), 16), dtype=torch.uint8, device="cuda:0")
+
+    def fwd(s):
+        s2d.scan2d_fwd_softplus_gated(s["x"], s["delta"], bias, s["A"], s["Bm"], s["Cm"], s["Dskip"], s["mask"], s["z"],
+                                      workspace=ws_f, y=s["y"], y_scan=s["y_scan"])
+
+    def fwd_infer(s):
+        s2d.scan2d_fwd_softplus_gated(s["x"], s["delta"], bias, s["A"], s["Bm"], s["Cm"], s["Dskip"], s["mask"], s["z"],
+                                      want_y_scan=False, workspace=ws_f, y=s["y"])
+
+    ms_f, _ = time_launches(fwd, sets, steps, warmup)
+    ms_i, _ = time_launches(fwd_infer, sets, steps, warmup)
+    out = {"fwd_ms": ms_f, "fwd_gunits_s": w.units / ms_f / 1e6, "fwd_without_y_scan_ms": ms_i}
+    if w.backward:
+        ws_b = torch.empty(max(s2d.workspace_bytes(desc, s2d.PASS_BWD_GATED), 16), dtype=torch.uint8, device="cuda:0")
+
+        def bwd(s):
+            s2d.scan2d_bwd_softplus_gated(s["x"], s["delta"], bias, s["A"], s["Bm"], s["Cm"], s["Dskip"], s["mask"], s["z"],
+                                          s["y_scan"], s["dy"], workspace=ws_b)
+
+        ms_b, _ = time_launches(bwd, sets, max(3, steps // 8), max(1, warmup // 8))
+        out.update({"bwd_ms": ms_b, "bwd_gunits_s": w.units / ms_b / 1e6})
+    return out
+
+
 def cpu_baseline(w, inp):
     """The oracle as it stands, all host cores, forward of the same workload repeated for ~10 s."""
     import oracle
@@ -154,6 +193,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="index into the five configurations (default: the 256x256 WSI grid)")
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under 'others')")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--gated", action="store_true",
+                    help="also time the block form: softplus step and output gate y * SiLU(z) in the kernels, reported under 'gated'")
     ap.add_argument("--softplus", action="store_true",
                     help="also time the entry points that compute the step themselves, delta = softplus(raw + bias) "
                          "(same tensors, delta read as the raw projection), reported under 'softplus'")
@@ -204,6 +245,8 @@ def main():
             r, _ = bench_workload(s2d, ow, max(20, args.steps // 3), max(5, args.warmup // 3), with_bwd=ow.backward)
             others.append(r)
         line["others"] = others
+    if args.gated:
+        line["gated"] = bench_gated(s2d, w, max(20, args.steps // 3), max(5, args.warmup // 3))
     if args.softplus:
         line["softplus"] = bench_softplus(s2d, w, max(20, args.steps // 3), max(5, args.warmup // 3))
     if args.paper_shapes:

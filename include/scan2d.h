@@ -64,7 +64,7 @@ enum {
 };
 
 enum { SCAN2D_F32 = 0, SCAN2D_BF16 = 1 };
-enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1 };
+enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2 };
 
 typedef struct {
     int32_t  Bt, Dc, H, W, N;  /* batch, channels, grid height, grid width, states: all >= 1, N <= 64 */
@@ -139,7 +139,45 @@ int scan2d_bwd_softplus(const scan2d_desc* desc,
                         float* dDskip,
                         void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD / _BWD).
+/*
+ * The scan as it sits in the block (Sec. 3.2 and Fig. 2: the Mamba block with its 1D scan replaced by the
+ * 2D one): the step is softplus(delta_raw + delta_bias[c]) as in scan2d_fwd_softplus, and the output is
+ * multiplied element by element by the SiLU of the block's gate branch z,
+ *     y[b,c,i,j] = y_scan[b,c,i,j] * z[b,c,i,j] / (1 + exp(-z[b,c,i,j])),
+ * by an element-wise kernel enqueued behind the scan on the same stream (y_scan is the stored scan output,
+ * already rounded to the storage type; the product is rounded once more).
+ *   z      : [Bt][Dc][H][W], dtype, device memory, read-only
+ *   y_scan : [Bt][Dc][H][W], dtype, device memory, written: the ungated scan output, which the backward
+ *            needs for dz; may be NULL (inference), then y holds it between the two kernels
+ *   y      : [Bt][Dc][H][W], dtype, device memory, written; must not overlap y_scan
+ * Everything else (layouts, mask, workspace, errors) as scan2d_fwd_softplus.
+ */
+int scan2d_fwd_softplus_gated(const scan2d_desc* desc,
+                              const void* x, const void* delta_raw, const float* delta_bias, const float* A,
+                              const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                              const void* z, void* y_scan, void* y,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of scan2d_fwd_softplus_gated for a given dy = dL/dy (y the gated output).  With s = 1/(1+exp(-z)):
+ *     dz[b,c,i,j] = dy * y_scan * s * (1 + z * (1 - s))
+ * and every other gradient is that of scan2d_bwd_softplus fed dy * z * s in place of dy.  One element-wise
+ * kernel writes dz and that product (rounded to the storage type) into the workspace, then the backward
+ * of the scan runs on it.
+ *   y_scan : as written by the forward (required)
+ *   dz     : [Bt][Dc][H][W], dtype, device memory, written
+ *   workspace : at least scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD_GATED) bytes
+ * Everything else as scan2d_bwd_softplus.
+ */
+int scan2d_bwd_softplus_gated(const scan2d_desc* desc,
+                              const void* x, const void* delta_raw, const float* delta_bias, const float* A,
+                              const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                              const void* z, const void* y_scan, const void* dy,
+                              void* dx, void* ddelta_raw, float* ddelta_bias, float* dA, float* dBm, float* dCm,
+                              float* dDskip, void* dz,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD / _BWD / _BWD_GATED).
  * Returns 0 for an invalid descriptor (the call itself then reports the error). */
 size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass);
 

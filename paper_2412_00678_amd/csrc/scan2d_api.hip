@@ -12,6 +12,7 @@
 
 #include "scan2d_variants.hpp"
 #include "scan2d_bwd.hpp"
+#include "scan2d_gate.hpp"
 
 namespace scan2d {
 namespace {
@@ -251,7 +252,8 @@ namespace {
 int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, bool softplus,
              const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
              const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
-             float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+             float* dDskip, void* workspace, size_t workspace_bytes, void* stream,
+             const void* z = nullptr, const void* y_scan = nullptr, void* dyg = nullptr, void* dz = nullptr) {
     int rc = check_desc(desc);
     if (rc != SCAN2D_OK) return rc;
     if (!x || !delta || !A || !Bm || !Cm || !dy || !dx || !ddelta || !dA || !dBm || !dCm)
@@ -263,6 +265,11 @@ int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
+    if (z != nullptr) {          // output gate: dz, and dy * SiLU(z) in place of dy
+        rc = gate_bwd_launch(desc, z, y_scan, dy, dyg, dz, static_cast<hipStream_t>(stream));
+        if (rc != SCAN2D_OK) return rc;
+        dy = dyg;
+    }
     return bwd_launch(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
                       dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
@@ -284,6 +291,38 @@ extern "C" int scan2d_bwd_softplus(const scan2d_desc* desc, const void* x, const
                     dDskip, workspace, workspace_bytes, stream);
 }
 
+// Gated forward: the scan writes its output to y_scan (to y when the caller does not want y_scan), then one
+// element-wise pass applies the gate.
+extern "C" int scan2d_fwd_softplus_gated(const scan2d_desc* desc, const void* x, const void* delta_raw, const float* delta_bias,
+                                         const float* A, const void* Bm, const void* Cm, const float* Dskip,
+                                         const uint8_t* mask, const void* z, void* y_scan, void* y, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+    if (!z || !y) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(z) || !aligned16(y_scan)) return SCAN2D_ERR_MISALIGNED;
+    void* ys = y_scan != nullptr ? y_scan : y;
+    const int rc = fwd_impl(desc, x, delta_raw, delta_bias, 1, A, Bm, Cm, Dskip, mask, ys, workspace, workspace_bytes, stream);
+    if (rc != SCAN2D_OK) return rc;
+    return gate_fwd_launch(desc, ys, z, y, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int scan2d_bwd_softplus_gated(const scan2d_desc* desc, const void* x, const void* delta_raw, const float* delta_bias,
+                                         const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                                         const void* z, const void* y_scan, const void* dy, void* dx, void* ddelta_raw,
+                                         float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* dz,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!z || !y_scan || !dy || !dz) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(z) || !aligned16(y_scan) || !aligned16(dy) || !aligned16(dz) || !aligned16(workspace)) return SCAN2D_ERR_MISALIGNED;
+    const size_t inner = bwd_workspace_bytes(desc);
+    if (inner == 0) return SCAN2D_ERR_BAD_SHAPE;
+    if (workspace == nullptr || workspace_bytes < inner + gate_bwd_bytes(desc)) return SCAN2D_ERR_WORKSPACE_SMALL;
+    // the gate only changes dy: dy * SiLU(z) goes behind the scan's own workspace, dz is final
+    void* dyg = static_cast<char*>(workspace) + inner;
+    return bwd_impl(desc, x, delta_raw, delta_bias, true, A, Bm, Cm, Dskip, mask, dy, dx, ddelta_raw, ddelta_bias, dA, dBm, dCm,
+                    dDskip, workspace, inner, stream, z, y_scan, dyg, dz);
+}
+
 extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
     if (check_desc(desc) != SCAN2D_OK) return 0;
     if (pass == SCAN2D_PASS_FWD) {
@@ -292,6 +331,10 @@ extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
         return fwd_workspace(desc, ch);
     }
     if (pass == SCAN2D_PASS_BWD) return bwd_workspace_bytes(desc);
+    if (pass == SCAN2D_PASS_BWD_GATED) {
+        const size_t inner = bwd_workspace_bytes(desc);
+        return inner == 0 ? 0 : inner + gate_bwd_bytes(desc);
+    }
     return 0;
 }
 

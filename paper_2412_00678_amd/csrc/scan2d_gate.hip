@@ -1,0 +1,113 @@
+// Element-wise kernels of the output gate (see scan2d_gate.hpp).
+#include "scan2d_gate.hpp"
+
+#include <algorithm>
+
+#include "scan2d_common.hpp"
+
+namespace scan2d {
+namespace {
+
+// y = y_scan * SiLU(z); four consecutive elements per thread and trip.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_gate_fwd_kernel(const T* __restrict__ ys, const T* __restrict__ z, T* __restrict__ y, size_t n) {
+    constexpr int XW = words_of<T, 4>();
+    const size_t quads = n / 4;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += (size_t)gridDim.x * blockDim.x) {
+        uint32_t rz[XW], ry[XW], o[XW];
+        load_words<XW>(reinterpret_cast<const uint32_t*>(z + 4 * q), rz);
+        load_words<XW>(reinterpret_cast<const uint32_t*>(ys + 4 * q), ry);
+#pragma unroll
+        for (int w = 0; w < XW; ++w) o[w] = 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float zv = get_elem<T, 4>(rz, j);
+            put_elem<T, 4>(o, j, to_elem_bits<T>(get_elem<T, 4>(ry, j) * (zv * logistic_f32(zv))));
+        }
+        store_words<XW>(reinterpret_cast<uint32_t*>(y + 4 * q), o);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - 4 * quads) {                 // the last n % 4 elements
+        const size_t e = 4 * quads + threadIdx.x;
+        float zv, yv;
+        if constexpr (Elem<T>::kBytes == 4) { zv = __uint_as_float(elem_bits(z + e)); yv = __uint_as_float(elem_bits(ys + e)); }
+        else { zv = __uint_as_float(elem_bits(z + e) << 16); yv = __uint_as_float(elem_bits(ys + e) << 16); }
+        store_elem(y + e, yv * (zv * logistic_f32(zv)));
+    }
+}
+
+// Output gate: dyg = dy * SiLU(z), dz = dy * y_scan * s (1 + z (1 - s)) with s = 1 / (1 + exp(-z));
+// four consecutive elements per thread and trip.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_gate_bwd_kernel(const T* __restrict__ z, const T* __restrict__ ys, const T* __restrict__ dy,
+                                                              T* __restrict__ dyg, T* __restrict__ dz, size_t n) {
+    constexpr int XW = words_of<T, 4>();
+    const size_t quads = n / 4;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += (size_t)gridDim.x * blockDim.x) {
+        uint32_t rz[XW], ry[XW], rd[XW], og[XW], oz[XW];
+        load_words<XW>(reinterpret_cast<const uint32_t*>(z + 4 * q), rz);
+        load_words<XW>(reinterpret_cast<const uint32_t*>(ys + 4 * q), ry);
+        load_words<XW>(reinterpret_cast<const uint32_t*>(dy + 4 * q), rd);
+#pragma unroll
+        for (int w = 0; w < XW; ++w) { og[w] = 0u; oz[w] = 0u; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float zv = get_elem<T, 4>(rz, j), yv = get_elem<T, 4>(ry, j), dv = get_elem<T, 4>(rd, j);
+            const float s = logistic_f32(zv);
+            put_elem<T, 4>(og, j, to_elem_bits<T>(dv * (zv * s)));
+            put_elem<T, 4>(oz, j, to_elem_bits<T>(dv * yv * (s * fmaf(zv, 1.0f - s, 1.0f))));
+        }
+        store_words<XW>(reinterpret_cast<uint32_t*>(dyg + 4 * q), og);
+        store_words<XW>(reinterpret_cast<uint32_t*>(dz + 4 * q), oz);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - 4 * quads) {                 // the last n % 4 elements
+        const size_t e = 4 * quads + threadIdx.x;
+        float zv, yv, dv;
+        if constexpr (Elem<T>::kBytes == 4) {
+            zv = __uint_as_float(elem_bits(z + e)); yv = __uint_as_float(elem_bits(ys + e)); dv = __uint_as_float(elem_bits(dy + e));
+        } else {
+            zv = __uint_as_float(elem_bits(z + e) << 16); yv = __uint_as_float(elem_bits(ys + e) << 16); dv = __uint_as_float(elem_bits(dy + e) << 16);
+        }
+        const float s = logistic_f32(zv);
+        store_elem(dyg + e, dv * (zv * s));
+        store_elem(dz + e, dv * yv * (s * fmaf(zv, 1.0f - s, 1.0f)));
+    }
+}
+
+
+unsigned gate_blocks(size_t n) { return (unsigned)std::min<size_t>((n / 4 + 255) / 256 + 1, 256 * 16); }
+
+}  // namespace
+
+int gate_fwd_launch(const scan2d_desc* d, const void* y_scan, const void* z, void* y, hipStream_t stream) {
+    const size_t n = (size_t)d->Bt * d->Dc * d->H * d->W;
+    (void)hipGetLastError();
+    if (d->dtype == SCAN2D_BF16)
+        hipLaunchKernelGGL(scan2d_gate_fwd_kernel<bf16_t>, dim3(gate_blocks(n)), dim3(256), 0, stream,
+                           static_cast<const bf16_t*>(y_scan), static_cast<const bf16_t*>(z), static_cast<bf16_t*>(y), n);
+    else
+        hipLaunchKernelGGL(scan2d_gate_fwd_kernel<float>, dim3(gate_blocks(n)), dim3(256), 0, stream,
+                           static_cast<const float*>(y_scan), static_cast<const float*>(z), static_cast<float*>(y), n);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+size_t gate_bwd_bytes(const scan2d_desc* d) {
+    const size_t bytes = (size_t)d->Bt * d->Dc * d->H * d->W * (d->dtype == SCAN2D_BF16 ? 2 : 4);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int gate_bwd_launch(const scan2d_desc* d, const void* z, const void* y_scan, const void* dy, void* dyg, void* dz,
+                    hipStream_t stream) {
+    const size_t n = (size_t)d->Bt * d->Dc * d->H * d->W;
+    (void)hipGetLastError();
+    if (d->dtype == SCAN2D_BF16)
+        hipLaunchKernelGGL(scan2d_gate_bwd_kernel<bf16_t>, dim3(gate_blocks(n)), dim3(256), 0, stream, static_cast<const bf16_t*>(z),
+                           static_cast<const bf16_t*>(y_scan), static_cast<const bf16_t*>(dy), static_cast<bf16_t*>(dyg),
+                           static_cast<bf16_t*>(dz), n);
+    else
+        hipLaunchKernelGGL(scan2d_gate_bwd_kernel<float>, dim3(gate_blocks(n)), dim3(256), 0, stream, static_cast<const float*>(z),
+                           static_cast<const float*>(y_scan), static_cast<const float*>(dy), static_cast<float*>(dyg),
+                           static_cast<float*>(dz), n);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+}  // namespace scan2d

@@ -1,0 +1,25 @@
+// Output gate of the block, y = y_scan * SiLU(z) (2DMamba Sec. 3.2 / Fig. 2: the Mamba block with
+// its scan replaced by the 2D one): two element-wise kernels beside the scan kernels.
+//
+// The gate is not applied inside the scan kernels.  That form was built and measured: the scan
+// kernels are bound by vector issue rate and registers, not by HBM, and the extra ring of raw
+// registers for z cost them a wave of occupancy or more than the extra pass over y costs here,
+// where it runs at the HBM copy rate.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "../../include/scan2d.h"
+
+namespace scan2d {
+
+// y = y_scan * z / (1 + exp(-z)); y may alias y_scan (in place).  [Bt][Dc][H][W], storage type.
+int gate_fwd_launch(const scan2d_desc* d, const void* y_scan, const void* z, void* y, hipStream_t stream);
+
+// The backward of the gated operator is the ungated one fed dy * SiLU(z).  One pass writes that product
+// (storage type) to `dyg` and the final dz = dy * y_scan * s (1 + z (1 - s)), s = 1 / (1 + exp(-z)).
+size_t gate_bwd_bytes(const scan2d_desc* d);     // bytes of `dyg`, a multiple of 256
+int gate_bwd_launch(const scan2d_desc* d, const void* z, const void* y_scan, const void* dy, void* dyg, void* dz,
+                    hipStream_t stream);
+
+}  // namespace scan2d

@@ -16,9 +16,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libscan2d.so")
 
 F32, BF16 = 0, 1
-PASS_FWD, PASS_BWD = 0, 1
+PASS_FWD, PASS_BWD, PASS_BWD_GATED = 0, 1, 2
 
-EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_bwd", "scan2d_bwd_softplus", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
+EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
+           "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
            "scan2d_version")
 
 
@@ -49,6 +50,10 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_bwd.restype = ctypes.c_int
     lib.scan2d_bwd_softplus.argtypes = [ctypes.POINTER(Desc)] + [vp] * 16 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_bwd_softplus.restype = ctypes.c_int
+    lib.scan2d_fwd_softplus_gated.argtypes = [ctypes.POINTER(Desc)] + [vp] * 11 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_fwd_softplus_gated.restype = ctypes.c_int
+    lib.scan2d_bwd_softplus_gated.argtypes = [ctypes.POINTER(Desc)] + [vp] * 19 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_bwd_softplus_gated.restype = ctypes.c_int
     lib.scan2d_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.c_int]
     lib.scan2d_workspace_bytes.restype = ctypes.c_size_t
     lib.scan2d_strerror.argtypes = [ctypes.c_int]
@@ -233,6 +238,78 @@ def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, wo
     if rc != 0:
         raise Scan2dError(rc, "scan2d_bwd_softplus")
     return dx, draw, dbias, dA, dBm, dCm, dDskip
+
+
+def scan2d_fwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, z, want_y_scan=True, workspace=None,
+                              y=None, y_scan=None):
+    """(y_scan or None, y) with y = y_scan * SiLU(z), step and gate computed in the kernel."""
+    desc = make_desc(x, A)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))
+    _check(delta_bias, "delta_bias", torch.float32, (Dc,), optional=True)
+    _check(z, "z", x.dtype, (Bt, Dc, H, W))
+    _check(A, "A", torch.float32, (Dc, N))
+    _check(Bm, "Bm", x.dtype, (Bt, N, H, W))
+    _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    if y is None:
+        y = torch.empty_like(x)
+    else:
+        _check(y, "y", x.dtype, (Bt, Dc, H, W))
+    if not want_y_scan:
+        y_scan = None
+    elif y_scan is None:
+        y_scan = torch.empty_like(x)
+    else:
+        _check(y_scan, "y_scan", x.dtype, (Bt, Dc, H, W))
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_FWD, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    rc = lib.scan2d_fwd_softplus_gated(ctypes.byref(desc), _ptr(x), _ptr(delta_raw), _ptr(delta_bias), _ptr(A), _ptr(Bm),
+                                       _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(z), _ptr(y_scan), _ptr(y),
+                                       _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_fwd_softplus_gated")
+    return y_scan, y
+
+
+def scan2d_bwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, z, y_scan, dy, workspace=None):
+    """Gradients (dx, ddelta_raw, ddelta_bias, dA, dBm, dCm, dDskip, dz) of the gated operator."""
+    desc = make_desc(x, A)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))
+    _check(delta_bias, "delta_bias", torch.float32, (Dc,), optional=True)
+    _check(z, "z", x.dtype, (Bt, Dc, H, W))
+    _check(y_scan, "y_scan", x.dtype, (Bt, Dc, H, W))
+    _check(dy, "dy", x.dtype, (Bt, Dc, H, W))
+    _check(A, "A", torch.float32, (Dc, N))
+    _check(Bm, "Bm", x.dtype, (Bt, N, H, W))
+    _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    dx = torch.empty_like(x)
+    draw = torch.empty_like(x)
+    dz = torch.empty_like(x)
+    dbias = None if delta_bias is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    dA = torch.empty((Dc, N), dtype=torch.float32, device=x.device)
+    dBm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dCm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dDskip = None if Dskip is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_BWD_GATED, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    rc = lib.scan2d_bwd_softplus_gated(ctypes.byref(desc), _ptr(x), _ptr(delta_raw), _ptr(delta_bias), _ptr(A), _ptr(Bm),
+                                       _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(z), _ptr(y_scan), _ptr(dy), _ptr(dx),
+                                       _ptr(draw), _ptr(dbias), _ptr(dA), _ptr(dBm), _ptr(dCm), _ptr(dDskip), _ptr(dz),
+                                       _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_bwd_softplus_gated")
+    return dx, draw, dbias, dA, dBm, dCm, dDskip, dz
 
 
 def to_device(arrs: dict, dtype_code: int, device="cuda:0") -> dict:

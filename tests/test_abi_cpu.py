@@ -27,7 +27,8 @@ def declared_functions():
 
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted(
-        ["scan2d_fwd", "scan2d_fwd_softplus", "scan2d_bwd", "scan2d_bwd_softplus", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
+        ["scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
+         "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
          "scan2d_version"])
 
 
@@ -78,6 +79,11 @@ def test_workspace_query(lib):
     assert lib.workspace_bytes(wide, lib.PASS_FWD) == 1 * 2 * 4 * 8 * 4
     assert lib.workspace_bytes(lib.Desc(0, 1, 1, 1, 1, 0, 0), lib.PASS_FWD) == 0
     assert lib.workspace_bytes(small, 5) == 0
+    # the gated backward adds one map-sized buffer (dy * SiLU(z), storage type), rounded up to 256 bytes
+    for dt, eb in ((0, 4), (1, 2)):
+        d = lib.Desc(2, 8, 20, 40, 16, dt, 0)
+        assert lib.workspace_bytes(d, lib.PASS_BWD_GATED) == lib.workspace_bytes(d, lib.PASS_BWD) + ((2 * 8 * 20 * 40 * eb + 255) // 256) * 256
+    assert lib.workspace_bytes(lib.Desc(1, 2, 8, 3000, 4, 0, 0), lib.PASS_BWD_GATED) == 0      # no backward plan for this width
 
 
 # ------------------------------------------------------------------ host logic: variant choice and launch plans

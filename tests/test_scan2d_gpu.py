@@ -502,6 +502,114 @@ def test_backward_with_softplus_step_matches_oracle(s2d, shape, with_bias):
             assert rel_err(s2d.to_host(got[k]).astype(np.float64), plain[j].astype(np.float64)) <= 2e-5, names[k]
 
 
+# ------------------------------------------------------------------ output gate of the block
+
+def _gated_inputs(w, seed):
+    """The softplus inputs plus a gate branch z spread over both tails of SiLU."""
+    inp = _softplus_inputs(w, seed)
+    r = np.random.default_rng(700 + seed)
+    z = r.normal(0.0, 2.0, (w.Bt, w.Dc, w.H, w.W))
+    z.reshape(-1)[3:: 89] = 25.0                       # SiLU(z) = z
+    z.reshape(-1)[7:: 103] = -30.0                     # SiLU(z) = z exp(z)
+    z.reshape(-1)[11:: 107] = 0.0
+    z = z.astype(np.float32)
+    inp["z"] = wl.f32_to_bf16_bits(z) if w.dtype == wl.BF16 else z
+    return inp
+
+
+GATED_SHAPES = [
+    (1, 6, 16, 21, 64, wl.F32, 0.3),       # one lane group per state, 16-lane groups
+    (2, 5, 16, 14, 14, wl.BF16, 0.2),      # narrow-map kernel
+    (1, 3, 16, 9, 200, wl.BF16, 0.3),      # wave-wide lane groups
+    (1, 4, 5, 7, 45, wl.F32, 0.2),         # ragged last lane group, mask rows off 4-byte boundaries
+    (1, 3, 16, 13, 192, wl.F32, 0.0),
+    (1, 2, 8, 5, 600, wl.F32, 0.3),        # wider than one panel
+    (1, 16, 16, 64, 256, wl.BF16, 0.5),    # one map per workgroup, 4 rows per barrier
+    (3, 2, 4, 6, 30, wl.F32, 0.3),
+    (2, 3, 64, 11, 40, wl.F32, 0.3),       # all states in one lane: the lane that owns the columns applies the gate
+    (1, 3, 64, 7, 57, wl.BF16, 0.3),
+    (1, 2, 2, 10, 100, wl.F32, 0.3),       # fewer lane groups than columns per lane: several columns per summing thread
+    (1, 5, 16, 9, 58, wl.BF16, 0.3),
+    (4, 3, 16, 23, 28, wl.F32, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape", GATED_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_gated_forward_matches_oracle(s2d, shape):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("gate", Bt, Dc, N, H, W, dtype, mask_frac=mf)
+    inp = _gated_inputs(w, seed=13)
+    print(f"gated fwd case Bt={Bt} Dc={Dc} N={N} H={H} W={W} dtype={dtype}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    db = torch.from_numpy(inp["delta_bias"]).cuda()
+    ys, y = s2d.scan2d_fwd_softplus_gated(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["z"])
+    _, y_only = s2d.scan2d_fwd_softplus_gated(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["z"],
+                                              want_y_scan=False)
+    plain = s2d.scan2d_fwd_softplus(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
+    torch.cuda.synchronize()
+    rys, ry = oracle.scan2d_fwd_softplus_gated(inp["x"], inp["delta"], inp["delta_bias"], inp["A"], inp["Bm"], inp["Cm"],
+                                               inp["Dskip"], inp["mask"], inp["z"], dtype=dtype)
+    gy, gys = wl.to_float(s2d.to_host(y), dtype), wl.to_float(s2d.to_host(ys), dtype)
+    assert np.isfinite(gy).all() and np.isfinite(gys).all()
+    assert rel_err(gys, wl.to_float(rys, dtype)) <= TOL[dtype]
+    assert rel_err(gy, wl.to_float(ry, dtype)) <= TOL[dtype]
+    # the ungated output is bit for bit that of the ungated entry point; leaving it out changes nothing
+    assert np.array_equal(s2d.to_host(ys), s2d.to_host(plain))
+    assert np.array_equal(s2d.to_host(y), s2d.to_host(y_only))
+    # z = 0 closes the gate exactly
+    zero = torch.zeros_like(d["z"])
+    _, y0 = s2d.scan2d_fwd_softplus_gated(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], zero)
+    assert not wl.to_float(s2d.to_host(y0), dtype).any()
+
+
+GATED_BWD_SHAPES = [
+    (2, 5, 16, 14, 14, wl.F32, 0.2), (1, 6, 16, 21, 64, wl.F32, 0.3), (2, 3, 16, 9, 128, wl.BF16, 0.3),
+    (1, 9, 16, 13, 190, wl.F32, 0.3), (1, 3, 16, 6, 251, wl.F32, 0.0), (3, 2, 40, 6, 30, wl.F32, 0.3),
+    (1, 4, 5, 9, 13, wl.BF16, 0.3), (1, 1, 16, 3, 5, wl.F32, 0.0),
+]
+
+
+@pytest.mark.parametrize("shape", GATED_BWD_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_gated_backward_matches_oracle(s2d, shape):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("gateb", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True)
+    inp = _gated_inputs(w, seed=14)
+    print(f"gated bwd case Bt={Bt} Dc={Dc} N={N} H={H} W={W} dtype={dtype}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    db = torch.from_numpy(inp["delta_bias"]).cuda()
+    ys, _ = s2d.scan2d_fwd_softplus_gated(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["z"])
+    got = s2d.scan2d_bwd_softplus_gated(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["z"], ys, d["dy"])
+    torch.cuda.synchronize()
+    ref = oracle.scan2d_bwd_softplus_gated(inp["x"], inp["delta"], inp["delta_bias"], inp["A"], inp["Bm"], inp["Cm"],
+                                           inp["Dskip"], inp["mask"], inp["z"], inp["dy"], dtype=dtype)
+    names = ("dx", "ddelta_raw", "ddelta_bias", "dA", "dBm", "dCm", "dDskip", "dz")
+    for k, (name, g, r) in enumerate(zip(names, got, ref)):
+        g = s2d.to_host(g)
+        stored = k < 2 or k == 7
+        gv = wl.to_float(g, dtype) if stored else g.astype(np.float64)
+        rv = wl.to_float(r, dtype) if stored else r.astype(np.float64)
+        assert np.isfinite(gv).all(), name
+        tol = TOL[dtype] if stored else (1e-4 if dtype == wl.F32 else 2e-2)
+        assert rel_err(gv, rv) <= tol, f"{name}: rel err {rel_err(gv, rv):.3e}"
+
+
+def test_gated_backward_reports_a_short_workspace(s2d):
+    import torch
+    w = wl.Workload("gatews", 1, 4, 16, 20, 40, wl.F32, mask_frac=0.2, backward=True)
+    inp = _gated_inputs(w, seed=15)
+    d = s2d.to_device(inp, wl.F32)
+    desc = s2d.make_desc(d["x"], d["A"])
+    plain, gated = s2d.workspace_bytes(desc, s2d.PASS_BWD), s2d.workspace_bytes(desc, s2d.PASS_BWD_GATED)
+    assert gated >= plain + d["x"].numel() * 4
+    ws = torch.empty(plain, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.scan2d_bwd_softplus_gated(d["x"], d["delta"], None, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["z"],
+                                      d["x"], d["dy"], workspace=ws)
+    assert e.value.code == -5
+
+
 def test_forward_and_backward_replay_from_a_hip_graph(s2d):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so its calls can be captured; every replay must equal the eager result bit for
