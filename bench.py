@@ -118,7 +118,7 @@ def bench_softplus(s2d, w, steps, warmup):
     ms_f, _ = time_launches(fwd, sets, steps, warmup)
     out = {"fwd_ms": ms_f, "fwd_gunits_s": w.units / ms_f / 1e6}
     if w.backward:
-        ws_b = torch.empty(max(s2d.workspace_bytes(desc, s2d.PASS_BWD), 16), dtype=torch.uint8, device="cuda:0")
+        ws_b = torch.empty(max(s2d.workspace_bytes(desc, s2d.PASS_BWD_SOFTPLUS), 16), dtype=torch.uint8, device="cuda:0")
 
         def bwd(s):
             s2d.scan2d_bwd_softplus(s["x"], s["delta"], bias, s["A"], s["Bm"], s["Cm"], s["Dskip"], s["mask"], s["dy"], workspace=ws_b)

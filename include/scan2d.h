@@ -64,7 +64,7 @@ enum {
 };
 
 enum { SCAN2D_F32 = 0, SCAN2D_BF16 = 1 };
-enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2 };
+enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2, SCAN2D_PASS_BWD_SOFTPLUS = 3 };
 
 typedef struct {
     int32_t  Bt, Dc, H, W, N;  /* batch, channels, grid height, grid width, states: all >= 1, N <= 64 */
@@ -129,7 +129,9 @@ int scan2d_bwd(const scan2d_desc* desc,
  *     ddelta_raw[b,c,i,j] = ddelta[b,c,i,j] / (1 + exp(-(delta_raw[b,c,i,j] + delta_bias[c])))
  *     ddelta_bias[c]      = sum_{b,i,j} ddelta_raw[b,c,i,j]      (summed from the stored ddelta_raw)
  * ddelta_raw has the layout and type of delta_raw; ddelta_bias is [Dc] fp32 and must be NULL iff
- * delta_bias is NULL.  Workspace as for scan2d_bwd (scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD)).
+ * delta_bias is NULL.  Workspace: scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD_SOFTPLUS) bytes (with fp32
+ * storage the step is written there once per position by a kernel of its own, and the chain rule is a
+ * second small kernel; with bf16 storage both happen inside the sweeps).
  */
 int scan2d_bwd_softplus(const scan2d_desc* desc,
                         const void* x, const void* delta_raw, const float* delta_bias, const float* A,
@@ -177,7 +179,8 @@ int scan2d_bwd_softplus_gated(const scan2d_desc* desc,
                               float* dDskip, void* dz,
                               void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD / _BWD / _BWD_GATED).
+/* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD for the three forward
+ * calls, SCAN2D_PASS_BWD / _BWD_SOFTPLUS / _BWD_GATED for scan2d_bwd / _bwd_softplus / _bwd_softplus_gated).
  * Returns 0 for an invalid descriptor (the call itself then reports the error). */
 size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass);
 

@@ -314,7 +314,7 @@ extern "C" int scan2d_bwd_softplus_gated(const scan2d_desc* desc, const void* x,
     if (rc != SCAN2D_OK) return rc;
     if (!z || !y_scan || !dy || !dz) return SCAN2D_ERR_NULL_POINTER;
     if (!aligned16(z) || !aligned16(y_scan) || !aligned16(dy) || !aligned16(dz) || !aligned16(workspace)) return SCAN2D_ERR_MISALIGNED;
-    const size_t inner = bwd_workspace_bytes(desc);
+    const size_t inner = bwd_workspace_bytes(desc, true);
     if (inner == 0) return SCAN2D_ERR_BAD_SHAPE;
     if (workspace == nullptr || workspace_bytes < inner + gate_bwd_bytes(desc)) return SCAN2D_ERR_WORKSPACE_SMALL;
     // the gate only changes dy: dy * SiLU(z) goes behind the scan's own workspace, dz is final
@@ -331,8 +331,9 @@ extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
         return fwd_workspace(desc, ch);
     }
     if (pass == SCAN2D_PASS_BWD) return bwd_workspace_bytes(desc);
+    if (pass == SCAN2D_PASS_BWD_SOFTPLUS) return bwd_workspace_bytes(desc, true);
     if (pass == SCAN2D_PASS_BWD_GATED) {
-        const size_t inner = bwd_workspace_bytes(desc);
+        const size_t inner = bwd_workspace_bytes(desc, true);
         return inner == 0 ? 0 : inner + gate_bwd_bytes(desc);
     }
     return 0;

@@ -73,12 +73,62 @@ __global__ void scan2d_bwd_reduce_bias_batch_kernel(const float* __restrict__ pb
     }
 }
 
+// fp32 storage, softplus step, banded form: the step is computed once per position here instead of by each of a
+// map's lane groups in both sweeps (16-fold in the main sweep for N = 16: a fifth of its run time), and the
+// sweeps run their plain instantiations on it.  One workgroup per 1024 positions of a map (`chunks` per map).
+__global__ __launch_bounds__(256) void scan2d_bwd_step_kernel(const float* __restrict__ raw, const float* __restrict__ bias,
+                                                              float* __restrict__ step, size_t HW, int Dc, unsigned chunks) {
+    const size_t map = blockIdx.x / chunks;
+    const float b = bias != nullptr ? bias[map % Dc] : 0.0f;
+    const float* src = raw + map * HW;
+    float* dst = step + map * HW;
+    const size_t e0 = ((size_t)(blockIdx.x % chunks) * 256 + threadIdx.x) * 4;
+    if (e0 + 4 <= HW) {
+        uint32_t r[4], o[4];
+        load_words<4>(reinterpret_cast<const uint32_t*>(src + e0), r);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = __float_as_uint(softplus_f32(__uint_as_float(r[j]) + b));
+        store_words<4>(reinterpret_cast<uint32_t*>(dst + e0), o);
+    } else {
+        for (size_t e = e0; e < HW; ++e) dst[e] = softplus_f32(src[e] + b);
+    }
+}
+
+// The matching chain rule: ddelta (gradient of the step, as the plain sweeps wrote it) becomes the gradient
+// of the raw projection in place, ddelta_raw = ddelta / (1 + exp(-(raw + bias))), and its sum over the
+// map's positions goes to pbias (null: no bias) in the fixed order of scan2d_bwd_reduce_bias_kernel.
+__global__ __launch_bounds__(256) void scan2d_bwd_chain_kernel(float* __restrict__ ddelta, const float* __restrict__ raw,
+                                                               const float* __restrict__ bias, float* __restrict__ pbias,
+                                                               size_t HW, int Dc) {
+    __shared__ float sh[256];
+    const size_t map = blockIdx.x;
+    const float b = bias != nullptr ? bias[map % Dc] : 0.0f;
+    float* dd = ddelta + map * HW;
+    const float* src = raw + map * HW;
+    float acc = 0.0f;
+    for (size_t e = threadIdx.x; e < HW; e += 256) {
+        const float v = dd[e] * logistic_f32(src[e] + b);
+        dd[e] = v;
+        acc += v;
+    }
+    if (pbias == nullptr) return;                        // uniform over the grid
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) pbias[map] = sh[0];
+}
+
 struct BwdPlan {
     bool small = false;                                    // one wavefront per map, no bands (scan2d_bwd_small.hpp)
     int LG = 0, K = 0, NW = 0, waves = 0, RB = 0;
     int NG = 0, GS = 0, CG = 0, nb = 0;
     BwdKernels k;
     size_t lds_bytes = 0;
+    bool step_outside = false;                             // softplus step and its chain rule in kernels of their own
+    size_t off_step = 0;                                   // the step [maps][H][W] fp32 (step_outside only)
     size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, off_pb = 0, total = 0;   // pb: bias-gradient partials
 };
 
@@ -134,7 +184,8 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     const int slots = waves * 64 / LG;
     if ((N + NW - 1) / NW > slots) return false;
     const bool fast = (W % K) == 0;                          // otherwise: the instantiations that treat the row end
-    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
+    pl.step_outside = sp && d->dtype == SCAN2D_F32;
+    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, false);
     if (pl.k.main == nullptr) return false;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
     pl.NG = (N + NW - 1) / NW;
@@ -178,6 +229,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
     pl.off_pD = o; o += d->Bt > 1 ? align_up(maps * sizeof(float)) : 0;
     pl.off_pb = o; o += align_up(maps * sizeof(float));
+    pl.off_step = o; o += pl.step_outside ? align_up(maps * (size_t)d->H * W * sizeof(float)) : 0;
     pl.total = o;
     *out = pl;
     return true;
@@ -185,9 +237,9 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
 
 }  // namespace
 
-size_t bwd_workspace_bytes(const scan2d_desc* d) {
+size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus) {
     BwdPlan pl;
-    return make_plan(d, &pl) ? pl.total : 0;
+    return make_plan(d, &pl, softplus) ? pl.total : 0;
 }
 
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
@@ -233,6 +285,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     BwdArgs a;
     a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.dy = dy;
     a.dx = dx; a.ddelta = ddelta; a.delta_bias = delta_bias;
+    if (pl.step_outside) a.delta = ws + pl.off_step;
     a.ck = reinterpret_cast<float*>(ws + pl.off_ck);
     a.pB = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pB) : dBm;   // one group: the partial is the result
     a.pC = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pC) : dCm;
@@ -272,6 +325,13 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     const long long wg2 = (jobs + MPW - 1) / MPW;
     if (wg1 > 2147483647LL || wg2 > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
     (void)hipGetLastError();
+    const size_t HW = (size_t)d->H * d->W;
+    if (pl.step_outside) {
+        const unsigned chunks = (unsigned)((HW + 1023) / 1024);
+        if ((long long)chunks * maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+        hipLaunchKernelGGL(scan2d_bwd_step_kernel, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
+                           static_cast<const float*>(delta), delta_bias, reinterpret_cast<float*>(ws + pl.off_step), HW, d->Dc, chunks);
+    }
     if (pl.nb > 1)
         hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.waves * 64), 0, stream, ac);
     if (pl.lds_bytes > 65536)
@@ -290,7 +350,16 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
         hipLaunchKernelGGL(scan2d_bwd_reduce_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
                            a.pA, a.pD, dA, dDskip, d->Bt, d->Dc, d->N);
     }
-    if (softplus && ddelta_bias != nullptr) launch_bias_sums(d, pl, ddelta, ddelta_bias, ws, stream);
+    if (pl.step_outside) {
+        float* pb = ddelta_bias == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pb) : ddelta_bias);
+        hipLaunchKernelGGL(scan2d_bwd_chain_kernel, dim3((unsigned)maps), dim3(256), 0, stream, static_cast<float*>(ddelta),
+                           static_cast<const float*>(delta), delta_bias, pb, HW, d->Dc);
+        if (ddelta_bias != nullptr && d->Bt > 1)
+            hipLaunchKernelGGL(scan2d_bwd_reduce_bias_batch_kernel, dim3((d->Dc + 255) / 256), dim3(256), 0, stream,
+                               pb, ddelta_bias, d->Bt, d->Dc);
+    } else if (softplus && ddelta_bias != nullptr) {
+        launch_bias_sums(d, pl, ddelta, ddelta_bias, ws, stream);
+    }
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
 

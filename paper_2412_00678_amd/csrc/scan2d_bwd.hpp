@@ -7,7 +7,8 @@
 
 namespace scan2d {
 
-size_t bwd_workspace_bytes(const scan2d_desc* d);
+// softplus: the workspace of scan2d_bwd_softplus (fp32 storage adds one map-sized buffer for the step).
+size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus = false);
 
 // One line describing the backward plan; false when the shape has no plan.
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes);

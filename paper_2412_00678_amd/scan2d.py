@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libscan2d.so")
 
 F32, BF16 = 0, 1
-PASS_FWD, PASS_BWD, PASS_BWD_GATED = 0, 1, 2
+PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS = 0, 1, 2, 3
 
 EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
@@ -229,7 +229,7 @@ def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, wo
     dCm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
     dDskip = None if Dskip is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
     if workspace is None:
-        workspace, wbytes = _workspace(desc, PASS_BWD, x.device)
+        workspace, wbytes = _workspace(desc, PASS_BWD_SOFTPLUS, x.device)
     else:
         wbytes = workspace.numel() * workspace.element_size()
     rc = lib.scan2d_bwd_softplus(ctypes.byref(desc), _ptr(x), _ptr(delta_raw), _ptr(delta_bias), _ptr(A), _ptr(Bm),

@@ -601,7 +601,7 @@ def test_gated_backward_reports_a_short_workspace(s2d):
     inp = _gated_inputs(w, seed=15)
     d = s2d.to_device(inp, wl.F32)
     desc = s2d.make_desc(d["x"], d["A"])
-    plain, gated = s2d.workspace_bytes(desc, s2d.PASS_BWD), s2d.workspace_bytes(desc, s2d.PASS_BWD_GATED)
+    plain, gated = s2d.workspace_bytes(desc, s2d.PASS_BWD_SOFTPLUS), s2d.workspace_bytes(desc, s2d.PASS_BWD_GATED)
     assert gated >= plain + d["x"].numel() * 4
     ws = torch.empty(plain, dtype=torch.uint8, device="cuda:0")
     with pytest.raises(s2d.Scan2dError) as e:
