@@ -329,7 +329,7 @@ def test_backward_edge_shapes(s2d, shape):
 
 
 @pytest.mark.parametrize("variant,W", [("16,4", 60), ("16,8", 60), ("16,12", 190), ("16,16", 250),
-                                       ("64,4", 250), ("64,8", 260), ("64,16", 60)])
+                                       ("64,4", 250), ("64,4,8", 250), ("64,8", 260), ("64,16", 60)])
 def test_backward_variants(s2d, variant, W):
     check_bwd(s2d, wl.Workload("bvar", 2, 6, 16, 11, W, wl.F32, mask_frac=0.3, backward=True), seed=6, variant=variant)
 
