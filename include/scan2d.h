@@ -129,9 +129,8 @@ int scan2d_bwd(const scan2d_desc* desc,
  *     ddelta_raw[b,c,i,j] = ddelta[b,c,i,j] / (1 + exp(-(delta_raw[b,c,i,j] + delta_bias[c])))
  *     ddelta_bias[c]      = sum_{b,i,j} ddelta_raw[b,c,i,j]      (summed from the stored ddelta_raw)
  * ddelta_raw has the layout and type of delta_raw; ddelta_bias is [Dc] fp32 and must be NULL iff
- * delta_bias is NULL.  Workspace: scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD_SOFTPLUS) bytes (with fp32
- * storage the step is written there once per position by a kernel of its own, and the chain rule is a
- * second small kernel; with bf16 storage both happen inside the sweeps).
+ * delta_bias is NULL.  Workspace: scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD_SOFTPLUS) bytes (except for
+ * small maps the step is written there once per position, as fp32, by a kernel of its own).
  */
 int scan2d_bwd_softplus(const scan2d_desc* desc,
                         const void* x, const void* delta_raw, const float* delta_bias, const float* A,

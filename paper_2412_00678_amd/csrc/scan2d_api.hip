@@ -53,7 +53,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // ------------------------------------------------------------------ forward variant choice
 struct FwdChoice {
     int LG = 0, K = 0, NW = 0, waves = 4;
-    bool exact = true, fast = true, multi = false;
+    bool exact = true, fast = true, multi = false, sp = false;
     int RPB = 1;
     size_t lds_bytes = 0;
     int NG = 0, MPW = 0, panels = 0;
@@ -75,7 +75,7 @@ FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool f
 bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb, bool sp, bool ma, FwdChoice* out) {
     const int slots = waves * 64 / LG;
     FwdChoice c;
-    c.LG = LG; c.K = K; c.NW = NW; c.waves = waves;
+    c.LG = LG; c.K = K; c.NW = NW; c.waves = waves; c.sp = sp;
     c.exact = (d->N % NW) == 0;
     c.NG = (d->N + NW - 1) / NW;
     if (c.NG > slots) return false;
@@ -152,7 +152,8 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     double row = c.K * c.NW * c_core + c.NW * c_scan + c_pos * c.K + 35.0 + c_red;
     if (!c.fast) row *= 1.6;
     if (c.multi) row += 8.0 * c.NW;
-    const double regs = fwd_regs(bf16, c.K, c.NW);
+    // the instantiations that compute the step need one or two VGPRs more, which matters at the 256 boundary
+    const double regs = fwd_regs(bf16, c.K, c.NW) + (c.sp ? 2 : 0);
     const double occ = std::min(8.0, std::max(std::floor(512.0 / regs), c.waves / 4.0));
     const double res_wg = 256.0 * std::max(1.0, std::floor(occ * 4.0 / c.waves));   // workgroups resident on the chip
     const double rounds = std::ceil(wgs / res_wg);
@@ -165,7 +166,7 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     return wgs * c.waves * steps * 4.0 / (1024.0 * eff) * tail;
 }
 
-// sp: pick the instantiation that computes the step itself; the choice of variant does not depend on it
+// sp: pick the instantiation that computes the step itself
 int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = true) {
     if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES[,RPB]"
         int LG = 0, K = 0, NW = 0, waves = 4, rpb = 0;

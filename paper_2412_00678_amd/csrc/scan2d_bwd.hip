@@ -73,43 +73,49 @@ __global__ void scan2d_bwd_reduce_bias_batch_kernel(const float* __restrict__ pb
     }
 }
 
-// fp32 storage, softplus step, banded form: the step is computed once per position here instead of by each of a
-// map's lane groups in both sweeps (16-fold in the main sweep for N = 16: a fifth of its run time), and the
-// sweeps run their plain instantiations on it.  One workgroup per 1024 positions of a map (`chunks` per map).
-__global__ __launch_bounds__(256) void scan2d_bwd_step_kernel(const float* __restrict__ raw, const float* __restrict__ bias,
+// Softplus step, banded form: the step is computed once per position here, as fp32 whatever the storage
+// type, instead of by each of a map's lane groups in both sweeps (16-fold in the main sweep for N = 16: a
+// fifth of its run time); the SP instantiations of the sweeps read it.  One workgroup per 1024 positions of
+// a map (`chunks` per map).
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_bwd_step_kernel(const T* __restrict__ raw, const float* __restrict__ bias,
                                                               float* __restrict__ step, size_t HW, int Dc, unsigned chunks) {
     const size_t map = blockIdx.x / chunks;
     const float b = bias != nullptr ? bias[map % Dc] : 0.0f;
-    const float* src = raw + map * HW;
+    const T* src = raw + map * HW;
     float* dst = step + map * HW;
     const size_t e0 = ((size_t)(blockIdx.x % chunks) * 256 + threadIdx.x) * 4;
-    if (e0 + 4 <= HW) {
-        uint32_t r[4], o[4];
-        load_words<4>(reinterpret_cast<const uint32_t*>(src + e0), r);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = __float_as_uint(softplus_f32(__uint_as_float(r[j]) + b));
-        store_words<4>(reinterpret_cast<uint32_t*>(dst + e0), o);
-    } else {
-        for (size_t e = e0; e < HW; ++e) dst[e] = softplus_f32(src[e] + b);
+    for (size_t e = e0; e < e0 + 4 && e < HW; ++e) {
+        float t;
+        if constexpr (Elem<T>::kBytes == 4) t = __uint_as_float(elem_bits(src + e));
+        else t = __uint_as_float(elem_bits(src + e) << 16);
+        dst[e] = softplus_f32(t + b);
     }
 }
 
-// The matching chain rule: ddelta (gradient of the step, as the plain sweeps wrote it) becomes the gradient
-// of the raw projection in place, ddelta_raw = ddelta / (1 + exp(-(raw + bias))), and its sum over the
-// map's positions goes to pbias (null: no bias) in the fixed order of scan2d_bwd_reduce_bias_kernel.
-__global__ __launch_bounds__(256) void scan2d_bwd_chain_kernel(float* __restrict__ ddelta, const float* __restrict__ raw,
-                                                               const float* __restrict__ bias, float* __restrict__ pbias,
-                                                               size_t HW, int Dc) {
+// The matching chain rule: `dstep` (fp32, the gradient of the step as the main sweep left it in the workspace)
+// becomes the gradient of the raw projection, ddelta_raw = dstep / (1 + exp(-(raw + bias))), rounded once to
+// the storage type; its sum over the map's positions, taken from the stored values, goes to pbias (null: no
+// bias) in a fixed order (strided partial sums per thread, then a tree over the workgroup).
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_bwd_chain_kernel(const float* __restrict__ dstep, const T* __restrict__ raw,
+                                                               const float* __restrict__ bias, T* __restrict__ ddelta_raw,
+                                                               float* __restrict__ pbias, size_t HW, int Dc) {
     __shared__ float sh[256];
     const size_t map = blockIdx.x;
     const float b = bias != nullptr ? bias[map % Dc] : 0.0f;
-    float* dd = ddelta + map * HW;
-    const float* src = raw + map * HW;
+    const float* dd = dstep + map * HW;
+    const T* src = raw + map * HW;
+    T* dst = ddelta_raw + map * HW;
     float acc = 0.0f;
     for (size_t e = threadIdx.x; e < HW; e += 256) {
-        const float v = dd[e] * logistic_f32(src[e] + b);
-        dd[e] = v;
-        acc += v;
+        float t;
+        if constexpr (Elem<T>::kBytes == 4) t = __uint_as_float(elem_bits(src + e));
+        else t = __uint_as_float(elem_bits(src + e) << 16);
+        const float v = dd[e] * logistic_f32(t + b);
+        store_elem(dst + e, v);
+        if constexpr (Elem<T>::kBytes == 4) acc += v;
+        else acc += __uint_as_float(f32_to_bf16_bits(v) << 16);
     }
     if (pbias == nullptr) return;                        // uniform over the grid
     sh[threadIdx.x] = acc;
@@ -127,7 +133,7 @@ struct BwdPlan {
     int NG = 0, GS = 0, CG = 0, nb = 0;
     BwdKernels k;
     size_t lds_bytes = 0;
-    bool step_outside = false;                             // softplus step and its chain rule in kernels of their own
+    bool step_outside = false;                             // softplus step written by a kernel of its own (banded form)
     size_t off_step = 0;                                   // the step [maps][H][W] fp32 (step_outside only)
     size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, off_pb = 0, total = 0;   // pb: bias-gradient partials
 };
@@ -186,8 +192,8 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     const int slots = waves * 64 / LG;
     if ((N + NW - 1) / NW > slots) return false;
     const bool fast = (W % K) == 0;                          // otherwise: the instantiations that treat the row end
-    pl.step_outside = sp && d->dtype == SCAN2D_F32;
-    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, false);
+    pl.step_outside = sp;
+    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
     if (pl.k.main == nullptr) return false;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
     pl.NG = (N + NW - 1) / NW;
@@ -331,8 +337,13 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     if (pl.step_outside) {
         const unsigned chunks = (unsigned)((HW + 1023) / 1024);
         if ((long long)chunks * maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
-        hipLaunchKernelGGL(scan2d_bwd_step_kernel, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
-                           static_cast<const float*>(delta), delta_bias, reinterpret_cast<float*>(ws + pl.off_step), HW, d->Dc, chunks);
+        float* step = reinterpret_cast<float*>(ws + pl.off_step);
+        if (d->dtype == SCAN2D_BF16)
+            hipLaunchKernelGGL(scan2d_bwd_step_kernel<bf16_t>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
+                               static_cast<const bf16_t*>(delta), delta_bias, step, HW, d->Dc, chunks);
+        else
+            hipLaunchKernelGGL(scan2d_bwd_step_kernel<float>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
+                               static_cast<const float*>(delta), delta_bias, step, HW, d->Dc, chunks);
     }
     if (pl.nb > 1)
         hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.waves * 64), 0, stream, ac);
@@ -354,8 +365,13 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     }
     if (pl.step_outside) {
         float* pb = ddelta_bias == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pb) : ddelta_bias);
-        hipLaunchKernelGGL(scan2d_bwd_chain_kernel, dim3((unsigned)maps), dim3(256), 0, stream, static_cast<float*>(ddelta),
-                           static_cast<const float*>(delta), delta_bias, pb, HW, d->Dc);
+        const float* dstep = reinterpret_cast<const float*>(ws + pl.off_step);
+        if (d->dtype == SCAN2D_BF16)
+            hipLaunchKernelGGL(scan2d_bwd_chain_kernel<bf16_t>, dim3((unsigned)maps), dim3(256), 0, stream, dstep,
+                               static_cast<const bf16_t*>(delta), delta_bias, static_cast<bf16_t*>(ddelta), pb, HW, d->Dc);
+        else
+            hipLaunchKernelGGL(scan2d_bwd_chain_kernel<float>, dim3((unsigned)maps), dim3(256), 0, stream, dstep,
+                               static_cast<const float*>(delta), delta_bias, static_cast<float*>(ddelta), pb, HW, d->Dc);
         if (ddelta_bias != nullptr && d->Bt > 1)
             hipLaunchKernelGGL(scan2d_bwd_reduce_bias_batch_kernel, dim3((d->Dc + 255) / 256), dim3(256), 0, stream,
                                pb, ddelta_bias, d->Bt, d->Dc);

@@ -7,7 +7,7 @@
 
 namespace scan2d {
 
-// softplus: the workspace of scan2d_bwd_softplus (fp32 storage adds one map-sized buffer for the step).
+// softplus: the workspace of scan2d_bwd_softplus (the banded form adds one fp32 map-sized buffer for the step).
 size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus = false);
 
 // One line describing the backward plan; false when the shape has no plan.

@@ -23,8 +23,12 @@
 // element); its cells past the row end get dy = 0 and a zero column state, which makes every
 // gradient they could contribute exactly 0 whatever finite values they hold, and it stores
 // element by element.
-// SP: `delta` holds the raw projection; the step is softplus(raw + delta_bias[c]) (Eq. 3) and ddelta
-// is the gradient with respect to the raw projection (a second set of instantiations).
+// SP: the caller's step is softplus(raw + delta_bias[c]) (Eq. 3).  A kernel of its own has written it
+// once per position as fp32 (`delta` points there, whatever the storage type T), because each of a map's
+// lane groups would otherwise repeat the softplus in both sweeps.  The main sweep writes the gradient of
+// the step, unrounded, over the step itself (a row's step is not read again once its gradient is stored),
+// and a last element-wise kernel applies the chain rule there - inside the sweep it would put a dependent
+// global load behind every row's barrier (a second set of instantiations).
 // PF: the inputs of the next row are requested before the current row is processed (costs one
 // more row of raw registers); without it the kernel relies on several waves per SIMD.
 #pragma once
@@ -37,7 +41,7 @@ namespace scan2d {
 struct BwdArgs {
     const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
     const float* Dskip; const uint8_t* mask; const void* dy;
-    const float* delta_bias;   // [Dc] or null; read by the SP instantiations only (delta then holds the raw projection)
+    const float* delta_bias;   // [Dc] or null (not read by the sweeps)
     void* dx; void* ddelta;
     float* ck;           // [maps][nb][N][W]   column state entering each band (band 0 unused)
     float* pB; float* pC; // [Bt][CG][N][H][W] partial sums over the channels of one group
@@ -91,6 +95,8 @@ template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool 
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdArgs p) {
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
+    using DT = std::conditional_t<SP, float, T>;              // element type of the step
+    constexpr int XWD = words_of<DT, K>();
     const int tid = threadIdx.x, slot = tid / LG, l = tid % LG;
     const int NG = p.NG, MPW = SLOTS / NG;
     const int map_local = slot / NG, sg = slot - map_local * NG;
@@ -105,7 +111,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
     const bool inside = col0 < W;
     const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
     const T* xm = reinterpret_cast<const T*>(p.x) + (size_t)map * HW;
-    const T* dm = reinterpret_cast<const T*>(p.delta) + (size_t)map * HW;
+    const DT* dm = reinterpret_cast<const DT*>(p.delta) + (size_t)map * HW;
     const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
     const T* Bs[NW];
     float Ap[NW], h[NW][K];
@@ -117,13 +123,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 #pragma unroll
         for (int j = 0; j < K; ++j) h[s][j] = 0.0f;
     }
-    const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;   // SP: delta = softplus(raw + bias)
     // x, delta, mask (one HBM stream per channel) run PDX rows ahead in a ring of raw registers, Bm one
     // row ahead; the row loop is written as trips of PDX rows without a test between them, so that
     // the wait counts the compiler derives let all of them stay in flight.
-    constexpr int PDX = (2 * XW + K / 4 <= 28) ? 2 : 1;
+    constexpr int PDX = (XW + XWD + K / 4 <= 28) ? 2 : 1;
     constexpr int SC = NW >= 4 ? 4 : NW;                      // states scanned together
-    uint32_t rx[PDX][XW], rd[PDX][XW], rm[PDX][K / 4], rB[NW][XW];
+    uint32_t rx[PDX][XW], rd[PDX][XWD], rm[PDX][K / 4], rB[NW][XW];
     const int last = H - 2;                                   // the last row's state is never needed
     const int wide_rows = H - 1;                              // without FAST: rows that may be read past their end
 #pragma unroll
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
         const int row = min(d, H - 1);
         const size_t ro = (size_t)row * W;
         ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, row < wide_rows, rx[d]);
-        ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, row < wide_rows, rd[d]);
+        ld_elems<DT, K, FAST>(dm + ro, col0, lcol, W, row < wide_rows, rd[d]);
         ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, row < wide_rows, rm[d]);
     }
 #pragma unroll
@@ -145,13 +150,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
         float dl[K], dxe[K];
 #pragma unroll
         for (int j = 0; j < K; ++j) {
-            dl[j] = get_elem<T, K>(rd[XS], j);
-            if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
+            dl[j] = get_elem<DT, K>(rd[XS], j);
             const float xe = mask_bit<K>(rm[XS], j) ? 0.0f : get_elem<T, K>(rx[XS], j);
             dxe[j] = dl[j] * xe;
         }
         ld_elems<T, K, FAST>(xm + nxt_x, col0, lcol, W, row_x < wide_rows, rx[XS]);
-        ld_elems<T, K, FAST>(dm + nxt_x, col0, lcol, W, row_x < wide_rows, rd[XS]);
+        ld_elems<DT, K, FAST>(dm + nxt_x, col0, lcol, W, row_x < wide_rows, rd[XS]);
         ld_mask<K, FAST>(mm ? mm + nxt_x : nullptr, col0, lcol, W, row_x < wide_rows, rm[XS]);
 #pragma unroll
         for (int s0 = 0; s0 < NW; s0 += SC) {
@@ -218,6 +222,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     constexpr int THREADS = WAVES * 64;
     constexpr int SLOTS = THREADS / LG;
     constexpr int XW = words_of<T, K>();
+    using DT = std::conditional_t<SP, float, T>;         // element type of the step
+    constexpr int XWD = words_of<DT, K>();
     constexpr int PANEL = LG * K;
     extern __shared__ float lds[];
     const int GS = p.GS;
@@ -283,7 +289,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             const int c = act ? c_first + ch : c_first;      // idle iterations re-read a valid channel
             const size_t map = (size_t)b * p.Dc + c;
             const T* xm = reinterpret_cast<const T*>(p.x) + map * HW;
-            const T* dm = reinterpret_cast<const T*>(p.delta) + map * HW;
+            const DT* dm = reinterpret_cast<const DT*>(p.delta) + map * HW;
+            float* ddw = SP ? const_cast<float*>(reinterpret_cast<const float*>(p.delta)) + map * HW : nullptr;
             const T* dym = reinterpret_cast<const T*>(p.dy) + map * HW;
             T* dxm = reinterpret_cast<T*>(p.dx) + map * HW;
             T* ddm = reinterpret_cast<T*>(p.ddelta) + map * HW;
@@ -294,17 +301,16 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                 Ap[s] = An[s] * kLog2e;
             }
             const float dsk = (p.Dskip != nullptr && sg == 0) ? p.Dskip[c] : 0.0f;
-            const float dbias = (SP && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;   // SP: delta = softplus(raw + bias)
 
             // ---- scans 1 and 2: rebuild h[i-1,j] and hhor[i,j-1] for the rows of the band
             float hprev[RB][NW][K], hhl[RB][NW][K];
             if (act) {
-                uint32_t fx[2][XW], fd[2][XW], fm[2][K / 4], fB[2][NW][XW];
+                uint32_t fx[2][XW], fd[2][XWD], fm[2][K / 4], fB[2][NW][XW];
                 auto issue = [&](int buf, int i) {
                     const size_t ro = (size_t)i * W;
                     const bool wide = i < wide_rows;
                     ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, wide, fx[buf]);
-                    ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, wide, fd[buf]);
+                    ld_elems<DT, K, FAST>(dm + ro, col0, lcol, W, wide, fd[buf]);
                     ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, wide, fm[buf]);
 #pragma unroll
                     for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, wide, fB[buf][s]);
@@ -335,8 +341,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                         float dl[K], dxe[K];
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
-                            dl[j] = get_elem<T, K>(fd[r & 1], j);
-                            if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
+                            dl[j] = get_elem<DT, K>(fd[r & 1], j);
+                            if (SP && !FAST && j >= nv) dl[j] = 0.0f;     // past the row end: the row below already holds gradients
                             const float xe = mask_bit<K>(fm[r & 1], j) ? 0.0f : get_elem<T, K>(fx[r & 1], j);
                             dxe[j] = dl[j] * xe;
                         }
@@ -376,12 +382,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                 for (int j = 0; j < K; ++j) ga[s][j] = gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j];
             }
-            uint32_t bx[2][XW], bd[2][XW], by[2][XW], bm[2][K / 4], bB[2][NW][XW], bC[2][NW][XW];
+            uint32_t bx[2][XW], bd[2][XWD], by[2][XW], bm[2][K / 4], bB[2][NW][XW], bC[2][NW][XW];
             auto issue_r = [&](int buf, int i) {
                 const size_t ro = (size_t)i * W;
                 const bool wide = i < wide_rows;
                 ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, wide, bx[buf]);
-                ld_elems<T, K, FAST>(dm + ro, col0, lcol, W, wide, bd[buf]);
+                ld_elems<DT, K, FAST>(dm + ro, col0, lcol, W, wide, bd[buf]);
                 ld_elems<T, K, FAST>(dym + ro, col0, lcol, W, wide, by[buf]);
                 ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, wide, bm[buf]);
 #pragma unroll
@@ -404,8 +410,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                     float dl[K], xe[K], dxe[K], dyv[K], ddl[K], dxl[K];
 #pragma unroll
                     for (int j = 0; j < K; ++j) {
-                        dl[j] = get_elem<T, K>(bd[r & 1], j);
-                        if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
+                        dl[j] = get_elem<DT, K>(bd[r & 1], j);
+                        if (SP && !FAST && j >= nv) dl[j] = 0.0f;
                         xe[j] = mask_bit<K>(bm[r & 1], j) ? 0.0f : get_elem<T, K>(bx[r & 1], j);
                         dxe[j] = dl[j] * xe[j];
                         dyv[j] = get_elem<T, K>(by[r & 1], j);
@@ -466,14 +472,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                         const float* base = part + (size_t)(step & 1) * 2 * THREADS * K + (size_t)(slot - sg) * PANEL;
                         for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
                             if (col < W) {
-                                float dd = sum_partials<PANEL>(base + col, NG);
-                                if constexpr (SP) {                    // chain rule through the softplus
-                                    float traw;
-                                    if constexpr (Elem<T>::kBytes == 4) traw = __uint_as_float(elem_bits(dm + ro + col));
-                                    else traw = __uint_as_float(elem_bits(dm + ro + col) << 16);
-                                    dd *= logistic_f32(traw + dbias);
-                                }
-                                store_elem(ddm + ro + col, dd);
+                                const float dd = sum_partials<PANEL>(base + col, NG);
+                                if constexpr (SP) ddw[ro + col] = dd;       // over the step of this cell, which nobody reads again
+                                else store_elem(ddm + ro + col, dd);
                                 store_elem(dxm + ro + col, sum_partials<PANEL>(base + THREADS * K + col, NG));
                             }
                         }

@@ -83,8 +83,8 @@ def test_workspace_query(lib):
     for dt, eb in ((0, 4), (1, 2)):
         d = lib.Desc(2, 8, 20, 40, 16, dt, 0)
         assert lib.workspace_bytes(d, lib.PASS_BWD_GATED) == lib.workspace_bytes(d, lib.PASS_BWD_SOFTPLUS) + ((2 * 8 * 20 * 40 * eb + 255) // 256) * 256
-        # the softplus backward keeps the step in the workspace when the storage is fp32 (one fp32 map-sized buffer)
-        extra = ((2 * 8 * 20 * 40 * 4 + 255) // 256) * 256 if dt == 0 else 0
+        # the softplus backward keeps the step in the workspace (one fp32 map-sized buffer)
+        extra = ((2 * 8 * 20 * 40 * 4 + 255) // 256) * 256
         assert lib.workspace_bytes(d, lib.PASS_BWD_SOFTPLUS) == lib.workspace_bytes(d, lib.PASS_BWD) + extra
     assert lib.workspace_bytes(lib.Desc(1, 2, 8, 3000, 4, 0, 0), lib.PASS_BWD_GATED) == 0      # no backward plan for this width
 
