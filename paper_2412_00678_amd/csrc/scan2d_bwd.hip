@@ -85,6 +85,14 @@ __global__ __launch_bounds__(256) void scan2d_bwd_step_kernel(const T* __restric
     const T* src = raw + map * HW;
     float* dst = step + map * HW;
     const size_t e0 = ((size_t)(blockIdx.x % chunks) * 256 + threadIdx.x) * 4;
+    if (e0 + 4 <= HW && (Elem<T>::kBytes == 4 || (HW & 1) == 0)) {      // four elements at once (rows of a map stay 4-byte aligned)
+        uint32_t r[words_of<T, 4>()], o[4];
+        load_words<words_of<T, 4>()>(reinterpret_cast<const uint32_t*>(src + e0), r);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = __float_as_uint(softplus_f32(get_elem<T, 4>(r, j) + b));
+        store_words<4>(reinterpret_cast<uint32_t*>(dst + e0), o);
+        return;
+    }
     for (size_t e = e0; e < e0 + 4 && e < HW; ++e) {
         float t;
         if constexpr (Elem<T>::kBytes == 4) t = __uint_as_float(elem_bits(src + e));
