@@ -65,8 +65,8 @@ struct V4 { int LG, K, NW, waves; };
 const V4 kFwdVariants[] = {SCAN2D_FWD_VARIANTS(SCAN2D_X)};
 #undef SCAN2D_X
 
-FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma) {
-    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi, sp, ma)
+FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma, bool ua) {
+    return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi, sp, ma, ua)
                                 : fwd_kernel_f32(LG, K, NW, waves, exact, fast, multi, sp, ma);
 }
 
@@ -82,11 +82,14 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb
     c.MPW = slots / c.NG;
     c.panels = (d->W + LG * K - 1) / (LG * K);
     c.multi = c.panels > 1;
-    c.fast = !c.multi && (d->dtype == SCAN2D_F32 || (d->W % 2) == 0) && (ma || !sp);   // rows start on a 4-byte boundary
+    // unguarded loads: one panel; rows on 4-byte boundaries, or (bf16 rows of odd width) the instantiations
+    // that shift the elements into place, which exist without sp only, as do those for unaligned mask rows
+    const bool ua = d->dtype == SCAN2D_BF16 && (d->W % 2) != 0;
+    c.fast = !c.multi && (ua ? !sp : (ma || !sp));
     // 32-bit lane offsets span up to `slots` maps and `slots + 1` batch items of states
     const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
     if (span >= 2147483648.0) return false;
-    c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi, sp, ma);
+    c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi, sp, ma, ua);
     if (c.kernel == nullptr) return false;
     // LDS for the partial sums: 2 buffers x RPB rows x (threads * K) floats.  Few large maps (one
     // workgroup per CU at most) can afford 64 KB; otherwise stay near 24 KB so that several

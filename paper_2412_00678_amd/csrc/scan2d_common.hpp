@@ -67,6 +67,24 @@ __device__ __forceinline__ void load_words_any(const void* __restrict__ q, uint3
 }
 
 template <int WORDS>
+__device__ __forceinline__ void store_words_any(void* __restrict__ q, const uint32_t* r) {
+    unsigned char* p = static_cast<unsigned char*>(q);
+    int w = 0;
+#pragma unroll
+    for (; w + 4 <= WORDS; w += 4) {
+        u32x4_a1 v; v.x = r[w]; v.y = r[w + 1]; v.z = r[w + 2]; v.w = r[w + 3];
+        *reinterpret_cast<u32x4_a1*>(p + 4 * w) = v;
+    }
+#pragma unroll
+    for (; w + 2 <= WORDS; w += 2) {
+        u32x2_a1 v; v.x = r[w]; v.y = r[w + 1];
+        *reinterpret_cast<u32x2_a1*>(p + 4 * w) = v;
+    }
+#pragma unroll
+    for (; w < WORDS; ++w) *reinterpret_cast<u32_a1*>(p + 4 * w) = r[w];
+}
+
+template <int WORDS>
 __device__ __forceinline__ void store_words(uint32_t* __restrict__ p, const uint32_t* r) {
     int w = 0;
 #pragma unroll
@@ -110,20 +128,6 @@ __device__ __forceinline__ void buffer_load_words(rsrc_t rs, uint32_t lane_bytes
     for (; w < WORDS; ++w) r[w] = __builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes + 4 * w, uniform_bytes, 0);
 }
 
-// K mask bytes from a byte offset that is not a multiple of 4 (rows of a width that is not): buffer
-// loads of dwords drop the low address bits, so read the K/4 + 1 aligned dwords around the bytes and
-// shift them into place (v_alignbyte_b32).
-template <int K>
-__device__ __forceinline__ void buffer_load_mask_unaligned(rsrc_t rs, uint32_t byte_off, uint32_t* m) {
-    constexpr int NWORD = K / 4;
-    const uint32_t base = byte_off & ~3u, sh = byte_off & 3u;
-    uint32_t w[NWORD + 1];
-#pragma unroll
-    for (int k = 0; k <= NWORD; ++k) w[k] = __builtin_amdgcn_raw_buffer_load_b32(rs, base + 4 * k, 0, 0);
-#pragma unroll
-    for (int k = 0; k < NWORD; ++k) m[k] = __builtin_amdgcn_alignbyte(w[k + 1], w[k], sh);
-}
-
 __device__ __forceinline__ uint32_t elem_bits(const float* p)  { return __float_as_uint(*p); }
 __device__ __forceinline__ uint32_t elem_bits(const bf16_t* p) { return p->bits; }
 
@@ -133,13 +137,16 @@ __device__ __forceinline__ void put_elem(uint32_t* r, int j, uint32_t bits) {
     else r[j >> 1] |= bits << (16 * (j & 1));
 }
 
-// The K elements [col0, col0+K) of one row; columns >= W read as +0 and are never touched
-// in memory (identity padding: delta = 0 gives a = 1, x = B = C = 0 gives u = 0).
+// The K elements [col0, col0+K) of one row (global memory); columns >= W read as +0 and are never
+// touched in memory (identity padding: delta = 0 gives a = 1, x = B = C = 0 gives u = 0).  A lane whose
+// K columns all exist reads them with wide loads whatever the address alignment (vec_ok: the address
+// is known to be 4-byte aligned); only a lane across the row end goes element by element.
 template <typename T, int K>
 __device__ __forceinline__ void load_row(const T* __restrict__ rowp, int col0, int W, bool vec_ok,
                                          uint32_t* r) {
-    if (vec_ok && col0 + K <= W) {
-        load_words<words_of<T, K>()>(reinterpret_cast<const uint32_t*>(rowp + col0), r);
+    if (col0 + K <= W) {
+        if (vec_ok) load_words<words_of<T, K>()>(reinterpret_cast<const uint32_t*>(rowp + col0), r);
+        else load_words_any<words_of<T, K>()>(rowp + col0, r);
     } else {
 #pragma unroll
         for (int w = 0; w < words_of<T, K>(); ++w) r[w] = 0u;
@@ -153,8 +160,9 @@ __device__ __forceinline__ void load_row(const T* __restrict__ rowp, int col0, i
 template <int K>
 __device__ __forceinline__ void load_mask(const uint8_t* __restrict__ rowp, int col0, int W, bool vec_ok,
                                           uint32_t* m) {
-    if (vec_ok && col0 + K <= W) {
-        load_words<K / 4>(reinterpret_cast<const uint32_t*>(rowp + col0), m);
+    if (col0 + K <= W) {
+        if (vec_ok) load_words<K / 4>(reinterpret_cast<const uint32_t*>(rowp + col0), m);
+        else load_words_any<K / 4>(rowp + col0, m);
     } else {
 #pragma unroll
         for (int w = 0; w < K / 4; ++w) m[w] = 0u;
@@ -193,13 +201,14 @@ __device__ __forceinline__ void store_elem(bf16_t* p, float f) { p->bits = stati
 // Write v[0..K) to columns [col0, col0+K) of a row, skipping columns >= W.
 template <typename T, int K>
 __device__ __forceinline__ void store_row(T* __restrict__ rowp, int col0, int W, bool vec_ok, const float* v) {
-    if (vec_ok && col0 + K <= W) {
+    if (col0 + K <= W) {                      // wide stores at any alignment (vec_ok: known to be 4-byte aligned)
         uint32_t r[words_of<T, K>()];
 #pragma unroll
         for (int w = 0; w < words_of<T, K>(); ++w) r[w] = 0u;
 #pragma unroll
         for (int j = 0; j < K; ++j) put_elem<T, K>(r, j, to_elem_bits<T>(v[j]));
-        store_words<words_of<T, K>()>(reinterpret_cast<uint32_t*>(rowp + col0), r);
+        if (vec_ok) store_words<words_of<T, K>()>(reinterpret_cast<uint32_t*>(rowp + col0), r);
+        else store_words_any<words_of<T, K>()>(rowp + col0, r);
     } else {
 #pragma unroll
         for (int j = 0; j < K; ++j)

@@ -66,11 +66,15 @@ struct FwdArgs {
 // discarded.  A lane that straddles the end of the row reads on into the next row (or zeros past the
 // end of the tensor: the buffer descriptors carry the exact size): those cells sit to the right of
 // every real column, so what they hold reaches no output (the row recurrence only runs rightwards,
-// the column recurrence stays in its column), and they are never stored.  Rows must start on a 4-byte
-// boundary (buffer loads of dwords drop the low address bits): always for fp32, even W for bf16; the
-// mask rows start on such a boundary only when W is a multiple of 4 (MA); the instantiations with MA = false
-// read the aligned dwords around a lane's mask bytes and shift them into place.  Without FAST (maps wider than one
-// panel, bf16 rows of odd width) every element access is guarded.
+// the column recurrence stays in its column), and they are never stored.  Buffer loads of dwords want
+// 4-byte aligned addresses: always so for fp32 rows, for bf16 rows of even width, and for mask rows when
+// W is a multiple of 4 (MA).  The instantiations with MA = false request the aligned dwords around a
+// lane's mask bytes and shift them into place (v_alignbyte_b32) where the row is unpacked - not where
+// it is requested, which would wait for the load at once.  Without FAST (maps wider than one panel)
+// every element access is guarded.
+// UA (bf16 only): rows of odd width start on odd 2-byte boundaries every other row.  The loads fetch one
+// dword more from the address rounded down to a dword and the K elements are shifted into place
+// (v_alignbit_b32 by 0 or 16) where they are unpacked.
 // MULTI: the map is wider than one panel (p.panels > 1); single-panel kernels carry no code
 // for the panel hand-over.
 // SP: the step is computed here, delta = softplus(raw + bias) (a second set of instantiations, so that
@@ -87,8 +91,10 @@ struct FwdArgs {
 #endif
 constexpr int kPrefetchBudgetX = SCAN2D_PREFETCH_BUDGET_X, kPrefetchBudgetS = SCAN2D_PREFETCH_BUDGET_S;
 
-template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI, bool SP = false, bool MA = true>
+template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI, bool SP = false, bool MA = true,
+          bool UA = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p) {
+    static_assert(!UA || (FAST && !MA && Elem<T>::kBytes == 2), "UA: bf16 rows on odd 2-byte boundaries, unguarded loads");
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
     constexpr int PANEL = LG * K;
@@ -129,9 +135,14 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
     const uint32_t mlane = (uint32_t)((size_t)(b - b0) * HW);
     constexpr size_t EBY = (size_t)Elem<T>::kBytes;
     const size_t left_maps = (size_t)(p.maps - map0) * HW, left_items = (size_t)(p.maps / p.Dc - b0) * HW;
-    const rsrc_t rsx = make_rsrc(xu, left_maps * EBY), rsd = make_rsrc(du, left_maps * EBY),
-                 rsB = make_rsrc(Bu, left_items * N * EBY), rsC = make_rsrc(Cu, left_items * N * EBY),
-                 rsm = make_rsrc(mu, left_items);
+    // Exact sizes, rounded up to whole dwords: a load whose dword is only partly inside the range would
+    // return 0 for all of it, and the last dword of a tensor with an odd number of bf16 elements, or of a
+    // mask whose size is not a multiple of 4, holds real data (the dword itself lies in mapped memory:
+    // its first bytes are the tensor's).
+    auto up4 = [](size_t bytes) { return (bytes + 3) & ~(size_t)3; };
+    const rsrc_t rsx = make_rsrc(xu, up4(left_maps * EBY)), rsd = make_rsrc(du, up4(left_maps * EBY)),
+                 rsB = make_rsrc(Bu, up4(left_items * N * EBY)), rsC = make_rsrc(Cu, up4(left_items * N * EBY)),
+                 rsm = make_rsrc(mu, up4(left_items));
 
     float Ap[NW];
 #pragma unroll
@@ -166,18 +177,21 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
         constexpr int PDX = 4 * XSET <= kPrefetchBudgetX ? 4 : (2 * XSET <= kPrefetchBudgetX ? 2 : 1);
         constexpr int PDS = 4 * SSET <= kPrefetchBudgetS ? 4 : (2 * SSET <= kPrefetchBudgetS ? 2 : 1);
         constexpr int TRIP = PDX > PDS ? PDX : PDS;
-        uint32_t rx[PDX][XW], rd[PDX][XW], rm[PDX][K / 4], rB[PDS][NW][XW], rC[PDS][NW][XW];
+        constexpr int XWR = XW + (UA ? 1 : 0);                 // raw dwords per lane and tensor row
+        constexpr int MWR = K / 4 + ((FAST && !MA) ? 1 : 0);   // raw mask dwords: one more when the bytes are shifted into place
+        uint32_t rx[PDX][XWR], rd[PDX][XWR], rm[PDX][MWR], rB[PDS][NW][XWR], rC[PDS][NW][XWR];
         // FAST: buffer addressing - uniform base and uniform row offset in scalar registers, one
         // loop-invariant 32-bit byte offset per lane (the host bounds the span to 2^31 bytes)
         constexpr uint32_t EB = (uint32_t)Elem<T>::kBytes;
         auto ld = [&](const T* base, rsrc_t rs, uint32_t uni_off, uint32_t lane_off, uint32_t* r) {
-            if constexpr (FAST) buffer_load_words<XW>(rs, (lane_off + lcol) * EB, uni_off * EB, r);
+            if constexpr (FAST && UA) buffer_load_words<XWR>(rs, ((lane_off + lcol + uni_off) * EB) & ~3u, 0u, r);   // rounded down to a dword
+            else if constexpr (FAST) buffer_load_words<XW>(rs, (lane_off + lcol) * EB, uni_off * EB, r);
             else load_row<T, K>(base + uni_off + lane_off, col0, W, false, r);
         };
         auto ldm = [&](uint32_t uni_off, uint32_t* r) {
             if constexpr (FAST) {
                 if constexpr (MA) buffer_load_words<K / 4>(rsm, mlane + lcol, uni_off, r);
-                else buffer_load_mask_unaligned<K>(rsm, mlane + lcol + uni_off, r);
+                else buffer_load_words<MWR>(rsm, (mlane + lcol + uni_off) & ~3u, 0u, r);   // the aligned dwords around the K bytes
             }
             else load_mask<K>(mu + uni_off + mlane, col0, W, false, r);
         };
@@ -187,13 +201,29 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
             if constexpr (EXACT) ld(base, rs, (uint32_t)s * (uint32_t)HW + row_off, slane, r);
             else ld(base, rs, row_off, slane + (uint32_t)((s < nvalid ? s : 0) * HW), r);
         };
+        // UA: the K elements of a raw register set, shifted into place; the element offset of the load
+        // (uniform + lane part) says whether it started on an odd 2-byte boundary
+        auto unpack = [&](const uint32_t* raw, uint32_t uni_off, uint32_t lane_off, uint32_t* out) {
+            if constexpr (UA) {
+                const uint32_t sh = ((uni_off ^ (lane_off + lcol)) & 1u) << 4;
+#pragma unroll
+                for (int w = 0; w < XW; ++w) out[w] = __builtin_amdgcn_alignbit(raw[w + 1], raw[w], sh);
+            } else {
+#pragma unroll
+                for (int w = 0; w < XW; ++w) out[w] = raw[w];
+            }
+        };
+        auto unpacks = [&](const uint32_t* raw, int s, uint32_t row_off, uint32_t* out) {
+            if constexpr (EXACT) unpack(raw, (uint32_t)s * (uint32_t)HW + row_off, slane, out);
+            else unpack(raw, row_off, slane + (uint32_t)((s < nvalid ? s : 0) * HW), out);
+        };
 #pragma unroll
         for (int d = 0; d < PDX; ++d) {
             const uint32_t ro = (uint32_t)min(d, H - 1) * (uint32_t)W;
             ld(xu, rsx, ro, xlane, rx[d]);
             ld(du, rsd, ro, xlane, rd[d]);
 #pragma unroll
-            for (int w = 0; w < K / 4; ++w) rm[d][w] = 0u;
+            for (int w = 0; w < MWR; ++w) rm[d][w] = 0u;
             if (mu) ldm(ro, rm[d]);
         }
 #pragma unroll
@@ -214,12 +244,24 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
             const uint32_t nxt_x = (uint32_t)min(i + PDX, H - 1) * (uint32_t)W;
             const uint32_t nxt_s = (uint32_t)min(i + PDS, H - 1) * (uint32_t)W;
             float dl[K], dx[K], yacc[K];
+            const uint32_t cur = (uint32_t)i * (uint32_t)W;
+            uint32_t ux[XW], ud[XW], um[K / 4];
+            unpack(rx[XS], cur, xlane, ux);
+            unpack(rd[XS], cur, xlane, ud);
+            if constexpr (FAST && !MA) {              // the K mask bytes, shifted into place where they are used, not where they are requested
+                const uint32_t sh = (mlane + lcol + cur) & 3u;
+#pragma unroll
+                for (int w = 0; w < K / 4; ++w) um[w] = __builtin_amdgcn_alignbyte(rm[XS][w + 1], rm[XS][w], sh);
+            } else {
+#pragma unroll
+                for (int w = 0; w < K / 4; ++w) um[w] = rm[XS][w];
+            }
 #pragma unroll
             for (int j = 0; j < K; ++j) {
-                dl[j] = get_elem<T, K>(rd[XS], j);
+                dl[j] = get_elem<T, K>(ud, j);
                 if constexpr (SP) dl[j] = softplus_f32(dl[j] + dbias);
-                const float xv = get_elem<T, K>(rx[XS], j);
-                const float xe = mask_bit<K>(rm[XS], j) ? 0.0f : xv;      // select: nothing under the mask leaks
+                const float xv = get_elem<T, K>(ux, j);
+                const float xe = mask_bit<K>(um, j) ? 0.0f : xv;          // select: nothing under the mask leaks
                 dx[j] = dl[j] * xe;
                 yacc[j] = dsk * xe;
             }
@@ -237,7 +279,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                         const int s = s0 + t;
 #pragma unroll
                         for (int j = 0; j < K; ++j) a[t][j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
-                        hl[t][0] = dx[0] * get_elem<T, K>(rB[SS][s], 0);
+                        uint32_t uB[XW];
+                        unpacks(rB[SS][s], s, cur, uB);
+                        hl[t][0] = dx[0] * get_elem<T, K>(uB, 0);
                         pl[t][0] = a[t][0];
                         if (MULTI && panel > 0 && l == 0) {   // state entering from the panel to the left
                             const float* cw = p.carry + ((size_t)map * N + n0 + ((EXACT || s < nvalid) ? s : 0)) * H + i;
@@ -245,7 +289,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                         }
 #pragma unroll
                         for (int j = 1; j < K; ++j) {
-                            hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dx[j] * get_elem<T, K>(rB[SS][s], j));
+                            hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dx[j] * get_elem<T, K>(uB, j));
                             pl[t][j] = pl[t][j - 1] * a[t][j];
                         }
                         lds(Bu, rsB, s, nxt_s, rB[SS][s]);
@@ -261,12 +305,14 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                             __hip_atomic_store(cw, Hh[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                         const float cmul = (EXACT || s < nvalid) ? 1.0f : 0.0f;   // idle state adds nothing to y
+                        uint32_t uC[XW];
+                        unpacks(rC[SS][s], s, cur, uC);
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
                             // Eq. 5; at the lane's last column the scan result is the state itself
                             const float hh = (j == K - 1) ? Hh[t] : fmaf(pl[t][j], cin[t], hl[t][j]);
                             fma_inplace(h[s][j], a[t][j], hh);                          // Eq. 6
-                            const float cv = EXACT ? get_elem<T, K>(rC[SS][s], j) : cmul * get_elem<T, K>(rC[SS][s], j);
+                            const float cv = EXACT ? get_elem<T, K>(uC, j) : cmul * get_elem<T, K>(uC, j);
                             yacc[j] = fmaf(cv, h[s][j], yacc[j]);
                         }
                         lds(Cu, rsC, s, nxt_s, rC[SS][s]);
@@ -278,7 +324,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
             if (!reduce) {
                 if (live) {
                     if constexpr (FAST) {
-                        if (inside) store_row<T, K>(yrow + xlane, col0, W, true, yacc);   // wide unless it straddles the row end
+                        if (inside) store_row<T, K>(yrow + xlane, col0, W, !UA, yacc);   // wide unless it straddles the row end
                     } else {
                         store_row<T, K>(yrow + xlane, col0, W, false, yacc);
                     }

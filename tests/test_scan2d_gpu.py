@@ -104,7 +104,12 @@ SHAPES = [
     (2, 5, 16, 19, 58, wl.BF16, 0.3),      # bf16, even width: rows on 4-byte boundaries, mask rows not
     (1, 6, 16, 11, 201, wl.F32, 0.4),
     (1, 6, 16, 11, 250, wl.BF16, 0.4),
-    (1, 3, 16, 9, 55, wl.BF16, 0.3),       # bf16, odd width: guarded accesses
+    (1, 3, 16, 9, 55, wl.BF16, 0.3),       # bf16, odd width: every other row starts on an odd 2-byte boundary
+    (3, 5, 16, 21, 57, wl.BF16, 0.4),      # odd width and odd H*W: maps alternate their alignment too
+    (2, 3, 16, 10, 201, wl.BF16, 0.3),     # the same with wave-wide lane groups
+    (1, 7, 5, 13, 99, wl.BF16, 0.3),       # ragged last lane group
+    (2, 4, 16, 12, 255, wl.BF16, 0.0),     # no mask
+    (1, 2, 16, 1, 63, wl.BF16, 0.3),       # a single row
     (1, 4, 16, 13, 101, wl.F32, 0.0),      # no mask
     (1, 2, 5, 7, 150, wl.F32, 0.3),        # ragged states and a ragged last lane
     (1, 1, 16, 3, 255, wl.F32, 0.5),       # the last lane of the last row of the last map reads past the tensor
@@ -160,9 +165,10 @@ def test_every_kernel_variant(s2d, variant, shape, dtype):
 
 # ------------------------------------------------------------------ mask / indexing: bit-exact
 
-def test_mask_is_bit_identical_to_prezeroed_x_and_blocks_garbage(s2d):
+@pytest.mark.parametrize("H,W", [(40, 72), (19, 57), (9, 55), (7, 33), (5, 250)])   # also mask and bf16 tensors that end inside a dword
+def test_mask_is_bit_identical_to_prezeroed_x_and_blocks_garbage(s2d, H, W):
     for dtype in (wl.F32, wl.BF16):
-        w = wl.Workload("mask", 2, 6, 16, 40, 72, dtype, mask_frac=0.4)
+        w = wl.Workload("mask", 2, 6, 16, H, W, dtype, mask_frac=0.4)
         inp = wl.make_inputs(w, seed=7)
         y_mask = run_fwd(s2d, inp, dtype)
         nomask = dict(inp, mask=None)                     # x is already +0 under the mask
