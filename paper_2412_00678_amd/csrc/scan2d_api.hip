@@ -82,10 +82,10 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb
     c.MPW = slots / c.NG;
     c.panels = (d->W + LG * K - 1) / (LG * K);
     c.multi = c.panels > 1;
-    // unguarded loads: one panel; rows on 4-byte boundaries, or (bf16 rows of odd width) the instantiations
-    // that shift the elements into place, which exist without sp only, as do those for unaligned mask rows
+    // unguarded loads whenever one panel covers the row (bf16 rows of odd width and mask rows off the 4-byte
+    // boundaries have instantiations that shift the elements into place)
     const bool ua = d->dtype == SCAN2D_BF16 && (d->W % 2) != 0;
-    c.fast = !c.multi && (ua ? !sp : (ma || !sp));
+    c.fast = !c.multi;
     // 32-bit lane offsets span up to `slots` maps and `slots + 1` batch items of states
     const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
     if (span >= 2147483648.0) return false;

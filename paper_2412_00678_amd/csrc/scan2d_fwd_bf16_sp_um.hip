@@ -1,0 +1,7 @@
+// bf16-storage instantiations of the unguarded softplus forward kernels for mask rows off the 4-byte boundaries.
+#include "scan2d_variants.hpp"
+namespace scan2d {
+FwdKernel fwd_kernel_bf16_sp_um(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {
+    return lookup_fwd_kernel_unaligned_mask<bf16_t, false, true>(LG, K, NW, waves, exact, fast, multi);
+}
+}

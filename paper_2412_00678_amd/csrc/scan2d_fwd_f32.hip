@@ -3,9 +3,10 @@
 namespace scan2d {
 FwdKernel fwd_kernel_f32_sp(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
 FwdKernel fwd_kernel_f32_um(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
+FwdKernel fwd_kernel_f32_sp_um(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
 FwdKernel fwd_small_kernel_f32_sp(int KS, int NW);
 FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma) {
-    if (fast && !ma) return sp ? nullptr : fwd_kernel_f32_um(LG, K, NW, waves, exact, fast, multi);
+    if (fast && !ma) return sp ? fwd_kernel_f32_sp_um(LG, K, NW, waves, exact, fast, multi) : fwd_kernel_f32_um(LG, K, NW, waves, exact, fast, multi);
     return sp ? fwd_kernel_f32_sp(LG, K, NW, waves, exact, fast, multi) : lookup_fwd_kernel<float, false>(LG, K, NW, waves, exact, fast, multi);
 }
 FwdKernel fwd_small_kernel_f32(int KS, int NW, bool sp) {

@@ -44,14 +44,14 @@ using FwdKernel = void (*)(const FwdArgs);
 // Returns nullptr when the variant is not compiled.
 // sp: the instantiations that compute the step themselves (softplus of the raw projection).
 // ma: mask rows start on 4-byte boundaries (no mask, or W a multiple of 4); the instantiations for the
-//     other case exist for the unguarded variants without sp only.
-// ua (bf16 only): tensor rows start on odd 2-byte boundaries (odd W); exists for the unguarded variants without sp.
+//     other case exist for the unguarded variants.
+// ua (bf16 only): tensor rows start on odd 2-byte boundaries (odd W); exists for the unguarded variants.
 FwdKernel fwd_kernel_f32(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma);
 FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma, bool ua = false);
 
 // Unguarded variants for mask rows that do not start on 4-byte boundaries, and (UA, bf16 only) for
 // tensor rows that do not either.
-template <typename T, bool UA = false>
+template <typename T, bool UA = false, bool SP = false>
 inline FwdKernel lookup_fwd_kernel_unaligned_mask(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
 
 // Narrow maps (W <= 32): KS columns per lane, NW = states per lane group of the wave's four.
@@ -91,14 +91,14 @@ inline FwdKernel lookup_fwd_kernel(int LG, int K, int NW, int waves, bool exact,
     return nullptr;
 }
 
-template <typename T, bool UA>
+template <typename T, bool UA, bool SP>
 inline FwdKernel lookup_fwd_kernel_unaligned_mask(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi) {
 #define SCAN2D_X(lg, k, nw, wv) \
-    if (exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, true, false, false, false, UA>;
+    if (exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, true, false, SP, false, UA>;
     SCAN2D_FWD_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
 #define SCAN2D_X(lg, k, nw, wv) \
-    if (!exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, false, true, false, false, false, UA>;
+    if (!exact && fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, false, true, false, SP, false, UA>;
     SCAN2D_FWD_RAGGED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
     return nullptr;

@@ -435,6 +435,7 @@ SOFTPLUS_SHAPES = [
     (1, 4, 5, 7, 45, wl.F32, 0.2), (1, 3, 16, 13, 192, wl.F32, 0.0), (1, 2, 8, 5, 600, wl.F32, 0.3),
     (1, 16, 16, 64, 256, wl.BF16, 0.5), (3, 2, 4, 6, 30, wl.F32, 0.3),
     (1, 5, 16, 9, 57, wl.F32, 0.3), (1, 5, 16, 9, 58, wl.BF16, 0.3),   # widths off the lane and mask boundaries
+    (2, 5, 16, 11, 55, wl.BF16, 0.3), (1, 3, 16, 7, 201, wl.BF16, 0.0),  # bf16 rows on odd 2-byte boundaries
 ]
 
 
