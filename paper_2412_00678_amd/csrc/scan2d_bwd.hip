@@ -135,6 +135,30 @@ __global__ __launch_bounds__(256) void scan2d_bwd_chain_kernel(const float* __re
     if (threadIdx.x == 0) pbias[map] = sh[0];
 }
 
+// Padded copies of the rows behind which the input tensors end (layout: TailRows in scan2d_bwd_kernels.hpp):
+// the last row of the last map of x, delta and dy, of the last state plane of Bm and Cm, and of the last
+// batch item's mask, each followed by 16 zeros.  The instantiations for widths that are not a multiple of
+// the columns per lane read these rows from here, because their last lane reads past the end of a row.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_bwd_tail_kernel(const T* __restrict__ x, const T* __restrict__ delta, const T* __restrict__ dy,
+                                                              const T* __restrict__ Bm, const T* __restrict__ Cm,
+                                                              const uint8_t* __restrict__ mask, T* __restrict__ tail,
+                                                              size_t last_map_row, size_t last_plane_row, size_t last_mask_row, int W) {
+    const int ts = W + 16;
+    uint8_t* tm = reinterpret_cast<uint8_t*>(tail + 5 * (size_t)ts);
+    for (int j = threadIdx.x; j < ts; j += 256) {
+        const bool in = j < W;
+        T zero;
+        if constexpr (Elem<T>::kBytes == 4) zero = 0.0f; else zero.bits = 0;
+        tail[j] = in ? x[last_map_row + j] : zero;
+        tail[ts + j] = in ? delta[last_map_row + j] : zero;
+        tail[2 * (size_t)ts + j] = in ? dy[last_map_row + j] : zero;
+        tail[3 * (size_t)ts + j] = in ? Bm[last_plane_row + j] : zero;
+        tail[4 * (size_t)ts + j] = in ? Cm[last_plane_row + j] : zero;
+        tm[j] = (in && mask != nullptr) ? mask[last_mask_row + j] : (uint8_t)0;
+    }
+}
+
 struct BwdPlan {
     bool small = false;                                    // one wavefront per map, no bands (scan2d_bwd_small.hpp)
     int LG = 0, K = 0, NW = 0, waves = 0, RB = 0;
@@ -142,7 +166,9 @@ struct BwdPlan {
     BwdKernels k;
     size_t lds_bytes = 0;
     bool step_outside = false;                             // softplus step written by a kernel of its own (banded form)
-    size_t off_step = 0;                                   // the step [maps][H][W] fp32 (step_outside only)
+    size_t off_step = 0;                                   // the step [maps][H][W] fp32 (step_outside only), 256 spare bytes behind it
+    bool fast = true;                                      // W is a multiple of the columns per lane
+    size_t off_tail = 0;                                   // padded copies of the tensors' last rows (TailRows)
     size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, off_pb = 0, total = 0;   // pb: bias-gradient partials
 };
 
@@ -201,6 +227,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     if ((N + NW - 1) / NW > slots) return false;
     const bool fast = (W % K) == 0;                          // otherwise: the instantiations that treat the row end
     pl.step_outside = sp;
+    pl.fast = fast;
     pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
     if (pl.k.main == nullptr) return false;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
@@ -245,7 +272,8 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
     pl.off_pD = o; o += d->Bt > 1 ? align_up(maps * sizeof(float)) : 0;
     pl.off_pb = o; o += align_up(maps * sizeof(float));
-    pl.off_step = o; o += pl.step_outside ? align_up(maps * (size_t)d->H * W * sizeof(float)) : 0;
+    pl.off_step = o; o += pl.step_outside ? align_up(maps * (size_t)d->H * W * sizeof(float)) + 256 : 0;
+    pl.off_tail = o; o += align_up((size_t)(W + 16) * (5 * (d->dtype == SCAN2D_BF16 ? 2 : 4) + 1));
     pl.total = o;
     *out = pl;
     return true;
@@ -302,6 +330,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.dy = dy;
     a.dx = dx; a.ddelta = ddelta; a.delta_bias = delta_bias;
     if (pl.step_outside) a.delta = ws + pl.off_step;
+    a.tail = pl.small ? nullptr : ws + pl.off_tail;
     a.ck = reinterpret_cast<float*>(ws + pl.off_ck);
     a.pB = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pB) : dBm;   // one group: the partial is the result
     a.pC = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pC) : dCm;
@@ -342,6 +371,19 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     if (wg1 > 2147483647LL || wg2 > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
     (void)hipGetLastError();
     const size_t HW = (size_t)d->H * d->W;
+    if (!pl.fast) {
+        const size_t r1 = ((size_t)maps - 1) * HW + (size_t)(d->H - 1) * d->W;
+        const size_t r2 = ((size_t)d->Bt * d->N - 1) * HW + (size_t)(d->H - 1) * d->W;
+        const size_t r3 = ((size_t)d->Bt - 1) * HW + (size_t)(d->H - 1) * d->W;
+        if (d->dtype == SCAN2D_BF16)
+            hipLaunchKernelGGL(scan2d_bwd_tail_kernel<bf16_t>, dim3(1), dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                               static_cast<const bf16_t*>(delta), static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(Bm),
+                               static_cast<const bf16_t*>(Cm), mask, reinterpret_cast<bf16_t*>(ws + pl.off_tail), r1, r2, r3, d->W);
+        else
+            hipLaunchKernelGGL(scan2d_bwd_tail_kernel<float>, dim3(1), dim3(256), 0, stream, static_cast<const float*>(x),
+                               static_cast<const float*>(delta), static_cast<const float*>(dy), static_cast<const float*>(Bm),
+                               static_cast<const float*>(Cm), mask, reinterpret_cast<float*>(ws + pl.off_tail), r1, r2, r3, d->W);
+    }
     if (pl.step_outside) {
         const unsigned chunks = (unsigned)((HW + 1023) / 1024);
         if ((long long)chunks * maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;

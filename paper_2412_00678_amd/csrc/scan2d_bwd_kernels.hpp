@@ -19,10 +19,12 @@
 // All accesses are unguarded and wide.  A lane past the last column mirrors lane 0 with dy
 // forced to 0, so nothing flows out of it into the reverse scans, and it never stores.
 // FAST = W is a multiple of K.  Without it the lane that holds the last column reads on into
-// the next row (only the last row of a map, after which the tensor may end, is read element by
-// element); its cells past the row end get dy = 0 and a zero column state, which makes every
+// the next row; its cells past the row end get dy = 0 and a zero column state, which makes every
 // gradient they could contribute exactly 0 whatever finite values they hold, and it stores
-// element by element.
+// element by element.  The one row behind which a tensor ends (the last row of its last map) is
+// read from a padded copy that a small kernel leaves in the workspace (`tail`): the row pointer is
+// a select, so that no load sits in a branch (loads in branches make the compiler's wait counts
+// conservative, which cost these instantiations a quarter of their speed).
 // SP: the caller's step is softplus(raw + delta_bias[c]) (Eq. 3).  A kernel of its own has written it
 // once per position as fp32 (`delta` points there, whatever the storage type T), because each of a map's
 // lane groups would otherwise repeat the softplus in both sweeps.  The main sweep writes the gradient of
@@ -45,6 +47,7 @@ struct BwdArgs {
     void* dx; void* ddelta;
     float* ck;           // [maps][nb][N][W]   column state entering each band (band 0 unused)
     float* pB; float* pC; // [Bt][CG][N][H][W] partial sums over the channels of one group
+    const void* tail;    // padded copies of the rows behind which the tensors end (instantiations without FAST)
     float* pA;           // [Bt][Dc][N]
     float* pD;           // [Bt][Dc]
     int Bt, Dc, H, W, N;
@@ -69,26 +72,39 @@ __device__ __forceinline__ void store_f32s(float* __restrict__ p, const float* v
     store_words<K>(reinterpret_cast<uint32_t*>(p), r);
 }
 
-// K elements of one row for this lane (see FAST above).  wide = the lane may read K elements
-// starting at its first column even if the row ends before the last of them: true for every row
-// but the last one of a map whose width is not a multiple of K (what follows a row in memory
-// is the next row of the same tensor, except after the very last row).
+// K elements of one row for this lane (see FAST above), read wide from any byte address.  Without
+// FAST the lane that holds the last column reads past the row end; `last` says that this is the row
+// behind which the tensor ends, and the padded copy `tail_row` is read instead.
 template <typename T, int K, bool FAST>
-__device__ __forceinline__ void ld_elems(const T* __restrict__ rowp, int col0, uint32_t lcol, int W, bool wide, uint32_t* r) {
-    if (FAST || wide) load_words_any<words_of<T, K>()>(rowp + lcol, r);
-    else load_row<T, K>(rowp, col0, W, false, r);
+__device__ __forceinline__ void ld_elems(const T* rowp, uint32_t lcol, bool last, const T* tail_row, uint32_t* r) {
+    const T* q = rowp;
+    if constexpr (!FAST) q = last ? tail_row : rowp;
+    load_words_any<words_of<T, K>()>(q + lcol, r);
 }
 template <int K, bool FAST>
-__device__ __forceinline__ void ld_mask(const uint8_t* __restrict__ rowp, int col0, uint32_t lcol, int W, bool wide, uint32_t* r) {
+__device__ __forceinline__ void ld_mask(const uint8_t* rowp, uint32_t lcol, bool last, const uint8_t* tail_row, uint32_t* r) {
     if (rowp == nullptr) {
 #pragma unroll
         for (int w = 0; w < K / 4; ++w) r[w] = 0u;
-    } else if (FAST || wide) {
-        load_words_any<K / 4>(rowp + lcol, r);
     } else {
-        load_mask<K>(rowp, col0, W, false, r);
+        const uint8_t* q = rowp;
+        if constexpr (!FAST) q = last ? tail_row : rowp;
+        load_words_any<K / 4>(q + lcol, r);
     }
 }
+// Layout of the padded copies: five rows of W + 16 elements (x, delta, dy, Bm, Cm) and one of W + 16
+// mask bytes; each holds the last row of the last map / state plane of its tensor, zeros behind it.
+template <typename T>
+struct TailRows {
+    const T *x, *delta, *dy, *B, *C;
+    const uint8_t* mask;
+    __device__ __forceinline__ TailRows(const void* base, int W) {
+        const T* t = static_cast<const T*>(base);
+        const size_t ts = (size_t)W + 16;
+        x = t; delta = t + ts; dy = t + 2 * ts; B = t + 3 * ts; C = t + 4 * ts;
+        mask = reinterpret_cast<const uint8_t*>(t + 5 * ts);
+    }
+};
 
 // ---------------------------------------------------------------------------- checkpoint sweep
 template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool SP = false>
@@ -130,17 +146,23 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
     constexpr int SC = NW >= 4 ? 4 : NW;                      // states scanned together
     uint32_t rx[PDX][XW], rd[PDX][XWD], rm[PDX][K / 4], rB[NW][XW];
     const int last = H - 2;                                   // the last row's state is never needed
-    const int wide_rows = H - 1;                              // without FAST: rows that may be read past their end
+    // without FAST: is this lane's map / state plane / batch item the last of its tensor?  (the step of
+    // the SP instantiations lives in the workspace, which has room behind it)
+    const TailRows<T> tl(p.tail, W);
+    const bool lastx = map == maps - 1, lastm = b == p.Bt - 1;
+    bool lastB[NW];
+#pragma unroll
+    for (int s = 0; s < NW; ++s) lastB[s] = lastm && (n0 + (s < nvalid ? s : 0) == N - 1);
 #pragma unroll
     for (int d = 0; d < PDX; ++d) {
         const int row = min(d, H - 1);
         const size_t ro = (size_t)row * W;
-        ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, row < wide_rows, rx[d]);
-        ld_elems<DT, K, FAST>(dm + ro, col0, lcol, W, row < wide_rows, rd[d]);
-        ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, row < wide_rows, rm[d]);
+        ld_elems<T, K, FAST>(xm + ro, lcol, lastx && row == H - 1, tl.x, rx[d]);
+        ld_elems<DT, K, FAST>(dm + ro, lcol, !SP && lastx && row == H - 1, reinterpret_cast<const DT*>(tl.delta), rd[d]);
+        ld_mask<K, FAST>(mm ? mm + ro : nullptr, lcol, lastm && row == H - 1, tl.mask, rm[d]);
     }
 #pragma unroll
-    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s], col0, lcol, W, 0 < wide_rows, rB[s]);
+    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s], lcol, lastB[s] && H == 1, tl.B, rB[s]);
 
     auto do_row = [&](const int i, auto par) __attribute__((always_inline)) {
         constexpr int XS = decltype(par)::value % PDX;
@@ -154,9 +176,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
             const float xe = mask_bit<K>(rm[XS], j) ? 0.0f : get_elem<T, K>(rx[XS], j);
             dxe[j] = dl[j] * xe;
         }
-        ld_elems<T, K, FAST>(xm + nxt_x, col0, lcol, W, row_x < wide_rows, rx[XS]);
-        ld_elems<DT, K, FAST>(dm + nxt_x, col0, lcol, W, row_x < wide_rows, rd[XS]);
-        ld_mask<K, FAST>(mm ? mm + nxt_x : nullptr, col0, lcol, W, row_x < wide_rows, rm[XS]);
+        ld_elems<T, K, FAST>(xm + nxt_x, lcol, lastx && row_x == H - 1, tl.x, rx[XS]);
+        ld_elems<DT, K, FAST>(dm + nxt_x, lcol, !SP && lastx && row_x == H - 1, reinterpret_cast<const DT*>(tl.delta), rd[XS]);
+        ld_mask<K, FAST>(mm ? mm + nxt_x : nullptr, lcol, lastm && row_x == H - 1, tl.mask, rm[XS]);
 #pragma unroll
         for (int s0 = 0; s0 < NW; s0 += SC) {
             float a[SC][K], hl[SC][K], pl[SC][K], P[SC], Hh[SC], cin[SC];
@@ -172,7 +194,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
                     hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dxe[j] * get_elem<T, K>(rB[s], j));
                     pl[t][j] = pl[t][j - 1] * a[t][j];
                 }
-                ld_elems<T, K, FAST>(Bs[s] + nxt_s, col0, lcol, W, row_s < wide_rows, rB[s]);
+                ld_elems<T, K, FAST>(Bs[s] + nxt_s, lcol, lastB[s] && row_s == H - 1, tl.B, rB[s]);
                 P[t] = pl[t][K - 1];
                 Hh[t] = hl[t][K - 1];
             }
@@ -251,7 +273,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     const int col0 = l * K;
     const bool inside = col0 < W;
     const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
-    const int wide_rows = H - 1;                         // without FAST: rows that may be read past their end
+    const TailRows<T> tl(p.tail, W);                     // without FAST: see the checkpoint sweep
+    const bool lastm = b == p.Bt - 1;
+    bool lastB[NW];
+#pragma unroll
+    for (int s = 0; s < NW; ++s) lastB[s] = lastm && (n0 + (s < nvalid ? s : 0) == N - 1);
     const int nv = FAST ? (inside ? K : 0) : max(0, min(K, W - col0));   // cells of this lane inside the map
     const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
     const T* Bs[NW];
@@ -288,6 +314,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             const bool act = ch < nch;
             const int c = act ? c_first + ch : c_first;      // idle iterations re-read a valid channel
             const size_t map = (size_t)b * p.Dc + c;
+            const bool lastx = map == (size_t)p.Bt * p.Dc - 1;
             const T* xm = reinterpret_cast<const T*>(p.x) + map * HW;
             const DT* dm = reinterpret_cast<const DT*>(p.delta) + map * HW;
             float* ddw = SP ? const_cast<float*>(reinterpret_cast<const float*>(p.delta)) + map * HW : nullptr;
@@ -308,12 +335,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                 uint32_t fx[2][XW], fd[2][XWD], fm[2][K / 4], fB[2][NW][XW];
                 auto issue = [&](int buf, int i) {
                     const size_t ro = (size_t)i * W;
-                    const bool wide = i < wide_rows;
-                    ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, wide, fx[buf]);
-                    ld_elems<DT, K, FAST>(dm + ro, col0, lcol, W, wide, fd[buf]);
-                    ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, wide, fm[buf]);
+                    const bool bottom = i == H - 1;
+                    ld_elems<T, K, FAST>(xm + ro, lcol, lastx && bottom, tl.x, fx[buf]);
+                    ld_elems<DT, K, FAST>(dm + ro, lcol, !SP && lastx && bottom, reinterpret_cast<const DT*>(tl.delta), fd[buf]);
+                    ld_mask<K, FAST>(mm ? mm + ro : nullptr, lcol, lastm && bottom, tl.mask, fm[buf]);
 #pragma unroll
-                    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, wide, fB[buf][s]);
+                    for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, lcol, lastB[s] && bottom, tl.B, fB[buf][s]);
                 };
                 if constexpr (PF) issue(0, r0);
                 float hcur[NW][K];
@@ -343,7 +370,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                         for (int j = 0; j < K; ++j) {
                             dl[j] = get_elem<DT, K>(fd[r & 1], j);
                             if (SP && !FAST && j >= nv) dl[j] = 0.0f;     // past the row end: the row below already holds gradients
-                            const float xe = mask_bit<K>(fm[r & 1], j) ? 0.0f : get_elem<T, K>(fx[r & 1], j);
+                            // past the row end x belongs to the next map but the mask bytes to the next batch item: no x there
+                            const float xe = (mask_bit<K>(fm[r & 1], j) || (!FAST && j >= nv)) ? 0.0f : get_elem<T, K>(fx[r & 1], j);
                             dxe[j] = dl[j] * xe;
                         }
 #pragma unroll
@@ -385,15 +413,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             uint32_t bx[2][XW], bd[2][XWD], by[2][XW], bm[2][K / 4], bB[2][NW][XW], bC[2][NW][XW];
             auto issue_r = [&](int buf, int i) {
                 const size_t ro = (size_t)i * W;
-                const bool wide = i < wide_rows;
-                ld_elems<T, K, FAST>(xm + ro, col0, lcol, W, wide, bx[buf]);
-                ld_elems<DT, K, FAST>(dm + ro, col0, lcol, W, wide, bd[buf]);
-                ld_elems<T, K, FAST>(dym + ro, col0, lcol, W, wide, by[buf]);
-                ld_mask<K, FAST>(mm ? mm + ro : nullptr, col0, lcol, W, wide, bm[buf]);
+                const bool bottom = i == H - 1;
+                ld_elems<T, K, FAST>(xm + ro, lcol, lastx && bottom, tl.x, bx[buf]);
+                ld_elems<DT, K, FAST>(dm + ro, lcol, !SP && lastx && bottom, reinterpret_cast<const DT*>(tl.delta), bd[buf]);
+                ld_elems<T, K, FAST>(dym + ro, lcol, lastx && bottom, tl.dy, by[buf]);
+                ld_mask<K, FAST>(mm ? mm + ro : nullptr, lcol, lastm && bottom, tl.mask, bm[buf]);
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
-                    ld_elems<T, K, FAST>(Bs[s] + ro, col0, lcol, W, wide, bB[buf][s]);
-                    ld_elems<T, K, FAST>(Cs[s] + ro, col0, lcol, W, wide, bC[buf][s]);
+                    ld_elems<T, K, FAST>(Bs[s] + ro, lcol, lastB[s] && bottom, tl.B, bB[buf][s]);
+                    ld_elems<T, K, FAST>(Cs[s] + ro, lcol, lastB[s] && bottom, tl.C, bC[buf][s]);
                 }
             };
 #pragma unroll
@@ -412,7 +440,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                     for (int j = 0; j < K; ++j) {
                         dl[j] = get_elem<DT, K>(bd[r & 1], j);
                         if (SP && !FAST && j >= nv) dl[j] = 0.0f;
-                        xe[j] = mask_bit<K>(bm[r & 1], j) ? 0.0f : get_elem<T, K>(bx[r & 1], j);
+                        xe[j] = (mask_bit<K>(bm[r & 1], j) || (!FAST && j >= nv)) ? 0.0f : get_elem<T, K>(bx[r & 1], j);
                         dxe[j] = dl[j] * xe[j];
                         dyv[j] = get_elem<T, K>(by[r & 1], j);
                         if (FAST ? !inside : j >= nv) dyv[j] = 0.0f;      // nothing flows out of a cell past the map
