@@ -39,7 +39,8 @@ def usage(unit: str) -> dict:
 def table(unit: str) -> dict:
     best = {}
     for name, regs in usage(unit).items():
-        m = re.search(r"scan2d_fwd_kernel<[^,]+, \d+, (\d+), (\d+), \d+, true, true, false, false>", name)
+        # EXACT, FAST, !MULTI, !SP, MA, !UA: the plain unguarded variants
+        m = re.search(r"scan2d_fwd_kernel<[^,]+, \d+, (\d+), (\d+), \d+, true, true, false, false, true, false>", name)
         if m:
             key = (int(m.group(1)), int(m.group(2)))
             best[key] = max(best.get(key, 0), regs)
