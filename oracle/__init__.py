@@ -214,3 +214,25 @@ def scan2d_bwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, 
     draw = dd / (1.0 + np.exp(-t))
     dbias = None if delta_bias is None else draw.sum(axis=(0, 2, 3)).astype(np.float32)
     return _narrow(dx, dtype), _narrow(draw, dtype), dbias, dA, dBm, dCm, dD, _narrow(dz, dtype)
+
+
+# ------------------------------------------------------------------ identity cells ("skip" mask mode)
+# Supp. "Tiling and edge cases": cells that are not part of the map are padded with A-bar = 1 and x = 0,
+# so that the state passes through them unchanged.  As a mask mode: a masked cell has step 0 (a = exp(0) = 1,
+# u = 0) besides x = 0.  That is the plain scan on a step that is zero under the mask; the gradient of the
+# step under the mask is zero because the step there is the constant 0.
+
+def _skip_step(delta, mask):
+    d = np.array(delta, copy=True)
+    if mask is not None:
+        d[np.broadcast_to(np.asarray(mask)[:, None] != 0, d.shape)] = 0      # +0 in every storage type
+    return d
+
+
+def scan2d_fwd_skip(x, delta, A, Bm, Cm, Dskip=None, mask=None, dtype=F32, threads=0):
+    return scan2d_fwd(x, _skip_step(delta, mask), A, Bm, Cm, Dskip, mask, dtype=dtype, threads=threads)
+
+
+def scan2d_bwd_skip(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F32, threads=0):
+    dx, dd, dA, dBm, dCm, dD = scan2d_bwd(x, _skip_step(delta, mask), A, Bm, Cm, Dskip, mask, dy, dtype=dtype, threads=threads)
+    return dx, _skip_step(dd, mask), dA, dBm, dCm, dD

@@ -563,3 +563,58 @@ def test_gated_output_is_rounded_once_from_the_unrounded_scan(dtype):
             np.testing.assert_array_equal(got, want)
         else:
             assert np.abs(got.astype(np.int32) - want.astype(np.int32)).max() <= 1
+
+
+# ---------------------------------------------------------------------------- identity cells (skip mask mode)
+
+def test_skipped_row_or_column_behaves_as_if_it_were_not_there():
+    """A fully masked row (column) of identity cells passes the state through: every other output equals
+    that of the map with the row (column) deleted (Supp. "Tiling and edge cases": A-bar = 1, x = 0)."""
+    rng = np.random.default_rng(61)
+    Bt, Dc, N, H, W = 2, 3, 3, 5, 6
+    x, delta, A, Bm, Cm, Dskip, _ = rand_problem(rng, Bt, Dc, N, H, W)
+    for axis, idx in ((2, 2), (3, 4), (2, 0), (3, 0), (2, H - 1)):
+        mask = np.zeros((Bt, H, W), np.uint8)
+        if axis == 2:
+            mask[:, idx, :] = 1
+        else:
+            mask[:, :, idx] = 1
+        y = oracle.scan2d_fwd_skip(x, delta, A, Bm, Cm, Dskip, mask, dtype=F64)
+        cut = lambda a: np.ascontiguousarray(np.delete(a, idx, axis=axis))
+        y_cut = oracle.scan2d_fwd(cut(x), cut(delta), A, cut(Bm), cut(Cm), Dskip, None, dtype=F64)
+        np.testing.assert_allclose(cut(y), y_cut, rtol=1e-13, atol=1e-13)
+    # without masked cells the mode changes nothing; the zero-token mode does not have the property
+    none = np.zeros((Bt, H, W), np.uint8)
+    np.testing.assert_array_equal(oracle.scan2d_fwd_skip(x, delta, A, Bm, Cm, Dskip, none, dtype=F64),
+                                  oracle.scan2d_fwd(x, delta, A, Bm, Cm, Dskip, none, dtype=F64))
+    mask = np.zeros((Bt, H, W), np.uint8)
+    mask[:, 2, :] = 1
+    y0 = oracle.scan2d_fwd(x, delta, A, Bm, Cm, Dskip, mask, dtype=F64)
+    cut = lambda a: np.ascontiguousarray(np.delete(a, 2, axis=2))
+    assert np.abs(cut(y0) - oracle.scan2d_fwd(cut(x), cut(delta), A, cut(Bm), cut(Cm), Dskip, None, dtype=F64)).max() > 1e-3
+
+
+def test_skip_mode_backward_matches_central_differences():
+    rng = np.random.default_rng(63)
+    Bt, Dc, N, H, W = 1, 2, 2, 4, 4
+    x, delta, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    mask[0, 1, 2] = 1
+    mask[0, 3, 0] = 1
+    dy = rng.standard_normal(x.shape)
+    m4 = np.broadcast_to(mask[:, None] != 0, x.shape)
+
+    def f(x_=x, d_=delta, Bm_=Bm, Cm_=Cm):
+        return float(np.sum(dy * oracle.scan2d_fwd_skip(x_, d_, A, Bm_, Cm_, Dskip, mask, dtype=F64)))
+
+    dx, dd, dA, dBm, dCm, dD = oracle.scan2d_bwd_skip(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F64)
+    for name, arr, got in (("x_", x, dx), ("d_", delta, dd), ("Bm_", Bm, dBm), ("Cm_", Cm, dCm)):
+        fd = np.zeros(arr.shape)
+        for idx in np.ndindex(arr.shape):
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += 1e-6
+            lo[idx] -= 1e-6
+            fd[idx] = (f(**{name: hi}) - f(**{name: lo})) / 2e-6
+        if name in ("x_", "d_"):
+            assert not np.abs(fd[m4]).max() > 0          # the function does not depend on x or the step under the mask
+            assert not got[m4].any()
+        np.testing.assert_allclose(got, fd, rtol=2e-7, atol=2e-7 * max(1e-30, np.abs(fd).max()), err_msg=name)
