@@ -56,7 +56,7 @@ enum {
     SCAN2D_ERR_BAD_SHAPE        = -2,  /* a dimension < 1, N > 64, N*H*W >= 2^27, element count overflow,
                                           or (backward only) W > 1024, or W > 256 with N > 16 */
     SCAN2D_ERR_BAD_DTYPE        = -3,
-    SCAN2D_ERR_BAD_FLAGS        = -4,  /* flags must be 0 */
+    SCAN2D_ERR_BAD_FLAGS        = -4,  /* flags holds an unknown bit */
     SCAN2D_ERR_WORKSPACE_SMALL  = -5,  /* workspace_bytes < scan2d_workspace_bytes() */
     SCAN2D_ERR_MISALIGNED       = -6,  /* a base pointer is not 16-byte aligned */
     SCAN2D_ERR_LAUNCH_FAILED    = -7,  /* the HIP runtime refused a launch */
@@ -64,12 +64,21 @@ enum {
 };
 
 enum { SCAN2D_F32 = 0, SCAN2D_BF16 = 1 };
+/*
+ * Mask mode (desc.flags).  By default a masked cell holds x = +0 (the zero-token form of the padded
+ * non-tissue cells, Sec. 3.2) and still decays the state that passes through it.  With
+ * SCAN2D_FLAG_IDENTITY_CELLS its step is 0 as well, i.e. A-bar = 1 and B-bar x = 0: the state passes through
+ * unchanged, the padding the supplement describes for cells outside the map ("Tiling and edge cases").  A
+ * fully masked row or column then behaves as if it were not there.  The backward returns ddelta = 0 at such
+ * cells (with the softplus step: ddelta_raw = 0).  Honoured by every forward and backward entry point.
+ */
+enum { SCAN2D_FLAG_IDENTITY_CELLS = 1 };
 enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2, SCAN2D_PASS_BWD_SOFTPLUS = 3 };
 
 typedef struct {
     int32_t  Bt, Dc, H, W, N;  /* batch, channels, grid height, grid width, states: all >= 1, N <= 64 */
     int32_t  dtype;            /* SCAN2D_F32 or SCAN2D_BF16: type of x, delta, Bm, Cm, y, dy, dx, ddelta */
-    uint32_t flags;            /* must be 0 */
+    uint32_t flags;            /* 0 or SCAN2D_FLAG_IDENTITY_CELLS */
 } scan2d_desc;
 
 /*

@@ -38,7 +38,7 @@ int check_desc(const scan2d_desc* d) {
     if (d == nullptr) return SCAN2D_ERR_NULL_POINTER;
     if (d->Bt < 1 || d->Dc < 1 || d->H < 1 || d->W < 1 || d->N < 1 || d->N > 64) return SCAN2D_ERR_BAD_SHAPE;
     if (d->dtype != SCAN2D_F32 && d->dtype != SCAN2D_BF16) return SCAN2D_ERR_BAD_DTYPE;
-    if (d->flags != 0u) return SCAN2D_ERR_BAD_FLAGS;
+    if ((d->flags & ~(uint32_t)SCAN2D_FLAG_IDENTITY_CELLS) != 0u) return SCAN2D_ERR_BAD_FLAGS;
     // element counts must fit 63 bits, and one map's states must be addressable with 32-bit
     // lane offsets (fill_choice checks the exact span): N * H * W < 2^27 bounds it
     const double M = (double)d->Bt * d->Dc * d->H * d->W;
@@ -64,6 +64,8 @@ struct V4 { int LG, K, NW, waves; };
 #define SCAN2D_X(lg, k, nw, wv) {lg, k, nw, wv},
 const V4 kFwdVariants[] = {SCAN2D_FWD_VARIANTS(SCAN2D_X)};
 #undef SCAN2D_X
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 FwdKernel lookup(int dtype, int LG, int K, int NW, int waves, bool exact, bool fast, bool multi, bool sp, bool ma, bool ua) {
     return dtype == SCAN2D_BF16 ? fwd_kernel_bf16(LG, K, NW, waves, exact, fast, multi, sp, ma, ua)
@@ -219,8 +221,15 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
     FwdChoice ch;
     rc = choose_fwd(desc, &ch, softplus != 0, mask == nullptr || (desc->W % 4) == 0);
     if (rc != SCAN2D_OK) return rc;
-    const size_t need = fwd_workspace(desc, ch);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SCAN2D_ERR_WORKSPACE_SMALL;
+    const size_t sk = skip_bytes(desc);
+    const size_t need = sk > 0 ? align256(fwd_workspace(desc, ch)) : fwd_workspace(desc, ch);
+    if (need + sk > 0 && (workspace == nullptr || workspace_bytes < need + sk)) return SCAN2D_ERR_WORKSPACE_SMALL;
+    if (sk > 0 && mask != nullptr) {       // identity cells: the kernels run on a copy of the step that is 0 under the mask
+        void* step = static_cast<char*>(workspace) + need;
+        rc = skip_step_launch(desc, delta, mask, softplus != 0, step, static_cast<hipStream_t>(stream));
+        if (rc != SCAN2D_OK) return rc;
+        delta = step;
+    }
 
     FwdArgs a;
     a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.y = y;
@@ -269,13 +278,31 @@ int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
+    const size_t sk = skip_bytes(desc);
+    if (sk > 0) {                // identity cells: the sweeps run on a copy of the step that is 0 under the mask
+        const size_t inner = bwd_workspace_bytes(desc, softplus);
+        if (inner == 0) return SCAN2D_ERR_BAD_SHAPE;
+        if (workspace == nullptr || workspace_bytes < inner + sk) return SCAN2D_ERR_WORKSPACE_SMALL;
+        if (mask != nullptr) {
+            void* step = static_cast<char*>(workspace) + inner;
+            rc = skip_step_launch(desc, delta, mask, softplus, step, static_cast<hipStream_t>(stream));
+            if (rc != SCAN2D_OK) return rc;
+            delta = step;
+        }
+        workspace_bytes = inner;
+    }
     if (z != nullptr) {          // output gate: dz, and dy * SiLU(z) in place of dy
         rc = gate_bwd_launch(desc, z, y_scan, dy, dyg, dz, static_cast<hipStream_t>(stream));
         if (rc != SCAN2D_OK) return rc;
         dy = dyg;
     }
-    return bwd_launch(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
-                      dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    rc = bwd_launch(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
+                    dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    // identity cells: their step is the constant 0, so it has no gradient (with the softplus step the chain
+    // rule has already multiplied by the logistic function of -inf, which is 0)
+    if (rc == SCAN2D_OK && sk > 0 && mask != nullptr && !softplus)
+        rc = skip_grad_launch(desc, mask, ddelta, static_cast<hipStream_t>(stream));
+    return rc;
 }
 }  // namespace
 
@@ -318,7 +345,7 @@ extern "C" int scan2d_bwd_softplus_gated(const scan2d_desc* desc, const void* x,
     if (rc != SCAN2D_OK) return rc;
     if (!z || !y_scan || !dy || !dz) return SCAN2D_ERR_NULL_POINTER;
     if (!aligned16(z) || !aligned16(y_scan) || !aligned16(dy) || !aligned16(dz) || !aligned16(workspace)) return SCAN2D_ERR_MISALIGNED;
-    const size_t inner = bwd_workspace_bytes(desc, true);
+    const size_t inner = bwd_workspace_bytes(desc, true) + skip_bytes(desc);
     if (inner == 0) return SCAN2D_ERR_BAD_SHAPE;
     if (workspace == nullptr || workspace_bytes < inner + gate_bwd_bytes(desc)) return SCAN2D_ERR_WORKSPACE_SMALL;
     // the gate only changes dy: dy * SiLU(z) goes behind the scan's own workspace, dz is final
@@ -332,13 +359,13 @@ extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
     if (pass == SCAN2D_PASS_FWD) {
         FwdChoice ch;
         if (choose_fwd(desc, &ch) != SCAN2D_OK) return 0;
-        return fwd_workspace(desc, ch);
+        const size_t sk = skip_bytes(desc);
+        return sk > 0 ? align256(fwd_workspace(desc, ch)) + sk : fwd_workspace(desc, ch);
     }
-    if (pass == SCAN2D_PASS_BWD) return bwd_workspace_bytes(desc);
-    if (pass == SCAN2D_PASS_BWD_SOFTPLUS) return bwd_workspace_bytes(desc, true);
-    if (pass == SCAN2D_PASS_BWD_GATED) {
-        const size_t inner = bwd_workspace_bytes(desc, true);
-        return inner == 0 ? 0 : inner + gate_bwd_bytes(desc);
+    if (pass == SCAN2D_PASS_BWD || pass == SCAN2D_PASS_BWD_SOFTPLUS || pass == SCAN2D_PASS_BWD_GATED) {
+        const size_t inner = bwd_workspace_bytes(desc, pass != SCAN2D_PASS_BWD);
+        if (inner == 0) return 0;
+        return inner + skip_bytes(desc) + (pass == SCAN2D_PASS_BWD_GATED ? gate_bwd_bytes(desc) : 0);
     }
     return 0;
 }
@@ -368,7 +395,7 @@ extern "C" const char* scan2d_strerror(int code) {
         case SCAN2D_ERR_NULL_POINTER: return "a required pointer is NULL (or dDskip/Dskip do not match)";
         case SCAN2D_ERR_BAD_SHAPE: return "bad shape: every dimension must be >= 1, N <= 64, N*H*W < 2^27";
         case SCAN2D_ERR_BAD_DTYPE: return "dtype must be SCAN2D_F32 or SCAN2D_BF16";
-        case SCAN2D_ERR_BAD_FLAGS: return "flags must be 0";
+        case SCAN2D_ERR_BAD_FLAGS: return "flags holds a bit other than SCAN2D_FLAG_IDENTITY_CELLS";
         case SCAN2D_ERR_WORKSPACE_SMALL: return "workspace is NULL or smaller than scan2d_workspace_bytes()";
         case SCAN2D_ERR_MISALIGNED: return "a base pointer is not 16-byte aligned";
         case SCAN2D_ERR_LAUNCH_FAILED: return "the HIP runtime refused a kernel launch";

@@ -74,6 +74,40 @@ __global__ __launch_bounds__(256) void scan2d_gate_bwd_kernel(const T* __restric
 }
 
 
+// out = mask ? fill : delta for one map per blockIdx.y-like chunk: map = blockIdx.x / chunks, 1024 positions per workgroup.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_skip_step_kernel(const T* __restrict__ delta, const uint8_t* __restrict__ mask,
+                                                               T* __restrict__ out, size_t HW, int Dc, unsigned chunks, uint32_t fill_bits) {
+    const size_t map = blockIdx.x / chunks;
+    const uint8_t* m = mask + (map / Dc) * HW;
+    const T* src = delta + map * HW;
+    T* dst = out + map * HW;
+    const size_t e0 = ((size_t)(blockIdx.x % chunks) * 256 + threadIdx.x) * 4;
+    for (size_t e = e0; e < e0 + 4 && e < HW; ++e) {
+        T v = src[e];
+        if (m[e] != 0) {
+            if constexpr (Elem<T>::kBytes == 4) v = __uint_as_float(fill_bits);
+            else v.bits = static_cast<uint16_t>(fill_bits);
+        }
+        dst[e] = v;
+    }
+}
+// ddelta = 0 under the mask.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_skip_grad_kernel(const uint8_t* __restrict__ mask, T* __restrict__ ddelta,
+                                                               size_t HW, int Dc, unsigned chunks) {
+    const size_t map = blockIdx.x / chunks;
+    const uint8_t* m = mask + (map / Dc) * HW;
+    T* dst = ddelta + map * HW;
+    const size_t e0 = ((size_t)(blockIdx.x % chunks) * 256 + threadIdx.x) * 4;
+    for (size_t e = e0; e < e0 + 4 && e < HW; ++e) {
+        if (m[e] != 0) {
+            if constexpr (Elem<T>::kBytes == 4) dst[e] = 0.0f;
+            else dst[e].bits = 0;
+        }
+    }
+}
+
 unsigned gate_blocks(size_t n) { return (unsigned)std::min<size_t>((n / 4 + 255) / 256 + 1, 256 * 16); }
 
 }  // namespace
@@ -107,6 +141,43 @@ int gate_bwd_launch(const scan2d_desc* d, const void* z, const void* y_scan, con
         hipLaunchKernelGGL(scan2d_gate_bwd_kernel<float>, dim3(gate_blocks(n)), dim3(256), 0, stream, static_cast<const float*>(z),
                            static_cast<const float*>(y_scan), static_cast<const float*>(dy), static_cast<float*>(dyg),
                            static_cast<float*>(dz), n);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+size_t skip_bytes(const scan2d_desc* d) {
+    if ((d->flags & SCAN2D_FLAG_IDENTITY_CELLS) == 0) return 0;
+    return gate_bwd_bytes(d);                      // one tensor of the storage type, rounded up to 256 bytes
+}
+
+int skip_step_launch(const scan2d_desc* d, const void* delta, const uint8_t* mask, bool minus_inf, void* out, hipStream_t stream) {
+    const size_t HW = (size_t)d->H * d->W;
+    const long long maps = (long long)d->Bt * d->Dc;
+    const unsigned chunks = (unsigned)((HW + 1023) / 1024);
+    if ((long long)chunks * maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    (void)hipGetLastError();
+    if (d->dtype == SCAN2D_BF16)
+        hipLaunchKernelGGL(scan2d_skip_step_kernel<bf16_t>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
+                           static_cast<const bf16_t*>(delta), mask, static_cast<bf16_t*>(out), HW, d->Dc, chunks,
+                           minus_inf ? 0xff80u : 0u);
+    else
+        hipLaunchKernelGGL(scan2d_skip_step_kernel<float>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
+                           static_cast<const float*>(delta), mask, static_cast<float*>(out), HW, d->Dc, chunks,
+                           minus_inf ? 0xff800000u : 0u);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+int skip_grad_launch(const scan2d_desc* d, const uint8_t* mask, void* ddelta, hipStream_t stream) {
+    const size_t HW = (size_t)d->H * d->W;
+    const long long maps = (long long)d->Bt * d->Dc;
+    const unsigned chunks = (unsigned)((HW + 1023) / 1024);
+    if ((long long)chunks * maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    (void)hipGetLastError();
+    if (d->dtype == SCAN2D_BF16)
+        hipLaunchKernelGGL(scan2d_skip_grad_kernel<bf16_t>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream, mask,
+                           static_cast<bf16_t*>(ddelta), HW, d->Dc, chunks);
+    else
+        hipLaunchKernelGGL(scan2d_skip_grad_kernel<float>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream, mask,
+                           static_cast<float*>(ddelta), HW, d->Dc, chunks);
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
 

@@ -22,4 +22,14 @@ size_t gate_bwd_bytes(const scan2d_desc* d);     // bytes of `dyg`, a multiple o
 int gate_bwd_launch(const scan2d_desc* d, const void* z, const void* y_scan, const void* dy, void* dyg, void* dz,
                     hipStream_t stream);
 
+// Identity cells (SCAN2D_FLAG_IDENTITY_CELLS): a masked cell has step 0 besides x = 0.  Element-wise kernels
+// too, for the same reason: a select per element inside the scan kernels costs every caller (measured: 15 % on
+// the 256x256 bf16 forward as a run-time flag), a second set of instantiations costs build time and size.
+// The scan kernels run on a copy of the step (storage type, [Bt][Dc][H][W]) that holds +0 under the mask -
+// or -inf when the step is the softplus of it, whose value (0) and derivative (0) are then exact.
+size_t skip_bytes(const scan2d_desc* d);         // bytes of that copy (a multiple of 256); 0 without the flag
+int skip_step_launch(const scan2d_desc* d, const void* delta, const uint8_t* mask, bool minus_inf, void* out, hipStream_t stream);
+// ddelta = 0 under the mask, in place (the step of an identity cell is a constant).
+int skip_grad_launch(const scan2d_desc* d, const uint8_t* mask, void* ddelta, hipStream_t stream);
+
 }  // namespace scan2d

@@ -98,9 +98,12 @@ def _check(t: Optional[torch.Tensor], name: str, dtype, shape, optional=False):
         raise ValueError(f"{name}: expected {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
 
 
-def make_desc(x: torch.Tensor, A: torch.Tensor) -> Desc:
+FLAG_IDENTITY_CELLS = 1      # masked cells pass the state through unchanged (step 0) instead of only holding x = 0
+
+
+def make_desc(x: torch.Tensor, A: torch.Tensor, flags: int = 0) -> Desc:
     Bt, Dc, H, W = x.shape
-    return Desc(Bt, Dc, H, W, A.shape[1], _dtype_code(x), 0)
+    return Desc(Bt, Dc, H, W, A.shape[1], _dtype_code(x), flags)
 
 
 def describe_plan(desc: Desc, which: int) -> str:
@@ -127,9 +130,9 @@ def _stream_ptr() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def scan2d_fwd(x, delta, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None):
+def scan2d_fwd(x, delta, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None, flags=0):
     """y = 2D selective scan; enqueued on torch's current stream.  Returns y (allocated if None)."""
-    desc = make_desc(x, A)
+    desc = make_desc(x, A, flags)
     Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
     _check(x, "x", x.dtype, (Bt, Dc, H, W))
     _check(delta, "delta", x.dtype, (Bt, Dc, H, W))
@@ -152,9 +155,9 @@ def scan2d_fwd(x, delta, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=Non
     return y
 
 
-def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None):
+def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None, flags=0):
     """y of the scan with delta = softplus(delta_raw + delta_bias[c]) computed in the kernels."""
-    desc = make_desc(x, A)
+    desc = make_desc(x, A, flags)
     Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
     _check(x, "x", x.dtype, (Bt, Dc, H, W))
     _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))
@@ -178,9 +181,9 @@ def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=No
     return y
 
 
-def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None):
+def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0):
     """Gradients (dx, ddelta, dA, dBm, dCm, dDskip) of sum(dy * y); dDskip is None iff Dskip is."""
-    desc = make_desc(x, A)
+    desc = make_desc(x, A, flags)
     Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
     _check(x, "x", x.dtype, (Bt, Dc, H, W))
     _check(delta, "delta", x.dtype, (Bt, Dc, H, W))
@@ -208,9 +211,9 @@ def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None):
     return dx, ddelta, dA, dBm, dCm, dDskip
 
 
-def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, workspace=None):
+def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0):
     """Gradients (dx, ddelta_raw, ddelta_bias, dA, dBm, dCm, dDskip) with the step computed in the kernels."""
-    desc = make_desc(x, A)
+    desc = make_desc(x, A, flags)
     Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
     _check(x, "x", x.dtype, (Bt, Dc, H, W))
     _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))
@@ -241,9 +244,9 @@ def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, wo
 
 
 def scan2d_fwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, z, want_y_scan=True, workspace=None,
-                              y=None, y_scan=None):
+                              y=None, y_scan=None, flags=0):
     """(y_scan or None, y) with y = y_scan * SiLU(z), step and gate computed in the kernel."""
-    desc = make_desc(x, A)
+    desc = make_desc(x, A, flags)
     Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
     _check(x, "x", x.dtype, (Bt, Dc, H, W))
     _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))
@@ -276,9 +279,9 @@ def scan2d_fwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, 
     return y_scan, y
 
 
-def scan2d_bwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, z, y_scan, dy, workspace=None):
+def scan2d_bwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, z, y_scan, dy, workspace=None, flags=0):
     """Gradients (dx, ddelta_raw, ddelta_bias, dA, dBm, dCm, dDskip, dz) of the gated operator."""
-    desc = make_desc(x, A)
+    desc = make_desc(x, A, flags)
     Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
     _check(x, "x", x.dtype, (Bt, Dc, H, W))
     _check(delta_raw, "delta_raw", x.dtype, (Bt, Dc, H, W))

@@ -54,7 +54,8 @@ def test_descriptor_validation_needs_no_device(lib):
     assert call(D(1, 1, 1, -3, 4, 0, 0)) == -2
     assert call(D(1, 1, 4096, 4096, 16, 0, 0)) == -2          # N*H*W >= 2^27
     assert call(D(1, 1, 8, 8, 4, 7, 0)) == -3
-    assert call(D(1, 1, 8, 8, 4, 0, 1)) == -4
+    assert call(D(1, 1, 8, 8, 4, 0, 2)) == -4                    # an unknown flag bit
+    assert call(D(1, 1, 8, 8, 4, 0, 1)) != -4                    # SCAN2D_FLAG_IDENTITY_CELLS
     assert call(D(1, 1, 8, 8, 4, 0, 0)) == -1                  # NULL tensors
     assert lib.lib.scan2d_fwd(None, *([None] * 8), None, 0, None) == -1
     bwd = lambda d: lib.lib.scan2d_bwd(ctypes.byref(d), *([None] * 14), None, 0, None)

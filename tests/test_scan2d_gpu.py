@@ -617,6 +617,74 @@ def test_gated_backward_reports_a_short_workspace(s2d):
     assert e.value.code == -5
 
 
+# ------------------------------------------------------------------ identity cells (skip mask mode)
+
+SKIP_SHAPES = [
+    (2, 5, 16, 21, 64, wl.F32, 0.4), (2, 5, 16, 14, 14, wl.BF16, 0.3), (1, 3, 16, 9, 200, wl.BF16, 0.5),
+    (1, 4, 5, 7, 45, wl.F32, 0.3), (1, 3, 16, 13, 190, wl.F32, 0.3), (1, 2, 8, 5, 600, wl.F32, 0.3),
+    (1, 4, 40, 6, 30, wl.F32, 0.3), (1, 3, 16, 9, 57, wl.BF16, 0.6), (3, 2, 4, 16, 16, wl.F32, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape", SKIP_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_identity_cells_forward_and_backward_match_oracle(s2d, shape):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("skip", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True)
+    inp = wl.make_inputs(w, seed=21, poison_under_mask=np.nan)      # nothing stored under the mask may matter
+    print(f"identity cells case Bt={Bt} Dc={Dc} N={N} H={H} W={W} dtype={dtype}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    args = (d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
+    y = s2d.scan2d_fwd(*args, flags=s2d.FLAG_IDENTITY_CELLS)
+    y_plain = s2d.scan2d_fwd(*args)
+    torch.cuda.synchronize()
+    clean = wl.make_inputs(w, seed=21)
+    ref = oracle.scan2d_fwd_skip(clean["x"], clean["delta"], clean["A"], clean["Bm"], clean["Cm"], clean["Dskip"], clean["mask"], dtype=dtype)
+    got = wl.to_float(s2d.to_host(y), dtype)
+    assert np.isfinite(got).all()
+    assert rel_err(got, wl.to_float(ref, dtype)) <= TOL[dtype]
+    assert not np.array_equal(s2d.to_host(y), s2d.to_host(y_plain))         # the mode does change the result
+    if W <= 1024 and (N <= 16 or W <= 256):
+        grads = s2d.scan2d_bwd(*args, d["dy"], flags=s2d.FLAG_IDENTITY_CELLS)
+        torch.cuda.synchronize()
+        refs = oracle.scan2d_bwd_skip(clean["x"], clean["delta"], clean["A"], clean["Bm"], clean["Cm"], clean["Dskip"],
+                                      clean["mask"], clean["dy"], dtype=dtype)
+        m4 = np.broadcast_to(clean["mask"][:, None] != 0, got.shape)
+        for k, (name, g, r) in enumerate(zip(GRADS, grads, refs)):
+            g = s2d.to_host(g)
+            gv = wl.to_float(g, dtype) if k < 2 else g.astype(np.float64)
+            rv = wl.to_float(r, dtype) if k < 2 else r.astype(np.float64)
+            assert np.isfinite(gv).all(), name
+            tol = TOL[dtype] if k < 2 else (1e-4 if dtype == wl.F32 else 2e-2)
+            assert rel_err(gv, rv) <= tol, f"{name}: rel err {rel_err(gv, rv):.3e}"
+            if k < 2:
+                assert not gv[m4].any(), name                                # dx and ddelta are exactly 0 under the mask
+
+
+def test_identity_cells_with_softplus_step(s2d):
+    import torch
+    w = wl.Workload("skipsp", 2, 6, 16, 18, 75, wl.F32, mask_frac=0.4, backward=True)
+    inp = _softplus_inputs(w, seed=22)
+    d = s2d.to_device(inp, wl.F32)
+    db = torch.from_numpy(inp["delta_bias"]).cuda()
+    y = s2d.scan2d_fwd_softplus(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], flags=s2d.FLAG_IDENTITY_CELLS)
+    g = s2d.scan2d_bwd_softplus(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["dy"], flags=s2d.FLAG_IDENTITY_CELLS)
+    torch.cuda.synchronize()
+    step = np.logaddexp(0.0, inp["delta"].astype(np.float64) + inp["delta_bias"][None, :, None, None])
+    ref = oracle.scan2d_fwd_skip(inp["x"].astype(np.float64), step, inp["A"], inp["Bm"].astype(np.float64), inp["Cm"].astype(np.float64),
+                                 inp["Dskip"], inp["mask"], dtype=oracle.F64)
+    assert rel_err(s2d.to_host(y), ref) <= 1e-4
+    m4 = np.broadcast_to(inp["mask"][:, None] != 0, ref.shape)
+    assert not s2d.to_host(g[1])[m4].any()                                   # ddelta_raw under the mask
+    refs = oracle.scan2d_bwd_skip(inp["x"].astype(np.float64), step, inp["A"], inp["Bm"].astype(np.float64), inp["Cm"].astype(np.float64),
+                                  inp["Dskip"], inp["mask"], inp["dy"].astype(np.float64), dtype=oracle.F64)
+    from scipy.special import expit
+    t = inp["delta"].astype(np.float64) + inp["delta_bias"][None, :, None, None]
+    assert rel_err(s2d.to_host(g[0]), refs[0]) <= 1e-4
+    assert rel_err(s2d.to_host(g[1]), refs[1] * expit(t)) <= 1e-4
+    assert rel_err(s2d.to_host(g[3]), refs[2]) <= 1e-4
+
+
 def test_forward_and_backward_replay_from_a_hip_graph(s2d):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so its calls can be captured; every replay must equal the eager result bit for
