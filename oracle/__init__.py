@@ -236,3 +236,23 @@ def scan2d_fwd_skip(x, delta, A, Bm, Cm, Dskip=None, mask=None, dtype=F32, threa
 def scan2d_bwd_skip(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F32, threads=0):
     dx, dd, dA, dBm, dCm, dD = scan2d_bwd(x, _skip_step(delta, mask), A, Bm, Cm, Dskip, mask, dy, dtype=dtype, threads=threads)
     return dx, _skip_step(dd, mask), dA, dBm, dCm, dD
+
+
+# ------------------------------------------------------------------ columns first (scan order ablation)
+# The supplement ablates the order of the two scans.  Columns first: v[i,j] = a[i,j] v[i-1,j] + u[i,j] down each
+# column, then h[i,j] = a[i,j] h[i,j-1] + v[i,j] along each row, y = C h + D x.  Exchanging the roles of i and
+# j turns these two lines into Eq. 5 and Eq. 6, so this is the row-first scan of the transposed maps,
+# transposed back (tests/test_oracle_pins.py checks it against the two recurrences written as loops).
+
+def _tr(a):
+    return None if a is None else np.ascontiguousarray(np.swapaxes(a, -1, -2))
+
+
+def scan2d_fwd_columns_first(x, delta, A, Bm, Cm, Dskip=None, mask=None, dtype=F32, threads=0):
+    return _tr(scan2d_fwd(_tr(x), _tr(delta), A, _tr(Bm), _tr(Cm), Dskip, _tr(mask), dtype=dtype, threads=threads))
+
+
+def scan2d_bwd_columns_first(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F32, threads=0):
+    dx, dd, dA, dBm, dCm, dD = scan2d_bwd(_tr(x), _tr(delta), A, _tr(Bm), _tr(Cm), Dskip, _tr(mask), _tr(dy),
+                                          dtype=dtype, threads=threads)
+    return _tr(dx), _tr(dd), dA, _tr(dBm), _tr(dCm), dD

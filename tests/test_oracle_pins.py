@@ -618,3 +618,57 @@ def test_skip_mode_backward_matches_central_differences():
             assert not np.abs(fd[m4]).max() > 0          # the function does not depend on x or the step under the mask
             assert not got[m4].any()
         np.testing.assert_allclose(got, fd, rtol=2e-7, atol=2e-7 * max(1e-30, np.abs(fd).max()), err_msg=name)
+
+
+# ---------------------------------------------------------------------------- columns first (scan order ablation)
+
+def test_columns_first_is_the_two_recurrences_in_the_other_order():
+    """v[i,j] = a v[i-1,j] + u, then h[i,j] = a h[i,j-1] + v, written as loops; equal to the row-first scan
+    when the decay does not depend on the position (the two scans then commute), different otherwise."""
+    rng = np.random.default_rng(71)
+    Bt, Dc, N, H, W = 2, 2, 3, 4, 5
+    x, delta, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    y = oracle.scan2d_fwd_columns_first(x, delta, A, Bm, Cm, Dskip, mask, dtype=F64)
+    want = np.zeros_like(y)
+    for b in range(Bt):
+        for c in range(Dc):
+            for n in range(N):
+                v = np.zeros((H, W))
+                h = np.zeros((H, W))
+                for i in range(H):
+                    for j in range(W):
+                        xe = 0.0 if mask[b, i, j] else x[b, c, i, j]
+                        a = np.exp(delta[b, c, i, j] * float(A[c, n]))
+                        u = delta[b, c, i, j] * Bm[b, n, i, j] * xe
+                        v[i, j] = a * (v[i - 1, j] if i > 0 else 0.0) + u
+                        h[i, j] = a * (h[i, j - 1] if j > 0 else 0.0) + v[i, j]
+                want[b, c] += Cm[b, n] * h
+            xe = np.where(mask[b] != 0, 0.0, x[b, c])
+            want[b, c] += float(Dskip[c]) * xe
+    np.testing.assert_allclose(y, want, rtol=1e-12, atol=1e-13)
+    assert np.abs(y - oracle.scan2d_fwd(x, delta, A, Bm, Cm, Dskip, mask, dtype=F64)).max() > 1e-3
+    const = np.full_like(delta, 0.37)                  # position-independent decay: the scans commute
+    np.testing.assert_allclose(oracle.scan2d_fwd_columns_first(x, const, A, Bm, Cm, Dskip, mask, dtype=F64),
+                               oracle.scan2d_fwd(x, const, A, Bm, Cm, Dskip, mask, dtype=F64), rtol=1e-12, atol=1e-13)
+
+
+def test_columns_first_backward_matches_central_differences():
+    rng = np.random.default_rng(73)
+    Bt, Dc, N, H, W = 1, 2, 2, 3, 4
+    x, delta, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    dy = rng.standard_normal(x.shape)
+
+    def f(x_=x, d_=delta, Bm_=Bm, Cm_=Cm):
+        return float(np.sum(dy * oracle.scan2d_fwd_columns_first(x_, d_, A, Bm_, Cm_, Dskip, mask, dtype=F64)))
+
+    dx, dd, dA, dBm, dCm, dD = oracle.scan2d_bwd_columns_first(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F64)
+    for name, arr, got in (("x_", x, dx), ("d_", delta, dd), ("Bm_", Bm, dBm), ("Cm_", Cm, dCm)):
+        fd = np.zeros(arr.shape)
+        for idx in np.ndindex(arr.shape):
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += 1e-6
+            lo[idx] -= 1e-6
+            fd[idx] = (f(**{name: hi}) - f(**{name: lo})) / 2e-6
+        if name == "x_":
+            fd[np.broadcast_to(mask[:, None] != 0, fd.shape)] = 0.0
+        np.testing.assert_allclose(got, fd, rtol=2e-7, atol=2e-7 * max(1e-30, np.abs(fd).max()), err_msg=name)
