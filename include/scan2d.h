@@ -73,12 +73,22 @@ enum { SCAN2D_F32 = 0, SCAN2D_BF16 = 1 };
  * cells (with the softplus step: ddelta_raw = 0).  Honoured by every forward and backward entry point.
  */
 enum { SCAN2D_FLAG_IDENTITY_CELLS = 1 };
+/*
+ * Scan order (desc.flags).  By default rows are scanned first, then columns (Eq. 5, then Eq. 6).  With
+ * SCAN2D_FLAG_COLUMNS_FIRST the order is the other one, the supplement's ablation of the scan order:
+ *     v[i,j] = a[i,j] * v[i-1,j] + u[i,j],    h[i,j] = a[i,j] * h[i,j-1] + v[i,j],    y = Cm . h + Dskip * x_eff
+ * (different from the default whenever the decay depends on the position).  Tensor layouts do not change.
+ * The library transposes the maps into the workspace, runs the row-first kernels on H and W exchanged and
+ * transposes the results back, so this order costs several passes over the tensors and a workspace of their
+ * size; scan2d_workspace_bytes accounts for it.  Honoured by every forward and backward entry point.
+ */
+enum { SCAN2D_FLAG_COLUMNS_FIRST = 2 };
 enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2, SCAN2D_PASS_BWD_SOFTPLUS = 3 };
 
 typedef struct {
     int32_t  Bt, Dc, H, W, N;  /* batch, channels, grid height, grid width, states: all >= 1, N <= 64 */
     int32_t  dtype;            /* SCAN2D_F32 or SCAN2D_BF16: type of x, delta, Bm, Cm, y, dy, dx, ddelta */
-    uint32_t flags;            /* 0 or SCAN2D_FLAG_IDENTITY_CELLS */
+    uint32_t flags;            /* 0 or a sum of SCAN2D_FLAG_IDENTITY_CELLS, SCAN2D_FLAG_COLUMNS_FIRST */
 } scan2d_desc;
 
 /*

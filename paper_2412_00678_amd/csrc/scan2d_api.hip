@@ -38,7 +38,7 @@ int check_desc(const scan2d_desc* d) {
     if (d == nullptr) return SCAN2D_ERR_NULL_POINTER;
     if (d->Bt < 1 || d->Dc < 1 || d->H < 1 || d->W < 1 || d->N < 1 || d->N > 64) return SCAN2D_ERR_BAD_SHAPE;
     if (d->dtype != SCAN2D_F32 && d->dtype != SCAN2D_BF16) return SCAN2D_ERR_BAD_DTYPE;
-    if ((d->flags & ~(uint32_t)SCAN2D_FLAG_IDENTITY_CELLS) != 0u) return SCAN2D_ERR_BAD_FLAGS;
+    if ((d->flags & ~(uint32_t)(SCAN2D_FLAG_IDENTITY_CELLS | SCAN2D_FLAG_COLUMNS_FIRST)) != 0u) return SCAN2D_ERR_BAD_FLAGS;
     // element counts must fit 63 bits, and one map's states must be addressable with 32-bit
     // lane offsets (fill_choice checks the exact span): N * H * W < 2^27 bounds it
     const double M = (double)d->Bt * d->Dc * d->H * d->W;
@@ -207,6 +207,77 @@ size_t fwd_workspace(const scan2d_desc* d, const FwdChoice& c) {
 using namespace scan2d;
 
 namespace {
+// ---- columns first: the same descriptor with H and W exchanged, and the transposed copies in the workspace
+bool columns_first(const scan2d_desc* d) { return (d->flags & SCAN2D_FLAG_COLUMNS_FIRST) != 0; }
+scan2d_desc swapped(const scan2d_desc* d) {
+    scan2d_desc t = *d;
+    t.H = d->W; t.W = d->H; t.flags = d->flags & ~(uint32_t)SCAN2D_FLAG_COLUMNS_FIRST;
+    return t;
+}
+struct Regions {                                 // byte offsets behind the inner call's own workspace
+    size_t x, delta, dy, dx, ddelta, Bm, Cm, dBm, dCm, mask, y, total;
+};
+Regions regions(const scan2d_desc* d, bool backward) {
+    const size_t e = d->dtype == SCAN2D_BF16 ? 2 : 4, HW = (size_t)d->H * d->W;
+    const size_t maps = align256((size_t)d->Bt * d->Dc * HW * e), st = align256((size_t)d->Bt * d->N * HW * e);
+    const size_t stf = align256((size_t)d->Bt * d->N * HW * 4), mk = align256((size_t)d->Bt * HW);
+    Regions r{};
+    size_t o = 0;
+    r.x = o; o += maps; r.delta = o; o += maps; r.Bm = o; o += st; r.Cm = o; o += st; r.mask = o; o += mk;
+    if (backward) { r.dy = o; o += maps; r.dx = o; o += maps; r.ddelta = o; o += maps; r.dBm = o; o += stf; r.dCm = o; o += stf; }
+    else { r.y = o; o += maps; }
+    r.total = o;
+    return r;
+}
+
+// Workspace of a forward call / of a backward call without the gate's own buffer; 0 = none, or no plan.
+size_t fwd_need(const scan2d_desc* d) {
+    if (columns_first(d)) {
+        const scan2d_desc t = swapped(d);
+        return align256(fwd_need(&t)) + regions(d, false).total;
+    }
+    FwdChoice ch;
+    if (choose_fwd(d, &ch) != SCAN2D_OK) return 0;
+    const size_t sk = skip_bytes(d);
+    return sk > 0 ? align256(fwd_workspace(d, ch)) + sk : fwd_workspace(d, ch);
+}
+size_t bwd_need(const scan2d_desc* d, bool softplus) {
+    if (columns_first(d)) {
+        const scan2d_desc t = swapped(d);
+        const size_t inner = bwd_need(&t, softplus);
+        return inner == 0 ? 0 : align256(inner) + regions(d, true).total;
+    }
+    const size_t inner = bwd_workspace_bytes(d, softplus);
+    return inner == 0 ? 0 : inner + skip_bytes(d);
+}
+
+int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, int softplus, const float* A,
+             const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+             void* y, void* workspace, size_t workspace_bytes, void* stream);
+
+int fwd_columns_first(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, int softplus,
+                      const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                      void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    const scan2d_desc t = swapped(desc);
+    const size_t inner = align256(fwd_need(&t));
+    const Regions r = regions(desc, false);
+    if (workspace == nullptr || workspace_bytes < inner + r.total) return SCAN2D_ERR_WORKSPACE_SMALL;
+    char* base = static_cast<char*>(workspace) + inner;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int e = desc->dtype == SCAN2D_BF16 ? 2 : 4;
+    const long long maps = (long long)desc->Bt * desc->Dc, planes = (long long)desc->Bt * desc->N;
+    int rc = transpose_launch(e, x, base + r.x, maps, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, delta, base + r.delta, maps, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, Bm, base + r.Bm, planes, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, Cm, base + r.Cm, planes, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK && mask != nullptr) rc = transpose_launch(1, mask, base + r.mask, desc->Bt, desc->H, desc->W, st);
+    if (rc != SCAN2D_OK) return rc;
+    rc = fwd_impl(&t, base + r.x, base + r.delta, delta_bias, softplus, A, base + r.Bm, base + r.Cm, Dskip,
+                  mask != nullptr ? reinterpret_cast<const uint8_t*>(base + r.mask) : nullptr, base + r.y, workspace, inner, stream);
+    if (rc != SCAN2D_OK) return rc;
+    return transpose_launch(e, base + r.y, y, maps, t.H, t.W, st);
+}
+
 int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, int softplus, const float* A,
              const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
              void* y, void* workspace, size_t workspace_bytes, void* stream) {
@@ -218,6 +289,8 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
+    if (columns_first(desc))
+        return fwd_columns_first(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, y, workspace, workspace_bytes, stream);
     FwdChoice ch;
     rc = choose_fwd(desc, &ch, softplus != 0, mask == nullptr || (desc->W % 4) == 0);
     if (rc != SCAN2D_OK) return rc;
@@ -262,6 +335,67 @@ extern "C" int scan2d_fwd_softplus(const scan2d_desc* desc, const void* x, const
 }
 
 namespace {
+// The backward of the scan proper: identity cells, sweeps, reductions.
+int bwd_core(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, bool softplus,
+             const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+             const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
+             float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = SCAN2D_OK;
+    const size_t sk = skip_bytes(desc);
+    if (sk > 0) {                // identity cells: the sweeps run on a copy of the step that is 0 under the mask
+        const size_t inner = bwd_workspace_bytes(desc, softplus);
+        if (inner == 0) return SCAN2D_ERR_BAD_SHAPE;
+        if (workspace == nullptr || workspace_bytes < inner + sk) return SCAN2D_ERR_WORKSPACE_SMALL;
+        if (mask != nullptr) {
+            void* step = static_cast<char*>(workspace) + inner;
+            rc = skip_step_launch(desc, delta, mask, softplus, step, static_cast<hipStream_t>(stream));
+            if (rc != SCAN2D_OK) return rc;
+            delta = step;
+        }
+        workspace_bytes = inner;
+    }
+    rc = bwd_launch(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
+                    dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    // identity cells: their step is the constant 0, so it has no gradient (with the softplus step the chain
+    // rule has already multiplied by the logistic function of -inf, which is 0)
+    if (rc == SCAN2D_OK && sk > 0 && mask != nullptr && !softplus)
+        rc = skip_grad_launch(desc, mask, ddelta, static_cast<hipStream_t>(stream));
+    return rc;
+}
+
+int bwd_columns_first(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, bool softplus,
+                      const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                      const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
+                      float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+    const scan2d_desc t = swapped(desc);
+    const size_t need = bwd_need(&t, softplus);
+    if (need == 0) return SCAN2D_ERR_BAD_SHAPE;
+    const size_t inner = align256(need);
+    const Regions r = regions(desc, true);
+    if (workspace == nullptr || workspace_bytes < inner + r.total) return SCAN2D_ERR_WORKSPACE_SMALL;
+    char* base = static_cast<char*>(workspace) + inner;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int e = desc->dtype == SCAN2D_BF16 ? 2 : 4;
+    const long long maps = (long long)desc->Bt * desc->Dc, planes = (long long)desc->Bt * desc->N;
+    int rc = transpose_launch(e, x, base + r.x, maps, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, delta, base + r.delta, maps, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, dy, base + r.dy, maps, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, Bm, base + r.Bm, planes, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, Cm, base + r.Cm, planes, desc->H, desc->W, st);
+    if (rc == SCAN2D_OK && mask != nullptr) rc = transpose_launch(1, mask, base + r.mask, desc->Bt, desc->H, desc->W, st);
+    if (rc != SCAN2D_OK) return rc;
+    rc = bwd_core(&t, base + r.x, base + r.delta, delta_bias, softplus, A, base + r.Bm, base + r.Cm, Dskip,
+                  mask != nullptr ? reinterpret_cast<const uint8_t*>(base + r.mask) : nullptr, base + r.dy, base + r.dx,
+                  base + r.ddelta, ddelta_bias, dA, reinterpret_cast<float*>(base + r.dBm), reinterpret_cast<float*>(base + r.dCm),
+                  dDskip, workspace, inner, stream);
+    if (rc != SCAN2D_OK) return rc;
+    rc = transpose_launch(e, base + r.dx, dx, maps, t.H, t.W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(e, base + r.ddelta, ddelta, maps, t.H, t.W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(4, base + r.dBm, dBm, planes, t.H, t.W, st);
+    if (rc == SCAN2D_OK) rc = transpose_launch(4, base + r.dCm, dCm, planes, t.H, t.W, st);
+    return rc;
+}
+
 int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, bool softplus,
              const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
              const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
@@ -278,31 +412,16 @@ int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
-    const size_t sk = skip_bytes(desc);
-    if (sk > 0) {                // identity cells: the sweeps run on a copy of the step that is 0 under the mask
-        const size_t inner = bwd_workspace_bytes(desc, softplus);
-        if (inner == 0) return SCAN2D_ERR_BAD_SHAPE;
-        if (workspace == nullptr || workspace_bytes < inner + sk) return SCAN2D_ERR_WORKSPACE_SMALL;
-        if (mask != nullptr) {
-            void* step = static_cast<char*>(workspace) + inner;
-            rc = skip_step_launch(desc, delta, mask, softplus, step, static_cast<hipStream_t>(stream));
-            if (rc != SCAN2D_OK) return rc;
-            delta = step;
-        }
-        workspace_bytes = inner;
-    }
     if (z != nullptr) {          // output gate: dz, and dy * SiLU(z) in place of dy
         rc = gate_bwd_launch(desc, z, y_scan, dy, dyg, dz, static_cast<hipStream_t>(stream));
         if (rc != SCAN2D_OK) return rc;
         dy = dyg;
     }
-    rc = bwd_launch(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
-                    dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
-    // identity cells: their step is the constant 0, so it has no gradient (with the softplus step the chain
-    // rule has already multiplied by the logistic function of -inf, which is 0)
-    if (rc == SCAN2D_OK && sk > 0 && mask != nullptr && !softplus)
-        rc = skip_grad_launch(desc, mask, ddelta, static_cast<hipStream_t>(stream));
-    return rc;
+    if (columns_first(desc))
+        return bwd_columns_first(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm,
+                                 dCm, dDskip, workspace, workspace_bytes, stream);
+    return bwd_core(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
+                    dDskip, workspace, workspace_bytes, stream);
 }
 }  // namespace
 
@@ -345,7 +464,7 @@ extern "C" int scan2d_bwd_softplus_gated(const scan2d_desc* desc, const void* x,
     if (rc != SCAN2D_OK) return rc;
     if (!z || !y_scan || !dy || !dz) return SCAN2D_ERR_NULL_POINTER;
     if (!aligned16(z) || !aligned16(y_scan) || !aligned16(dy) || !aligned16(dz) || !aligned16(workspace)) return SCAN2D_ERR_MISALIGNED;
-    const size_t inner = bwd_workspace_bytes(desc, true) + skip_bytes(desc);
+    const size_t inner = align256(bwd_need(desc, true));
     if (inner == 0) return SCAN2D_ERR_BAD_SHAPE;
     if (workspace == nullptr || workspace_bytes < inner + gate_bwd_bytes(desc)) return SCAN2D_ERR_WORKSPACE_SMALL;
     // the gate only changes dy: dy * SiLU(z) goes behind the scan's own workspace, dz is final
@@ -356,16 +475,11 @@ extern "C" int scan2d_bwd_softplus_gated(const scan2d_desc* desc, const void* x,
 
 extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
     if (check_desc(desc) != SCAN2D_OK) return 0;
-    if (pass == SCAN2D_PASS_FWD) {
-        FwdChoice ch;
-        if (choose_fwd(desc, &ch) != SCAN2D_OK) return 0;
-        const size_t sk = skip_bytes(desc);
-        return sk > 0 ? align256(fwd_workspace(desc, ch)) + sk : fwd_workspace(desc, ch);
-    }
+    if (pass == SCAN2D_PASS_FWD) return fwd_need(desc);
     if (pass == SCAN2D_PASS_BWD || pass == SCAN2D_PASS_BWD_SOFTPLUS || pass == SCAN2D_PASS_BWD_GATED) {
-        const size_t inner = bwd_workspace_bytes(desc, pass != SCAN2D_PASS_BWD);
+        const size_t inner = bwd_need(desc, pass != SCAN2D_PASS_BWD);
         if (inner == 0) return 0;
-        return inner + skip_bytes(desc) + (pass == SCAN2D_PASS_BWD_GATED ? gate_bwd_bytes(desc) : 0);
+        return pass == SCAN2D_PASS_BWD_GATED ? align256(inner) + gate_bwd_bytes(desc) : inner;
     }
     return 0;
 }
@@ -395,7 +509,7 @@ extern "C" const char* scan2d_strerror(int code) {
         case SCAN2D_ERR_NULL_POINTER: return "a required pointer is NULL (or dDskip/Dskip do not match)";
         case SCAN2D_ERR_BAD_SHAPE: return "bad shape: every dimension must be >= 1, N <= 64, N*H*W < 2^27";
         case SCAN2D_ERR_BAD_DTYPE: return "dtype must be SCAN2D_F32 or SCAN2D_BF16";
-        case SCAN2D_ERR_BAD_FLAGS: return "flags holds a bit other than SCAN2D_FLAG_IDENTITY_CELLS";
+        case SCAN2D_ERR_BAD_FLAGS: return "flags holds a bit other than SCAN2D_FLAG_IDENTITY_CELLS and SCAN2D_FLAG_COLUMNS_FIRST";
         case SCAN2D_ERR_WORKSPACE_SMALL: return "workspace is NULL or smaller than scan2d_workspace_bytes()";
         case SCAN2D_ERR_MISALIGNED: return "a base pointer is not 16-byte aligned";
         case SCAN2D_ERR_LAUNCH_FAILED: return "the HIP runtime refused a kernel launch";

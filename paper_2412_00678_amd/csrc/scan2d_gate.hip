@@ -108,6 +108,30 @@ __global__ __launch_bounds__(256) void scan2d_skip_grad_kernel(const uint8_t* __
     }
 }
 
+// dst[p][j][i] = src[p][i][j]; one workgroup (32 x 8 threads) per 32 x 32 tile, tiles of all planes in one 1D grid.
+template <typename E>
+__global__ __launch_bounds__(256) void scan2d_transpose_kernel(const E* __restrict__ src, E* __restrict__ dst, int H, int W,
+                                                               unsigned tiles_w, unsigned tiles_h) {
+    __shared__ E tile[32][33];
+    const unsigned per = tiles_w * tiles_h;
+    const size_t plane = blockIdx.x / per;
+    const unsigned rem = blockIdx.x % per, th = rem / tiles_w, tw = rem % tiles_w;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const E* s = src + plane * (size_t)H * W;
+    E* d = dst + plane * (size_t)H * W;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int row = (int)th * 32 + ty + 8 * k, col = (int)tw * 32 + tx;
+        if (row < H && col < W) tile[ty + 8 * k][tx] = s[(size_t)row * W + col];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int orow = (int)tw * 32 + ty + 8 * k, ocol = (int)th * 32 + tx;      // row of dst = column of src
+        if (orow < W && ocol < H) d[(size_t)orow * H + ocol] = tile[tx][ty + 8 * k];
+    }
+}
+
 unsigned gate_blocks(size_t n) { return (unsigned)std::min<size_t>((n / 4 + 255) / 256 + 1, 256 * 16); }
 
 }  // namespace
@@ -178,6 +202,23 @@ int skip_grad_launch(const scan2d_desc* d, const uint8_t* mask, void* ddelta, hi
     else
         hipLaunchKernelGGL(scan2d_skip_grad_kernel<float>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream, mask,
                            static_cast<float*>(ddelta), HW, d->Dc, chunks);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+int transpose_launch(int elem_bytes, const void* src, void* dst, long long planes, int H, int W, hipStream_t stream) {
+    const unsigned tw = (unsigned)((W + 31) / 32), th = (unsigned)((H + 31) / 32);
+    const long long blocks = planes * tw * th;
+    if (blocks > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    (void)hipGetLastError();
+    if (elem_bytes == 4)
+        hipLaunchKernelGGL(scan2d_transpose_kernel<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), H, W, tw, th);
+    else if (elem_bytes == 2)
+        hipLaunchKernelGGL(scan2d_transpose_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), H, W, tw, th);
+    else
+        hipLaunchKernelGGL(scan2d_transpose_kernel<uint8_t>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst), H, W, tw, th);
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
 

@@ -32,4 +32,9 @@ int skip_step_launch(const scan2d_desc* d, const void* delta, const uint8_t* mas
 // ddelta = 0 under the mask, in place (the step of an identity cell is a constant).
 int skip_grad_launch(const scan2d_desc* d, const uint8_t* mask, void* ddelta, hipStream_t stream);
 
+// Columns first (SCAN2D_FLAG_COLUMNS_FIRST, the supplement's ablation of the scan order): the scan of the
+// transposed maps, transposed back.  dst[p][j][i] = src[p][i][j] for `planes` planes of H x W elements of
+// 1, 2 or 4 bytes; 32 x 32 tiles through LDS.
+int transpose_launch(int elem_bytes, const void* src, void* dst, long long planes, int H, int W, hipStream_t stream);
+
 }  // namespace scan2d

@@ -99,6 +99,7 @@ def _check(t: Optional[torch.Tensor], name: str, dtype, shape, optional=False):
 
 
 FLAG_IDENTITY_CELLS = 1      # masked cells pass the state through unchanged (step 0) instead of only holding x = 0
+FLAG_COLUMNS_FIRST = 2       # columns are scanned first, then rows
 
 
 def make_desc(x: torch.Tensor, A: torch.Tensor, flags: int = 0) -> Desc:

@@ -54,8 +54,8 @@ def test_descriptor_validation_needs_no_device(lib):
     assert call(D(1, 1, 1, -3, 4, 0, 0)) == -2
     assert call(D(1, 1, 4096, 4096, 16, 0, 0)) == -2          # N*H*W >= 2^27
     assert call(D(1, 1, 8, 8, 4, 7, 0)) == -3
-    assert call(D(1, 1, 8, 8, 4, 0, 2)) == -4                    # an unknown flag bit
-    assert call(D(1, 1, 8, 8, 4, 0, 1)) != -4                    # SCAN2D_FLAG_IDENTITY_CELLS
+    assert call(D(1, 1, 8, 8, 4, 0, 4)) == -4                    # an unknown flag bit
+    assert call(D(1, 1, 8, 8, 4, 0, 3)) != -4                    # SCAN2D_FLAG_IDENTITY_CELLS | SCAN2D_FLAG_COLUMNS_FIRST
     assert call(D(1, 1, 8, 8, 4, 0, 0)) == -1                  # NULL tensors
     assert lib.lib.scan2d_fwd(None, *([None] * 8), None, 0, None) == -1
     bwd = lambda d: lib.lib.scan2d_bwd(ctypes.byref(d), *([None] * 14), None, 0, None)
@@ -88,6 +88,13 @@ def test_workspace_query(lib):
         extra = ((2 * 8 * 20 * 40 * 4 + 255) // 256) * 256 + 256      # and room behind it for reads past the last row
         assert lib.workspace_bytes(d, lib.PASS_BWD_SOFTPLUS) == lib.workspace_bytes(d, lib.PASS_BWD) + extra
     assert lib.workspace_bytes(lib.Desc(1, 2, 8, 3000, 4, 0, 0), lib.PASS_BWD_GATED) == 0      # no backward plan for this width
+    # columns first: the transposed copies (x, delta, y; Bm, Cm; mask) behind the workspace of the swapped shape;
+    # identity cells: one more copy of the step
+    r256 = lambda v: (v + 255) // 256 * 256
+    d = lib.Desc(2, 8, 20, 40, 16, 0, lib.FLAG_COLUMNS_FIRST)
+    assert lib.workspace_bytes(d, lib.PASS_FWD) == 3 * r256(2 * 8 * 800 * 4) + 2 * r256(2 * 16 * 800 * 4) + r256(2 * 800)
+    assert lib.workspace_bytes(lib.Desc(2, 8, 20, 40, 16, 1, lib.FLAG_IDENTITY_CELLS), lib.PASS_FWD) == r256(2 * 8 * 800 * 2)
+    assert lib.workspace_bytes(lib.Desc(1, 2, 3000, 8, 4, 0, lib.FLAG_COLUMNS_FIRST), lib.PASS_BWD) == 0   # 3000 columns after the swap
 
 
 # ------------------------------------------------------------------ host logic: variant choice and launch plans

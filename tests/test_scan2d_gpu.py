@@ -685,6 +685,84 @@ def test_identity_cells_with_softplus_step(s2d):
     assert rel_err(s2d.to_host(g[3]), refs[2]) <= 1e-4
 
 
+# ------------------------------------------------------------------ columns first (scan order ablation)
+
+CF_SHAPES = [
+    (2, 5, 16, 21, 64, wl.F32, 0.3), (2, 5, 16, 14, 9, wl.BF16, 0.3), (1, 3, 16, 70, 33, wl.BF16, 0.4),
+    (1, 4, 5, 45, 7, wl.F32, 0.0), (1, 3, 16, 130, 190, wl.F32, 0.3), (3, 2, 4, 1, 50, wl.F32, 0.3), (1, 2, 8, 37, 1, wl.F32, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape", CF_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_columns_first_forward_and_backward_match_oracle(s2d, shape):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("cf", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True)
+    inp = wl.make_inputs(w, seed=31)
+    print(f"columns first case Bt={Bt} Dc={Dc} N={N} H={H} W={W} dtype={dtype}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    args = (d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
+    y = s2d.scan2d_fwd(*args, flags=s2d.FLAG_COLUMNS_FIRST)
+    torch.cuda.synchronize()
+    ref = oracle.scan2d_fwd_columns_first(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"], inp["mask"], dtype=dtype)
+    got = wl.to_float(s2d.to_host(y), dtype)
+    assert np.isfinite(got).all()
+    assert rel_err(got, wl.to_float(ref, dtype)) <= TOL[dtype]
+    grads = s2d.scan2d_bwd(*args, d["dy"], flags=s2d.FLAG_COLUMNS_FIRST)
+    torch.cuda.synchronize()
+    refs = oracle.scan2d_bwd_columns_first(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"], inp["mask"],
+                                           inp["dy"], dtype=dtype)
+    for k, (name, g, r) in enumerate(zip(GRADS, grads, refs)):
+        if r is None:
+            assert g is None
+            continue
+        g = s2d.to_host(g)
+        gv = wl.to_float(g, dtype) if k < 2 else g.astype(np.float64)
+        rv = wl.to_float(r, dtype) if k < 2 else r.astype(np.float64)
+        assert np.isfinite(gv).all(), name
+        tol = TOL[dtype] if k < 2 else (1e-4 if dtype == wl.F32 else 2e-2)
+        assert rel_err(gv, rv) <= tol, f"{name}: rel err {rel_err(gv, rv):.3e}"
+
+
+def test_columns_first_with_identity_cells_softplus_and_gate(s2d):
+    """All the options at once against the oracle's compositions: columns first = the transposed problem."""
+    import torch
+    w = wl.Workload("cfall", 2, 4, 16, 19, 42, wl.F32, mask_frac=0.4, backward=True)
+    inp = _gated_inputs(w, seed=32)
+    d = s2d.to_device(inp, wl.F32)
+    db = torch.from_numpy(inp["delta_bias"]).cuda()
+    fl = s2d.FLAG_COLUMNS_FIRST | s2d.FLAG_IDENTITY_CELLS
+    ys, y = s2d.scan2d_fwd_softplus_gated(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["z"], flags=fl)
+    g = s2d.scan2d_bwd_softplus_gated(d["x"], d["delta"], db, d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["z"], ys, d["dy"], flags=fl)
+    torch.cuda.synchronize()
+    tr = lambda a: None if a is None else np.ascontiguousarray(np.swapaxes(a, -1, -2))
+    m4 = np.broadcast_to(inp["mask"][:, None] != 0, inp["x"].shape)
+    raw = inp["delta"].astype(np.float64).copy()
+    step = np.logaddexp(0.0, raw + inp["delta_bias"][None, :, None, None])
+    step[m4] = 0.0
+    f64 = lambda a: a.astype(np.float64)
+    y_scan = tr(oracle.scan2d_fwd(tr(f64(inp["x"])), tr(step), inp["A"], tr(f64(inp["Bm"])), tr(f64(inp["Cm"])), inp["Dskip"], tr(inp["mask"]),
+                                  dtype=oracle.F64))
+    z = f64(inp["z"])
+    sg = 1.0 / (1.0 + np.exp(-z))
+    assert rel_err(s2d.to_host(ys), y_scan) <= 1e-4
+    assert rel_err(s2d.to_host(y), y_scan * z * sg) <= 1e-4
+    dyg = f64(inp["dy"]) * z * sg
+    refs = oracle.scan2d_bwd(tr(f64(inp["x"])), tr(step), inp["A"], tr(f64(inp["Bm"])), tr(f64(inp["Cm"])), inp["Dskip"], tr(inp["mask"]),
+                             tr(dyg), dtype=oracle.F64)
+    from scipy.special import expit
+    draw = tr(refs[1]) * expit(raw + inp["delta_bias"][None, :, None, None])
+    draw[m4] = 0.0
+    assert rel_err(s2d.to_host(g[0]), tr(refs[0])) <= 1e-4                   # dx
+    assert rel_err(s2d.to_host(g[1]), draw) <= 1e-4                          # ddelta_raw
+    assert not s2d.to_host(g[1])[m4].any()
+    assert rel_err(s2d.to_host(g[2]), draw.sum(axis=(0, 2, 3))) <= 1e-4      # ddelta_bias
+    assert rel_err(s2d.to_host(g[3]), refs[2]) <= 1e-4                       # dA
+    assert rel_err(s2d.to_host(g[4]), tr(refs[3])) <= 1e-4                   # dBm
+    assert rel_err(s2d.to_host(g[5]), tr(refs[4])) <= 1e-4                   # dCm
+    assert rel_err(s2d.to_host(g[7]), f64(inp["dy"]) * y_scan * sg * (1.0 + z * (1.0 - sg))) <= 1e-4   # dz
+
+
 def test_forward_and_backward_replay_from_a_hip_graph(s2d):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so its calls can be captured; every replay must equal the eager result bit for
