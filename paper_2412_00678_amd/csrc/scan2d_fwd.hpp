@@ -66,9 +66,10 @@ struct FwdArgs {
 // discarded.  A lane that straddles the end of the row reads on into the next row (or zeros past the
 // end of the tensor: the buffer descriptors carry the exact size): those cells sit to the right of
 // every real column, so what they hold reaches no output (the row recurrence only runs rightwards,
-// the column recurrence stays in its column), and they are never stored.  Buffer loads of dwords want
-// 4-byte aligned addresses: always so for fp32 rows, for bf16 rows of even width, and for mask rows when
-// W is a multiple of 4 (MA).  The instantiations with MA = false request the aligned dwords around a
+// the column recurrence stays in its column), and they are never stored.  Buffer loads of dwords ignore
+// the two low bits of the offset (measured: loads at other offsets return the dword below), so they need
+// offsets that are multiples of 4 bytes: always so for fp32 rows, for bf16 rows of even width, and for mask
+// rows when W is a multiple of 4 (MA).  The instantiations with MA = false request the aligned dwords around a
 // lane's mask bytes and shift them into place (v_alignbyte_b32) where the row is unpacked - not where
 // it is requested, which would wait for the load at once.  Without FAST (maps wider than one panel)
 // every element access is guarded.
