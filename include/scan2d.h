@@ -207,7 +207,9 @@ size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass);
  * the library would use for this descriptor and pass (kernel form, lane-group width LG, columns K
  * and states NW per lane, wavefronts per workgroup, rows per barrier or per band, channels per
  * workgroup, workgroups, dynamic LDS bytes, workspace bytes) into `text` (host memory, at most
- * `text_bytes` bytes including the terminating 0).  Touches no device memory and enqueues nothing.
+ * `text_bytes` bytes including the terminating 0).  The workspace figure is that of the scan kernels alone
+ * (without the buffers of the gate, the identity cells and the columns-first order); with
+ * SCAN2D_FLAG_COLUMNS_FIRST the plan is that of the transposed maps.  Touches no device memory and enqueues nothing.
  * Returns SCAN2D_OK, or the error code the corresponding call would return for this descriptor.
  */
 int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* text, size_t text_bytes);

@@ -489,6 +489,13 @@ extern "C" int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* tex
     text[0] = 0;
     int rc = check_desc(desc);
     if (rc != SCAN2D_OK) return rc;
+    if (columns_first(desc)) {                   // the plan of the kernels that run: those of the transposed maps
+        const scan2d_desc t = swapped(desc);
+        const int n = std::snprintf(text, text_bytes, "columns-first(transposed) ");
+        if (n < 0 || (size_t)n >= text_bytes) return SCAN2D_OK;
+        return scan2d_describe_plan(&t, pass, text + n, text_bytes - (size_t)n);
+    }
+    if (pass == SCAN2D_PASS_BWD_SOFTPLUS || pass == SCAN2D_PASS_BWD_GATED) pass = SCAN2D_PASS_BWD;   // the same sweeps
     if (pass == SCAN2D_PASS_FWD) {
         FwdChoice ch;
         rc = choose_fwd(desc, &ch);
