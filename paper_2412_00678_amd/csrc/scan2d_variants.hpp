@@ -27,14 +27,8 @@ namespace scan2d {
 // Variants that also exist for N not divisible by NW (the last lane group idles some states).
 #define SCAN2D_FWD_RAGGED_VARIANTS(X) X(16, 4, 4, 4) X(16, 8, 4, 4) X(16, 12, 4, 4) X(16, 16, 4, 4)
 
-// Variants that also exist with guarded element-wise accesses (W not a multiple of K, or rows
-// that do not start 4-byte aligned).
-#define SCAN2D_FWD_GUARDED_VARIANTS(X)                                          \
-    X(16, 4, 1, 4) X(16, 4, 2, 4) X(16, 4, 4, 4) X(16, 4, 8, 4) X(16, 4, 16, 4) \
-    X(64, 4, 1, 4) X(64, 4, 2, 4) X(64, 4, 4, 4) X(64, 4, 8, 4) X(64, 4, 16, 4) \
-    X(64, 4, 1, 8) X(64, 4, 2, 8) X(64, 4, 1, 16)
-
-// Variants that also exist for maps wider than one panel (guarded accesses, any W).
+// Variants that also exist for maps wider than one panel (guarded accesses, any W); single-panel maps
+// always take the unguarded variants.
 #define SCAN2D_FWD_MULTI_VARIANTS(X)                                            \
     X(64, 4, 1, 4) X(64, 4, 2, 4) X(64, 4, 4, 4) X(64, 4, 8, 4) X(64, 4, 16, 4) \
     X(64, 4, 1, 8) X(64, 4, 2, 8) X(64, 4, 1, 16) X(16, 4, 4, 4)
@@ -79,15 +73,11 @@ inline FwdKernel lookup_fwd_kernel(int LG, int K, int NW, int waves, bool exact,
     SCAN2D_FWD_RAGGED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
 #define SCAN2D_X(lg, k, nw, wv) \
-    if (exact && !fast && !multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, false, SP>;
-    SCAN2D_FWD_GUARDED_VARIANTS(SCAN2D_X)
-#undef SCAN2D_X
-#define SCAN2D_X(lg, k, nw, wv) \
     if (exact && !fast && multi && LG == lg && K == k && NW == nw && waves == wv) return scan2d_fwd_kernel<T, lg, k, nw, wv, true, false, true, SP>;
     SCAN2D_FWD_MULTI_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
-    if (!exact && !fast && LG == 16 && K == 4 && NW == 4 && waves == 4)
-        return multi ? scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, true, SP> : scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, false, SP>;
+    if (!exact && !fast && multi && LG == 16 && K == 4 && NW == 4 && waves == 4)
+        return scan2d_fwd_kernel<T, 16, 4, 4, 4, false, false, true, SP>;
     return nullptr;
 }
 
