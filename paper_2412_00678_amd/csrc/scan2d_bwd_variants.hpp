@@ -11,7 +11,7 @@ namespace scan2d {
 #define SCAN2D_BWD_VARIANTS(X)                                             \
     X(16, 4, 1, 4, 4, true) X(16, 8, 1, 4, 4, true) X(16, 12, 1, 4, 4, false) X(16, 16, 1, 4, 2, true) \
     X(16, 4, 4, 4, 2, true) X(16, 8, 4, 4, 1, true)                                                   \
-    X(64, 4, 2, 8, 4, false) X(64, 8, 2, 8, 2, true) X(64, 16, 4, 4, 1, true)                           \
+    X(64, 4, 2, 8, 4, false) X(64, 8, 2, 8, 2, false) X(64, 16, 4, 4, 1, false)                           \
     X(64, 4, 4, 16, 2, false) X(64, 8, 4, 16, 1, false) X(64, 4, 1, 16, 2, false)
 
 using BwdKernel = void (*)(const BwdArgs);
