@@ -94,14 +94,15 @@ bool fill_choice(const scan2d_desc* d, int LG, int K, int NW, int waves, int rpb
     c.kernel = lookup(d->dtype, LG, K, NW, waves, c.exact, c.fast, c.multi, sp, ma, ua);
     if (c.kernel == nullptr) return false;
     // LDS for the partial sums: 2 buffers x RPB rows x (threads * K) floats.  Few large maps (one
-    // workgroup per CU at most) can afford 64 KB; otherwise stay near 24 KB so that several
-    // workgroups fit a CU.
+    // workgroup per CU at most) can afford 128 KB (8 rows per barrier measured 1-3 % faster than 4 there);
+    // otherwise stay near 24 KB so that several workgroups fit a CU.
     const size_t row_bytes = (size_t)waves * 64 * K * sizeof(float);
     const double wgs = std::ceil((double)d->Bt * d->Dc / c.MPW);
-    const size_t budget = wgs <= 256.0 ? 65536 : 24576;
+    const size_t budget = wgs <= 256.0 ? 131072 : 24576;
     c.RPB = 1;
     if (c.NG > 1) {
-        if (rpb == 1 || rpb == 2 || rpb == 4) c.RPB = rpb;
+        if (rpb == 1 || rpb == 2 || rpb == 4 || rpb == 8) c.RPB = rpb;
+        else if (wgs <= 256.0 && 2 * 8 * row_bytes <= budget) c.RPB = 8;
         else if (2 * 4 * row_bytes <= budget) c.RPB = 4;
         else if (2 * 2 * row_bytes <= budget) c.RPB = 2;
     }

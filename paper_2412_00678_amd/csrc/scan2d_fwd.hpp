@@ -58,7 +58,7 @@ struct FwdArgs {
     int NG;              // lane groups per map = ceil(N / NW)
     int MPW;             // maps per workgroup = (lane groups per workgroup) / NG, >= 1
     int panels;          // ceil(W / (LG * K))
-    int RPB;             // rows between two workgroup barriers (1, 2 or 4); sizes the dynamic LDS
+    int RPB;             // rows between two workgroup barriers (1, 2, 4 or 8); sizes the dynamic LDS
 };
 
 // FAST (single-panel maps, any W): every lane reads its K columns with one wide buffer load per tensor.

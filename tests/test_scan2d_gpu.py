@@ -145,9 +145,10 @@ VARIANT_CASES = [
     ("32,4,1,8", (1, 3, 16, 13, 128)), ("32,4,2,4", (1, 5, 16, 13, 124)), ("32,4,4,4", (1, 5, 16, 13, 128)),
     ("32,8,1,8", (1, 3, 16, 13, 256)), ("32,8,2,4", (1, 3, 16, 13, 248)), ("32,8,2,8", (1, 5, 16, 13, 256)),
     ("32,8,4,4", (1, 5, 16, 13, 200)),
-    # rows between two barriers forced to 1, 2, 4 (H = 13, 21: short last batch)
+    # rows between two barriers forced to 1, 2, 4, 8 (H = 13, 21, 3: short last batch)
     ("32,8,1,8,1", (1, 3, 16, 13, 256)), ("64,4,2,8,2", (1, 3, 16, 13, 256)), ("16,4,4,4,4", (2, 5, 16, 21, 56)),
     ("16,12,2,4,2", (1, 6, 4, 13, 180)), ("64,4,2,8,4", (1, 3, 16, 2, 256)), ("64,4,1,16,4", (1, 2, 16, 7, 600)),
+    ("64,4,2,8,8", (1, 3, 16, 21, 256)), ("16,4,1,4,8", (1, 3, 16, 8, 64)), ("16,4,1,4,8", (2, 2, 16, 3, 60)),   # and 8
     # guarded (ragged W) and multi-panel forms of the K = 4 variants
     ("16,4,4", (1, 6, 16, 9, 61)), ("64,4,4", (1, 6, 16, 9, 203)), ("64,4,2", (1, 3, 4, 7, 777)),
     ("16,4,4", (1, 3, 16, 7, 150)), ("16,4,4", (1, 3, 10, 7, 150)), ("16,8,4", (1, 3, 10, 7, 128)),
