@@ -19,7 +19,7 @@ PROBE = os.path.join(HERE, "roofprobe")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-value",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-UNITS = ["scan2d_api.hip", "scan2d_gate.hip", "scan2d_fwd_f32.hip", "scan2d_fwd_bf16.hip", "scan2d_fwd_f32_sp.hip", "scan2d_fwd_bf16_sp.hip", "scan2d_fwd_f32_um.hip", "scan2d_fwd_bf16_um.hip", "scan2d_fwd_bf16_ua.hip", "scan2d_fwd_f32_sp_um.hip", "scan2d_fwd_bf16_sp_um.hip", "scan2d_fwd_bf16_sp_ua.hip",
+UNITS = ["scan2d_api.hip", "scan2d_elementwise.hip", "scan2d_fwd_f32.hip", "scan2d_fwd_bf16.hip", "scan2d_fwd_f32_sp.hip", "scan2d_fwd_bf16_sp.hip", "scan2d_fwd_f32_um.hip", "scan2d_fwd_bf16_um.hip", "scan2d_fwd_bf16_ua.hip", "scan2d_fwd_f32_sp_um.hip", "scan2d_fwd_bf16_sp_um.hip", "scan2d_fwd_bf16_sp_ua.hip",
          "scan2d_bwd.hip", "scan2d_bwd_f32.hip", "scan2d_bwd_bf16.hip", "scan2d_bwd_f32_sp.hip", "scan2d_bwd_bf16_sp.hip"]
 
 

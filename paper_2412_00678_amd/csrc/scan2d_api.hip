@@ -12,7 +12,7 @@
 
 #include "scan2d_variants.hpp"
 #include "scan2d_bwd.hpp"
-#include "scan2d_gate.hpp"
+#include "scan2d_elementwise.hpp"
 
 namespace scan2d {
 namespace {

@@ -1,5 +1,5 @@
-// Element-wise kernels of the output gate (see scan2d_gate.hpp).
-#include "scan2d_gate.hpp"
+// Element-wise kernels beside the scan kernels (see scan2d_elementwise.hpp).
+#include "scan2d_elementwise.hpp"
 
 #include <algorithm>
 

@@ -1,10 +1,12 @@
-// Output gate of the block, y = y_scan * SiLU(z) (2DMamba Sec. 3.2 / Fig. 2: the Mamba block with
-// its scan replaced by the 2D one): two element-wise kernels beside the scan kernels.
+// Element-wise kernels beside the scan kernels: the output gate of the block, identity cells, and the
+// transposes of the columns-first order.  What they have in common: the work is per position, not per
+// (position, state), so doing it inside the scan kernels would either be repeated by every lane group of
+// a map or cost the scan kernels registers and branches; they are bound by vector issue and registers, not
+// by HBM, while a pass over a map-sized tensor here runs at the HBM copy rate.
 //
-// The gate is not applied inside the scan kernels.  That form was built and measured: the scan
-// kernels are bound by vector issue rate and registers, not by HBM, and the extra ring of raw
-// registers for z cost them a wave of occupancy or more than the extra pass over y costs here,
-// where it runs at the HBM copy rate.
+// Output gate, y = y_scan * SiLU(z) (2DMamba Sec. 3.2 / Fig. 2: the Mamba block with its scan replaced by
+// the 2D one).  The gate inside the scan kernels was built and measured: the extra ring of raw registers
+// for z cost them a wave of occupancy, more than the extra pass over y costs here.
 #pragma once
 
 #include <hip/hip_runtime.h>
