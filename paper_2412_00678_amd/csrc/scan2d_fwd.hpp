@@ -339,13 +339,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                 if (rb == RPB - 1 || i == H - 1) {                         // uniform: batch complete
                     __syncthreads();
                     if (live) {
-                        for (int r = 0; r <= rb; ++r) {
-                            const float* base = buf + ((size_t)r * SLOTS + slot - sg) * PANEL;   // first group of this map
-                            T* yr = yrow - (size_t)(rb - r) * W;
-                            for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
-                                const int gc = panel * PANEL + col;
-                                if (gc < W) store_elem(yr + xlane + gc, sum_partials<PANEL>(base + col, NG));
-                            }
+                        // the (row, column) outputs of the batch are dealt out over all threads of the map, not row by
+                        // row: with fewer columns than threads a row would keep only the first lane groups busy
+                        const float* base0 = buf + (size_t)(slot - sg) * PANEL;       // first group of this map, first row
+                        for (int idx = sg * LG + l; idx < (rb + 1) * PANEL; idx += NG * LG) {
+                            const int r = idx / PANEL, col = idx - r * PANEL;
+                            const int gc = panel * PANEL + col;
+                            if (gc < W)
+                                store_elem(yrow - (size_t)(rb - r) * W + xlane + gc,
+                                           sum_partials<PANEL>(base0 + (size_t)r * SLOTS * PANEL + col, NG));
                         }
                     }
                     step += RPB - 1 - rb;                                  // a short last batch still ends its buffer
