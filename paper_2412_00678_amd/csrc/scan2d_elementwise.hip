@@ -83,6 +83,21 @@ __global__ __launch_bounds__(256) void scan2d_skip_step_kernel(const T* __restri
     const T* src = delta + map * HW;
     T* dst = out + map * HW;
     const size_t e0 = ((size_t)(blockIdx.x % chunks) * 256 + threadIdx.x) * 4;
+    if (e0 + 4 <= HW && (Elem<T>::kBytes == 4 || (HW & 1) == 0)) {      // four elements at once (maps stay 4-byte aligned)
+        constexpr int XW = words_of<T, 4>();
+        uint32_t r[XW], o[XW];
+        load_words<XW>(reinterpret_cast<const uint32_t*>(src + e0), r);
+#pragma unroll
+        for (int w = 0; w < XW; ++w) o[w] = 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t bits;
+            if constexpr (Elem<T>::kBytes == 4) bits = r[j]; else bits = (r[j >> 1] >> (16 * (j & 1))) & 0xffffu;
+            put_elem<T, 4>(o, j, m[e0 + j] != 0 ? fill_bits : bits);
+        }
+        store_words<XW>(reinterpret_cast<uint32_t*>(dst + e0), o);
+        return;
+    }
     for (size_t e = e0; e < e0 + 4 && e < HW; ++e) {
         T v = src[e];
         if (m[e] != 0) {
