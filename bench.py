@@ -67,13 +67,15 @@ def time_launches(fn, sets, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def bench_workload(s2d, w, steps, warmup, with_bwd):
+def bench_workload(s2d, w, steps, warmup, with_bwd, force_sets=None):
     import torch
     inp = wl.make_inputs(w, seed=0)
     set_bytes = w.fwd_bytes() + (w.bwd_bytes() if with_bwd else 0)
     nsets = int(min(16, max(2, np.ceil(1.2e9 / set_bytes))))
     free, _ = torch.cuda.mem_get_info()
     nsets = int(max(1, min(nsets, free // (4 * set_bytes))))
+    if force_sets:
+        nsets = int(force_sets)
     sets = device_sets(s2d, inp, w.dtype, nsets, with_bwd)
     desc = s2d.make_desc(sets[0]["x"], sets[0]["A"])
     wf = s2d.workspace_bytes(desc, s2d.PASS_FWD)

@@ -4,17 +4,61 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 
+#include <mutex>
+
 #include "scan2d_variants.hpp"
 #include "scan2d_bwd.hpp"
 #include "scan2d_elementwise.hpp"
+#include "scan2d_tuning.hpp"
 
 namespace scan2d {
+
+// ------------------------------------------------------------------ tuning overrides (see scan2d_tuning.hpp)
+namespace {
+TuneSlot g_tune[kTuneKinds];
+std::once_flag g_tune_env_once;
+
+void tune_read_env() {
+    static const char* const names[kTuneKinds] = {"SCAN2D_FWD_VARIANT", "SCAN2D_FWD_SHARED", "SCAN2D_BWD_VARIANT"};
+    for (int k = 0; k < kTuneKinds; ++k) {
+        const char* e = std::getenv(names[k]);
+        if (e == nullptr) continue;
+        int v[kTuneMaxValues] = {0, 0, 0, 0, 0};
+        const int n = std::sscanf(e, "%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4]);
+        if (n > 0) {
+            for (int i = 0; i < kTuneMaxValues; ++i) g_tune[k].v[i].store(v[i], std::memory_order_relaxed);
+            g_tune[k].n.store(n, std::memory_order_release);
+        }
+    }
+}
+}  // namespace
+
+TuneValues tune_get(int kind) {
+    std::call_once(g_tune_env_once, tune_read_env);
+    TuneValues t;
+    if (kind < 0 || kind >= kTuneKinds) return t;
+    t.n = g_tune[kind].n.load(std::memory_order_acquire);
+    for (int i = 0; i < kTuneMaxValues; ++i) t.v[i] = g_tune[kind].v[i].load(std::memory_order_relaxed);
+    return t;
+}
+
+void tune_set(int kind, const int* values, int n) {
+    std::call_once(g_tune_env_once, tune_read_env);
+    if (kind < 0 || kind >= kTuneKinds) return;
+    if (n < 0 || values == nullptr) n = 0;
+    if (n > kTuneMaxValues) n = kTuneMaxValues;
+    g_tune[kind].n.store(0, std::memory_order_release);
+    for (int i = 0; i < kTuneMaxValues; ++i) g_tune[kind].v[i].store(i < n ? values[i] : 0, std::memory_order_relaxed);
+    g_tune[kind].n.store(n, std::memory_order_release);
+}
+
 namespace {
 
 constexpr int kMaxDevices = 64;
@@ -57,6 +101,7 @@ struct FwdChoice {
     int RPB = 1;
     size_t lds_bytes = 0;
     int NG = 0, MPW = 0, panels = 0;
+    bool shared = false;          // the form that computes the per-position values once per map (scan2d_fwd_shared.hpp)
     FwdKernel kernel = nullptr;
 };
 
@@ -127,17 +172,51 @@ bool fill_small(const scan2d_desc* d, int KS, bool sp, FwdChoice* out) {
     return true;
 }
 
-// VGPRs of the compiled forward variants by (K, NW) and storage type, as the compiler reports
-// them for this source (VGPRs + AGPRs; more than 256 means one wave per SIMD).  Only used to rank variants;
-// `python -m paper_2412_00678_amd.fwd_regs_table` prints these rows for the current kernel source.
+// The form whose lane groups share the per-position work through LDS: single panel, N = NG * NW exactly,
+// whole maps per workgroup.
+struct V6 { int LG, K, NW, NG, waves, RPB; };
+#define SCAN2D_X(lg, k, nw, ng, wv, rpb) {lg, k, nw, ng, wv, rpb},
+const V6 kFwdSharedVariants[] = {SCAN2D_FWD_SHARED_VARIANTS(SCAN2D_X)};
+#undef SCAN2D_X
+
+bool fill_shared(const scan2d_desc* d, int LG, int K, int NW, int waves, int RPB, bool sp, FwdChoice* out) {
+    if (NW < 1 || LG < 16 || K < 4 || waves < 1 || RPB < 2) return false;
+    if (d->N % NW != 0 || d->W > LG * K) return false;
+    const int slots = waves * 64 / LG, NG = d->N / NW;
+    if (NG > slots || slots % NG != 0) return false;
+    FwdChoice c;
+    c.LG = LG; c.K = K; c.NW = NW; c.waves = waves; c.sp = sp; c.RPB = RPB;
+    c.exact = true; c.fast = true; c.multi = false; c.shared = true;
+    c.NG = NG; c.MPW = slots / NG; c.panels = 1;
+    const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
+    if (span >= 2147483648.0) return false;
+    const bool ua = d->dtype == SCAN2D_BF16 && (d->W % 2) != 0;
+    c.kernel = d->dtype == SCAN2D_BF16 ? fwd_shared_kernel_bf16(LG, K, NW, NG, waves, RPB, sp, ua)
+                                       : fwd_shared_kernel_f32(LG, K, NW, NG, waves, RPB, sp);
+    if (c.kernel == nullptr) return false;
+    const size_t panel = (size_t)LG * K;
+    c.lds_bytes = (2 * (size_t)c.MPW * RPB * 2 * panel + 2 * (size_t)RPB * slots * panel) * sizeof(float);
+    if (c.lds_bytes > 160 * 1024) return false;
+    *out = c;
+    return true;
+}
+
+// VGPRs + AGPRs of the compiled forward kernels (more than 256 means one wave per SIMD), used only to rank
+// variants.  The table is generated by the build from the compiler's resource-usage remarks for exactly the
+// kernels that are linked into this library.
+struct PlainRegs { int K, NW, b, f; };
+struct SharedRegs { int bf16, LG, K, NW, NG, waves, RPB, regs; };
+#include "scan2d_fwd_regs.inc"
+
 int fwd_regs(bool bf16, int K, int NW) {
-    struct R { int K, NW, b, f; };
-    static const R t[] = {{4, 1, 84, 116},   {4, 2, 115, 131},  {4, 4, 148, 172},  {4, 8, 168, 255}, {4, 16, 247, 336},
-                          {8, 1, 144, 127},  {8, 2, 163, 167},  {8, 4, 243, 258},  {8, 8, 314, 386},
-                          {12, 1, 157, 182}, {12, 2, 228, 253}, {12, 4, 256, 331},
-                          {16, 1, 200, 168}, {16, 2, 253, 265}, {16, 4, 338, 400}};
-    for (const R& r : t)
+    for (const PlainRegs& r : kPlainRegs)
         if (r.K == K && r.NW == NW) return bf16 ? r.b : r.f;
+    return 300;
+}
+int fwd_shared_regs(bool bf16, const V6& v) {
+    for (const SharedRegs& r : kSharedRegs)
+        if (r.bf16 == (bf16 ? 1 : 0) && r.LG == v.LG && r.K == v.K && r.NW == v.NW && r.NG == v.NG && r.waves == v.waves && r.RPB == v.RPB)
+            return r.regs;
     return 300;
 }
 
@@ -151,32 +230,48 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     const double maps = (double)d->Bt * d->Dc;
     const double wgs = std::ceil(maps / c.MPW);
     const double c_core = bf16 ? 10.5 : 8.5;
-    const double c_scan = c.LG == 64 ? 13.0 : (c.LG == 32 ? 12.0 : 9.0);
+    const double c_scan = (c.LG == 64 ? 13.0 : (c.LG == 32 ? 12.0 : 9.0)) + (c.NW == 1 ? 4.0 : 0.0);   // a lone recurrence pads its DPP wait states
     const double c_pos = bf16 ? 9.0 : 6.0;
     const double cols_t = std::max(1.0, (double)c.K / c.NG);
-    const double c_red = c.NG > 1 ? cols_t * (4.0 + 1.5 * c.NG) + 6.0 : 4.0;
-    double row = c.K * c.NW * c_core + c.NW * c_scan + c_pos * c.K + 35.0 + c_red;
+    double c_red = c.NG > 1 ? cols_t * (4.0 + 1.5 * c.NG) + 6.0 : 4.0;
+    // shared-producer form: the per-position work is done once per map, every cell is summed by one thread
+    double pos = c_pos * c.K;
+    if (c.shared) {
+        pos = (c_pos + 4.0) * c.K / c.NG + 4.0;
+        c_red = (double)c.K / c.NG * (c.NG + 6.0) + 4.0;
+    }
+    double row = c.K * c.NW * c_core + c.NW * c_scan + pos + (c.shared ? 20.0 : 35.0) + c_red;
     if (!c.fast) row *= 1.6;
     if (c.multi) row += 8.0 * c.NW;
     // the instantiations that compute the step need one or two VGPRs more, which matters at the 256 boundary
-    const double regs = fwd_regs(bf16, c.K, c.NW) + (c.sp ? 2 : 0);
+    const V6 v6{c.LG, c.K, c.NW, c.NG, c.waves, c.RPB};
+    const double regs = (c.shared ? fwd_shared_regs(bf16, v6) : fwd_regs(bf16, c.K, c.NW)) + (c.sp ? 2 : 0);
     const double occ = std::min(8.0, std::max(std::floor(512.0 / regs), c.waves / 4.0));
-    const double res_wg = 256.0 * std::max(1.0, std::floor(occ * 4.0 / c.waves));   // workgroups resident on the chip
+    double wg_cu = std::max(1.0, std::floor(occ * 4.0 / c.waves));                    // workgroups resident on a CU: registers ...
+    if (c.lds_bytes > 0) wg_cu = std::min(wg_cu, std::max(1.0, std::floor(163840.0 / (double)c.lds_bytes)));   // ... and LDS
+    const double res_wg = 256.0 * wg_cu;                                             // workgroups resident on the chip
     const double rounds = std::ceil(wgs / res_wg);
-    double wps = std::min(occ, wgs * c.waves / 1024.0 / rounds);
+    double wps = std::min(std::min(occ, wg_cu * c.waves / 4.0), wgs * c.waves / 1024.0 / rounds);
     if (rounds > 1.0) wps = std::max(wps, 1.0);                                      // several rounds: SIMDs are never empty
     const double steps = (double)d->H * c.panels * row;                              // instructions of one wave
     if (wps < 1.0) return steps * 8.0;                                               // a lone wave: its own critical path
-    const double eff = std::min(0.95, 0.30 + 0.20 * wps);
+    // measured issue efficiencies: the plain kernels keep gaining up to four waves per SIMD, the shared-producer
+    // kernels (fewer, longer dependent chains per row and an LDS hand-over) level off near 0.85
+    const double eff = c.shared ? std::min(0.85, 0.35 + 0.20 * wps) : std::min(0.95, 0.30 + 0.20 * wps);
     const double tail = wgs > res_wg ? rounds / (wgs / res_wg) : 1.0;
-    return wgs * c.waves * steps * 4.0 / (1024.0 * eff) * tail;
+    // the shared-producer kernels run about 15 % faster than this count predicts (measured on the benchmark
+    // shapes: fewer global loads per lane, no unpacking of x, step and mask in the scanning lanes)
+    return wgs * c.waves * steps * 4.0 / (1024.0 * eff) * tail * (c.shared ? 0.85 : 1.0);
 }
 
 // sp: pick the instantiation that computes the step itself
 int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = true) {
-    if (const char* env = std::getenv("SCAN2D_FWD_VARIANT")) {   // tuning aid: "LG,K,NW,WAVES[,RPB]"
-        int LG = 0, K = 0, NW = 0, waves = 4, rpb = 0;
-        const int got = std::sscanf(env, "%d,%d,%d,%d,%d", &LG, &K, &NW, &waves, &rpb);
+    const TuneValues tsh = tune_get(kTuneShared);
+    if (tsh.n >= 5 && fill_shared(d, tsh.v[0], tsh.v[1], tsh.v[2], tsh.v[3], tsh.v[4], sp, out)) return SCAN2D_OK;
+    const TuneValues tf = tune_get(kTuneFwd);
+    if (tf.n >= 2) {                                               // tuning aid: LG,K,NW,WAVES[,RPB]
+        const int LG = tf.v[0], K = tf.v[1], NW = tf.v[2], waves = tf.n >= 4 ? tf.v[3] : 4, rpb = tf.n >= 5 ? tf.v[4] : 0;
+        const int got = tf.n;
         if (got >= 2 && LG == 16 && (K == 1 || K == 2) && fill_small(d, K, sp, out)) return SCAN2D_OK;
         if (got >= 3 && (LG == 16 || LG == 32 || LG == 64) && NW >= 1 && (waves == 4 || waves == 8 || waves == 16) &&
             fill_choice(d, LG, K, NW, waves, rpb, sp, ma, out))
@@ -194,9 +289,37 @@ int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = 
         const double cost = fwd_cost(d, c);
         if (!found || cost < best) { best = cost; *out = c; found = true; }
     }
+    if (!(tsh.n == 1 && tsh.v[0] == 0))                              // override "0": never the shared-producer form
+        for (const V6& v : kFwdSharedVariants) {
+            FwdChoice c;
+            if (v.NG * v.NW != d->N || !fill_shared(d, v.LG, v.K, v.NW, v.waves, v.RPB, sp, &c)) continue;
+            const double cost = fwd_cost(d, c);
+            if (!found || cost < best) { best = cost; *out = c; found = true; }
+        }
     return found ? SCAN2D_OK : SCAN2D_ERR_BAD_SHAPE;
 }
 
+// Kernels that use more than 64 KB of dynamic LDS need the attribute raised once per (device, kernel); the
+// pairs already done are remembered so that a launch (possibly under stream capture) makes no attribute call.
+bool allow_large_lds(const void* kernel, size_t bytes) {
+    struct Done { int dev; const void* kernel; size_t bytes; };
+    static std::mutex mu;
+    static Done done[256];
+    static int ndone = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < ndone; ++i)
+        if (done[i].dev == dev && done[i].kernel == kernel && done[i].bytes >= bytes) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (ndone < 256) done[ndone++] = Done{dev, kernel, bytes};
+    return true;
+}
+
+// Workspace of the scan kernel itself: row-end states between column panels (wide maps).
 size_t fwd_workspace(const scan2d_desc* d, const FwdChoice& c) {
     if (!c.multi) return 0;
     return (size_t)d->Bt * d->Dc * d->N * d->H * sizeof(float);
@@ -237,10 +360,16 @@ size_t fwd_need(const scan2d_desc* d) {
         const scan2d_desc t = swapped(d);
         return align256(fwd_need(&t)) + regions(d, false).total;
     }
-    FwdChoice ch;
-    if (choose_fwd(d, &ch) != SCAN2D_OK) return 0;
+    // the variant may depend on whether the step is computed in the kernel and on the mask alignment (the cost
+    // model knows their register counts): size the workspace for the largest of the four cases
+    size_t inner = 0;
+    for (int sp = 0; sp < 2; ++sp)
+        for (int ma = 0; ma < 2; ++ma) {
+            FwdChoice ch;
+            if (choose_fwd(d, &ch, sp != 0, ma != 0) == SCAN2D_OK) inner = std::max(inner, fwd_workspace(d, ch));
+        }
     const size_t sk = skip_bytes(d);
-    return sk > 0 ? align256(fwd_workspace(d, ch)) + sk : fwd_workspace(d, ch);
+    return sk > 0 ? align256(inner) + sk : inner;
 }
 size_t bwd_need(const scan2d_desc* d, bool softplus) {
     if (columns_first(d)) {
@@ -315,9 +444,7 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
     const long long wgs = (a.maps + ch.MPW - 1) / ch.MPW;
     if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
     (void)hipGetLastError();
-    if (ch.lds_bytes > 65536)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ch.kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)ch.lds_bytes);
+    if (ch.lds_bytes > 65536 && !allow_large_lds(reinterpret_cast<const void*>(ch.kernel), ch.lds_bytes)) return SCAN2D_ERR_LAUNCH_FAILED;
     hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(ch.waves * 64), ch.lds_bytes, static_cast<hipStream_t>(stream), a);
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
@@ -503,7 +630,7 @@ extern "C" int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* tex
         if (rc != SCAN2D_OK) return rc;
         const long long maps = (long long)desc->Bt * desc->Dc;
         std::snprintf(text, text_bytes, "fwd form=%s LG=%d K=%d NW=%d waves=%d RPB=%d NG=%d MPW=%d panels=%d fast=%d exact=%d wgs=%lld lds=%zu workspace=%zu",
-                      ch.K < 4 ? "small" : "general", ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
+                      ch.K < 4 ? "small" : (ch.shared ? "shared" : "general"), ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
                       (int)ch.fast, (int)ch.exact, (maps + ch.MPW - 1) / ch.MPW, ch.lds_bytes, fwd_workspace(desc, ch));
         return SCAN2D_OK;
     }
@@ -526,4 +653,11 @@ extern "C" const char* scan2d_strerror(int code) {
     }
 }
 
-extern "C" int scan2d_version(void) { return 100; }
+extern "C" int scan2d_debug_force_variant(int kind, const int* values, int n) {
+    if (kind < 0 || kind >= kTuneKinds) return SCAN2D_ERR_BAD_FLAGS;
+    if (n > 0 && values == nullptr) return SCAN2D_ERR_NULL_POINTER;
+    tune_set(kind, values, n);
+    return SCAN2D_OK;
+}
+
+extern "C" int scan2d_version(void) { return 200; }

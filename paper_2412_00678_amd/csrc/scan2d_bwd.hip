@@ -6,6 +6,7 @@
 #include <cstdlib>
 
 #include "scan2d_bwd_variants.hpp"
+#include "scan2d_tuning.hpp"
 
 namespace scan2d {
 namespace {
@@ -177,7 +178,8 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     BwdPlan pl;
     const int W = d->W, N = d->N;
-    if (W <= 16 && d->H <= 16 && N <= 16 && !std::getenv("SCAN2D_BWD_VARIANT")) {
+    const TuneValues tb = tune_get(kTuneBwd);
+    if (W <= 16 && d->H <= 16 && N <= 16 && tb.n == 0) {
         // small maps: the whole map stays in registers; dBm/dCm partials per channel
         pl.small = true;
         pl.LG = 16; pl.K = 1; pl.NW = N <= 4 ? 1 : (N <= 8 ? 2 : 4); pl.waves = 4; pl.RB = d->H;
@@ -206,9 +208,9 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     else if (W <= 1024) { LG = 64; K = 16; }
     else return false;
     int force_waves = 0, force_gs = 0;
-    if (const char* env = std::getenv("SCAN2D_BWD_VARIANT")) {   // tuning aid: "LG,K[,WAVES[,GS]]"
-        int eLG = 0, eK = 0, eW = 0, eG = 0;
-        const int got = std::sscanf(env, "%d,%d,%d,%d", &eLG, &eK, &eW, &eG);
+    if (tb.n >= 1) {                                             // tuning aid: LG,K[,WAVES[,GS]]
+        const int eLG = tb.v[0], eK = tb.v[1], eW = tb.v[2], eG = tb.v[3];
+        const int got = tb.n;
         if (got >= 2 && (eLG == 16 || eLG == 64) && eLG * eK >= W) { LG = eLG; K = eK; }
         if (got >= 3) force_waves = eW;
         if (got >= 4) force_gs = eG;

@@ -373,6 +373,52 @@ __device__ __forceinline__ void group_scan(float* P, float* H, float* C) {
     }
 }
 
+// The same scans without the copy of the left neighbour's state: for callers that apply the carry with the
+// lane movement inside the multiply-add (DPP source).  C is only written for half-wave groups, which keep
+// the plain form.  The trailing s_nop of the one-state form covers the DPP read that follows.
+template <int LG, int S>
+__device__ __forceinline__ void group_scan_nocarry(float* P, float* H, float* C) {
+    if constexpr (LG == 32) {
+        group_scan<LG, S>(P, H, C);
+    } else if constexpr (S == 1) {
+        if constexpr (LG == 16)
+            asm volatile("s_nop 1\n\t"
+                         SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
+                         SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_LAST(SCAN2D_SHR(8))
+                         : "+v"(H[0]), "+v"(P[0]));
+        else
+            asm volatile("s_nop 1\n\t"
+                         SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
+                         SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_STEP(SCAN2D_SHR(8))
+                         SCAN2D_S1_STEP(SCAN2D_BC15) SCAN2D_S1_LAST(SCAN2D_BC31)
+                         : "+v"(H[0]), "+v"(P[0]));
+    } else if constexpr (S == 2) {
+        if constexpr (LG == 16)
+            asm volatile("s_nop 1\n\t"
+                         SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
+                         SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_LAST(SCAN2D_SHR(8))
+                         : "+v"(H[0]), "+v"(H[1]), "+v"(P[0]), "+v"(P[1]));
+        else
+            asm volatile("s_nop 1\n\t"
+                         SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
+                         SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_STEP(SCAN2D_SHR(8))
+                         SCAN2D_S2_STEP(SCAN2D_BC15) SCAN2D_S2_LAST(SCAN2D_BC31)
+                         : "+v"(H[0]), "+v"(H[1]), "+v"(P[0]), "+v"(P[1]));
+    } else {
+        if constexpr (LG == 16)
+            asm volatile("s_nop 1\n\t"
+                         SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
+                         SCAN2D_S4_STEP(SCAN2D_SHR(4)) SCAN2D_S4_LAST(SCAN2D_SHR(8))
+                         : "+v"(H[0]), "+v"(H[1]), "+v"(H[2]), "+v"(H[3]), "+v"(P[0]), "+v"(P[1]), "+v"(P[2]), "+v"(P[3]));
+        else
+            asm volatile("s_nop 1\n\t"
+                         SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
+                         SCAN2D_S4_STEP(SCAN2D_SHR(4)) SCAN2D_S4_STEP(SCAN2D_SHR(8))
+                         SCAN2D_S4_STEP(SCAN2D_BC15) SCAN2D_S4_LAST(SCAN2D_BC31)
+                         : "+v"(H[0]), "+v"(H[1]), "+v"(H[2]), "+v"(H[3]), "+v"(P[0]), "+v"(P[1]), "+v"(P[2]), "+v"(P[3]));
+    }
+}
+
 // ------------------------------------------------------------------ group scan (leftwards)
 // Mirror image for the reverse row scan of the backward pass: q <- Q + P * q_in where q_in
 // comes from the lane to the RIGHT.  Out: C = the value at the first column of the lane to the

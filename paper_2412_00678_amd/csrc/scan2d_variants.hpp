@@ -8,6 +8,7 @@
 #pragma once
 
 #include "scan2d_fwd.hpp"
+#include "scan2d_fwd_shared.hpp"
 #include "scan2d_fwd_small.hpp"
 
 namespace scan2d {
@@ -34,6 +35,29 @@ namespace scan2d {
     X(64, 4, 1, 8) X(64, 4, 2, 8) X(64, 4, 1, 16) X(16, 4, 4, 4)
 
 using FwdKernel = void (*)(const FwdArgs);
+
+// Variants of the form that shares the per-position work of a map through LDS: (LG, K, NW, NG, WAVES, RPB);
+// NG = N / NW lane groups per map, RPB rows between two barriers.
+#define SCAN2D_FWD_SHARED_VARIANTS(X)                                                     \
+    X(64, 4, 2, 8, 8, 4) X(64, 4, 2, 8, 8, 8) X(64, 4, 1, 16, 16, 4)                      \
+    X(16, 12, 1, 16, 4, 4) X(16, 12, 2, 8, 4, 2) X(16, 8, 1, 16, 4, 4) X(16, 8, 2, 8, 4, 2) \
+    X(16, 4, 1, 16, 4, 4) X(16, 4, 2, 8, 4, 4) X(16, 4, 4, 4, 4, 4) X(16, 4, 8, 2, 4, 4)   \
+    /* N = 8 */ X(64, 4, 1, 8, 8, 4) X(16, 4, 1, 8, 4, 4) X(16, 4, 2, 4, 4, 4) X(16, 8, 1, 8, 4, 4) X(16, 12, 1, 8, 4, 4) \
+    /* N = 4 */ X(64, 4, 1, 4, 4, 4) X(16, 4, 1, 4, 4, 4) X(16, 8, 1, 4, 4, 4)             \
+    /* N = 32 */ X(64, 4, 2, 16, 16, 4) X(64, 4, 4, 8, 8, 4) X(16, 4, 2, 16, 4, 4) X(16, 8, 2, 16, 4, 4) X(16, 4, 4, 8, 4, 4) \
+    /* N = 64 */ X(64, 4, 4, 16, 16, 4) X(16, 4, 4, 16, 4, 4) X(16, 8, 4, 16, 4, 2)
+
+FwdKernel fwd_shared_kernel_f32(int LG, int K, int NW, int NG, int waves, int RPB, bool sp);
+FwdKernel fwd_shared_kernel_bf16(int LG, int K, int NW, int NG, int waves, int RPB, bool sp, bool ua);
+
+template <typename T, bool SP, bool UA>
+inline FwdKernel lookup_fwd_shared_kernel(int LG, int K, int NW, int NG, int waves, int RPB) {
+#define SCAN2D_X(lg, k, nw, ng, wv, rpb) \
+    if (LG == lg && K == k && NW == nw && NG == ng && waves == wv && RPB == rpb) return scan2d_fwd_shared_kernel<T, lg, k, nw, ng, wv, rpb, SP, UA>;
+    SCAN2D_FWD_SHARED_VARIANTS(SCAN2D_X)
+#undef SCAN2D_X
+    return nullptr;
+}
 
 // Returns nullptr when the variant is not compiled.
 // sp: the instantiations that compute the step themselves (softplus of the raw projection).

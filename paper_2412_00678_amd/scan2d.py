@@ -20,7 +20,8 @@ PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS = 0, 1, 2, 3
 
 EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
-           "scan2d_version")
+           "scan2d_version", "scan2d_debug_force_variant")
+TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
 
 
 class Desc(ctypes.Structure):
@@ -61,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_version.restype = ctypes.c_int
     lib.scan2d_describe_plan.argtypes = [ctypes.POINTER(Desc), ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
     lib.scan2d_describe_plan.restype = ctypes.c_int
+    lib.scan2d_debug_force_variant.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.c_int]
+    lib.scan2d_debug_force_variant.restype = ctypes.c_int
     return lib
 
 
@@ -73,6 +76,36 @@ def strerror(code: int) -> str:
 
 def version() -> int:
     return int(lib.scan2d_version())
+
+
+def force_variant(kind: int, values=None) -> None:
+    """Test hook: force a kernel variant for the whole process (None or "" clears the override).
+
+    `values` is a sequence of ints or a comma-separated string, in the order the header gives for `kind`."""
+    if isinstance(values, str):
+        values = [int(t) for t in values.split(",") if t.strip()]
+    values = list(values or [])
+    arr = (ctypes.c_int * max(1, len(values)))(*values)
+    rc = lib.scan2d_debug_force_variant(int(kind), arr, len(values))
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_debug_force_variant")
+
+
+class forced_variant:
+    """Context manager around force_variant: the override is cleared on exit."""
+
+    def __init__(self, kind: int, values=None):
+        self.kind, self.values = kind, values
+
+    def __enter__(self):
+        if self.values is not None:
+            force_variant(self.kind, self.values)
+        return self
+
+    def __exit__(self, *exc):
+        if self.values is not None:
+            force_variant(self.kind, None)
+        return False
 
 
 def _dtype_code(t: torch.Tensor) -> int:

@@ -32,16 +32,16 @@ def rel_err(got, ref):
 def run_fwd(s2d, inp, dtype, variant=None):
     import torch
     d = s2d.to_device(inp, dtype)
-    old = os.environ.pop("SCAN2D_FWD_VARIANT", None)
-    if variant is not None:
-        os.environ["SCAN2D_FWD_VARIANT"] = variant
-    try:
+    kind = s2d.TUNE_FWD
+    if variant is not None and variant.startswith("shared:"):
+        kind, variant = s2d.TUNE_FWD_SHARED, variant[len("shared:"):]
+    with s2d.forced_variant(kind, variant):
+        if kind == s2d.TUNE_FWD_SHARED:                   # the forced form must be the one that runs
+            plan = s2d.describe_plan(s2d.make_desc(d["x"], d["A"]), s2d.PASS_FWD)
+            LG, K, NW, waves, rpb = (int(t) for t in variant.split(","))
+            assert f"form=shared LG={LG} K={K} NW={NW} waves={waves} RPB={rpb} " in plan, plan
         y = s2d.scan2d_fwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
         torch.cuda.synchronize()
-    finally:
-        os.environ.pop("SCAN2D_FWD_VARIANT", None)
-        if old is not None:
-            os.environ["SCAN2D_FWD_VARIANT"] = old
     return s2d.to_host(y)
 
 
@@ -164,6 +164,32 @@ def test_every_kernel_variant(s2d, variant, shape, dtype):
     check_fwd(s2d, wl.Workload("var", Bt, Dc, N, H, W, dtype, mask_frac=0.25), seed=5, variant=variant)
 
 
+# The form whose lane groups share the per-position work through LDS: LG,K,NW,WAVES,RPB forced on shapes with
+# N = NG * NW; odd widths, heights off the batch grid, map counts off the workgroup grid (idle lane groups).
+SHARED_CASES = [
+    ("64,4,2,8,4", (1, 3, 16, 13, 256)), ("64,4,2,8,4", (1, 2, 16, 9, 203)), ("64,4,2,8,8", (1, 3, 16, 21, 250)),
+    ("64,4,1,16,4", (2, 3, 16, 13, 256)), ("64,4,1,16,4", (1, 2, 16, 6, 131)),
+    ("16,12,1,4,4", (1, 5, 16, 13, 192)), ("16,12,1,4,4", (1, 3, 16, 7, 181)), ("16,12,2,4,2", (1, 5, 16, 13, 190)),
+    ("16,8,1,4,4", (1, 3, 16, 9, 128)), ("16,8,2,4,2", (2, 3, 16, 9, 121)),
+    ("16,4,1,4,4", (1, 3, 16, 11, 64)), ("16,4,2,4,4", (1, 5, 16, 11, 57)), ("16,4,4,4,4", (1, 7, 16, 11, 56)),
+    ("16,4,8,4,4", (1, 11, 16, 11, 50)), ("16,4,8,4,4", (3, 64, 16, 5, 33)),
+    # N = 8, 4, 32, 64
+    ("64,4,1,8,4", (1, 3, 8, 13, 256)), ("16,4,1,4,4", (1, 3, 8, 9, 60)), ("16,4,2,4,4", (1, 7, 8, 9, 61)),
+    ("16,8,1,4,4", (1, 3, 8, 9, 100)), ("16,12,1,4,4", (1, 3, 8, 9, 180)),
+    ("64,4,1,4,4", (1, 3, 4, 9, 250)), ("16,4,1,4,4", (1, 6, 4, 9, 64)), ("16,8,1,4,4", (1, 5, 4, 9, 127)),
+    ("64,4,2,16,4", (1, 2, 32, 9, 256)), ("64,4,4,8,4", (1, 2, 32, 9, 240)), ("16,4,2,4,4", (1, 2, 32, 9, 64)),
+    ("16,8,2,4,4", (1, 2, 32, 9, 128)), ("16,4,4,4,4", (1, 3, 32, 9, 63)),
+    ("64,4,4,16,4", (1, 2, 64, 5, 256)), ("16,4,4,4,4", (1, 2, 64, 5, 64)), ("16,8,4,4,2", (1, 2, 64, 5, 100)),
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("variant,shape", SHARED_CASES, ids=[f"shared-{v}-{s[4]}-{s[2]}" for v, s in SHARED_CASES])
+def test_every_shared_producer_variant(s2d, variant, shape, dtype):
+    Bt, Dc, N, H, W = shape
+    check_fwd(s2d, wl.Workload("shared", Bt, Dc, N, H, W, dtype, mask_frac=0.25), seed=6, variant="shared:" + variant)
+
+
 # ------------------------------------------------------------------ mask / indexing: bit-exact
 
 @pytest.mark.parametrize("H,W", [(40, 72), (19, 57), (9, 55), (7, 33), (5, 250)])   # also mask and bf16 tensors that end inside a dword
@@ -240,16 +266,9 @@ GRADS = ("dx", "ddelta", "dA", "dBm", "dCm", "dDskip")
 def run_bwd(s2d, inp, dtype, variant=None):
     import torch
     d = s2d.to_device(inp, dtype)
-    old = os.environ.pop("SCAN2D_BWD_VARIANT", None)
-    if variant is not None:
-        os.environ["SCAN2D_BWD_VARIANT"] = variant
-    try:
+    with s2d.forced_variant(s2d.TUNE_BWD, variant):
         out = s2d.scan2d_bwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["dy"])
         torch.cuda.synchronize()
-    finally:
-        os.environ.pop("SCAN2D_BWD_VARIANT", None)
-        if old is not None:
-            os.environ["SCAN2D_BWD_VARIANT"] = old
     return [None if t is None else s2d.to_host(t) for t in out]
 
 
