@@ -60,7 +60,8 @@ enum {
     SCAN2D_ERR_WORKSPACE_SMALL  = -5,  /* workspace_bytes < scan2d_workspace_bytes() */
     SCAN2D_ERR_MISALIGNED       = -6,  /* a base pointer is not 16-byte aligned */
     SCAN2D_ERR_LAUNCH_FAILED    = -7,  /* the HIP runtime refused a launch */
-    SCAN2D_ERR_UNSUPPORTED_DEVICE = -8 /* current device is not gfx950 */
+    SCAN2D_ERR_UNSUPPORTED_DEVICE = -8, /* current device is not gfx950 */
+    SCAN2D_ERR_SCRATCH_LIMIT    = -9   /* scan2d_bwd_static_scratch only: the call needs more than SCAN2D_STATIC_SCRATCH_BYTES */
 };
 
 enum { SCAN2D_F32 = 0, SCAN2D_BF16 = 1 };
@@ -196,6 +197,28 @@ int scan2d_bwd_softplus_gated(const scan2d_desc* desc,
                               void* dx, void* ddelta_raw, float* ddelta_bias, float* dA, float* dBm, float* dCm,
                               float* dDskip, void* dz,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * scan2d_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving or
+ * training loops, harnesses that forbid hipMalloc): the same computation and the same kernels as scan2d_bwd,
+ * every argument as there, but no workspace argument.  The band checkpoints and partial sums go to a scratch
+ * array of SCAN2D_STATIC_SCRATCH_BYTES bytes that is part of the library's device code: every GPU the library
+ * runs on holds one copy from load time until the process ends.  The call allocates nothing and frees nothing.
+ *   - A descriptor whose scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD) exceeds SCAN2D_STATIC_SCRATCH_BYTES is
+ *     refused with SCAN2D_ERR_SCRATCH_LIMIT before anything is enqueued (use scan2d_bwd with a workspace).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (different
+ *     streams, or different host threads) race on it.  Calls on one stream are ordered and safe.  Nothing in
+ *     the array has to survive from one call to the next and nothing has to start at zero: every kernel
+ *     writes what it later reads.
+ *   - The first call on a device asks the runtime once for the array's address on that device.
+ */
+#define SCAN2D_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+int scan2d_bwd_static_scratch(const scan2d_desc* desc,
+                              const void* x, const void* delta, const float* A,
+                              const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                              const void* dy,
+                              void* dx, void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip,
+                              void* stream);
 
 /* Bytes of workspace a call with this descriptor needs (pass = SCAN2D_PASS_FWD for the three forward
  * calls, SCAN2D_PASS_BWD / _BWD_SOFTPLUS / _BWD_GATED for scan2d_bwd / _bwd_softplus / _bwd_softplus_gated).

@@ -649,8 +649,51 @@ extern "C" const char* scan2d_strerror(int code) {
         case SCAN2D_ERR_MISALIGNED: return "a base pointer is not 16-byte aligned";
         case SCAN2D_ERR_LAUNCH_FAILED: return "the HIP runtime refused a kernel launch";
         case SCAN2D_ERR_UNSUPPORTED_DEVICE: return "the current device is not gfx950 (MI355X)";
+        case SCAN2D_ERR_SCRATCH_LIMIT: return "scan2d_bwd_static_scratch: the call needs more workspace than the built-in scratch array holds (SCAN2D_STATIC_SCRATCH_BYTES); use scan2d_bwd with a workspace";
         default: return "unknown scan2d error code";
     }
+}
+
+// ------------------------------------------------------------------ backward without a caller's workspace
+// The workspace of this entry point: device memory that lives in the library's code object, one copy per GPU,
+// from the moment the library is loaded on that GPU until the process ends.
+static __device__ __align__(256) unsigned char scratch[SCAN2D_STATIC_SCRATCH_BYTES];
+
+namespace {
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, asked for once per device
+
+// The array's name is a host-side handle, not a device address: kernels and copies get the address that the
+// runtime reports for the current device.
+void* scratch_address() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p != nullptr) return p;
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || q == nullptr) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(q, std::memory_order_release);
+    return q;
+}
+}  // namespace
+
+extern "C" int scan2d_bwd_static_scratch(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
+                                         const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                                         const void* dy, void* dx, void* ddelta, float* dA, float* dBm, float* dCm,
+                                         float* dDskip, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    const size_t need = bwd_need(desc, false);
+    if (need == 0) return SCAN2D_ERR_BAD_SHAPE;
+    if (need > (size_t)SCAN2D_STATIC_SCRATCH_BYTES) return SCAN2D_ERR_SCRATCH_LIMIT;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    void* ws = scratch_address();
+    if (ws == nullptr) return SCAN2D_ERR_LAUNCH_FAILED;
+    return bwd_impl(desc, x, delta, nullptr, false, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, nullptr, dA, dBm, dCm, dDskip,
+                    ws, need, stream);
 }
 
 extern "C" int scan2d_debug_force_variant(int kind, const int* values, int n) {

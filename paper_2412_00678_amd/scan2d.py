@@ -20,7 +20,9 @@ PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS = 0, 1, 2, 3
 
 EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
-           "scan2d_version", "scan2d_debug_force_variant")
+           "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch")
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+ERR_SCRATCH_LIMIT = -9
 TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
 
 
@@ -49,6 +51,8 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_fwd_softplus.restype = ctypes.c_int
     lib.scan2d_bwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 14 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_bwd.restype = ctypes.c_int
+    lib.scan2d_bwd_static_scratch.argtypes = [ctypes.POINTER(Desc)] + [vp] * 14 + [vp]
+    lib.scan2d_bwd_static_scratch.restype = ctypes.c_int
     lib.scan2d_bwd_softplus.argtypes = [ctypes.POINTER(Desc)] + [vp] * 16 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_bwd_softplus.restype = ctypes.c_int
     lib.scan2d_fwd_softplus_gated.argtypes = [ctypes.POINTER(Desc)] + [vp] * 11 + [vp, ctypes.c_size_t, vp]
@@ -243,6 +247,19 @@ def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0):
     if rc != 0:
         raise Scan2dError(rc, "scan2d_bwd")
     return dx, ddelta, dA, dBm, dCm, dDskip
+
+
+def scan2d_bwd_static_scratch(x, delta, A, Bm, Cm, Dskip, mask, dy, out, flags=0):
+    """scan2d_bwd with the library's built-in scratch array as workspace.  Nothing is allocated, here or in the
+    library: `out` = (dx, ddelta, dA, dBm, dCm, dDskip) are the caller's tensors (dDskip None iff Dskip is)."""
+    desc = make_desc(x, A, flags)
+    dx, ddelta, dA, dBm, dCm, dDskip = out
+    rc = lib.scan2d_bwd_static_scratch(ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm),
+                                       _ptr(Dskip), _ptr(mask), _ptr(dy), _ptr(dx), _ptr(ddelta), _ptr(dA),
+                                       _ptr(dBm), _ptr(dCm), _ptr(dDskip), _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_bwd_static_scratch")
+    return out
 
 
 def scan2d_bwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0):

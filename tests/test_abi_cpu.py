@@ -29,7 +29,7 @@ def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted(
         ["scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
          "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
-         "scan2d_version", "scan2d_debug_force_variant"])
+         "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch"])
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -41,8 +41,8 @@ def test_library_exports_every_declared_symbol(lib):
 
 
 def test_error_strings_are_distinct_and_static(lib):
-    seen = {lib.strerror(c) for c in range(0, -9, -1)}
-    assert len(seen) == 9
+    seen = {lib.strerror(c) for c in range(0, -10, -1)}
+    assert len(seen) == 10
     assert "unknown" in lib.strerror(-99)
 
 
