@@ -219,8 +219,9 @@ def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=No
     return y
 
 
-def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0):
-    """Gradients (dx, ddelta, dA, dBm, dCm, dDskip) of sum(dy * y); dDskip is None iff Dskip is."""
+def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0, out=None):
+    """Gradients (dx, ddelta, dA, dBm, dCm, dDskip) of sum(dy * y); dDskip is None iff Dskip is.
+    `out`: the six tensors to write into (nothing is allocated then when a workspace is given too)."""
     desc = make_desc(x, A, flags)
     Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
     _check(x, "x", x.dtype, (Bt, Dc, H, W))
@@ -231,12 +232,21 @@ def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0):
     _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
     _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
     _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
-    dx = torch.empty_like(x)
-    ddelta = torch.empty_like(x)
-    dA = torch.empty((Dc, N), dtype=torch.float32, device=x.device)
-    dBm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
-    dCm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
-    dDskip = None if Dskip is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    if out is not None:
+        dx, ddelta, dA, dBm, dCm, dDskip = out
+        _check(dx, "dx", x.dtype, (Bt, Dc, H, W))
+        _check(ddelta, "ddelta", x.dtype, (Bt, Dc, H, W))
+        _check(dA, "dA", torch.float32, (Dc, N))
+        _check(dBm, "dBm", torch.float32, (Bt, N, H, W))
+        _check(dCm, "dCm", torch.float32, (Bt, N, H, W))
+        _check(dDskip, "dDskip", torch.float32, (Dc,), optional=True)
+    else:
+        dx = torch.empty_like(x)
+        ddelta = torch.empty_like(x)
+        dA = torch.empty((Dc, N), dtype=torch.float32, device=x.device)
+        dBm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+        dCm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+        dDskip = None if Dskip is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace, wbytes = _workspace(desc, PASS_BWD, x.device)
     else:
