@@ -166,6 +166,8 @@ struct BwdPlan {
     int NG = 0, GS = 0, CG = 0, nb = 0;
     BwdKernels k;
     size_t lds_bytes = 0;
+    bool shared = false;                                   // main sweep of scan2d_bwd_shared.hpp
+    int ck_LG = 0, ck_waves = 0;                           // lane tiling of the checkpoint sweep
     bool step_outside = false;                             // softplus step written by a kernel of its own (banded form)
     size_t off_step = 0;                                   // the step [maps][H][W] fp32 (step_outside only), 256 spare bytes behind it
     bool fast = true;                                      // W is a multiple of the columns per lane
@@ -174,6 +176,11 @@ struct BwdPlan {
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Tilings whose shared-producer main sweep is the default: measured 10-30 % faster than the plain one for 16-lane
+// groups (56x56 bf16 x 6144 maps: 1.41 -> 1.08 ms; 128x192 fp32 x 2048 maps: 3.63 -> 2.86 ms); slower for wave-wide
+// groups on 16 waves, where the 128-register budget makes it spill (256x256 bf16: 2.0 -> 3.0 ms).
+bool shared_by_default(int LG, int K) { (void)K; return LG == 16; }
 
 bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     BwdPlan pl;
@@ -207,13 +214,14 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     else if (W <= 512) { LG = 64; K = 8; }
     else if (W <= 1024) { LG = 64; K = 16; }
     else return false;
-    int force_waves = 0, force_gs = 0;
-    if (tb.n >= 1) {                                             // tuning aid: LG,K[,WAVES[,GS]]
+    int force_waves = 0, force_gs = 0, want_shared = -1;
+    if (tb.n >= 1) {                                             // tuning aid: LG,K[,WAVES[,GS[,shared]]]
         const int eLG = tb.v[0], eK = tb.v[1], eW = tb.v[2], eG = tb.v[3];
         const int got = tb.n;
-        if (got >= 2 && (eLG == 16 || eLG == 64) && eLG * eK >= W) { LG = eLG; K = eK; }
+        if (got >= 2 && (eLG == 16 || eLG == 32 || eLG == 64) && eLG * eK >= W) { LG = eLG; K = eK; }
         if (got >= 3) force_waves = eW;
         if (got >= 4) force_gs = eG;
+        if (got >= 5) want_shared = tb.v[4];
     }
     // states per lane and waves per workgroup: 16 lane groups of one DPP row with one state each;
     // wavefront-wide lane groups: 16 of them with one state each for 4 columns per lane (four waves
@@ -221,6 +229,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     // columns; four states per lane beyond N = 16
     int waves, NW;
     if (LG == 16) { waves = 4; NW = N <= 16 ? 1 : 4; }
+    else if (LG == 32) { waves = 8; NW = 1; }
     else if (N <= 16 && K == 16) { waves = 4; NW = 4; }     // widest maps: LDS bounds the workgroup size
     else if (N <= 16 && K == 4 && force_waves != 8) { waves = 16; NW = 1; }
     else if (N <= 16) { waves = 8; NW = 2; }
@@ -230,8 +239,18 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     const bool fast = (W % K) == 0;                          // otherwise: the instantiations that treat the row end
     pl.step_outside = sp;
     pl.fast = fast;
-    pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
+    // the main sweep that shares the per-position work through LDS, where it exists for this tiling (N = NG * NW)
+    if (want_shared != 0 && N % NW == 0) {
+        const BwdKernels ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16(LG, K, NW, N / NW, waves, W, sp)
+                                                      : bwd_shared_kernels_f32(LG, K, NW, N / NW, waves, W, sp);
+        if (ks.main != nullptr && (want_shared == 1 || shared_by_default(LG, K))) pl.k = ks;
+    }
+    if (pl.k.main == nullptr)
+        pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
     if (pl.k.main == nullptr) return false;
+    pl.shared = pl.k.shared;
+    pl.fast = fast && pl.k.ckpt_fast;                        // false: the padded copies of the tensors' last rows are needed
+    pl.ck_LG = pl.k.ckpt_LG; pl.ck_waves = pl.k.ckpt_waves;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;
     pl.NG = (N + NW - 1) / NW;
     pl.nb = (d->H + pl.RB - 1) / pl.RB;
@@ -241,7 +260,11 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     // if it cannot be asked - times channels per workgroup), the larger count on a tie (fewer
     // partial sums to write and add up)
     const size_t T = (size_t)waves * 64;
-    const size_t fixed = 4 * T * K, per = T * ((size_t)NW * K + NW + 1);
+    size_t fixed = 4 * T * K, per = T * ((size_t)NW * K + NW + 1);
+    if (pl.shared) {             // see the LDS layout in scan2d_bwd_shared.hpp
+        fixed = 4 * T * K + (T / (size_t)pl.NG / LG) * ((size_t)pl.RB * 5 * LG * K);
+        per = T * (size_t)NW * K + (T / LG) * NW + (size_t)waves;
+    }
     const int gs_lds = (int)std::max<size_t>(1, (40960 - std::min<size_t>(fixed, 40960)) / per);
     const int JPW = slots / pl.NG;
     const int gs_max = std::min({gs_lds, 8, d->Dc});
@@ -296,7 +319,7 @@ bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
     if (pl.small) wgs = (maps + 3) / 4;
     else wgs = ((long long)d->Bt * pl.CG + (pl.waves * 64 / pl.LG) / pl.NG - 1) / ((pl.waves * 64 / pl.LG) / pl.NG);
     std::snprintf(text, text_bytes, "bwd form=%s LG=%d K=%d NW=%d waves=%d RB=%d GS=%d CG=%d bands=%d wgs=%lld lds=%zu workspace=%zu",
-                  pl.small ? "small" : "banded", pl.LG, pl.K, pl.NW, pl.waves, pl.RB, pl.GS, pl.CG, pl.nb, wgs,
+                  pl.small ? "small" : (pl.shared ? "banded-shared" : "banded"), pl.LG, pl.K, pl.NW, pl.waves, pl.RB, pl.GS, pl.CG, pl.nb, wgs,
                   pl.lds_bytes, pl.total);
     return true;
 }
@@ -366,7 +389,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     const int MPW = slots / pl.NG;
     BwdArgs ac = a;                                            // the checkpoint sweep may hold more states per lane
     ac.NG = (d->N + pl.k.ckpt_NW - 1) / pl.k.ckpt_NW;
-    const int MPW1 = slots / ac.NG;
+    const int MPW1 = (pl.ck_waves * 64 / pl.ck_LG) / ac.NG;
     const long long wg1 = (maps + MPW1 - 1) / MPW1;
     const long long jobs = (long long)d->Bt * pl.CG;
     const long long wg2 = (jobs + MPW - 1) / MPW;
@@ -397,8 +420,22 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
             hipLaunchKernelGGL(scan2d_bwd_step_kernel<float>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
                                static_cast<const float*>(delta), delta_bias, step, HW, d->Dc, chunks);
     }
-    if (pl.nb > 1)
-        hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.waves * 64), 0, stream, ac);
+    if (pl.nb > 1 && pl.k.ckpt_fwd != nullptr && d->N == pl.k.cf_NG * pl.k.cf_NW) {
+        // the checkpoint sweep by the shared-producer forward kernel (checkpoint mode): it computes the softplus
+        // step itself from the raw projection, with the same function as the step kernel above
+        FwdArgs f;
+        f.x = x; f.delta = delta; f.A = A; f.Bm = Bm; f.Cm = Cm; f.Dskip = nullptr; f.mask = mask; f.y = nullptr;
+        f.delta_bias = delta_bias; f.carry = nullptr;
+        f.ck = a.ck; f.nb = pl.nb;
+        f.maps = maps; f.Dc = d->Dc; f.H = d->H; f.W = d->W; f.N = d->N;
+        f.NG = pl.k.cf_NG; f.MPW = (pl.k.cf_waves * 64 / pl.k.cf_LG) / pl.k.cf_NG; f.panels = 1; f.RPB = pl.k.cf_RPB;
+        const long long wgf = (maps + f.MPW - 1) / f.MPW;
+        if (wgf > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+        const size_t lds_f = 2 * (size_t)f.MPW * f.RPB * 2 * pl.k.cf_LG * pl.k.cf_K * sizeof(float);   // the per-position buffers only
+        hipLaunchKernelGGL(pl.k.ckpt_fwd, dim3((unsigned)wgf), dim3(pl.k.cf_waves * 64), lds_f, stream, f);
+    } else if (pl.nb > 1) {
+        hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.ck_waves * 64), 0, stream, ac);
+    }
     if (pl.lds_bytes > 65536)
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(pl.k.main),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes);

@@ -53,6 +53,8 @@ struct FwdArgs {
     const float* Dskip; const uint8_t* mask; void* y;
     const float* delta_bias;   // [Dc] or null; read by the SP instantiations only (delta then holds the raw projection)
     float* carry;        // [maps][N][H] row-end states between column panels (panels > 1 only)
+    float* ck = nullptr; // checkpoint sweep of the backward pass only: [maps][nb][N][W] column states entering each band
+    int nb = 0;          // bands of that sweep
     long long maps;      // Bt * Dc
     int Dc, H, W, N;
     int NG;              // lane groups per map = ceil(N / NW)

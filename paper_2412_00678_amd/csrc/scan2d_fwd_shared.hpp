@@ -57,7 +57,10 @@ __device__ __forceinline__ void carry_apply(float* hl, const float* pl, const fl
 
 // UA (bf16 only): rows of odd width; Bm/Cm rows then start on odd 2-byte boundaries every other row and
 // are shifted into place where they are unpacked, as in the plain form.
-template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA>
+// CK > 0: the checkpoint sweep of the backward pass instead of the forward pass.  The recurrences are the same;
+// Cm, the sum over states and y are left out, and the column state h at the bottom of every band of CK rows is
+// written to p.ck ([maps][p.nb][N][W], the state entering band (i+1)/CK after row i; the last row's is never needed).
+template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const FwdArgs p) {
     static_assert(!UA || Elem<T>::kBytes == 2, "UA: bf16 rows on odd 2-byte boundaries");
     constexpr int XW = words_of<T, K>();
@@ -205,7 +208,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
     for (int d = 0; d < PDS; ++d) {
         const uint32_t ro = (uint32_t)min(d, H - 1) * (uint32_t)W;
 #pragma unroll
-        for (int s = 0; s < NW; ++s) { lds(rsB, s, ro, rB[d][s]); lds(rsC, s, ro, rC[d][s]); }
+        for (int s = 0; s < NW; ++s) {
+            lds(rsB, s, ro, rB[d][s]);
+            if constexpr (CK == 0) lds(rsC, s, ro, rC[d][s]);
+        }
     }
     produce(0);
 #pragma unroll
@@ -265,22 +271,44 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                     const int s = s0 + t;
                     if constexpr (kDppApply && LG != 32) carry_apply<LG, K>(hl[t], pl[t], Hh[t]);                 // Eq. 5
                     uint32_t uC[XW];
-                    unpacks(rC[SS][s], s, cur, uC);
+                    if constexpr (CK == 0) unpacks(rC[SS][s], s, cur, uC);
 #pragma unroll
                     for (int j = 0; j < K; ++j) {
                         const float hh = (j == K - 1) ? Hh[t] : ((kDppApply && LG != 32) ? hl[t][j] : fmaf(pl[t][j], cin[t], hl[t][j]));
                         fma_inplace(h[s][j], a[t][j], hh);                                          // Eq. 6
-                        const float cv = get_elem<T, K>(uC, j);
-                        yacc[j] = s == 0 ? cv * h[s][j] : fmaf(cv, h[s][j], yacc[j]);
+                        if constexpr (CK == 0) {
+                            const float cv = get_elem<T, K>(uC, j);
+                            yacc[j] = s == 0 ? cv * h[s][j] : fmaf(cv, h[s][j], yacc[j]);
+                        }
                     }
-                    lds(rsC, s, nxt, rC[SS][s]);
+                    if constexpr (CK == 0) lds(rsC, s, nxt, rC[SS][s]);
                 }
             }
-            float* mine = ypart + buf * YP_BUF + r * YP_ROW + slot * PANEL + l * 4;
+            if constexpr (CK == 0) {
+                float* mine = ypart + buf * YP_BUF + r * YP_ROW + slot * PANEL + l * 4;
 #pragma unroll
-            for (int j4 = 0; j4 < K / 4; ++j4)
-                *reinterpret_cast<float4*>(mine + j4 * (LG * 4)) =
-                    make_float4(yacc[4 * j4], yacc[4 * j4 + 1], yacc[4 * j4 + 2], yacc[4 * j4 + 3]);
+                for (int j4 = 0; j4 < K / 4; ++j4)
+                    *reinterpret_cast<float4*>(mine + j4 * (LG * 4)) =
+                        make_float4(yacc[4 * j4], yacc[4 * j4 + 1], yacc[4 * j4 + 2], yacc[4 * j4 + 3]);
+            } else {
+                if ((i + 1) % CK == 0 && i + 1 < H && live) {             // h[i] enters band (i+1)/CK
+                    const int band = (i + 1) / CK;
+#pragma unroll
+                    for (int s = 0; s < NW; ++s) {
+                        float* dst = p.ck + (((size_t)map * p.nb + band) * N + n0 + s) * W + col0;
+                        if (col0 + K <= W) {
+                            uint32_t bits[K];
+#pragma unroll
+                            for (int j = 0; j < K; ++j) bits[j] = __float_as_uint(h[s][j]);
+                            store_words<K>(reinterpret_cast<uint32_t*>(dst), bits);
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < K; ++j)
+                                if (col0 + j < W) dst[j] = h[s][j];
+                        }
+                    }
+                }
+            }
         }
         // the next batch's cells: produced before the barrier (its LDS buffer was last read one batch ago,
         // before the previous barrier), then the loads of the batch after that are requested
@@ -289,7 +317,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
         __syncthreads();
         fetch_row(buf ^ 1, 0, 0);
         // sums over the lane groups of the cells this thread produced, skip term, one rounding, store
-        if (live) {
+        if (CK == 0 && live) {
             const float* ybase = ypart + buf * YP_BUF + (slot - sg) * PANEL;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {

@@ -169,10 +169,12 @@ def test_backward_plans_cover_the_documented_range_and_nothing_else(lib):
 
 def test_benchmark_configurations_take_the_intended_forms(lib):
     f = plan(lib, lib.Desc(1, 256, 256, 256, 16, 1, 0), lib.PASS_FWD)
-    assert (f["LG"], f["K"], f["NW"], f["waves"]) == (64, 4, 2, 8) and f["fast"] and f["wgs"] == 256
+    assert (f["form"], f["LG"], f["K"], f["NW"], f["waves"]) == ("shared", 64, 4, 2, 8) and f["fast"] and f["wgs"] == 256
     f = plan(lib, lib.Desc(32, 192, 56, 56, 16, 1, 0), lib.PASS_FWD)
-    assert f["LG"] == 16 and f["K"] == 4 and f["fast"]
+    assert f["form"] == "shared" and f["LG"] == 16 and f["K"] == 4 and f["fast"]
+    f = plan(lib, lib.Desc(1, 256, 64, 64, 16, 0, 0), lib.PASS_FWD)
+    assert (f["form"], f["LG"], f["K"], f["NW"]) == ("shared", 16, 4, 1)
     f = plan(lib, lib.Desc(1, 16, 16, 16, 4, 0, 0), lib.PASS_FWD)
     assert f["form"] == "small"
     b = plan(lib, lib.Desc(4, 512, 128, 192, 16, 0, 0), lib.PASS_BWD)
-    assert (b["form"], b["LG"], b["K"], b["NW"]) == ("banded", 16, 12, 1) and b["wgs"] * b["GS"] >= 4 * 512 // 1
+    assert (b["form"], b["LG"], b["K"], b["NW"]) == ("banded-shared", 16, 12, 1) and b["wgs"] * b["GS"] >= 4 * 512 // 1

@@ -355,9 +355,30 @@ def test_backward_edge_shapes(s2d, shape):
 
 
 @pytest.mark.parametrize("variant,W", [("16,4", 60), ("16,8", 60), ("16,12", 190), ("16,16", 250),
-                                       ("64,4", 250), ("64,4,8", 250), ("64,8", 260), ("64,16", 60)])
+                                       ("64,4", 250), ("64,4,8", 250), ("64,8", 260), ("64,16", 60),
+                                       # LG,K,WAVES,GS,shared: the plain main sweep where the shared-producer one is the default
+                                       ("16,4,4,0,0", 60), ("16,8,4,0,0", 121), ("16,12,4,0,0", 190)])
 def test_backward_variants(s2d, variant, W):
     check_bwd(s2d, wl.Workload("bvar", 2, 6, 16, 11, W, wl.F32, mask_frac=0.3, backward=True), seed=6, variant=variant)
+
+
+# The main sweep whose lane groups share the per-position work through LDS, every compiled tiling (LG,K,WAVES,GS,1):
+# widths on and off the lane grid, heights off the band grid, channel counts off the channel-group grid.
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("variant,shape", [
+    ("16,4,4,0,1", (2, 7, 16, 11, 64)), ("16,4,4,3,1", (1, 10, 16, 9, 57)), ("16,8,4,0,1", (2, 5, 16, 10, 128)),
+    ("16,8,4,2,1", (1, 7, 16, 13, 99)), ("16,12,4,0,1", (1, 9, 16, 6, 192)), ("16,12,4,4,1", (2, 6, 16, 11, 185)),
+    ("32,6,8,0,1", (1, 5, 16, 9, 192)), ("32,6,8,2,1", (2, 3, 16, 7, 187)), ("32,4,8,0,1", (1, 5, 16, 9, 128)),
+    ("32,4,8,0,1", (2, 3, 16, 6, 101)), ("64,4,16,0,1", (1, 5, 16, 9, 256)), ("64,4,16,0,1", (1, 3, 16, 5, 203)),
+], ids=lambda v: v if isinstance(v, str) else "x".join(map(str, v)))
+def test_backward_shared_producer_variants(s2d, variant, shape, dtype):
+    Bt, Dc, N, H, W = shape
+    w = wl.Workload("bshared", Bt, Dc, N, H, W, dtype, mask_frac=0.3, backward=True)
+    import torch
+    with s2d.forced_variant(s2d.TUNE_BWD, variant):
+        plan = s2d.describe_plan(s2d.Desc(Bt, Dc, H, W, N, dtype, 0), s2d.PASS_BWD)
+    assert "form=banded-shared" in plan, plan
+    check_bwd(s2d, w, seed=12, variant=variant)
 
 
 @pytest.mark.parametrize("W", [72, 75, 190])
