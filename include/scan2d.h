@@ -36,9 +36,9 @@
  * Thread safety: entry points may be called concurrently from several host threads.
  *
  * Limits of this version: 1 <= N <= 64; N*H*W < 2^27 (the kernels address one map's states
- * with 32-bit lane offsets); any H, W >= 1 in the forward (maps wider than one lane-group
- * panel need a workspace, see scan2d_workspace_bytes); the backward accepts W <= 1024, and
- * W <= 256 when N > 16.  Shapes outside these limits return SCAN2D_ERR_BAD_SHAPE.
+ * with 32-bit lane offsets); any H, W >= 1 in the forward and in the backward (maps wider than
+ * one lane-group panel are swept panel by panel and need workspace for the carries between the
+ * panels, see scan2d_workspace_bytes).  Shapes outside these limits return SCAN2D_ERR_BAD_SHAPE.
  */
 #ifndef SCAN2D_H_
 #define SCAN2D_H_
@@ -53,8 +53,7 @@ extern "C" {
 enum {
     SCAN2D_OK                   =  0,
     SCAN2D_ERR_NULL_POINTER     = -1,  /* a required pointer is NULL */
-    SCAN2D_ERR_BAD_SHAPE        = -2,  /* a dimension < 1, N > 64, N*H*W >= 2^27, element count overflow,
-                                          or (backward only) W > 1024, or W > 256 with N > 16 */
+    SCAN2D_ERR_BAD_SHAPE        = -2,  /* a dimension < 1, N > 64, N*H*W >= 2^27, element count overflow */
     SCAN2D_ERR_BAD_DTYPE        = -3,
     SCAN2D_ERR_BAD_FLAGS        = -4,  /* flags holds an unknown bit */
     SCAN2D_ERR_WORKSPACE_SMALL  = -5,  /* workspace_bytes < scan2d_workspace_bytes() */

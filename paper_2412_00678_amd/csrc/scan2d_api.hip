@@ -299,6 +299,7 @@ int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = 
     return found ? SCAN2D_OK : SCAN2D_ERR_BAD_SHAPE;
 }
 
+}  // namespace
 // Kernels that use more than 64 KB of dynamic LDS need the attribute raised once per (device, kernel); the
 // pairs already done are remembered so that a launch (possibly under stream capture) makes no attribute call.
 bool allow_large_lds(const void* kernel, size_t bytes) {
@@ -318,6 +319,7 @@ bool allow_large_lds(const void* kernel, size_t bytes) {
     if (ndone < 256) done[ndone++] = Done{dev, kernel, bytes};
     return true;
 }
+namespace {
 
 // Workspace of the scan kernel itself: row-end states between column panels (wide maps).
 size_t fwd_workspace(const scan2d_desc* d, const FwdChoice& c) {

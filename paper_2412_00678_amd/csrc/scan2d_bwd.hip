@@ -166,6 +166,8 @@ struct BwdPlan {
     int NG = 0, GS = 0, CG = 0, nb = 0;
     BwdKernels k;
     size_t lds_bytes = 0;
+    int panels = 1;                                        // column panels of LG*K columns, one launch of each sweep per panel
+    size_t off_hc = 0, off_qc = 0;                         // carries between panels: [panels-1][maps][N][H] and [2][maps][N][H]
     bool shared = false;                                   // main sweep of scan2d_bwd_shared.hpp
     int ck_LG = 0, ck_waves = 0;                           // lane tiling of the checkpoint sweep
     bool step_outside = false;                             // softplus step written by a kernel of its own (banded form)
@@ -181,6 +183,10 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 // groups (56x56 bf16 x 6144 maps: 1.41 -> 1.08 ms; 128x192 fp32 x 2048 maps: 3.63 -> 2.86 ms); slower for wave-wide
 // groups on 16 waves, where the 128-register budget makes it spill (256x256 bf16: 2.0 -> 3.0 ms).
 bool shared_by_default(int LG, int K) { (void)K; return LG == 16; }
+
+}  // namespace
+bool allow_large_lds(const void* kernel, size_t bytes);   // scan2d_api.hip
+namespace {
 
 bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     BwdPlan pl;
@@ -213,12 +219,18 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     else if (W <= 256) { LG = 64; K = 4; }
     else if (W <= 512) { LG = 64; K = 8; }
     else if (W <= 1024) { LG = 64; K = 16; }
-    else return false;
+    else { LG = 64; K = 4; }
+    // maps wider than the widest tiling (and, beyond 16 states, wider than 256 columns: the band arrays of four
+    // states per lane and 16 waves fill the LDS) are swept in panels of 256 columns
+    // (measured faster than the 8- and 16-column tilings from 257 columns on: 512x512 bf16 x 256 maps 9.97 -> 8.74 ms)
+    if (W > 256) { LG = 64; K = 4; pl.panels = (W + 255) / 256; }
     int force_waves = 0, force_gs = 0, want_shared = -1;
     if (tb.n >= 1) {                                             // tuning aid: LG,K[,WAVES[,GS[,shared]]]
         const int eLG = tb.v[0], eK = tb.v[1], eW = tb.v[2], eG = tb.v[3];
         const int got = tb.n;
-        if (got >= 2 && (eLG == 16 || eLG == 32 || eLG == 64) && eLG * eK >= W) { LG = eLG; K = eK; }
+        if (got >= 2 && (eLG == 16 || eLG == 32 || eLG == 64) && eLG * eK >= W && W <= 1024 && (N <= 16 || W <= 256)) {
+            LG = eLG; K = eK; pl.panels = 1;                     // a single-panel tiling forced on a map it covers
+        }
         if (got >= 3) force_waves = eW;
         if (got >= 4) force_gs = eG;
         if (got >= 5) want_shared = tb.v[4];
@@ -240,7 +252,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     pl.step_outside = sp;
     pl.fast = fast;
     // the main sweep that shares the per-position work through LDS, where it exists for this tiling (N = NG * NW)
-    if (want_shared != 0 && N % NW == 0) {
+    if (want_shared != 0 && N % NW == 0 && pl.panels == 1) {
         const BwdKernels ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16(LG, K, NW, N / NW, waves, W, sp)
                                                       : bwd_shared_kernels_f32(LG, K, NW, N / NW, waves, W, sp);
         if (ks.main != nullptr && (want_shared == 1 || shared_by_default(LG, K))) pl.k = ks;
@@ -299,6 +311,11 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     pl.off_pb = o; o += align_up(maps * sizeof(float));
     pl.off_step = o; o += pl.step_outside ? align_up(maps * (size_t)d->H * W * sizeof(float)) + 256 : 0;
     pl.off_tail = o; o += align_up((size_t)(W + 16) * (5 * (d->dtype == SCAN2D_BF16 ? 2 : 4) + 1));
+    if (pl.panels > 1) {
+        const size_t one = align_up(maps * N * (size_t)d->H * sizeof(float));
+        pl.off_hc = o; o += (size_t)(pl.panels - 1) * one;
+        pl.off_qc = o; o += 2 * one;
+    }
     pl.total = o;
     *out = pl;
     return true;
@@ -318,9 +335,9 @@ bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
     long long wgs;
     if (pl.small) wgs = (maps + 3) / 4;
     else wgs = ((long long)d->Bt * pl.CG + (pl.waves * 64 / pl.LG) / pl.NG - 1) / ((pl.waves * 64 / pl.LG) / pl.NG);
-    std::snprintf(text, text_bytes, "bwd form=%s LG=%d K=%d NW=%d waves=%d RB=%d GS=%d CG=%d bands=%d wgs=%lld lds=%zu workspace=%zu",
-                  pl.small ? "small" : (pl.shared ? "banded-shared" : "banded"), pl.LG, pl.K, pl.NW, pl.waves, pl.RB, pl.GS, pl.CG, pl.nb, wgs,
-                  pl.lds_bytes, pl.total);
+    std::snprintf(text, text_bytes, "bwd form=%s LG=%d K=%d NW=%d waves=%d RB=%d GS=%d CG=%d bands=%d panels=%d wgs=%lld lds=%zu workspace=%zu",
+                  pl.small ? "small" : (pl.shared ? "banded-shared" : "banded"), pl.LG, pl.K, pl.NW, pl.waves, pl.RB, pl.GS, pl.CG, pl.nb,
+                  pl.panels, wgs, pl.lds_bytes, pl.total);
     return true;
 }
 
@@ -420,26 +437,46 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
             hipLaunchKernelGGL(scan2d_bwd_step_kernel<float>, dim3((unsigned)(chunks * maps)), dim3(256), 0, stream,
                                static_cast<const float*>(delta), delta_bias, step, HW, d->Dc, chunks);
     }
-    if (pl.nb > 1 && pl.k.ckpt_fwd != nullptr && d->N == pl.k.cf_NG * pl.k.cf_NW) {
-        // the checkpoint sweep by the shared-producer forward kernel (checkpoint mode): it computes the softplus
-        // step itself from the raw projection, with the same function as the step kernel above
-        FwdArgs f;
-        f.x = x; f.delta = delta; f.A = A; f.Bm = Bm; f.Cm = Cm; f.Dskip = nullptr; f.mask = mask; f.y = nullptr;
-        f.delta_bias = delta_bias; f.carry = nullptr;
-        f.ck = a.ck; f.nb = pl.nb;
-        f.maps = maps; f.Dc = d->Dc; f.H = d->H; f.W = d->W; f.N = d->N;
-        f.NG = pl.k.cf_NG; f.MPW = (pl.k.cf_waves * 64 / pl.k.cf_LG) / pl.k.cf_NG; f.panels = 1; f.RPB = pl.k.cf_RPB;
-        const long long wgf = (maps + f.MPW - 1) / f.MPW;
-        if (wgf > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
-        const size_t lds_f = 2 * (size_t)f.MPW * f.RPB * 2 * pl.k.cf_LG * pl.k.cf_K * sizeof(float);   // the per-position buffers only
-        hipLaunchKernelGGL(pl.k.ckpt_fwd, dim3((unsigned)wgf), dim3(pl.k.cf_waves * 64), lds_f, stream, f);
-    } else if (pl.nb > 1) {
-        hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.ck_waves * 64), 0, stream, ac);
+    if (pl.lds_bytes > 65536 && !allow_large_lds(reinterpret_cast<const void*>(pl.k.main), pl.lds_bytes)) return SCAN2D_ERR_LAUNCH_FAILED;
+    if (pl.panels > 1) {
+        // wide maps: checkpoint sweeps left to right (row-end states handed on), main sweeps right to left (a*q handed on)
+        const size_t one = align_up((size_t)maps * d->N * d->H * sizeof(float));
+        const int PW = pl.LG * pl.K;
+        for (int q = 0; q < pl.panels; ++q) {
+            BwdArgs c = ac;
+            c.cb = q * PW;
+            c.hc_in = q > 0 ? reinterpret_cast<const float*>(ws + pl.off_hc + (size_t)(q - 1) * one) : nullptr;
+            c.hc_out = q + 1 < pl.panels ? reinterpret_cast<float*>(ws + pl.off_hc + (size_t)q * one) : nullptr;
+            hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.ck_waves * 64), 0, stream, c);
+        }
+        for (int q = pl.panels - 1; q >= 0; --q) {
+            BwdArgs m = a;
+            m.cb = q * PW;
+            m.hc_in = q > 0 ? reinterpret_cast<const float*>(ws + pl.off_hc + (size_t)(q - 1) * one) : nullptr;
+            m.qc_in = q + 1 < pl.panels ? reinterpret_cast<const float*>(ws + pl.off_qc + (size_t)((q + 1) & 1) * one) : nullptr;
+            m.qc_out = q > 0 ? reinterpret_cast<float*>(ws + pl.off_qc + (size_t)(q & 1) * one) : nullptr;
+            m.accum = q + 1 < pl.panels ? 1 : 0;
+            hipLaunchKernelGGL(pl.k.main, dim3((unsigned)wg2), dim3(pl.waves * 64), pl.lds_bytes, stream, m);
+        }
+    } else {
+        if (pl.nb > 1 && pl.k.ckpt_fwd != nullptr && d->N == pl.k.cf_NG * pl.k.cf_NW) {
+            // the checkpoint sweep by the shared-producer forward kernel (checkpoint mode): it computes the softplus
+            // step itself from the raw projection, with the same function as the step kernel above
+            FwdArgs f;
+            f.x = x; f.delta = delta; f.A = A; f.Bm = Bm; f.Cm = Cm; f.Dskip = nullptr; f.mask = mask; f.y = nullptr;
+            f.delta_bias = delta_bias; f.carry = nullptr;
+            f.ck = a.ck; f.nb = pl.nb;
+            f.maps = maps; f.Dc = d->Dc; f.H = d->H; f.W = d->W; f.N = d->N;
+            f.NG = pl.k.cf_NG; f.MPW = (pl.k.cf_waves * 64 / pl.k.cf_LG) / pl.k.cf_NG; f.panels = 1; f.RPB = pl.k.cf_RPB;
+            const long long wgf = (maps + f.MPW - 1) / f.MPW;
+            if (wgf > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+            const size_t lds_f = 2 * (size_t)f.MPW * f.RPB * 2 * pl.k.cf_LG * pl.k.cf_K * sizeof(float);   // the per-position buffers only
+            hipLaunchKernelGGL(pl.k.ckpt_fwd, dim3((unsigned)wgf), dim3(pl.k.cf_waves * 64), lds_f, stream, f);
+        } else if (pl.nb > 1) {
+            hipLaunchKernelGGL(pl.k.ckpt, dim3((unsigned)wg1), dim3(pl.ck_waves * 64), 0, stream, ac);
+        }
+        hipLaunchKernelGGL(pl.k.main, dim3((unsigned)wg2), dim3(pl.waves * 64), pl.lds_bytes, stream, a);
     }
-    if (pl.lds_bytes > 65536)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(pl.k.main),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes);
-    hipLaunchKernelGGL(pl.k.main, dim3((unsigned)wg2), dim3(pl.waves * 64), pl.lds_bytes, stream, a);
     if (pl.CG > 1) {
         const size_t NHW = (size_t)d->N * d->H * d->W;
         const size_t total = (size_t)d->Bt * NHW;

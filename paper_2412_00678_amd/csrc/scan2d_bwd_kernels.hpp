@@ -55,6 +55,15 @@ struct BwdArgs {
     int GS;              // channels a workgroup handles one after the other
     int CG;              // channel groups = ceil(Dc / GS)
     int nb;              // bands = ceil(H / RB)
+    // Maps wider than one lane-group panel are swept panel by panel (one launch each).  The row recurrences cross
+    // the panel borders through carry buffers [maps][N][H]: the checkpoint sweeps run left to right and hand on the
+    // row-end states hhor, the main sweeps run right to left and hand on a*q of their first column.
+    int cb = 0;                          // first column of this launch's panel
+    const float* hc_in = nullptr;        // row-end states of the panel to the left (null: first panel)
+    float* hc_out = nullptr;             // checkpoint sweep: row-end states of this panel (null: last panel)
+    const float* qc_in = nullptr;        // main sweep: a*q entering from the panel to the right (null: last panel)
+    float* qc_out = nullptr;             // main sweep: a*q of this panel's first column (null: first panel)
+    int accum = 0;                       // main sweep: add to pA / pD instead of overwriting them (all but the first launch)
 };
 
 template <int K>
@@ -123,9 +132,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
     const size_t HW = (size_t)H * W;
     const int b = (int)(map / p.Dc), c = (int)(map % p.Dc);
     const int n0 = sg * NW, nvalid = min(NW, N - n0);
-    const int col0 = l * K;
+    const int col0 = p.cb + l * K;
     const bool inside = col0 < W;
-    const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
+    const uint32_t lcol = inside ? (uint32_t)col0 : (uint32_t)p.cb;
     const T* xm = reinterpret_cast<const T*>(p.x) + (size_t)map * HW;
     const DT* dm = reinterpret_cast<const DT*>(p.delta) + (size_t)map * HW;
     const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
@@ -145,7 +154,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
     constexpr int PDX = (XW + XWD + K / 4 <= 28) ? 2 : 1;
     constexpr int SC = NW >= 4 ? 4 : NW;                      // states scanned together
     uint32_t rx[PDX][XW], rd[PDX][XWD], rm[PDX][K / 4], rB[NW][XW];
-    const int last = H - 2;                                   // the last row's state is never needed
+    const int last = p.hc_out != nullptr ? H - 1 : H - 2;     // the last row's state is never needed, its row-end state is
     // without FAST: is this lane's map / state plane / batch item the last of its tensor?  (the step of
     // the SP instantiations lives in the workspace, which has room behind it)
     const TailRows<T> tl(p.tail, W);
@@ -189,6 +198,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
                 for (int j = 0; j < K; ++j) a[t][j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
                 hl[t][0] = dxe[0] * get_elem<T, K>(rB[s], 0);
                 pl[t][0] = a[t][0];
+                if (p.hc_in != nullptr && l == 0)             // state entering from the panel to the left
+                    hl[t][0] = fmaf(a[t][0], p.hc_in[((size_t)map * N + n0 + (s < nvalid ? s : 0)) * H + i], hl[t][0]);
 #pragma unroll
                 for (int j = 1; j < K; ++j) {
                     hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dxe[j] * get_elem<T, K>(rB[s], j));
@@ -199,6 +210,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
                 Hh[t] = hl[t][K - 1];
             }
             group_scan<LG, SC>(P, Hh, cin);
+            if (p.hc_out != nullptr && l == LG - 1) {         // row-end states of this panel (a panel with a successor is full)
+#pragma unroll
+                for (int t = 0; t < SC; ++t)
+                    if (s0 + t < nvalid) p.hc_out[((size_t)map * N + n0 + s0 + t) * H + i] = Hh[t];
+            }
 #pragma unroll
             for (int t = 0; t < SC; ++t) {
 #pragma unroll
@@ -208,7 +224,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
                 }
             }
         }
-        if ((i + 1) % RB == 0) {                              // h[i] enters band (i+1)/RB
+        if ((i + 1) % RB == 0 && i + 1 < H) {                 // h[i] enters band (i+1)/RB
             const int band = (i + 1) / RB;
 #pragma unroll
             for (int s = 0; s < NW; ++s) {
@@ -270,9 +286,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     const int H = p.H, W = p.W, N = p.N;
     const size_t HW = (size_t)H * W;
     const int n0 = sg * NW, nvalid = min(NW, N - n0);
-    const int col0 = l * K;
+    const int col0 = p.cb + l * K;
     const bool inside = col0 < W;
-    const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
+    const uint32_t lcol = inside ? (uint32_t)col0 : (uint32_t)p.cb;
     const TailRows<T> tl(p.tail, W);                     // without FAST: see the checkpoint sweep
     const bool lastm = b == p.Bt - 1;
     bool lastB[NW];
@@ -381,6 +397,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                             for (int j = 0; j < K; ++j) a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
                             hl[0] = dxe[0] * get_elem<T, K>(fB[r & 1][s], 0);
                             pl[0] = a[0];
+                            float hcv = 0.0f;                             // state entering from the panel to the left
+                            if (p.hc_in != nullptr && l == 0) {
+                                hcv = p.hc_in[(map * N + n0 + (s < nvalid ? s : 0)) * H + i];
+                                hl[0] = fmaf(a[0], hcv, hl[0]);
+                            }
 #pragma unroll
                             for (int j = 1; j < K; ++j) {
                                 hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(fB[r & 1][s], j));
@@ -389,6 +410,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                             float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
                             group_scan<LG, 1>(P, Hh, cin);
                             float left = cin[0];                          // hhor[i, j-1]
+                            if (p.hc_in != nullptr && l == 0) left = hcv;
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
@@ -468,6 +490,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                             for (int j = 0; j + 1 < K; ++j) ar[j] = a[j + 1];
                             ar[K - 1] = from_right<LG>(a[0]);
                             ql[K - 1] = g[K - 1];
+                            if (p.qc_in != nullptr && l == LG - 1)        // a*q entering from the panel to the right
+                                ql[K - 1] += p.qc_in[(map * N + n0 + s) * H + i];
                             pr[K - 1] = ar[K - 1];
 #pragma unroll
                             for (int j = K - 2; j >= 0; --j) {
@@ -479,6 +503,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 const float q = fmaf(pr[j], qin[0], ql[j]);
+                                if (j == 0 && p.qc_out != nullptr && l == 0) p.qc_out[(map * N + n0 + s) * H + i] = a[0] * q;
                                 const float da = fmaf(g[j], hprev[r][s][j], q * hhl[r][s][j]);
                                 const float t = da * a[j];
                                 dAb[s] = fmaf(t, dl[j], dAb[s]);
@@ -499,11 +524,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                     if (act) {
                         const float* base = part + (size_t)(step & 1) * 2 * THREADS * K + (size_t)(slot - sg) * PANEL;
                         for (int col = sg * LG + l; col < PANEL; col += NG * LG) {
-                            if (col < W) {
+                            const int gc = p.cb + col;
+                            if (gc < W) {
                                 const float dd = sum_partials<PANEL>(base + col, NG);
-                                if constexpr (SP) ddw[ro + col] = dd;       // over the step of this cell, which nobody reads again
-                                else store_elem(ddm + ro + col, dd);
-                                store_elem(dxm + ro + col, sum_partials<PANEL>(base + THREADS * K + col, NG));
+                                if constexpr (SP) ddw[ro + gc] = dd;        // over the step of this cell, which nobody reads again
+                                else store_elem(ddm + ro + gc, dd);
+                                store_elem(dxm + ro + gc, sum_partials<PANEL>(base + THREADS * K + col, NG));
                             }
                         }
                     }
@@ -562,9 +588,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             }
             if (act && l == 0) {
                 if (s < NW) {
-                    if (s < nvalid) p.pA[((size_t)b * p.Dc + c) * N + n0 + s] = v;
+                    if (s < nvalid) {
+                        float* dst = p.pA + ((size_t)b * p.Dc + c) * N + n0 + s;
+                        *dst = p.accum ? *dst + v : v;            // panels are launched one after the other
+                    }
                 } else if (sg == 0 && p.pD != nullptr) {
-                    p.pD[(size_t)b * p.Dc + c] = v;
+                    float* dst = p.pD + (size_t)b * p.Dc + c;
+                    *dst = p.accum ? *dst + v : v;
                 }
             }
         }

@@ -381,6 +381,18 @@ def test_backward_shared_producer_variants(s2d, variant, shape, dtype):
     check_bwd(s2d, w, seed=12, variant=variant)
 
 
+# Maps wider than one lane-group panel (and, beyond 16 states, wider than 256 columns) are swept in panels of 256
+# columns with the row recurrences carried across the panel borders in both directions.
+@pytest.mark.parametrize("shape", [(1, 3, 16, 7, 1500, wl.F32, 0.3), (1, 2, 64, 6, 600, wl.BF16, 0.3), (2, 3, 32, 9, 300, wl.F32, 0.2),
+                                   (1, 2, 16, 3, 1027, wl.BF16, 0.0), (1, 2, 24, 1, 513, wl.F32, 0.3), (1, 5, 16, 5, 2049, wl.F32, 0.3)],
+                         ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_backward_of_wide_maps_in_column_panels(s2d, shape):
+    Bt, Dc, N, H, W, dtype, mf = shape
+    plan = s2d.describe_plan(s2d.Desc(Bt, Dc, H, W, N, dtype, 0), s2d.PASS_BWD)
+    assert f"panels={-(-W // 256)} " in plan, plan
+    check_bwd(s2d, wl.Workload("bwide", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True), seed=14)
+
+
 @pytest.mark.parametrize("W", [72, 75, 190])
 def test_backward_is_reproducible_and_ignores_garbage_under_the_mask(s2d, W):
     w = wl.Workload("brep", 2, 12, 16, 20, W, wl.F32, mask_frac=0.4, backward=True)
@@ -421,11 +433,8 @@ def test_workspace_too_small_and_unsupported_shapes_are_reported(s2d):
     assert e.value.code == -5
     torch.cuda.synchronize()
     assert bool((y == 7.0).all())                                          # nothing was written
-    # backward of maps wider than 1024 columns is not available in this version
-    assert s2d.workspace_bytes(desc, s2d.PASS_BWD) == 0
-    with pytest.raises(s2d.Scan2dError) as e:
-        s2d.scan2d_bwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], None, d["dy"])
-    assert e.value.code == -2
+    # backward of maps wider than 1024 columns: column panels, hence a workspace for the carries too
+    assert s2d.workspace_bytes(desc, s2d.PASS_BWD) > 0
     # a backward workspace that is too small
     w2 = wl.Workload("err2", 2, 8, 16, 12, 40, wl.F32, backward=True)
     d2 = s2d.to_device(wl.make_inputs(w2, seed=1), wl.F32)
@@ -685,7 +694,7 @@ def test_identity_cells_forward_and_backward_match_oracle(s2d, shape):
     assert np.isfinite(got).all()
     assert rel_err(got, wl.to_float(ref, dtype)) <= TOL[dtype]
     assert not np.array_equal(s2d.to_host(y), s2d.to_host(y_plain))         # the mode does change the result
-    if W <= 1024 and (N <= 16 or W <= 256):
+    if True:
         grads = s2d.scan2d_bwd(*args, d["dy"], flags=s2d.FLAG_IDENTITY_CELLS)
         torch.cuda.synchronize()
         refs = oracle.scan2d_bwd_skip(clean["x"], clean["delta"], clean["A"], clean["Bm"], clean["Cm"], clean["Dskip"],
