@@ -15,6 +15,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "scan2d_oracle.c")
+_SRC_VARIANTS = os.path.join(_HERE, "scan2d_oracle_variants.c")     # padding token, independent vertical decay
 _LIB = os.path.join(_HERE, "liboracle_scan2d.so")
 
 F32, BF16, F64 = 0, 1, 2
@@ -23,9 +24,10 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle (gcc -O2, no fast-math, OpenMP over independent maps)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_VARIANTS))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, _SRC, _SRC_VARIANTS, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -40,6 +42,10 @@ def _load():
         lib.oracle_scan2d_fwd.restype = ip
         lib.oracle_scan2d_bwd.argtypes = [ip] * 6 + [vp] * 14 + [ip]
         lib.oracle_scan2d_bwd.restype = ip
+        lib.oracle_scan2d_fwd_variants.argtypes = [ip] * 6 + [vp] * 10
+        lib.oracle_scan2d_fwd_variants.restype = ip
+        lib.oracle_scan2d_bwd_variants.argtypes = [ip] * 6 + [vp] * 18
+        lib.oracle_scan2d_bwd_variants.restype = ip
         lib.oracle_num_procs.restype = ip
         lib.oracle_round_to_bf16.argtypes = [vp, vp, ctypes.c_size_t]
         lib.oracle_round_to_bf16.restype = None
@@ -256,3 +262,62 @@ def scan2d_bwd_columns_first(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F32, th
     dx, dd, dA, dBm, dCm, dD = scan2d_bwd(_tr(x), _tr(delta), A, _tr(Bm), _tr(Cm), Dskip, _tr(mask), _tr(dy),
                                           dtype=dtype, threads=threads)
     return _tr(dx), _tr(dd), dA, _tr(dBm), _tr(dCm), dD
+
+
+# ----------------------------------------------------------------------------------------------
+# The two variants the paper ablates besides the scan order (scan2d_oracle_variants.c): a learnable padding
+# token under the mask (Eq. 4: x_eff = pad[c] there) and an independent decay parameter A_v for the vertical
+# scan (the supplement's ablation of re-using A-bar).  None = the default of the operator.
+
+def scan2d_fwd_variants(x, delta, A, Bm, Cm, Dskip=None, mask=None, A_v=None, pad=None, dtype=F32):
+    st = _storage(dtype)
+    x = np.ascontiguousarray(x)
+    Bt, Dc, H, W = x.shape
+    N = np.asarray(A).shape[1]
+    x = _chk(x, st, (Bt, Dc, H, W), "x")
+    delta = _chk(delta, st, (Bt, Dc, H, W), "delta")
+    A = _chk(A, np.float32, (Dc, N), "A")
+    A_v = _chk(A_v, np.float32, (Dc, N), "A_v", optional=True)
+    Bm = _chk(Bm, st, (Bt, N, H, W), "Bm")
+    Cm = _chk(Cm, st, (Bt, N, H, W), "Cm")
+    Dskip = _chk(Dskip, np.float32, (Dc,), "Dskip", optional=True)
+    mask = _chk(mask, np.uint8, (Bt, H, W), "mask", optional=True)
+    pad = _chk(pad, np.float32, (Dc,), "pad", optional=True)
+    y = np.empty_like(x)
+    rc = _load().oracle_scan2d_fwd_variants(Bt, Dc, H, W, N, dtype, _ptr(x), _ptr(delta), _ptr(A), _ptr(A_v),
+                                            _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(pad), _ptr(y))
+    if rc != 0:
+        raise RuntimeError(f"oracle_scan2d_fwd_variants failed ({rc})")
+    return y
+
+
+def scan2d_bwd_variants(x, delta, A, Bm, Cm, Dskip, mask, dy, A_v=None, pad=None, dtype=F32):
+    """Gradients (dx, ddelta, dA, dA_v, dBm, dCm, dDskip, dpad); dA_v / dDskip / dpad are None iff their input is."""
+    st = _storage(dtype)
+    x = np.ascontiguousarray(x)
+    Bt, Dc, H, W = x.shape
+    N = np.asarray(A).shape[1]
+    x = _chk(x, st, (Bt, Dc, H, W), "x")
+    delta = _chk(delta, st, (Bt, Dc, H, W), "delta")
+    dy = _chk(dy, st, (Bt, Dc, H, W), "dy")
+    A = _chk(A, np.float32, (Dc, N), "A")
+    A_v = _chk(A_v, np.float32, (Dc, N), "A_v", optional=True)
+    Bm = _chk(Bm, st, (Bt, N, H, W), "Bm")
+    Cm = _chk(Cm, st, (Bt, N, H, W), "Cm")
+    Dskip = _chk(Dskip, np.float32, (Dc,), "Dskip", optional=True)
+    mask = _chk(mask, np.uint8, (Bt, H, W), "mask", optional=True)
+    pad = _chk(pad, np.float32, (Dc,), "pad", optional=True)
+    dx, ddelta = np.empty_like(x), np.empty_like(x)
+    dA = np.empty((Dc, N), np.float32)
+    dA_v = None if A_v is None else np.empty((Dc, N), np.float32)
+    dBm = np.empty((Bt, N, H, W), np.float32)
+    dCm = np.empty((Bt, N, H, W), np.float32)
+    dDskip = None if Dskip is None else np.empty((Dc,), np.float32)
+    dpad = None if pad is None else np.empty((Dc,), np.float32)
+    rc = _load().oracle_scan2d_bwd_variants(Bt, Dc, H, W, N, dtype, _ptr(x), _ptr(delta), _ptr(A), _ptr(A_v),
+                                            _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(pad), _ptr(dy),
+                                            _ptr(dx), _ptr(ddelta), _ptr(dA), _ptr(dA_v), _ptr(dBm), _ptr(dCm),
+                                            _ptr(dDskip), _ptr(dpad))
+    if rc != 0:
+        raise RuntimeError(f"oracle_scan2d_bwd_variants failed ({rc})")
+    return dx, ddelta, dA, dA_v, dBm, dCm, dDskip, dpad

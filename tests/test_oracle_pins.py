@@ -672,3 +672,135 @@ def test_columns_first_backward_matches_central_differences():
         if name == "x_":
             fd[np.broadcast_to(mask[:, None] != 0, fd.shape)] = 0.0
         np.testing.assert_allclose(got, fd, rtol=2e-7, atol=2e-7 * max(1e-30, np.abs(fd).max()), err_msg=name)
+
+
+# ----------------------------------------------------------------------------- padding token, independent vertical decay
+# oracle.scan2d_fwd_variants / scan2d_bwd_variants (Eq. 4 and the padding-token ablation; the supplement's ablation
+# of re-using A-bar for the vertical scan).
+
+def brute_force_variants(x, delta, A, A_v, Bm, Cm, Dskip, mask, pad):
+    """Path-product closed form with its own decay on the vertical leg: right along row i' with a = exp(delta A),
+    then down column j with a_v = exp(delta A_v); x under the mask is pad[c].  Pure loops, no recurrence."""
+    Bt, Dc, H, W = x.shape
+    N = A.shape[1]
+    y = np.zeros((Bt, Dc, H, W))
+    for b in range(Bt):
+        for c in range(Dc):
+            xe = np.where(mask[b] != 0, float(pad[c]) if pad is not None else 0.0, x[b, c]) if mask is not None else x[b, c]
+            for i in range(H):
+                for j in range(W):
+                    acc = 0.0
+                    for n in range(N):
+                        a = np.exp(delta[b, c] * float(A[c, n]))
+                        av = np.exp(delta[b, c] * float((A_v if A_v is not None else A)[c, n]))
+                        hsum = 0.0
+                        for i2 in range(i + 1):
+                            for j2 in range(j + 1):
+                                w = 1.0
+                                for s in range(j2 + 1, j + 1):
+                                    w *= a[i2, s]
+                                for r in range(i2 + 1, i + 1):
+                                    w *= av[r, j]
+                                hsum += w * delta[b, c, i2, j2] * Bm[b, n, i2, j2] * xe[i2, j2]
+                        acc += Cm[b, n, i, j] * hsum
+                    y[b, c, i, j] = acc + (float(Dskip[c]) * xe[i, j] if Dskip is not None else 0.0)
+    return y
+
+
+def _variant_problem(seed, Bt=2, Dc=2, N=3, H=4, W=5):
+    rng = np.random.default_rng(seed)
+    x, delta, A, Bm, Cm, Dskip, mask = rand_problem(rng, Bt, Dc, N, H, W)
+    A = (np.round(A * 64) / 64).astype(np.float32)
+    A_v = (np.round(-np.exp(rng.normal(0.3, 0.5, A.shape)) * 64) / 64).astype(np.float32)
+    Dskip = (np.round(Dskip * 64) / 64).astype(np.float32)
+    pad = (np.round(rng.standard_normal(Dc) * 64) / 64).astype(np.float32)
+    return rng, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad
+
+
+@pytest.mark.parametrize("use_av,use_pad", [(True, True), (True, False), (False, True)])
+def test_variants_match_the_brute_force_path_products(use_av, use_pad):
+    _, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad = _variant_problem(71, 1, 2, 2, 4, 4)
+    A_v, pad = (A_v if use_av else None), (pad if use_pad else None)
+    y = oracle.scan2d_fwd_variants(x, delta, A, Bm, Cm, Dskip, mask, A_v=A_v, pad=pad, dtype=F64)
+    np.testing.assert_allclose(y, brute_force_variants(x, delta, A, A_v, Bm, Cm, Dskip, mask, pad), rtol=1e-12, atol=1e-12)
+
+
+def test_variants_reduce_to_the_plain_operator():
+    """A_v = A is the paper's default (A-bar re-used); pad = 0 is the fixed zero token: bit for bit."""
+    rng, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad = _variant_problem(72, 2, 3, 4, 6, 5)
+    dy = rng.standard_normal(x.shape)
+    base_y = oracle.scan2d_fwd(x, delta, A, Bm, Cm, Dskip, mask, dtype=F64)
+    base_g = oracle.scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, dtype=F64)
+    zero = np.zeros_like(pad)
+    for av, pd in ((None, None), (A, None), (None, zero), (A, zero)):
+        assert np.array_equal(oracle.scan2d_fwd_variants(x, delta, A, Bm, Cm, Dskip, mask, A_v=av, pad=pd, dtype=F64), base_y)
+        dx, dd, dA, dAv, dB, dC, dD, dP = oracle.scan2d_bwd_variants(x, delta, A, Bm, Cm, Dskip, mask, dy, A_v=av, pad=pd, dtype=F64)
+        assert np.array_equal(dx, base_g[0]) and np.array_equal(dB, base_g[3]) and np.array_equal(dC, base_g[4])
+        assert np.array_equal(dD, base_g[5])
+        np.testing.assert_allclose(dd, base_g[1], rtol=1e-13, atol=1e-13)
+        # one parameter driving both decays: its gradient is the sum of the two
+        np.testing.assert_allclose(dA if av is None else dA.astype(np.float64) + dAv, base_g[2], rtol=2e-6)
+
+
+def test_vertical_decay_only_acts_down_the_columns():
+    """With a single row the vertical decay never acts; with a single column only it acts on the way down."""
+    _, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad = _variant_problem(73, 1, 2, 3, 1, 7)
+    y = oracle.scan2d_fwd_variants(x, delta, A, Bm, Cm, Dskip, mask, A_v=A_v, dtype=F64)
+    assert np.array_equal(y, oracle.scan2d_fwd(x, delta, A, Bm, Cm, Dskip, mask, dtype=F64))
+    _, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad = _variant_problem(74, 1, 2, 3, 7, 1)
+    y = oracle.scan2d_fwd_variants(x, delta, A, Bm, Cm, Dskip, mask, A_v=A_v, dtype=F64)
+    # a single column: h[i] = a_v[i] h[i-1] + u[i], the 1D recurrence (Eq. 1-2) with A_v as its parameter
+    assert np.allclose(y, oracle.scan2d_fwd(x, delta, A_v, Bm, Cm, Dskip, mask, dtype=F64), rtol=1e-13, atol=1e-13)
+
+
+def test_padding_token_is_x_replaced_under_the_mask():
+    """The operator only sees x_eff: storing pad[c] into x under the mask and dropping the mask gives the same y."""
+    _, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad = _variant_problem(75, 2, 3, 4, 5, 6)
+    y = oracle.scan2d_fwd_variants(x, delta, A, Bm, Cm, Dskip, mask, pad=pad, dtype=F64)
+    xr = np.where(mask[:, None] != 0, pad.astype(np.float64)[None, :, None, None], x)
+    assert np.array_equal(y, oracle.scan2d_fwd(xr, delta, A, Bm, Cm, Dskip, None, dtype=F64))
+    poisoned = np.where(mask[:, None] != 0, np.nan, x)           # a select: what is stored under the mask never leaks
+    assert np.array_equal(y, oracle.scan2d_fwd_variants(poisoned, delta, A, Bm, Cm, Dskip, mask, pad=pad, dtype=F64))
+
+
+def test_variants_backward_matches_central_differences_for_every_input():
+    rng, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad = _variant_problem(76)
+    dy = rng.standard_normal(x.shape)
+    dx, dd, dA, dAv, dB, dC, dD, dP = oracle.scan2d_bwd_variants(x, delta, A, Bm, Cm, Dskip, mask, dy, A_v=A_v, pad=pad, dtype=F64)
+    p = {"x": x, "delta": delta, "A": A, "A_v": A_v, "Bm": Bm, "Cm": Cm, "Dskip": Dskip, "pad": pad}
+    grads = {"x": dx, "delta": dd, "A": dA, "A_v": dAv, "Bm": dB, "Cm": dC, "Dskip": dD, "pad": dP}
+
+    def f(q):
+        y = oracle.scan2d_fwd_variants(q["x"], q["delta"], q["A"], q["Bm"], q["Cm"], q["Dskip"], mask, A_v=q["A_v"], pad=q["pad"], dtype=F64)
+        return float(np.sum(dy * y))
+
+    for k, g in grads.items():
+        fp32 = p[k].dtype == np.float32
+        eps = 2.0 ** -12 if fp32 else 1e-6
+        fd = np.zeros(p[k].shape)
+        it = np.nditer(p[k], flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            hi = {n: t.copy() for n, t in p.items()}
+            lo = {n: t.copy() for n, t in p.items()}
+            hi[k][idx] += eps
+            lo[k][idx] -= eps
+            fd[idx] = (f(hi) - f(lo)) / (2 * eps)
+        tol = 2e-6 if fp32 else 1e-7                     # fp32 outputs come back rounded
+        np.testing.assert_allclose(g, fd, rtol=tol, atol=tol * max(np.abs(fd).max(), 1e-30), err_msg=k)
+    assert not dx[np.broadcast_to(mask[:, None] != 0, dx.shape)].any()      # x under the mask has no influence
+
+
+def test_variants_low_precision_storage_rounds_once():
+    rng, x, delta, A, A_v, Bm, Cm, Dskip, mask, pad = _variant_problem(77, 1, 3, 4, 6, 7)
+    for dtype in (oracle.F32, oracle.BF16):
+        cast = (lambda t: wl.f32_to_bf16_bits(t.astype(np.float32))) if dtype == oracle.BF16 else (lambda t: t.astype(np.float32))
+        xs, ds, Bs, Cs = cast(x), cast(delta), cast(Bm), cast(Cm)
+        y = oracle.scan2d_fwd_variants(xs, ds, A, Bs, Cs, Dskip, mask, A_v=A_v, pad=pad, dtype=dtype)
+        wide = [wl.to_float(t, dtype) for t in (xs, ds, Bs, Cs)]
+        y64 = oracle.scan2d_fwd_variants(wide[0], wide[1], A, wide[2], wide[3], Dskip, mask, A_v=A_v, pad=pad, dtype=F64)
+        expect = wl.f32_to_bf16_bits(y64.astype(np.float32)) if dtype == oracle.BF16 else y64.astype(np.float32)
+        if dtype == oracle.F32:
+            assert np.array_equal(y, expect)
+        else:                                             # double -> bf16 directly; via fp32 may differ in rare double-rounding ties
+            assert np.mean(y == expect) > 0.999
