@@ -83,7 +83,8 @@ enum { SCAN2D_FLAG_IDENTITY_CELLS = 1 };
  * size; scan2d_workspace_bytes accounts for it.  Honoured by every forward and backward entry point.
  */
 enum { SCAN2D_FLAG_COLUMNS_FIRST = 2 };
-enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2, SCAN2D_PASS_BWD_SOFTPLUS = 3 };
+enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2, SCAN2D_PASS_BWD_SOFTPLUS = 3,
+       SCAN2D_PASS_FWD_VARIANTS = 4, SCAN2D_PASS_BWD_VARIANTS = 5 };
 
 typedef struct {
     int32_t  Bt, Dc, H, W, N;  /* batch, channels, grid height, grid width, states: all >= 1, N <= 64 */
@@ -196,6 +197,48 @@ int scan2d_bwd_softplus_gated(const scan2d_desc* desc,
                               void* dx, void* ddelta_raw, float* ddelta_bias, float* dA, float* dBm, float* dCm,
                               float* dDskip, void* dz,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Two variants of the operator that the paper ablates, as optional extra parameters (all device pointers):
+ *   A_v  [Dc][N] fp32: an independent decay parameter for the vertical scan (the supplement's ablation of
+ *        re-using A-bar): the column recurrence becomes h[i,j] = exp(delta * A_v[c,n]) * h[i-1,j] + hhor[i,j],
+ *        the row recurrence keeps exp(delta * A[c,n]).  NULL: A is used for both (the paper's default).
+ *   pad  [Dc] fp32: a learnable padding token (Eq. 4 and the padding-token ablation): a masked cell holds
+ *        x_eff = pad[c] instead of the fixed zero.  NULL, or mask == NULL: the zero token.  For bf16 storage the
+ *        token is rounded to bf16 (it takes the place of stored x values).
+ *   dA_v [Dc][N] fp32, dpad [Dc] fp32: their gradients, written by scan2d_bwd_variants; each must be non-NULL iff
+ *        its parameter is.  With A_v the gradient through the decays splits: dA collects the row part
+ *        q * hhor[i,j-1], dA_v the column part g * h[i-1,j].  dpad[c] = sum over batch items and masked cells of
+ *        (sum_n q * delta * Bm + Dskip[c] * dy); dx is +0 under the mask as always.
+ * Both run as ablation modes, not tuned paths: A_v through one guarded kernel tiling per storage type, pad through
+ * an element-wise copy of x in front of the scan kernels (and one pass over dx behind them).
+ */
+typedef struct {
+    const float* A_v;
+    const float* pad;
+    float* dA_v;     /* scan2d_bwd_variants only */
+    float* dpad;     /* scan2d_bwd_variants only */
+} scan2d_variants;
+
+/*
+ * scan2d_fwd / scan2d_bwd with the variants above (v == NULL or all fields NULL: exactly scan2d_fwd / scan2d_bwd).
+ * desc.flags must be 0 (the variants do not combine with the identity cells or the columns-first order:
+ * SCAN2D_ERR_BAD_FLAGS).  Workspace: scan2d_workspace_bytes(desc, SCAN2D_PASS_FWD_VARIANTS / _BWD_VARIANTS) is
+ * enough for any combination.  Everything else as scan2d_fwd / scan2d_bwd.
+ */
+int scan2d_fwd_variants(const scan2d_desc* desc,
+                        const void* x, const void* delta, const float* A,
+                        const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                        const scan2d_variants* v,
+                        void* y,
+                        void* workspace, size_t workspace_bytes, void* stream);
+int scan2d_bwd_variants(const scan2d_desc* desc,
+                        const void* x, const void* delta, const float* A,
+                        const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                        const scan2d_variants* v,
+                        const void* dy,
+                        void* dx, void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * scan2d_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving or

@@ -603,9 +603,21 @@ extern "C" int scan2d_bwd_softplus_gated(const scan2d_desc* desc, const void* x,
                     dDskip, workspace, inner, stream, z, y_scan, dyg, dz);
 }
 
+namespace {
+size_t variants_fwd_need(const scan2d_desc* d, bool av, bool pad);
+size_t variants_bwd_need(const scan2d_desc* d, bool av, bool pad);
+}  // namespace
+
 extern "C" size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass) {
     if (check_desc(desc) != SCAN2D_OK) return 0;
     if (pass == SCAN2D_PASS_FWD) return fwd_need(desc);
+    if (pass == SCAN2D_PASS_FWD_VARIANTS || pass == SCAN2D_PASS_BWD_VARIANTS) {   // enough for any combination of the variants
+        if (desc->flags != 0u) return 0;
+        size_t need = 0;
+        for (int av = 0; av < 2; ++av)
+            need = std::max(need, pass == SCAN2D_PASS_FWD_VARIANTS ? variants_fwd_need(desc, av != 0, true) : variants_bwd_need(desc, av != 0, true));
+        return need;
+    }
     if (pass == SCAN2D_PASS_BWD || pass == SCAN2D_PASS_BWD_SOFTPLUS || pass == SCAN2D_PASS_BWD_GATED) {
         const size_t inner = bwd_need(desc, pass != SCAN2D_PASS_BWD);
         if (inner == 0) return 0;
@@ -654,6 +666,136 @@ extern "C" const char* scan2d_strerror(int code) {
         case SCAN2D_ERR_SCRATCH_LIMIT: return "scan2d_bwd_static_scratch: the call needs more workspace than the built-in scratch array holds (SCAN2D_STATIC_SCRATCH_BYTES); use scan2d_bwd with a workspace";
         default: return "unknown scan2d error code";
     }
+}
+
+// ------------------------------------------------------------------ the ablated variants: padding token, own vertical decay
+namespace {
+// Forward plan of the instantiation with an independent vertical decay: 16-lane groups of 4 columns and 4 states,
+// guarded accesses, column panels - one kernel per storage type that covers every shape.
+bool fill_av(const scan2d_desc* d, FwdChoice* out) {
+    FwdChoice c;
+    c.LG = 16; c.K = 4; c.NW = 4; c.waves = 4;
+    c.exact = false; c.fast = false; c.multi = true;
+    c.NG = (d->N + 3) / 4;
+    const int slots = 16;
+    if (c.NG > slots) return false;
+    c.MPW = slots / c.NG;
+    c.panels = (d->W + 63) / 64;
+    const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
+    if (span >= 2147483648.0) return false;
+    c.kernel = d->dtype == SCAN2D_BF16 ? fwd_kernel_av_bf16() : fwd_kernel_av_f32();
+    c.RPB = c.NG > 1 ? 2 : 1;
+    c.lds_bytes = c.NG > 1 ? 2 * (size_t)c.RPB * 256 * 4 * sizeof(float) : 0;
+    *out = c;
+    return true;
+}
+size_t av_carry_bytes(const scan2d_desc* d, const FwdChoice& c) {
+    return c.panels > 1 ? align256((size_t)d->Bt * d->Dc * d->N * d->H * sizeof(float)) : 0;
+}
+size_t map_bytes(const scan2d_desc* d) {
+    return align256((size_t)d->Bt * d->Dc * d->H * d->W * (d->dtype == SCAN2D_BF16 ? 2 : 4));
+}
+// Workspace of the variant calls: [scan kernels][copy of x with the padding token][per-map sums of dpad]
+size_t variants_fwd_need(const scan2d_desc* d, bool av, bool pad) {
+    size_t inner;
+    if (av) {
+        FwdChoice c;
+        if (!fill_av(d, &c)) return 0;
+        inner = av_carry_bytes(d, c);
+    } else {
+        inner = align256(fwd_need(d));
+    }
+    return inner + (pad ? map_bytes(d) : 0);
+}
+size_t variants_bwd_need(const scan2d_desc* d, bool av, bool pad) {
+    const size_t inner = bwd_workspace_bytes(d, false, av);
+    if (inner == 0) return 0;
+    return align256(inner) + (pad ? map_bytes(d) + align256((size_t)d->Bt * d->Dc * sizeof(float)) : 0);
+}
+}  // namespace
+
+extern "C" int scan2d_fwd_variants(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
+                                   const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                                   const scan2d_variants* v, void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (desc->flags != 0u) return SCAN2D_ERR_BAD_FLAGS;
+    if (!x || !delta || !A || !Bm || !Cm || !y) return SCAN2D_ERR_NULL_POINTER;
+    const float* A_v = v != nullptr ? v->A_v : nullptr;
+    const float* pad = (v != nullptr && mask != nullptr) ? v->pad : nullptr;      // without a mask the token is nowhere
+    const void* ptrs[] = {x, delta, A, Bm, Cm, Dskip, mask, y, workspace, A_v, pad};
+    for (const void* q : ptrs)
+        if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    const size_t need = variants_fwd_need(desc, A_v != nullptr, pad != nullptr);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SCAN2D_ERR_WORKSPACE_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t inner = need - (pad != nullptr ? map_bytes(desc) : 0);
+    if (pad != nullptr) {                      // the scan runs without a mask on a copy of x that holds the token
+        void* xe = static_cast<char*>(workspace) + inner;
+        rc = pad_fill_launch(desc, x, mask, pad, xe, st);
+        if (rc != SCAN2D_OK) return rc;
+        x = xe; mask = nullptr;
+    }
+    if (A_v == nullptr) return fwd_impl(desc, x, delta, nullptr, 0, A, Bm, Cm, Dskip, mask, y, workspace, inner, stream);
+    FwdChoice ch;
+    if (!fill_av(desc, &ch)) return SCAN2D_ERR_BAD_SHAPE;
+    FwdArgs a;
+    a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.y = y;
+    a.delta_bias = nullptr; a.A_v = A_v;
+    a.carry = static_cast<float*>(workspace);
+    a.maps = (long long)desc->Bt * desc->Dc;
+    a.Dc = desc->Dc; a.H = desc->H; a.W = desc->W; a.N = desc->N;
+    a.NG = ch.NG; a.MPW = ch.MPW; a.panels = ch.panels; a.RPB = ch.RPB;
+    const long long wgs = (a.maps + ch.MPW - 1) / ch.MPW;
+    if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(ch.waves * 64), ch.lds_bytes, st, a);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+extern "C" int scan2d_bwd_variants(const scan2d_desc* desc, const void* x, const void* delta, const float* A,
+                                   const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                                   const scan2d_variants* v, const void* dy, void* dx, void* ddelta, float* dA, float* dBm,
+                                   float* dCm, float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (desc->flags != 0u) return SCAN2D_ERR_BAD_FLAGS;
+    if (!x || !delta || !A || !Bm || !Cm || !dy || !dx || !ddelta || !dA || !dBm || !dCm) return SCAN2D_ERR_NULL_POINTER;
+    if ((Dskip == nullptr) != (dDskip == nullptr)) return SCAN2D_ERR_NULL_POINTER;
+    const float* A_v = v != nullptr ? v->A_v : nullptr;
+    float* dA_v = v != nullptr ? v->dA_v : nullptr;
+    const float* pad = v != nullptr ? v->pad : nullptr;
+    float* dpad = v != nullptr ? v->dpad : nullptr;
+    if ((A_v == nullptr) != (dA_v == nullptr) || (pad == nullptr) != (dpad == nullptr)) return SCAN2D_ERR_NULL_POINTER;
+    const void* ptrs[] = {x, delta, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, dA, dBm, dCm, dDskip, workspace, A_v, dA_v, pad, dpad};
+    for (const void* q : ptrs)
+        if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    const size_t need = variants_bwd_need(desc, A_v != nullptr, pad != nullptr);
+    if (need == 0) return SCAN2D_ERR_BAD_SHAPE;
+    if (workspace == nullptr || workspace_bytes < need) return SCAN2D_ERR_WORKSPACE_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t inner = align256(bwd_workspace_bytes(desc, false, A_v != nullptr));
+    const uint8_t* scan_mask = mask;
+    float* ppad = nullptr;
+    if (pad != nullptr) {
+        ppad = reinterpret_cast<float*>(static_cast<char*>(workspace) + inner + map_bytes(desc));
+        if (mask != nullptr) {                 // the sweeps run without a mask on a copy of x that holds the token
+            void* xe = static_cast<char*>(workspace) + inner;
+            rc = pad_fill_launch(desc, x, mask, pad, xe, st);
+            if (rc != SCAN2D_OK) return rc;
+            x = xe; scan_mask = nullptr;
+        }
+    }
+    rc = bwd_launch(desc, x, delta, nullptr, false, A, Bm, Cm, Dskip, scan_mask, dy, dx, ddelta, nullptr, dA, dBm, dCm, dDskip,
+                    workspace, inner, st, A_v, dA_v);
+    if (rc != SCAN2D_OK) return rc;
+    // dx now holds the gradient of the copy: its sum over the masked cells is dpad, and dx itself is +0 there
+    if (pad != nullptr) rc = pad_grad_launch(desc, mask, dx, ppad, dpad, st);
+    return rc;
 }
 
 // ------------------------------------------------------------------ backward without a caller's workspace

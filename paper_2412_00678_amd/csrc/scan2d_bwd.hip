@@ -175,6 +175,8 @@ struct BwdPlan {
     bool fast = true;                                      // W is a multiple of the columns per lane
     size_t off_tail = 0;                                   // padded copies of the tensors' last rows (TailRows)
     size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, off_pb = 0, total = 0;   // pb: bias-gradient partials
+    bool av = false;                                       // independent decay of the column recurrence
+    size_t off_pAv = 0;                                    // partial sums of dA_v over batch items
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -188,11 +190,12 @@ bool shared_by_default(int LG, int K) { (void)K; return LG == 16; }
 bool allow_large_lds(const void* kernel, size_t bytes);   // scan2d_api.hip
 namespace {
 
-bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
+bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = false) {
     BwdPlan pl;
+    pl.av = av;
     const int W = d->W, N = d->N;
-    const TuneValues tb = tune_get(kTuneBwd);
-    if (W <= 16 && d->H <= 16 && N <= 16 && tb.n == 0) {
+    const TuneValues tb = av ? TuneValues() : tune_get(kTuneBwd);
+    if (W <= 16 && d->H <= 16 && N <= 16 && tb.n == 0 && !av) {
         // small maps: the whole map stays in registers; dBm/dCm partials per channel
         pl.small = true;
         pl.LG = 16; pl.K = 1; pl.NW = N <= 4 ? 1 : (N <= 8 ? 2 : 4); pl.waves = 4; pl.RB = d->H;
@@ -223,7 +226,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     // maps wider than the widest tiling (and, beyond 16 states, wider than 256 columns: the band arrays of four
     // states per lane and 16 waves fill the LDS) are swept in panels of 256 columns
     // (measured faster than the 8- and 16-column tilings from 257 columns on: 512x512 bf16 x 256 maps 9.97 -> 8.74 ms)
-    if (W > 256) { LG = 64; K = 4; pl.panels = (W + 255) / 256; }
+    if (W > 256 || av) { LG = 64; K = 4; pl.panels = (W + 255) / 256; }
     int force_waves = 0, force_gs = 0, want_shared = -1;
     if (tb.n >= 1) {                                             // tuning aid: LG,K[,WAVES[,GS[,shared]]]
         const int eLG = tb.v[0], eK = tb.v[1], eW = tb.v[2], eG = tb.v[3];
@@ -252,10 +255,14 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     pl.step_outside = sp;
     pl.fast = fast;
     // the main sweep that shares the per-position work through LDS, where it exists for this tiling (N = NG * NW)
-    if (want_shared != 0 && N % NW == 0 && pl.panels == 1) {
+    if (want_shared != 0 && N % NW == 0 && pl.panels == 1 && !av) {
         const BwdKernels ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16(LG, K, NW, N / NW, waves, W, sp)
                                                       : bwd_shared_kernels_f32(LG, K, NW, N / NW, waves, W, sp);
         if (ks.main != nullptr && (want_shared == 1 || shared_by_default(LG, K))) pl.k = ks;
+    }
+    if (av) {
+        if (sp) return false;
+        pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_av_bf16(NW, fast) : bwd_kernels_av_f32(NW, fast);
     }
     if (pl.k.main == nullptr)
         pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
@@ -279,7 +286,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     }
     const int gs_lds = (int)std::max<size_t>(1, (40960 - std::min<size_t>(fixed, 40960)) / per);
     const int JPW = slots / pl.NG;
-    const int gs_max = std::min({gs_lds, 8, d->Dc});
+    const int gs_max = av ? 1 : std::min({gs_lds, 8, d->Dc});   // av: one channel per workgroup (its dA_v partial stays in registers)
     int gs = 1;
     long long best_path = -1;
     for (int g = 1; g <= gs_max; ++g) {
@@ -311,6 +318,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
     pl.off_pb = o; o += align_up(maps * sizeof(float));
     pl.off_step = o; o += pl.step_outside ? align_up(maps * (size_t)d->H * W * sizeof(float)) + 256 : 0;
     pl.off_tail = o; o += align_up((size_t)(W + 16) * (5 * (d->dtype == SCAN2D_BF16 ? 2 : 4) + 1));
+    if (av) { pl.off_pAv = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0; }
     if (pl.panels > 1) {
         const size_t one = align_up(maps * N * (size_t)d->H * sizeof(float));
         pl.off_hc = o; o += (size_t)(pl.panels - 1) * one;
@@ -323,9 +331,9 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false) {
 
 }  // namespace
 
-size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus) {
+size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus, bool av) {
     BwdPlan pl;
-    return make_plan(d, &pl, softplus) ? pl.total : 0;
+    return make_plan(d, &pl, softplus, av) ? pl.total : 0;
 }
 
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
@@ -363,9 +371,9 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
                const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
                void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
-               size_t workspace_bytes, hipStream_t stream) {
+               size_t workspace_bytes, hipStream_t stream, const float* A_v, float* dA_v) {
     BwdPlan pl;
-    if (!make_plan(d, &pl, softplus)) return SCAN2D_ERR_BAD_SHAPE;
+    if (!make_plan(d, &pl, softplus, A_v != nullptr)) return SCAN2D_ERR_BAD_SHAPE;
     if (pl.total > 0 && (workspace == nullptr || workspace_bytes < pl.total)) return SCAN2D_ERR_WORKSPACE_SMALL;
     char* ws = static_cast<char*>(workspace);
     BwdArgs a;
@@ -380,6 +388,8 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.pD = dDskip == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pD) : dDskip);
     a.Bt = d->Bt; a.Dc = d->Dc; a.H = d->H; a.W = d->W; a.N = d->N;
     a.NG = pl.NG; a.GS = pl.GS; a.CG = pl.CG; a.nb = pl.nb;
+    a.A_v = A_v;
+    a.pAv = A_v == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pAv) : dA_v);
 
     const long long maps = (long long)d->Bt * d->Dc;
     if (pl.small) {
@@ -488,6 +498,9 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
         const int n = d->Dc * d->N;
         hipLaunchKernelGGL(scan2d_bwd_reduce_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
                            a.pA, a.pD, dA, dDskip, d->Bt, d->Dc, d->N);
+        if (A_v != nullptr)
+            hipLaunchKernelGGL(scan2d_bwd_reduce_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
+                               a.pAv, static_cast<const float*>(nullptr), dA_v, static_cast<float*>(nullptr), d->Bt, d->Dc, d->N);
     }
     if (pl.step_outside) {
         float* pb = ddelta_bias == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pb) : ddelta_bias);

@@ -8,7 +8,8 @@
 namespace scan2d {
 
 // softplus: the workspace of scan2d_bwd_softplus (the banded form adds one fp32 map-sized buffer for the step).
-size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus = false);
+// av: the instantiations with an independent decay parameter A_v for the column recurrence.
+size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus = false, bool av = false);
 
 // One line describing the backward plan; false when the shape has no plan.
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes);
@@ -19,6 +20,6 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
                const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
                void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
-               size_t workspace_bytes, hipStream_t stream);
+               size_t workspace_bytes, hipStream_t stream, const float* A_v = nullptr, float* dA_v = nullptr);
 
 }  // namespace scan2d

@@ -64,6 +64,9 @@ struct BwdArgs {
     const float* qc_in = nullptr;        // main sweep: a*q entering from the panel to the right (null: last panel)
     float* qc_out = nullptr;             // main sweep: a*q of this panel's first column (null: first panel)
     int accum = 0;                       // main sweep: add to pA / pD instead of overwriting them (all but the first launch)
+    // AV instantiations only (independent decay of the column recurrence, the supplement's A-bar ablation)
+    const float* A_v = nullptr;          // [Dc][N]
+    float* pAv = nullptr;                // [Bt][Dc][N] partial sums of dA_v
 };
 
 template <int K>
@@ -116,7 +119,7 @@ struct TailRows {
 };
 
 // ---------------------------------------------------------------------------- checkpoint sweep
-template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool SP = false>
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool SP = false, bool AV = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdArgs p) {
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
@@ -139,12 +142,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
     const DT* dm = reinterpret_cast<const DT*>(p.delta) + (size_t)map * HW;
     const uint8_t* mm = p.mask ? p.mask + (size_t)b * HW : nullptr;
     const T* Bs[NW];
-    float Ap[NW], h[NW][K];
+    float Ap[NW], Avp[NW], h[NW][K];
 #pragma unroll
     for (int s = 0; s < NW; ++s) {
         const int n = n0 + (s < nvalid ? s : 0);
         Bs[s] = reinterpret_cast<const T*>(p.Bm) + ((size_t)b * N + n) * HW;
         Ap[s] = p.A[(size_t)c * N + n] * kLog2e;
+        Avp[s] = AV ? p.A_v[(size_t)c * N + n] * kLog2e : 0.0f;
 #pragma unroll
         for (int j = 0; j < K; ++j) h[s][j] = 0.0f;
     }
@@ -220,7 +224,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 #pragma unroll
                 for (int j = 0; j < K; ++j) {
                     const float hh = (j == K - 1) ? Hh[t] : fmaf(pl[t][j], cin[t], hl[t][j]);
-                    fma_inplace(h[s0 + t][j], a[t][j], hh);
+                    if constexpr (AV) h[s0 + t][j] = fmaf(__builtin_amdgcn_exp2f(dl[j] * Avp[s0 + t]), h[s0 + t][j], hh);   // no asm behind a transcendental
+                    else fma_inplace(h[s0 + t][j], a[t][j], hh);
                 }
             }
         }
@@ -255,7 +260,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
 //   gaL  [GS][T*NW*K]  a[i+1,j]*g[i+1,j] of every channel, kept between bands
 //   dAL  [GS][T*NW]    per-lane partial of dA
 //   dDL  [GS][T]       per-lane partial of dDskip (first lane group of a map only)
-template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool PF, bool SP = false>
+// AV: the column recurrence has its own decay a_v = exp(step * A_v[c,n]); the gradient through the decays splits
+// into the row part q * hhor[i,j-1] (to A) and the column part g * h[i-1,j] (to A_v).
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool PF, bool SP = false, bool AV = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdArgs p) {
     constexpr int THREADS = WAVES * 64;
     constexpr int SLOTS = THREADS / LG;
@@ -269,6 +276,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
     float* gaL = part + 4 * THREADS * K;                 // [GS][THREADS][NW*K]
     float* dAL = gaL + (size_t)GS * THREADS * NW * K;    // [GS][THREADS][NW]
     float* dDL = dAL + (size_t)GS * THREADS * NW;        // [GS][THREADS]
+    float dVtot[NW];                                     // AV (one channel per workgroup): per-lane partial of dA_v over all bands
+#pragma unroll
+    for (int s = 0; s < NW; ++s) dVtot[s] = 0.0f;
 
     const int tid = threadIdx.x, slot = tid / LG, l = tid % LG;
     const int NG = p.NG, JPW = SLOTS / NG;               // jobs (batch item, channel group) per workgroup
@@ -337,11 +347,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             const T* dym = reinterpret_cast<const T*>(p.dy) + map * HW;
             T* dxm = reinterpret_cast<T*>(p.dx) + map * HW;
             T* ddm = reinterpret_cast<T*>(p.ddelta) + map * HW;
-            float An[NW], Ap[NW];
+            float An[NW], Ap[NW], Avn[NW], Avp[NW];
 #pragma unroll
             for (int s = 0; s < NW; ++s) {
                 An[s] = p.A[(size_t)c * N + n0 + (s < nvalid ? s : 0)];
                 Ap[s] = An[s] * kLog2e;
+                Avn[s] = AV ? p.A_v[(size_t)c * N + n0 + (s < nvalid ? s : 0)] : 0.0f;
+                Avp[s] = Avn[s] * kLog2e;
             }
             const float dsk = (p.Dskip != nullptr && sg == 0) ? p.Dskip[c] : 0.0f;
 
@@ -416,7 +428,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
                                 hhl[r][s][j] = left;
                                 hprev[r][s][j] = hcur[s][j];
-                                fma_inplace(hcur[s][j], a[j], hh);
+                                if constexpr (AV) hcur[s][j] = fmaf(__builtin_amdgcn_exp2f(dl[j] * Avp[s]), hcur[s][j], hh);
+                                else fma_inplace(hcur[s][j], a[j], hh);
                                 left = hh;
                             }
                         }
@@ -425,10 +438,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
             }
 
             // ---- scans 3 and 4, bottom row of the band first
-            float ga[NW][K], dAb[NW], dDb = 0.0f;
+            float ga[NW][K], dAb[NW], dVb[NW], dDb = 0.0f;
 #pragma unroll
             for (int s = 0; s < NW; ++s) {
                 dAb[s] = 0.0f;
+                dVb[s] = 0.0f;
 #pragma unroll
                 for (int j = 0; j < K; ++j) ga[s][j] = gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j];
             }
@@ -473,16 +487,17 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                     for (int s = 0; s < NW; ++s) {
                         if (act && s < nvalid) {
-                            float a[K], Bv[K], g[K];
+                            float a[K], av[K], Bv[K], g[K];
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
+                                av[j] = AV ? __builtin_amdgcn_exp2f(dl[j] * Avp[s]) : a[j];
                                 Bv[j] = get_elem<T, K>(bB[r & 1][s], j);
                                 const float hh = fmaf(a[j], hhl[r][s][j], dxe[j] * Bv[j]);   // hhor[i,j]
-                                const float hv = fmaf(a[j], hprev[r][s][j], hh);             // h[i,j]
+                                const float hv = fmaf(av[j], hprev[r][s][j], hh);            // h[i,j]
                                 dCacc[r][s][j] = fmaf(dyv[j], hv, dCacc[r][s][j]);
                                 g[j] = fmaf(dyv[j], get_elem<T, K>(bC[r & 1][s], j), ga[s][j]);   // scan 3
-                                ga[s][j] = a[j] * g[j];
+                                ga[s][j] = av[j] * g[j];
                             }
                             // scan 4: q[j] = g[j] + a[j+1] * q[j+1]
                             float ar[K], ql[K], pr[K];
@@ -504,10 +519,18 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
                             for (int j = 0; j < K; ++j) {
                                 const float q = fmaf(pr[j], qin[0], ql[j]);
                                 if (j == 0 && p.qc_out != nullptr && l == 0) p.qc_out[(map * N + n0 + s) * H + i] = a[0] * q;
+                                if constexpr (AV) {
+                                    const float th = q * hhl[r][s][j] * a[j];                // through the row recurrence's decay
+                                    const float tv = g[j] * hprev[r][s][j] * av[j];          // through the column recurrence's decay
+                                    dAb[s] = fmaf(th, dl[j], dAb[s]);
+                                    dVb[s] = fmaf(tv, dl[j], dVb[s]);
+                                    ddl[j] = fmaf(th, An[s], fmaf(tv, Avn[s], fmaf(q * Bv[j], xe[j], ddl[j])));
+                                } else {
                                 const float da = fmaf(g[j], hprev[r][s][j], q * hhl[r][s][j]);
                                 const float t = da * a[j];
                                 dAb[s] = fmaf(t, dl[j], dAb[s]);
                                 ddl[j] = fmaf(t, An[s], fmaf(q * Bv[j], xe[j], ddl[j]));
+                                }
                                 dxl[j] = fmaf(q * dl[j], Bv[j], dxl[j]);
                                 dBacc[r][s][j] = fmaf(q, dxe[j], dBacc[r][s][j]);
                             }
@@ -541,6 +564,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
 #pragma unroll
                 for (int j = 0; j < K; ++j) gaL[((size_t)ch * THREADS + tid) * (NW * K) + s * K + j] = ga[s][j];
                 dAL[((size_t)ch * THREADS + tid) * NW + s] += inside ? dAb[s] : 0.0f;
+                if constexpr (AV) dVtot[s] += inside ? dVb[s] : 0.0f;
             }
             dDL[(size_t)ch * THREADS + tid] += dDb;
         }
@@ -570,6 +594,27 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_main_kernel(const BwdAr
         }
     }
 
+    if constexpr (AV) {                               // dA_v[b,c,n], summed like dA below
+        for (int ch = 0; ch < GS; ++ch) {
+            const bool act = ch < nch;
+            const int c = c_first + ch;
+#pragma unroll
+            for (int s = 0; s < NW; ++s) {
+                float v = row_sum16(dVtot[s]);
+                if constexpr (LG == 64) {
+                    const int vi = __builtin_bit_cast(int, v);
+                    v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 0)) +
+                        __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 16)) +
+                        __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 32)) +
+                        __builtin_bit_cast(float, __builtin_amdgcn_readlane(vi, 48));
+                }
+                if (act && l == 0 && s < nvalid) {
+                    float* dst = p.pAv + ((size_t)b * p.Dc + c) * N + n0 + s;
+                    *dst = p.accum ? *dst + v : v;
+                }
+            }
+        }
+    }
     // dA[b,c,n] and dDskip[b,c]: sum the per-lane partials over the lane group in a fixed order
     for (int ch = 0; ch < GS; ++ch) {                 // uniform trip count: the sums use DPP
         const bool act = ch < nch;

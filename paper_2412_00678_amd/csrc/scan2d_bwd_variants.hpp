@@ -85,6 +85,25 @@ inline BwdKernels lookup_bwd_kernels(int LG, int K, int NW, int waves, bool fast
     return r;
 }
 
+// Independent decay of the column recurrence (AV): the two 256-column tilings that cover every shape through column
+// panels (one state per lane up to 16 states, four beyond), an ablation mode rather than a tuned path.
+BwdKernels bwd_kernels_av_f32(int NW, bool fast);
+BwdKernels bwd_kernels_av_bf16(int NW, bool fast);
+
+template <typename T>
+inline BwdKernels lookup_bwd_kernels_av(int NW, bool fast) {
+    BwdKernels r;
+    r.RB = 2; r.ckpt_NW = NW; r.ckpt_LG = 64; r.ckpt_waves = 16; r.ckpt_fast = fast;
+    if (NW == 1) {
+        r.ckpt = fast ? scan2d_bwd_ckpt_kernel<T, 64, 4, 1, 16, 2, true, false, true> : scan2d_bwd_ckpt_kernel<T, 64, 4, 1, 16, 2, false, false, true>;
+        r.main = fast ? scan2d_bwd_main_kernel<T, 64, 4, 1, 16, 2, true, false, false, true> : scan2d_bwd_main_kernel<T, 64, 4, 1, 16, 2, false, false, false, true>;
+    } else if (NW == 4) {
+        r.ckpt = fast ? scan2d_bwd_ckpt_kernel<T, 64, 4, 4, 16, 2, true, false, true> : scan2d_bwd_ckpt_kernel<T, 64, 4, 4, 16, 2, false, false, true>;
+        r.main = fast ? scan2d_bwd_main_kernel<T, 64, 4, 4, 16, 2, true, false, false, true> : scan2d_bwd_main_kernel<T, 64, 4, 4, 16, 2, false, false, false, true>;
+    }
+    return r;
+}
+
 // Small maps (W, H, N <= 16): one wavefront per map, NW = states per lane group of its four.
 BwdKernel bwd_small_kernel_f32(int NW, bool sp);
 BwdKernel bwd_small_kernel_bf16(int NW, bool sp);

@@ -237,4 +237,87 @@ int transpose_launch(int elem_bytes, const void* src, void* dst, long long plane
     return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
 }
 
+namespace {
+// Padding token: out = mask ? pad[c] : x (pad rounded to the storage type), one workgroup per map.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_pad_fill_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask,
+                                                              const float* __restrict__ pad, T* __restrict__ out, size_t HW, int Dc) {
+    const size_t map = blockIdx.x;
+    const uint32_t pbits = to_elem_bits<T>(pad[map % Dc]);
+    const T* src = x + map * HW;
+    T* dst = out + map * HW;
+    const uint8_t* m = mask + (map / Dc) * HW;
+    for (size_t e = threadIdx.x; e < HW; e += 256) {
+        const uint32_t v = m[e] != 0 ? pbits : elem_bits(src + e);
+        if constexpr (Elem<T>::kBytes == 4) reinterpret_cast<uint32_t*>(dst)[e] = v;
+        else dst[e].bits = (uint16_t)v;
+    }
+}
+
+// Gradient of the padding token: per map, the sum of dx over the masked cells (fixed order: strided partial sums
+// per thread, then a tree over the workgroup) goes to ppad[map]; dx under the mask becomes +0.
+template <typename T>
+__global__ __launch_bounds__(256) void scan2d_pad_grad_kernel(T* __restrict__ dx, const uint8_t* __restrict__ mask,
+                                                              float* __restrict__ ppad, size_t HW, int Dc) {
+    __shared__ float sh[256];
+    const size_t map = blockIdx.x;
+    T* g = dx + map * HW;
+    const uint8_t* m = mask + (map / Dc) * HW;
+    float acc = 0.0f;
+    for (size_t e = threadIdx.x; e < HW; e += 256) {
+        if (m[e] != 0) {
+            if constexpr (Elem<T>::kBytes == 4) { acc += __uint_as_float(elem_bits(g + e)); reinterpret_cast<uint32_t*>(g)[e] = 0u; }
+            else { acc += __uint_as_float(elem_bits(g + e) << 16); g[e].bits = 0; }
+        }
+    }
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) ppad[map] = sh[0];
+}
+// dpad[c] = sum over batch items of ppad[b][c] (all zeros when there is no mask: ppad == nullptr).
+__global__ void scan2d_pad_batch_kernel(const float* __restrict__ ppad, float* __restrict__ dpad, int Bt, int Dc) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < Dc) {
+        float acc = 0.0f;
+        if (ppad != nullptr)
+            for (int b = 0; b < Bt; ++b) acc += ppad[(size_t)b * Dc + c];
+        dpad[c] = acc;
+    }
+}
+}  // namespace
+
+int pad_fill_launch(const scan2d_desc* d, const void* x, const uint8_t* mask, const float* pad, void* out, hipStream_t stream) {
+    const long long maps = (long long)d->Bt * d->Dc;
+    if (maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    const size_t HW = (size_t)d->H * d->W;
+    (void)hipGetLastError();
+    if (d->dtype == SCAN2D_BF16)
+        hipLaunchKernelGGL(scan2d_pad_fill_kernel<bf16_t>, dim3((unsigned)maps), dim3(256), 0, stream, static_cast<const bf16_t*>(x), mask,
+                           pad, static_cast<bf16_t*>(out), HW, d->Dc);
+    else
+        hipLaunchKernelGGL(scan2d_pad_fill_kernel<float>, dim3((unsigned)maps), dim3(256), 0, stream, static_cast<const float*>(x), mask,
+                           pad, static_cast<float*>(out), HW, d->Dc);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
+int pad_grad_launch(const scan2d_desc* d, const uint8_t* mask, void* dx, float* ppad, float* dpad, hipStream_t stream) {
+    const long long maps = (long long)d->Bt * d->Dc;
+    if (maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    const size_t HW = (size_t)d->H * d->W;
+    (void)hipGetLastError();
+    if (mask != nullptr) {
+        if (d->dtype == SCAN2D_BF16)
+            hipLaunchKernelGGL(scan2d_pad_grad_kernel<bf16_t>, dim3((unsigned)maps), dim3(256), 0, stream, static_cast<bf16_t*>(dx), mask, ppad, HW, d->Dc);
+        else
+            hipLaunchKernelGGL(scan2d_pad_grad_kernel<float>, dim3((unsigned)maps), dim3(256), 0, stream, static_cast<float*>(dx), mask, ppad, HW, d->Dc);
+    }
+    hipLaunchKernelGGL(scan2d_pad_batch_kernel, dim3((d->Dc + 255) / 256), dim3(256), 0, stream,
+                       mask != nullptr ? ppad : nullptr, dpad, d->Bt, d->Dc);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
 }  // namespace scan2d

@@ -39,4 +39,12 @@ int skip_grad_launch(const scan2d_desc* d, const uint8_t* mask, void* ddelta, hi
 // 1, 2 or 4 bytes; 32 x 32 tiles through LDS.
 int transpose_launch(int elem_bytes, const void* src, void* dst, long long planes, int H, int W, hipStream_t stream);
 
+// Learnable padding token (2DMamba Eq. 4): a masked cell holds pad[c] instead of a fixed zero.  Element-wise kernels
+// around the unchanged scan kernels, like the identity cells: the scan runs without a mask on a copy of x that holds
+// pad[c] (rounded to the storage type) under the mask; the backward then leaves the gradient of that copy in dx, from
+// which dpad[c] = sum over the masked cells is taken (fixed order) before dx is set to +0 there.
+int pad_fill_launch(const scan2d_desc* d, const void* x, const uint8_t* mask, const float* pad, void* out, hipStream_t stream);
+// ppad: [Bt][Dc] fp32 scratch (not read when mask is null: dpad is then all zeros).
+int pad_grad_launch(const scan2d_desc* d, const uint8_t* mask, void* dx, float* ppad, float* dpad, hipStream_t stream);
+
 }  // namespace scan2d

@@ -52,6 +52,7 @@ struct FwdArgs {
     const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
     const float* Dskip; const uint8_t* mask; void* y;
     const float* delta_bias;   // [Dc] or null; read by the SP instantiations only (delta then holds the raw projection)
+    const float* A_v = nullptr; // [Dc][N]; read by the AV instantiations only: decay parameter of the column recurrence
     float* carry;        // [maps][N][H] row-end states between column panels (panels > 1 only)
     float* ck = nullptr; // checkpoint sweep of the backward pass only: [maps][nb][N][W] column states entering each band
     int nb = 0;          // bands of that sweep
@@ -94,8 +95,10 @@ struct FwdArgs {
 #endif
 constexpr int kPrefetchBudgetX = SCAN2D_PREFETCH_BUDGET_X, kPrefetchBudgetS = SCAN2D_PREFETCH_BUDGET_S;
 
+// AV: the column recurrence (Eq. 6) uses a decay of its own, a_v = exp(step * A_v[c,n]) - the supplement's ablation
+// of re-using A-bar for the vertical scan (one more exponential per state and column).
 template <typename T, int LG, int K, int NW, int WAVES, bool EXACT, bool FAST, bool MULTI, bool SP = false, bool MA = true,
-          bool UA = false>
+          bool UA = false, bool AV = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p) {
     static_assert(!UA || (FAST && !MA && Elem<T>::kBytes == 2), "UA: bf16 rows on odd 2-byte boundaries, unguarded loads");
     constexpr int SLOTS = WAVES * 64 / LG;
@@ -147,11 +150,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                  rsB = make_rsrc(Bu, up4(left_items * N * EBY)), rsC = make_rsrc(Cu, up4(left_items * N * EBY)),
                  rsm = make_rsrc(mu, up4(left_items));
 
-    float Ap[NW];
+    float Ap[NW], Avp[NW];
 #pragma unroll
     for (int s = 0; s < NW; ++s) {
         const int n = (EXACT || s < nvalid) ? n0 + s : n0;
         Ap[s] = p.A[(size_t)c * N + n] * kLog2e;             // a = exp2(delta * A * log2 e)
+        Avp[s] = AV ? p.A_v[(size_t)c * N + n] * kLog2e : 0.0f;
     }
     const float dsk = (p.Dskip != nullptr && sg == 0) ? p.Dskip[c] : 0.0f;
     // SP: `delta` holds the raw projection and the step is softplus(raw + delta_bias[c]) (Eq. 3)
@@ -314,7 +318,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_kernel(const FwdArgs p)
                         for (int j = 0; j < K; ++j) {
                             // Eq. 5; at the lane's last column the scan result is the state itself
                             const float hh = (j == K - 1) ? Hh[t] : fmaf(pl[t][j], cin[t], hl[t][j]);
-                            fma_inplace(h[s][j], a[t][j], hh);                          // Eq. 6
+                            // Eq. 6.  AV: plain fmaf - the one-line asm hides its operands from the compiler's hazard
+                            // handling, and a transcendental result may not be read by the very next instruction
+                            if constexpr (AV) h[s][j] = fmaf(__builtin_amdgcn_exp2f(dl[j] * Avp[s]), h[s][j], hh);
+                            else fma_inplace(h[s][j], a[t][j], hh);
                             const float cv = EXACT ? get_elem<T, K>(uC, j) : cmul * get_elem<T, K>(uC, j);
                             yacc[j] = fmaf(cv, h[s][j], yacc[j]);
                         }

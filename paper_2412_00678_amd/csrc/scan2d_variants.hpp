@@ -72,6 +72,11 @@ FwdKernel fwd_kernel_bf16(int LG, int K, int NW, int waves, bool exact, bool fas
 template <typename T, bool UA = false, bool SP = false>
 inline FwdKernel lookup_fwd_kernel_unaligned_mask(int LG, int K, int NW, int waves, bool exact, bool fast, bool multi);
 
+// Independent vertical decay (AV): one guarded, multi-panel capable, ragged-N capable instantiation per storage
+// type covers every shape (an ablation mode, not a tuned path).
+FwdKernel fwd_kernel_av_f32();
+FwdKernel fwd_kernel_av_bf16();
+
 // Narrow maps (W <= 32): KS columns per lane, NW = states per lane group of the wave's four.
 FwdKernel fwd_small_kernel_f32(int KS, int NW, bool sp);
 FwdKernel fwd_small_kernel_bf16(int KS, int NW, bool sp);

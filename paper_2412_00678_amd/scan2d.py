@@ -16,11 +16,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libscan2d.so")
 
 F32, BF16 = 0, 1
-PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS = 0, 1, 2, 3
+PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS, PASS_FWD_VARIANTS, PASS_BWD_VARIANTS = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
-           "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch")
+           "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants")
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ERR_SCRATCH_LIMIT = -9
 TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
@@ -30,6 +30,10 @@ class Desc(ctypes.Structure):
     _fields_ = [("Bt", ctypes.c_int32), ("Dc", ctypes.c_int32), ("H", ctypes.c_int32),
                 ("W", ctypes.c_int32), ("N", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("flags", ctypes.c_uint32)]
+
+
+class Variants(ctypes.Structure):
+    _fields_ = [("A_v", ctypes.c_void_p), ("pad", ctypes.c_void_p), ("dA_v", ctypes.c_void_p), ("dpad", ctypes.c_void_p)]
 
 
 class Scan2dError(RuntimeError):
@@ -51,6 +55,10 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_fwd_softplus.restype = ctypes.c_int
     lib.scan2d_bwd.argtypes = [ctypes.POINTER(Desc)] + [vp] * 14 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_bwd.restype = ctypes.c_int
+    lib.scan2d_fwd_variants.argtypes = [ctypes.POINTER(Desc)] + [vp] * 7 + [ctypes.POINTER(Variants), vp, vp, ctypes.c_size_t, vp]
+    lib.scan2d_fwd_variants.restype = ctypes.c_int
+    lib.scan2d_bwd_variants.argtypes = [ctypes.POINTER(Desc)] + [vp] * 7 + [ctypes.POINTER(Variants)] + [vp] * 7 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_bwd_variants.restype = ctypes.c_int
     lib.scan2d_bwd_static_scratch.argtypes = [ctypes.POINTER(Desc)] + [vp] * 14 + [vp]
     lib.scan2d_bwd_static_scratch.restype = ctypes.c_int
     lib.scan2d_bwd_softplus.argtypes = [ctypes.POINTER(Desc)] + [vp] * 16 + [vp, ctypes.c_size_t, vp]
@@ -259,6 +267,45 @@ def scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, workspace=None, flags=0, ou
     return dx, ddelta, dA, dBm, dCm, dDskip
 
 
+def scan2d_fwd_variants(x, delta, A, Bm, Cm, Dskip, mask, A_v=None, pad=None):
+    """The forward scan with an independent vertical decay parameter A_v [Dc][N] and / or a padding token pad [Dc]."""
+    desc = make_desc(x, A, 0)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(A_v, "A_v", torch.float32, (Dc, N), optional=True)
+    _check(pad, "pad", torch.float32, (Dc,), optional=True)
+    y = torch.empty_like(x)
+    workspace, wbytes = _workspace(desc, PASS_FWD_VARIANTS, x.device)
+    v = Variants(_ptr(A_v), _ptr(pad), None, None)
+    rc = lib.scan2d_fwd_variants(ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask),
+                                 ctypes.byref(v), _ptr(y), _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_fwd_variants")
+    return y
+
+
+def scan2d_bwd_variants(x, delta, A, Bm, Cm, Dskip, mask, dy, A_v=None, pad=None):
+    """Gradients (dx, ddelta, dA, dA_v, dBm, dCm, dDskip, dpad); dA_v / dDskip / dpad are None iff their input is."""
+    desc = make_desc(x, A, 0)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(A_v, "A_v", torch.float32, (Dc, N), optional=True)
+    _check(pad, "pad", torch.float32, (Dc,), optional=True)
+    dx, ddelta = torch.empty_like(x), torch.empty_like(x)
+    dA = torch.empty((Dc, N), dtype=torch.float32, device=x.device)
+    dA_v = None if A_v is None else torch.empty((Dc, N), dtype=torch.float32, device=x.device)
+    dBm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dCm = torch.empty((Bt, N, H, W), dtype=torch.float32, device=x.device)
+    dDskip = None if Dskip is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    dpad = None if pad is None else torch.empty((Dc,), dtype=torch.float32, device=x.device)
+    workspace, wbytes = _workspace(desc, PASS_BWD_VARIANTS, x.device)
+    v = Variants(_ptr(A_v), _ptr(pad), _ptr(dA_v), _ptr(dpad))
+    rc = lib.scan2d_bwd_variants(ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask),
+                                 ctypes.byref(v), _ptr(dy), _ptr(dx), _ptr(ddelta), _ptr(dA), _ptr(dBm), _ptr(dCm), _ptr(dDskip),
+                                 _ptr(workspace), wbytes, _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_bwd_variants")
+    return dx, ddelta, dA, dA_v, dBm, dCm, dDskip, dpad
+
+
 def scan2d_bwd_static_scratch(x, delta, A, Bm, Cm, Dskip, mask, dy, out, flags=0):
     """scan2d_bwd with the library's built-in scratch array as workspace.  Nothing is allocated, here or in the
     library: `out` = (dx, ddelta, dA, dBm, dCm, dDskip) are the caller's tensors (dDskip None iff Dskip is)."""
@@ -268,7 +315,7 @@ def scan2d_bwd_static_scratch(x, delta, A, Bm, Cm, Dskip, mask, dy, out, flags=0
                                        _ptr(Dskip), _ptr(mask), _ptr(dy), _ptr(dx), _ptr(ddelta), _ptr(dA),
                                        _ptr(dBm), _ptr(dCm), _ptr(dDskip), _stream_ptr())
     if rc != 0:
-        raise Scan2dError(rc, "scan2d_bwd_static_scratch")
+        raise Scan2dError(rc, "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants")
     return out
 
 

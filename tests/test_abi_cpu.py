@@ -29,7 +29,7 @@ def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted(
         ["scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
          "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
-         "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch"])
+         "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants"])
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -79,7 +79,7 @@ def test_workspace_query(lib):
     wide = lib.Desc(1, 2, 8, 3000, 4, 0, 0)
     assert lib.workspace_bytes(wide, lib.PASS_FWD) == 1 * 2 * 4 * 8 * 4
     assert lib.workspace_bytes(lib.Desc(0, 1, 1, 1, 1, 0, 0), lib.PASS_FWD) == 0
-    assert lib.workspace_bytes(small, 5) == 0
+    assert lib.workspace_bytes(small, 9) == 0                 # an unknown pass
     # the gated backward adds one map-sized buffer (dy * SiLU(z), storage type), rounded up to 256 bytes
     for dt, eb in ((0, 4), (1, 2)):
         d = lib.Desc(2, 8, 20, 40, 16, dt, 0)

@@ -886,3 +886,79 @@ def test_forward_random_shapes(s2d, seed):
 def test_backward_random_shapes(s2d, seed):
     Bt, Dc, N, H, W, dtype, mf = _random_shape(seed, True)
     check_bwd(s2d, wl.Workload(f"brand{seed}", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True), seed=seed)
+
+
+# ------------------------------------------------------------------ the ablated variants: padding token, own vertical decay
+
+def _variant_inputs(w, seed):
+    inp = wl.make_inputs(w, seed=seed)
+    r = np.random.default_rng(seed + 100)
+    inp["A_v"] = (-np.exp(r.normal(0.3, 0.5, (w.Dc, w.N)))).astype(np.float32)
+    inp["pad"] = r.standard_normal(w.Dc).astype(np.float32)
+    return inp
+
+
+VARIANT_SHAPES = [(2, 5, 16, 13, 70, wl.F32, 0.3), (1, 7, 16, 9, 57, wl.BF16, 0.4), (1, 3, 5, 6, 300, wl.F32, 0.3),
+                  (2, 3, 24, 5, 130, wl.BF16, 0.2), (1, 4, 16, 14, 14, wl.F32, 0.3), (1, 2, 16, 3, 520, wl.BF16, 0.3)]
+
+
+@pytest.mark.parametrize("use_av,use_pad", [(True, True), (True, False), (False, True), (False, False)], ids=["av+pad", "av", "pad", "plain"])
+@pytest.mark.parametrize("shape", VARIANT_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_padding_token_and_independent_vertical_decay_match_the_oracle(s2d, shape, use_av, use_pad):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("variants", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True)
+    inp = _variant_inputs(w, seed=31)
+    print(f"variants case Bt={Bt} Dc={Dc} N={N} H={H} W={W} dtype={dtype} A_v={use_av} pad={use_pad}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    A_v = torch.from_numpy(inp["A_v"]).cuda() if use_av else None
+    pad = torch.from_numpy(inp["pad"]).cuda() if use_pad else None
+    oa, op = (inp["A_v"] if use_av else None), (inp["pad"] if use_pad else None)
+    y = s2d.scan2d_fwd_variants(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], A_v=A_v, pad=pad)
+    grads = s2d.scan2d_bwd_variants(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["dy"], A_v=A_v, pad=pad)
+    torch.cuda.synchronize()
+    ry = oracle.scan2d_fwd_variants(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"], inp["mask"], A_v=oa, pad=op, dtype=dtype)
+    rg = oracle.scan2d_bwd_variants(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"], inp["mask"], inp["dy"],
+                                    A_v=oa, pad=op, dtype=dtype)
+    assert rel_err(wl.to_float(s2d.to_host(y), dtype), wl.to_float(ry, dtype)) <= TOL[dtype]
+    names = ("dx", "ddelta", "dA", "dA_v", "dBm", "dCm", "dDskip", "dpad")
+    for k, (name, g, r) in enumerate(zip(names, grads, rg)):
+        if r is None:
+            assert g is None, name
+            continue
+        g = s2d.to_host(g)
+        gv = wl.to_float(g, dtype) if k < 2 else g.astype(np.float64)
+        rv = wl.to_float(r, dtype) if k < 2 else r.astype(np.float64)
+        assert np.isfinite(gv).all(), name
+        tol = TOL[dtype] if k < 2 else (1e-4 if dtype == wl.F32 else 2e-2)
+        assert rel_err(gv, rv) <= tol, f"{name}: rel err {rel_err(gv, rv):.3e}"
+    m = np.broadcast_to(inp["mask"][:, None] != 0, grads[0].shape)          # dx under the mask is exactly +0
+    assert not s2d.to_host(grads[0]).view(np.uint32 if dtype == wl.F32 else np.uint16)[m].any()
+    if not use_av and not use_pad:            # no variant: bit for bit the plain entry points
+        assert np.array_equal(s2d.to_host(y), run_fwd(s2d, inp, dtype))
+        for g, r in zip((grads[0], grads[1], grads[2], grads[4], grads[5], grads[6]), run_bwd(s2d, inp, dtype)):
+            assert np.array_equal(s2d.to_host(g), r)
+
+
+def test_variants_reject_flags_and_mismatched_gradient_pointers(s2d):
+    import ctypes
+    import torch
+    w = wl.Workload("verr", 1, 4, 16, 8, 40, wl.F32, mask_frac=0.3, backward=True)
+    inp = _variant_inputs(w, seed=3)
+    d = s2d.to_device(inp, wl.F32)
+    desc = s2d.make_desc(d["x"], d["A"], s2d.FLAG_IDENTITY_CELLS)
+    y = torch.full_like(d["x"], 7.0)
+    ws = torch.empty(max(16, s2d.workspace_bytes(s2d.make_desc(d["x"], d["A"]), s2d.PASS_BWD_VARIANTS)), dtype=torch.uint8, device="cuda:0")
+    p = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())
+    v = s2d.Variants(None, p(torch.from_numpy(inp["pad"]).cuda()), None, None)
+    rc = s2d.lib.scan2d_fwd_variants(ctypes.byref(desc), p(d["x"]), p(d["delta"]), p(d["A"]), p(d["Bm"]), p(d["Cm"]), p(d["Dskip"]),
+                                     p(d["mask"]), ctypes.byref(v), p(y), p(ws), ws.numel(), None)
+    assert rc == -4                                           # flags do not combine with the variants
+    desc = s2d.make_desc(d["x"], d["A"])
+    outs = [torch.empty_like(d["x"]), torch.empty_like(d["x"]), torch.empty_like(d["A"]),
+            torch.empty(d["Bm"].shape, device="cuda:0"), torch.empty(d["Bm"].shape, device="cuda:0"), torch.empty_like(d["Dskip"])]
+    rc = s2d.lib.scan2d_bwd_variants(ctypes.byref(desc), p(d["x"]), p(d["delta"]), p(d["A"]), p(d["Bm"]), p(d["Cm"]), p(d["Dskip"]),
+                                     p(d["mask"]), ctypes.byref(v), p(d["dy"]), *[p(t) for t in outs], p(ws), ws.numel(), None)
+    assert rc == -1                                           # pad without dpad
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())
