@@ -315,7 +315,7 @@ def scan2d_bwd_static_scratch(x, delta, A, Bm, Cm, Dskip, mask, dy, out, flags=0
                                        _ptr(Dskip), _ptr(mask), _ptr(dy), _ptr(dx), _ptr(ddelta), _ptr(dA),
                                        _ptr(dBm), _ptr(dCm), _ptr(dDskip), _stream_ptr())
     if rc != 0:
-        raise Scan2dError(rc, "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants")
+        raise Scan2dError(rc, "scan2d_bwd_static_scratch")
     return out
 
 
