@@ -813,15 +813,21 @@ def test_columns_first_with_identity_cells_softplus_and_gate(s2d):
     assert rel_err(s2d.to_host(g[7]), f64(inp["dy"]) * y_scan * sg * (1.0 + z * (1.0 - sg))) <= 1e-4   # dz
 
 
-def test_forward_and_backward_replay_from_a_hip_graph(s2d):
+@pytest.mark.parametrize("shape", [(2, 12, 16, 40, 96, wl.F32), (1, 4, 16, 24, 256, wl.BF16)], ids=["40x96-f32", "24x256-bf16-large-lds"])
+def test_forward_and_backward_replay_from_a_hip_graph(s2d, shape):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so its calls can be captured; every replay must equal the eager result bit for
-    bit, also after the inputs changed and eager work ran in between."""
+    bit, also after the inputs changed and eager work ran in between.  The second shape takes kernels that
+    need more than 64 KB of dynamic LDS (the attribute is raised once per kernel, outside the capture)."""
     import torch
-    w = wl.Workload("graph", 2, 12, 16, 40, 96, wl.F32, mask_frac=0.3, backward=True)
+    Bt, Dc, N, H, W, dtype = shape
+    w = wl.Workload("graph", Bt, Dc, N, H, W, dtype, mask_frac=0.3, backward=True)
     sets = [wl.make_inputs(w, seed=k) for k in (11, 12)]
-    static = s2d.to_device(sets[0], wl.F32)
+    static = s2d.to_device(sets[0], dtype)
     desc = s2d.make_desc(static["x"], static["A"])
+    if W == 256:
+        lds = lambda which: int(s2d.describe_plan(desc, which).split(" lds=")[1].split()[0])
+        assert lds(s2d.PASS_FWD) > 65536 and lds(s2d.PASS_BWD) > 65536
     y = torch.empty_like(static["x"])
     ws_f = torch.empty(max(16, s2d.workspace_bytes(desc, s2d.PASS_FWD)), dtype=torch.uint8, device="cuda:0")
     ws_b = torch.empty(max(16, s2d.workspace_bytes(desc, s2d.PASS_BWD)), dtype=torch.uint8, device="cuda:0")
@@ -845,7 +851,7 @@ def test_forward_and_backward_replay_from_a_hip_graph(s2d):
         s2d.scan2d_fwd(*args, y=y, workspace=ws_f)
         grads = s2d.scan2d_bwd(*args, static["dy"], workspace=ws_b)
     for k in (0, 1, 0):
-        new = s2d.to_device(sets[k], wl.F32)
+        new = s2d.to_device(sets[k], dtype)
         for name in ("x", "delta", "A", "Bm", "Cm", "Dskip", "mask", "dy"):
             static[name].copy_(new[name])
         y.fill_(float("nan"))
@@ -857,8 +863,8 @@ def test_forward_and_backward_replay_from_a_hip_graph(s2d):
         ref = eager()                                   # eager work between the replays
         for a, b in zip(got, ref):
             assert np.array_equal(a, b)
-    yo = oracle_fwd(sets[0], wl.F32)
-    assert rel_err(got[0], yo) <= 1e-4
+    yo = oracle_fwd(sets[0], dtype)
+    assert rel_err(wl.to_float(got[0], dtype), wl.to_float(yo, dtype)) <= TOL[dtype]
 
 
 # ------------------------------------------------------------------ shapes nobody chose by hand
@@ -867,8 +873,6 @@ def _random_shape(seed, backward):
     r = np.random.default_rng(1000 + seed)
     N = int(r.choice([1, 2, 3, 4, 5, 8, 12, 16, 16, 16, 17, 24, 32, 64]))
     W = int(r.choice([r.integers(1, 17), r.integers(17, 65), r.integers(65, 257), r.integers(257, 700)]))
-    if backward and N > 16:
-        W = min(W, 256)
     H = int(r.integers(1, 24))
     Bt, Dc = int(r.integers(1, 4)), int(r.integers(1, 10))
     dtype = int(r.integers(0, 2))
@@ -962,3 +966,47 @@ def test_variants_reject_flags_and_mismatched_gradient_pointers(s2d):
     assert rc == -1                                           # pad without dpad
     torch.cuda.synchronize()
     assert bool((y == 7.0).all())
+
+
+# ------------------------------------------------------------------ tensors beyond 2^32 bytes
+
+def test_maps_beyond_the_32_bit_byte_range_land_at_their_own_index(s2d):
+    """x, step, y (and dy, dx, ddelta) of 4.4 GB each: the maps that straddle the 2^31- and 2^32-byte offsets, the
+    first and the last map are checked against the oracle.  The maps are eight random ones repeated with a per-map
+    scale, made on the GPU; the oracle gets the bits of the maps it checks."""
+    import torch
+    Dc, N, H, W = 4400, 4, 500, 500
+    HW = H * W
+    assert Dc * HW * 4 > 2 ** 32
+    w8 = wl.Workload("big8", 1, 8, N, H, W, wl.F32, mask_frac=0.3, backward=True)
+    inp = wl.make_inputs(w8, seed=41)
+    dev = "cuda:0"
+    scale = (1.0 + torch.arange(Dc, device=dev, dtype=torch.float32) / 8192.0)[None, :, None, None]
+    rep = lambda a: torch.from_numpy(a).to(dev).repeat(1, Dc // 8, 1, 1)
+    x, dy = rep(inp["x"]) * scale, rep(inp["dy"]) * scale
+    delta = rep(inp["delta"])
+    A = torch.from_numpy(np.tile(inp["A"], (Dc // 8, 1))).to(dev)
+    Dskip = torch.from_numpy(np.tile(inp["Dskip"], Dc // 8)).to(dev)
+    Bm, Cm, mask = (torch.from_numpy(inp[k]).to(dev) for k in ("Bm", "Cm", "mask"))
+    print(f"large-offset case Dc={Dc} N={N} H={H} W={W}: {x.numel() * 4 / 2**30:.2f} GiB per tensor", flush=True)
+    y = s2d.scan2d_fwd(x, delta, A, Bm, Cm, Dskip, mask)
+    torch.cuda.synchronize()
+    picks = sorted({0, 2 ** 31 // (HW * 4), 2 ** 31 // (HW * 4) + 1, 2 ** 32 // (HW * 4), 2 ** 32 // (HW * 4) + 1, Dc - 1})
+    sub = lambda t: np.ascontiguousarray(t[:, picks].cpu().numpy())
+    hA, hD = A[picks].cpu().numpy(), Dskip[picks].cpu().numpy()
+    ref = oracle.scan2d_fwd(sub(x), sub(delta), hA, inp["Bm"], inp["Cm"], hD, inp["mask"], dtype=wl.F32)
+    assert rel_err(sub(y), ref) <= 1e-4
+    # every other map: y of map m is that of map m % 8 computed with its own scale (linear in x), within rounding
+    probe = [7, 1234, 2146, 3333, 4295, 4398]
+    ref8 = oracle.scan2d_fwd(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"], inp["mask"], dtype=wl.F32)
+    for m in probe:
+        assert rel_err(y[0, m].cpu().numpy(), ref8[0, m % 8].astype(np.float64) * (1.0 + m / 8192.0)) <= 1e-4, m
+    del y
+    dx, ddelta, dA, dBm, dCm, dD = s2d.scan2d_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy)
+    torch.cuda.synchronize()
+    rg = oracle.scan2d_bwd(sub(x), sub(delta), hA, inp["Bm"], inp["Cm"], hD, inp["mask"], sub(dy), dtype=wl.F32)
+    assert rel_err(sub(dx), rg[0]) <= 1e-4
+    assert rel_err(sub(ddelta), rg[1]) <= 1e-4
+    assert rel_err(dA[picks].cpu().numpy(), rg[2]) <= 1e-4
+    assert rel_err(dD[picks].cpu().numpy(), rg[5]) <= 1e-4
+    assert bool(torch.isfinite(dBm).all()) and bool(torch.isfinite(dCm).all())
