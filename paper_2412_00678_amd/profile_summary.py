@@ -42,6 +42,9 @@ def runs():
     out.append(("trace_all", "--kernel-trace --stats", "python3 bench.py --no-cpu --all --paper-shapes --steps 150 --warmup 20", "trace_all.json"))
     out.append(("trace_block", "--kernel-trace --stats", "python3 bench.py --no-cpu --workload 4 --softplus --gated --steps 40 --warmup 8",
                 "trace_block.json"))
+    # the same two commands without the profiler: kernel tracing adds several microseconds to every launch
+    out.append(("plain_all", None, "python3 bench.py --no-cpu --all --paper-shapes --steps 150 --warmup 20", "plain_all.json"))
+    out.append(("plain_block", None, "python3 bench.py --no-cpu --workload 4 --softplus --gated --steps 40 --warmup 8", "plain_block.json"))
     out.append(("fetch_copy", "--pmc FETCH_SIZE", "./paper_2412_00678_amd/roofprobe --copy 5", None))
     out.append(("write_copy", "--pmc WRITE_SIZE", "./paper_2412_00678_amd/roofprobe --copy 5", None))
     return out
@@ -50,13 +53,15 @@ def runs():
 def command(run, runs_dir):
     name, opts, prog, stdout = run
     prog = prog.replace("bench.py", os.path.join(ROOT, "bench.py")).replace("./paper_2412_00678_amd", os.path.join(ROOT, "paper_2412_00678_amd"))
-    line = f"rocprofv3 {opts} -d {runs_dir}/{name} -o r -- {prog}"
+    line = prog if opts is None else f"rocprofv3 {opts} -d {runs_dir}/{name} -o r -- {prog}"
     return line + (f" > {runs_dir}/{stdout}" if stdout else " > /dev/null")
 
 
 def shown(run):
     """The command as the summaries quote it: relative paths, output folder elided."""
     name, opts, prog, _ = run
+    if opts is None:
+        return prog
     return f"cd /tmp && export TMPDIR=/tmp && rocprofv3 {opts} -d <out>/{name} -o r -- {prog}"
 
 
@@ -274,7 +279,7 @@ the 8 XCDs, kernel `{clock_kernel[:60]}`) was {ghz:.2f} GHz.
 | WRITE_SIZE | {write_copy:,.0f} | 1,048,576 | {ws:.3f} |
 """)
 
-    with open(os.path.join(runs_dir, "trace_all.json")) as f:
+    with open(os.path.join(runs_dir, "plain_all.json")) as f:
         ball = json.loads(f.read().strip().splitlines()[-1])
     rows = ["| workload | pass | plan | time by bench.py events (us) | G units/s | algorithmic GB/s |", "|---|---|---|---|---|---|"]
     for r in [ball["detail"]] + ball["others"]:
@@ -289,12 +294,13 @@ the 8 XCDs, kernel `{clock_kernel[:60]}`) was {ghz:.2f} GHz.
 
 `{shown(by_name['trace_all'])}`
 
-One process times all workloads, so a kernel instantiation that serves several workloads shows their average; kernel
-tracing adds a few microseconds per launch, which shows in the workloads of a dozen microseconds.
+One process times all workloads, so a kernel instantiation that serves several workloads shows their average.
 
 {kernel_table(runs_dir, 'trace_all')}
 
-The same run's own timings (events on the launch stream):
+Timings by bench.py's own events on the launch stream, from the same command without the profiler
+(`{shown(by_name['plain_all'])}`; kernel tracing adds several microseconds to every launch, which would double the
+figures of the workloads that take a dozen microseconds):
 
 """ + "\n".join(rows) + """
 
@@ -302,7 +308,7 @@ Grids of the paper's speed table (N = 16, fp32):
 
 """ + "\n".join(prow) + "\n")
 
-    with open(os.path.join(runs_dir, "trace_block.json")) as f:
+    with open(os.path.join(runs_dir, "plain_block.json")) as f:
         bb = json.loads(f.read().strip().splitlines()[-1])
     us = lambda d, k: f"{d[k] * 1e3:.0f}"
     with open(os.path.join(PROFILES, "scan2d_block_form_train128x192_fp32.md"), "w") as f:
@@ -314,7 +320,7 @@ One process times the plain, the softplus and the gated entry points one after t
 
 {kernel_table(runs_dir, 'trace_block')}
 
-bench.py's own event timings in the same run (us per call):
+bench.py's own event timings, from the same command without the profiler (us per call):
 
 | entry points | forward | backward |
 |---|---|---|
