@@ -78,9 +78,13 @@ enum { SCAN2D_FLAG_IDENTITY_CELLS = 1 };
  * SCAN2D_FLAG_COLUMNS_FIRST the order is the other one, the supplement's ablation of the scan order:
  *     v[i,j] = a[i,j] * v[i-1,j] + u[i,j],    h[i,j] = a[i,j] * h[i,j-1] + v[i,j],    y = Cm . h + Dskip * x_eff
  * (different from the default whenever the decay depends on the position).  Tensor layouts do not change.
- * The library transposes the maps into the workspace, runs the row-first kernels on H and W exchanged and
- * transposes the results back, so this order costs several passes over the tensors and a workspace of their
- * size; scan2d_workspace_bytes accounts for it.  Honoured by every forward and backward entry point.
+ * Where the kernels that share the per-position work of a map through LDS take the shape (forward: maps of at
+ * most 256 columns whose state count they are built for; backward: at most 192 columns and 16 states) the order
+ * is exchanged inside the kernels, at the cost of the default order and with its workspace.  For every other
+ * shape the library transposes the maps into the workspace, runs the row-first kernels on H and W exchanged and
+ * transposes the results back, which costs several passes over the tensors and a workspace of their size;
+ * scan2d_workspace_bytes accounts for it and scan2d_describe_plan says which form runs.  Honoured by every
+ * forward and backward entry point.
  */
 enum { SCAN2D_FLAG_COLUMNS_FIRST = 2 };
 enum { SCAN2D_PASS_FWD = 0, SCAN2D_PASS_BWD = 1, SCAN2D_PASS_BWD_GATED = 2, SCAN2D_PASS_BWD_SOFTPLUS = 3,
@@ -274,7 +278,8 @@ size_t scan2d_workspace_bytes(const scan2d_desc* desc, int pass);
  * workgroup, workgroups, dynamic LDS bytes, workspace bytes) into `text` (host memory, at most
  * `text_bytes` bytes including the terminating 0).  The workspace figure is that of the scan kernels alone
  * (without the buffers of the gate, the identity cells and the columns-first order); with
- * SCAN2D_FLAG_COLUMNS_FIRST the plan is that of the transposed maps.  Touches no device memory and enqueues nothing.
+ * SCAN2D_FLAG_COLUMNS_FIRST the text starts with "columns-first(in-kernel)" or with "columns-first(transposed)",
+ * and the plan is then that of the transposed maps.  Touches no device memory and enqueues nothing.
  * Returns SCAN2D_OK, or the error code the corresponding call would return for this descriptor.
  */
 int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* text, size_t text_bytes);

@@ -102,6 +102,7 @@ struct FwdChoice {
     size_t lds_bytes = 0;
     int NG = 0, MPW = 0, panels = 0;
     bool shared = false;          // the form that computes the per-position values once per map (scan2d_fwd_shared.hpp)
+    bool cf = false;              // columns first inside the kernel
     FwdKernel kernel = nullptr;
 };
 
@@ -179,7 +180,7 @@ struct V6 { int LG, K, NW, NG, waves, RPB; };
 const V6 kFwdSharedVariants[] = {SCAN2D_FWD_SHARED_VARIANTS(SCAN2D_X)};
 #undef SCAN2D_X
 
-bool fill_shared(const scan2d_desc* d, int LG, int K, int NW, int waves, int RPB, bool sp, FwdChoice* out) {
+bool fill_shared(const scan2d_desc* d, int LG, int K, int NW, int waves, int RPB, bool sp, FwdChoice* out, bool cf = false) {
     if (NW < 1 || LG < 16 || K < 4 || waves < 1 || RPB < 2) return false;
     if (d->N % NW != 0 || d->W > LG * K) return false;
     const int slots = waves * 64 / LG, NG = d->N / NW;
@@ -191,8 +192,11 @@ bool fill_shared(const scan2d_desc* d, int LG, int K, int NW, int waves, int RPB
     const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
     if (span >= 2147483648.0) return false;
     const bool ua = d->dtype == SCAN2D_BF16 && (d->W % 2) != 0;
-    c.kernel = d->dtype == SCAN2D_BF16 ? fwd_shared_kernel_bf16(LG, K, NW, NG, waves, RPB, sp, ua)
-                                       : fwd_shared_kernel_f32(LG, K, NW, NG, waves, RPB, sp);
+    c.cf = cf;
+    if (cf) c.kernel = d->dtype == SCAN2D_BF16 ? fwd_shared_kernel_bf16_cf(LG, K, NW, NG, waves, RPB, sp, ua)
+                                               : fwd_shared_kernel_f32_cf(LG, K, NW, NG, waves, RPB, sp);
+    else c.kernel = d->dtype == SCAN2D_BF16 ? fwd_shared_kernel_bf16(LG, K, NW, NG, waves, RPB, sp, ua)
+                                            : fwd_shared_kernel_f32(LG, K, NW, NG, waves, RPB, sp);
     if (c.kernel == nullptr) return false;
     const size_t panel = (size_t)LG * K;
     c.lds_bytes = (2 * (size_t)c.MPW * RPB * 2 * panel + 2 * (size_t)RPB * slots * panel) * sizeof(float);
@@ -265,9 +269,22 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
 }
 
 // sp: pick the instantiation that computes the step itself
-int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = true) {
+// cf: columns first inside the kernel; only the shared-producer form has such instantiations (SCAN2D_ERR_BAD_SHAPE
+//     when none of them takes the shape: the caller then runs columns first through transposes)
+int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = true, bool cf = false) {
     const TuneValues tsh = tune_get(kTuneShared);
-    if (tsh.n >= 5 && fill_shared(d, tsh.v[0], tsh.v[1], tsh.v[2], tsh.v[3], tsh.v[4], sp, out)) return SCAN2D_OK;
+    if (tsh.n >= 5 && fill_shared(d, tsh.v[0], tsh.v[1], tsh.v[2], tsh.v[3], tsh.v[4], sp, out, cf)) return SCAN2D_OK;
+    if (cf) {
+        bool any = false;
+        double low = 0.0;
+        for (const V6& v : kFwdSharedVariants) {
+            FwdChoice c;
+            if (v.NG * v.NW != d->N || !fill_shared(d, v.LG, v.K, v.NW, v.waves, v.RPB, sp, &c, true)) continue;
+            const double cost = fwd_cost(d, c);
+            if (!any || cost < low) { low = cost; *out = c; any = true; }
+        }
+        return any ? SCAN2D_OK : SCAN2D_ERR_BAD_SHAPE;
+    }
     const TuneValues tf = tune_get(kTuneFwd);
     if (tf.n >= 2) {                                               // tuning aid: LG,K,NW,WAVES[,RPB]
         const int LG = tf.v[0], K = tf.v[1], NW = tf.v[2], waves = tf.n >= 4 ? tf.v[3] : 4, rpb = tf.n >= 5 ? tf.v[4] : 0;
@@ -340,6 +357,19 @@ scan2d_desc swapped(const scan2d_desc* d) {
     t.H = d->W; t.W = d->H; t.flags = d->flags & ~(uint32_t)SCAN2D_FLAG_COLUMNS_FIRST;
     return t;
 }
+// Columns first inside the kernels (the same descriptor, no transposes): the forward when a shared-producer tiling
+// takes the shape, the backward when its plan is the banded form with the shared-producer main sweep.  Everything
+// else goes through the transposed copies.
+bool fwd_fused_cf(const scan2d_desc* d) {
+    FwdChoice ch;
+    return columns_first(d) && choose_fwd(d, &ch, false, true, true) == SCAN2D_OK;
+}
+bool bwd_fused_cf(const scan2d_desc* d, bool softplus) { return columns_first(d) && bwd_workspace_bytes(d, softplus) != 0; }
+scan2d_desc rows_first(const scan2d_desc* d) {
+    scan2d_desc t = *d;
+    t.flags = d->flags & ~(uint32_t)SCAN2D_FLAG_COLUMNS_FIRST;
+    return t;
+}
 struct Regions {                                 // byte offsets behind the inner call's own workspace
     size_t x, delta, dy, dx, ddelta, Bm, Cm, dBm, dCm, mask, y, total;
 };
@@ -358,6 +388,10 @@ Regions regions(const scan2d_desc* d, bool backward) {
 
 // Workspace of a forward call / of a backward call without the gate's own buffer; 0 = none, or no plan.
 size_t fwd_need(const scan2d_desc* d) {
+    if (fwd_fused_cf(d)) {
+        const scan2d_desc t = rows_first(d);
+        return fwd_need(&t);
+    }
     if (columns_first(d)) {
         const scan2d_desc t = swapped(d);
         return align256(fwd_need(&t)) + regions(d, false).total;
@@ -374,7 +408,7 @@ size_t fwd_need(const scan2d_desc* d) {
     return sk > 0 ? align256(inner) + sk : inner;
 }
 size_t bwd_need(const scan2d_desc* d, bool softplus) {
-    if (columns_first(d)) {
+    if (columns_first(d) && !bwd_fused_cf(d, softplus)) {
         const scan2d_desc t = swapped(d);
         const size_t inner = bwd_need(&t, softplus);
         return inner == 0 ? 0 : align256(inner) + regions(d, true).total;
@@ -421,10 +455,11 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
-    if (columns_first(desc))
+    const bool cf = fwd_fused_cf(desc);
+    if (columns_first(desc) && !cf)
         return fwd_columns_first(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, y, workspace, workspace_bytes, stream);
     FwdChoice ch;
-    rc = choose_fwd(desc, &ch, softplus != 0, mask == nullptr || (desc->W % 4) == 0);
+    rc = choose_fwd(desc, &ch, softplus != 0, mask == nullptr || (desc->W % 4) == 0, cf);
     if (rc != SCAN2D_OK) return rc;
     const size_t sk = skip_bytes(desc);
     const size_t need = sk > 0 ? align256(fwd_workspace(desc, ch)) : fwd_workspace(desc, ch);
@@ -547,7 +582,7 @@ int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         if (rc != SCAN2D_OK) return rc;
         dy = dyg;
     }
-    if (columns_first(desc))
+    if (columns_first(desc) && !bwd_fused_cf(desc, softplus))
         return bwd_columns_first(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm,
                                  dCm, dDskip, workspace, workspace_bytes, stream);
     return bwd_core(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
@@ -631,7 +666,9 @@ extern "C" int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* tex
     text[0] = 0;
     int rc = check_desc(desc);
     if (rc != SCAN2D_OK) return rc;
-    if (columns_first(desc)) {                   // the plan of the kernels that run: those of the transposed maps
+    const bool bwd_pass = pass == SCAN2D_PASS_BWD || pass == SCAN2D_PASS_BWD_SOFTPLUS || pass == SCAN2D_PASS_BWD_GATED;
+    const bool fused = pass == SCAN2D_PASS_FWD ? fwd_fused_cf(desc) : (bwd_pass && bwd_fused_cf(desc, pass != SCAN2D_PASS_BWD));
+    if (columns_first(desc) && !fused) {         // the plan of the kernels that run: those of the transposed maps
         const scan2d_desc t = swapped(desc);
         const int n = std::snprintf(text, text_bytes, "columns-first(transposed) ");
         if (n < 0 || (size_t)n >= text_bytes) return SCAN2D_OK;
@@ -640,11 +677,11 @@ extern "C" int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* tex
     if (pass == SCAN2D_PASS_BWD_SOFTPLUS || pass == SCAN2D_PASS_BWD_GATED) pass = SCAN2D_PASS_BWD;   // the same sweeps
     if (pass == SCAN2D_PASS_FWD) {
         FwdChoice ch;
-        rc = choose_fwd(desc, &ch);
+        rc = choose_fwd(desc, &ch, false, true, fused);
         if (rc != SCAN2D_OK) return rc;
         const long long maps = (long long)desc->Bt * desc->Dc;
-        std::snprintf(text, text_bytes, "fwd form=%s LG=%d K=%d NW=%d waves=%d RPB=%d NG=%d MPW=%d panels=%d fast=%d exact=%d wgs=%lld lds=%zu workspace=%zu",
-                      ch.K < 4 ? "small" : (ch.shared ? "shared" : "general"), ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
+        std::snprintf(text, text_bytes, "%sfwd form=%s LG=%d K=%d NW=%d waves=%d RPB=%d NG=%d MPW=%d panels=%d fast=%d exact=%d wgs=%lld lds=%zu workspace=%zu",
+                      fused ? "columns-first(in-kernel) " : "", ch.K < 4 ? "small" : (ch.shared ? "shared" : "general"), ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
                       (int)ch.fast, (int)ch.exact, (maps + ch.MPW - 1) / ch.MPW, ch.lds_bytes, fwd_workspace(desc, ch));
         return SCAN2D_OK;
     }

@@ -194,8 +194,12 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
     BwdPlan pl;
     pl.av = av;
     const int W = d->W, N = d->N;
+    // columns first inside the kernels: only the banded form with the shared-producer main sweep has such
+    // instantiations; no plan otherwise (the caller then runs columns first through transposes)
+    const bool cf = (d->flags & SCAN2D_FLAG_COLUMNS_FIRST) != 0;
+    if (cf && av) return false;
     const TuneValues tb = av ? TuneValues() : tune_get(kTuneBwd);
-    if (W <= 16 && d->H <= 16 && N <= 16 && tb.n == 0 && !av) {
+    if (W <= 16 && d->H <= 16 && N <= 16 && tb.n == 0 && !av && !cf) {
         // small maps: the whole map stays in registers; dBm/dCm partials per channel
         pl.small = true;
         pl.LG = 16; pl.K = 1; pl.NW = N <= 4 ? 1 : (N <= 8 ? 2 : 4); pl.waves = 4; pl.RB = d->H;
@@ -256,10 +260,14 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
     pl.fast = fast;
     // the main sweep that shares the per-position work through LDS, where it exists for this tiling (N = NG * NW)
     if (want_shared != 0 && N % NW == 0 && pl.panels == 1 && !av) {
-        const BwdKernels ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16(LG, K, NW, N / NW, waves, W, sp)
-                                                      : bwd_shared_kernels_f32(LG, K, NW, N / NW, waves, W, sp);
+        BwdKernels ks;
+        if (cf) ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16_cf(LG, K, NW, N / NW, waves, W, sp)
+                                             : bwd_shared_kernels_f32_cf(LG, K, NW, N / NW, waves, W, sp);
+        else ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16(LG, K, NW, N / NW, waves, W, sp)
+                                          : bwd_shared_kernels_f32(LG, K, NW, N / NW, waves, W, sp);
         if (ks.main != nullptr && (want_shared == 1 || shared_by_default(LG, K))) pl.k = ks;
     }
+    if (cf && pl.k.main == nullptr) return false;
     if (av) {
         if (sp) return false;
         pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_av_bf16(NW, fast) : bwd_kernels_av_f32(NW, fast);
@@ -343,7 +351,8 @@ bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
     long long wgs;
     if (pl.small) wgs = (maps + 3) / 4;
     else wgs = ((long long)d->Bt * pl.CG + (pl.waves * 64 / pl.LG) / pl.NG - 1) / ((pl.waves * 64 / pl.LG) / pl.NG);
-    std::snprintf(text, text_bytes, "bwd form=%s LG=%d K=%d NW=%d waves=%d RB=%d GS=%d CG=%d bands=%d panels=%d wgs=%lld lds=%zu workspace=%zu",
+    std::snprintf(text, text_bytes, "%sbwd form=%s LG=%d K=%d NW=%d waves=%d RB=%d GS=%d CG=%d bands=%d panels=%d wgs=%lld lds=%zu workspace=%zu",
+                  (d->flags & SCAN2D_FLAG_COLUMNS_FIRST) != 0 ? "columns-first(in-kernel) " : "",
                   pl.small ? "small" : (pl.shared ? "banded-shared" : "banded"), pl.LG, pl.K, pl.NW, pl.waves, pl.RB, pl.GS, pl.CG, pl.nb,
                   pl.panels, wgs, pl.lds_bytes, pl.total);
     return true;

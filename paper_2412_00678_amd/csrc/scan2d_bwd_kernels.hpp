@@ -119,8 +119,11 @@ struct TailRows {
 };
 
 // ---------------------------------------------------------------------------- checkpoint sweep
-template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool SP = false, bool AV = false>
+// CF (columns first, single panel only): the state that persists from row to row is v = a * v[i-1,j] + u, which
+// needs no row scan at all.
+template <typename T, int LG, int K, int NW, int WAVES, int RB, bool FAST, bool SP = false, bool AV = false, bool CF = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdArgs p) {
+    static_assert(!(CF && AV), "columns first has one decay");
     constexpr int SLOTS = WAVES * 64 / LG;
     constexpr int XW = words_of<T, K>();
     using DT = std::conditional_t<SP, float, T>;              // element type of the step
@@ -192,8 +195,17 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_ckpt_kernel(const BwdAr
         ld_elems<T, K, FAST>(xm + nxt_x, lcol, lastx && row_x == H - 1, tl.x, rx[XS]);
         ld_elems<DT, K, FAST>(dm + nxt_x, lcol, !SP && lastx && row_x == H - 1, reinterpret_cast<const DT*>(tl.delta), rd[XS]);
         ld_mask<K, FAST>(mm ? mm + nxt_x : nullptr, lcol, lastm && row_x == H - 1, tl.mask, rm[XS]);
+        if constexpr (CF) {
 #pragma unroll
-        for (int s0 = 0; s0 < NW; s0 += SC) {
+            for (int s = 0; s < NW; ++s) {
+#pragma unroll
+                for (int j = 0; j < K; ++j)
+                    h[s][j] = fmaf(__builtin_amdgcn_exp2f(dl[j] * Ap[s]), h[s][j], dxe[j] * get_elem<T, K>(rB[s], j));
+                ld_elems<T, K, FAST>(Bs[s] + nxt_s, lcol, lastB[s] && row_s == H - 1, tl.B, rB[s]);
+            }
+        }
+#pragma unroll
+        for (int s0 = 0; s0 < (CF ? 0 : NW); s0 += SC) {
             float a[SC][K], hl[SC][K], pl[SC][K], P[SC], Hh[SC], cin[SC];
 #pragma unroll
             for (int t = 0; t < SC; ++t) {

@@ -108,7 +108,11 @@ __device__ __forceinline__ float from_right_any(float v) {
 //   gaL  [GS][T][NW*K]             a[i+1,j]*g[i+1,j] of every channel, kept between bands
 //   dAL  [GS][SLOTS][NW]           dA of every channel, accumulated over the bands
 //   dDL  [GS][WAVES]               dDskip of every channel per wavefront, accumulated over the bands
-template <typename T, int LG, int K, int NW, int NG, int WAVES, int RB, bool FAST, bool SP>
+// CF: columns first (v = a * v[i-1,j] + u, then h = a * h[i,j-1] + v).  The checkpoints then hold v, the band
+// arrays hold v[i-1,j] (in `hprev`) and h[i,j-1] (in `hhl`), the reverse row scan q runs on dy * Cm alone and the
+// reverse column recurrence on its result (gv = q + a[i+1,j] * gv[i+1,j], kept in `ga` as a * gv); the gradient of u
+// is gv, that of the decay gv * v[i-1,j] + q * h[i,j-1]: the same instructions in the other order.
+template <typename T, int LG, int K, int NW, int NG, int WAVES, int RB, bool FAST, bool SP, bool CF = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const BwdArgs p) {
     constexpr int THREADS = WAVES * 64, SLOTS = THREADS / LG, JPW = SLOTS / NG, PANEL = LG * K, TMJ = NG * LG;
     static_assert(SLOTS % NG == 0 && JPW >= 1, "whole jobs per workgroup");
@@ -312,22 +316,33 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                             float a[K], hl[K], pl[K];
 #pragma unroll
                             for (int j = 0; j < K; ++j) a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
-                            hl[0] = dxe[0] * get_elem<T, K>(fB[PF ? (r & 1) : 0][s], 0);
+                            if constexpr (CF) {
+#pragma unroll
+                                for (int j = 0; j < K; ++j) {
+                                    hprev[r][s][j] = hcur[s][j];                                   // v[i-1,j]
+                                    hcur[s][j] = fmaf(a[j], hcur[s][j], dxe[j] * get_elem<T, K>(fB[PF ? (r & 1) : 0][s], j));
+                                }
+                                hl[0] = hcur[s][0];
+                            } else {
+                                hl[0] = dxe[0] * get_elem<T, K>(fB[PF ? (r & 1) : 0][s], 0);
+                            }
                             pl[0] = a[0];
 #pragma unroll
                             for (int j = 1; j < K; ++j) {
-                                hl[j] = fmaf(a[j], hl[j - 1], dxe[j] * get_elem<T, K>(fB[PF ? (r & 1) : 0][s], j));
+                                hl[j] = fmaf(a[j], hl[j - 1], CF ? hcur[s][j] : dxe[j] * get_elem<T, K>(fB[PF ? (r & 1) : 0][s], j));
                                 pl[j] = pl[j - 1] * a[j];
                             }
                             float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
                             group_scan<LG, 1>(P, Hh, cin);
-                            float left = cin[0];                          // hhor[i, j-1]
+                            float left = cin[0];                          // hhor[i, j-1] (CF: h[i, j-1])
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
                                 hhl[r][s][j] = left;
-                                hprev[r][s][j] = hcur[s][j];
-                                hcur[s][j] = fmaf(a[j], hcur[s][j], hh);
+                                if constexpr (!CF) {
+                                    hprev[r][s][j] = hcur[s][j];
+                                    hcur[s][j] = fmaf(a[j], hcur[s][j], hh);
+                                }
                                 left = hh;
                             }
                         }
@@ -379,11 +394,17 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                         for (int j = 0; j < K; ++j) {
                             a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
                             Bv[j] = get_elem<T, K>(bB[PF ? (r & 1) : 0][s], j);
-                            const float hh = fmaf(a[j], hhl[r][s][j], dxe[j] * Bv[j]);   // hhor[i,j]
-                            const float hv = fmaf(a[j], hprev[r][s][j], hh);             // h[i,j]
+                            // row first: hhor[i,j], then h[i,j]; columns first: v[i,j], then h[i,j]
+                            const float hh = fmaf(a[j], CF ? hprev[r][s][j] : hhl[r][s][j], dxe[j] * Bv[j]);
+                            const float hv = fmaf(a[j], CF ? hhl[r][s][j] : hprev[r][s][j], hh);
                             dCacc[r][s][j] = fmaf(dyv[j], hv, dCacc[r][s][j]);
-                            g[j] = fmaf(dyv[j], get_elem<T, K>(bC[PF ? (r & 1) : 0][s], j), ga[s][j]);   // scan 3
-                            ga[s][j] = a[j] * g[j];
+                            const float dyC = dyv[j] * get_elem<T, K>(bC[PF ? (r & 1) : 0][s], j);
+                            if constexpr (CF) {
+                                g[j] = dyC;
+                            } else {
+                                g[j] = dyC + ga[s][j];                                                  // scan 3
+                                ga[s][j] = a[j] * g[j];
+                            }
                         }
                         // scan 4: q[j] = g[j] + a[j+1] * q[j+1]
                         float ar[K], ql[K], pr[K];
@@ -402,13 +423,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
                             const float q = fmaf(pr[j], qin[0], ql[j]);
-                            const float da = fmaf(g[j], hprev[r][s][j], q * hhl[r][s][j]);
+                            float gc, du;                                  // gradient along the column recurrence, gradient of u
+                            if constexpr (CF) {
+                                gc = q + ga[s][j];
+                                ga[s][j] = a[j] * gc;
+                                du = gc;
+                            } else {
+                                gc = g[j];
+                                du = q;
+                            }
+                            const float da = fmaf(gc, hprev[r][s][j], q * hhl[r][s][j]);
                             const float t = da * a[j];
-                            const float qB = q * Bv[j];
+                            const float qB = du * Bv[j];
                             dAb[s] = fmaf(t, dl[j], dAb[s]);
                             ddl[j] = fmaf(t, An[s], fmaf(qB, xe[j], ddl[j]));
                             dxl[j] = fmaf(qB, dl[j], dxl[j]);
-                            dBacc[r][s][j] = fmaf(q, dxe[j], dBacc[r][s][j]);
+                            dBacc[r][s][j] = fmaf(du, dxe[j], dBacc[r][s][j]);
                         }
                     }
                     // sums over the states held by the other lane groups of this job

@@ -1,0 +1,8 @@
+// bf16-storage instantiations of the columns-first backward sweeps (16-lane tilings, shared-producer main sweep).
+#include "scan2d_bwd_variants.hpp"
+namespace scan2d {
+BwdKernels bwd_shared_kernels_bf16_cf(int LG, int K, int NW, int NG, int waves, int W, bool sp) {
+    return sp ? lookup_bwd_shared_kernels<bf16_t, true, true>(LG, K, NW, NG, waves, W)
+              : lookup_bwd_shared_kernels<bf16_t, false, true>(LG, K, NW, NG, waves, W);
+}
+}

@@ -40,25 +40,32 @@ struct BwdKernels {
 // W: the map width (the checkpoint sweep has its own columns per lane, hence its own row-end treatment)
 BwdKernels bwd_shared_kernels_f32(int LG, int K, int NW, int NG, int waves, int W, bool sp);
 BwdKernels bwd_shared_kernels_bf16(int LG, int K, int NW, int NG, int waves, int W, bool sp);
+// The columns-first instantiations (16-lane tilings only; everything else runs columns first through transposes)
+BwdKernels bwd_shared_kernels_f32_cf(int LG, int K, int NW, int NG, int waves, int W, bool sp);
+BwdKernels bwd_shared_kernels_bf16_cf(int LG, int K, int NW, int NG, int waves, int W, bool sp);
 
-template <typename T, bool SP>
+template <typename T, bool SP, bool CF = false>
 inline BwdKernels lookup_bwd_shared_kernels(int LG, int K, int NW, int NG, int waves, int W) {
     BwdKernels r;
 #define SCAN2D_X(lg, k, nw, ng, wv, rb, clg, ck, cnw, flg, fk, fnw, fng, fwv, frpb)                      \
+    if constexpr (!CF || lg == 16) {                                                                     \
     if (LG == lg && K == k && NW == nw && NG == ng && waves == wv) {                                     \
         constexpr int cwv = clg == 16 ? 4 : wv;                                                          \
         const bool fast = W % k == 0, cfast = W % ck == 0;                                               \
-        r.ckpt = cfast ? scan2d_bwd_ckpt_kernel<T, clg, ck, cnw, cwv, rb, true, SP> : scan2d_bwd_ckpt_kernel<T, clg, ck, cnw, cwv, rb, false, SP>; \
+        r.ckpt = cfast ? scan2d_bwd_ckpt_kernel<T, clg, ck, cnw, cwv, rb, true, SP, false, CF>           \
+                       : scan2d_bwd_ckpt_kernel<T, clg, ck, cnw, cwv, rb, false, SP, false, CF>;         \
         r.ckpt_NW = cnw; r.ckpt_LG = clg; r.ckpt_waves = cwv; r.ckpt_fast = cfast;                       \
-        r.main = fast ? scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, true, SP> : scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, false, SP>; \
+        r.main = fast ? scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, true, SP, CF>                 \
+                      : scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, false, SP, CF>;               \
         r.RB = rb; r.shared = true;                                                                      \
         if constexpr (Elem<T>::kBytes == 2) {                                                            \
-            r.ckpt_fwd = (W % 2) != 0 ? scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, true, rb>     \
-                                      : scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, false, rb>;   \
+            r.ckpt_fwd = (W % 2) != 0 ? scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, true, rb, CF>     \
+                                      : scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, false, rb, CF>;   \
         } else {                                                                                         \
-            r.ckpt_fwd = scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, false, rb>;       \
+            r.ckpt_fwd = scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, false, rb, CF>;   \
         }                                                                                                \
         r.cf_LG = flg; r.cf_K = fk; r.cf_NW = fnw; r.cf_NG = fng; r.cf_waves = fwv; r.cf_RPB = frpb;     \
+    }                                                                                                    \
     }
     SCAN2D_BWD_SHARED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X

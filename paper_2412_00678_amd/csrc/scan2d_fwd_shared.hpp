@@ -60,7 +60,10 @@ __device__ __forceinline__ void carry_apply(float* hl, const float* pl, const fl
 // CK > 0: the checkpoint sweep of the backward pass instead of the forward pass.  The recurrences are the same;
 // Cm, the sum over states and y are left out, and the column state h at the bottom of every band of CK rows is
 // written to p.ck ([maps][p.nb][N][W], the state entering band (i+1)/CK after row i; the last row's is never needed).
-template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0>
+// CF: columns first.  The column recurrence runs on u (v = a * v[i-1,j] + u, the register that persists from row to
+// row), the row scan then runs on its result (h = a * h[i,j-1] + v) and y reads the scanned value: the same
+// instructions in the other order.  The checkpoint sweep (CK > 0) then keeps v and needs no row scan at all.
+template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0, bool CF = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const FwdArgs p) {
     static_assert(!UA || Elem<T>::kBytes == 2, "UA: bf16 rows on odd 2-byte boundaries");
     constexpr int XW = words_of<T, K>();
@@ -254,31 +257,47 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                     for (int j = 0; j < K; ++j) a[t][j] = __builtin_amdgcn_exp2f(dlq[set][j] * Ap[s]);
                     uint32_t uB[XW];
                     unpacks(rB[SS][s], s, cur, uB);
-                    hl[t][0] = dxq[set][0] * get_elem<T, K>(uB, 0);
-                    pl[t][0] = a[t][0];
+                    if constexpr (CF) {
 #pragma unroll
-                    for (int j = 1; j < K; ++j) {
-                        hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dxq[set][j] * get_elem<T, K>(uB, j));
-                        pl[t][j] = pl[t][j - 1] * a[t][j];
+                        for (int j = 0; j < K; ++j)      // column recurrence first; plain fmaf: a comes straight from v_exp_f32
+                            h[s][j] = fmaf(a[t][j], h[s][j], dxq[set][j] * get_elem<T, K>(uB, j));
+                        hl[t][0] = h[s][0];
+                    } else {
+                        hl[t][0] = dxq[set][0] * get_elem<T, K>(uB, 0);
+                    }
+                    pl[t][0] = a[t][0];
+                    if constexpr (!(CF && CK > 0)) {
+#pragma unroll
+                        for (int j = 1; j < K; ++j) {
+                            hl[t][j] = fmaf(a[t][j], hl[t][j - 1], CF ? h[s][j] : dxq[set][j] * get_elem<T, K>(uB, j));
+                            pl[t][j] = pl[t][j - 1] * a[t][j];
+                        }
                     }
                     lds(rsB, s, nxt, rB[SS][s]);
-                    P[t] = pl[t][K - 1];
-                    Hh[t] = hl[t][K - 1];
+                    if constexpr (!(CF && CK > 0)) {
+                        P[t] = pl[t][K - 1];
+                        Hh[t] = hl[t][K - 1];
+                    }
                 }
-                if constexpr (kDppApply) group_scan_nocarry<LG, SC>(P, Hh, cin); else group_scan<LG, SC>(P, Hh, cin);
+                if constexpr (!(CF && CK > 0)) {
+                    if constexpr (kDppApply) group_scan_nocarry<LG, SC>(P, Hh, cin); else group_scan<LG, SC>(P, Hh, cin);
+                }
 #pragma unroll
                 for (int t = 0; t < SC; ++t) {
                     const int s = s0 + t;
-                    if constexpr (kDppApply && LG != 32) carry_apply<LG, K>(hl[t], pl[t], Hh[t]);                 // Eq. 5
+                    if constexpr (kDppApply && LG != 32 && !(CF && CK > 0)) carry_apply<LG, K>(hl[t], pl[t], Hh[t]);   // Eq. 5
                     uint32_t uC[XW];
                     if constexpr (CK == 0) unpacks(rC[SS][s], s, cur, uC);
+                    if constexpr (!(CF && CK > 0)) {
 #pragma unroll
-                    for (int j = 0; j < K; ++j) {
-                        const float hh = (j == K - 1) ? Hh[t] : ((kDppApply && LG != 32) ? hl[t][j] : fmaf(pl[t][j], cin[t], hl[t][j]));
-                        fma_inplace(h[s][j], a[t][j], hh);                                          // Eq. 6
-                        if constexpr (CK == 0) {
-                            const float cv = get_elem<T, K>(uC, j);
-                            yacc[j] = s == 0 ? cv * h[s][j] : fmaf(cv, h[s][j], yacc[j]);
+                        for (int j = 0; j < K; ++j) {
+                            const float hh = (j == K - 1) ? Hh[t] : ((kDppApply && LG != 32) ? hl[t][j] : fmaf(pl[t][j], cin[t], hl[t][j]));
+                            if constexpr (!CF) fma_inplace(h[s][j], a[t][j], hh);                   // Eq. 6
+                            if constexpr (CK == 0) {
+                                const float cv = get_elem<T, K>(uC, j);
+                                const float hv = CF ? hh : h[s][j];
+                                yacc[j] = s == 0 ? cv * hv : fmaf(cv, hv, yacc[j]);
+                            }
                         }
                     }
                     if constexpr (CK == 0) lds(rsC, s, nxt, rC[SS][s]);

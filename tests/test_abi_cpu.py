@@ -88,11 +88,23 @@ def test_workspace_query(lib):
         extra = ((2 * 8 * 20 * 40 * 4 + 255) // 256) * 256 + 256      # and room behind it for reads past the last row
         assert lib.workspace_bytes(d, lib.PASS_BWD_SOFTPLUS) == lib.workspace_bytes(d, lib.PASS_BWD) + extra
     assert lib.workspace_bytes(lib.Desc(1, 2, 8, 3000, 4, 0, 0), lib.PASS_BWD_GATED) > 0       # wide maps: column panels
-    # columns first: the transposed copies (x, delta, y; Bm, Cm; mask) behind the workspace of the swapped shape;
-    # identity cells: one more copy of the step
+    # columns first inside the kernels (a shared-producer tiling takes the shape): the workspace of the plain call;
+    # through transposes otherwise (here: 5 states): the transposed copies (x, delta, y; Bm, Cm; mask) behind the
+    # workspace of the swapped shape; identity cells: one more copy of the step
     r256 = lambda v: (v + 255) // 256 * 256
     d = lib.Desc(2, 8, 20, 40, 16, 0, lib.FLAG_COLUMNS_FIRST)
-    assert lib.workspace_bytes(d, lib.PASS_FWD) == 3 * r256(2 * 8 * 800 * 4) + 2 * r256(2 * 16 * 800 * 4) + r256(2 * 800)
+    assert lib.workspace_bytes(d, lib.PASS_FWD) == 0
+    assert lib.describe_plan(d, lib.PASS_FWD).startswith("columns-first(in-kernel) fwd form=shared")
+    assert lib.describe_plan(d, lib.PASS_BWD).startswith("columns-first(in-kernel) bwd form=banded-shared")
+    assert lib.workspace_bytes(d, lib.PASS_BWD) == lib.workspace_bytes(lib.Desc(2, 8, 20, 40, 16, 0, 0), lib.PASS_BWD)
+    d = lib.Desc(2, 8, 20, 40, 5, 0, lib.FLAG_COLUMNS_FIRST)
+    assert lib.describe_plan(d, lib.PASS_FWD).startswith("columns-first(transposed) fwd")
+    assert lib.workspace_bytes(d, lib.PASS_FWD) == 3 * r256(2 * 8 * 800 * 4) + 2 * r256(2 * 5 * 800 * 4) + r256(2 * 800)
+    # the two timed configurations run columns first inside the kernels, forward and backward
+    for shape in ((1, 256, 256, 256, 16, 1), (8, 256, 128, 192, 16, 0)):
+        d = lib.Desc(*shape, lib.FLAG_COLUMNS_FIRST)
+        assert lib.describe_plan(d, lib.PASS_FWD).startswith("columns-first(in-kernel)")
+    assert lib.describe_plan(lib.Desc(8, 256, 128, 192, 16, 0, lib.FLAG_COLUMNS_FIRST), lib.PASS_BWD).startswith("columns-first(in-kernel)")
     assert lib.workspace_bytes(lib.Desc(2, 8, 20, 40, 16, 1, lib.FLAG_IDENTITY_CELLS), lib.PASS_FWD) == r256(2 * 8 * 800 * 2)
     assert lib.workspace_bytes(lib.Desc(1, 2, 3000, 8, 4, 0, lib.FLAG_COLUMNS_FIRST), lib.PASS_BWD) > 0    # 3000 columns after the swap
 

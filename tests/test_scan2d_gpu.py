@@ -740,6 +740,10 @@ def test_identity_cells_with_softplus_step(s2d):
 CF_SHAPES = [
     (2, 5, 16, 21, 64, wl.F32, 0.3), (2, 5, 16, 14, 9, wl.BF16, 0.3), (1, 3, 16, 70, 33, wl.BF16, 0.4),
     (1, 4, 5, 45, 7, wl.F32, 0.0), (1, 3, 16, 130, 190, wl.F32, 0.3), (3, 2, 4, 1, 50, wl.F32, 0.3), (1, 2, 8, 37, 1, wl.F32, 0.3),
+    # in-kernel form: wave-wide forward tiling on odd bf16 rows with the ragged 12-column backward, 32 and 64 states,
+    # several maps per workgroup, a width that needs column panels (transposed form)
+    (1, 2, 16, 33, 191, wl.BF16, 0.3), (2, 3, 16, 37, 50, wl.F32, 0.5), (1, 2, 32, 20, 40, wl.F32, 0.3), (1, 2, 64, 9, 30, wl.BF16, 0.3),
+    (3, 7, 16, 56, 56, wl.BF16, 0.2), (1, 2, 16, 12, 300, wl.F32, 0.3),
 ]
 
 
