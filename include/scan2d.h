@@ -245,6 +245,36 @@ int scan2d_bwd_variants(const scan2d_desc* desc,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The two producers in front of the scan inside a 2DMamba block (Sec. 3.2, Fig. 2: "the design of the original Mamba
+ * block" with the scan replaced; Sec. 3.3 names the layers in front of the scan as normalization, projection and
+ * convolution; Eq. 3: Delta, B and C are linear functions of x).  Both write the storage type of desc.dtype, so
+ * their outputs are the inputs of scan2d_fwd_softplus / scan2d_fwd_softplus_gated as they stand.  Forward only.
+ * All pointers are device pointers, 16-byte aligned; asynchronous on `stream`; no workspace.
+ *
+ * scan2d_block_conv_silu: depth-wise cross-correlation over the map, zero outside it, then SiLU:
+ *     t[b,c,i,j] = bias[c] + sum_{p<KH, q<KW} w[c,p,q] * u[b,c,i+p-PH,j+q-PW],     x = t / (1 + exp(-t))
+ *   u, x : [Bt][Dc][H][W] storage type (x is written; u == x is not allowed);  w : [Dc][KH][KW] fp32;
+ *   bias : [Dc] fp32 or NULL.  1 <= KH, KW <= 7, 0 <= PH < KH, 0 <= PW < KW (else SCAN2D_ERR_BAD_SHAPE):
+ *   KH = KW = 3, PH = PW = 1 is the zero-padded 3x3 filter, KH = 1, KW = 4, PW = 3 the causal filter of the 1D
+ *   block along the rows.  desc.N and desc.flags are not used.  fp32 arithmetic, one rounding.
+ *
+ * scan2d_block_xproj: at every position, low = Wx . x (R + 2N rows), then
+ *     delta_raw[b,c,i,j] = sum_{r<R} Wdt[c,r] * low[r],    Bm[b,n,i,j] = low[R+n],    Cm[b,n,i,j] = low[R+N+n]
+ *   x : [Bt][Dc][H][W], Wx : [R + 2N][Dc], both storage type;  Wdt : [Dc][R] fp32;
+ *   delta_raw : [Bt][Dc][H][W], Bm, Cm : [Bt][N][H][W] storage type (written).  The bias of the step projection is
+ *   the delta_bias argument of the softplus entry points.  The first product runs on the matrix cores (bf16 or
+ *   fp32 inputs as stored, fp32 accumulation); low is not rounded before the second product.
+ *   1 <= R <= 64, and the tile of x must fit the LDS: Dc <= 1088 for bf16 storage, Dc <= 448 for fp32 storage
+ *   (else SCAN2D_ERR_BAD_SHAPE).  desc.flags is not used.
+ */
+typedef struct { int32_t KH, KW, PH, PW; } scan2d_conv_shape;
+int scan2d_block_conv_silu(const scan2d_desc* desc, const scan2d_conv_shape* shape,
+                           const void* u, const float* w, const float* bias, void* x, void* stream);
+int scan2d_block_xproj(const scan2d_desc* desc, int R,
+                       const void* x, const void* Wx, const float* Wdt,
+                       void* delta_raw, void* Bm, void* Cm, void* stream);
+
+/*
  * scan2d_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving or
  * training loops, harnesses that forbid hipMalloc): the same computation and the same kernels as scan2d_bwd,
  * every argument as there, but no workspace argument.  The band checkpoints and partial sums go to a scratch

@@ -16,6 +16,7 @@
 #include "scan2d_variants.hpp"
 #include "scan2d_bwd.hpp"
 #include "scan2d_elementwise.hpp"
+#include "scan2d_block.hpp"
 #include "scan2d_tuning.hpp"
 
 namespace scan2d {
@@ -875,6 +876,30 @@ extern "C" int scan2d_bwd_static_scratch(const scan2d_desc* desc, const void* x,
     if (ws == nullptr) return SCAN2D_ERR_LAUNCH_FAILED;
     return bwd_impl(desc, x, delta, nullptr, false, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, nullptr, dA, dBm, dCm, dDskip,
                     ws, need, stream);
+}
+
+extern "C" int scan2d_block_conv_silu(const scan2d_desc* desc, const scan2d_conv_shape* shape, const void* u, const float* w,
+                                      const float* bias, void* x, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!shape || !u || !w || !x) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(u) || !aligned16(w) || !aligned16(bias) || !aligned16(x)) return SCAN2D_ERR_MISALIGNED;
+    if (u == x) return SCAN2D_ERR_BAD_SHAPE;                       // every output reads its neighbours' inputs
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    return block_conv_silu_launch(desc, shape, u, w, bias, x, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int scan2d_block_xproj(const scan2d_desc* desc, int R, const void* x, const void* Wx, const float* Wdt,
+                                  void* delta_raw, void* Bm, void* Cm, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!x || !Wx || !Wdt || !delta_raw || !Bm || !Cm) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(Wx) || !aligned16(Wdt) || !aligned16(delta_raw) || !aligned16(Bm) || !aligned16(Cm))
+        return SCAN2D_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    return block_xproj_launch(desc, R, x, Wx, Wdt, delta_raw, Bm, Cm, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int scan2d_debug_force_variant(int kind, const int* values, int n) {

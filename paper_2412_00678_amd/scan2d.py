@@ -20,7 +20,8 @@ PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS, PASS_FWD_VARIANTS, PASS_B
 
 EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
-           "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants")
+           "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants",
+           "scan2d_block_conv_silu", "scan2d_block_xproj")
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ERR_SCRATCH_LIMIT = -9
 TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
@@ -34,6 +35,10 @@ class Desc(ctypes.Structure):
 
 class Variants(ctypes.Structure):
     _fields_ = [("A_v", ctypes.c_void_p), ("pad", ctypes.c_void_p), ("dA_v", ctypes.c_void_p), ("dpad", ctypes.c_void_p)]
+
+
+class ConvShape(ctypes.Structure):
+    _fields_ = [("KH", ctypes.c_int32), ("KW", ctypes.c_int32), ("PH", ctypes.c_int32), ("PW", ctypes.c_int32)]
 
 
 class Scan2dError(RuntimeError):
@@ -67,6 +72,10 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_fwd_softplus_gated.restype = ctypes.c_int
     lib.scan2d_bwd_softplus_gated.argtypes = [ctypes.POINTER(Desc)] + [vp] * 19 + [vp, ctypes.c_size_t, vp]
     lib.scan2d_bwd_softplus_gated.restype = ctypes.c_int
+    lib.scan2d_block_conv_silu.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(ConvShape)] + [vp] * 5
+    lib.scan2d_block_conv_silu.restype = ctypes.c_int
+    lib.scan2d_block_xproj.argtypes = [ctypes.POINTER(Desc), ctypes.c_int] + [vp] * 7
+    lib.scan2d_block_xproj.restype = ctypes.c_int
     lib.scan2d_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.c_int]
     lib.scan2d_workspace_bytes.restype = ctypes.c_size_t
     lib.scan2d_strerror.argtypes = [ctypes.c_int]
@@ -421,6 +430,47 @@ def scan2d_bwd_softplus_gated(x, delta_raw, delta_bias, A, Bm, Cm, Dskip, mask, 
     if rc != 0:
         raise Scan2dError(rc, "scan2d_bwd_softplus_gated")
     return dx, draw, dbias, dA, dBm, dCm, dDskip, dz
+
+
+def block_conv_silu(u, w, bias=None, PH=None, PW=None, x=None):
+    """x = SiLU(depth-wise correlation of u [Bt][Dc][H][W] with w [Dc][KH][KW] + bias [Dc]); PH, PW: offset of the
+    filter's first tap (default: centred)."""
+    Bt, Dc, H, W = u.shape
+    KH, KW = int(w.shape[1]), int(w.shape[2])
+    desc = Desc(Bt, Dc, H, W, 1, _dtype_code(u), 0)
+    _check(u, "u", u.dtype, (Bt, Dc, H, W))
+    _check(w, "w", torch.float32, (Dc, KH, KW))
+    _check(bias, "bias", torch.float32, (Dc,), optional=True)
+    if x is None:
+        x = torch.empty_like(u)
+    else:
+        _check(x, "x", u.dtype, (Bt, Dc, H, W))
+    shape = ConvShape(KH, KW, KH // 2 if PH is None else PH, KW // 2 if PW is None else PW)
+    rc = lib.scan2d_block_conv_silu(ctypes.byref(desc), ctypes.byref(shape), _ptr(u), _ptr(w), _ptr(bias), _ptr(x), _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_block_conv_silu")
+    return x
+
+
+def block_xproj(x, Wx, Wdt, N, out=None):
+    """(delta_raw, Bm, Cm) from x [Bt][Dc][H][W], Wx [(R + 2N)][Dc] (type of x) and Wdt [Dc][R] fp32."""
+    Bt, Dc, H, W = x.shape
+    R = int(Wdt.shape[1])
+    desc = Desc(Bt, Dc, H, W, N, _dtype_code(x), 0)
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(Wx, "Wx", x.dtype, (R + 2 * N, Dc))
+    _check(Wdt, "Wdt", torch.float32, (Dc, R))
+    if out is None:
+        out = (torch.empty_like(x), torch.empty((Bt, N, H, W), dtype=x.dtype, device=x.device),
+               torch.empty((Bt, N, H, W), dtype=x.dtype, device=x.device))
+    else:
+        _check(out[0], "delta_raw", x.dtype, (Bt, Dc, H, W))
+        _check(out[1], "Bm", x.dtype, (Bt, N, H, W))
+        _check(out[2], "Cm", x.dtype, (Bt, N, H, W))
+    rc = lib.scan2d_block_xproj(ctypes.byref(desc), R, _ptr(x), _ptr(Wx), _ptr(Wdt), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_block_xproj")
+    return out
 
 
 def to_device(arrs: dict, dtype_code: int, device="cuda:0") -> dict:

@@ -161,3 +161,30 @@ def make_inputs(wl: Workload, seed: int = 0, poison_under_mask: Optional[float] 
     if wl.backward:
         out["dy"] = cast(rng.standard_normal((Bt, Dc, H, W)))
     return out
+
+
+def make_block_inputs(wl: Workload, R: int, KH: int = 3, KW: int = 3, seed: int = 0) -> Dict[str, Optional[np.ndarray]]:
+    """Tensors of the producers in front of the scan for a workload's shape (the paper trains these weights; here they
+    are drawn): the block's pre-convolution activations u ~ N(0,1), a depth-wise filter w ~ N(0,1)/sqrt(KH*KW) with bias
+    ~ N(0, 0.1), the projection Wx ~ N(0,1)/sqrt(Dc) [(R + 2N)][Dc] in the storage type, the step expansion
+    Wdt ~ N(0,1)/sqrt(R) [Dc][R] with the step bias delta_bias ~ N(delta_mu, 0.5) (so that the softplus step has the
+    workloads' distribution), the gate branch z ~ N(0,1), and A, Dskip, mask as make_inputs draws them.
+    Draw order: u, w, bias, Wx, Wdt, delta_bias, z, A, Dskip, mask noise."""
+    rng = np.random.default_rng(seed)
+    Bt, Dc, N, H, W = wl.Bt, wl.Dc, wl.N, wl.H, wl.W
+
+    def cast(a64: np.ndarray) -> np.ndarray:
+        a32 = a64.astype(np.float32)
+        return f32_to_bf16_bits(a32) if wl.dtype == BF16 else a32
+
+    u = cast(rng.standard_normal((Bt, Dc, H, W)))
+    w = (rng.standard_normal((Dc, KH, KW)) / np.sqrt(KH * KW)).astype(np.float32)
+    bias = rng.normal(0.0, 0.1, (Dc,)).astype(np.float32)
+    Wx = cast(rng.standard_normal((R + 2 * N, Dc)) / np.sqrt(Dc))
+    Wdt = (rng.standard_normal((Dc, R)) / np.sqrt(R)).astype(np.float32)
+    delta_bias = rng.normal(wl.delta_mu, 0.5, (Dc,)).astype(np.float32)
+    z = cast(rng.standard_normal((Bt, Dc, H, W)))
+    A = (-np.exp(rng.normal(0.0, 0.5, (Dc, N)))).astype(np.float32)
+    Dskip = rng.standard_normal((Dc,)).astype(np.float32)
+    mask = blob_mask(rng.standard_normal((Bt, H, W)), wl.mask_frac) if wl.mask_frac > 0 else None
+    return {"u": u, "w": w, "bias": bias, "Wx": Wx, "Wdt": Wdt, "delta_bias": delta_bias, "z": z, "A": A, "Dskip": Dskip, "mask": mask}

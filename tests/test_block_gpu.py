@@ -1,0 +1,123 @@
+"""GPU parity of the producers in front of the scan (scan2d_block_conv_silu, scan2d_block_xproj) against
+oracle/block.py, through the C ABI, and of the chain conv -> projections -> gated scan against the oracle's chain."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import block
+from paper_2412_00678_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+# max|gpu - ref| / max|ref| per tensor: fp32 arithmetic on both products and one rounding to the storage type
+TOL_BLOCK = {wl.F32: 1e-5, wl.BF16: 2.0 ** -7}
+TOL_SCAN = {wl.F32: 1e-4, wl.BF16: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def s2d():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2412_00678_amd import scan2d
+    return scan2d
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+
+
+CONV_CASES = [
+    # Bt, Dc, H, W, dtype, KH, KW, PH, PW
+    (2, 5, 13, 17, wl.F32, 3, 3, 1, 1), (1, 3, 14, 14, wl.BF16, 3, 3, 1, 1), (2, 4, 9, 30, wl.BF16, 1, 4, 0, 3),
+    (1, 2, 7, 5, wl.F32, 7, 7, 3, 3), (1, 2, 5, 9, wl.F32, 2, 5, 1, 0), (1, 3, 1, 1, wl.BF16, 3, 3, 1, 1),
+    (1, 2, 6, 64, wl.BF16, 5, 3, 4, 2), (3, 2, 33, 3, wl.F32, 3, 1, 0, 0), (1, 64, 56, 56, wl.BF16, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(map(str, c[:4])) + ("bf16" if c[4] else "f32") + f"-k{c[5]}x{c[6]}")
+def test_conv_silu_matches_oracle(s2d, case):
+    import torch
+    Bt, Dc, H, W, dtype, KH, KW, PH, PW = case
+    w_ = wl.Workload("conv", Bt, Dc, 1, H, W, dtype)
+    inp = wl.make_block_inputs(w_, R=1, KH=KH, KW=KW, seed=41)
+    print(f"conv case {case}", flush=True)
+    d = s2d.to_device({k: inp[k] for k in ("u", "w", "bias")}, dtype)
+    for bias in (d["bias"], None):
+        x = s2d.block_conv_silu(d["u"], d["w"], bias, PH, PW)
+        torch.cuda.synchronize()
+        ref = block.conv_silu(inp["u"], inp["w"], None if bias is None else inp["bias"], PH, PW, dtype=dtype)
+        got = wl.to_float(s2d.to_host(x), dtype)
+        assert np.isfinite(got).all()
+        assert rel_err(got, wl.to_float(ref, dtype)) <= TOL_BLOCK[dtype]
+        if dtype == wl.BF16:                              # one rounding: almost every output has the oracle's bits
+            assert np.mean(s2d.to_host(x) == ref) > 0.99
+
+
+XPROJ_CASES = [
+    # Bt, Dc, N, H, W, dtype, R
+    (1, 256, 16, 37, 41, wl.BF16, 8), (2, 64, 16, 8, 24, wl.BF16, 4), (1, 100, 5, 9, 20, wl.F32, 7), (1, 37, 3, 5, 7, wl.BF16, 2),
+    (1, 96, 64, 6, 22, wl.F32, 64), (1, 1024, 16, 4, 16, wl.BF16, 64), (2, 30, 4, 1, 1, wl.F32, 1), (1, 256, 16, 64, 64, wl.F32, 8),
+    (1, 130, 8, 3, 70, wl.BF16, 5),
+]
+
+
+@pytest.mark.parametrize("case", XPROJ_CASES, ids=lambda c: "x".join(map(str, c[:5])) + ("bf16" if c[5] else "f32") + f"-R{c[6]}")
+def test_xproj_matches_oracle(s2d, case):
+    import torch
+    Bt, Dc, N, H, W, dtype, R = case
+    w_ = wl.Workload("xproj", Bt, Dc, N, H, W, dtype)
+    inp = wl.make_block_inputs(w_, R=R, seed=42)
+    print(f"xproj case {case}", flush=True)
+    d = s2d.to_device({"x": inp["u"], "Wx": inp["Wx"], "Wdt": inp["Wdt"]}, dtype)
+    delta_raw, Bm, Cm = s2d.block_xproj(d["x"], d["Wx"], d["Wdt"], N)
+    torch.cuda.synchronize()
+    refs = block.xproj(inp["u"], inp["Wx"], inp["Wdt"], N, dtype=dtype)
+    for name, g, r in zip(("delta_raw", "Bm", "Cm"), (delta_raw, Bm, Cm), refs):
+        got = wl.to_float(s2d.to_host(g), dtype)
+        assert np.isfinite(got).all(), name
+        e = rel_err(got, wl.to_float(r, dtype))
+        assert e <= TOL_BLOCK[dtype], f"{name}: rel err {e:.3e}"
+
+
+def test_block_entry_points_reject_bad_arguments(s2d):
+    import torch
+    u = torch.zeros((1, 4, 8, 8), device="cuda")
+    w = torch.zeros((4, 3, 3), device="cuda")
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.block_conv_silu(u, w, None, 3, 1)            # the first tap's offset must lie inside the filter
+    assert e.value.code == -2
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.block_conv_silu(u, w, None, 1, 1, x=u)       # in place
+    assert e.value.code == -2
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.block_conv_silu(u, torch.zeros((4, 9, 3), device="cuda"), None, 1, 1)
+    assert e.value.code == -2
+    x = torch.zeros((1, 2048, 4, 4), device="cuda", dtype=torch.bfloat16)    # the tile of x would not fit the LDS
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.block_xproj(x, torch.zeros((8 + 32, 2048), device="cuda", dtype=torch.bfloat16), torch.zeros((2048, 8), device="cuda"), 16)
+    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("shape", [(2, 24, 16, 21, 40, wl.F32, 4), (1, 64, 16, 56, 56, wl.BF16, 4), (1, 32, 16, 30, 255, wl.BF16, 2)],
+                         ids=["21x40-f32", "56x56-bf16", "30x255-bf16"])
+def test_conv_projections_and_gated_scan_chain_matches_the_oracle_chain(s2d, shape):
+    """u -> conv + SiLU -> x -> (delta_raw, Bm, Cm) -> softplus step, 2D scan, gate -> y, every tensor between the stages
+    in the storage type on both sides."""
+    import torch
+    Bt, Dc, N, H, W, dtype, R = shape
+    w_ = wl.Workload("chain", Bt, Dc, N, H, W, dtype, mask_frac=0.3)
+    inp = wl.make_block_inputs(w_, R=R, seed=43)
+    d = s2d.to_device(inp, dtype)
+    x = s2d.block_conv_silu(d["u"], d["w"], d["bias"])
+    delta_raw, Bm, Cm = s2d.block_xproj(x, d["Wx"], d["Wdt"], N)
+    _, y = s2d.scan2d_fwd_softplus_gated(x, delta_raw, d["delta_bias"], d["A"], Bm, Cm, d["Dskip"], d["mask"], d["z"], want_y_scan=False)
+    torch.cuda.synchronize()
+    xr = block.conv_silu(inp["u"], inp["w"], inp["bias"], 1, 1, dtype=dtype)
+    dr, Br, Cr = block.xproj(xr, inp["Wx"], inp["Wdt"], N, dtype=dtype)
+    _, yr = oracle.scan2d_fwd_softplus_gated(xr, dr, inp["delta_bias"], inp["A"], Br, Cr, inp["Dskip"], inp["mask"], inp["z"], dtype=dtype)
+    got = wl.to_float(s2d.to_host(y), dtype)
+    assert np.isfinite(got).all()
+    assert rel_err(wl.to_float(s2d.to_host(x), dtype), wl.to_float(xr, dtype)) <= TOL_BLOCK[dtype]
+    assert rel_err(wl.to_float(s2d.to_host(delta_raw), dtype), wl.to_float(dr, dtype)) <= 2 * TOL_BLOCK[dtype]
+    assert rel_err(got, wl.to_float(yr, dtype)) <= TOL_SCAN[dtype]
