@@ -264,8 +264,7 @@ int scan2d_bwd_variants(const scan2d_desc* desc,
  *   delta_raw : [Bt][Dc][H][W], Bm, Cm : [Bt][N][H][W] storage type (written).  The bias of the step projection is
  *   the delta_bias argument of the softplus entry points.  The first product runs on the matrix cores (bf16 or
  *   fp32 inputs as stored, fp32 accumulation); low is not rounded before the second product.
- *   1 <= R <= 64, and the tile of x must fit the LDS: Dc <= 1088 for bf16 storage, Dc <= 448 for fp32 storage
- *   (else SCAN2D_ERR_BAD_SHAPE).  desc.flags is not used.
+ *   1 <= R <= 64 (else SCAN2D_ERR_BAD_SHAPE); any Dc.  desc.flags is not used.
  */
 typedef struct { int32_t KH, KW, PH, PW; } scan2d_conv_shape;
 int scan2d_block_conv_silu(const scan2d_desc* desc, const scan2d_conv_shape* shape,

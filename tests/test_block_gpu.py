@@ -58,7 +58,11 @@ XPROJ_CASES = [
     # Bt, Dc, N, H, W, dtype, R
     (1, 256, 16, 37, 41, wl.BF16, 8), (2, 64, 16, 8, 24, wl.BF16, 4), (1, 100, 5, 9, 20, wl.F32, 7), (1, 37, 3, 5, 7, wl.BF16, 2),
     (1, 96, 64, 6, 22, wl.F32, 64), (1, 1024, 16, 4, 16, wl.BF16, 64), (2, 30, 4, 1, 1, wl.F32, 1), (1, 256, 16, 64, 64, wl.F32, 8),
-    (1, 130, 8, 3, 70, wl.BF16, 5),
+    (1, 130, 8, 3, 70, wl.BF16, 5), (1, 600, 16, 5, 30, wl.BF16, 10), (2, 300, 16, 7, 19, wl.F32, 9), (1, 512, 64, 2, 40, wl.F32, 33),
+    # the kernel for the common case (H*W a multiple of 64, Dc a multiple of 16 within one chunk, at most 48 rows of Wx):
+    # both storage types, every size class of the low-rank step, several tiles per workgroup
+    (2, 128, 16, 8, 16, wl.F32, 8), (1, 256, 16, 16, 16, wl.BF16, 12), (1, 64, 8, 8, 8, wl.BF16, 20), (1, 16, 4, 8, 8, wl.F32, 3),
+    (3, 192, 16, 56, 56, wl.BF16, 6), (1, 48, 16, 32, 1200, wl.BF16, 16), (1, 112, 12, 16, 20, wl.F32, 24),
 ]
 
 
@@ -93,9 +97,9 @@ def test_block_entry_points_reject_bad_arguments(s2d):
     with pytest.raises(s2d.Scan2dError) as e:
         s2d.block_conv_silu(u, torch.zeros((4, 9, 3), device="cuda"), None, 1, 1)
     assert e.value.code == -2
-    x = torch.zeros((1, 2048, 4, 4), device="cuda", dtype=torch.bfloat16)    # the tile of x would not fit the LDS
-    with pytest.raises(s2d.Scan2dError) as e:
-        s2d.block_xproj(x, torch.zeros((8 + 32, 2048), device="cuda", dtype=torch.bfloat16), torch.zeros((2048, 8), device="cuda"), 16)
+    x = torch.zeros((1, 64, 4, 4), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(s2d.Scan2dError) as e:            # more than 64 low-rank rows
+        s2d.block_xproj(x, torch.zeros((65 + 32, 64), device="cuda", dtype=torch.bfloat16), torch.zeros((64, 65), device="cuda"), 16)
     assert e.value.code == -2
 
 
