@@ -212,6 +212,58 @@ def bench_gated(s2d, w, steps, warmup):
     return out
 
 
+def bench_block(s2d, w, steps, warmup):
+    """The two producers in front of the scan (depth-wise 3x3 convolution + SiLU; step, B and C projections on the
+    matrix cores) on the workload's shape, then the chain conv -> projections -> gated scan.  R = ceil(Dc / 32): the
+    low-rank step of a block whose inner width Dc is twice its model width."""
+    import torch
+    R = max(1, (w.Dc // 2 + 15) // 16)
+    inp = wl.make_block_inputs(w, R=R, seed=0)
+    eb = 2 if w.dtype == wl.BF16 else 4
+    maps, states = w.Bt * w.Dc * w.H * w.W, w.Bt * w.N * w.H * w.W
+    set_bytes = (5 * maps + 2 * states) * eb
+    nsets = int(min(8, max(2, np.ceil(1.2e9 / set_bytes))))
+    sets = []
+    for _ in range(nsets):
+        d = s2d.to_device(inp, w.dtype)
+        d["x"] = torch.empty_like(d["u"])
+        d["y"] = torch.empty_like(d["u"])
+        d["proj"] = (torch.empty_like(d["u"]), torch.empty((w.Bt, w.N, w.H, w.W), dtype=d["u"].dtype, device="cuda:0"),
+                     torch.empty((w.Bt, w.N, w.H, w.W), dtype=d["u"].dtype, device="cuda:0"))
+        sets.append(d)
+    desc = s2d.make_desc(sets[0]["x"], sets[0]["A"])
+    ws = torch.empty(max(s2d.workspace_bytes(desc, s2d.PASS_FWD), 16), dtype=torch.uint8, device="cuda:0")
+
+    def conv(s):
+        s2d.block_conv_silu(s["u"], s["w"], s["bias"], x=s["x"])
+
+    def proj(s):
+        s2d.block_xproj(s["x"], s["Wx"], s["Wdt"], w.N, out=s["proj"])
+
+    def scan(s):
+        s2d.scan2d_fwd_softplus_gated(s["x"], s["proj"][0], s["delta_bias"], s["A"], s["proj"][1], s["proj"][2], s["Dskip"], s["mask"],
+                                      s["z"], want_y_scan=False, workspace=ws, y=s["y"])
+
+    def chain(s):
+        conv(s); proj(s); scan(s)
+
+    out = {"R": R, "buffer_sets": nsets}
+    conv_bytes = 2 * maps * eb
+    proj_bytes = (2 * maps + 2 * states) * eb + (R + 2 * w.N) * w.Dc * eb + w.Dc * R * 4
+    proj_flops = 2.0 * (R + 2 * w.N) * w.Dc * w.Bt * w.H * w.W + 2.0 * w.Dc * R * w.Bt * w.H * w.W
+    for name, fn, nbytes in (("conv_silu", conv, conv_bytes), ("xproj", proj, proj_bytes), ("gated_scan", scan, None), ("chain", chain, None)):
+        t, _ = time_launches(fn, sets, steps, warmup)
+        out[name + "_ms"] = float(t)
+        if nbytes is not None:
+            gbs = nbytes / (float(t) * 1e-3) / 1e9
+            out[name + "_roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                                       "algorithmic_bytes": nbytes}
+    out["xproj_tflops"] = proj_flops / (out["xproj_ms"] * 1e-3) / 1e12
+    del sets
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(w, inp, budget_s=8.0):
     """The oracle as it stands on the host cores of this machine: forward of the same workload, first on all cores,
     then on one thread, each repeated for about `budget_s` seconds (at least one pass)."""
@@ -268,6 +320,9 @@ def main():
     ap.add_argument("--softplus", action="store_true",
                     help="also time the entry points that compute the step themselves, delta = softplus(raw + bias) "
                          "(same tensors, delta read as the raw projection), reported under 'softplus'")
+    ap.add_argument("--block", action="store_true",
+                    help="also time the producers in front of the scan (depth-wise convolution + SiLU, step/B/C projections) and "
+                         "the chain into the gated scan, reported under 'block'")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also time the grids the paper times (14x14, 56x56, 200x200; N = 16): 128-channel maps and "
                          "batches of single-channel maps, reported under 'paper_shapes' as feature maps per second")
@@ -331,6 +386,8 @@ def main():
         line["gated"] = bench_gated(s2d, w, max(20, args.steps // 3), max(5, args.warmup // 3))
     if args.softplus:
         line["softplus"] = bench_softplus(s2d, w, max(20, args.steps // 3), max(5, args.warmup // 3))
+    if args.block:
+        line["block"] = bench_block(s2d, w, max(20, args.steps // 3), max(5, args.warmup // 3))
     if args.paper_shapes:
         rows = []
         for side in (14, 56, 200):

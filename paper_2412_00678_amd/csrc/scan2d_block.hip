@@ -74,7 +74,9 @@ __global__ __launch_bounds__(256) void scan2d_block_conv_silu_kernel(const T* __
 // Wide maps (W >= 32): one workgroup per tile of 32 rows x 64 columns.  The tile and its halo go to LDS as fp32 through
 // aligned vector loads (zero outside the map), the channel's filter goes there too, then every thread forms 4 consecutive
 // outputs in each of two rows from LDS.  KHC x KWC: the filter size at compile time (0: any size up to 7 x 7).
-constexpr int kConvTH = 32, kConvTW = 64, kConvHalo = 8, kConvPitch = kConvTW + 2 * kConvHalo;   // 80 floats per LDS row
+constexpr int kConvTH = 32, kConvTW = 64, kConvHalo = 8, kConvCols = kConvTW + 2 * kConvHalo;   // 80 columns per tile row
+// LDS row pitch: odd, so that the four rows a wavefront reads (lanes: 16 groups of 4 columns x 4 rows) fall on different banks
+constexpr int kConvPitch = kConvCols + 1;
 template <typename T, int KHC, int KWC>
 __global__ __launch_bounds__(256) void scan2d_block_conv_silu_tile_kernel(const T* __restrict__ u, const float* __restrict__ w,
                                                                           const float* __restrict__ bias, T* __restrict__ x,
@@ -95,8 +97,8 @@ __global__ __launch_bounds__(256) void scan2d_block_conv_silu_tile_kernel(const 
     const bool vec_ok = (W % 4) == 0;                     // rows and maps then start on vector boundaries
     if (tid < KH * KW) wts[tid] = w[(size_t)c * KH * KW + tid];
     if (tid == 63) wts[49] = bias != nullptr ? bias[c] : 0.0f;
-    for (int idx = tid; idx < rows * (kConvPitch / 4); idx += 256) {
-        const int r = idx / (kConvPitch / 4), q = idx % (kConvPitch / 4);
+    for (int idx = tid; idx < rows * (kConvCols / 4); idx += 256) {
+        const int r = idx / (kConvCols / 4), q = idx % (kConvCols / 4);
         const int ii = i0 + r - PH, jj = j0 - kConvHalo + 4 * q;
         float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (ii >= 0 && ii < H && jj + 3 >= 0 && jj < W) {
@@ -116,7 +118,8 @@ __global__ __launch_bounds__(256) void scan2d_block_conv_silu_tile_kernel(const 
                 if (jj + 3 >= 0 && jj + 3 < W) v.w = widen_bits<T>(elem_bits(src + 3));
             }
         }
-        *reinterpret_cast<float4*>(tile + r * kConvPitch + 4 * q) = v;
+        float* dst = tile + r * kConvPitch + 4 * q;
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     }
     __syncthreads();
     const int jq = tid % 16, j = j0 + 4 * jq;

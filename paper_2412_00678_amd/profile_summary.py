@@ -45,6 +45,11 @@ def runs():
     # the same two commands without the profiler: kernel tracing adds several microseconds to every launch
     out.append(("plain_all", None, "python3 bench.py --no-cpu --all --paper-shapes --steps 150 --warmup 20", "plain_all.json"))
     out.append(("plain_block", None, "python3 bench.py --no-cpu --workload 4 --softplus --gated --steps 40 --warmup 8", "plain_block.json"))
+    # the producers in front of the scan (convolution + SiLU, projections) and the chain into the gated scan
+    for w in (2, 3):
+        b = f"python3 bench.py --no-cpu --block --workload {w} --steps 60 --warmup 10"
+        out.append((f"trace_producers_{w}", "--kernel-trace --stats", b, f"trace_producers_{w}.json"))
+        out.append((f"plain_producers_{w}", None, b, f"plain_producers_{w}.json"))
     out.append(("fetch_copy", "--pmc FETCH_SIZE", "./paper_2412_00678_amd/roofprobe --copy 5", None))
     out.append(("write_copy", "--pmc WRITE_SIZE", "./paper_2412_00678_amd/roofprobe --copy 5", None))
     return out
@@ -330,6 +335,33 @@ bench.py's own event timings, from the same command without the profiler (us per
 """)
 
 
+def write_producers(runs_dir, by_name):
+    names = {2: "scan2d_block_producers_wsi256_bf16.md", 3: "scan2d_block_producers_vmamba56_bf16.md"}
+    for w, fname in names.items():
+        with open(os.path.join(runs_dir, f"plain_producers_{w}.json")) as f:
+            bench = json.loads(f.read().strip().splitlines()[-1])
+        blk = bench["block"]
+        rows = ["| step | time by bench.py events (us) | algorithmic MB | GB/s | % of 8 TB/s |", "|---|---|---|---|---|"]
+        for key, label in (("conv_silu", "scan2d_block_conv_silu (3x3 depth-wise + SiLU)"), ("xproj", "scan2d_block_xproj (step, B, C projections)")):
+            r = blk[key + "_roofline"]
+            rows.append(f"| {label} | {blk[key + '_ms'] * 1e3:.1f} | {r['algorithmic_bytes'] / 1e6:.1f} | {r['achieved']:.0f} | {100 * r['frac']:.1f} |")
+        rows.append(f"| scan2d_fwd_softplus_gated on their outputs | {blk['gated_scan_ms'] * 1e3:.1f} | | | |")
+        rows.append(f"| the three calls back to back | {blk['chain_ms'] * 1e3:.1f} | | | |")
+        with open(os.path.join(PROFILES, fname), "w") as f:
+            f.write(f"""# The producers in front of the scan on {bench['detail']['workload']}: convolution + SiLU, projections (MFMA), gated scan
+
+`{shown(by_name[f'trace_producers_{w}'])}`
+
+{kernel_table(runs_dir, f'trace_producers_{w}')}
+
+The kernel averages above cover both of the run's passes (buffer sets cycling, then one set resident in the Infinity
+Cache).  bench.py's own event timings from the same command without the profiler (`{shown(by_name[f'plain_producers_{w}'])}`,
+buffer sets cycling; low-rank step R = {blk['R']}; the projection runs at {blk['xproj_tflops']:.0f} TFLOP/s, far below
+the matrix cores' rate: it is bound by the bytes of x and delta_raw):
+
+""" + "\n".join(rows) + "\n")
+
+
 def main(argv):
     if len(argv) != 3 or argv[1] not in ("commands", "write"):
         print(__doc__, file=sys.stderr)
@@ -341,6 +373,7 @@ def main(argv):
         print(f"{os.path.join(ROOT, 'paper_2412_00678_amd', 'roofprobe')} > {runs_dir}/roofprobe.txt")
         return 0
     write(runs_dir)
+    write_producers(runs_dir, {r[0]: r for r in runs()})
     return 0
 
 
