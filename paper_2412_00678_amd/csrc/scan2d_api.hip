@@ -422,10 +422,24 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
              const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
              void* y, void* workspace, size_t workspace_bytes, void* stream);
 
+// Everything the scan launch of fwd_impl could refuse for this descriptor, without enqueuing anything.
+int fwd_check(const scan2d_desc* d, bool sp, bool has_mask, bool cf) {
+    FwdChoice ch;
+    const int rc = choose_fwd(d, &ch, sp, !has_mask || (d->W % 4) == 0, cf);
+    if (rc != SCAN2D_OK) return rc;
+    const long long maps = (long long)d->Bt * d->Dc;
+    if ((maps + ch.MPW - 1) / ch.MPW > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    const long long chunks = ((long long)d->H * d->W + 1023) / 1024;
+    if (skip_bytes(d) > 0 && has_mask && chunks * maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    return SCAN2D_OK;
+}
+
 int fwd_columns_first(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, int softplus,
                       const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
                       void* y, void* workspace, size_t workspace_bytes, void* stream) {
     const scan2d_desc t = swapped(desc);
+    int rc = fwd_check(&t, softplus != 0, mask != nullptr, false);             // nothing is enqueued for a call that will fail
+    if (rc != SCAN2D_OK) return rc;
     const size_t inner = align256(fwd_need(&t));
     const Regions r = regions(desc, false);
     if (workspace == nullptr || workspace_bytes < inner + r.total) return SCAN2D_ERR_WORKSPACE_SMALL;
@@ -433,7 +447,7 @@ int fwd_columns_first(const scan2d_desc* desc, const void* x, const void* delta,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int e = desc->dtype == SCAN2D_BF16 ? 2 : 4;
     const long long maps = (long long)desc->Bt * desc->Dc, planes = (long long)desc->Bt * desc->N;
-    int rc = transpose_launch(e, x, base + r.x, maps, desc->H, desc->W, st);
+    rc = transpose_launch(e, x, base + r.x, maps, desc->H, desc->W, st);
     if (rc == SCAN2D_OK) rc = transpose_launch(e, delta, base + r.delta, maps, desc->H, desc->W, st);
     if (rc == SCAN2D_OK) rc = transpose_launch(e, Bm, base + r.Bm, planes, desc->H, desc->W, st);
     if (rc == SCAN2D_OK) rc = transpose_launch(e, Cm, base + r.Cm, planes, desc->H, desc->W, st);
@@ -459,6 +473,8 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
     const bool cf = fwd_fused_cf(desc);
     if (columns_first(desc) && !cf)
         return fwd_columns_first(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, y, workspace, workspace_bytes, stream);
+    rc = fwd_check(desc, softplus != 0, mask != nullptr, cf);                  // nothing is enqueued for a call that will fail
+    if (rc != SCAN2D_OK) return rc;
     FwdChoice ch;
     rc = choose_fwd(desc, &ch, softplus != 0, mask == nullptr || (desc->W % 4) == 0, cf);
     if (rc != SCAN2D_OK) return rc;
@@ -506,7 +522,8 @@ int bwd_core(const scan2d_desc* desc, const void* x, const void* delta, const fl
              const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
              const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
              float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = SCAN2D_OK;
+    int rc = bwd_check(desc, softplus);                                        // nothing is enqueued for a call that will fail
+    if (rc != SCAN2D_OK) return rc;
     const size_t sk = skip_bytes(desc);
     if (sk > 0) {                // identity cells: the sweeps run on a copy of the step that is 0 under the mask
         const size_t inner = bwd_workspace_bytes(desc, softplus);
@@ -534,6 +551,8 @@ int bwd_columns_first(const scan2d_desc* desc, const void* x, const void* delta,
                       const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
                       float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
     const scan2d_desc t = swapped(desc);
+    int rc = bwd_check(&t, softplus);                                          // nothing is enqueued for a call that will fail
+    if (rc != SCAN2D_OK) return rc;
     const size_t need = bwd_need(&t, softplus);
     if (need == 0) return SCAN2D_ERR_BAD_SHAPE;
     const size_t inner = align256(need);
@@ -543,7 +562,7 @@ int bwd_columns_first(const scan2d_desc* desc, const void* x, const void* delta,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int e = desc->dtype == SCAN2D_BF16 ? 2 : 4;
     const long long maps = (long long)desc->Bt * desc->Dc, planes = (long long)desc->Bt * desc->N;
-    int rc = transpose_launch(e, x, base + r.x, maps, desc->H, desc->W, st);
+    rc = transpose_launch(e, x, base + r.x, maps, desc->H, desc->W, st);
     if (rc == SCAN2D_OK) rc = transpose_launch(e, delta, base + r.delta, maps, desc->H, desc->W, st);
     if (rc == SCAN2D_OK) rc = transpose_launch(e, dy, base + r.dy, maps, desc->H, desc->W, st);
     if (rc == SCAN2D_OK) rc = transpose_launch(e, Bm, base + r.Bm, planes, desc->H, desc->W, st);

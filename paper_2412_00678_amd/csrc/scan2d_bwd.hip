@@ -344,6 +344,22 @@ size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus, bool av) {
     return make_plan(d, &pl, softplus, av) ? pl.total : 0;
 }
 
+// Everything bwd_launch could refuse, without enqueuing anything: the plan and the grid sizes of its launches.
+int bwd_check(const scan2d_desc* d, bool softplus, bool av) {
+    BwdPlan pl;
+    if (!make_plan(d, &pl, softplus, av)) return SCAN2D_ERR_BAD_SHAPE;
+    const long long maps = (long long)d->Bt * d->Dc;
+    if (pl.small) return (maps + 3) / 4 > 2147483647LL ? SCAN2D_ERR_BAD_SHAPE : SCAN2D_OK;
+    const int MPW = (pl.waves * 64 / pl.LG) / pl.NG;
+    const int ck_NG = (d->N + pl.k.ckpt_NW - 1) / pl.k.ckpt_NW;
+    const int MPW1 = (pl.ck_waves * 64 / pl.ck_LG) / ck_NG;
+    const long long wg1 = (maps + MPW1 - 1) / MPW1, wg2 = ((long long)d->Bt * pl.CG + MPW - 1) / MPW;
+    if (wg1 > 2147483647LL || wg2 > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    const long long chunks = ((long long)d->H * d->W + 1023) / 1024;
+    if (pl.step_outside && chunks * maps > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    return SCAN2D_OK;
+}
+
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
     BwdPlan pl;
     if (!make_plan(d, &pl)) return false;

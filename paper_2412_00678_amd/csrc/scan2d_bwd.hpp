@@ -11,6 +11,10 @@ namespace scan2d {
 // av: the instantiations with an independent decay parameter A_v for the column recurrence.
 size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus = false, bool av = false);
 
+// SCAN2D_OK when bwd_launch would accept the descriptor (plan and grid sizes), else the error it would return;
+// enqueues nothing.
+int bwd_check(const scan2d_desc* d, bool softplus = false, bool av = false);
+
 // One line describing the backward plan; false when the shape has no plan.
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes);
 
