@@ -125,3 +125,34 @@ def test_conv_projections_and_gated_scan_chain_matches_the_oracle_chain(s2d, sha
     assert rel_err(wl.to_float(s2d.to_host(x), dtype), wl.to_float(xr, dtype)) <= TOL_BLOCK[dtype]
     assert rel_err(wl.to_float(s2d.to_host(delta_raw), dtype), wl.to_float(dr, dtype)) <= 2 * TOL_BLOCK[dtype]
     assert rel_err(got, wl.to_float(yr, dtype)) <= TOL_SCAN[dtype]
+
+
+@pytest.mark.parametrize("k", [2, 3], ids=["wsi-256x256-bf16", "vmamba-56x56-bf16"])
+def test_producers_at_full_size_on_sampled_outputs(s2d, k):
+    """The launch configuration bench.py --block times.  The convolution is checked on whole sampled maps, the
+    projections (independent per position) on sampled positions of every batch item, against the oracle."""
+    import torch
+    w = wl.CONFIGS[k]
+    R = max(1, (w.Dc // 2 + 15) // 16)
+    inp = wl.make_block_inputs(w, R=R, seed=0)
+    d = s2d.to_device({key: inp[key] for key in ("u", "w", "bias", "Wx", "Wdt")}, w.dtype)
+    x = s2d.block_conv_silu(d["u"], d["w"], d["bias"])
+    delta_raw, Bm, Cm = s2d.block_xproj(x, d["Wx"], d["Wdt"], w.N)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    xh = s2d.to_host(x)
+    for _ in range(6):                                   # whole maps of the convolution
+        b, c = int(rng.integers(w.Bt)), int(rng.integers(w.Dc))
+        ref = block.conv_silu(inp["u"][b:b + 1, c:c + 1], inp["w"][c:c + 1], inp["bias"][c:c + 1], 1, 1, dtype=w.dtype)
+        assert rel_err(wl.to_float(xh[b, c], w.dtype), wl.to_float(ref[0, 0], w.dtype)) <= TOL_BLOCK[w.dtype]
+    # sampled positions: a 1 x P' problem made of the sampled columns of x as the GPU produced it
+    P = w.H * w.W
+    pos = np.unique(np.concatenate([rng.integers(0, P, 400), [0, 63, 64, P - 65, P - 64, P - 1]]))
+    dh, Bh, Ch = (s2d.to_host(t).reshape(w.Bt, -1, P) for t in (delta_raw, Bm, Cm))
+    xs = xh.reshape(w.Bt, w.Dc, P)
+    for b in sorted({0, w.Bt - 1, int(rng.integers(w.Bt))}):
+        sub = np.ascontiguousarray(xs[b][:, pos]).reshape(1, w.Dc, 1, len(pos))
+        refs = block.xproj(sub, inp["Wx"], inp["Wdt"], w.N, dtype=w.dtype)
+        for name, got, ref in zip(("delta_raw", "Bm", "Cm"), (dh, Bh, Ch), refs):
+            e = rel_err(wl.to_float(got[b][:, pos], w.dtype), wl.to_float(ref[0, :, 0, :], w.dtype))
+            assert e <= TOL_BLOCK[w.dtype], f"{name} of batch item {b}: rel err {e:.3e}"
