@@ -210,6 +210,62 @@ def scan2d_fwd(x, delta, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=Non
     return y
 
 
+class Prepared:
+    """An entry point with its arguments marshalled once.  Calling the object enqueues the same call again on torch's
+    current stream: same tensors (their contents may change between calls), same workspace.  For loops that issue
+    one short call after another, where checking and converting a dozen arguments costs more than the kernel."""
+
+    def __init__(self, fn, name, args, keep):
+        self._fn, self._name, self._args, self._keep = fn, name, args, keep      # keep: the tensors stay alive
+
+    def __call__(self):
+        rc = self._fn(*self._args, torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise Scan2dError(rc, self._name)
+
+
+def prepare_fwd(x, delta, A, Bm, Cm, Dskip, mask, y, workspace=None, flags=0) -> Prepared:
+    """scan2d_fwd with the argument checks and conversions done now; see Prepared."""
+    desc = make_desc(x, A, flags)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    _check(x, "x", x.dtype, (Bt, Dc, H, W))
+    _check(delta, "delta", x.dtype, (Bt, Dc, H, W))
+    _check(A, "A", torch.float32, (Dc, N))
+    _check(Bm, "Bm", x.dtype, (Bt, N, H, W))
+    _check(Cm, "Cm", x.dtype, (Bt, N, H, W))
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    _check(y, "y", x.dtype, (Bt, Dc, H, W))
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_FWD, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    args = (ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(y), _ptr(workspace), wbytes)
+    return Prepared(lib.scan2d_fwd, "scan2d_fwd", args, (desc, x, delta, A, Bm, Cm, Dskip, mask, y, workspace))
+
+
+def prepare_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, out, workspace=None, flags=0) -> Prepared:
+    """scan2d_bwd with the argument checks and conversions done now; out = (dx, ddelta, dA, dBm, dCm, dDskip)."""
+    desc = make_desc(x, A, flags)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    for t, name, dt, shape in ((x, "x", x.dtype, (Bt, Dc, H, W)), (delta, "delta", x.dtype, (Bt, Dc, H, W)), (A, "A", torch.float32, (Dc, N)),
+                               (Bm, "Bm", x.dtype, (Bt, N, H, W)), (Cm, "Cm", x.dtype, (Bt, N, H, W)), (dy, "dy", x.dtype, (Bt, Dc, H, W)),
+                               (out[0], "dx", x.dtype, (Bt, Dc, H, W)), (out[1], "ddelta", x.dtype, (Bt, Dc, H, W)),
+                               (out[2], "dA", torch.float32, (Dc, N)), (out[3], "dBm", torch.float32, (Bt, N, H, W)),
+                               (out[4], "dCm", torch.float32, (Bt, N, H, W))):
+        _check(t, name, dt, shape)
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(out[5], "dDskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    if workspace is None:
+        workspace, wbytes = _workspace(desc, PASS_BWD, x.device)
+    else:
+        wbytes = workspace.numel() * workspace.element_size()
+    args = (ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(dy),
+            _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _ptr(out[3]), _ptr(out[4]), _ptr(out[5]), _ptr(workspace), wbytes)
+    return Prepared(lib.scan2d_bwd, "scan2d_bwd", args, (desc, x, delta, A, Bm, Cm, Dskip, mask, dy, out, workspace))
+
+
 def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None, flags=0):
     """y of the scan with delta = softplus(delta_raw + delta_bias[c]) computed in the kernels."""
     desc = make_desc(x, A, flags)
