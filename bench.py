@@ -326,7 +326,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed steps before the timed ones (the first tens of milliseconds of a process run below the steady clock)")
     ap.add_argument("--workload", type=int, default=2, help="index into the five configurations (default: the 256x256 WSI grid)")
     ap.add_argument("--all", action="store_true", help="also time the other configurations (reported under 'others')")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")

@@ -235,7 +235,8 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     const double maps = (double)d->Bt * d->Dc;
     const double wgs = std::ceil(maps / c.MPW);
     const double c_core = bf16 ? 10.5 : 8.5;
-    const double c_scan = (c.LG == 64 ? 13.0 : (c.LG == 32 ? 12.0 : 9.0)) + (c.NW == 1 ? 4.0 : 0.0);   // a lone recurrence pads its DPP wait states
+    // a lone recurrence pads its DPP wait states (16- and 32-lane scans; the wave-wide scan has enough steps of its own)
+    const double c_scan = (c.LG == 64 ? 13.0 : (c.LG == 32 ? 12.0 : 9.0)) + (c.NW == 1 && c.LG != 64 ? 4.0 : 0.0);
     const double c_pos = bf16 ? 9.0 : 6.0;
     const double cols_t = std::max(1.0, (double)c.K / c.NG);
     double c_red = c.NG > 1 ? cols_t * (4.0 + 1.5 * c.NG) + 6.0 : 4.0;
@@ -245,7 +246,7 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
         pos = (c_pos + 4.0) * c.K / c.NG + 4.0;
         c_red = (double)c.K / c.NG * (c.NG + 6.0) + 4.0;
     }
-    double row = c.K * c.NW * c_core + c.NW * c_scan + pos + (c.shared ? 20.0 : 35.0) + c_red;
+    double row = c.K * c.NW * c_core + c.NW * c_scan + pos + (c.shared ? 8.0 : 35.0) + c_red;
     if (!c.fast) row *= 1.6;
     if (c.multi) row += 8.0 * c.NW;
     // the instantiations that compute the step need one or two VGPRs more, which matters at the 256 boundary
@@ -261,8 +262,9 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
     const double steps = (double)d->H * c.panels * row;                              // instructions of one wave
     if (wps < 1.0) return steps * 8.0;                                               // a lone wave: its own critical path
     // measured issue efficiencies: the plain kernels keep gaining up to four waves per SIMD, the shared-producer
-    // kernels (fewer, longer dependent chains per row and an LDS hand-over) level off near 0.85
-    const double eff = c.shared ? std::min(0.85, 0.35 + 0.20 * wps) : std::min(0.95, 0.30 + 0.20 * wps);
+    // kernels (fewer, longer dependent chains per row and an LDS hand-over) level off near 0.88 (256 maps of 256x256
+    // bf16: one state per lane on 16 waves 124 us, two states per lane on 8 waves 133 us; with 512 maps 245 against 219 us)
+    const double eff = c.shared ? std::min(0.88, 0.35 + 0.20 * wps) : std::min(0.95, 0.30 + 0.20 * wps);
     const double tail = wgs > res_wg ? rounds / (wgs / res_wg) : 1.0;
     // the shared-producer kernels run about 15 % faster than this count predicts (measured on the benchmark
     // shapes: fewer global loads per lane, no unpacking of x, step and mask in the scanning lanes)

@@ -179,7 +179,11 @@ def test_backward_plans_cover_every_shape_the_forward_accepts(lib):
 
 def test_benchmark_configurations_take_the_intended_forms(lib):
     f = plan(lib, lib.Desc(1, 256, 256, 256, 16, 1, 0), lib.PASS_FWD)
-    assert (f["form"], f["LG"], f["K"], f["NW"], f["waves"]) == ("shared", 64, 4, 2, 8) and f["fast"] and f["wgs"] == 256
+    # one map per compute unit: one state per lane on 16 wavefronts (four per SIMD); with more maps than compute units
+    # two states per lane on 8 wavefronts, two workgroups per compute unit
+    assert (f["form"], f["LG"], f["K"], f["NW"], f["waves"]) == ("shared", 64, 4, 1, 16) and f["fast"] and f["wgs"] == 256
+    f = plan(lib, lib.Desc(2, 256, 256, 256, 16, 1, 0), lib.PASS_FWD)
+    assert (f["form"], f["LG"], f["K"], f["NW"], f["waves"]) == ("shared", 64, 4, 2, 8) and f["wgs"] == 512
     f = plan(lib, lib.Desc(32, 192, 56, 56, 16, 1, 0), lib.PASS_FWD)
     assert f["form"] == "shared" and f["LG"] == 16 and f["K"] == 4 and f["fast"]
     f = plan(lib, lib.Desc(1, 256, 64, 64, 16, 0, 0), lib.PASS_FWD)
