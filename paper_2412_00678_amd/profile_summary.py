@@ -26,7 +26,7 @@ SIMDS = 1024                     # 256 compute units x 4 SIMDs
 COPY_KIB = 1048576.0             # roofprobe --copy moves 2^30 bytes each way per launch
 
 # run name -> (rocprofv3 options, program and its arguments, file that takes the program's stdout or None)
-TRACE_STEPS = {1: "--steps 200 --warmup 20", 2: "--steps 200 --warmup 20", 3: "--steps 100 --warmup 10", 4: "--steps 40 --warmup 8"}
+TRACE_STEPS = {1: "--steps 300 --warmup 200", 2: "--steps 300 --warmup 200", 3: "--steps 200 --warmup 100", 4: "--steps 40 --warmup 20"}
 PMC_STEPS = {1: "--steps 20 --warmup 4", 2: "--steps 20 --warmup 4", 3: "--steps 12 --warmup 4", 4: "--steps 8 --warmup 4"}
 
 
@@ -39,15 +39,15 @@ def runs():
         out.append((f"write_{w}", "--pmc WRITE_SIZE", f"{b} {PMC_STEPS[w]}", None))
         out.append((f"sq_{w}", f"--pmc {SQ}", f"{b} {PMC_STEPS[w]}", None))
     out.append(("grbm_2", "--pmc GRBM_GUI_ACTIVE", "python3 bench.py --no-cpu --workload 2 --steps 20 --warmup 4", None))
-    out.append(("trace_all", "--kernel-trace --stats", "python3 bench.py --no-cpu --all --paper-shapes --steps 150 --warmup 20", "trace_all.json"))
+    out.append(("trace_all", "--kernel-trace --stats", "python3 bench.py --no-cpu --all --paper-shapes --steps 300 --warmup 200", "trace_all.json"))
     out.append(("trace_block", "--kernel-trace --stats", "python3 bench.py --no-cpu --workload 4 --softplus --gated --steps 40 --warmup 8",
                 "trace_block.json"))
     # the same two commands without the profiler: kernel tracing adds several microseconds to every launch
-    out.append(("plain_all", None, "python3 bench.py --no-cpu --all --paper-shapes --steps 150 --warmup 20", "plain_all.json"))
+    out.append(("plain_all", None, "python3 bench.py --no-cpu --all --paper-shapes --steps 300 --warmup 200", "plain_all.json"))
     out.append(("plain_block", None, "python3 bench.py --no-cpu --workload 4 --softplus --gated --steps 40 --warmup 8", "plain_block.json"))
     # the producers in front of the scan (convolution + SiLU, projections) and the chain into the gated scan
     for w in (2, 3):
-        b = f"python3 bench.py --no-cpu --block --workload {w} --steps 60 --warmup 10"
+        b = f"python3 bench.py --no-cpu --block --workload {w} --steps 150 --warmup 100"
         out.append((f"trace_producers_{w}", "--kernel-trace --stats", b, f"trace_producers_{w}.json"))
         out.append((f"plain_producers_{w}", None, b, f"plain_producers_{w}.json"))
     out.append(("fetch_copy", "--pmc FETCH_SIZE", "./paper_2412_00678_amd/roofprobe --copy 5", None))
