@@ -245,6 +245,32 @@ int scan2d_bwd_variants(const scan2d_desc* desc,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Training pair (Supp. B: the backward first rebuilds the states with two forward scans).  The forward pass of a
+ * training step can leave the column state at the top of every band of rows, which the backward pass otherwise
+ * recomputes with a sweep of its own, in a buffer `saved` that the caller keeps until the backward pass:
+ *   scan2d_saved_bytes(desc)  : size of that buffer; 0 when this shape has no saving forward (then pass saved = NULL:
+ *                               the two calls below are exactly scan2d_fwd and scan2d_bwd).  It exists for
+ *                               desc.flags == 0, N = 16 and maps of at most 192 columns with more rows than one band.
+ *   scan2d_fwd_saving(...)    : scan2d_fwd that also writes `saved` ([Bt*Dc][bands][N][W] fp32, device memory,
+ *                               16-byte aligned, at least scan2d_saved_bytes(desc) bytes: SCAN2D_ERR_WORKSPACE_SMALL)
+ *   scan2d_bwd_saved(...)     : scan2d_bwd without its checkpoint sweep, reading `saved` (not modified)
+ * y and the gradients are those of scan2d_fwd / scan2d_bwd up to the order of the fp32 sums over states (the saving
+ * forward has one fixed tiling).  Workspaces as for scan2d_fwd / scan2d_bwd.  desc.flags must be 0 (SCAN2D_ERR_BAD_FLAGS).
+ */
+size_t scan2d_saved_bytes(const scan2d_desc* desc);
+int scan2d_fwd_saving(const scan2d_desc* desc,
+                      const void* x, const void* delta, const float* A,
+                      const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                      void* y, void* saved, size_t saved_bytes,
+                      void* workspace, size_t workspace_bytes, void* stream);
+int scan2d_bwd_saved(const scan2d_desc* desc,
+                     const void* x, const void* delta, const float* A,
+                     const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
+                     const void* dy, const void* saved, size_t saved_bytes,
+                     void* dx, void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The two producers in front of the scan inside a 2DMamba block (Sec. 3.2, Fig. 2: "the design of the original Mamba
  * block" with the scan replaced; Sec. 3.3 names the layers in front of the scan as normalization, projection and
  * convolution; Eq. 3: Delta, B and C are linear functions of x).  Both write the storage type of desc.dtype, so

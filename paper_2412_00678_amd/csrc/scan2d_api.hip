@@ -899,6 +899,54 @@ extern "C" int scan2d_bwd_static_scratch(const scan2d_desc* desc, const void* x,
                     ws, need, stream);
 }
 
+extern "C" size_t scan2d_saved_bytes(const scan2d_desc* desc) {
+    if (check_desc(desc) != SCAN2D_OK || desc->flags != 0u) return 0;
+    return bwd_saved_bytes(desc);
+}
+
+extern "C" int scan2d_fwd_saving(const scan2d_desc* desc, const void* x, const void* delta, const float* A, const void* Bm,
+                                 const void* Cm, const float* Dskip, const uint8_t* mask, void* y, void* saved, size_t saved_bytes,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (desc->flags != 0u) return SCAN2D_ERR_BAD_FLAGS;
+    const size_t need = bwd_saved_bytes(desc);
+    if (need == 0) return fwd_impl(desc, x, delta, nullptr, 0, A, Bm, Cm, Dskip, mask, y, workspace, workspace_bytes, stream);
+    if (!x || !delta || !A || !Bm || !Cm || !y || !saved) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(x) || !aligned16(delta) || !aligned16(A) || !aligned16(Bm) || !aligned16(Cm) || !aligned16(y) ||
+        !aligned16(Dskip) || !aligned16(mask) || !aligned16(saved))
+        return SCAN2D_ERR_MISALIGNED;
+    if (saved_bytes < need) return SCAN2D_ERR_WORKSPACE_SMALL;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    return fwd_saving_launch(desc, x, delta, A, Bm, Cm, Dskip, mask, y, static_cast<float*>(saved), static_cast<hipStream_t>(stream));
+}
+
+extern "C" int scan2d_bwd_saved(const scan2d_desc* desc, const void* x, const void* delta, const float* A, const void* Bm,
+                                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, const void* saved,
+                                size_t saved_bytes, void* dx, void* ddelta, float* dA, float* dBm, float* dCm, float* dDskip,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (desc->flags != 0u) return SCAN2D_ERR_BAD_FLAGS;
+    const size_t need = bwd_saved_bytes(desc);
+    if (need == 0)
+        return bwd_impl(desc, x, delta, nullptr, false, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, nullptr, dA, dBm, dCm, dDskip, workspace,
+                        workspace_bytes, stream);
+    if (!x || !delta || !A || !Bm || !Cm || !dy || !dx || !ddelta || !dA || !dBm || !dCm || !saved) return SCAN2D_ERR_NULL_POINTER;
+    if ((Dskip == nullptr) != (dDskip == nullptr)) return SCAN2D_ERR_NULL_POINTER;
+    const void* ptrs[] = {x, delta, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, dA, dBm, dCm, dDskip, workspace, saved};
+    for (const void* q : ptrs)
+        if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
+    if (saved_bytes < need) return SCAN2D_ERR_WORKSPACE_SMALL;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    rc = bwd_check(desc, false);
+    if (rc != SCAN2D_OK) return rc;
+    return bwd_launch(desc, x, delta, nullptr, false, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, nullptr, dA, dBm, dCm, dDskip, workspace,
+                      workspace_bytes, static_cast<hipStream_t>(stream), nullptr, nullptr, static_cast<const float*>(saved));
+}
+
 extern "C" int scan2d_block_conv_silu(const scan2d_desc* desc, const scan2d_conv_shape* shape, const void* u, const float* w,
                                       const float* bias, void* x, void* stream) {
     int rc = check_desc(desc);

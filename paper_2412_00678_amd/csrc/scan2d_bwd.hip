@@ -360,6 +360,42 @@ int bwd_check(const scan2d_desc* d, bool softplus, bool av) {
     return SCAN2D_OK;
 }
 
+namespace {
+bool saving_plan(const scan2d_desc* d, BwdPlan* pl) {
+    if (d->flags != 0u || !make_plan(d, pl)) return false;
+    return !pl->small && pl->panels == 1 && pl->nb > 1 && pl->k.train_fwd != nullptr && d->N == pl->k.cf_NG * pl->k.cf_NW;
+}
+}  // namespace
+
+size_t bwd_saved_bytes(const scan2d_desc* d) {
+    BwdPlan pl;
+    if (!saving_plan(d, &pl)) return 0;
+    return align_up((size_t)d->Bt * d->Dc * pl.nb * d->N * d->W * sizeof(float));
+}
+
+int fwd_saving_launch(const scan2d_desc* d, const void* x, const void* delta, const float* A, const void* Bm, const void* Cm,
+                      const float* Dskip, const uint8_t* mask, void* y, float* saved, hipStream_t stream) {
+    BwdPlan pl;
+    if (!saving_plan(d, &pl)) return SCAN2D_ERR_BAD_SHAPE;
+    const long long maps = (long long)d->Bt * d->Dc;
+    FwdArgs f;
+    f.x = x; f.delta = delta; f.A = A; f.Bm = Bm; f.Cm = Cm; f.Dskip = Dskip; f.mask = mask; f.y = y;
+    f.delta_bias = nullptr; f.carry = nullptr;
+    f.ck = saved; f.nb = pl.nb;
+    f.maps = maps; f.Dc = d->Dc; f.H = d->H; f.W = d->W; f.N = d->N;
+    const int slots = pl.k.cf_waves * 64 / pl.k.cf_LG;
+    f.NG = pl.k.cf_NG; f.MPW = slots / pl.k.cf_NG; f.panels = 1; f.RPB = pl.k.cf_RPB;
+    const long long wgf = (maps + f.MPW - 1) / f.MPW;
+    if (wgf > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    const size_t panel = (size_t)pl.k.cf_LG * pl.k.cf_K;
+    const size_t lds = (2 * (size_t)f.MPW * f.RPB * 2 * panel + 2 * (size_t)f.RPB * slots * panel) * sizeof(float);
+    if (lds > 160 * 1024) return SCAN2D_ERR_BAD_SHAPE;
+    (void)hipGetLastError();
+    if (lds > 65536 && !allow_large_lds(reinterpret_cast<const void*>(pl.k.train_fwd), lds)) return SCAN2D_ERR_LAUNCH_FAILED;
+    hipLaunchKernelGGL(pl.k.train_fwd, dim3((unsigned)wgf), dim3(pl.k.cf_waves * 64), lds, stream, f);
+    return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+}
+
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
     BwdPlan pl;
     if (!make_plan(d, &pl)) return false;
@@ -396,7 +432,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
                const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
                void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
-               size_t workspace_bytes, hipStream_t stream, const float* A_v, float* dA_v) {
+               size_t workspace_bytes, hipStream_t stream, const float* A_v, float* dA_v, const float* saved) {
     BwdPlan pl;
     if (!make_plan(d, &pl, softplus, A_v != nullptr)) return SCAN2D_ERR_BAD_SHAPE;
     if (pl.total > 0 && (workspace == nullptr || workspace_bytes < pl.total)) return SCAN2D_ERR_WORKSPACE_SMALL;
@@ -406,7 +442,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.dx = dx; a.ddelta = ddelta; a.delta_bias = delta_bias;
     if (pl.step_outside) a.delta = ws + pl.off_step;
     a.tail = pl.small ? nullptr : ws + pl.off_tail;
-    a.ck = reinterpret_cast<float*>(ws + pl.off_ck);
+    a.ck = saved != nullptr ? const_cast<float*>(saved) : reinterpret_cast<float*>(ws + pl.off_ck);
     a.pB = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pB) : dBm;   // one group: the partial is the result
     a.pC = pl.CG > 1 ? reinterpret_cast<float*>(ws + pl.off_pC) : dCm;
     a.pA = d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pA) : dA;
@@ -494,7 +530,9 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
             hipLaunchKernelGGL(pl.k.main, dim3((unsigned)wg2), dim3(pl.waves * 64), pl.lds_bytes, stream, m);
         }
     } else {
-        if (pl.nb > 1 && pl.k.ckpt_fwd != nullptr && d->N == pl.k.cf_NG * pl.k.cf_NW) {
+        if (saved != nullptr) {
+            // the forward pass of the training step has left the checkpoints
+        } else if (pl.nb > 1 && pl.k.ckpt_fwd != nullptr && d->N == pl.k.cf_NG * pl.k.cf_NW) {
             // the checkpoint sweep by the shared-producer forward kernel (checkpoint mode): it computes the softplus
             // step itself from the raw projection, with the same function as the step kernel above
             FwdArgs f;

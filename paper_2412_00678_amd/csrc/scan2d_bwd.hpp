@@ -15,6 +15,12 @@ size_t bwd_workspace_bytes(const scan2d_desc* d, bool softplus = false, bool av 
 // enqueues nothing.
 int bwd_check(const scan2d_desc* d, bool softplus = false, bool av = false);
 
+// Training pair: bytes of the band checkpoints that a forward pass can leave for the backward pass (0: this shape has
+// no such forward), and that forward pass (the shared-producer forward kernel in its checkpoint-and-output mode).
+size_t bwd_saved_bytes(const scan2d_desc* d);
+int fwd_saving_launch(const scan2d_desc* d, const void* x, const void* delta, const float* A, const void* Bm, const void* Cm,
+                      const float* Dskip, const uint8_t* mask, void* y, float* saved, hipStream_t stream);
+
 // One line describing the backward plan; false when the shape has no plan.
 bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes);
 
@@ -24,6 +30,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
                const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
                void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
-               size_t workspace_bytes, hipStream_t stream, const float* A_v = nullptr, float* dA_v = nullptr);
+               size_t workspace_bytes, hipStream_t stream, const float* A_v = nullptr, float* dA_v = nullptr,
+               const float* saved = nullptr);   // saved: the checkpoints left by fwd_saving_launch (no checkpoint sweep then)
 
 }  // namespace scan2d

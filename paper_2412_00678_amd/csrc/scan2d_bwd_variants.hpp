@@ -25,6 +25,8 @@ struct BwdKernels {
     // checkpoint sweep run by the shared-producer forward kernel in its checkpoint mode (FwdArgs), with its tiling
     void (*ckpt_fwd)(const FwdArgs) = nullptr;
     int cf_LG = 0, cf_K = 0, cf_NW = 0, cf_NG = 0, cf_waves = 0, cf_RPB = 0;
+    // the same tiling as a forward pass that also writes the checkpoints (training step: scan2d_fwd_saving)
+    void (*train_fwd)(const FwdArgs) = nullptr;
 };
 
 // Main sweeps that share the per-position work of a job through LDS: (LG, K, NW, NG, WAVES, RB) and the tiling
@@ -34,7 +36,7 @@ struct BwdKernels {
 // checkpoint sweep in its checkpoint mode.
 #define SCAN2D_BWD_SHARED_VARIANTS(X)                                                       \
     X(16, 4, 1, 16, 4, 4, 16, 4, 2, 16, 4, 2, 8, 4, 4) X(16, 8, 1, 16, 4, 4, 16, 8, 2, 16, 8, 2, 8, 4, 2)       \
-    X(16, 12, 1, 16, 4, 4, 16, 12, 2, 16, 12, 2, 8, 4, 2) X(32, 6, 1, 16, 8, 4, 16, 12, 2, 16, 12, 2, 8, 4, 2)  \
+    X(16, 12, 1, 16, 4, 4, 16, 12, 2, 16, 12, 2, 8, 4, 2) X(32, 6, 1, 16, 8, 2, 16, 12, 2, 16, 12, 2, 8, 4, 2)  \
     X(32, 4, 1, 16, 8, 4, 16, 8, 2, 16, 8, 2, 8, 4, 2) X(64, 4, 1, 16, 16, 2, 64, 4, 1, 64, 4, 2, 8, 8, 4)
 
 // W: the map width (the checkpoint sweep has its own columns per lane, hence its own row-end treatment)
@@ -65,6 +67,14 @@ inline BwdKernels lookup_bwd_shared_kernels(int LG, int K, int NW, int NG, int w
             r.ckpt_fwd = scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, false, rb, CF>;   \
         }                                                                                                \
         r.cf_LG = flg; r.cf_K = fk; r.cf_NW = fnw; r.cf_NG = fng; r.cf_waves = fwv; r.cf_RPB = frpb;     \
+        if constexpr (!SP && !CF && lg == 16) {                                                          \
+            if constexpr (Elem<T>::kBytes == 2) {                                                        \
+                r.train_fwd = (W % 2) != 0 ? scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, false, true, rb, false, true>    \
+                                           : scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, false, false, rb, false, true>;  \
+            } else {                                                                                     \
+                r.train_fwd = scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, false, false, rb, false, true>;                 \
+            }                                                                                            \
+        }                                                                                                \
     }                                                                                                    \
     }
     SCAN2D_BWD_SHARED_VARIANTS(SCAN2D_X)

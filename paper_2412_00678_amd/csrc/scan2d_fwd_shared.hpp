@@ -63,8 +63,12 @@ __device__ __forceinline__ void carry_apply(float* hl, const float* pl, const fl
 // CF: columns first.  The column recurrence runs on u (v = a * v[i-1,j] + u, the register that persists from row to
 // row), the row scan then runs on its result (h = a * h[i,j-1] + v) and y reads the scanned value: the same
 // instructions in the other order.  The checkpoint sweep (CK > 0) then keeps v and needs no row scan at all.
-template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0, bool CF = false>
+// KEEPY (with CK > 0): the forward pass of a training step - y is produced as usual and the band checkpoints are written
+// on the way, so that the backward pass need not run its checkpoint sweep.
+template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0, bool CF = false, bool KEEPY = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const FwdArgs p) {
+    constexpr bool YOUT = CK == 0 || KEEPY;               // Cm, the sum over states and y are part of this instantiation
+    constexpr bool NOSCAN = CF && CK > 0 && !KEEPY;       // columns-first checkpoint sweep: the row scan feeds nothing
     static_assert(!UA || Elem<T>::kBytes == 2, "UA: bf16 rows on odd 2-byte boundaries");
     constexpr int XW = words_of<T, K>();
     constexpr int SLOTS = WAVES * 64 / LG, MPW = SLOTS / NG, PANEL = LG * K, TM = NG * LG;
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
 #pragma unroll
         for (int s = 0; s < NW; ++s) {
             lds(rsB, s, ro, rB[d][s]);
-            if constexpr (CK == 0) lds(rsC, s, ro, rC[d][s]);
+            if constexpr (YOUT) lds(rsC, s, ro, rC[d][s]);
         }
     }
     produce(0);
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                         hl[t][0] = dxq[set][0] * get_elem<T, K>(uB, 0);
                     }
                     pl[t][0] = a[t][0];
-                    if constexpr (!(CF && CK > 0)) {
+                    if constexpr (!NOSCAN) {
 #pragma unroll
                         for (int j = 1; j < K; ++j) {
                             hl[t][j] = fmaf(a[t][j], hl[t][j - 1], CF ? h[s][j] : dxq[set][j] * get_elem<T, K>(uB, j));
@@ -274,42 +278,43 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                         }
                     }
                     lds(rsB, s, nxt, rB[SS][s]);
-                    if constexpr (!(CF && CK > 0)) {
+                    if constexpr (!NOSCAN) {
                         P[t] = pl[t][K - 1];
                         Hh[t] = hl[t][K - 1];
                     }
                 }
-                if constexpr (!(CF && CK > 0)) {
+                if constexpr (!NOSCAN) {
                     if constexpr (kDppApply) group_scan_nocarry<LG, SC>(P, Hh, cin); else group_scan<LG, SC>(P, Hh, cin);
                 }
 #pragma unroll
                 for (int t = 0; t < SC; ++t) {
                     const int s = s0 + t;
-                    if constexpr (kDppApply && LG != 32 && !(CF && CK > 0)) carry_apply<LG, K>(hl[t], pl[t], Hh[t]);   // Eq. 5
+                    if constexpr (kDppApply && LG != 32 && !NOSCAN) carry_apply<LG, K>(hl[t], pl[t], Hh[t]);   // Eq. 5
                     uint32_t uC[XW];
-                    if constexpr (CK == 0) unpacks(rC[SS][s], s, cur, uC);
-                    if constexpr (!(CF && CK > 0)) {
+                    if constexpr (YOUT) unpacks(rC[SS][s], s, cur, uC);
+                    if constexpr (!NOSCAN) {
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
                             const float hh = (j == K - 1) ? Hh[t] : ((kDppApply && LG != 32) ? hl[t][j] : fmaf(pl[t][j], cin[t], hl[t][j]));
                             if constexpr (!CF) fma_inplace(h[s][j], a[t][j], hh);                   // Eq. 6
-                            if constexpr (CK == 0) {
+                            if constexpr (YOUT) {
                                 const float cv = get_elem<T, K>(uC, j);
                                 const float hv = CF ? hh : h[s][j];
                                 yacc[j] = s == 0 ? cv * hv : fmaf(cv, hv, yacc[j]);
                             }
                         }
                     }
-                    if constexpr (CK == 0) lds(rsC, s, nxt, rC[SS][s]);
+                    if constexpr (YOUT) lds(rsC, s, nxt, rC[SS][s]);
                 }
             }
-            if constexpr (CK == 0) {
+            if constexpr (YOUT) {
                 float* mine = ypart + buf * YP_BUF + r * YP_ROW + slot * PANEL + l * 4;
 #pragma unroll
                 for (int j4 = 0; j4 < K / 4; ++j4)
                     *reinterpret_cast<float4*>(mine + j4 * (LG * 4)) =
                         make_float4(yacc[4 * j4], yacc[4 * j4 + 1], yacc[4 * j4 + 2], yacc[4 * j4 + 3]);
-            } else {
+            }
+            if constexpr (CK > 0) {
                 if ((i + 1) % CK == 0 && i + 1 < H && live) {             // h[i] enters band (i+1)/CK
                     const int band = (i + 1) / CK;
 #pragma unroll
@@ -336,7 +341,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
         __syncthreads();
         fetch_row(buf ^ 1, 0, 0);
         // sums over the lane groups of the cells this thread produced, skip term, one rounding, store
-        if (CK == 0 && live) {
+        if (YOUT && live) {
             const float* ybase = ypart + buf * YP_BUF + (slot - sg) * PANEL;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {

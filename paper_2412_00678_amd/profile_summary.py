@@ -117,18 +117,36 @@ def counters(runs_dir, name, like="%scan2d%"):
     return out
 
 
+def pair_weights(table):
+    """Launches per reported step for a run of the training workload, which times scan2d_fwd + scan2d_bwd and then the
+    training pair scan2d_fwd_saving + scan2d_bwd_saved (the reported step): the plain forward and the checkpoint sweep
+    are not part of the pair, the kernels both backward calls share run once per step.  None for other runs."""
+    saving = [k for k in table if k.startswith("scan2d_fwd_shared_kernel") and k.endswith(", true>")]
+    if not saving:
+        return None
+    w = {}
+    for k in table:
+        if k.startswith("scan2d_fwd_shared_kernel"):
+            w[k] = 1.0 if k in saving else 0.0
+        else:
+            w[k] = 0.5                                    # dispatched by scan2d_bwd and by scan2d_bwd_saved
+    return w
+
+
 def per_step(table, counter):
     """Sum over kernels of (mean per dispatch x dispatches per step).  A step is one bench.py step; the kernel
     with the fewest dispatches runs once per step and every other count must be a multiple of it."""
     counts = {k: v[counter][1] for k, v in table.items() if counter in v}
     steps = min(counts.values())
+    weights = pair_weights(table)
     total, rows = 0.0, []
     for k, c in sorted(counts.items()):
         if c % steps:
             raise ValueError(f"{k}: {c} dispatches is not a multiple of {steps} steps")
         mean, _, dur = table[k][counter]
-        total += mean * (c // steps)
-        rows.append((k, c // steps, mean, dur))
+        n = (c // steps) * (weights[k] if weights else 1.0)
+        total += mean * n
+        rows.append((k, n, mean, dur))
     return total, rows, steps
 
 
@@ -162,7 +180,7 @@ def workload_summary(runs_dir, w, bench, fs, ws, ghz):
     for k, n, mean, dur in frows:
         v, vd = vmap.get(k, (0.0, dur))
         util = v * 4.0 / SIMDS / (ghz * 1e3) / vd if vd else 0.0
-        lines.append(f"| `{k[:100]}` | {n} | {vd:.1f} | {v * 64 * n / units:.2f} | {100 * util:.0f} % | {mean * fs * 1024 / 1e6:.1f} | "
+        lines.append(f"| `{k[:100]}` | {n:g} | {vd:.1f} | {v * 64 * max(n, 1) / units:.2f} | {100 * util:.0f} % | {mean * fs * 1024 / 1e6:.1f} | "
                      f"{wmap[k][1] * ws * 1024 / 1e6:.1f} |")
     rec = {"hbm_bytes_per_launch": int(round((fetch_kib * fs + write_kib * ws) * 1024)),
            "hbm_read_bytes": int(round(fetch_kib * fs * 1024)), "hbm_written_bytes": int(round(write_kib * ws * 1024)),
@@ -220,6 +238,10 @@ def write(runs_dir):
         timing = f"forward {d['fwd_ms'] * 1e3:.1f} us (median {d['fwd_ms_median'] * 1e3:.1f}, minimum {d['fwd_ms_min'] * 1e3:.1f})"
         if "bwd_ms" in d:
             timing += f", backward {d['bwd_ms'] * 1e3:.1f} us (median {d['bwd_ms_median'] * 1e3:.1f}, minimum {d['bwd_ms_min'] * 1e3:.1f})"
+        if "pair_fwd_ms" in d:
+            timing += (f"; training pair (the reported step; launches per step below are those of the pair): scan2d_fwd_saving "
+                       f"{d['pair_fwd_ms'] * 1e3:.1f} us, scan2d_bwd_saved {d['pair_bwd_ms'] * 1e3:.1f} us, "
+                       f"{d['pair_saved_bytes'] / 1e6:.0f} MB of checkpoints handed over")
         with open(os.path.join(PROFILES, fname), "w") as f:
             f.write(f"""# {title}
 

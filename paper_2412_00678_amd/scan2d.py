@@ -21,7 +21,7 @@ PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS, PASS_FWD_VARIANTS, PASS_B
 EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
            "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants",
-           "scan2d_block_conv_silu", "scan2d_block_xproj")
+           "scan2d_block_conv_silu", "scan2d_block_xproj", "scan2d_saved_bytes", "scan2d_fwd_saving", "scan2d_bwd_saved")
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ERR_SCRATCH_LIMIT = -9
 TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
@@ -76,6 +76,12 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_block_conv_silu.restype = ctypes.c_int
     lib.scan2d_block_xproj.argtypes = [ctypes.POINTER(Desc), ctypes.c_int] + [vp] * 7
     lib.scan2d_block_xproj.restype = ctypes.c_int
+    lib.scan2d_saved_bytes.argtypes = [ctypes.POINTER(Desc)]
+    lib.scan2d_saved_bytes.restype = ctypes.c_size_t
+    lib.scan2d_fwd_saving.argtypes = [ctypes.POINTER(Desc)] + [vp] * 8 + [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+    lib.scan2d_fwd_saving.restype = ctypes.c_int
+    lib.scan2d_bwd_saved.argtypes = [ctypes.POINTER(Desc)] + [vp] * 8 + [vp, ctypes.c_size_t] + [vp] * 6 + [vp, ctypes.c_size_t, vp]
+    lib.scan2d_bwd_saved.restype = ctypes.c_int
     lib.scan2d_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.c_int]
     lib.scan2d_workspace_bytes.restype = ctypes.c_size_t
     lib.scan2d_strerror.argtypes = [ctypes.c_int]
@@ -264,6 +270,41 @@ def prepare_bwd(x, delta, A, Bm, Cm, Dskip, mask, dy, out, workspace=None, flags
     args = (ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(dy),
             _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _ptr(out[3]), _ptr(out[4]), _ptr(out[5]), _ptr(workspace), wbytes)
     return Prepared(lib.scan2d_bwd, "scan2d_bwd", args, (desc, x, delta, A, Bm, Cm, Dskip, mask, dy, out, workspace))
+
+
+def saved_bytes(desc: Desc) -> int:
+    """Bytes of the buffer that scan2d_fwd_saving leaves for scan2d_bwd_saved (0: this shape has no saving forward)."""
+    return int(lib.scan2d_saved_bytes(ctypes.byref(desc)))
+
+
+def prepare_training_pair(x, delta, A, Bm, Cm, Dskip, mask, y, dy, out, workspace_fwd=None, workspace_bwd=None):
+    """(forward, backward, saved): scan2d_fwd_saving and scan2d_bwd_saved on these tensors as Prepared calls that share
+    the buffer `saved` (None when the shape has no saving forward: the calls are then scan2d_fwd and scan2d_bwd)."""
+    desc = make_desc(x, A, 0)
+    Bt, Dc, H, W, N = desc.Bt, desc.Dc, desc.H, desc.W, desc.N
+    for t, name, dt, shape in ((x, "x", x.dtype, (Bt, Dc, H, W)), (delta, "delta", x.dtype, (Bt, Dc, H, W)), (A, "A", torch.float32, (Dc, N)),
+                               (Bm, "Bm", x.dtype, (Bt, N, H, W)), (Cm, "Cm", x.dtype, (Bt, N, H, W)), (y, "y", x.dtype, (Bt, Dc, H, W)),
+                               (dy, "dy", x.dtype, (Bt, Dc, H, W)), (out[0], "dx", x.dtype, (Bt, Dc, H, W)),
+                               (out[1], "ddelta", x.dtype, (Bt, Dc, H, W)), (out[2], "dA", torch.float32, (Dc, N)),
+                               (out[3], "dBm", torch.float32, (Bt, N, H, W)), (out[4], "dCm", torch.float32, (Bt, N, H, W))):
+        _check(t, name, dt, shape)
+    _check(Dskip, "Dskip", torch.float32, (Dc,), optional=True)
+    _check(out[5], "dDskip", torch.float32, (Dc,), optional=True)
+    _check(mask, "mask", torch.uint8, (Bt, H, W), optional=True)
+    nsaved = saved_bytes(desc)
+    saved = torch.empty(nsaved, dtype=torch.uint8, device=x.device) if nsaved > 0 else None
+    if workspace_fwd is None:
+        workspace_fwd, _ = _workspace(desc, PASS_FWD, x.device)
+    if workspace_bwd is None:
+        workspace_bwd, _ = _workspace(desc, PASS_BWD, x.device)
+    nbytes = lambda t: 0 if t is None else t.numel() * t.element_size()
+    fargs = (ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(y), _ptr(saved), nsaved,
+             _ptr(workspace_fwd), nbytes(workspace_fwd))
+    bargs = (ctypes.byref(desc), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dskip), _ptr(mask), _ptr(dy), _ptr(saved), nsaved,
+             _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _ptr(out[3]), _ptr(out[4]), _ptr(out[5]), _ptr(workspace_bwd), nbytes(workspace_bwd))
+    keep = (desc, x, delta, A, Bm, Cm, Dskip, mask, y, dy, out, saved, workspace_fwd, workspace_bwd)
+    return (Prepared(lib.scan2d_fwd_saving, "scan2d_fwd_saving", fargs, keep), Prepared(lib.scan2d_bwd_saved, "scan2d_bwd_saved", bargs, keep),
+            saved)
 
 
 def scan2d_fwd_softplus(x, delta_raw, delta_bias, A, Bm, Cm, Dskip=None, mask=None, y=None, workspace=None, flags=0):

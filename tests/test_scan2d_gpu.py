@@ -1014,3 +1014,71 @@ def test_maps_beyond_the_32_bit_byte_range_land_at_their_own_index(s2d):
     assert rel_err(dA[picks].cpu().numpy(), rg[2]) <= 1e-4
     assert rel_err(dD[picks].cpu().numpy(), rg[5]) <= 1e-4
     assert bool(torch.isfinite(dBm).all()) and bool(torch.isfinite(dCm).all())
+
+
+# ------------------------------------------------------------------ training pair: the forward leaves the band checkpoints
+
+PAIR_SHAPES = [
+    (2, 5, 16, 37, 50, wl.F32, 0.3), (1, 3, 16, 130, 190, wl.F32, 0.3), (2, 4, 16, 23, 101, wl.BF16, 0.4), (1, 6, 16, 56, 56, wl.BF16, 0.0),
+    (1, 2, 16, 9, 128, wl.F32, 0.2),
+    # no saving forward for these (8 states; 256 columns; one band; small maps): the pair is scan2d_fwd / scan2d_bwd
+    (1, 3, 8, 20, 40, wl.F32, 0.3), (1, 2, 16, 12, 256, wl.BF16, 0.3), (1, 2, 16, 3, 40, wl.F32, 0.0), (2, 3, 16, 14, 14, wl.F32, 0.0),
+]
+
+
+@pytest.mark.parametrize("shape", PAIR_SHAPES, ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
+def test_training_pair_matches_oracle_and_the_plain_backward(s2d, shape):
+    import torch
+    Bt, Dc, N, H, W, dtype, mf = shape
+    w = wl.Workload("pair", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True)
+    inp = wl.make_inputs(w, seed=51)
+    d = s2d.to_device(inp, dtype)
+    desc = s2d.make_desc(d["x"], d["A"])
+    print(f"training pair case {shape}: saved bytes {s2d.saved_bytes(desc)}", flush=True)
+    expect_saving = N == 16 and 16 < W <= 192 and H > 4
+    assert (s2d.saved_bytes(desc) > 0) == expect_saving
+    y = torch.empty_like(d["x"])
+    out = (torch.empty_like(d["x"]), torch.empty_like(d["x"]), torch.empty_like(d["A"]), torch.empty(d["Bm"].shape, dtype=torch.float32, device="cuda"),
+           torch.empty(d["Bm"].shape, dtype=torch.float32, device="cuda"), None if d["Dskip"] is None else torch.empty_like(d["Dskip"]))
+    fwd, bwd, saved = s2d.prepare_training_pair(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], y, d["dy"], out)
+    assert (saved is not None) == expect_saving
+    fwd()
+    bwd()
+    torch.cuda.synchronize()
+    ref = oracle.scan2d_fwd(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"], inp["mask"], dtype=dtype)
+    assert rel_err(wl.to_float(s2d.to_host(y), dtype), wl.to_float(ref, dtype)) <= TOL[dtype]
+    plain = s2d.scan2d_bwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"], d["dy"])
+    torch.cuda.synchronize()
+    for name, g, p in zip(GRADS, out, plain):             # the same sweeps on the same checkpoints: bit for bit
+        if p is None:
+            assert g is None
+            continue
+        assert torch.equal(g.view(torch.uint8), p.view(torch.uint8)), name
+    refs = oracle.scan2d_bwd(inp["x"], inp["delta"], inp["A"], inp["Bm"], inp["Cm"], inp["Dskip"], inp["mask"], inp["dy"], dtype=dtype)
+    for k, (name, g, r) in enumerate(zip(GRADS, out, refs)):
+        if r is None:
+            continue
+        gv = wl.to_float(s2d.to_host(g), dtype) if k < 2 else s2d.to_host(g).astype(np.float64)
+        rv = wl.to_float(r, dtype) if k < 2 else r.astype(np.float64)
+        tol = TOL[dtype] if k < 2 else (1e-4 if dtype == wl.F32 else 2e-2)
+        assert rel_err(gv, rv) <= tol, f"{name}: rel err {rel_err(gv, rv):.3e}"
+
+
+def test_training_pair_rejects_flags_and_short_buffers(s2d):
+    import ctypes
+    import torch
+    w = wl.Workload("pairerr", 1, 2, 16, 24, 64, wl.F32, backward=True)
+    d = s2d.to_device(wl.make_inputs(w, seed=52), wl.F32)
+    desc = s2d.make_desc(d["x"], d["A"])
+    need = s2d.saved_bytes(desc)
+    assert need > 0
+    assert s2d.saved_bytes(s2d.make_desc(d["x"], d["A"], s2d.FLAG_COLUMNS_FIRST)) == 0
+    y = torch.empty_like(d["x"])
+    saved = torch.empty(need, dtype=torch.uint8, device="cuda")
+    p = lambda t: None if t is None else t.data_ptr()
+    args = (p(d["x"]), p(d["delta"]), p(d["A"]), p(d["Bm"]), p(d["Cm"]), p(d["Dskip"]), p(d["mask"]), p(y))
+    rc = s2d.lib.scan2d_fwd_saving(ctypes.byref(desc), *args, p(saved), need - 1, None, 0, None)
+    assert rc == -5
+    flagged = s2d.make_desc(d["x"], d["A"], s2d.FLAG_IDENTITY_CELLS)
+    assert s2d.lib.scan2d_fwd_saving(ctypes.byref(flagged), *args, p(saved), need, None, 0, None) == -4
+    assert s2d.lib.scan2d_fwd_saving(ctypes.byref(desc), *args, None, need, None, 0, None) == -1
