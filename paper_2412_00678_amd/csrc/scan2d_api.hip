@@ -420,9 +420,12 @@ size_t bwd_need(const scan2d_desc* d, bool softplus) {
     return inner == 0 ? 0 : inner + skip_bytes(d);
 }
 
+// z, y_gated (softplus form only): where the chosen kernel has an instantiation with the output gate, it also writes
+// y_gated = y * SiLU(z) (and y only if y != y_gated) and *gated is set; otherwise the call is the ungated one.
 int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, int softplus, const float* A,
              const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
-             void* y, void* workspace, size_t workspace_bytes, void* stream);
+             void* y, void* workspace, size_t workspace_bytes, void* stream,
+             const void* z = nullptr, void* y_gated = nullptr, bool* gated = nullptr);
 
 // Everything the scan launch of fwd_impl could refuse for this descriptor, without enqueuing anything.
 int fwd_check(const scan2d_desc* d, bool sp, bool has_mask, bool cf) {
@@ -463,7 +466,7 @@ int fwd_columns_first(const scan2d_desc* desc, const void* x, const void* delta,
 
 int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, int softplus, const float* A,
              const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
-             void* y, void* workspace, size_t workspace_bytes, void* stream) {
+             void* y, void* workspace, size_t workspace_bytes, void* stream, const void* z, void* y_gated, bool* gated) {
     int rc = check_desc(desc);
     if (rc != SCAN2D_OK) return rc;
     if (!x || !delta || !A || !Bm || !Cm || !y) return SCAN2D_ERR_NULL_POINTER;
@@ -499,6 +502,17 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
     a.NG = ch.NG; a.MPW = ch.MPW; a.panels = ch.panels; a.RPB = ch.RPB;
     const long long wgs = (a.maps + ch.MPW - 1) / ch.MPW;
     if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
+    if (z != nullptr && y_gated != nullptr && softplus != 0 && ch.shared && !ch.cf) {   // the gate in the same kernel
+        const bool ua = desc->dtype == SCAN2D_BF16 && (desc->W % 2) != 0;
+        const FwdKernel k = desc->dtype == SCAN2D_BF16 ? fwd_shared_kernel_gate_bf16(ch.LG, ch.K, ch.NW, ch.NG, ch.waves, ch.RPB, ua)
+                                                       : fwd_shared_kernel_gate_f32(ch.LG, ch.K, ch.NW, ch.NG, ch.waves, ch.RPB);
+        if (k != nullptr) {
+            ch.kernel = k;
+            a.z = z; a.y_gated = y_gated;
+            if (y == y_gated) a.y = nullptr;
+            if (gated != nullptr) *gated = true;
+        }
+    }
     (void)hipGetLastError();
     if (ch.lds_bytes > 65536 && !allow_large_lds(reinterpret_cast<const void*>(ch.kernel), ch.lds_bytes)) return SCAN2D_ERR_LAUNCH_FAILED;
     hipLaunchKernelGGL(ch.kernel, dim3((unsigned)wgs), dim3(ch.waves * 64), ch.lds_bytes, static_cast<hipStream_t>(stream), a);
@@ -637,8 +651,9 @@ extern "C" int scan2d_fwd_softplus_gated(const scan2d_desc* desc, const void* x,
     if (!z || !y) return SCAN2D_ERR_NULL_POINTER;
     if (!aligned16(z) || !aligned16(y_scan)) return SCAN2D_ERR_MISALIGNED;
     void* ys = y_scan != nullptr ? y_scan : y;
-    const int rc = fwd_impl(desc, x, delta_raw, delta_bias, 1, A, Bm, Cm, Dskip, mask, ys, workspace, workspace_bytes, stream);
-    if (rc != SCAN2D_OK) return rc;
+    bool gated = false;
+    const int rc = fwd_impl(desc, x, delta_raw, delta_bias, 1, A, Bm, Cm, Dskip, mask, ys, workspace, workspace_bytes, stream, z, y, &gated);
+    if (rc != SCAN2D_OK || gated) return rc;
     return gate_fwd_launch(desc, ys, z, y, static_cast<hipStream_t>(stream));
 }
 

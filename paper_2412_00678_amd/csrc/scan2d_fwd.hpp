@@ -55,6 +55,8 @@ struct FwdArgs {
     const float* A_v = nullptr; // [Dc][N]; read by the AV instantiations only: decay parameter of the column recurrence
     float* carry;        // [maps][N][H] row-end states between column panels (panels > 1 only)
     float* ck = nullptr; // checkpoint sweep of the backward pass only: [maps][nb][N][W] column states entering each band
+    const void* z = nullptr;     // GATE instantiations only: the block's gate branch, layout of x
+    void* y_gated = nullptr;     // GATE instantiations only: y * SiLU(z); y itself may then be null (not stored)
     int nb = 0;          // bands of that sweep
     long long maps;      // Bt * Dc
     int Dc, H, W, N;

@@ -65,7 +65,11 @@ __device__ __forceinline__ void carry_apply(float* hl, const float* pl, const fl
 // instructions in the other order.  The checkpoint sweep (CK > 0) then keeps v and needs no row scan at all.
 // KEEPY (with CK > 0): the forward pass of a training step - y is produced as usual and the band checkpoints are written
 // on the way, so that the backward pass need not run its checkpoint sweep.
-template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0, bool CF = false, bool KEEPY = false>
+// GATE: the output gate of the block (Fig. 2) in the same kernel: the thread that produces a cell also loads z there,
+// keeps SiLU(z) beside the skip term, and multiplies the unrounded sum over states by it where it stores the cell
+// (p.y_gated; the ungated p.y is stored too unless it is null).
+template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0, bool CF = false, bool KEEPY = false,
+          bool GATE = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const FwdArgs p) {
     constexpr bool YOUT = CK == 0 || KEEPY;               // Cm, the sum over states and y are part of this instantiation
     constexpr bool NOSCAN = CF && CK > 0 && !KEEPY;       // columns-first checkpoint sweep: the row scan feeds nothing
@@ -106,6 +110,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
     const T* __restrict__ xu = reinterpret_cast<const T*>(p.x) + (size_t)map0 * HW;
     const T* __restrict__ du = reinterpret_cast<const T*>(p.delta) + (size_t)map0 * HW;
     T* __restrict__ yu = reinterpret_cast<T*>(p.y) + (size_t)map * HW;
+    const T* __restrict__ zu = reinterpret_cast<const T*>(p.z) + (size_t)map0 * HW;                // GATE only
+    T* __restrict__ ygu = reinterpret_cast<T*>(p.y_gated) + (size_t)map * HW;                        // GATE only
     const T* __restrict__ Bu = reinterpret_cast<const T*>(p.Bm) + (size_t)b0 * N * HW;
     const T* __restrict__ Cu = reinterpret_cast<const T*>(p.Cm) + (size_t)b0 * N * HW;
     const uint8_t* __restrict__ mu = p.mask ? p.mask + (size_t)b0 * HW : nullptr;
@@ -118,6 +124,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
     const rsrc_t rsx = make_rsrc(xu, up4(left_maps * EB)), rsd = make_rsrc(du, up4(left_maps * EB)),
                  rsB = make_rsrc(Bu, up4(left_items * N * EB)), rsC = make_rsrc(Cu, up4(left_items * N * EB)),
                  rsm = make_rsrc(mu, up4(left_items));
+    const rsrc_t rsz = make_rsrc(GATE ? zu : xu, up4(left_maps * EB));
 
     float Ap[NW];
 #pragma unroll
@@ -138,7 +145,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
     }
     const int nbatch = (H + RPB - 1) / RPB;
 
-    uint32_t rawx[CT], rawd[CT], rawm[CT];
+    uint32_t rawx[CT], rawd[CT], rawm[CT], rawz[GATE ? CT : 1];
     // element loads: any alignment, any width; a load past the end of the tensor returns 0
     auto request = [&](int batch) {
         const uint32_t ro = (uint32_t)batch * (uint32_t)(RPB * W);
@@ -150,16 +157,18 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                 if constexpr (EB == 4) {
                     rawx[v * VEC + e] = __builtin_amdgcn_raw_buffer_load_b32(rsx, lo * 4u, ro * 4u, 0);
                     rawd[v * VEC + e] = __builtin_amdgcn_raw_buffer_load_b32(rsd, lo * 4u, ro * 4u, 0);
+                    if constexpr (GATE) rawz[v * VEC + e] = __builtin_amdgcn_raw_buffer_load_b32(rsz, lo * 4u, ro * 4u, 0);
                 } else {
                     rawx[v * VEC + e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsx, lo * 2u, ro * 2u, 0);
                     rawd[v * VEC + e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsd, lo * 2u, ro * 2u, 0);
+                    if constexpr (GATE) rawz[v * VEC + e] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsz, lo * 2u, ro * 2u, 0);
                 }
                 rawm[v * VEC + e] = 0u;
                 if (has_mask)
                     rawm[v * VEC + e] = (uint32_t)(uint8_t)__builtin_amdgcn_raw_buffer_load_b8(rsm, mlane + cell_off[v] + (uint32_t)e, ro, 0);
             }
     };
-    float sk_cur[CT], sk_next[CT];
+    float sk_cur[CT], sk_next[CT], gt_cur[GATE ? CT : 1], gt_next[GATE ? CT : 1];
     auto produce = [&](int buf) {
         float* base = pp + buf * PP_BUF + map_slot * PP_MAP;
 #pragma unroll
@@ -175,6 +184,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                 row[e] = dl;
                 row[PANEL + e] = dl * xe;
                 sk_next[k] = dsk * xe;
+                if constexpr (GATE) {
+                    const float zv = EB == 4 ? __uint_as_float(rawz[k]) : __uint_as_float(rawz[k] << 16);
+                    gt_next[k] = zv / (1.0f + __builtin_amdgcn_exp2f(-zv * kLog2e));                      // SiLU(z)
+                }
             }
         }
     };
@@ -222,7 +235,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
     }
     produce(0);
 #pragma unroll
-    for (int k = 0; k < CT; ++k) sk_cur[k] = sk_next[k];
+    for (int k = 0; k < CT; ++k) {
+        sk_cur[k] = sk_next[k];
+        if constexpr (GATE) gt_cur[k] = gt_next[k];
+    }
     request(min(1, nbatch - 1));
     __syncthreads();
 
@@ -373,33 +389,47 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                     float out[VEC];
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) out[e] = acc[e] + sk_cur[v * VEC + e];
-                    T* dst = yu + (size_t)i * W + cell_col[v];
-                    if (cell_col[v] + VEC <= W) {
-                        if constexpr (EB == 4) {
-                            uint32_t bits[VEC];
+                    auto store_vec = [&](T* base, const float* val) {
+                        T* dst = base + (size_t)i * W + cell_col[v];
+                        if (cell_col[v] + VEC <= W) {
+                            if constexpr (EB == 4) {
+                                uint32_t bits[VEC];
 #pragma unroll
-                            for (int e = 0; e < VEC; ++e) bits[e] = __float_as_uint(out[e]);
-                            store_words<VEC>(reinterpret_cast<uint32_t*>(dst), bits);
-                        } else if (VEC >= 2 && (((size_t)i * W + cell_col[v]) & 1u) == 0u) {   // pairs on dword boundaries
-                            uint32_t bits[VEC >= 2 ? VEC / 2 : 1];
+                                for (int e = 0; e < VEC; ++e) bits[e] = __float_as_uint(val[e]);
+                                store_words<VEC>(reinterpret_cast<uint32_t*>(dst), bits);
+                            } else if (VEC >= 2 && (((size_t)i * W + cell_col[v]) & 1u) == 0u) {   // pairs on dword boundaries
+                                uint32_t bits[VEC >= 2 ? VEC / 2 : 1];
 #pragma unroll
-                            for (int e = 0; e < VEC / 2; ++e)
-                                bits[e] = f32_to_bf16_bits(out[2 * e]) | (f32_to_bf16_bits(out[2 * e + 1]) << 16);
-                            store_words<(VEC >= 2 ? VEC / 2 : 1)>(reinterpret_cast<uint32_t*>(dst), bits);
+                                for (int e = 0; e < VEC / 2; ++e)
+                                    bits[e] = f32_to_bf16_bits(val[2 * e]) | (f32_to_bf16_bits(val[2 * e + 1]) << 16);
+                                store_words<(VEC >= 2 ? VEC / 2 : 1)>(reinterpret_cast<uint32_t*>(dst), bits);
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < VEC; ++e) store_elem(dst + e, val[e]);
+                            }
                         } else {
 #pragma unroll
-                            for (int e = 0; e < VEC; ++e) store_elem(dst + e, out[e]);
+                            for (int e = 0; e < VEC; ++e)
+                                if (cell_col[v] + e < W) store_elem(dst + e, val[e]);
                         }
-                    } else {
+                    };
+                    if constexpr (GATE) {
+                        float gated[VEC];
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e)
-                            if (cell_col[v] + e < W) store_elem(dst + e, out[e]);
+                        for (int e = 0; e < VEC; ++e) gated[e] = out[e] * gt_cur[v * VEC + e];
+                        store_vec(ygu, gated);
+                        if (p.y != nullptr) store_vec(yu, out);
+                    } else {
+                        store_vec(yu, out);
                     }
                 }
             }
         }
 #pragma unroll
-        for (int k = 0; k < CT; ++k) sk_cur[k] = sk_next[k];
+        for (int k = 0; k < CT; ++k) {
+            sk_cur[k] = sk_next[k];
+            if constexpr (GATE) gt_cur[k] = gt_next[k];
+        }
     }
 }
 

@@ -53,10 +53,14 @@ FwdKernel fwd_shared_kernel_bf16(int LG, int K, int NW, int NG, int waves, int R
 FwdKernel fwd_shared_kernel_f32_cf(int LG, int K, int NW, int NG, int waves, int RPB, bool sp);
 FwdKernel fwd_shared_kernel_bf16_cf(int LG, int K, int NW, int NG, int waves, int RPB, bool sp, bool ua);
 
-template <typename T, bool SP, bool UA, bool CF = false>
+// The instantiations that also apply the block's output gate (softplus step, rows first).
+FwdKernel fwd_shared_kernel_gate_f32(int LG, int K, int NW, int NG, int waves, int RPB);
+FwdKernel fwd_shared_kernel_gate_bf16(int LG, int K, int NW, int NG, int waves, int RPB, bool ua);
+
+template <typename T, bool SP, bool UA, bool CF = false, bool GATE = false>
 inline FwdKernel lookup_fwd_shared_kernel(int LG, int K, int NW, int NG, int waves, int RPB) {
 #define SCAN2D_X(lg, k, nw, ng, wv, rpb) \
-    if (LG == lg && K == k && NW == nw && NG == ng && waves == wv && RPB == rpb) return scan2d_fwd_shared_kernel<T, lg, k, nw, ng, wv, rpb, SP, UA, 0, CF>;
+    if (LG == lg && K == k && NW == nw && NG == ng && waves == wv && RPB == rpb) return scan2d_fwd_shared_kernel<T, lg, k, nw, ng, wv, rpb, SP, UA, 0, CF, false, GATE>;
     SCAN2D_FWD_SHARED_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
     return nullptr;
