@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void scan2d_block_conv_silu_kernel(const T* __
     T* out = x + (size_t)map * H * W + (size_t)i * W + j0;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-        if (j0 + e < W) store_elem(out + e, acc[e] / (1.0f + __expf(-acc[e])));
+        if (j0 + e < W) store_elem(out + e, acc[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-acc[e] * kLog2e)));
 }
 
 // Wide maps (W >= 32): one workgroup per tile of 32 rows x 64 columns.  The tile and its halo go to LDS as fp32 through
@@ -125,13 +125,18 @@ __global__ __launch_bounds__(256) void scan2d_block_conv_silu_tile_kernel(const 
     const int jq = tid % 16, j = j0 + 4 * jq;
     if (j >= W) return;
     const float b = wts[49];
+    constexpr int KHM = KHC > 0 ? KHC : 7, KWM = KWC > 0 ? KWC : 7;
+    float wreg[KHC > 0 ? KHC * KWC : 1];                  // the filter in registers when its size is known
+    if constexpr (KHC > 0) {
+#pragma unroll
+        for (int k = 0; k < KHC * KWC; ++k) wreg[k] = wts[k];
+    }
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int r = tid / 16 + 16 * half;               // output row inside the tile
         const int i = i0 + r;
         if (i >= H) continue;
         float acc[4] = {b, b, b, b};
-        constexpr int KHM = KHC > 0 ? KHC : 7, KWM = KWC > 0 ? KWC : 7;
 #pragma unroll
         for (int pp = 0; pp < KHM; ++pp) {
             if (pp < KH) {
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(256) void scan2d_block_conv_silu_tile_kernel(const 
 #pragma unroll
                 for (int q = 0; q < KWM; ++q) {
                     if (q < KW) {
-                        const float wv = wts[pp * KW + q];
+                        const float wv = KHC > 0 ? wreg[KHC > 0 ? pp * KWC + q : 0] : wts[pp * KW + q];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) acc[e] = fmaf(wv, win[e + q], acc[e]);
                     }
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(256) void scan2d_block_conv_silu_tile_kernel(const 
         }
         float o[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = acc[e] / (1.0f + __expf(-acc[e]));
+        for (int e = 0; e < 4; ++e) o[e] = acc[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-acc[e] * kLog2e));   // SiLU: v_exp, v_rcp
         T* out = x + (size_t)map * H * W + (size_t)i * W + j;
         if (vec_ok && j + 3 < W) {
             if constexpr (EB == 2) {

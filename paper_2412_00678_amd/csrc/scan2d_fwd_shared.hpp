@@ -186,7 +186,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                 sk_next[k] = dsk * xe;
                 if constexpr (GATE) {
                     const float zv = EB == 4 ? __uint_as_float(rawz[k]) : __uint_as_float(rawz[k] << 16);
-                    gt_next[k] = zv / (1.0f + __builtin_amdgcn_exp2f(-zv * kLog2e));                      // SiLU(z)
+                    gt_next[k] = zv * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-zv * kLog2e));  // SiLU(z)
                 }
             }
         }
