@@ -176,6 +176,7 @@ struct BwdPlan {
     size_t off_tail = 0;                                   // padded copies of the tensors' last rows (TailRows)
     size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, off_pb = 0, total = 0;   // pb: bias-gradient partials
     bool av = false;                                       // independent decay of the column recurrence
+    bool ck_chunked = false;                               // checkpoint rows in the lane order of the two shared-producer sweeps
     size_t off_pAv = 0;                                    // partial sums of dA_v over batch items
 };
 
@@ -318,7 +319,11 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
     const size_t maps = (size_t)d->Bt * d->Dc;
     const size_t NHW = (size_t)N * d->H * W;
     size_t o = 0;
-    pl.off_ck = o; o += align_up(maps * pl.nb * N * W * sizeof(float));
+    // the shared-producer forward kernel writes the checkpoints and the shared-producer main sweep reads them with the same
+    // lane tiling: rows of LG*K floats in lane order, so that both move whole 16-byte x LG pieces per instruction
+    pl.ck_chunked = pl.shared && pl.panels == 1 && pl.k.ckpt_fwd != nullptr && N == pl.k.cf_NG * pl.k.cf_NW && pl.k.cf_LG == LG &&
+                    pl.k.cf_K == K && K % 4 == 0;
+    pl.off_ck = o; o += align_up(maps * pl.nb * N * (pl.ck_chunked ? (size_t)LG * K : (size_t)W) * sizeof(float));
     pl.off_pB = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * NHW * sizeof(float)) : 0;
     pl.off_pC = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * NHW * sizeof(float)) : 0;
     pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
@@ -370,7 +375,7 @@ bool saving_plan(const scan2d_desc* d, BwdPlan* pl) {
 size_t bwd_saved_bytes(const scan2d_desc* d) {
     BwdPlan pl;
     if (!saving_plan(d, &pl)) return 0;
-    return align_up((size_t)d->Bt * d->Dc * pl.nb * d->N * d->W * sizeof(float));
+    return align_up((size_t)d->Bt * d->Dc * pl.nb * d->N * (pl.ck_chunked ? (size_t)pl.LG * pl.K : (size_t)d->W) * sizeof(float));
 }
 
 int fwd_saving_launch(const scan2d_desc* d, const void* x, const void* delta, const float* A, const void* Bm, const void* Cm,
@@ -381,7 +386,7 @@ int fwd_saving_launch(const scan2d_desc* d, const void* x, const void* delta, co
     FwdArgs f;
     f.x = x; f.delta = delta; f.A = A; f.Bm = Bm; f.Cm = Cm; f.Dskip = Dskip; f.mask = mask; f.y = y;
     f.delta_bias = nullptr; f.carry = nullptr;
-    f.ck = saved; f.nb = pl.nb;
+    f.ck = saved; f.nb = pl.nb; f.ck_chunked = pl.ck_chunked ? 1 : 0;
     f.maps = maps; f.Dc = d->Dc; f.H = d->H; f.W = d->W; f.N = d->N;
     const int slots = pl.k.cf_waves * 64 / pl.k.cf_LG;
     f.NG = pl.k.cf_NG; f.MPW = slots / pl.k.cf_NG; f.panels = 1; f.RPB = pl.k.cf_RPB;
@@ -450,6 +455,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.Bt = d->Bt; a.Dc = d->Dc; a.H = d->H; a.W = d->W; a.N = d->N;
     a.NG = pl.NG; a.GS = pl.GS; a.CG = pl.CG; a.nb = pl.nb;
     a.A_v = A_v;
+    a.ck_chunked = pl.ck_chunked ? 1 : 0;
     a.pAv = A_v == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pAv) : dA_v);
 
     const long long maps = (long long)d->Bt * d->Dc;
@@ -538,7 +544,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
             FwdArgs f;
             f.x = x; f.delta = delta; f.A = A; f.Bm = Bm; f.Cm = Cm; f.Dskip = nullptr; f.mask = mask; f.y = nullptr;
             f.delta_bias = delta_bias; f.carry = nullptr;
-            f.ck = a.ck; f.nb = pl.nb;
+            f.ck = a.ck; f.nb = pl.nb; f.ck_chunked = pl.ck_chunked ? 1 : 0;
             f.maps = maps; f.Dc = d->Dc; f.H = d->H; f.W = d->W; f.N = d->N;
             f.NG = pl.k.cf_NG; f.MPW = (pl.k.cf_waves * 64 / pl.k.cf_LG) / pl.k.cf_NG; f.panels = 1; f.RPB = pl.k.cf_RPB;
             const long long wgf = (maps + f.MPW - 1) / f.MPW;

@@ -294,7 +294,16 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
                         for (int j = 0; j < K; ++j) hcur[s][j] = 0.0f;
                     } else {
-                        load_f32s<K>(src + lcol, hcur[s]);               // past the row end: the next checkpoint row or the region behind
+                        if (p.ck_chunked) {
+                            const float* cs = p.ck + ((map * p.nb + band) * N + n0 + s) * PANEL + l * 4;
+#pragma unroll
+                            for (int j4 = 0; j4 < K / 4; ++j4) {
+                                const float4 v = *reinterpret_cast<const float4*>(cs + j4 * (LG * 4));
+                                hcur[s][4 * j4] = v.x; hcur[s][4 * j4 + 1] = v.y; hcur[s][4 * j4 + 2] = v.z; hcur[s][4 * j4 + 3] = v.w;
+                            }
+                        } else {
+                            load_f32s<K>(src + lcol, hcur[s]);           // past the row end: the next checkpoint row or the region behind
+                        }
                         if constexpr (!FAST) {
 #pragma unroll
                             for (int j = 0; j < K; ++j)

@@ -58,6 +58,9 @@ struct FwdArgs {
     const void* z = nullptr;     // GATE instantiations only: the block's gate branch, layout of x
     void* y_gated = nullptr;     // GATE instantiations only: y * SiLU(z); y itself may then be null (not stored)
     int nb = 0;          // bands of that sweep
+    // checkpoint rows of LG*K floats in the lane order of the tiling, [K/4][LG][4]: every store instruction of a lane group
+    // then writes 16 bytes x LG contiguously (the reader must have the same LG and K); 0: rows of W floats by column
+    int ck_chunked = 0;
     long long maps;      // Bt * Dc
     int Dc, H, W, N;
     int NG;              // lane groups per map = ceil(N / NW)

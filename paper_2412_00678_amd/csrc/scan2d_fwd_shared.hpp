@@ -335,6 +335,14 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                     const int band = (i + 1) / CK;
 #pragma unroll
                     for (int s = 0; s < NW; ++s) {
+                        if (p.ck_chunked) {                            // every lane of the group writes, also past the last column
+                            float* dst = p.ck + (((size_t)map * p.nb + band) * N + n0 + s) * PANEL + l * 4;
+#pragma unroll
+                            for (int j4 = 0; j4 < K / 4; ++j4)
+                                *reinterpret_cast<float4*>(dst + j4 * (LG * 4)) =
+                                    make_float4(h[s][4 * j4], h[s][4 * j4 + 1], h[s][4 * j4 + 2], h[s][4 * j4 + 3]);
+                            continue;
+                        }
                         float* dst = p.ck + (((size_t)map * p.nb + band) * N + n0 + s) * W + col0;
                         if (col0 + K <= W) {
                             uint32_t bits[K];
