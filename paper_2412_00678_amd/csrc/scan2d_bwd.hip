@@ -28,6 +28,28 @@ __global__ void scan2d_bwd_reduce_groups_kernel(const float* __restrict__ pB, co
     }
 }
 
+// The same sum for partials whose rows are LG*K floats in the lane order of the main sweep, [K/4][LG][4]: element q of a
+// row is column (q / 4 % LG) * K + (q / (4 * LG)) * 4 + q % 4.  rows = N * H.
+__global__ void scan2d_bwd_reduce_groups_chunked_kernel(const float* __restrict__ pB, const float* __restrict__ pC,
+                                                        float* __restrict__ dBm, float* __restrict__ dCm,
+                                                        int Bt, int CG, size_t rows, int W, int LG, int K) {
+    const size_t panel = (size_t)LG * K, per_item = rows * panel, total = (size_t)Bt * per_item;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t b = e / per_item, r = e - b * per_item;
+        const size_t row = r / panel;
+        const int q = (int)(r - row * panel);
+        const int col = (q / 4 % LG) * K + (q / (4 * LG)) * 4 + q % 4;
+        if (col >= W) continue;
+        const float* sB = pB + b * CG * per_item + r;
+        const float* sC = pC + b * CG * per_item + r;
+        float aB = 0.0f, aC = 0.0f;
+        for (int g = 0; g < CG; ++g) { aB += sB[(size_t)g * per_item]; aC += sC[(size_t)g * per_item]; }
+        const size_t o = (b * rows + row) * W + col;
+        dBm[o] = aB;
+        dCm[o] = aC;
+    }
+}
+
 // dA[c,n] = sum_b pA[b,c,n]; dDskip[c] = sum_b pD[b,c].
 __global__ void scan2d_bwd_reduce_batch_kernel(const float* __restrict__ pA, const float* __restrict__ pD,
                                                float* __restrict__ dA, float* __restrict__ dDskip,
@@ -177,6 +199,7 @@ struct BwdPlan {
     size_t off_ck = 0, off_pB = 0, off_pC = 0, off_pA = 0, off_pD = 0, off_pb = 0, total = 0;   // pb: bias-gradient partials
     bool av = false;                                       // independent decay of the column recurrence
     bool ck_chunked = false;                               // checkpoint rows in the lane order of the two shared-producer sweeps
+    bool part_chunked = false;                             // rows of the dBm / dCm partials in the lane order of the main sweep
     size_t off_pAv = 0;                                    // partial sums of dA_v over batch items
 };
 
@@ -317,15 +340,18 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
     pl.lds_bytes = (fixed + (size_t)gs * per) * sizeof(float);
     if (pl.lds_bytes > 160 * 1024) return false;
     const size_t maps = (size_t)d->Bt * d->Dc;
-    const size_t NHW = (size_t)N * d->H * W;
     size_t o = 0;
     // the shared-producer forward kernel writes the checkpoints and the shared-producer main sweep reads them with the same
     // lane tiling: rows of LG*K floats in lane order, so that both move whole 16-byte x LG pieces per instruction
-    pl.ck_chunked = pl.shared && pl.panels == 1 && pl.k.ckpt_fwd != nullptr && N == pl.k.cf_NG * pl.k.cf_NW && pl.k.cf_LG == LG &&
+    // (only where the padding of the rows to LG*K columns costs less than 7 %)
+    const bool tight = (size_t)LG * K * 15 <= (size_t)W * 16;
+    pl.ck_chunked = tight && pl.shared && pl.panels == 1 && pl.k.ckpt_fwd != nullptr && N == pl.k.cf_NG * pl.k.cf_NW && pl.k.cf_LG == LG &&
                     pl.k.cf_K == K && K % 4 == 0;
     pl.off_ck = o; o += align_up(maps * pl.nb * N * (pl.ck_chunked ? (size_t)LG * K : (size_t)W) * sizeof(float));
-    pl.off_pB = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * NHW * sizeof(float)) : 0;
-    pl.off_pC = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * NHW * sizeof(float)) : 0;
+    pl.part_chunked = tight && pl.shared && pl.panels == 1 && pl.CG > 1 && K % 4 == 0;
+    const size_t part_row = pl.part_chunked ? (size_t)LG * K : (size_t)W;
+    pl.off_pB = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * N * d->H * part_row * sizeof(float)) : 0;
+    pl.off_pC = o; o += pl.CG > 1 ? align_up((size_t)d->Bt * pl.CG * N * d->H * part_row * sizeof(float)) : 0;
     pl.off_pA = o; o += d->Bt > 1 ? align_up(maps * N * sizeof(float)) : 0;
     pl.off_pD = o; o += d->Bt > 1 ? align_up(maps * sizeof(float)) : 0;
     pl.off_pb = o; o += align_up(maps * sizeof(float));
@@ -456,6 +482,7 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.NG = pl.NG; a.GS = pl.GS; a.CG = pl.CG; a.nb = pl.nb;
     a.A_v = A_v;
     a.ck_chunked = pl.ck_chunked ? 1 : 0;
+    a.part_chunked = pl.part_chunked ? 1 : 0;
     a.pAv = A_v == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pAv) : dA_v);
 
     const long long maps = (long long)d->Bt * d->Dc;
@@ -556,7 +583,13 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
         }
         hipLaunchKernelGGL(pl.k.main, dim3((unsigned)wg2), dim3(pl.waves * 64), pl.lds_bytes, stream, a);
     }
-    if (pl.CG > 1) {
+    if (pl.CG > 1 && pl.part_chunked) {
+        const size_t rows = (size_t)d->N * d->H;
+        const size_t total = (size_t)d->Bt * rows * pl.LG * pl.K;
+        const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 16384);
+        hipLaunchKernelGGL(scan2d_bwd_reduce_groups_chunked_kernel, dim3(blocks), dim3(256), 0, stream,
+                           a.pB, a.pC, dBm, dCm, d->Bt, pl.CG, rows, d->W, pl.LG, pl.K);
+    } else if (pl.CG > 1) {
         const size_t NHW = (size_t)d->N * d->H * d->W;
         const size_t total = (size_t)d->Bt * NHW;
         const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 16384);

@@ -47,6 +47,8 @@ struct BwdArgs {
     void* dx; void* ddelta;
     float* ck;           // [maps][nb][N][W]   column state entering each band (band 0 unused)
     int ck_chunked = 0;  // shared-producer sweeps only: rows of LG*K floats in lane order [K/4][LG][4] (see FwdArgs)
+    int part_chunked = 0; // shared-producer main sweep, CG > 1: the rows of pB / pC in the same lane order (the reduction
+                         // kernel puts the columns back in place)
     float* pB; float* pC; // [Bt][CG][N][H][W] partial sums over the channels of one group
     const void* tail;    // padded copies of the rows behind which the tensors end (instantiations without FAST)
     float* pA;           // [Bt][Dc][N]

@@ -497,6 +497,17 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                 if (i < H) {
 #pragma unroll
                     for (int s = 0; s < NW; ++s) {
+                        if (p.part_chunked) {                          // every lane stores; the reduction drops the columns past W
+                            const size_t oc = ((((size_t)b * p.CG + cg) * N + n0 + s) * H + i) * PANEL + l * 4;
+#pragma unroll
+                            for (int j4 = 0; j4 < K / 4; ++j4) {
+                                *reinterpret_cast<float4*>(p.pB + oc + j4 * (LG * 4)) =
+                                    make_float4(dBacc[r][s][4 * j4], dBacc[r][s][4 * j4 + 1], dBacc[r][s][4 * j4 + 2], dBacc[r][s][4 * j4 + 3]);
+                                *reinterpret_cast<float4*>(p.pC + oc + j4 * (LG * 4)) =
+                                    make_float4(dCacc[r][s][4 * j4], dCacc[r][s][4 * j4 + 1], dCacc[r][s][4 * j4 + 2], dCacc[r][s][4 * j4 + 3]);
+                            }
+                            continue;
+                        }
                         const size_t o = ((((size_t)b * p.CG + cg) * N + n0 + s) * H + i) * W;
                         if (nv == K) {
                             store_f32s<K>(p.pB + o + col0, dBacc[r][s]);

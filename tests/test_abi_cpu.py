@@ -175,8 +175,10 @@ def test_backward_plans_cover_every_shape_the_forward_accepts(lib):
                         # ... + the carries between column panels (row-end states per border, a*q twice)
                         carries = (f["panels"] + 1) * (Bt * Dc * N * H * 4 + 256) if f["panels"] > 1 else 0
                         # (checkpoint rows of the shared-producer sweeps are padded to the lane grid LG * K)
-                        ck_max = Bt * Dc * f["bands"] * N * max(W, f["LG"] * f["K"]) * 4 if f["form"] == "banded-shared" else ck
-                        assert f["workspace"] <= ck_max + part + Bt * Dc * (N + 2) * 4 + tail + carries + 7 * 256, where
+                        wide = max(W, f["LG"] * f["K"]) if f["form"] == "banded-shared" else W
+                        ck_max = Bt * Dc * f["bands"] * N * wide * 4
+                        part_max = 2 * Bt * f["CG"] * N * H * wide * 4 if f["CG"] > 1 else 0
+                        assert f["workspace"] <= ck_max + part_max + Bt * Dc * (N + 2) * 4 + tail + carries + 7 * 256, where
 
 
 def test_benchmark_configurations_take_the_intended_forms(lib):
