@@ -121,7 +121,10 @@ def pair_weights(table):
     """Launches per reported step for a run of the training workload, which times scan2d_fwd + scan2d_bwd and then the
     training pair scan2d_fwd_saving + scan2d_bwd_saved (the reported step): the plain forward and the checkpoint sweep
     are not part of the pair, the kernels both backward calls share run once per step.  None for other runs."""
-    saving = [k for k in table if k.startswith("scan2d_fwd_shared_kernel") and k.endswith(", true>")]
+    def keepy(k):                                         # <T, LG, K, NW, NG, WAVES, RPB, SP, UA, CK, CF, KEEPY, GATE>
+        args = k[k.index("<") + 1:k.rindex(">")].split(", ")
+        return len(args) >= 12 and args[11] == "true"
+    saving = [k for k in table if k.startswith("scan2d_fwd_shared_kernel") and keepy(k)]
     if not saving:
         return None
     w = {}
