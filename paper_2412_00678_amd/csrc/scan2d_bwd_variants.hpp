@@ -37,7 +37,8 @@ struct BwdKernels {
 #define SCAN2D_BWD_SHARED_VARIANTS(X)                                                       \
     X(16, 4, 1, 16, 4, 4, 16, 4, 2, 16, 4, 2, 8, 4, 4) X(16, 8, 1, 16, 4, 4, 16, 8, 2, 16, 8, 2, 8, 4, 2)       \
     X(16, 12, 1, 16, 4, 4, 16, 12, 2, 16, 12, 2, 8, 4, 2) X(32, 6, 1, 16, 8, 2, 16, 12, 2, 16, 12, 2, 8, 4, 2)  \
-    X(32, 4, 1, 16, 8, 4, 16, 8, 2, 16, 8, 2, 8, 4, 2) X(64, 4, 1, 16, 16, 2, 64, 4, 1, 64, 4, 2, 8, 8, 4)
+    X(32, 4, 1, 16, 8, 4, 16, 8, 2, 16, 8, 2, 8, 4, 2) X(64, 4, 1, 16, 16, 2, 64, 4, 1, 64, 4, 2, 8, 8, 4) \
+    X(64, 4, 2, 8, 8, 2, 64, 4, 2, 64, 4, 2, 8, 8, 4)
 
 // W: the map width (the checkpoint sweep has its own columns per lane, hence its own row-end treatment)
 BwdKernels bwd_shared_kernels_f32(int LG, int K, int NW, int NG, int waves, int W, bool sp);

@@ -817,7 +817,8 @@ def test_columns_first_with_identity_cells_softplus_and_gate(s2d):
     assert rel_err(s2d.to_host(g[7]), f64(inp["dy"]) * y_scan * sg * (1.0 + z * (1.0 - sg))) <= 1e-4   # dz
 
 
-@pytest.mark.parametrize("shape", [(2, 12, 16, 40, 96, wl.F32), (1, 4, 16, 24, 256, wl.BF16)], ids=["40x96-f32", "24x256-bf16-large-lds"])
+@pytest.mark.parametrize("shape", [(2, 12, 16, 40, 96, wl.F32), (1, 4, 16, 24, 256, wl.BF16), (1, 16, 16, 24, 190, wl.F32)],
+                         ids=["40x96-f32", "24x256-bf16-large-lds-fwd", "24x190-f32-large-lds-bwd"])
 def test_forward_and_backward_replay_from_a_hip_graph(s2d, shape):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so its calls can be captured; every replay must equal the eager result bit for
@@ -829,9 +830,11 @@ def test_forward_and_backward_replay_from_a_hip_graph(s2d, shape):
     sets = [wl.make_inputs(w, seed=k) for k in (11, 12)]
     static = s2d.to_device(sets[0], dtype)
     desc = s2d.make_desc(static["x"], static["A"])
+    lds = lambda which: int(s2d.describe_plan(desc, which).split(" lds=")[1].split()[0])
     if W == 256:
-        lds = lambda which: int(s2d.describe_plan(desc, which).split(" lds=")[1].split()[0])
-        assert lds(s2d.PASS_FWD) > 65536 and lds(s2d.PASS_BWD) > 65536
+        assert lds(s2d.PASS_FWD) > 65536
+    if W == 190:
+        assert lds(s2d.PASS_BWD) > 65536
     y = torch.empty_like(static["x"])
     ws_f = torch.empty(max(16, s2d.workspace_bytes(desc, s2d.PASS_FWD)), dtype=torch.uint8, device="cuda:0")
     ws_b = torch.empty(max(16, s2d.workspace_bytes(desc, s2d.PASS_BWD)), dtype=torch.uint8, device="cuda:0")
