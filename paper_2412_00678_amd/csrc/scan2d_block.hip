@@ -652,6 +652,225 @@ __global__ __launch_bounds__(256) void scan2d_block_xproj_fast_kernel(const Xpro
     }
 }
 
+// More channels than one chunk (Dc up to 512, R <= 16, otherwise the conditions of the kernel above): one workgroup per
+// compute unit keeps all of Wx in LDS for its whole life (rows padded so that the 16 lanes of a k-group read different
+// banks with one wide load each) and the Wdt fragments in registers; x goes through LDS chunk by chunk, the next chunk
+// (or the next tile's first) in flight during the products.  The contraction runs over the channels of a 16-channel
+// group in the order (lane's k-group, step) instead of (step, k-group): the same permutation on both operands, so each
+// lane takes its four Wx values of a group with one 128-bit read (fp32 storage).
+constexpr int kWideBlocks = 32;                                               // 16-channel blocks: Dc <= 512
+template <typename T> struct XprojWide;
+template <> struct XprojWide<bf16_t> { static constexpr int kPitch = 68, kPad = 8; };
+template <> struct XprojWide<float>  { static constexpr int kPitch = 68, kPad = 4; };   // 4 rows apart = 64 B mod 256
+template <typename T, int KSTM>
+__global__ __launch_bounds__(256) void scan2d_block_xproj_wide_kernel(const XprojArgs p) {
+    constexpr int KC = XprojTile<T>::kChunk, PT = XprojWide<T>::kPitch;
+    constexpr int EB = Elem<T>::kBytes, NLD = KC * (kTile / 4) / 256, LP = kTile + 4, CB = KC / 16;   // CB: blocks per chunk
+    using Raw = std::conditional_t<EB == 2, uint16_t, uint32_t>;
+    using Vec = std::conditional_t<EB == 2, uint2, uint4>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int Dc = p.Dc, N = p.N, R = p.R, M = R + 2 * N;
+    constexpr int RW = 4 * KSTM + 1;
+    const int WP = Dc + XprojWide<T>::kPad;                                    // pitch of a Wx row in LDS
+    Raw* wxL = reinterpret_cast<Raw*>(smem);                                   // [48][WP]
+    Raw* xs = wxL + (size_t)48 * WP;                                           // [KC][PT]
+    float* low = reinterpret_cast<float*>(smem + ((size_t)48 * WP + (size_t)KC * PT) * EB);   // [48][LP]
+    const int tid = threadIdx.x;
+    const long long P = p.P;
+    const int l = tid & 63, wv = tid >> 6, g = l >> 4, n = l & 15;
+    const int ncol = wv * 16 + n;
+    const T* Wx = static_cast<const T*>(p.Wx);
+    const int n16 = Dc / 16, NC = (n16 + CB - 1) / CB;
+
+    // ---- once per workgroup: Wdt through the x region into fragment registers, Wx into LDS
+    float wfr[kWideBlocks][KSTM];
+    {
+        float* wdtL = reinterpret_cast<float*>(xs);                            // [Dc][RW], zero past R
+        const int nw = Dc * RW;
+        for (int base = 0; base < nw; base += 8 * 256) {
+            float wv8[8];
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int idx = min(base + it * 256 + tid, nw - 1);
+                const int c = idx / RW, r = idx - c * RW;
+                wv8[it] = p.Wdt[(size_t)c * R + min(r, R - 1)];
+                if (r >= R) wv8[it] = 0.0f;
+            }
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int idx = base + it * 256 + tid;
+                if (idx < nw) wdtL[idx] = wv8[it];
+            }
+        }
+        const int nvec = M * Dc / 4;
+        for (int base = 0; base < nvec; base += 8 * 256) {
+            Vec wv4[8];
+#pragma unroll
+            for (int it = 0; it < 8; ++it) wv4[it] = *reinterpret_cast<const Vec*>(Wx + 4 * (size_t)min(base + it * 256 + tid, nvec - 1));
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int e = 4 * (base + it * 256 + tid);
+                if (e < M * Dc) *reinterpret_cast<Vec*>(wxL + (size_t)(e / Dc) * WP + e % Dc) = wv4[it];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mbc = 0; mbc < kWideBlocks; ++mbc)
+#pragma unroll
+            for (int kk = 0; kk < KSTM; ++kk)
+                wfr[mbc][kk] = wdtL[(size_t)(min(mbc, n16 - 1) * 16 + n) * RW + 4 * kk + g];
+        __syncthreads();
+    }
+
+    const long long total_tiles = (long long)p.tiles * p.Bt;
+    const int cr0 = tid >> 4, q = tid & 15;
+    const size_t lane_off = (size_t)cr0 * P + 4 * q;
+    const size_t row_step = (size_t)16 * P;
+    Vec xv[NLD];
+    auto issue_x = [&](long long tile, int chunk) {       // rows past Dc: a valid row is read and zeros are kept
+        const T* src = static_cast<const T*>(p.x) + (size_t)(tile / p.tiles) * Dc * P + (size_t)(tile % p.tiles) * kTile + lane_off;
+        const int nb = n16 - chunk * CB;                   // blocks of this chunk (may exceed CB)
+#pragma unroll
+        for (int it = 0; it < NLD; ++it) {
+            const Vec t = *reinterpret_cast<const Vec*>(src + (size_t)(chunk * CB + min(it, nb - 1)) * row_step);
+            xv[it] = it < nb ? t : Vec{};
+        }
+    };
+    if (blockIdx.x < total_tiles) issue_x(blockIdx.x, 0);
+    Raw* const xs_mine = xs + (size_t)cr0 * PT + 4 * q;
+    const Raw* const xs_col = xs + (size_t)(4 * g) * PT + ncol;
+    float* const low_mine = low + (4 * g) * LP + ncol;
+    Raw* const stage_mine = xs + (size_t)(4 * g) * PT + ncol;
+    const Raw* wrow[3];
+#pragma unroll
+    for (int mb = 0; mb < 3; ++mb) wrow[mb] = wxL + (size_t)min(mb * 16 + n, M - 1) * WP + 4 * g;
+
+    for (long long tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+        const int b = (int)(tile / p.tiles);
+        const long long p0 = (tile % p.tiles) * kTile;
+        float4v acc[3];
+#pragma unroll
+        for (int mb = 0; mb < 3; ++mb) acc[mb] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+        // ---- low = Wx . x, chunk by chunk
+        for (int chunk = 0; chunk < NC; ++chunk) {
+#pragma unroll
+            for (int it = 0; it < NLD; ++it) *reinterpret_cast<Vec*>(xs_mine + (size_t)it * 16 * PT) = xv[it];
+            if (chunk + 1 < NC) issue_x(tile, chunk + 1);
+            else if (tile + gridDim.x < total_tiles) issue_x(tile + gridDim.x, 0);
+            __syncthreads();
+            const int nb = min(CB, n16 - chunk * CB);      // 16-channel groups of this chunk
+            if constexpr (EB == 2) {
+                uint2 a_cur[3], a_nxt[3];
+                uint16_t b_cur[4], b_nxt[4];
+                auto fetch = [&](int kg, uint2* a, uint16_t* bv) {
+#pragma unroll
+                    for (int mb = 0; mb < 3; ++mb) a[mb] = *reinterpret_cast<const uint2*>(wrow[mb] + chunk * KC + kg * 16);
+                    const Raw* col = xs_col + (size_t)kg * 16 * PT;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) bv[i] = col[i * PT];
+                };
+                fetch(0, a_cur, b_cur);
+                for (int kg = 0; kg < nb; ++kg) {
+                    fetch(min(kg + 1, nb - 1), a_nxt, b_nxt);
+                    short4v bf;
+                    bf.x = (short)b_cur[0]; bf.y = (short)b_cur[1]; bf.z = (short)b_cur[2]; bf.w = (short)b_cur[3];
+#pragma unroll
+                    for (int mb = 0; mb < 3; ++mb) {
+                        short4v af;
+                        af.x = (short)(a_cur[mb].x & 0xffffu); af.y = (short)(a_cur[mb].x >> 16);
+                        af.z = (short)(a_cur[mb].y & 0xffffu); af.w = (short)(a_cur[mb].y >> 16);
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(af, bf, acc[mb], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < 3; ++mb) a_cur[mb] = a_nxt[mb];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) b_cur[i] = b_nxt[i];
+                }
+            } else {
+                float4 a_cur[3], a_nxt[3];
+                float b_cur[4], b_nxt[4];
+                auto fetch = [&](int kg, float4* a, float* bv) {
+#pragma unroll
+                    for (int mb = 0; mb < 3; ++mb) a[mb] = *reinterpret_cast<const float4*>(wrow[mb] + chunk * KC + kg * 16);
+                    const Raw* col = xs_col + (size_t)kg * 16 * PT;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) bv[i] = __uint_as_float(col[i * PT]);
+                };
+                fetch(0, a_cur, b_cur);
+                for (int kg = 0; kg < nb; ++kg) {
+                    fetch(min(kg + 1, nb - 1), a_nxt, b_nxt);
+#pragma unroll
+                    for (int mb = 0; mb < 3; ++mb) {
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[mb].x, b_cur[0], acc[mb], 0, 0, 0);
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[mb].y, b_cur[1], acc[mb], 0, 0, 0);
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[mb].z, b_cur[2], acc[mb], 0, 0, 0);
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[mb].w, b_cur[3], acc[mb], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < 3; ++mb) a_cur[mb] = a_nxt[mb];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) b_cur[i] = b_nxt[i];
+                }
+            }
+            __syncthreads();                               // the next chunk overwrites the x region
+        }
+#pragma unroll
+        for (int mb = 0; mb < 3; ++mb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) low_mine[(mb * 16 + i) * LP] = acc[mb][i];
+        __syncthreads();
+        // ---- delta_raw = Wdt . low[:R], a chunk of channels at a time through the x region, whole rows out
+        float bfrag[KSTM];
+#pragma unroll
+        for (int kk = 0; kk < KSTM; ++kk) {
+            const float v = low[(4 * kk + g) * LP + ncol];
+            bfrag[kk] = 4 * kk + g < R ? v : 0.0f;
+        }
+        T* db = static_cast<T*>(p.delta_raw) + (size_t)b * Dc * P + p0 + lane_off;
+#pragma unroll
+        for (int mbc = 0; mbc < kWideBlocks; ++mbc) {
+            if (mbc < n16) {
+                float4v d4 = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int kk = 0; kk < KSTM; ++kk) d4 = __builtin_amdgcn_mfma_f32_16x16x4f32(wfr[mbc][kk], bfrag[kk], d4, 0, 0, 0);
+                Raw* st = stage_mine + (size_t)(mbc % CB) * 16 * PT;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (EB == 2) st[i * PT] = (Raw)(pack_bf16x2(d4[i], 0.0f) & 0xffffu);
+                    else st[i * PT] = __float_as_uint(d4[i]);
+                }
+            }
+            if ((mbc + 1) % CB == 0 && mbc + 1 - CB < n16) {       // a chunk of rows is staged (uniform)
+                const int first = mbc + 1 - CB;
+                const int nb = min(CB, n16 - first);
+                __syncthreads();
+                for (int it = 0; it < nb; ++it)
+                    *reinterpret_cast<Vec*>(db + (size_t)(first + it) * row_step) = *reinterpret_cast<const Vec*>(xs_mine + (size_t)it * 16 * PT);
+                __syncthreads();
+            }
+        }
+        for (int idx = tid; idx < 2 * N * (kTile / 4); idx += 256) {
+            const int row = idx >> 4, qq = idx & 15;
+            const float4 v = *reinterpret_cast<const float4*>(low + (R + row) * LP + 4 * qq);
+            T* dst = (row < N ? static_cast<T*>(p.Bm) + ((size_t)b * N + row) * P : static_cast<T*>(p.Cm) + ((size_t)b * N + row - N) * P) + p0 + 4 * qq;
+            if constexpr (EB == 2) {
+                uint2 o;
+                o.x = pack_bf16x2(v.x, v.y); o.y = pack_bf16x2(v.z, v.w);
+                *reinterpret_cast<uint2*>(dst) = o;
+            } else {
+                *reinterpret_cast<float4*>(dst) = v;
+            }
+        }
+        __syncthreads();                                   // `low` and the x region are rewritten by the next tile
+    }
+}
+
+template <typename T>
+size_t xproj_wide_lds_bytes(int Dc) {
+    return ((size_t)48 * (Dc + XprojWide<T>::kPad) + (size_t)XprojTile<T>::kChunk * XprojWide<T>::kPitch) * Elem<T>::kBytes +
+           (size_t)48 * (kTile + 4) * sizeof(float);
+}
+
 template <typename T, int KSTM>
 size_t xproj_fast_lds_bytes(int Dc) {
     return (size_t)XprojTile<T>::kChunk * XprojTile<T>::kPitch * Elem<T>::kBytes + (size_t)48 * (kTile + 4) * sizeof(float) +
@@ -728,6 +947,25 @@ int block_xproj_launch(const scan2d_desc* d, int R, const void* x, const void* W
             (void)hipGetLastError();
             if (lds > 65536 && !allow_large_lds(reinterpret_cast<const void*>(kernel), lds)) return SCAN2D_ERR_LAUNCH_FAILED;
             const long long grid = std::min<long long>((long long)a.tiles * d->Bt, 2 * 256);
+            hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, stream, a);
+            return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
+        }
+    }
+    {   // more channels than one chunk: see scan2d_block_xproj_wide_kernel
+        const long long P = (long long)d->H * d->W;
+        if (P % kTile == 0 && d->Dc % 16 == 0 && d->Dc <= 16 * kWideBlocks && R <= 16 && R + 2 * d->N <= 48 &&
+            (long long)d->Bt * (P / kTile) <= 2147483647LL) {
+            XprojArgs a;
+            a.x = x; a.Wx = Wx; a.Wdt = Wdt; a.delta_raw = delta_raw; a.Bm = Bm; a.Cm = Cm;
+            a.Dc = d->Dc; a.N = d->N; a.R = R; a.P = P; a.tiles = (int)(P / kTile); a.Bt = d->Bt; a.wdt_lds = 0;
+            using Kernel = void (*)(const XprojArgs);
+            Kernel kernel;
+            if (bf16) kernel = R <= 8 ? scan2d_block_xproj_wide_kernel<bf16_t, 2> : scan2d_block_xproj_wide_kernel<bf16_t, 4>;
+            else kernel = R <= 8 ? scan2d_block_xproj_wide_kernel<float, 2> : scan2d_block_xproj_wide_kernel<float, 4>;
+            const size_t lds = bf16 ? xproj_wide_lds_bytes<bf16_t>(d->Dc) : xproj_wide_lds_bytes<float>(d->Dc);
+            (void)hipGetLastError();
+            if (lds > 65536 && !allow_large_lds(reinterpret_cast<const void*>(kernel), lds)) return SCAN2D_ERR_LAUNCH_FAILED;
+            const long long grid = std::min<long long>((long long)a.tiles * d->Bt, 256);   // one workgroup per compute unit (LDS)
             hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, stream, a);
             return hipGetLastError() == hipSuccess ? SCAN2D_OK : SCAN2D_ERR_LAUNCH_FAILED;
         }

@@ -63,6 +63,10 @@ XPROJ_CASES = [
     # both storage types, every size class of the low-rank step, several tiles per workgroup
     (2, 128, 16, 8, 16, wl.F32, 8), (1, 256, 16, 16, 16, wl.BF16, 12), (1, 64, 8, 8, 8, wl.BF16, 20), (1, 16, 4, 8, 8, wl.F32, 3),
     (3, 192, 16, 56, 56, wl.BF16, 6), (1, 48, 16, 32, 1200, wl.BF16, 16), (1, 112, 12, 16, 20, wl.F32, 24),
+    # the kernel for more channels than one chunk (up to 512, low-rank step of at most 16 rows): whole chunks and a
+    # ragged last chunk, both storage types and both size classes of the low-rank step, several tiles per workgroup
+    (1, 512, 16, 16, 64, wl.F32, 16), (2, 144, 16, 8, 8, wl.F32, 5), (1, 384, 16, 24, 32, wl.BF16, 12), (1, 272, 8, 8, 16, wl.BF16, 3),
+    (1, 512, 16, 64, 300, wl.BF16, 16), (3, 320, 12, 8, 40, wl.F32, 9),
 ]
 
 
@@ -127,7 +131,7 @@ def test_conv_projections_and_gated_scan_chain_matches_the_oracle_chain(s2d, sha
     assert rel_err(got, wl.to_float(yr, dtype)) <= TOL_SCAN[dtype]
 
 
-@pytest.mark.parametrize("k", [2, 3], ids=["wsi-256x256-bf16", "vmamba-56x56-bf16"])
+@pytest.mark.parametrize("k", [2, 3, 4], ids=["wsi-256x256-bf16", "vmamba-56x56-bf16", "train-128x192-fp32"])
 def test_producers_at_full_size_on_sampled_outputs(s2d, k):
     """The launch configuration bench.py --block times.  The convolution is checked on whole sampled maps, the
     projections (independent per position) on sampled positions of every batch item, against the oracle."""
