@@ -1,4 +1,5 @@
-"""CPU oracle for the two producers in front of the scan inside a 2DMamba block (Sec. 3.2, Fig. 2).
+"""CPU oracle for the layers around the scan: the two producers in front of it inside a 2DMamba block (Sec. 3.2,
+Fig. 2) and the aggregator behind the last block (Supp. A "Aggregator", the two equations of the attention pooling).
 
 TEST INFRASTRUCTURE ONLY: plain numpy in double precision, nothing shared with the GPU library.
 
@@ -17,6 +18,11 @@ are learnable linear functions of x.  Readings taken here (both stated in the de
       low[b,m,i,j]  = sum_c Wx[m,c] * x[b,c,i,j]
       delta_raw[b,c,i,j] = sum_r Wdt[c,r] * low[b,r,i,j],   Bm = low[:, R:R+N],   Cm = low[:, R+N:R+2N]
   The low-rank step is not rounded between the two products; every output is rounded once to the storage type.
+* aggregator: the bag is the set of positions of a map that are not background (the paper pools "a bag of K
+  embeddings"; with no mask every position is a member).  With V [D][M] and w [D] (D = 128 in the paper):
+      s_k = sum_d w[d] * tanh(sum_m V[d,m] * h[m,k]),    a_k = exp(s_k) / sum_{j in bag} exp(s_j),    z = sum_k a_k h_k.
+  Positions outside the bag get a = 0; an empty bag gives a = 0 and z = 0.  The outputs stay in double precision
+  (the library returns fp32).
 """
 from __future__ import annotations
 
@@ -56,3 +62,28 @@ def xproj(x, Wx, Wdt, N, dtype=F32):
     low = np.einsum("mc,bchw->bmhw", Wxw, xw)
     delta_raw = np.einsum("cr,brhw->bchw", Wdt, low[:, :R])
     return _narrow(delta_raw, dtype), _narrow(low[:, R:R + N], dtype), _narrow(low[:, R + N:], dtype)
+
+
+def attn_pool(h, V, w, mask=None, dtype=F32):
+    """Attention pooling over the positions of each batch item (Supp. A, the weighted sum and its attention weights).
+    h: [Bt][M][H][W] and V: [D][M] in the storage type; w: [D] fp32; mask: [Bt][H][W] uint8 (non-zero = not in the
+    bag) or None.  Returns (z [Bt][M], a [Bt][H][W]) as float64."""
+    hw = _widen(h, dtype)
+    Vw = _widen(V, dtype)
+    w = np.asarray(w, np.float64)
+    Bt, M, H, W = hw.shape
+    if Vw.shape != (w.shape[0], M):
+        raise ValueError("V must be [D][M] and w [D]")
+    z = np.zeros((Bt, M))
+    a = np.zeros((Bt, H, W))
+    for b in range(Bt):
+        bag = hw[b].reshape(M, H * W)                        # column k = embedding h_k
+        member = np.ones(H * W, bool) if mask is None else (np.asarray(mask[b]).reshape(-1) == 0)
+        if not member.any():
+            continue
+        s = w @ np.tanh(Vw @ bag)                            # [H*W]
+        e = np.where(member, np.exp(s - s[member].max()), 0.0)
+        ab = e / e.sum()
+        a[b] = ab.reshape(H, W)
+        z[b] = bag @ ab
+    return z, a

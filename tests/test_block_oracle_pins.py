@@ -163,3 +163,136 @@ def test_xproj_low_precision_runs_on_the_stored_values_and_rounds_once():
         assert np.all(np.abs(wl.to_float(got, wl.BF16) - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-40)
     with pytest.raises(ValueError):
         block.xproj(xb, Wb[:-1], Wdt, N, dtype=oracle.BF16)
+
+
+# ------------------------------------------------------------------------------------------------ aggregator
+def _pool_by_loops(h, V, w, member):
+    """The two equations of the attention pooling with scalar loops (Supp. A): plain exponentials, no shift."""
+    M, K = len(h), len(h[0])
+    D = len(w)
+    s = []
+    for k in range(K):
+        acc = 0.0
+        for d in range(D):
+            pre = 0.0
+            for m in range(M):
+                pre += V[d][m] * h[m][k]
+            acc += w[d] * math.tanh(pre)
+        s.append(acc)
+    den = sum(math.exp(s[k]) for k in range(K) if member[k])
+    a = [math.exp(s[k]) / den if member[k] else 0.0 for k in range(K)]
+    z = [sum(a[k] * h[m][k] for k in range(K)) for m in range(M)]
+    return z, a
+
+
+def test_attn_pool_matches_loops_over_the_two_equations():
+    rng = np.random.default_rng(11)
+    Bt, M, H, W, D = 2, 5, 3, 4, 6
+    h = rng.standard_normal((Bt, M, H, W))
+    V = rng.standard_normal((D, M))
+    w = rng.standard_normal(D).astype(np.float32)
+    mask = (rng.random((Bt, H, W)) < 0.3).astype(np.uint8)
+    for mk in (None, mask):
+        z, a = block.attn_pool(h, V, w, mk, dtype=F64)
+        assert z.shape == (Bt, M) and a.shape == (Bt, H, W)
+        for b in range(Bt):
+            member = [True] * (H * W) if mk is None else [bool(v == 0) for v in mk[b].reshape(-1)]
+            zr, ar = _pool_by_loops(h[b].reshape(M, -1).tolist(), V.tolist(), [float(v) for v in w], member)
+            np.testing.assert_allclose(a[b].reshape(-1), ar, rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(z[b], zr, rtol=1e-12, atol=1e-14)
+
+
+def test_attn_pool_closed_forms():
+    rng = np.random.default_rng(12)
+    M, H, W, D = 4, 5, 6, 8
+    h = rng.standard_normal((1, M, H, W))
+    V = rng.standard_normal((D, M))
+    # w = 0: every score is 0, the attention is uniform and z is the mean embedding of the bag
+    z, a = block.attn_pool(h, V, np.zeros(D, np.float32), None, dtype=F64)
+    np.testing.assert_allclose(a, 1.0 / (H * W), rtol=1e-15)
+    np.testing.assert_allclose(z[0], h[0].reshape(M, -1).mean(axis=1), rtol=1e-13, atol=1e-15)
+    mask = np.zeros((1, H, W), np.uint8)
+    mask[0, :2] = 1
+    z, a = block.attn_pool(h, V, np.zeros(D, np.float32), mask, dtype=F64)
+    assert not a[0, :2].any()
+    np.testing.assert_allclose(a[0, 2:], 1.0 / ((H - 2) * W), rtol=1e-15)
+    np.testing.assert_allclose(z[0], h[0, :, 2:].reshape(M, -1).mean(axis=1), rtol=1e-13, atol=1e-15)
+    # a bag of one embedding returns it; an empty bag returns zeros
+    one = np.ones((1, H, W), np.uint8)
+    one[0, 3, 4] = 0
+    w = rng.standard_normal(D).astype(np.float32)
+    z, a = block.attn_pool(h, V, w, one, dtype=F64)
+    assert a[0, 3, 4] == 1.0 and a.sum() == 1.0
+    np.testing.assert_array_equal(z[0], h[0, :, 3, 4])
+    z, a = block.attn_pool(h, V, w, np.ones((1, H, W), np.uint8), dtype=F64)
+    assert not z.any() and not a.any()
+    # two embeddings, one hidden unit: a_1 / a_2 = exp(w (tanh(v.h_1) - tanh(v.h_2)))
+    h2 = np.array([[0.3, -1.2], [0.7, 0.4]]).reshape(1, 2, 1, 2)
+    v = np.array([[1.5, -0.5]])
+    z, a = block.attn_pool(h2, v, np.array([2.0], np.float32), None, dtype=F64)
+    t1, t2 = math.tanh(1.5 * 0.3 - 0.5 * 0.7), math.tanh(1.5 * -1.2 - 0.5 * 0.4)
+    assert a[0, 0, 0] / a[0, 0, 1] == pytest.approx(math.exp(2.0 * (t1 - t2)), rel=1e-13)
+    assert a[0, 0, 0] == pytest.approx(1.0 / (1.0 + math.exp(2.0 * (t2 - t1))), rel=1e-13)
+    np.testing.assert_allclose(z[0], a[0, 0, 0] * h2[0, :, 0, 0] + a[0, 0, 1] * h2[0, :, 0, 1], rtol=1e-14)
+
+
+def test_attn_pool_invariants():
+    rng = np.random.default_rng(13)
+    Bt, M, H, W, D = 3, 6, 4, 7, 5
+    h = rng.standard_normal((Bt, M, H, W))
+    V = rng.standard_normal((D, M))
+    w = rng.standard_normal(D).astype(np.float32)
+    mask = (rng.random((Bt, H, W)) < 0.4).astype(np.uint8)
+    z, a = block.attn_pool(h, V, w, mask, dtype=F64)
+    assert (a >= 0).all() and not a[mask != 0].any()
+    np.testing.assert_allclose(a.reshape(Bt, -1).sum(axis=1), 1.0, rtol=1e-14)
+    # z lies in the convex hull of the bag: inside the per-channel range of its members
+    for b in range(Bt):
+        mem = h[b][:, mask[b] == 0]
+        assert (z[b] >= mem.min(axis=1) - 1e-12).all() and (z[b] <= mem.max(axis=1) + 1e-12).all()
+    # what lies under the mask is never read into the result
+    h2 = h.copy()
+    h2[np.broadcast_to(mask[:, None] != 0, h.shape)] = 1e30
+    z2, a2 = block.attn_pool(h2, V, w, mask, dtype=F64)
+    np.testing.assert_array_equal(a2, a)
+    np.testing.assert_allclose(z2, z, rtol=1e-13, atol=1e-13)
+    # the order of the positions does not matter: a permutation of the bag permutes a and leaves z
+    perm = rng.permutation(H * W)
+    hp = h.reshape(Bt, M, -1)[:, :, perm].reshape(h.shape)
+    mp = mask.reshape(Bt, -1)[:, perm].reshape(mask.shape)
+    zp, ap = block.attn_pool(hp, V, w, mp, dtype=F64)
+    np.testing.assert_allclose(ap.reshape(Bt, -1), a.reshape(Bt, -1)[:, perm], rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(zp, z, rtol=1e-12, atol=1e-14)
+    # batch items are independent; the sign of a hidden unit and of its weight cancel (tanh is odd)
+    z1, a1 = block.attn_pool(h[1:2], V, w, mask[1:2], dtype=F64)
+    np.testing.assert_array_equal(z1[0], z[1])
+    Vs, ws = V.copy(), w.copy()
+    Vs[2] *= -1.0
+    ws[2] *= -1.0
+    z3, a3 = block.attn_pool(h, Vs, ws, mask, dtype=F64)
+    np.testing.assert_allclose(a3, a, rtol=1e-12, atol=1e-16)
+    # scores far above the others: the pooling returns that embedding (saturated tanh, weight 60 per unit)
+    hs = np.zeros((1, 2, 1, 3))
+    hs[0, :, 0, 1] = (5.0, -2.0)
+    z4, a4 = block.attn_pool(hs, np.array([[4.0, 0.0]]), np.array([60.0], np.float32), None, dtype=F64)
+    assert a4[0, 0, 1] == pytest.approx(1.0, abs=1e-25) and z4[0] == pytest.approx([5.0, -2.0], abs=1e-24)
+    # large scores do not overflow (the shift by the largest score): 1000 * tanh(.) would overflow exp
+    z5, a5 = block.attn_pool(h[:1], V, (w * 1000.0).astype(np.float32), None, dtype=F64)
+    assert np.isfinite(z5).all() and a5.sum() == pytest.approx(1.0, rel=1e-14)
+
+
+def test_attn_pool_reads_stored_bits_of_both_storage_types():
+    rng = np.random.default_rng(14)
+    h = rng.standard_normal((1, 8, 3, 5)).astype(np.float32)
+    V = (rng.standard_normal((4, 8)) / 3).astype(np.float32)
+    w = rng.standard_normal(4).astype(np.float32)
+    hb, Vb = wl.f32_to_bf16_bits(h), wl.f32_to_bf16_bits(V)
+    zb, ab = block.attn_pool(hb, Vb, w, None, dtype=oracle.BF16)
+    zw, aw = block.attn_pool(wl.to_float(hb, wl.BF16), wl.to_float(Vb, wl.BF16), w, None, dtype=F64)
+    np.testing.assert_array_equal(zb, zw)
+    np.testing.assert_array_equal(ab, aw)
+    zf, af = block.attn_pool(h, V, w, None, dtype=oracle.F32)
+    zd, ad = block.attn_pool(h.astype(np.float64), V.astype(np.float64), w, None, dtype=F64)
+    np.testing.assert_array_equal(zf, zd)
+    with pytest.raises(ValueError):
+        block.attn_pool(h, V[:, :7], w, None, dtype=oracle.F32)
