@@ -81,9 +81,10 @@ def attn_pool(h, V, w, mask=None, dtype=F32):
         member = np.ones(H * W, bool) if mask is None else (np.asarray(mask[b]).reshape(-1) == 0)
         if not member.any():
             continue
-        s = w @ np.tanh(Vw @ bag)                            # [H*W]
-        e = np.where(member, np.exp(s - s[member].max()), 0.0)
-        ab = e / e.sum()
-        a[b] = ab.reshape(H, W)
-        z[b] = bag @ ab
+        members = bag[:, member]                             # what lies outside the bag is never read
+        s = w @ np.tanh(Vw @ members)
+        e = np.exp(s - s.max())
+        am = e / e.sum()
+        a[b].reshape(-1)[member] = am
+        z[b] = members @ am
     return z, a
