@@ -286,6 +286,28 @@ def bench_block(s2d, w, steps, warmup):
     out["xproj_tflops"] = proj_flops / (out["xproj_ms"] * 1e-3) / 1e12
     del sets
     torch.cuda.empty_cache()
+    # the aggregator behind the last block: embeddings of the block's model width (half the inner width), 128 hidden units
+    M, D = max(1, w.Dc // 2), 128
+    wp = wl.Workload("pool", w.Bt, M, 1, w.H, w.W, w.dtype, mask_frac=w.mask_frac)
+    pin = wl.make_pool_inputs(wp, D=D, seed=0)
+    pool_bytes = 2 * w.Bt * M * w.H * w.W * eb + 3 * w.Bt * w.H * w.W * 4 + D * M * eb   # h twice, the scores / weights three times
+    psets = []
+    for _ in range(int(min(8, max(2, np.ceil(0.6e9 / pool_bytes))))):
+        d = s2d.to_device(pin, w.dtype)
+        d["out"] = (torch.empty((w.Bt, M), dtype=torch.float32, device="cuda:0"), torch.empty((w.Bt, w.H, w.W), dtype=torch.float32, device="cuda:0"))
+        psets.append(d)
+
+    def pool(s):
+        s2d.block_attn_pool(s["h"], s["V"], s["w"], s["mask"], out=s["out"])
+
+    t, _ = time_launches(pool, psets, steps, warmup)
+    gbs = pool_bytes / (float(t) * 1e-3) / 1e9
+    out["attn_pool_ms"] = float(t)
+    out["attn_pool_shape"] = {"M": M, "D": D}
+    out["attn_pool_roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                                 "algorithmic_bytes": pool_bytes}
+    del psets
+    torch.cuda.empty_cache()
     return out
 
 

@@ -300,6 +300,20 @@ int scan2d_block_xproj(const scan2d_desc* desc, int R,
                        void* delta_raw, void* Bm, void* Cm, void* stream);
 
 /*
+ * The aggregator behind the last block (Supp. A "Aggregator": attention pooling with two linear layers, the weighted
+ * sum and the attention weights): per batch item, over the positions k of the map that are in the bag,
+ *     s_k = sum_{d<D} w[d] * tanh(sum_{m<M} V[d,m] * h[b,m,k]),   a_k = exp(s_k) / sum_j exp(s_j),   z[b,m] = sum_k a_k h[b,m,k]
+ *   h : [Bt][M][H][W] with M = desc.Dc, V : [D][M], both storage type;  w : [D] fp32 (D = 128 in the paper);
+ *   mask : [Bt][H][W] bytes or NULL, non-zero = the position is not in the bag (its h is never read into a or z);
+ *   attn : [Bt][H][W] fp32 (written: a, 0 outside the bag);  z : [Bt][M] fp32 (written).  An empty bag gives a = 0, z = 0.
+ *   V . h runs on the matrix cores (bf16 or fp32 inputs as stored, fp32 accumulation); all sums have a fixed order.
+ *   1 <= D <= 128 and Bt <= 65535 (else SCAN2D_ERR_BAD_SHAPE); any M.  desc.N and desc.flags are not used.
+ *   Device pointers, 16-byte aligned; asynchronous on `stream`; no workspace (attn holds the scores in between).
+ */
+int scan2d_block_attn_pool(const scan2d_desc* desc, int D, const void* h, const void* V, const float* w,
+                           const uint8_t* mask, float* attn, float* z, void* stream);
+
+/*
  * scan2d_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving or
  * training loops, harnesses that forbid hipMalloc): the same computation and the same kernels as scan2d_bwd,
  * every argument as there, but no workspace argument.  The band checkpoints and partial sums go to a scratch

@@ -986,6 +986,18 @@ extern "C" int scan2d_block_xproj(const scan2d_desc* desc, int R, const void* x,
     return block_xproj_launch(desc, R, x, Wx, Wdt, delta_raw, Bm, Cm, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int scan2d_block_attn_pool(const scan2d_desc* desc, int D, const void* h, const void* V, const float* w,
+                                      const uint8_t* mask, float* attn, float* z, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!h || !V || !w || !attn || !z) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(h) || !aligned16(V) || !aligned16(w) || !aligned16(attn) || !aligned16(z) || (mask && !aligned16(mask)))
+        return SCAN2D_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    return block_attn_pool_launch(desc, D, h, V, w, mask, attn, z, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int scan2d_debug_force_variant(int kind, const int* values, int n) {
     if (kind < 0 || kind >= kTuneKinds) return SCAN2D_ERR_BAD_FLAGS;
     if (n > 0 && values == nullptr) return SCAN2D_ERR_NULL_POINTER;

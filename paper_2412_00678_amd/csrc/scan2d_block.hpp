@@ -1,4 +1,5 @@
-// Producers of the scan's inputs inside a 2DMamba block (Sec. 3.2, Fig. 2): host-side entries used by the C ABI.
+// Layers around the scan (producers of its inputs inside a 2DMamba block, Sec. 3.2, Fig. 2; the aggregator behind the
+// last block, Supp. A): host-side entries used by the C ABI.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -14,5 +15,9 @@ int block_conv_silu_launch(const scan2d_desc* d, const scan2d_conv_shape* cs, co
 // Step, B and C projections; SCAN2D_ERR_BAD_SHAPE when R, Dc or R + 2N are outside the documented range.
 int block_xproj_launch(const scan2d_desc* d, int R, const void* x, const void* Wx, const float* Wdt, void* delta_raw, void* Bm,
                        void* Cm, hipStream_t stream);
+
+// Attention pooling of the aggregator (scan2d_pool.hip); SCAN2D_ERR_BAD_SHAPE when D is outside 1..128 or Bt above 65535.
+int block_attn_pool_launch(const scan2d_desc* d, int D, const void* h, const void* V, const float* w, const uint8_t* mask,
+                           float* attn, float* z, hipStream_t stream);
 
 }  // namespace scan2d

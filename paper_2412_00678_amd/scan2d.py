@@ -21,7 +21,8 @@ PASS_FWD, PASS_BWD, PASS_BWD_GATED, PASS_BWD_SOFTPLUS, PASS_FWD_VARIANTS, PASS_B
 EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "scan2d_bwd", "scan2d_bwd_softplus",
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
            "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants",
-           "scan2d_block_conv_silu", "scan2d_block_xproj", "scan2d_saved_bytes", "scan2d_fwd_saving", "scan2d_bwd_saved")
+           "scan2d_block_conv_silu", "scan2d_block_xproj", "scan2d_saved_bytes", "scan2d_fwd_saving", "scan2d_bwd_saved",
+           "scan2d_block_attn_pool")
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ERR_SCRATCH_LIMIT = -9
 TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
@@ -76,6 +77,8 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_block_conv_silu.restype = ctypes.c_int
     lib.scan2d_block_xproj.argtypes = [ctypes.POINTER(Desc), ctypes.c_int] + [vp] * 7
     lib.scan2d_block_xproj.restype = ctypes.c_int
+    lib.scan2d_block_attn_pool.argtypes = [ctypes.POINTER(Desc), ctypes.c_int] + [vp] * 7
+    lib.scan2d_block_attn_pool.restype = ctypes.c_int
     lib.scan2d_saved_bytes.argtypes = [ctypes.POINTER(Desc)]
     lib.scan2d_saved_bytes.restype = ctypes.c_size_t
     lib.scan2d_fwd_saving.argtypes = [ctypes.POINTER(Desc)] + [vp] * 8 + [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
@@ -567,6 +570,29 @@ def block_xproj(x, Wx, Wdt, N, out=None):
     rc = lib.scan2d_block_xproj(ctypes.byref(desc), R, _ptr(x), _ptr(Wx), _ptr(Wdt), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream_ptr())
     if rc != 0:
         raise Scan2dError(rc, "scan2d_block_xproj")
+    return out
+
+
+def block_attn_pool(h, V, w, mask=None, out=None):
+    """(z [Bt][M] fp32, attn [Bt][H][W] fp32) from h [Bt][M][H][W], V [D][M] (type of h), w [D] fp32 and an optional
+    mask [Bt][H][W] uint8 (non-zero = not in the bag)."""
+    Bt, M, H, W = h.shape
+    D = int(w.shape[0])
+    desc = Desc(Bt, M, H, W, 1, _dtype_code(h), 0)
+    _check(h, "h", h.dtype, (Bt, M, H, W))
+    _check(V, "V", h.dtype, (D, M))
+    _check(w, "w", torch.float32, (D,))
+    if mask is not None:
+        _check(mask, "mask", torch.uint8, (Bt, H, W))
+    if out is None:
+        out = (torch.empty((Bt, M), dtype=torch.float32, device=h.device), torch.empty((Bt, H, W), dtype=torch.float32, device=h.device))
+    else:
+        _check(out[0], "z", torch.float32, (Bt, M))
+        _check(out[1], "attn", torch.float32, (Bt, H, W))
+    rc = lib.scan2d_block_attn_pool(ctypes.byref(desc), D, _ptr(h), _ptr(V), _ptr(w), _ptr(mask) if mask is not None else None,
+                                    _ptr(out[1]), _ptr(out[0]), _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_block_attn_pool")
     return out
 
 

@@ -188,3 +188,22 @@ def make_block_inputs(wl: Workload, R: int, KH: int = 3, KW: int = 3, seed: int 
     Dskip = rng.standard_normal((Dc,)).astype(np.float32)
     mask = blob_mask(rng.standard_normal((Bt, H, W)), wl.mask_frac) if wl.mask_frac > 0 else None
     return {"u": u, "w": w, "bias": bias, "Wx": Wx, "Wdt": Wdt, "delta_bias": delta_bias, "z": z, "A": A, "Dskip": Dskip, "mask": mask}
+
+
+def make_pool_inputs(wl: Workload, D: int = 128, seed: int = 0) -> Dict[str, Optional[np.ndarray]]:
+    """Tensors of the aggregator for a workload's shape (the paper trains V and w; here they are drawn): embeddings
+    h ~ N(0,1) [Bt][Dc][H][W] in the storage type, V ~ N(0,1)/sqrt(Dc) [D][Dc] in the storage type (hidden units of
+    unit variance before the tanh), w ~ N(0,1) [D] fp32 (scores with a spread of a few units, so the attention is
+    neither uniform nor one-hot), and the workload's mask.  Draw order: h, V, w, mask noise."""
+    rng = np.random.default_rng(seed)
+    Bt, Dc, H, W = wl.Bt, wl.Dc, wl.H, wl.W
+
+    def cast(a64: np.ndarray) -> np.ndarray:
+        a32 = a64.astype(np.float32)
+        return f32_to_bf16_bits(a32) if wl.dtype == BF16 else a32
+
+    h = cast(rng.standard_normal((Bt, Dc, H, W)))
+    V = cast(rng.standard_normal((D, Dc)) / np.sqrt(Dc))
+    w = rng.standard_normal((D,)).astype(np.float32)
+    mask = blob_mask(rng.standard_normal((Bt, H, W)), wl.mask_frac) if wl.mask_frac > 0 else None
+    return {"h": h, "V": V, "w": w, "mask": mask}

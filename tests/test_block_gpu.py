@@ -160,3 +160,98 @@ def test_producers_at_full_size_on_sampled_outputs(s2d, k):
         for name, got, ref in zip(("delta_raw", "Bm", "Cm"), (dh, Bh, Ch), refs):
             e = rel_err(wl.to_float(got[b][:, pos], w.dtype), wl.to_float(ref[0, :, 0, :], w.dtype))
             assert e <= TOL_BLOCK[w.dtype], f"{name} of batch item {b}: rel err {e:.3e}"
+
+
+# ------------------------------------------------------------------------------------------------ aggregator
+# fp32 sums and a tanh / exp of about 1e-6 relative accuracy against double precision: the attention weights carry
+# the absolute error of the scores (a few 1e-6 for scores of a few units) as a relative one
+TOL_POOL = 2e-5
+
+POOL_CASES = [
+    # Bt, M, H, W, dtype, D, mask_frac
+    (1, 128, 16, 16, wl.BF16, 128, 0.0), (2, 64, 9, 21, wl.F32, 128, 0.3), (1, 37, 5, 7, wl.BF16, 50, 0.4), (3, 5, 1, 1, wl.F32, 1, 0.0),
+    (1, 300, 8, 24, wl.BF16, 128, 0.5), (2, 200, 7, 19, wl.F32, 96, 0.2), (1, 128, 3, 70, wl.F32, 128, 0.0), (1, 16, 64, 65, wl.BF16, 17, 0.3),
+    (2, 256, 40, 40, wl.BF16, 128, 0.5),
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "x".join(map(str, c[:4])) + ("bf16" if c[4] else "f32") + f"-D{c[5]}-m{c[6]}")
+def test_attn_pool_matches_oracle(s2d, case):
+    import torch
+    Bt, M, H, W, dtype, D, mf = case
+    w_ = wl.Workload("pool", Bt, M, 1, H, W, dtype, mask_frac=mf)
+    inp = wl.make_pool_inputs(w_, D=D, seed=44)
+    print(f"attn_pool case {case}", flush=True)
+    d = s2d.to_device(inp, dtype)
+    z, attn = s2d.block_attn_pool(d["h"], d["V"], d["w"], d["mask"])
+    torch.cuda.synchronize()
+    zr, ar = block.attn_pool(inp["h"], inp["V"], inp["w"], inp["mask"], dtype=dtype)
+    zg, ag = s2d.to_host(z).astype(np.float64), s2d.to_host(attn).astype(np.float64)
+    assert np.isfinite(zg).all() and np.isfinite(ag).all()
+    assert rel_err(ag, ar) <= TOL_POOL and rel_err(zg, zr) <= TOL_POOL
+    if inp["mask"] is not None:
+        assert not ag[inp["mask"] != 0].any()                               # exactly zero outside the bag
+    np.testing.assert_allclose(ag.reshape(Bt, -1).sum(axis=1), 1.0, rtol=1e-5)
+
+
+def test_attn_pool_edge_cases(s2d):
+    import torch
+    rng = np.random.default_rng(45)
+    Bt, M, H, W, D = 2, 24, 6, 10, 128
+    w_ = wl.Workload("pool", Bt, M, 1, H, W, wl.F32, mask_frac=0.3)
+    inp = wl.make_pool_inputs(w_, D=D, seed=46)
+    # what lies under the mask is never read into the result: NaN there changes nothing
+    hp = inp["h"].copy()
+    hp[np.broadcast_to(inp["mask"][:, None] != 0, hp.shape)] = np.nan
+    d = s2d.to_device(inp, wl.F32)
+    z0, a0 = s2d.block_attn_pool(d["h"], d["V"], d["w"], d["mask"])
+    z1, a1 = s2d.block_attn_pool(torch.from_numpy(hp).cuda(), d["V"], d["w"], d["mask"])
+    torch.cuda.synchronize()
+    assert torch.equal(z0, z1) and torch.equal(a0, a1)
+    # an empty bag (batch item 1) gives zeros, the other item is unchanged; a bag of one returns that embedding
+    m2 = inp["mask"].copy()
+    m2[1] = 1
+    z2, a2 = s2d.block_attn_pool(d["h"], d["V"], d["w"], torch.from_numpy(m2).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(z2[0], z0[0]) and not z2[1].any() and not a2[1].any()
+    m3 = np.ones_like(m2)
+    m3[0, 2, 3] = 0
+    m3[1, 5, 9] = 0
+    z3, a3 = s2d.block_attn_pool(d["h"], d["V"], d["w"], torch.from_numpy(m3).cuda())
+    torch.cuda.synchronize()
+    assert a3[0, 2, 3] == 1.0 and a3[1, 5, 9] == 1.0 and float(a3.sum()) == 2.0
+    assert np.array_equal(s2d.to_host(z3)[0], inp["h"][0, :, 2, 3]) and np.array_equal(s2d.to_host(z3)[1], inp["h"][1, :, 5, 9])
+    # w = 0: uniform attention over the bag, z = mean embedding
+    z4, a4 = s2d.block_attn_pool(d["h"], d["V"], torch.zeros(D, device="cuda"), d["mask"])
+    torch.cuda.synchronize()
+    for b in range(Bt):
+        mem = inp["mask"][b] == 0
+        np.testing.assert_allclose(s2d.to_host(a4)[b][mem], 1.0 / mem.sum(), rtol=1e-6)
+        np.testing.assert_allclose(s2d.to_host(z4)[b], inp["h"][b][:, mem].astype(np.float64).mean(axis=1), rtol=1e-4, atol=1e-6)
+    # scores of +-1000 (saturated tanh times large w) neither overflow nor lose the normalisation
+    z5, a5 = s2d.block_attn_pool(d["h"], d["V"], d["w"] * 100.0, d["mask"])
+    torch.cuda.synchronize()
+    assert torch.isfinite(z5).all() and abs(float(a5[0].sum()) - 1.0) < 1e-5
+    # two calls give the same bits; more than 128 hidden units are refused
+    z6, a6 = s2d.block_attn_pool(d["h"], d["V"], d["w"], d["mask"])
+    torch.cuda.synchronize()
+    assert torch.equal(z6, z0) and torch.equal(a6, a0)
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.block_attn_pool(d["h"], torch.zeros((129, M), device="cuda"), torch.zeros(129, device="cuda"))
+    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("k", [2, 3], ids=["wsi-256x256-bf16", "vmamba-56x56-bf16"])
+def test_attn_pool_at_full_size(s2d, k):
+    """The launch configuration bench.py --block times: embeddings of half the scan's channel count (the block's model
+    width for an expansion of 2), 128 hidden units, the workload's mask."""
+    import torch
+    w = wl.CONFIGS[k]
+    w_ = wl.Workload("pool", w.Bt, w.Dc // 2, 1, w.H, w.W, w.dtype, mask_frac=w.mask_frac)
+    inp = wl.make_pool_inputs(w_, D=128, seed=0)
+    d = s2d.to_device(inp, w.dtype)
+    z, attn = s2d.block_attn_pool(d["h"], d["V"], d["w"], d["mask"])
+    torch.cuda.synchronize()
+    zr, ar = block.attn_pool(inp["h"], inp["V"], inp["w"], inp["mask"], dtype=w.dtype)
+    assert rel_err(s2d.to_host(attn).astype(np.float64), ar) <= TOL_POOL
+    assert rel_err(s2d.to_host(z).astype(np.float64), zr) <= TOL_POOL
