@@ -23,6 +23,11 @@ are learnable linear functions of x.  Readings taken here (both stated in the de
       s_k = sum_d w[d] * tanh(sum_m V[d,m] * h[m,k]),    a_k = exp(s_k) / sum_{j in bag} exp(s_j),    z = sum_k a_k h_k.
   Positions outside the bag get a = 0; an empty bag gives a = 0 and z = 0.  The outputs stay in double precision
   (the library returns fp32).
+* linear layers of the block (Fig. 2: the projections into and out of the block's inner width; Sec. 3.2 keeps the
+  original block's design): applied at every position of a channel-major map,
+      out[b,o,i,j] = bias[o] + sum_c Wt[o,c] * in[b,c,i,j] (+ residual[b,o,i,j]),
+  weights in the storage type, bias fp32, one rounding at the end.  The residual is the block's skip connection
+  around the whole block (Fig. 2) and is added before that rounding.
 """
 from __future__ import annotations
 
@@ -88,3 +93,18 @@ def attn_pool(h, V, w, mask=None, dtype=F32):
         a[b].reshape(-1)[member] = am
         z[b] = members @ am
     return z, a
+
+
+def linear(x, Wt, bias=None, residual=None, dtype=F32):
+    """out [Bt][Cout][H][W] (storage type) = Wt [Cout][Cin] applied to x [Bt][Cin][H][W] at every position, plus
+    bias [Cout] (fp32 or None), plus residual [Bt][Cout][H][W] (storage type or None)."""
+    xw = _widen(x, dtype)
+    Ww = _widen(Wt, dtype)
+    if Ww.ndim != 2 or Ww.shape[1] != xw.shape[1]:
+        raise ValueError("Wt must be [Cout][Cin]")
+    out = np.einsum("oc,bchw->bohw", Ww, xw)
+    if bias is not None:
+        out = out + np.asarray(bias, np.float64)[None, :, None, None]
+    if residual is not None:
+        out = out + _widen(residual, dtype)
+    return _narrow(out, dtype)

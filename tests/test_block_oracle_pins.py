@@ -296,3 +296,68 @@ def test_attn_pool_reads_stored_bits_of_both_storage_types():
     np.testing.assert_array_equal(zf, zd)
     with pytest.raises(ValueError):
         block.attn_pool(h, V[:, :7], w, None, dtype=oracle.F32)
+
+
+# ------------------------------------------------------------------------------------------------ linear layers
+def test_linear_matches_loops_and_has_the_stated_operand_order():
+    rng = np.random.default_rng(21)
+    Bt, Cin, Cout, H, W = 2, 5, 3, 2, 4
+    x = rng.standard_normal((Bt, Cin, H, W))
+    Wt = rng.standard_normal((Cout, Cin))
+    bias = rng.standard_normal(Cout).astype(np.float32)
+    res = rng.standard_normal((Bt, Cout, H, W))
+    got = block.linear(x, Wt, bias, res, dtype=F64)
+    assert got.shape == (Bt, Cout, H, W)
+    for b in range(Bt):
+        for o in range(Cout):
+            for i in range(H):
+                for j in range(W):
+                    ref = float(bias[o]) + res[b, o, i, j]
+                    for c in range(Cin):
+                        ref += Wt[o, c] * x[b, c, i, j]
+                    assert got[b, o, i, j] == pytest.approx(ref, rel=1e-13, abs=1e-13)
+    # optional terms really are optional
+    plain = block.linear(x, Wt, None, None, dtype=F64)
+    np.testing.assert_allclose(got - plain, bias.astype(np.float64)[None, :, None, None] + res, rtol=1e-12, atol=1e-12)
+
+
+def test_linear_special_cases_and_composition():
+    rng = np.random.default_rng(22)
+    x = rng.standard_normal((1, 4, 3, 5))
+    # identity, a permutation of the channels, one-hot rows
+    np.testing.assert_array_equal(block.linear(x, np.eye(4), dtype=F64), x)
+    perm = np.eye(4)[[2, 0, 3, 1]]
+    np.testing.assert_array_equal(block.linear(x, perm, dtype=F64), x[:, [2, 0, 3, 1]])
+    # the torch layer on token-major data is the same map
+    import torch
+    Wt = rng.standard_normal((6, 4))
+    bias = rng.standard_normal(6).astype(np.float32)
+    tok = torch.from_numpy(x[0].reshape(4, -1).T.copy())                     # [positions][channels]
+    ref = torch.nn.functional.linear(tok, torch.from_numpy(Wt), torch.from_numpy(bias.astype(np.float64))).numpy().T.reshape(1, 6, 3, 5)
+    np.testing.assert_allclose(block.linear(x, Wt, bias, dtype=F64), ref, rtol=1e-13, atol=1e-13)
+    # two layers in a row are the product of their matrices; positions do not mix
+    W2 = rng.standard_normal((2, 6))
+    np.testing.assert_allclose(block.linear(block.linear(x, Wt, dtype=F64), W2, dtype=F64), block.linear(x, W2 @ Wt, dtype=F64), rtol=1e-12, atol=1e-12)
+    x2 = x.copy()
+    x2[0, :, 1, 2] += 1.0
+    d = block.linear(x2, Wt, dtype=F64) - block.linear(x, Wt, dtype=F64)
+    assert np.count_nonzero(np.abs(d).sum(axis=1)) == 1
+    np.testing.assert_allclose(d[0, :, 1, 2], Wt.sum(axis=1), rtol=1e-12)
+    # the split input projection: two calls on the two halves of the rows give the two halves of one call
+    both = block.linear(x, Wt, bias, dtype=F64)
+    np.testing.assert_array_equal(block.linear(x, Wt[:3], bias[:3], dtype=F64), both[:, :3])
+    np.testing.assert_array_equal(block.linear(x, Wt[3:], bias[3:], dtype=F64), both[:, 3:])
+
+
+def test_linear_rounds_once_after_bias_and_residual():
+    rng = np.random.default_rng(23)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((1, 8, 2, 6)).astype(np.float32))
+    Wt = wl.f32_to_bf16_bits((rng.standard_normal((5, 8)) / 3).astype(np.float32))
+    bias = rng.standard_normal(5).astype(np.float32)
+    res = wl.f32_to_bf16_bits(rng.standard_normal((1, 5, 2, 6)).astype(np.float32))
+    got = block.linear(x, Wt, bias, res, dtype=oracle.BF16)
+    assert got.dtype == np.uint16
+    exact = block.linear(wl.to_float(x, wl.BF16), wl.to_float(Wt, wl.BF16), bias, wl.to_float(res, wl.BF16), dtype=F64)
+    assert np.all(np.abs(wl.to_float(got, wl.BF16) - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-40)
+    with pytest.raises(ValueError):
+        block.linear(x, Wt[:, :7], dtype=oracle.BF16)
