@@ -314,6 +314,22 @@ int scan2d_block_attn_pool(const scan2d_desc* desc, int D, const void* h, const 
                            const uint8_t* mask, float* attn, float* z, void* stream);
 
 /*
+ * The linear layers of a block (Fig. 2: the projections into the block's inner width and back; Sec. 3.2 keeps the
+ * design of the original block) at every position of a channel-major map:
+ *     out[b,o,i,j] = bias[o] + sum_{c<Cin} Wt[o,c] * in[b,c,i,j] + residual[b,o,i,j]
+ *   in : [Bt][Cin][H][W] with Cin = desc.Dc, Wt : [Cout][Cin], both storage type;  bias : [Cout] fp32 or NULL;
+ *   residual : [Bt][Cout][H][W] storage type or NULL (the skip connection around the block; may be `out` itself);
+ *   out : [Bt][Cout][H][W] storage type (written; out == in is refused with SCAN2D_ERR_BAD_SHAPE).
+ *   The product runs on the matrix cores (inputs as stored, fp32 accumulation); bias and residual are added in fp32
+ *   and the sum is rounded once.  The input projection of a block is two calls, one per half of its rows, so that
+ *   both halves are tensors of their own.  Cout >= 1 (else SCAN2D_ERR_BAD_SHAPE); any Cin, any H*W (multiples of 4
+ *   take the fast path).  desc.N and desc.flags are not used.  Device pointers, 16-byte aligned; asynchronous on
+ *   `stream`; no workspace.
+ */
+int scan2d_block_linear(const scan2d_desc* desc, int Cout, const void* in, const void* Wt, const float* bias,
+                        const void* residual, void* out, void* stream);
+
+/*
  * scan2d_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving or
  * training loops, harnesses that forbid hipMalloc): the same computation and the same kernels as scan2d_bwd,
  * every argument as there, but no workspace argument.  The band checkpoints and partial sums go to a scratch

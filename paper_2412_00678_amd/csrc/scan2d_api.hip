@@ -998,6 +998,19 @@ extern "C" int scan2d_block_attn_pool(const scan2d_desc* desc, int D, const void
     return block_attn_pool_launch(desc, D, h, V, w, mask, attn, z, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int scan2d_block_linear(const scan2d_desc* desc, int Cout, const void* in, const void* Wt, const float* bias,
+                                   const void* residual, void* out, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!in || !Wt || !out) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(in) || !aligned16(Wt) || !aligned16(out) || (bias && !aligned16(bias)) || (residual && !aligned16(residual)))
+        return SCAN2D_ERR_MISALIGNED;
+    if (in == out) return SCAN2D_ERR_BAD_SHAPE;           // every output reads all input channels of its position
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    return block_linear_launch(desc, Cout, in, Wt, bias, residual, out, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int scan2d_debug_force_variant(int kind, const int* values, int n) {
     if (kind < 0 || kind >= kTuneKinds) return SCAN2D_ERR_BAD_FLAGS;
     if (n > 0 && values == nullptr) return SCAN2D_ERR_NULL_POINTER;

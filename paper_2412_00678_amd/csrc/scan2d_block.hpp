@@ -20,4 +20,8 @@ int block_xproj_launch(const scan2d_desc* d, int R, const void* x, const void* W
 int block_attn_pool_launch(const scan2d_desc* d, int D, const void* h, const void* V, const float* w, const uint8_t* mask,
                            float* attn, float* z, hipStream_t stream);
 
+// Linear layer at every position of a channel-major map (scan2d_linear.hip); SCAN2D_ERR_BAD_SHAPE when Cout < 1.
+int block_linear_launch(const scan2d_desc* d, int Cout, const void* in, const void* Wt, const float* bias, const void* residual,
+                        void* out, hipStream_t stream);
+
 }  // namespace scan2d

@@ -22,7 +22,7 @@ EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "sc
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
            "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants",
            "scan2d_block_conv_silu", "scan2d_block_xproj", "scan2d_saved_bytes", "scan2d_fwd_saving", "scan2d_bwd_saved",
-           "scan2d_block_attn_pool")
+           "scan2d_block_attn_pool", "scan2d_block_linear")
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ERR_SCRATCH_LIMIT = -9
 TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
@@ -79,6 +79,8 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_block_xproj.restype = ctypes.c_int
     lib.scan2d_block_attn_pool.argtypes = [ctypes.POINTER(Desc), ctypes.c_int] + [vp] * 7
     lib.scan2d_block_attn_pool.restype = ctypes.c_int
+    lib.scan2d_block_linear.argtypes = [ctypes.POINTER(Desc), ctypes.c_int] + [vp] * 6
+    lib.scan2d_block_linear.restype = ctypes.c_int
     lib.scan2d_saved_bytes.argtypes = [ctypes.POINTER(Desc)]
     lib.scan2d_saved_bytes.restype = ctypes.c_size_t
     lib.scan2d_fwd_saving.argtypes = [ctypes.POINTER(Desc)] + [vp] * 8 + [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
@@ -570,6 +572,28 @@ def block_xproj(x, Wx, Wdt, N, out=None):
     rc = lib.scan2d_block_xproj(ctypes.byref(desc), R, _ptr(x), _ptr(Wx), _ptr(Wdt), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]), _stream_ptr())
     if rc != 0:
         raise Scan2dError(rc, "scan2d_block_xproj")
+    return out
+
+
+def block_linear(x, Wt, bias=None, residual=None, out=None):
+    """out [Bt][Cout][H][W] = Wt [Cout][Cin] (type of x) applied at every position of x [Bt][Cin][H][W], plus
+    bias [Cout] fp32 and residual [Bt][Cout][H][W] (type of x), both optional."""
+    Bt, Cin, H, W = x.shape
+    Cout = int(Wt.shape[0])
+    desc = Desc(Bt, Cin, H, W, 1, _dtype_code(x), 0)
+    _check(x, "x", x.dtype, (Bt, Cin, H, W))
+    _check(Wt, "Wt", x.dtype, (Cout, Cin))
+    if bias is not None:
+        _check(bias, "bias", torch.float32, (Cout,))
+    if residual is not None:
+        _check(residual, "residual", x.dtype, (Bt, Cout, H, W))
+    if out is None:
+        out = torch.empty((Bt, Cout, H, W), dtype=x.dtype, device=x.device)
+    else:
+        _check(out, "out", x.dtype, (Bt, Cout, H, W))
+    rc = lib.scan2d_block_linear(ctypes.byref(desc), Cout, _ptr(x), _ptr(Wt), _ptr(bias), _ptr(residual), _ptr(out), _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_block_linear")
     return out
 
 

@@ -255,3 +255,76 @@ def test_attn_pool_at_full_size(s2d, k):
     zr, ar = block.attn_pool(inp["h"], inp["V"], inp["w"], inp["mask"], dtype=w.dtype)
     assert rel_err(s2d.to_host(attn).astype(np.float64), ar) <= TOL_POOL
     assert rel_err(s2d.to_host(z).astype(np.float64), zr) <= TOL_POOL
+
+
+# ------------------------------------------------------------------------------------------------ linear layers
+LINEAR_CASES = [
+    # Bt, Cin, Cout, H, W, dtype, bias, residual
+    (1, 128, 256, 16, 32, wl.BF16, True, False), (2, 64, 128, 8, 16, wl.F32, False, False), (1, 256, 128, 16, 24, wl.BF16, True, True),
+    (1, 36, 50, 5, 12, wl.F32, True, True), (3, 100, 130, 7, 20, wl.BF16, False, True), (1, 4, 1, 2, 2, wl.F32, True, False),
+    (1, 512, 300, 3, 44, wl.BF16, True, False), (2, 96, 192, 56, 56, wl.BF16, False, False), (1, 160, 96, 20, 52, wl.F32, True, True),
+    # neither H*W nor the channel count a multiple of 4: the kernel with one thread per output
+    (2, 37, 19, 5, 7, wl.BF16, True, True), (1, 30, 64, 3, 9, wl.F32, True, False), (1, 64, 10, 1, 1, wl.F32, False, True),
+]
+
+
+@pytest.mark.parametrize("case", LINEAR_CASES, ids=lambda c: "x".join(map(str, c[:5])) + ("bf16" if c[5] else "f32") + ("-b" if c[6] else "") + ("-r" if c[7] else ""))
+def test_linear_matches_oracle(s2d, case):
+    import torch
+    Bt, Cin, Cout, H, W, dtype, has_bias, has_res = case
+    print(f"linear case {case}", flush=True)
+    rng = np.random.default_rng(47)
+    cast = (lambda a: wl.f32_to_bf16_bits(a.astype(np.float32))) if dtype == wl.BF16 else (lambda a: a.astype(np.float32))
+    inp = {"x": cast(rng.standard_normal((Bt, Cin, H, W))), "Wt": cast(rng.standard_normal((Cout, Cin)) / np.sqrt(Cin)),
+           "bias": rng.standard_normal(Cout).astype(np.float32) if has_bias else None,
+           "res": cast(rng.standard_normal((Bt, Cout, H, W))) if has_res else None}
+    d = s2d.to_device(inp, dtype)
+    out = s2d.block_linear(d["x"], d["Wt"], d["bias"], d["res"])
+    torch.cuda.synchronize()
+    ref = block.linear(inp["x"], inp["Wt"], inp["bias"], inp["res"], dtype=dtype)
+    got = wl.to_float(s2d.to_host(out), dtype)
+    assert np.isfinite(got).all()
+    assert rel_err(got, wl.to_float(ref, dtype)) <= TOL_BLOCK[dtype]
+    if dtype == wl.BF16:
+        assert np.mean(s2d.to_host(out) == ref) > 0.99
+    if has_res:                                           # the skip connection accumulated in place
+        acc = d["res"].clone()
+        s2d.block_linear(d["x"], d["Wt"], d["bias"], acc, out=acc)
+        torch.cuda.synchronize()
+        assert torch.equal(acc, out)
+
+
+def test_linear_rejects_bad_arguments(s2d):
+    import torch
+    x = torch.zeros((1, 8, 4, 4), device="cuda")
+    with pytest.raises(s2d.Scan2dError) as e:
+        s2d.block_linear(x, torch.zeros((8, 8), device="cuda"), out=x)                   # in place on the input
+    assert e.value.code == -2
+    with pytest.raises(ValueError):
+        s2d.block_linear(x, torch.zeros((8, 7), device="cuda"))
+
+
+@pytest.mark.parametrize("k", [2, 3], ids=["wsi-256x256-bf16", "vmamba-56x56-bf16"])
+def test_linear_at_full_size_on_sampled_positions(s2d, k):
+    """The block's input projection (model width Dc / 2 -> inner width Dc) and output projection with the skip
+    connection (Dc -> Dc / 2), in the launch configuration bench.py --block times, on sampled positions."""
+    import torch
+    w = wl.CONFIGS[k]
+    Dm, P = w.Dc // 2, w.H * w.W
+    rng = np.random.default_rng(48)
+    cast = lambda a: wl.f32_to_bf16_bits(a.astype(np.float32))
+    inp = {"t": cast(rng.standard_normal((w.Bt, Dm, w.H, w.W))), "Win": cast(rng.standard_normal((w.Dc, Dm)) / np.sqrt(Dm)),
+           "Wout": cast(rng.standard_normal((Dm, w.Dc)) / np.sqrt(w.Dc)), "bias": rng.standard_normal(w.Dc).astype(np.float32)}
+    d = s2d.to_device(inp, w.dtype)
+    u = s2d.block_linear(d["t"], d["Win"], d["bias"])
+    back = s2d.block_linear(u, d["Wout"], None, d["t"])
+    torch.cuda.synchronize()
+    pos = np.unique(np.concatenate([rng.integers(0, P, 300), [0, 127, 128, P - 129, P - 128, P - 1]]))
+    uh, bh, th = (s2d.to_host(t).reshape(w.Bt, -1, P) for t in (u, back, d["t"]))
+    for b in sorted({0, w.Bt - 1}):
+        sub = np.ascontiguousarray(th[b][:, pos]).reshape(1, Dm, 1, len(pos))
+        ur = block.linear(sub, inp["Win"], inp["bias"], None, dtype=w.dtype)
+        assert rel_err(wl.to_float(uh[b][:, pos], w.dtype), wl.to_float(ur[0, :, 0, :], w.dtype)) <= TOL_BLOCK[w.dtype]
+        usub = np.ascontiguousarray(uh[b][:, pos]).reshape(1, w.Dc, 1, len(pos))
+        br = block.linear(usub, inp["Wout"], None, sub, dtype=w.dtype)
+        assert rel_err(wl.to_float(bh[b][:, pos], w.dtype), wl.to_float(br[0, :, 0, :], w.dtype)) <= TOL_BLOCK[w.dtype]
