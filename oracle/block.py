@@ -28,6 +28,10 @@ are learnable linear functions of x.  Readings taken here (both stated in the de
       out[b,o,i,j] = bias[o] + sum_c Wt[o,c] * in[b,c,i,j] (+ residual[b,o,i,j]),
   weights in the storage type, bias fp32, one rounding at the end.  The residual is the block's skip connection
   around the whole block (Fig. 2) and is added before that rounding.
+* normalisation in front of the block (Sec. 3.3 lists "normalization, projection, and convolution" and does not say
+  which): over the channels of each position, either of the two the Mamba blocks in use take,
+      layer norm: out = (x - mean_c x) / sqrt(var_c x + eps) * gamma[c] + beta[c]     (biased variance)
+      RMS norm:   out = x / sqrt(mean_c x^2 + eps) * gamma[c]                         (+ beta[c] if given)
 """
 from __future__ import annotations
 
@@ -107,4 +111,24 @@ def linear(x, Wt, bias=None, residual=None, dtype=F32):
         out = out + np.asarray(bias, np.float64)[None, :, None, None]
     if residual is not None:
         out = out + _widen(residual, dtype)
+    return _narrow(out, dtype)
+
+
+LAYER_NORM, RMS_NORM = 0, 1
+
+
+def norm(x, gamma, beta=None, eps=1e-5, kind=LAYER_NORM, dtype=F32):
+    """Normalisation over the channel axis of x [Bt][C][H][W] at every position; gamma, beta: [C] fp32 (beta or None)."""
+    xw = _widen(x, dtype)
+    g = np.asarray(gamma, np.float64)[None, :, None, None]
+    if kind == LAYER_NORM:
+        mean = xw.mean(axis=1, keepdims=True)
+        var = ((xw - mean) ** 2).mean(axis=1, keepdims=True)
+        out = (xw - mean) / np.sqrt(var + eps) * g
+    elif kind == RMS_NORM:
+        out = xw / np.sqrt((xw ** 2).mean(axis=1, keepdims=True) + eps) * g
+    else:
+        raise ValueError("kind must be LAYER_NORM or RMS_NORM")
+    if beta is not None:
+        out = out + np.asarray(beta, np.float64)[None, :, None, None]
     return _narrow(out, dtype)

@@ -361,3 +361,71 @@ def test_linear_rounds_once_after_bias_and_residual():
     assert np.all(np.abs(wl.to_float(got, wl.BF16) - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-40)
     with pytest.raises(ValueError):
         block.linear(x, Wt[:, :7], dtype=oracle.BF16)
+
+
+# ------------------------------------------------------------------------------------------------ normalisation
+def test_norm_matches_loops_and_the_torch_layers_on_token_major_data():
+    import torch
+    rng = np.random.default_rng(31)
+    Bt, C, H, W = 2, 7, 3, 4
+    x = rng.standard_normal((Bt, C, H, W)) * 3.0 + 1.5
+    gamma = rng.standard_normal(C).astype(np.float32)
+    beta = rng.standard_normal(C).astype(np.float32)
+    eps = 1e-5
+    ln = block.norm(x, gamma, beta, eps, block.LAYER_NORM, dtype=F64)
+    rms = block.norm(x, gamma, None, eps, block.RMS_NORM, dtype=F64)
+    for b in range(Bt):
+        for i in range(H):
+            for j in range(W):
+                v = [x[b, c, i, j] for c in range(C)]
+                mean = sum(v) / C
+                var = sum((t - mean) ** 2 for t in v) / C
+                ms = sum(t * t for t in v) / C
+                for c in range(C):
+                    assert ln[b, c, i, j] == pytest.approx((v[c] - mean) / math.sqrt(var + eps) * float(gamma[c]) + float(beta[c]), rel=1e-12, abs=1e-13)
+                    assert rms[b, c, i, j] == pytest.approx(v[c] / math.sqrt(ms + eps) * float(gamma[c]), rel=1e-12, abs=1e-13)
+    tok = torch.from_numpy(x.transpose(0, 2, 3, 1).copy())                   # [Bt][H][W][C]
+    ref = torch.nn.functional.layer_norm(tok, (C,), torch.from_numpy(gamma.astype(np.float64)), torch.from_numpy(beta.astype(np.float64)), eps)
+    np.testing.assert_allclose(ln, ref.numpy().transpose(0, 3, 1, 2), rtol=1e-12, atol=1e-12)
+    if hasattr(torch.nn.functional, "rms_norm"):
+        ref = torch.nn.functional.rms_norm(tok, (C,), torch.from_numpy(gamma.astype(np.float64)), eps)
+        np.testing.assert_allclose(rms, ref.numpy().transpose(0, 3, 1, 2), rtol=1e-12, atol=1e-12)
+
+
+def test_norm_invariants_and_special_cases():
+    rng = np.random.default_rng(32)
+    x = rng.standard_normal((1, 16, 2, 5)) * 2.0 - 0.7
+    ones, zeros = np.ones(16, np.float32), np.zeros(16, np.float32)
+    ln = block.norm(x, ones, None, 0.0, block.LAYER_NORM, dtype=F64)
+    np.testing.assert_allclose(ln.mean(axis=1), 0.0, atol=1e-14)             # zero mean, unit variance over the channels
+    np.testing.assert_allclose((ln ** 2).mean(axis=1), 1.0, rtol=1e-13)
+    rms = block.norm(x, ones, None, 0.0, block.RMS_NORM, dtype=F64)
+    np.testing.assert_allclose((rms ** 2).mean(axis=1), 1.0, rtol=1e-13)     # unit mean square, the mean is kept
+    np.testing.assert_allclose(rms * np.sqrt((x ** 2).mean(axis=1, keepdims=True)), x, rtol=1e-13)
+    # layer norm ignores a shift and a positive scale of the input, RMS norm only the scale
+    np.testing.assert_allclose(block.norm(3.0 * x + 5.0, ones, None, 0.0, block.LAYER_NORM, dtype=F64), ln, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(block.norm(3.0 * x, ones, None, 0.0, block.RMS_NORM, dtype=F64), rms, rtol=1e-12)
+    # equal channels: layer norm returns beta (0 / sqrt(eps)), RMS norm the sign times gamma up to eps
+    flat = np.full((1, 16, 1, 3), 2.5)
+    beta = rng.standard_normal(16).astype(np.float32)
+    np.testing.assert_allclose(block.norm(flat, ones, beta, 1e-5, block.LAYER_NORM, dtype=F64)[0, :, 0, 0], beta, atol=1e-12)
+    np.testing.assert_allclose(block.norm(flat, ones, None, 0.0, block.RMS_NORM, dtype=F64), 1.0, rtol=1e-14)
+    assert not block.norm(np.zeros((1, 4, 1, 1)), ones[:4], None, 1e-5, block.RMS_NORM, dtype=F64).any()
+    # eps enters under the root: one channel pair (+t, -t) has mean 0, variance t^2
+    pair = np.array([2.0, -2.0]).reshape(1, 2, 1, 1)
+    assert block.norm(pair, ones[:2], None, 5.0, block.LAYER_NORM, dtype=F64)[0, 0, 0, 0] == pytest.approx(2.0 / 3.0, rel=1e-15)
+    assert block.norm(pair, ones[:2], None, 5.0, block.RMS_NORM, dtype=F64)[0, 1, 0, 0] == pytest.approx(-2.0 / 3.0, rel=1e-15)
+    # positions do not mix; gamma and beta are per channel; one rounding to bf16
+    x2 = x.copy()
+    x2[0, :, 1, 3] *= -2.0
+    d = block.norm(x2, ones, None, 1e-5, block.LAYER_NORM, dtype=F64) - block.norm(x, ones, None, 1e-5, block.LAYER_NORM, dtype=F64)
+    assert np.count_nonzero(np.abs(d).sum(axis=1)) == 1
+    g = rng.standard_normal(16).astype(np.float32)
+    np.testing.assert_allclose(block.norm(x, g, beta, 1e-5, block.LAYER_NORM, dtype=F64),
+                               block.norm(x, ones, None, 1e-5, block.LAYER_NORM, dtype=F64) * g.astype(np.float64)[None, :, None, None] + beta.astype(np.float64)[None, :, None, None], rtol=1e-13, atol=1e-13)
+    xb = wl.f32_to_bf16_bits(x.astype(np.float32))
+    got = block.norm(xb, g, beta, 1e-5, block.LAYER_NORM, dtype=oracle.BF16)
+    exact = block.norm(wl.to_float(xb, wl.BF16), g, beta, 1e-5, block.LAYER_NORM, dtype=F64)
+    assert got.dtype == np.uint16 and np.all(np.abs(wl.to_float(got, wl.BF16) - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-40)
+    with pytest.raises(ValueError):
+        block.norm(x, ones, None, 1e-5, 7, dtype=F64)
