@@ -286,13 +286,14 @@ def bench_block(s2d, w, steps, warmup):
     out["xproj_tflops"] = proj_flops / (out["xproj_ms"] * 1e-3) / 1e12
     del sets
     torch.cuda.empty_cache()
-    # the linear layers around them: model width Dm = Dc / 2 -> inner width Dc (twice: the scan branch and the gate
-    # branch), and back with the skip connection; then the whole block forward back to back
+    # the layers around them: layer norm over the model width Dm = Dc / 2, Dm -> inner width Dc (twice: the scan branch
+    # and the gate branch), and back with the skip connection; then the whole block forward back to back
     Dm = max(4, w.Dc // 2)
     rng = np.random.default_rng(1)
     cast = (lambda a: wl.f32_to_bf16_bits(a.astype(np.float32))) if w.dtype == wl.BF16 else (lambda a: a.astype(np.float32))
     lin = {"t": cast(rng.standard_normal((w.Bt, Dm, w.H, w.W))), "Win_x": cast(rng.standard_normal((w.Dc, Dm)) / np.sqrt(Dm)),
-           "Win_z": cast(rng.standard_normal((w.Dc, Dm)) / np.sqrt(Dm)), "Wout": cast(rng.standard_normal((Dm, w.Dc)) / np.sqrt(w.Dc))}
+           "Win_z": cast(rng.standard_normal((w.Dc, Dm)) / np.sqrt(Dm)), "Wout": cast(rng.standard_normal((Dm, w.Dc)) / np.sqrt(w.Dc)),
+           "gamma": rng.normal(1.0, 0.1, Dm).astype(np.float32), "beta": rng.normal(0.0, 0.1, Dm).astype(np.float32)}
     tokens = w.Bt * Dm * w.H * w.W
     lsets = []
     for _ in range(int(min(8, max(2, np.ceil(1.2e9 / ((7 * maps + 2 * tokens + 2 * states) * eb)))))):
@@ -300,33 +301,42 @@ def bench_block(s2d, w, steps, warmup):
         d["x"] = torch.empty_like(d["u"])
         d["y"] = torch.empty_like(d["u"])
         d["t_out"] = torch.empty_like(d["t"])
+        d["tn"] = torch.empty_like(d["t"])
         d["proj"] = (torch.empty_like(d["u"]), torch.empty((w.Bt, w.N, w.H, w.W), dtype=d["u"].dtype, device="cuda:0"),
                      torch.empty((w.Bt, w.N, w.H, w.W), dtype=d["u"].dtype, device="cuda:0"))
         lsets.append(d)
 
+    def norm(s):
+        s2d.block_norm(s["t"], s["gamma"], s["beta"], 1e-5, s2d.LAYER_NORM, out=s["tn"])
+
     def in_proj(s):
-        s2d.block_linear(s["t"], s["Win_x"], out=s["u"])
+        s2d.block_linear(s["tn"], s["Win_x"], out=s["u"])
 
     def out_proj(s):
         s2d.block_linear(s["y"], s["Wout"], None, s["t"], out=s["t_out"])
 
     def whole_block(s):
-        s2d.block_linear(s["t"], s["Win_x"], out=s["u"])
-        s2d.block_linear(s["t"], s["Win_z"], out=s["z"])
+        norm(s)
+        s2d.block_linear(s["tn"], s["Win_x"], out=s["u"])
+        s2d.block_linear(s["tn"], s["Win_z"], out=s["z"])
         conv(s); proj(s); scan(s)
         out_proj(s)
 
     in_bytes = (tokens + maps) * eb + w.Dc * Dm * eb
     out_bytes = (maps + 2 * tokens) * eb + w.Dc * Dm * eb
     lin_flops = 2.0 * w.Dc * Dm * w.Bt * w.H * w.W
-    for name, fn, nbytes in (("in_proj", in_proj, in_bytes), ("out_proj", out_proj, out_bytes), ("whole_block", whole_block, None)):
+    for s_ in lsets:
+        norm(s_)                                           # in_proj alone reads the normalised tokens
+    for name, fn, nbytes in (("norm", norm, 2 * tokens * eb), ("in_proj", in_proj, in_bytes), ("out_proj", out_proj, out_bytes),
+                             ("whole_block", whole_block, None)):
         t, _ = time_launches(fn, lsets, steps, warmup)
         out[name + "_ms"] = float(t)
         if nbytes is not None:
             gbs = nbytes / (float(t) * 1e-3) / 1e9
             out[name + "_roofline"] = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                                        "algorithmic_bytes": nbytes}
-            out[name + "_tflops"] = lin_flops / (float(t) * 1e-3) / 1e12
+            if name != "norm":
+                out[name + "_tflops"] = lin_flops / (float(t) * 1e-3) / 1e12
     out["model_width"] = Dm
     del lsets
     torch.cuda.empty_cache()

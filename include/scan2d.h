@@ -330,6 +330,21 @@ int scan2d_block_linear(const scan2d_desc* desc, int Cout, const void* in, const
                         const void* residual, void* out, void* stream);
 
 /*
+ * The normalisation in front of a block (Sec. 3.3 lists normalization, projection and convolution in front of the scan
+ * and does not say which normalisation; both kinds the Mamba blocks in use take are offered), over the channels c of
+ * every position of a channel-major map:
+ *     SCAN2D_LAYER_NORM : out = (in - mean_c in) / sqrt(var_c in + eps) * gamma[c] + beta[c]     (biased variance)
+ *     SCAN2D_RMS_NORM   : out = in / sqrt(mean_c in^2 + eps) * gamma[c] + beta[c]
+ *   in, out : [Bt][C][H][W] storage type with C = desc.Dc (out is written; out == in is allowed);
+ *   gamma : [C] fp32;  beta : [C] fp32 or NULL (= 0).  fp32 arithmetic (mean first, then the mean of the squared
+ *   deviations), one rounding.  eps >= 0 and kind one of the two (else SCAN2D_ERR_BAD_SHAPE).  desc.N and desc.flags
+ *   are not used.  Device pointers, 16-byte aligned; asynchronous on `stream`; no workspace.
+ */
+enum { SCAN2D_LAYER_NORM = 0, SCAN2D_RMS_NORM = 1 };
+int scan2d_block_norm(const scan2d_desc* desc, int kind, float eps, const void* in, const float* gamma,
+                      const float* beta, void* out, void* stream);
+
+/*
  * scan2d_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving or
  * training loops, harnesses that forbid hipMalloc): the same computation and the same kernels as scan2d_bwd,
  * every argument as there, but no workspace argument.  The band checkpoints and partial sums go to a scratch

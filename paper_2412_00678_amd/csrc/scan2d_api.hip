@@ -1011,6 +1011,17 @@ extern "C" int scan2d_block_linear(const scan2d_desc* desc, int Cout, const void
     return block_linear_launch(desc, Cout, in, Wt, bias, residual, out, static_cast<hipStream_t>(stream));
 }
 
+extern "C" int scan2d_block_norm(const scan2d_desc* desc, int kind, float eps, const void* in, const float* gamma,
+                                 const float* beta, void* out, void* stream) {
+    int rc = check_desc(desc);
+    if (rc != SCAN2D_OK) return rc;
+    if (!in || !gamma || !out) return SCAN2D_ERR_NULL_POINTER;
+    if (!aligned16(in) || !aligned16(gamma) || !aligned16(out) || (beta && !aligned16(beta))) return SCAN2D_ERR_MISALIGNED;
+    rc = check_device();
+    if (rc != SCAN2D_OK) return rc;
+    return block_norm_launch(desc, kind, eps, in, gamma, beta, out, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int scan2d_debug_force_variant(int kind, const int* values, int n) {
     if (kind < 0 || kind >= kTuneKinds) return SCAN2D_ERR_BAD_FLAGS;
     if (n > 0 && values == nullptr) return SCAN2D_ERR_NULL_POINTER;

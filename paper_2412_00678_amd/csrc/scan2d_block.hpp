@@ -24,4 +24,9 @@ int block_attn_pool_launch(const scan2d_desc* d, int D, const void* h, const voi
 int block_linear_launch(const scan2d_desc* d, int Cout, const void* in, const void* Wt, const float* bias, const void* residual,
                         void* out, hipStream_t stream);
 
+// Normalisation over the channels of each position (scan2d_norm.hip); kind 0 = layer norm, 1 = RMS norm;
+// SCAN2D_ERR_BAD_SHAPE for another kind or a negative eps.
+int block_norm_launch(const scan2d_desc* d, int kind, float eps, const void* in, const float* gamma, const float* beta, void* out,
+                      hipStream_t stream);
+
 }  // namespace scan2d

@@ -372,11 +372,13 @@ def write_producers(runs_dir, by_name):
             rows.append(f"| {label} | {blk[key + '_ms'] * 1e3:.1f} | {r['algorithmic_bytes'] / 1e6:.1f} | {r['achieved']:.0f} | {100 * r['frac']:.1f} |")
         rows.append(f"| scan2d_fwd_softplus_gated on their outputs | {blk['gated_scan_ms'] * 1e3:.1f} | | | |")
         rows.append(f"| the three calls back to back | {blk['chain_ms'] * 1e3:.1f} | | | |")
+        r = blk["norm_roofline"]
+        rows.append(f"| scan2d_block_norm (layer norm over the {blk['model_width']} channels of the model width) | {blk['norm_ms'] * 1e3:.1f} | {r['algorithmic_bytes'] / 1e6:.1f} | {r['achieved']:.0f} | {100 * r['frac']:.1f} |")
         for key, label in (("in_proj", f"scan2d_block_linear, model width {blk['model_width']} -> inner width (one of the two input projections)"),
                            ("out_proj", "scan2d_block_linear, inner width -> model width, plus the skip connection")):
             r = blk[key + "_roofline"]
             rows.append(f"| {label} ({blk[key + '_tflops']:.0f} TFLOP/s) | {blk[key + '_ms'] * 1e3:.1f} | {r['algorithmic_bytes'] / 1e6:.1f} | {r['achieved']:.0f} | {100 * r['frac']:.1f} |")
-        rows.append(f"| the whole block forward: two input projections, convolution, projections, gated scan, output projection | {blk['whole_block_ms'] * 1e3:.1f} | | | |")
+        rows.append(f"| the whole block forward: layer norm, two input projections, convolution, projections, gated scan, output projection | {blk['whole_block_ms'] * 1e3:.1f} | | | |")
         r = blk["attn_pool_roofline"]
         rows.append(f"| scan2d_block_attn_pool (M = {blk['attn_pool_shape']['M']} channels, D = {blk['attn_pool_shape']['D']} hidden units; three launches) | "
                     f"{blk['attn_pool_ms'] * 1e3:.1f} | {r['algorithmic_bytes'] / 1e6:.1f} | {r['achieved']:.0f} | {100 * r['frac']:.1f} |")

@@ -22,7 +22,7 @@ EXPORTS = ("scan2d_fwd", "scan2d_fwd_softplus", "scan2d_fwd_softplus_gated", "sc
            "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
            "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants",
            "scan2d_block_conv_silu", "scan2d_block_xproj", "scan2d_saved_bytes", "scan2d_fwd_saving", "scan2d_bwd_saved",
-           "scan2d_block_attn_pool", "scan2d_block_linear")
+           "scan2d_block_attn_pool", "scan2d_block_linear", "scan2d_block_norm")
 STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 ERR_SCRATCH_LIMIT = -9
 TUNE_FWD, TUNE_FWD_SHARED, TUNE_BWD = 0, 1, 2
@@ -81,6 +81,8 @@ def _load() -> ctypes.CDLL:
     lib.scan2d_block_attn_pool.restype = ctypes.c_int
     lib.scan2d_block_linear.argtypes = [ctypes.POINTER(Desc), ctypes.c_int] + [vp] * 6
     lib.scan2d_block_linear.restype = ctypes.c_int
+    lib.scan2d_block_norm.argtypes = [ctypes.POINTER(Desc), ctypes.c_int, ctypes.c_float] + [vp] * 5
+    lib.scan2d_block_norm.restype = ctypes.c_int
     lib.scan2d_saved_bytes.argtypes = [ctypes.POINTER(Desc)]
     lib.scan2d_saved_bytes.restype = ctypes.c_size_t
     lib.scan2d_fwd_saving.argtypes = [ctypes.POINTER(Desc)] + [vp] * 8 + [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
@@ -594,6 +596,27 @@ def block_linear(x, Wt, bias=None, residual=None, out=None):
     rc = lib.scan2d_block_linear(ctypes.byref(desc), Cout, _ptr(x), _ptr(Wt), _ptr(bias), _ptr(residual), _ptr(out), _stream_ptr())
     if rc != 0:
         raise Scan2dError(rc, "scan2d_block_linear")
+    return out
+
+
+LAYER_NORM, RMS_NORM = 0, 1
+
+
+def block_norm(x, gamma, beta=None, eps=1e-5, kind=LAYER_NORM, out=None):
+    """Layer norm or RMS norm over the channels of every position of x [Bt][C][H][W]; gamma, beta: [C] fp32."""
+    Bt, C, H, W = x.shape
+    desc = Desc(Bt, C, H, W, 1, _dtype_code(x), 0)
+    _check(x, "x", x.dtype, (Bt, C, H, W))
+    _check(gamma, "gamma", torch.float32, (C,))
+    if beta is not None:
+        _check(beta, "beta", torch.float32, (C,))
+    if out is None:
+        out = torch.empty_like(x)
+    else:
+        _check(out, "out", x.dtype, (Bt, C, H, W))
+    rc = lib.scan2d_block_norm(ctypes.byref(desc), int(kind), float(eps), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(out), _stream_ptr())
+    if rc != 0:
+        raise Scan2dError(rc, "scan2d_block_norm")
     return out
 
 

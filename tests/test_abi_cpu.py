@@ -31,7 +31,7 @@ def test_header_declares_the_expected_entry_points():
          "scan2d_bwd_softplus_gated", "scan2d_workspace_bytes", "scan2d_describe_plan", "scan2d_strerror",
          "scan2d_version", "scan2d_debug_force_variant", "scan2d_bwd_static_scratch", "scan2d_fwd_variants", "scan2d_bwd_variants",
          "scan2d_block_conv_silu", "scan2d_block_xproj", "scan2d_saved_bytes", "scan2d_fwd_saving", "scan2d_bwd_saved",
-         "scan2d_block_attn_pool", "scan2d_block_linear"])
+         "scan2d_block_attn_pool", "scan2d_block_linear", "scan2d_block_norm"])
 
 
 def test_library_exports_every_declared_symbol(lib):

@@ -328,3 +328,86 @@ def test_linear_at_full_size_on_sampled_positions(s2d, k):
         usub = np.ascontiguousarray(uh[b][:, pos]).reshape(1, w.Dc, 1, len(pos))
         br = block.linear(usub, inp["Wout"], None, sub, dtype=w.dtype)
         assert rel_err(wl.to_float(bh[b][:, pos], w.dtype), wl.to_float(br[0, :, 0, :], w.dtype)) <= TOL_BLOCK[w.dtype]
+
+
+# ------------------------------------------------------------------------------------------------ normalisation
+NORM_CASES = [
+    # Bt, C, H, W, dtype, kind, beta
+    (1, 128, 16, 32, wl.BF16, 0, True), (2, 64, 8, 16, wl.F32, 1, False), (1, 100, 5, 12, wl.F32, 0, True), (3, 37, 7, 9, wl.BF16, 0, False),
+    (1, 1, 4, 4, wl.F32, 1, True), (2, 5, 1, 1, wl.F32, 0, True), (1, 192, 56, 56, wl.BF16, 1, True), (1, 512, 3, 70, wl.F32, 0, True),
+    (1, 19, 64, 65, wl.BF16, 1, False),
+]
+
+
+@pytest.mark.parametrize("case", NORM_CASES, ids=lambda c: "x".join(map(str, c[:4])) + ("bf16" if c[4] else "f32") + ("-rms" if c[5] else "-ln") + ("-b" if c[6] else ""))
+def test_norm_matches_oracle(s2d, case):
+    import torch
+    Bt, C, H, W, dtype, kind, has_beta = case
+    print(f"norm case {case}", flush=True)
+    rng = np.random.default_rng(49)
+    cast = (lambda a: wl.f32_to_bf16_bits(a.astype(np.float32))) if dtype == wl.BF16 else (lambda a: a.astype(np.float32))
+    # a mean of several standard deviations: the variance must not come from a difference of large sums
+    inp = {"x": cast(rng.standard_normal((Bt, C, H, W)) * 0.5 + 4.0), "gamma": rng.standard_normal(C).astype(np.float32),
+           "beta": rng.standard_normal(C).astype(np.float32) if has_beta else None}
+    d = s2d.to_device(inp, dtype)
+    out = s2d.block_norm(d["x"], d["gamma"], d["beta"], 1e-5, kind)
+    torch.cuda.synchronize()
+    ref = block.norm(inp["x"], inp["gamma"], inp["beta"], 1e-5, kind, dtype=dtype)
+    got = wl.to_float(s2d.to_host(out), dtype)
+    assert np.isfinite(got).all()
+    assert rel_err(got, wl.to_float(ref, dtype)) <= TOL_BLOCK[dtype]
+    if dtype == wl.BF16:
+        assert np.mean(s2d.to_host(out) == ref) > 0.99
+    inplace = d["x"].clone()
+    s2d.block_norm(inplace, d["gamma"], d["beta"], 1e-5, kind, out=inplace)
+    torch.cuda.synchronize()
+    assert torch.equal(inplace, out)
+
+
+def test_norm_rejects_bad_arguments(s2d):
+    import torch
+    x = torch.zeros((1, 8, 4, 4), device="cuda")
+    g = torch.ones(8, device="cuda")
+    for kind, eps in ((2, 1e-5), (0, -1.0), (0, float("nan"))):
+        with pytest.raises(s2d.Scan2dError) as e:
+            s2d.block_norm(x, g, None, eps, kind)
+        assert e.value.code == -2
+
+
+@pytest.mark.parametrize("shape", [(1, 32, 16, 16, 24, wl.BF16, 4), (2, 16, 8, 9, 20, wl.F32, 2)], ids=["16x24-bf16", "9x20-f32"])
+def test_whole_block_forward_matches_the_oracle_chain(s2d, shape):
+    """Layer norm -> the two input projections -> convolution + SiLU -> step / B / C projections -> softplus step, 2D
+    scan, gate -> output projection with the skip connection, every tensor between the stages in the storage type on
+    both sides (Fig. 2)."""
+    import torch
+    Bt, Dm, N, H, W, dtype, R = shape
+    Dc = 2 * Dm
+    w_ = wl.Workload("block", Bt, Dc, N, H, W, dtype, mask_frac=0.3)
+    inp = wl.make_block_inputs(w_, R=R, seed=50)
+    rng = np.random.default_rng(51)
+    cast = (lambda a: wl.f32_to_bf16_bits(a.astype(np.float32))) if dtype == wl.BF16 else (lambda a: a.astype(np.float32))
+    ext = {"t": cast(rng.standard_normal((Bt, Dm, H, W))), "Win_x": cast(rng.standard_normal((Dc, Dm)) / np.sqrt(Dm)),
+           "Win_z": cast(rng.standard_normal((Dc, Dm)) / np.sqrt(Dm)), "Wout": cast(rng.standard_normal((Dm, Dc)) / np.sqrt(Dc)),
+           "gamma": rng.normal(1.0, 0.1, Dm).astype(np.float32), "beta": rng.normal(0.0, 0.1, Dm).astype(np.float32)}
+    d = s2d.to_device({**inp, **ext}, dtype)
+    tn = s2d.block_norm(d["t"], d["gamma"], d["beta"], 1e-5, s2d.LAYER_NORM)
+    u = s2d.block_linear(tn, d["Win_x"])
+    z = s2d.block_linear(tn, d["Win_z"])
+    x = s2d.block_conv_silu(u, d["w"], d["bias"])
+    delta_raw, Bm, Cm = s2d.block_xproj(x, d["Wx"], d["Wdt"], N)
+    _, y = s2d.scan2d_fwd_softplus_gated(x, delta_raw, d["delta_bias"], d["A"], Bm, Cm, d["Dskip"], d["mask"], z, want_y_scan=False)
+    t_out = s2d.block_linear(y, d["Wout"], None, d["t"])
+    torch.cuda.synchronize()
+    tnr = block.norm(ext["t"], ext["gamma"], ext["beta"], 1e-5, block.LAYER_NORM, dtype=dtype)
+    ur = block.linear(tnr, ext["Win_x"], dtype=dtype)
+    zr = block.linear(tnr, ext["Win_z"], dtype=dtype)
+    xr = block.conv_silu(ur, inp["w"], inp["bias"], 1, 1, dtype=dtype)
+    dr, Br, Cr = block.xproj(xr, inp["Wx"], inp["Wdt"], N, dtype=dtype)
+    _, yr = oracle.scan2d_fwd_softplus_gated(xr, dr, inp["delta_bias"], inp["A"], Br, Cr, inp["Dskip"], inp["mask"], zr, dtype=dtype)
+    tr = block.linear(yr, ext["Wout"], None, ext["t"], dtype=dtype)
+    got = wl.to_float(s2d.to_host(t_out), dtype)
+    assert np.isfinite(got).all()
+    # roundings of the storage type between seven stages: a few units in the last place of bf16 at the end
+    tol = {wl.F32: 2e-5, wl.BF16: 3e-2}[dtype]
+    assert rel_err(wl.to_float(s2d.to_host(u), dtype), wl.to_float(ur, dtype)) <= 2 * TOL_BLOCK[dtype]
+    assert rel_err(got, wl.to_float(tr, dtype)) <= tol
