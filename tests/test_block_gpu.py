@@ -411,3 +411,79 @@ def test_whole_block_forward_matches_the_oracle_chain(s2d, shape):
     tol = {wl.F32: 2e-5, wl.BF16: 3e-2}[dtype]
     assert rel_err(wl.to_float(s2d.to_host(u), dtype), wl.to_float(ur, dtype)) <= 2 * TOL_BLOCK[dtype]
     assert rel_err(got, wl.to_float(tr, dtype)) <= tol
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32], ids=["bf16", "f32"])
+def test_whole_block_and_aggregator_replay_from_a_hip_graph(s2d, dtype):
+    """The layers around the scan only enqueue kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a whole block forward plus the aggregator can be captured; every replay equals the eager
+    result bit for bit, also after the inputs changed and eager work ran in between.  fp32 takes the linear kernel
+    that needs more than 64 KB of dynamic LDS (the attribute is raised once, outside the capture)."""
+    import torch
+    Bt, Dm, N, H, W, R = 2, 32, 16, 16, 32, 4
+    Dc = 2 * Dm
+    w_ = wl.Workload("graph_block", Bt, Dc, N, H, W, dtype, mask_frac=0.3)
+    cast = (lambda a: wl.f32_to_bf16_bits(a.astype(np.float32))) if dtype == wl.BF16 else (lambda a: a.astype(np.float32))
+
+    def draw(seed):
+        inp = wl.make_block_inputs(w_, R=R, seed=seed)
+        rng = np.random.default_rng(seed + 100)
+        inp.update({"t": cast(rng.standard_normal((Bt, Dm, H, W))), "Win_x": cast(rng.standard_normal((Dc, Dm)) / np.sqrt(Dm)),
+                    "Win_z": cast(rng.standard_normal((Dc, Dm)) / np.sqrt(Dm)), "Wout": cast(rng.standard_normal((Dm, Dc)) / np.sqrt(Dc)),
+                    "gamma": rng.normal(1.0, 0.1, Dm).astype(np.float32), "beta": rng.normal(0.0, 0.1, Dm).astype(np.float32),
+                    "V": cast(rng.standard_normal((128, Dm)) / np.sqrt(Dm)), "wp": rng.standard_normal(128).astype(np.float32)})
+        return inp
+
+    sets = [draw(61), draw(62)]
+    st = s2d.to_device(sets[0], dtype)
+    like = lambda C: torch.empty((Bt, C, H, W), dtype=st["t"].dtype, device="cuda:0")
+    buf = {"tn": like(Dm), "u": like(Dc), "zb": like(Dc), "x": like(Dc), "y": like(Dc), "t_out": like(Dm),
+           "proj": (like(Dc), like(N), like(N)), "pool": (torch.empty((Bt, Dm), device="cuda:0"), torch.empty((Bt, H, W), device="cuda:0"))}
+    desc = s2d.make_desc(buf["x"], st["A"])
+    ws = torch.empty(max(16, s2d.workspace_bytes(desc, s2d.PASS_FWD)), dtype=torch.uint8, device="cuda:0")
+
+    def run():
+        s2d.block_norm(st["t"], st["gamma"], st["beta"], 1e-5, s2d.LAYER_NORM, out=buf["tn"])
+        s2d.block_linear(buf["tn"], st["Win_x"], out=buf["u"])
+        s2d.block_linear(buf["tn"], st["Win_z"], out=buf["zb"])
+        s2d.block_conv_silu(buf["u"], st["w"], st["bias"], x=buf["x"])
+        s2d.block_xproj(buf["x"], st["Wx"], st["Wdt"], N, out=buf["proj"])
+        s2d.scan2d_fwd_softplus_gated(buf["x"], buf["proj"][0], st["delta_bias"], st["A"], buf["proj"][1], buf["proj"][2], st["Dskip"],
+                                      st["mask"], buf["zb"], want_y_scan=False, workspace=ws, y=buf["y"])
+        s2d.block_linear(buf["y"], st["Wout"], None, st["t"], out=buf["t_out"])
+        s2d.block_attn_pool(buf["t_out"], st["V"], st["wp"], st["mask"], out=buf["pool"])
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [s2d.to_host(buf["t_out"]).copy(), s2d.to_host(buf["pool"][0]).copy(), s2d.to_host(buf["pool"][1]).copy()]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for k in (0, 1, 0):
+        new = s2d.to_device(sets[k], dtype)
+        for name, t in st.items():
+            if t is not None:
+                t.copy_(new[name])
+        for t in (buf["t_out"], buf["pool"][0], buf["pool"][1]):
+            t.fill_(float("nan"))
+        graph.replay()
+        got = snapshot()
+        run()                                           # eager work between the replays
+        ref = snapshot()
+        for a, b in zip(got, ref):
+            assert np.array_equal(a, b)
+    # and the replayed result is the oracle's chain (first draw)
+    i0 = sets[0]
+    tnr = block.norm(i0["t"], i0["gamma"], i0["beta"], 1e-5, block.LAYER_NORM, dtype=dtype)
+    xr = block.conv_silu(block.linear(tnr, i0["Win_x"], dtype=dtype), i0["w"], i0["bias"], 1, 1, dtype=dtype)
+    dr, Br, Cr = block.xproj(xr, i0["Wx"], i0["Wdt"], N, dtype=dtype)
+    _, yr = oracle.scan2d_fwd_softplus_gated(xr, dr, i0["delta_bias"], i0["A"], Br, Cr, i0["Dskip"], i0["mask"], block.linear(tnr, i0["Win_z"], dtype=dtype), dtype=dtype)
+    tr = block.linear(yr, i0["Wout"], None, i0["t"], dtype=dtype)
+    assert rel_err(wl.to_float(got[0], dtype), wl.to_float(tr, dtype)) <= {wl.F32: 2e-5, wl.BF16: 3e-2}[dtype]
