@@ -277,6 +277,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 
             // ---- scans 1 and 2: rebuild h[i-1,j] and hhor[i,j-1] for the rows of the band
             float hprev[RB][NW][K], hhl[RB][NW][K];
+            float hcur[NW][K];                                 // after scans 1 and 2: the state of the band's bottom row
             {
                 uint32_t fB[NB][NW][XW];
                 auto issue = [&](int buf, int i) {
@@ -286,7 +287,6 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                     for (int s = 0; s < NW; ++s) ld_elems<T, K, FAST>(Bs[s] + ro, lcol, lastB[s] && bottom, tl.B, fB[buf][s]);
                 };
                 if constexpr (PF) issue(0, r0);
-                float hcur[NW][K];
 #pragma unroll
                 for (int s = 0; s < NW; ++s) {
                     const float* src = p.ck + ((map * p.nb + band) * N + n0 + s) * W;
@@ -355,6 +355,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 left = hh;
                             }
                         }
+                    } else if constexpr (!CF) {                  // below the map: the row above finds the bottom state here
+#pragma unroll
+                        for (int s = 0; s < NW; ++s)
+#pragma unroll
+                            for (int j = 0; j < K; ++j) hprev[r][s][j] = hcur[s][j];
                     }
                 }
             }
@@ -403,9 +408,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                         for (int j = 0; j < K; ++j) {
                             a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
                             Bv[j] = get_elem<T, K>(bB[PF ? (r & 1) : 0][s], j);
-                            // row first: hhor[i,j], then h[i,j]; columns first: v[i,j], then h[i,j]
-                            const float hh = fmaf(a[j], CF ? hprev[r][s][j] : hhl[r][s][j], dxe[j] * Bv[j]);
-                            const float hv = fmaf(a[j], CF ? hhl[r][s][j] : hprev[r][s][j], hh);
+                            float hv;
+                            if constexpr (CF) {                // v[i,j], then h[i,j]
+                                const float hh = fmaf(a[j], hprev[r][s][j], dxe[j] * Bv[j]);
+                                hv = fmaf(a[j], hhl[r][s][j], hh);
+                            } else {                           // h[i,j] is what the row below started from
+                                hv = r == RB - 1 ? hcur[s][j] : hprev[r + 1 < RB ? r + 1 : r][s][j];
+                            }
                             dCacc[r][s][j] = fmaf(dyv[j], hv, dCacc[r][s][j]);
                             const float dyC = dyv[j] * get_elem<T, K>(bC[PF ? (r & 1) : 0][s], j);
                             if constexpr (CF) {
