@@ -14,9 +14,11 @@
 // ahead - and leave them in LDS as fp32:
 //     dl = step       xe = mask ? 0 : x       dxe = dl * xe       dyv = dy       and the mask flag itself.
 // The scanning lanes read their K columns with wide LDS loads; only Bm and Cm still come from global memory.
-// The sums over states of ddelta and dx go through LDS as before (double-buffered per row), but every
-// (column, tensor) pair of a row is summed by one thread of the job, so all of them are busy after the barrier;
-// that thread also adds the skip term Dskip * dy and writes +0 under the mask.
+// The sums over the states of ddelta and dx go through LDS (double-buffered per row); the threads of the job add
+// them up over the lane groups, add the skip term Dskip * dy and write +0 under the mask.  Where a row has more
+// (column, tensor) pairs than the job has threads, the two sums are those of the decay gradients times a * A and of
+// the gradients of u times B, one thread per column forms both and only then applies the factors that depend on the
+// position alone (ddelta = first sum + x * second sum, dx = step * second sum): two instructions per state less.
 // dA is summed over the lane group once per (band, channel) (DPP) and accumulated by one lane in LDS; dDskip
 // is accumulated by the producing threads and summed per wavefront: both in a fixed order, so results are
 // bit-reproducible.  K only has to be even here (the scanning lanes load no mask bytes), which allows
@@ -117,7 +119,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
     constexpr int THREADS = WAVES * 64, SLOTS = THREADS / LG, JPW = SLOTS / NG, PANEL = LG * K, TMJ = NG * LG;
     static_assert(SLOTS % NG == 0 && JPW >= 1, "whole jobs per workgroup");
     constexpr int CELLS = RB * PANEL, CT = (CELLS + TMJ - 1) / TMJ;     // cells of a band per producing thread
-    constexpr int TASKS = 2 * PANEL, TT = (TASKS + TMJ - 1) / TMJ;      // (column, tensor) sums of a row per thread
+    // Sums over the states of a row: where the job has fewer threads than (column, tensor) pairs, one thread per column
+    // forms both sums and the factors that depend on the position alone (x, the step) are applied after them (LATEF);
+    // otherwise one thread per (column, tensor) pair, the factors applied per state
+    constexpr bool LATEF = 2 * PANEL > TMJ;
+    constexpr int TASKS = LATEF ? PANEL : 2 * PANEL, TT = (TASKS + TMJ - 1) / TMJ;
     constexpr int XW = words_of<T, K>();
     using DT = std::conditional_t<SP, float, T>;                        // element type of the step
     constexpr int PP_ROW = 5 * PANEL, PP_JOB = RB * PP_ROW;
@@ -394,9 +400,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                     }
                     const size_t ro = (size_t)i * W;
                     const float* prow = ppj + r * PP_ROW;
-                    float dl[K], xe[K], dxe[K], dyv[K], ddl[K], dxl[K];
+                    // ddl: sum over this lane's states of (gradient of the decay) * a * A; dxl: of (gradient of u) * B.  The
+                    // factors that depend on the position only (x and the step) are applied after the sum over all states
+                    float dl[K], xe[LATEF ? 1 : K], dxe[K], dyv[K], ddl[K], dxl[K];
                     lds_read_k<LG, K>(prow, l, dl);
-                    lds_read_k<LG, K>(prow + PANEL, l, xe);
+                    if constexpr (!LATEF) lds_read_k<LG, K>(prow + PANEL, l, xe);
                     lds_read_k<LG, K>(prow + 2 * PANEL, l, dxe);
                     lds_read_k<LG, K>(prow + 3 * PANEL, l, dyv);
 #pragma unroll
@@ -454,8 +462,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                             const float t = da * a[j];
                             const float qB = du * Bv[j];
                             dAb[s] = fmaf(t, dl[j], dAb[s]);
-                            ddl[j] = fmaf(t, An[s], fmaf(qB, xe[j], ddl[j]));
-                            dxl[j] = fmaf(qB, dl[j], dxl[j]);
+                            if constexpr (LATEF) {
+                                ddl[j] = fmaf(t, An[s], ddl[j]);
+                                dxl[j] += qB;
+                            } else {
+                                ddl[j] = fmaf(t, An[s], fmaf(qB, xe[j], ddl[j]));
+                                dxl[j] = fmaf(qB, dl[j], dxl[j]);
+                            }
                             dBacc[r][s][j] = fmaf(du, dxe[j], dBacc[r][s][j]);
                         }
                     }
@@ -468,17 +481,32 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                         const float* base = part + (size_t)(step & 1) * 2 * THREADS * K + (size_t)(slot - sg) * PANEL;
 #pragma unroll
                         for (int v = 0; v < TT; ++v) {
-                            const int t = tm + v * TMJ;
-                            const int tens = t / PANEL, col = t - tens * PANEL;
-                            if (t < TASKS && col < W) {
-                                const float sum = sum_partials_fixed<PANEL, NG>(base + tens * (THREADS * K) + lds_colk<LG, K>(col));
-                                if (tens == 0) {
-                                    if constexpr (SP) ddw[ro + col] = sum;      // over the step of this cell, which nobody reads again
-                                    else store_elem(ddm + ro + col, sum);
-                                } else {                                        // skip term; exactly +0 under the mask
-                                    const float* cell = prow + lds_colk<LG, K>(col);
-                                    store_elem(dxm + ro + col, cell[4 * PANEL] != 0.0f ? 0.0f : fmaf(dsk, cell[3 * PANEL], sum));
+                            if constexpr (!LATEF) {
+                                const int t = tm + v * TMJ;
+                                const int tens = t / PANEL, col = t - tens * PANEL;
+                                if (t < TASKS && col < W) {
+                                    const float sum = sum_partials_fixed<PANEL, NG>(base + tens * (THREADS * K) + lds_colk<LG, K>(col));
+                                    if (tens == 0) {
+                                        if constexpr (SP) ddw[ro + col] = sum;  // over the step of this cell, which nobody reads again
+                                        else store_elem(ddm + ro + col, sum);
+                                    } else {                                    // skip term; exactly +0 under the mask
+                                        const float* cell = prow + lds_colk<LG, K>(col);
+                                        store_elem(dxm + ro + col, cell[4 * PANEL] != 0.0f ? 0.0f : fmaf(dsk, cell[3 * PANEL], sum));
+                                    }
                                 }
+                                continue;
+                            }
+                            const int col = tm + v * TMJ;
+                            if (col < PANEL && col < W) {
+                                const int at = lds_colk<LG, K>(col);
+                                const float sA = sum_partials_fixed<PANEL, NG>(base + at);
+                                const float sB = sum_partials_fixed<PANEL, NG>(base + THREADS * K + at);
+                                const float* cell = prow + at;                  // dl, xe, dl*xe, dy, mask flag of this cell
+                                const float dd = fmaf(cell[PANEL], sB, sA);
+                                if constexpr (SP) ddw[ro + col] = dd;           // over the step of this cell, which nobody reads again
+                                else store_elem(ddm + ro + col, dd);
+                                // skip term; exactly +0 under the mask
+                                store_elem(dxm + ro + col, cell[4 * PANEL] != 0.0f ? 0.0f : fmaf(dsk, cell[3 * PANEL], cell[0] * sB));
                             }
                         }
                     }
