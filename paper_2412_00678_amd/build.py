@@ -22,7 +22,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # scan2d_api.hip is compiled last: it includes the register table generated from the remarks of the forward units
 UNITS = ["scan2d_elementwise.hip", "scan2d_block.hip", "scan2d_pool.hip", "scan2d_linear.hip", "scan2d_norm.hip", "scan2d_fwd_f32.hip", "scan2d_fwd_bf16.hip", "scan2d_fwd_f32_sp.hip", "scan2d_fwd_bf16_sp.hip", "scan2d_fwd_f32_um.hip", "scan2d_fwd_bf16_um.hip", "scan2d_fwd_bf16_ua.hip", "scan2d_fwd_f32_sp_um.hip", "scan2d_fwd_bf16_sp_um.hip", "scan2d_fwd_bf16_sp_ua.hip",
-         "scan2d_fwd_shared_f32.hip", "scan2d_fwd_shared_bf16.hip", "scan2d_fwd_shared_gate.hip", "scan2d_fwd_shared_f32_cf.hip", "scan2d_fwd_shared_bf16_cf.hip", "scan2d_fwd_av.hip",
+         "scan2d_fwd_shared_f32.hip", "scan2d_fwd_shared_bf16.hip", "scan2d_fwd_shared_gate.hip", "scan2d_fwd_shared_f32_cf.hip", "scan2d_fwd_shared_bf16_cf.hip", "scan2d_fwd_av.hip", "scan2d_fwd_tile16.hip",
          "scan2d_bwd.hip", "scan2d_bwd_f32.hip", "scan2d_bwd_bf16.hip", "scan2d_bwd_f32_sp.hip", "scan2d_bwd_bf16_sp.hip",
          "scan2d_bwd_shared_f32.hip", "scan2d_bwd_shared_bf16.hip", "scan2d_bwd_shared_f32_cf.hip", "scan2d_bwd_shared_bf16_cf.hip", "scan2d_bwd_av.hip"]
 API_UNIT = "scan2d_api.hip"

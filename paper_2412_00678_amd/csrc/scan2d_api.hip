@@ -104,6 +104,7 @@ struct FwdChoice {
     int NG = 0, MPW = 0, panels = 0;
     bool shared = false;          // the form that computes the per-position values once per map (scan2d_fwd_shared.hpp)
     bool cf = false;              // columns first inside the kernel
+    bool tile = false;            // one workgroup per map of at most 16 x 16 positions (scan2d_fwd_tile16.hip)
     FwdKernel kernel = nullptr;
 };
 
@@ -170,6 +171,22 @@ bool fill_small(const scan2d_desc* d, int KS, bool sp, FwdChoice* out) {
     c.NG = 4; c.MPW = 4; c.panels = 1; c.RPB = 1; c.lds_bytes = 0;
     c.kernel = d->dtype == SCAN2D_BF16 ? fwd_small_kernel_bf16(KS, NW, sp) : fwd_small_kernel_f32(KS, NW, sp);
     if (c.kernel == nullptr) return false;
+    *out = c;
+    return true;
+}
+
+// Few maps of at most 16 x 16 positions and 16 states: one workgroup per map, rows and columns as parallel scans
+// (scan2d_fwd_tile16.hip).  With many maps the kernel above wins: it repeats nothing and runs four maps per workgroup.
+#ifndef SCAN2D_TILE16_MAX_MAPS
+#define SCAN2D_TILE16_MAX_MAPS 1024
+#endif
+bool fill_tile16(const scan2d_desc* d, bool sp, FwdChoice* out) {
+    if (d->H > 16 || d->W > 16 || d->N > 16 || (long long)d->Bt * d->Dc > SCAN2D_TILE16_MAX_MAPS) return false;
+    FwdChoice c;
+    c.LG = 16; c.K = 1; c.NW = d->N; c.waves = 4; c.sp = sp;
+    c.exact = true; c.fast = false; c.multi = false; c.tile = true;
+    c.NG = 1; c.MPW = 1; c.panels = 1; c.RPB = 1; c.lds_bytes = 0;
+    c.kernel = fwd_tile16_kernel(d->dtype, sp);
     *out = c;
     return true;
 }
@@ -299,6 +316,7 @@ int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = 
     }
     // narrow maps: one column per lane up to 16 columns; two per lane up to 32 where the width rules out
     // the unguarded wide loads of the 4-column variants (measured: twice as fast as their guarded form)
+    if (fill_tile16(d, sp, out)) return SCAN2D_OK;
     if (d->W <= 16 && fill_small(d, 1, sp, out)) return SCAN2D_OK;
     if (d->W <= 32 && d->W % 4 != 0 && fill_small(d, 2, sp, out)) return SCAN2D_OK;
     bool found = false;
@@ -718,7 +736,7 @@ extern "C" int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* tex
         if (rc != SCAN2D_OK) return rc;
         const long long maps = (long long)desc->Bt * desc->Dc;
         std::snprintf(text, text_bytes, "%sfwd form=%s LG=%d K=%d NW=%d waves=%d RPB=%d NG=%d MPW=%d panels=%d fast=%d exact=%d wgs=%lld lds=%zu workspace=%zu",
-                      fused ? "columns-first(in-kernel) " : "", ch.K < 4 ? "small" : (ch.shared ? "shared" : "general"), ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
+                      fused ? "columns-first(in-kernel) " : "", ch.tile ? "tile16" : (ch.K < 4 ? "small" : (ch.shared ? "shared" : "general")), ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
                       (int)ch.fast, (int)ch.exact, (maps + ch.MPW - 1) / ch.MPW, ch.lds_bytes, fwd_workspace(desc, ch));
         return SCAN2D_OK;
     }

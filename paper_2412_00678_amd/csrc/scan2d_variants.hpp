@@ -86,6 +86,9 @@ FwdKernel fwd_kernel_av_bf16();
 
 // Narrow maps (W <= 32): KS columns per lane, NW = states per lane group of the wave's four.
 FwdKernel fwd_small_kernel_f32(int KS, int NW, bool sp);
+// maps of at most 16 x 16 positions and 16 states, one workgroup per map, both recurrences as parallel scans
+// (scan2d_fwd_tile16.hip)
+FwdKernel fwd_tile16_kernel(int dtype, bool sp);
 FwdKernel fwd_small_kernel_bf16(int KS, int NW, bool sp);
 
 template <typename T, bool SP>

@@ -136,7 +136,10 @@ def test_every_shape_has_a_forward_plan_within_the_hardware_limits(lib):
                     where = f"dtype {dtype} W {W} N {N} Bt {Bt} Dc {Dc} H {H}: {f}"
                     assert f["lds"] <= 160 * 1024, where
                     assert f["waves"] in (4, 8, 16), where
-                    if f["form"] == "small":
+                    if f["form"] == "tile16":                 # few tiny maps: one workgroup per map
+                        assert W <= 16 and H <= 16 and N <= 16 and Bt * Dc <= 1024, where
+                        assert f["wgs"] == Bt * Dc and f["workspace"] == 0, where
+                    elif f["form"] == "small":
                         assert W <= 16 * f["K"] and 4 * f["NW"] >= N, where
                         assert f["wgs"] == -(-Bt * Dc // 4), where
                     else:
@@ -194,6 +197,10 @@ def test_benchmark_configurations_take_the_intended_forms(lib):
     f = plan(lib, lib.Desc(1, 256, 64, 64, 16, 0, 0), lib.PASS_FWD)
     assert (f["form"], f["LG"], f["K"], f["NW"]) == ("shared", 16, 4, 1)
     f = plan(lib, lib.Desc(1, 16, 16, 16, 4, 0, 0), lib.PASS_FWD)
-    assert f["form"] == "small"
+    assert f["form"] == "tile16" and f["wgs"] == 16          # few tiny maps: rows and columns as parallel scans
+    f = plan(lib, lib.Desc(8, 128, 14, 14, 16, 0, 0), lib.PASS_FWD)
+    assert f["form"] == "tile16" and f["wgs"] == 1024
+    f = plan(lib, lib.Desc(64, 128, 14, 14, 16, 0, 0), lib.PASS_FWD)
+    assert f["form"] == "small"                              # many of them: four maps per workgroup, row by row
     b = plan(lib, lib.Desc(4, 512, 128, 192, 16, 0, 0), lib.PASS_BWD)
     assert (b["form"], b["LG"], b["K"], b["NW"]) == ("banded-shared", 16, 12, 1) and b["wgs"] * b["GS"] >= 4 * 512 // 1

@@ -99,6 +99,12 @@ SHAPES = [
     (1, 3, 30, 6, 15, wl.F32, 0.2),        # eight states per lane, last group ragged
     (1, 2, 64, 5, 32, wl.F32, 0.2),        # sixteen states per lane, two columns
     (3, 1, 16, 14, 14, wl.F32, 0.0),       # a partly filled last workgroup
+    (9, 128, 16, 14, 14, wl.F32, 0.2),     # more than 1024 tiny maps: four per workgroup, row by row
+    # at most 1024 maps of at most 16 x 16 positions and 16 states: one workgroup per map, rows and columns as parallel scans
+    (1, 4, 5, 16, 16, wl.F32, 0.3),        # a full tile, states not a multiple of 4
+    (2, 3, 13, 15, 9, wl.BF16, 0.4),       # ragged in both directions
+    (8, 128, 16, 14, 14, wl.F32, 0.0),     # the paper's 14 x 14 grid at 128 channels, batch 8
+    (1, 2, 1, 16, 1, wl.F32, 0.3),         # one column, one state
     # widths that are not a multiple of the columns per lane: the last lane reads across the row end
     (2, 5, 16, 19, 57, wl.F32, 0.3),       # mask rows off the 4-byte boundaries
     (2, 5, 16, 19, 58, wl.BF16, 0.3),      # bf16, even width: rows on 4-byte boundaries, mask rows not
@@ -483,7 +489,7 @@ def _softplus_inputs(w, seed):
 SOFTPLUS_SHAPES = [
     (1, 6, 16, 21, 64, wl.F32, 0.3), (2, 5, 16, 14, 14, wl.BF16, 0.2), (1, 3, 16, 9, 200, wl.BF16, 0.3),
     (1, 4, 5, 7, 45, wl.F32, 0.2), (1, 3, 16, 13, 192, wl.F32, 0.0), (1, 2, 8, 5, 600, wl.F32, 0.3),
-    (1, 16, 16, 64, 256, wl.BF16, 0.5), (3, 2, 4, 6, 30, wl.F32, 0.3),
+    (1, 16, 16, 64, 256, wl.BF16, 0.5), (3, 2, 4, 6, 30, wl.F32, 0.3), (1, 4, 6, 12, 16, wl.F32, 0.3),
     (1, 5, 16, 9, 57, wl.F32, 0.3), (1, 5, 16, 9, 58, wl.BF16, 0.3),   # widths off the lane and mask boundaries
     (2, 5, 16, 11, 55, wl.BF16, 0.3), (1, 3, 16, 7, 201, wl.BF16, 0.0),  # bf16 rows on odd 2-byte boundaries
 ]
