@@ -36,15 +36,10 @@ KERNEL_SOURCES = os.path.join(ROOT, "paper_2412_00678_amd", "csrc")
 
 
 def kernel_source_digest() -> str:
-    """sha256 over the kernel sources: a counter figure recorded for other sources is not this build's."""
-    import hashlib
-    h = hashlib.sha256()
-    for name in sorted(os.listdir(KERNEL_SOURCES)):
-        if name.endswith((".hip", ".hpp")):
-            h.update(name.encode())
-            with open(os.path.join(KERNEL_SOURCES, name), "rb") as f:
-                h.update(f.read())
-    return h.hexdigest()
+    """sha256 over the sources of the scan kernels and their dispatcher (not the probe and the layers around the
+    scan, which the recorded workloads do not run): a counter figure recorded for other sources is not this build's."""
+    from paper_2412_00678_amd.profile_summary import kernel_source_digest as digest
+    return digest()
 
 
 def recorded_traffic(workload: str):

@@ -1,6 +1,6 @@
 // Roofline probe for the box the benchmark runs on: achievable HBM bandwidth (copy and
-// read-only kernels of known size), fp32 vector issue rates (FMA, add, v_exp_f32) against the
-// number of waves per CU, and the launch overhead.  Stand-alone executable:
+// read-only kernels of known size), fp32 vector issue rates (FMA, add, v_exp_f32; a short loop of 8
+// operations and an unrolled stream of 256) against the number of waves per CU, and the launch overhead.  Stand-alone executable:
 //     roofprobe            all measurements
 //     roofprobe --copy N   only N launches of the 1 GiB copy kernel (counter calibration:
 //                          each launch reads 2^30 bytes and writes 2^30 bytes)
@@ -19,6 +19,25 @@ __global__ void k_fma(float* out, int iters, float s) {
         a4 = fmaf(a4, s, 1.f); a5 = fmaf(a5, s, 1.f); a6 = fmaf(a6, s, 1.f); a7 = fmaf(a7, s, 1.f);
     }
     out[blockIdx.x * blockDim.x + threadIdx.x] = a0 + a1 + a2 + a3 + a4 + a5 + a6 + a7;
+}
+// The same with 256 FMAs per trip: 16 independent chains (DEP = false) or one dependent chain (DEP = true).  A wave
+// that is alone on its SIMD pays for the loop control of the short loop above in full; here it issues back to back.
+template <bool DEP>
+__global__ void k_fma_unrolled(float* out, int iters, float s) {
+    float a[16];
+    for (int i = 0; i < 16; ++i) a[i] = threadIdx.x + i;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (DEP) a[0] = fmaf(a[0], s, 1.f);
+                else a[i] = fmaf(a[i], s, 1.f);
+            }
+    }
+    float t = 0;
+    for (int i = 0; i < 16; ++i) t += a[i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = t;
 }
 __global__ void k_add(float* out, int iters, float s) {
     float a0 = threadIdx.x * 1e-3f, a1 = a0 + .1f, a2 = a0 + .2f, a3 = a0 + .3f, a4 = a0 + .4f, a5 = a0 + .5f, a6 = a0 + .6f, a7 = a0 + .7f;
@@ -83,8 +102,13 @@ int main(int argc, char** argv) {
         const float f = time_ms([&] { k_fma<<<g, t>>>(out, iters, 0.999f); }, 3);
         const float ad = time_ms([&] { k_add<<<g, t>>>(out, iters, 0.001f); }, 3);
         const float ex = time_ms([&] { k_exp<<<g, t>>>(out, iters); }, 3);
+        const int ui = iters / 20;
+        const float fu = time_ms([&] { k_fma_unrolled<false><<<g, t>>>(out, ui, 0.999f); }, 3);
+        const float fd = time_ms([&] { k_fma_unrolled<true><<<g, t>>>(out, ui, 0.999f); }, 3);
         std::printf("waves/CU %2d: fma %.2f T lane-op/s, add %.2f T lane-op/s, exp2+sub pair takes %.2f add slots (v_exp_f32 ~ %.2f slots)\n",
                     wpc, lanes * iters * 8 / f / 1e9, lanes * iters * 8 / ad / 1e9, ex / ad, ex / ad - 1.0);
+        std::printf("             256 FMAs per loop trip: %.2f T lane-op/s in 16 independent chains, %.2f T in one dependent chain\n",
+                    lanes * ui * 256 / fu / 1e9, lanes * ui * 256 / fd / 1e9);
     }
     for (int blocks : {CUs * 4, CUs * 8, CUs * 16}) {
         const float c = time_ms([&] { k_copy<<<blocks, 256>>>(a, b, n); }, 5);

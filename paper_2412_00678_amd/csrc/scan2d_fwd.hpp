@@ -88,9 +88,10 @@ struct FwdArgs {
 // for the panel hand-over.
 // SP: the step is computed here, delta = softplus(raw + bias) (a second set of instantiations, so that
 // the plain kernels carry neither the code nor its registers).
-// WAVES: wavefronts per workgroup (4, 8 or 16).  One wave per SIMD reaches only about half of
-// the vector issue rate on this chip, so maps that are few but large spread their states over
-// more waves (smaller NW) rather than leaving SIMDs with a single wave.
+// WAVES: wavefronts per workgroup (4, 8 or 16).  A wave that is alone on its SIMD has nothing to cover
+// its waits (loads, LDS, barriers, DPP chains) and these kernels then reach about half of the vector
+// issue rate, so maps that are few but large spread their states over more waves (smaller NW) rather
+// than leaving SIMDs with a single wave.
 // VGPRs a kernel may spend on rows of loads in flight, per group of tensors.
 #ifndef SCAN2D_PREFETCH_BUDGET_X
 #define SCAN2D_PREFETCH_BUDGET_X 56
