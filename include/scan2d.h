@@ -387,8 +387,8 @@ int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* text, size_t t
 /*
  * Test and tuning hook, not part of the paper's operator: forces a kernel variant for every later call of this
  * process (n = 0 clears the override).  kind 0: the plain forward kernels, values LG,K,NW,WAVES[,RPB];
- * kind 1: the forward kernels that share the per-position work of a map through LDS, values LG,K,NW,WAVES,RPB
- * (the single value 0 = never use that form); kind 2: the banded backward, values LG,K[,WAVES[,GS]].
+ * kind 1: the forward kernels that share the per-position work of a map through LDS, values LG,K,NW,WAVES,RPB[,SKEW]
+ * (SKEW = 1: the tilings with skewed rows, which nothing else selects; the single value 0 = never use that form); kind 2: the banded backward, values LG,K[,WAVES[,GS]].
  * A forced variant that does not fit a descriptor is ignored for that call.  The same overrides can be given
  * once at start-up through the environment (SCAN2D_FWD_VARIANT, SCAN2D_FWD_SHARED, SCAN2D_BWD_VARIANT, comma
  * separated); the environment is read once per process, never by the entry points.  `values` is host memory.

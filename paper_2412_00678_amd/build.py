@@ -22,7 +22,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # scan2d_api.hip is compiled last: it includes the register table generated from the remarks of the forward units
 UNITS = ["scan2d_elementwise.hip", "scan2d_block.hip", "scan2d_pool.hip", "scan2d_linear.hip", "scan2d_norm.hip", "scan2d_fwd_f32.hip", "scan2d_fwd_bf16.hip", "scan2d_fwd_f32_sp.hip", "scan2d_fwd_bf16_sp.hip", "scan2d_fwd_f32_um.hip", "scan2d_fwd_bf16_um.hip", "scan2d_fwd_bf16_ua.hip", "scan2d_fwd_f32_sp_um.hip", "scan2d_fwd_bf16_sp_um.hip", "scan2d_fwd_bf16_sp_ua.hip",
-         "scan2d_fwd_shared_f32.hip", "scan2d_fwd_shared_bf16.hip", "scan2d_fwd_shared_gate.hip", "scan2d_fwd_shared_f32_cf.hip", "scan2d_fwd_shared_bf16_cf.hip", "scan2d_fwd_av.hip", "scan2d_fwd_tile16.hip",
+         "scan2d_fwd_shared_f32.hip", "scan2d_fwd_shared_bf16.hip", "scan2d_fwd_shared_gate.hip", "scan2d_fwd_skew.hip", "scan2d_fwd_shared_f32_cf.hip", "scan2d_fwd_shared_bf16_cf.hip", "scan2d_fwd_av.hip", "scan2d_fwd_tile16.hip",
          "scan2d_bwd.hip", "scan2d_bwd_f32.hip", "scan2d_bwd_bf16.hip", "scan2d_bwd_f32_sp.hip", "scan2d_bwd_bf16_sp.hip",
          "scan2d_bwd_shared_f32.hip", "scan2d_bwd_shared_bf16.hip", "scan2d_bwd_shared_f32_cf.hip", "scan2d_bwd_shared_bf16_cf.hip", "scan2d_bwd_av.hip"]
 API_UNIT = "scan2d_api.hip"
@@ -74,7 +74,7 @@ def _write_regs_inc(regs: dict, path: str) -> None:
 
     Plain kernels <T, LG, K, NW, WAVES, EXACT, FAST, MULTI, SP, MA, UA, AV>: per (K, NW) the largest count over the
     unguarded instantiations (EXACT, FAST, !MULTI, !SP, MA, !UA, !AV), bf16 and fp32 storage.
-    Shared-producer kernels <T, LG, K, NW, NG, WAVES, RPB, SP, UA, CK, CF, KEEPY, GATE>: the count of each (!SP, !UA, CK = 0, !CF, !KEEPY, !GATE) instantiation."""
+    Shared-producer kernels <T, LG, K, NW, NG, WAVES, RPB, SP, UA, CK, CF, KEEPY, GATE, SKEW>: the count of each (!SP, !UA, CK = 0, !CF, !KEEPY, !GATE, !SKEW) instantiation."""
     plain, shared = {}, {}
     for name, n in regs.items():
         m = _KERNEL.search(name)
@@ -83,7 +83,7 @@ def _write_regs_inc(regs: dict, path: str) -> None:
         bf16 = m.group(2) != "f"
         a = [int(t) for t in re.findall(r"L[ib](\d+)E", m.group(3))]
         if m.group(1):
-            if len(a) == 12 and a[6:] == [0, 0, 0, 0, 0, 0]:  # !SP, !UA, forward (not the checkpoint mode), rows first, !KEEPY, !GATE
+            if len(a) == 13 and a[6:] == [0, 0, 0, 0, 0, 0, 0]:  # !SP, !UA, forward (not the checkpoint mode), rows first, !KEEPY, !GATE
                 shared[(int(bf16), *a[:6])] = n
         elif len(a) == 11 and a[4:] == [1, 1, 0, 0, 1, 0, 0]:
             key = (a[1], a[2])

@@ -31,8 +31,8 @@ void tune_read_env() {
     for (int k = 0; k < kTuneKinds; ++k) {
         const char* e = std::getenv(names[k]);
         if (e == nullptr) continue;
-        int v[kTuneMaxValues] = {0, 0, 0, 0, 0};
-        const int n = std::sscanf(e, "%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4]);
+        int v[kTuneMaxValues] = {0, 0, 0, 0, 0, 0};
+        const int n = std::sscanf(e, "%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5]);
         if (n > 0) {
             for (int i = 0; i < kTuneMaxValues; ++i) g_tune[k].v[i].store(v[i], std::memory_order_relaxed);
             g_tune[k].n.store(n, std::memory_order_release);
@@ -104,6 +104,7 @@ struct FwdChoice {
     int NG = 0, MPW = 0, panels = 0;
     bool shared = false;          // the form that computes the per-position values once per map (scan2d_fwd_shared.hpp)
     bool cf = false;              // columns first inside the kernel
+    bool skew = false;            // shared form with skewed rows: lane l of a group on row t - l, no scan across the lanes
     bool tile = false;            // one workgroup per map of at most 16 x 16 positions (scan2d_fwd_tile16.hip)
     FwdKernel kernel = nullptr;
 };
@@ -198,9 +199,11 @@ struct V6 { int LG, K, NW, NG, waves, RPB; };
 const V6 kFwdSharedVariants[] = {SCAN2D_FWD_SHARED_VARIANTS(SCAN2D_X)};
 #undef SCAN2D_X
 
-bool fill_shared(const scan2d_desc* d, int LG, int K, int NW, int waves, int RPB, bool sp, FwdChoice* out, bool cf = false) {
+// skew: the tilings with skewed rows; they read whole dwords along the diagonal, so bf16 rows must have an even width
+bool fill_shared(const scan2d_desc* d, int LG, int K, int NW, int waves, int RPB, bool sp, FwdChoice* out, bool cf = false, bool skew = false) {
     if (NW < 1 || LG < 16 || K < 4 || waves < 1 || RPB < 2) return false;
     if (d->N % NW != 0 || d->W > LG * K) return false;
+    if (skew && (cf || (d->dtype == SCAN2D_BF16 && (d->W % 2) != 0))) return false;
     const int slots = waves * 64 / LG, NG = d->N / NW;
     if (NG > slots || slots % NG != 0) return false;
     FwdChoice c;
@@ -210,8 +213,9 @@ bool fill_shared(const scan2d_desc* d, int LG, int K, int NW, int waves, int RPB
     const double span = (double)(slots + 1) * d->N * d->H * d->W * 4.0;
     if (span >= 2147483648.0) return false;
     const bool ua = d->dtype == SCAN2D_BF16 && (d->W % 2) != 0;
-    c.cf = cf;
-    if (cf) c.kernel = d->dtype == SCAN2D_BF16 ? fwd_shared_kernel_bf16_cf(LG, K, NW, NG, waves, RPB, sp, ua)
+    c.cf = cf; c.skew = skew;
+    if (skew) c.kernel = fwd_skew_kernel(d->dtype == SCAN2D_BF16, LG, K, NW, NG, waves, RPB, sp);
+    else if (cf) c.kernel = d->dtype == SCAN2D_BF16 ? fwd_shared_kernel_bf16_cf(LG, K, NW, NG, waves, RPB, sp, ua)
                                                : fwd_shared_kernel_f32_cf(LG, K, NW, NG, waves, RPB, sp);
     else c.kernel = d->dtype == SCAN2D_BF16 ? fwd_shared_kernel_bf16(LG, K, NW, NG, waves, RPB, sp, ua)
                                             : fwd_shared_kernel_f32(LG, K, NW, NG, waves, RPB, sp);
@@ -293,7 +297,7 @@ double fwd_cost(const scan2d_desc* d, const FwdChoice& c) {
 //     when none of them takes the shape: the caller then runs columns first through transposes)
 int choose_fwd(const scan2d_desc* d, FwdChoice* out, bool sp = false, bool ma = true, bool cf = false) {
     const TuneValues tsh = tune_get(kTuneShared);
-    if (tsh.n >= 5 && fill_shared(d, tsh.v[0], tsh.v[1], tsh.v[2], tsh.v[3], tsh.v[4], sp, out, cf)) return SCAN2D_OK;
+    if (tsh.n >= 5 && fill_shared(d, tsh.v[0], tsh.v[1], tsh.v[2], tsh.v[3], tsh.v[4], sp, out, cf, tsh.n >= 6 && tsh.v[5] != 0 && !cf)) return SCAN2D_OK;
     if (cf) {
         bool any = false;
         double low = 0.0;
@@ -520,7 +524,7 @@ int fwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
     a.NG = ch.NG; a.MPW = ch.MPW; a.panels = ch.panels; a.RPB = ch.RPB;
     const long long wgs = (a.maps + ch.MPW - 1) / ch.MPW;
     if (wgs > 2147483647LL) return SCAN2D_ERR_BAD_SHAPE;
-    if (z != nullptr && y_gated != nullptr && softplus != 0 && ch.shared && !ch.cf) {   // the gate in the same kernel
+    if (z != nullptr && y_gated != nullptr && softplus != 0 && ch.shared && !ch.cf && !ch.skew) {   // the gate in the same kernel
         const bool ua = desc->dtype == SCAN2D_BF16 && (desc->W % 2) != 0;
         const FwdKernel k = desc->dtype == SCAN2D_BF16 ? fwd_shared_kernel_gate_bf16(ch.LG, ch.K, ch.NW, ch.NG, ch.waves, ch.RPB, ua)
                                                        : fwd_shared_kernel_gate_f32(ch.LG, ch.K, ch.NW, ch.NG, ch.waves, ch.RPB);
@@ -736,7 +740,7 @@ extern "C" int scan2d_describe_plan(const scan2d_desc* desc, int pass, char* tex
         if (rc != SCAN2D_OK) return rc;
         const long long maps = (long long)desc->Bt * desc->Dc;
         std::snprintf(text, text_bytes, "%sfwd form=%s LG=%d K=%d NW=%d waves=%d RPB=%d NG=%d MPW=%d panels=%d fast=%d exact=%d wgs=%lld lds=%zu workspace=%zu",
-                      fused ? "columns-first(in-kernel) " : "", ch.tile ? "tile16" : (ch.K < 4 ? "small" : (ch.shared ? "shared" : "general")), ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
+                      fused ? "columns-first(in-kernel) " : "", ch.tile ? "tile16" : (ch.K < 4 ? "small" : (ch.skew ? "skew" : (ch.shared ? "shared" : "general"))), ch.LG, ch.K, ch.NW, ch.waves, ch.RPB, ch.NG, ch.MPW, ch.panels,
                       (int)ch.fast, (int)ch.exact, (maps + ch.MPW - 1) / ch.MPW, ch.lds_bytes, fwd_workspace(desc, ch));
         return SCAN2D_OK;
     }

@@ -68,9 +68,21 @@ __device__ __forceinline__ void carry_apply(float* hl, const float* pl, const fl
 // GATE: the output gate of the block (Fig. 2) in the same kernel: the thread that produces a cell also loads z there,
 // keeps SiLU(z) beside the skip term, and multiplies the unrounded sum over states by it where it stores the cell
 // (p.y_gated; the ungated p.y is stored too unless it is null).
+// SKEW: the row recurrence without a scan across the lanes.  Lane l of a 16-lane group works on row t - l at step t
+// (H + 15 steps instead of H), so the state its row recurrence starts from is the last local state of the lane to its
+// left at the previous step: one multiply-add with a DPP source replaces the decay prefix, the log-step scan and the
+// carry multiply-add.  The LDS buffers keep their layout (a "row" of a batch is a step: the cell of step t and lane
+// l belongs to row t - l); what changes are the global addresses of the producers' loads, of the Bm / Cm loads and
+// of the stores, which follow the diagonal.  Cells of rows outside the map are produced as step = 0, x = 0 (decay 1,
+// input 0: the column state stays 0 above the map) and never stored.  One state per lane, rows first, forward only.
+// A measured alternative, reachable only through the tuning override: the dispatcher never ranks it.  On 256 maps of
+// 256x256 bf16 positions it needs 11-12 vector instructions per (position, channel, state) against 15.4, but every
+// access to memory follows the diagonal in pieces of one lane's K columns, and with 16 columns per lane a compute unit
+// holds one wavefront per SIMD: 309 us (16 lanes x 16 columns) and 658 us (64 lanes x 4 columns) against 125 us.
 template <typename T, int LG, int K, int NW, int NG, int WAVES, int RPB, bool SP, bool UA, int CK = 0, bool CF = false, bool KEEPY = false,
-          bool GATE = false>
+          bool GATE = false, bool SKEW = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const FwdArgs p) {
+    static_assert(!SKEW || ((LG == 16 || LG == 64) && NW == 1 && CK == 0 && !CF && !UA), "skewed rows: 16- or 64-lane groups, one state per lane, forward, rows first");
     constexpr bool YOUT = CK == 0 || KEEPY;               // Cm, the sum over states and y are part of this instantiation
     constexpr bool NOSCAN = CF && CK > 0 && !KEEPY;       // columns-first checkpoint sweep: the row scan feeds nothing
     static_assert(!UA || Elem<T>::kBytes == 2, "UA: bf16 rows on odd 2-byte boundaries");
@@ -135,22 +147,29 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
 
     // ---- the cells this thread produces and later sums: vector v covers VEC columns of one row of a batch
     uint32_t cell_off[NV];     // element offset of the vector inside the batch (row * W + column)
-    int cell_row[NV], cell_col[NV];
+    int cell_row[NV], cell_col[NV], cell_step[NV];
+    static_assert(!SKEW || K % VEC == 0, "a vector of cells stays inside one lane's columns");
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
         const int id = tm + v * TM;
         cell_row[v] = id / VPR;
         cell_col[v] = (id - cell_row[v] * VPR) * VEC;
         cell_off[v] = (uint32_t)cell_row[v] * (uint32_t)W + (uint32_t)cell_col[v];
+        cell_step[v] = cell_row[v];                              // LDS row of the cell inside a batch
+        if constexpr (SKEW) cell_row[v] -= cell_col[v] / K;      // map row of the cell relative to the batch's first step
     }
-    const int nbatch = (H + RPB - 1) / RPB;
+    const int nsteps = SKEW ? H + LG - 1 : H;
+    const int nbatch = (nsteps + RPB - 1) / RPB;
+    auto clamp_row = [&](int i) { return min(max(i, 0), H - 1); };
 
     uint32_t rawx[CT], rawd[CT], rawm[CT], rawz[GATE ? CT : 1];
     // element loads: any alignment, any width; a load past the end of the tensor returns 0
     auto request = [&](int batch) {
-        const uint32_t ro = (uint32_t)batch * (uint32_t)(RPB * W);
+        const uint32_t ro = SKEW ? 0u : (uint32_t)batch * (uint32_t)(RPB * W);
 #pragma unroll
-        for (int v = 0; v < NV; ++v)
+        for (int v = 0; v < NV; ++v) {
+            if constexpr (SKEW)          // the cell's own row (clamped into the map: cells outside are produced as zeros)
+                cell_off[v] = (uint32_t)clamp_row(batch * RPB + cell_row[v]) * (uint32_t)W + (uint32_t)cell_col[v];
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 const uint32_t lo = xlane + cell_off[v] + (uint32_t)e;
@@ -167,20 +186,23 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                 if (has_mask)
                     rawm[v * VEC + e] = (uint32_t)(uint8_t)__builtin_amdgcn_raw_buffer_load_b8(rsm, mlane + cell_off[v] + (uint32_t)e, ro, 0);
             }
+        }
     };
     float sk_cur[CT], sk_next[CT], gt_cur[GATE ? CT : 1], gt_next[GATE ? CT : 1];
-    auto produce = [&](int buf) {
+    auto produce = [&](int buf, int batch) {
         float* base = pp + buf * PP_BUF + map_slot * PP_MAP;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            float* row = base + cell_row[v] * PP_ROW + lds_col<LG, K>(cell_col[v]);
+            float* row = base + cell_step[v] * PP_ROW + lds_col<LG, K>(cell_col[v]);
+            const bool inside = !SKEW || (unsigned)(batch * RPB + cell_row[v]) < (unsigned)H;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 const int k = v * VEC + e;
                 float dl = EB == 4 ? __uint_as_float(rawd[k]) : __uint_as_float(rawd[k] << 16);
                 if constexpr (SP) dl = softplus_f32(dl + dbias);
+                if constexpr (SKEW) dl = inside ? dl : 0.0f;
                 const float xv = EB == 4 ? __uint_as_float(rawx[k]) : __uint_as_float(rawx[k] << 16);
-                const float xe = rawm[k] != 0u ? 0.0f : xv;     // select: nothing under the mask leaks
+                const float xe = (rawm[k] != 0u || !inside) ? 0.0f : xv;     // select: nothing under the mask leaks
                 row[e] = dl;
                 row[PANEL + e] = dl * xe;
                 sk_next[k] = dsk * xe;
@@ -200,6 +222,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
     const uint32_t lcol = col0 < W ? (uint32_t)col0 : 0u;      // lanes past the last column mirror lane 0
     uint32_t rB[PDS][NW][XWR], rC[PDS][NW][XWR];
     auto lds = [&](rsrc_t rs, int s, uint32_t row_off, uint32_t* r) {
+        if constexpr (SKEW) {          // row_off differs from lane to lane: it is part of the vector offset
+            buffer_load_words<XW>(rs, (slane + lcol + row_off) * EB, (uint32_t)s * (uint32_t)HW * EB, r);
+            return;
+        }
         const uint32_t uni = (uint32_t)s * (uint32_t)HW + row_off;
         if constexpr (UA) buffer_load_words<XWR>(rs, ((slane + lcol + uni) * EB) & ~3u, 0u, r);   // rounded down to a dword
         else buffer_load_words<XW>(rs, (slane + lcol) * EB, uni * EB, r);
@@ -221,19 +247,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
     for (int s = 0; s < NW; ++s)
 #pragma unroll
         for (int j = 0; j < K; ++j) h[s][j] = 0.0f;            // h[-1, j] = 0
+    float hrow[NW];                                            // SKEW: row state at this lane's last column, previous step
+#pragma unroll
+    for (int s = 0; s < NW; ++s) hrow[s] = 0.0f;
 
     // ---- prologue: batch 0 into LDS, batch 1 requested, first rows of Bm / Cm in flight
     request(0);
 #pragma unroll
     for (int d = 0; d < PDS; ++d) {
-        const uint32_t ro = (uint32_t)min(d, H - 1) * (uint32_t)W;
+        const uint32_t ro = (uint32_t)clamp_row(d - (SKEW ? l : 0)) * (uint32_t)W;
 #pragma unroll
         for (int s = 0; s < NW; ++s) {
             lds(rsB, s, ro, rB[d][s]);
             if constexpr (YOUT) lds(rsC, s, ro, rC[d][s]);
         }
     }
-    produce(0);
+    produce(0, 0);
 #pragma unroll
     for (int k = 0; k < CT; ++k) {
         sk_cur[k] = sk_next[k];
@@ -263,8 +292,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
             const int i = row0 + r;
             const int set = r & 1, SS = r % PDS;
             if (r + 1 < RPB) fetch_row(buf, r + 1, set ^ 1);
-            const uint32_t cur = (uint32_t)min(i, H - 1) * (uint32_t)W;
-            const uint32_t nxt = (uint32_t)min(i + PDS, H - 1) * (uint32_t)W;
+            const uint32_t cur = (uint32_t)min(i, H - 1) * (uint32_t)W;                    // only the UA form reads it
+            const uint32_t nxt = (uint32_t)(SKEW ? clamp_row(i + PDS - l) : min(i + PDS, H - 1)) * (uint32_t)W;
             float yacc[K];
 #pragma unroll
             for (int s0 = 0; s0 < NW; s0 += SC) {
@@ -285,6 +314,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                     } else {
                         hl[t][0] = dxq[set][0] * get_elem<T, K>(uB, 0);
                     }
+                    if constexpr (SKEW) {
+                        // Eq. 5 across the lane boundary: the row this lane works on was the left neighbour's row one
+                        // step ago, and hrow holds the state that neighbour ended with.  The group's first lane has no
+                        // source lane and is not written: its row starts from 0.
+                        if constexpr (LG == 64)
+                            asm volatile("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 wave_shr:1 row_mask:0xf bank_mask:0xf"
+                                         : "+v"(hl[t][0]) : "v"(hrow[s]), "v"(a[t][0]));
+                        else
+                            asm volatile("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 row_shr:1 row_mask:0xf bank_mask:0xf"
+                                         : "+v"(hl[t][0]) : "v"(hrow[s]), "v"(a[t][0]));
+#pragma unroll
+                        for (int j = 1; j < K; ++j) hl[t][j] = fmaf(a[t][j], hl[t][j - 1], dxq[set][j] * get_elem<T, K>(uB, j));
+                        hrow[s] = hl[t][K - 1];
+                        lds(rsB, s, nxt, rB[SS][s]);
+                        continue;
+                    }
                     pl[t][0] = a[t][0];
                     if constexpr (!NOSCAN) {
 #pragma unroll
@@ -299,19 +344,20 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                         Hh[t] = hl[t][K - 1];
                     }
                 }
-                if constexpr (!NOSCAN) {
+                if constexpr (!NOSCAN && !SKEW) {
                     if constexpr (kDppApply) group_scan_nocarry<LG, SC>(P, Hh, cin); else group_scan<LG, SC>(P, Hh, cin);
                 }
 #pragma unroll
                 for (int t = 0; t < SC; ++t) {
                     const int s = s0 + t;
-                    if constexpr (kDppApply && LG != 32 && !NOSCAN) carry_apply<LG, K>(hl[t], pl[t], Hh[t]);   // Eq. 5
+                    if constexpr (kDppApply && LG != 32 && !NOSCAN && !SKEW) carry_apply<LG, K>(hl[t], pl[t], Hh[t]);   // Eq. 5
                     uint32_t uC[XW];
                     if constexpr (YOUT) unpacks(rC[SS][s], s, cur, uC);
                     if constexpr (!NOSCAN) {
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
-                            const float hh = (j == K - 1) ? Hh[t] : ((kDppApply && LG != 32) ? hl[t][j] : fmaf(pl[t][j], cin[t], hl[t][j]));
+                            const float hh = SKEW ? hl[t][j]
+                                           : (j == K - 1) ? Hh[t] : ((kDppApply && LG != 32) ? hl[t][j] : fmaf(pl[t][j], cin[t], hl[t][j]));
                             if constexpr (!CF) fma_inplace(h[s][j], a[t][j], hh);                   // Eq. 6
                             if constexpr (YOUT) {
                                 const float cv = get_elem<T, K>(uC, j);
@@ -360,7 +406,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
         }
         // the next batch's cells: produced before the barrier (its LDS buffer was last read one batch ago,
         // before the previous barrier), then the loads of the batch after that are requested
-        produce(buf ^ 1);
+        produce(buf ^ 1, bt + 1);
         request(min(bt + 2, nbatch - 1));
         __syncthreads();
         fetch_row(buf ^ 1, 0, 0);
@@ -369,7 +415,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
             const float* ybase = ypart + buf * YP_BUF + (slot - sg) * PANEL;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                const float* src = ybase + cell_row[v] * YP_ROW + lds_col<LG, K>(cell_col[v]);
+                const float* src = ybase + cell_step[v] * YP_ROW + lds_col<LG, K>(cell_col[v]);
                 float acc[VEC];
                 if constexpr (VEC == 4) {
                     float4 t0 = *reinterpret_cast<const float4*>(src);
@@ -393,7 +439,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                     for (int g = 1; g < NG; ++g) acc[0] += src[g * PANEL];
                 }
                 const int i = row0 + cell_row[v];
-                if (i < H) {
+                if ((unsigned)i < (unsigned)H) {
                     float out[VEC];
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) out[e] = acc[e] + sk_cur[v * VEC + e];

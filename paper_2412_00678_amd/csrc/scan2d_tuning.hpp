@@ -2,8 +2,8 @@
 // and can afterwards only be changed through scan2d_debug_force_variant (a test hook): the entry points
 // themselves never call getenv.
 //   SCAN2D_FWD_VARIANT = LG,K,NW,WAVES[,RPB]     force a variant of the plain forward kernel
-//   SCAN2D_FWD_SHARED  = LG,K,NW,WAVES,RPB       force a variant of the shared-producer forward kernel
-//                        ("0" = never use that form)
+//   SCAN2D_FWD_SHARED  = LG,K,NW,WAVES,RPB[,SKEW] force a variant of the shared-producer forward kernel (SKEW = 1: its
+//                        skewed-row tilings; "0" alone = never use that form)
 //   SCAN2D_BWD_VARIANT = LG,K[,WAVES[,GS]]       force a variant of the banded backward
 #pragma once
 
@@ -11,7 +11,7 @@
 
 namespace scan2d {
 
-enum { kTuneFwd = 0, kTuneShared = 1, kTuneBwd = 2, kTuneKinds = 3, kTuneMaxValues = 5 };
+enum { kTuneFwd = 0, kTuneShared = 1, kTuneBwd = 2, kTuneKinds = 3, kTuneMaxValues = 6 };
 
 struct TuneSlot {
     std::atomic<int> n{0};                       // number of values given (0 = no override)
@@ -21,7 +21,7 @@ struct TuneSlot {
 // Snapshot of one override (plain ints, taken once per call).
 struct TuneValues {
     int n = 0;
-    int v[kTuneMaxValues] = {0, 0, 0, 0, 0};
+    int v[kTuneMaxValues] = {0, 0, 0, 0, 0, 0};
 };
 
 TuneValues tune_get(int kind);                   // reads the environment on first use

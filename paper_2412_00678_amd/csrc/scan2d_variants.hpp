@@ -47,6 +47,13 @@ using FwdKernel = void (*)(const FwdArgs);
     /* N = 32 */ X(64, 4, 2, 16, 16, 4) X(64, 4, 4, 8, 8, 4) X(16, 4, 2, 16, 4, 4) X(16, 8, 2, 16, 4, 4) X(16, 4, 4, 8, 4, 4) \
     /* N = 64 */ X(64, 4, 4, 16, 16, 4) X(16, 4, 4, 16, 4, 4) X(16, 8, 4, 16, 4, 2)
 
+// Tilings of the same kernel with skewed rows (lane l of a group on row t - l: no scan across the lanes), all with
+// one state per lane: (LG, K, NW, NG, WAVES, RPB).  Only the tuning override selects them.
+#define SCAN2D_FWD_SKEW_VARIANTS(X) \
+    X(16, 16, 1, 16, 4, 4) X(16, 8, 1, 16, 4, 4) X(64, 4, 1, 16, 16, 4)
+// nullptr when the tiling is not compiled
+FwdKernel fwd_skew_kernel(bool bf16, int LG, int K, int NW, int NG, int waves, int RPB, bool sp);
+
 FwdKernel fwd_shared_kernel_f32(int LG, int K, int NW, int NG, int waves, int RPB, bool sp);
 FwdKernel fwd_shared_kernel_bf16(int LG, int K, int NW, int NG, int waves, int RPB, bool sp, bool ua);
 // The columns-first instantiations of the same tilings.
@@ -62,6 +69,15 @@ inline FwdKernel lookup_fwd_shared_kernel(int LG, int K, int NW, int NG, int wav
 #define SCAN2D_X(lg, k, nw, ng, wv, rpb) \
     if (LG == lg && K == k && NW == nw && NG == ng && waves == wv && RPB == rpb) return scan2d_fwd_shared_kernel<T, lg, k, nw, ng, wv, rpb, SP, UA, 0, CF, false, GATE>;
     SCAN2D_FWD_SHARED_VARIANTS(SCAN2D_X)
+#undef SCAN2D_X
+    return nullptr;
+}
+
+template <typename T, bool SP>
+inline FwdKernel lookup_fwd_skew_kernel(int LG, int K, int NW, int NG, int waves, int RPB) {
+#define SCAN2D_X(lg, k, nw, ng, wv, rpb) \
+    if (LG == lg && K == k && NW == nw && NG == ng && waves == wv && RPB == rpb) return scan2d_fwd_shared_kernel<T, lg, k, nw, ng, wv, rpb, SP, false, 0, false, false, false, true>;
+    SCAN2D_FWD_SKEW_VARIANTS(SCAN2D_X)
 #undef SCAN2D_X
     return nullptr;
 }

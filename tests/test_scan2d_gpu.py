@@ -38,8 +38,9 @@ def run_fwd(s2d, inp, dtype, variant=None):
     with s2d.forced_variant(kind, variant):
         if kind == s2d.TUNE_FWD_SHARED:                   # the forced form must be the one that runs
             plan = s2d.describe_plan(s2d.make_desc(d["x"], d["A"]), s2d.PASS_FWD)
-            LG, K, NW, waves, rpb = (int(t) for t in variant.split(","))
-            assert f"form=shared LG={LG} K={K} NW={NW} waves={waves} RPB={rpb} " in plan, plan
+            LG, K, NW, waves, rpb, *skew = (int(t) for t in variant.split(","))
+            form = "skew" if skew and skew[0] else "shared"
+            assert f"form={form} LG={LG} K={K} NW={NW} waves={waves} RPB={rpb} " in plan, plan
         y = s2d.scan2d_fwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
         torch.cuda.synchronize()
     return s2d.to_host(y)
@@ -194,6 +195,23 @@ SHARED_CASES = [
 def test_every_shared_producer_variant(s2d, variant, shape, dtype):
     Bt, Dc, N, H, W = shape
     check_fwd(s2d, wl.Workload("shared", Bt, Dc, N, H, W, dtype, mask_frac=0.25), seed=6, variant="shared:" + variant)
+
+
+# The same kernel with skewed rows (lane l of a group works on row t - l, no scan across the lanes; a measured
+# alternative that only the override selects): LG,K,NW,WAVES,RPB,1.  Maps shorter than the skew, heights off the
+# batch grid, even widths below the panel (bf16 rows of odd width are refused: the override is then ignored).
+SKEW_CASES = [
+    ("16,16,1,4,4,1", (1, 3, 16, 37, 256)), ("16,16,1,4,4,1", (2, 2, 16, 5, 250)), ("16,16,1,4,4,1", (1, 2, 16, 70, 202)),
+    ("16,8,1,4,4,1", (2, 3, 16, 19, 100)), ("16,8,1,4,4,1", (1, 1, 16, 3, 8)), ("16,8,1,4,4,1", (1, 2, 16, 1, 66)),
+    ("64,4,1,16,4,1", (1, 2, 16, 37, 256)), ("64,4,1,16,4,1", (1, 2, 16, 5, 202)), ("64,4,1,16,4,1", (1, 3, 16, 130, 130)),
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("variant,shape", SKEW_CASES, ids=[f"skew-{v}-{s[3]}x{s[4]}" for v, s in SKEW_CASES])
+def test_skewed_row_variants(s2d, variant, shape, dtype):
+    Bt, Dc, N, H, W = shape
+    check_fwd(s2d, wl.Workload("skew", Bt, Dc, N, H, W, dtype, mask_frac=0.25), seed=8, variant="shared:" + variant)
 
 
 # ------------------------------------------------------------------ mask / indexing: bit-exact
