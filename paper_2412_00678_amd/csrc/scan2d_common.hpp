@@ -250,7 +250,9 @@ __device__ __forceinline__ void fma_inplace(float& h, float a, float add) {
 //      entering this lane.  P is consumed (afterwards: the product of the decays up to and
 //      including this lane inside its DPP row).
 // A lane whose source lane does not exist (or whose row is switched off by row_mask) is not
-// written by a DPP instruction, which is exactly the identity element of the recurrence.
+// written by a DPP instruction, which is exactly the identity element of the recurrence.  The
+// copy that fetches the carry sets bound_ctrl instead: such a lane then reads 0, so C needs no
+// initial value.
 // Each step is H += P * H[lane-d]; P *= P[lane-d], written as VOP2 instructions with a DPP
 // source so that the lane movement costs no extra instruction.  S independent recurrences
 // are interleaved in one block: that keeps the two wait states the hardware requires between
@@ -258,8 +260,8 @@ __device__ __forceinline__ void fma_inplace(float& h, float a, float add) {
 #define SCAN2D_SHR(n) " row_shr:" #n " row_mask:0xf bank_mask:0xf\n\t"
 #define SCAN2D_BC15 " row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
 #define SCAN2D_BC31 " row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-#define SCAN2D_CIN16 " row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
-#define SCAN2D_CIN64 " wave_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+#define SCAN2D_CIN16 " row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0\n\t"
+#define SCAN2D_CIN64 " wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0\n\t"
 
 #define SCAN2D_S1_STEP(M) "v_fmac_f32_dpp %0, %0, %1" M "v_mul_f32_dpp %1, %1, %1" M "s_nop 0\n\t"
 #define SCAN2D_S1_LAST(M) "v_fmac_f32_dpp %0, %0, %1" M "s_nop 1\n\t"
@@ -275,53 +277,51 @@ __device__ __forceinline__ void fma_inplace(float& h, float a, float add) {
 
 template <int LG>
 __device__ __forceinline__ void group_scan1(float& P0, float& H0, float& C0) {
-    C0 = 0.0f;
     if constexpr (LG == 32) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
                      SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_STEP(SCAN2D_SHR(8))
                      SCAN2D_S1_LAST(SCAN2D_BC15)
                      "v_mov_b32_dpp %2, %0" SCAN2D_CIN64
-                     : "+v"(H0), "+v"(P0), "+v"(C0));
+                     : "+v"(H0), "+v"(P0), "=&v"(C0));
     } else if constexpr (LG == 16) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
                      SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_LAST(SCAN2D_SHR(8))
                      "v_mov_b32_dpp %2, %0" SCAN2D_CIN16
-                     : "+v"(H0), "+v"(P0), "+v"(C0));
+                     : "+v"(H0), "+v"(P0), "=&v"(C0));
     } else {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S1_STEP(SCAN2D_SHR(1)) SCAN2D_S1_STEP(SCAN2D_SHR(2))
                      SCAN2D_S1_STEP(SCAN2D_SHR(4)) SCAN2D_S1_STEP(SCAN2D_SHR(8))
                      SCAN2D_S1_STEP(SCAN2D_BC15) SCAN2D_S1_LAST(SCAN2D_BC31)
                      "v_mov_b32_dpp %2, %0" SCAN2D_CIN64
-                     : "+v"(H0), "+v"(P0), "+v"(C0));
+                     : "+v"(H0), "+v"(P0), "=&v"(C0));
     }
 }
 
 template <int LG>
 __device__ __forceinline__ void group_scan2(float& P0, float& P1, float& H0, float& H1, float& C0, float& C1) {
-    C0 = 0.0f; C1 = 0.0f;
     if constexpr (LG == 32) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
                      SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_STEP(SCAN2D_SHR(8))
                      SCAN2D_S2_LAST(SCAN2D_BC15)
                      "v_mov_b32_dpp %4, %0" SCAN2D_CIN64 "v_mov_b32_dpp %5, %1" SCAN2D_CIN64
-                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "+v"(C0), "+v"(C1));
+                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "=&v"(C0), "=&v"(C1));
     } else if constexpr (LG == 16) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
                      SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_LAST(SCAN2D_SHR(8))
                      "v_mov_b32_dpp %4, %0" SCAN2D_CIN16 "v_mov_b32_dpp %5, %1" SCAN2D_CIN16
-                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "+v"(C0), "+v"(C1));
+                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "=&v"(C0), "=&v"(C1));
     } else {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S2_STEP(SCAN2D_SHR(1)) SCAN2D_S2_STEP(SCAN2D_SHR(2))
                      SCAN2D_S2_STEP(SCAN2D_SHR(4)) SCAN2D_S2_STEP(SCAN2D_SHR(8))
                      SCAN2D_S2_STEP(SCAN2D_BC15) SCAN2D_S2_LAST(SCAN2D_BC31)
                      "v_mov_b32_dpp %4, %0" SCAN2D_CIN64 "v_mov_b32_dpp %5, %1" SCAN2D_CIN64
-                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "+v"(C0), "+v"(C1));
+                     : "+v"(H0), "+v"(H1), "+v"(P0), "+v"(P1), "=&v"(C0), "=&v"(C1));
     }
 }
 
@@ -329,7 +329,6 @@ template <int LG>
 __device__ __forceinline__ void group_scan4(float& P0, float& P1, float& P2, float& P3,
                                             float& H0, float& H1, float& H2, float& H3,
                                             float& C0, float& C1, float& C2, float& C3) {
-    C0 = 0.0f; C1 = 0.0f; C2 = 0.0f; C3 = 0.0f;
     if constexpr (LG == 32) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
@@ -338,7 +337,7 @@ __device__ __forceinline__ void group_scan4(float& P0, float& P1, float& P2, flo
                      "v_mov_b32_dpp %8, %0" SCAN2D_CIN64 "v_mov_b32_dpp %9, %1" SCAN2D_CIN64
                      "v_mov_b32_dpp %10, %2" SCAN2D_CIN64 "v_mov_b32_dpp %11, %3" SCAN2D_CIN64
                      : "+v"(H0), "+v"(H1), "+v"(H2), "+v"(H3), "+v"(P0), "+v"(P1), "+v"(P2), "+v"(P3),
-                       "+v"(C0), "+v"(C1), "+v"(C2), "+v"(C3));
+                       "=&v"(C0), "=&v"(C1), "=&v"(C2), "=&v"(C3));
     } else if constexpr (LG == 16) {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
@@ -346,7 +345,7 @@ __device__ __forceinline__ void group_scan4(float& P0, float& P1, float& P2, flo
                      "v_mov_b32_dpp %8, %0" SCAN2D_CIN16 "v_mov_b32_dpp %9, %1" SCAN2D_CIN16
                      "v_mov_b32_dpp %10, %2" SCAN2D_CIN16 "v_mov_b32_dpp %11, %3" SCAN2D_CIN16
                      : "+v"(H0), "+v"(H1), "+v"(H2), "+v"(H3), "+v"(P0), "+v"(P1), "+v"(P2), "+v"(P3),
-                       "+v"(C0), "+v"(C1), "+v"(C2), "+v"(C3));
+                       "=&v"(C0), "=&v"(C1), "=&v"(C2), "=&v"(C3));
     } else {
         asm volatile("s_nop 1\n\t"
                      SCAN2D_S4_STEP(SCAN2D_SHR(1)) SCAN2D_S4_STEP(SCAN2D_SHR(2))
@@ -355,7 +354,7 @@ __device__ __forceinline__ void group_scan4(float& P0, float& P1, float& P2, flo
                      "v_mov_b32_dpp %8, %0" SCAN2D_CIN64 "v_mov_b32_dpp %9, %1" SCAN2D_CIN64
                      "v_mov_b32_dpp %10, %2" SCAN2D_CIN64 "v_mov_b32_dpp %11, %3" SCAN2D_CIN64
                      : "+v"(H0), "+v"(H1), "+v"(H2), "+v"(H3), "+v"(P0), "+v"(P1), "+v"(P2), "+v"(P3),
-                       "+v"(C0), "+v"(C1), "+v"(C2), "+v"(C3));
+                       "=&v"(C0), "=&v"(C1), "=&v"(C2), "=&v"(C3));
     }
 }
 

@@ -338,6 +338,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_fwd_shared_kernel(const Fwd
                             pl[t][j] = pl[t][j - 1] * a[t][j];
                         }
                     }
+                    // the refill of a ring slot stays behind the last use of the slot's old content (every instruction
+                    // but a memory read may still cross): hoisted above it, the load needs a register pair of its own
+                    // and the ring is rotated with copies at the end of every batch
+                    __builtin_amdgcn_sched_barrier(0x7CF);
                     lds(rsB, s, nxt, rB[SS][s]);
                     if constexpr (!NOSCAN) {
                         P[t] = pl[t][K - 1];
