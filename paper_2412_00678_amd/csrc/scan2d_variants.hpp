@@ -40,6 +40,7 @@ using FwdKernel = void (*)(const FwdArgs);
 // NG = N / NW lane groups per map, RPB rows between two barriers.
 #define SCAN2D_FWD_SHARED_VARIANTS(X)                                                     \
     X(64, 4, 2, 8, 8, 4) X(64, 4, 2, 8, 8, 8) X(64, 4, 1, 16, 16, 4)                      \
+    /* 257 to 1024 columns */ X(64, 8, 1, 16, 16, 2) X(64, 8, 2, 8, 8, 2) X(64, 12, 2, 8, 8, 2) X(64, 16, 2, 8, 8, 2) \
     X(16, 12, 1, 16, 4, 4) X(16, 12, 2, 8, 4, 2) X(16, 8, 1, 16, 4, 4) X(16, 8, 2, 8, 4, 2) \
     X(16, 4, 1, 16, 4, 4) X(16, 4, 2, 8, 4, 4) X(16, 4, 4, 4, 4, 4) X(16, 4, 8, 2, 4, 4)   \
     /* N = 8 */ X(64, 4, 1, 8, 8, 4) X(16, 4, 1, 8, 4, 4) X(16, 4, 2, 4, 4, 4) X(16, 8, 1, 8, 4, 4) X(16, 12, 1, 8, 4, 4) \

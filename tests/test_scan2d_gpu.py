@@ -180,6 +180,10 @@ SHARED_CASES = [
     ("16,8,1,4,4", (1, 3, 16, 9, 128)), ("16,8,2,4,2", (2, 3, 16, 9, 121)),
     ("16,4,1,4,4", (1, 3, 16, 11, 64)), ("16,4,2,4,4", (1, 5, 16, 11, 57)), ("16,4,4,4,4", (1, 7, 16, 11, 56)),
     ("16,4,8,4,4", (1, 11, 16, 11, 50)), ("16,4,8,4,4", (3, 64, 16, 5, 33)),
+    # 257 to 1024 columns: 8, 12 and 16 columns per lane of a wave-wide group
+    ("64,8,1,16,2", (1, 2, 16, 9, 512)), ("64,8,1,16,2", (1, 3, 16, 5, 301)), ("64,8,2,8,2", (2, 2, 16, 7, 334)),
+    ("64,12,2,8,2", (1, 2, 16, 5, 768)), ("64,12,2,8,2", (1, 2, 16, 6, 601)), ("64,16,2,8,2", (1, 2, 16, 5, 1024)),
+    ("64,16,2,8,2", (1, 2, 16, 3, 903)),
     # N = 8, 4, 32, 64
     ("64,4,1,8,4", (1, 3, 8, 13, 256)), ("16,4,1,4,4", (1, 3, 8, 9, 60)), ("16,4,2,4,4", (1, 7, 8, 9, 61)),
     ("16,8,1,4,4", (1, 3, 8, 9, 100)), ("16,12,1,4,4", (1, 3, 8, 9, 180)),
@@ -765,7 +769,7 @@ CF_SHAPES = [
     (2, 5, 16, 21, 64, wl.F32, 0.3), (2, 5, 16, 14, 9, wl.BF16, 0.3), (1, 3, 16, 70, 33, wl.BF16, 0.4),
     (1, 4, 5, 45, 7, wl.F32, 0.0), (1, 3, 16, 130, 190, wl.F32, 0.3), (3, 2, 4, 1, 50, wl.F32, 0.3), (1, 2, 8, 37, 1, wl.F32, 0.3),
     # in-kernel form: wave-wide forward tiling on odd bf16 rows with the ragged 12-column backward, 32 and 64 states,
-    # several maps per workgroup, a width that needs column panels (transposed form)
+    # several maps per workgroup, a width whose backward needs column panels (transposed form; the forward stays in-kernel)
     (1, 2, 16, 33, 191, wl.BF16, 0.3), (2, 3, 16, 37, 50, wl.F32, 0.5), (1, 2, 32, 20, 40, wl.F32, 0.3), (1, 2, 64, 9, 30, wl.BF16, 0.3),
     (3, 7, 16, 56, 56, wl.BF16, 0.2), (1, 2, 16, 12, 300, wl.F32, 0.3),
 ]
