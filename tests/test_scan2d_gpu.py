@@ -218,6 +218,27 @@ def test_skewed_row_variants(s2d, variant, shape, dtype):
     check_fwd(s2d, wl.Workload("skew", Bt, Dc, N, H, W, dtype, mask_frac=0.25), seed=8, variant="shared:" + variant)
 
 
+# A grid wider than 256 columns at full size, as bench-like launches see it (one map per compute unit, 256 maps): the
+# oracle computes three of the 256 channels, the tiling must be the shared-producer one with 8 or 12 columns per lane.
+@pytest.mark.parametrize("H,W,K", [(400, 400, 8), (150, 600, 12)])
+def test_wide_grid_at_full_size_on_sampled_channels(s2d, H, W, K):
+    import torch
+    w = wl.Workload("wide_full", 1, 256, 16, H, W, wl.BF16, mask_frac=0.5)
+    inp = wl.make_inputs(w, seed=12)
+    print(f"wide grid Bt=1 Dc=256 N=16 H={H} W={W} bf16", flush=True)
+    d = s2d.to_device(inp, w.dtype)
+    plan = s2d.describe_plan(s2d.make_desc(d["x"], d["A"]), s2d.PASS_FWD)
+    assert f"form=shared LG=64 K={K} " in plan, plan
+    y = s2d.scan2d_fwd(d["x"], d["delta"], d["A"], d["Bm"], d["Cm"], d["Dskip"], d["mask"])
+    torch.cuda.synchronize()
+    got = s2d.to_host(y)
+    for c in (0, 131, 255):
+        ref = oracle.scan2d_fwd(inp["x"][:, c:c + 1], inp["delta"][:, c:c + 1], inp["A"][c:c + 1], inp["Bm"], inp["Cm"],
+                                inp["Dskip"][c:c + 1], inp["mask"], dtype=w.dtype)
+        err = rel_err(wl.to_float(got[:, c:c + 1], w.dtype), wl.to_float(ref, w.dtype))
+        assert err <= TOL[w.dtype], f"channel {c}: rel err {err:.3e}"
+
+
 # ------------------------------------------------------------------ mask / indexing: bit-exact
 
 @pytest.mark.parametrize("H,W", [(40, 72), (19, 57), (9, 55), (7, 33), (5, 250)])   # also mask and bf16 tensors that end inside a dword
