@@ -276,7 +276,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
     else if (N <= 16 && K == 16) { waves = 4; NW = 4; }     // widest maps: LDS bounds the workgroup size
     // (one panel of 16 states: two states per lane on 8 waves with the shared-producer main sweep, measured 13 % faster
     // than 16 waves of one state that each repeat the per-position work: 256 maps of 256x256 bf16 2.11 -> 1.83 ms)
-    else if (N == 16 && K == 4 && pl.panels == 1 && !av && want_shared != 0 && force_waves != 16) { waves = 8; NW = 2; }
+    else if (N == 16 && K == 4 && !av && want_shared != 0 && force_waves != 16) { waves = 8; NW = 2; }
     else if (N <= 16 && K == 4 && force_waves != 8) { waves = 16; NW = 1; }
     else if (N <= 16) { waves = 8; NW = 2; }
     else { waves = 16; NW = 4; }
@@ -286,7 +286,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
     pl.step_outside = sp;
     pl.fast = fast;
     // the main sweep that shares the per-position work through LDS, where it exists for this tiling (N = NG * NW)
-    if (want_shared != 0 && N % NW == 0 && pl.panels == 1 && !av) {
+    if (want_shared != 0 && N % NW == 0 && !av) {              // (its kernels take column panels too)
         BwdKernels ks;
         if (cf) ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16_cf(LG, K, NW, N / NW, waves, W, sp)
                                              : bwd_shared_kernels_f32_cf(LG, K, NW, N / NW, waves, W, sp);

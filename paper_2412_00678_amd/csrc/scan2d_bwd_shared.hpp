@@ -23,6 +23,10 @@
 // is accumulated by the producing threads and summed per wavefront: both in a fixed order, so results are
 // bit-reproducible.  K only has to be even here (the scanning lanes load no mask bytes), which allows
 // half-wave groups of 6 columns on 192-wide maps: band state of 96 registers, two waves per SIMD.
+// Column panels (maps wider than LG*K columns, one launch per panel, right to left): p.cb is the panel's first column;
+// the row-scan state entering from the left panel (p.hc_in, left by the checkpoint sweeps) starts lane 0's rebuilt
+// row recurrence, a*q entering from the right panel (p.qc_in) joins the last lane's reverse recurrence, a*q of the
+// panel's first column goes to p.qc_out, and dA / dDskip add to what the panels to the right have left (p.accum).
 #pragma once
 
 #include "scan2d_bwd_kernels.hpp"
@@ -159,9 +163,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
     const int H = p.H, W = p.W, N = p.N;
     const size_t HW = (size_t)H * W;
     const int n0 = sg * NW;
-    const int col0 = l * K;
+    const int col0 = p.cb + l * K;                         // first column of this lane in the map
     const bool inside = col0 < W;
-    const uint32_t lcol = inside ? (uint32_t)col0 : 0u;
+    const uint32_t lcol = inside ? (uint32_t)col0 : (uint32_t)p.cb;
     const TailRows<T> tl(p.tail, W);
     const bool lastm = b == p.Bt - 1;
     bool lastB[NW];
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
         for (int v = 0; v < CT; ++v) {
             const int i = min(band * RB + cell_r[v], H - 1);
-            const size_t o = (size_t)i * W + (size_t)min(cell_c[v], W - 1);
+            const size_t o = (size_t)i * W + (size_t)min(p.cb + cell_c[v], W - 1);
             rawx[v] = elem_bits(xm + o);
             rawd[v] = elem_bits(dm + o);
             rawy[v] = elem_bits(dym + o);
@@ -260,7 +264,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             float dDb = 0.0f;
 #pragma unroll
             for (int v = 0; v < CT; ++v) {
-                const bool in = cell_ok[v] && act && r0 + cell_r[v] < H && cell_c[v] < W;
+                const bool in = cell_ok[v] && act && r0 + cell_r[v] < H && p.cb + cell_c[v] < W;
                 const bool m = rawm[v] != 0u;
                 const float dl = in ? widen(rawd[v], DT{}) : 0.0f;
                 const float xv = widen(rawx[v], T{});
@@ -341,6 +345,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                             } else {
                                 hl[0] = dxe[0] * get_elem<T, K>(fB[PF ? (r & 1) : 0][s], 0);
                             }
+                            float hcv = 0.0f;                             // state entering from the panel to the left
+                            if (p.hc_in != nullptr && l == 0) {
+                                hcv = p.hc_in[(map * N + n0 + s) * H + i];
+                                hl[0] = fmaf(a[0], hcv, hl[0]);
+                            }
                             pl[0] = a[0];
 #pragma unroll
                             for (int j = 1; j < K; ++j) {
@@ -350,6 +359,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                             float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
                             group_scan<LG, 1>(P, Hh, cin);
                             float left = cin[0];                          // hhor[i, j-1] (CF: h[i, j-1])
+                            if (p.hc_in != nullptr && l == 0) left = hcv;
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
@@ -438,6 +448,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                         for (int j = 0; j + 1 < K; ++j) ar[j] = a[j + 1];
                         ar[K - 1] = from_right_any<LG>(a[0]);
                         ql[K - 1] = g[K - 1];
+                        if (p.qc_in != nullptr && l == LG - 1)            // a*q entering from the panel to the right
+                            ql[K - 1] += p.qc_in[(map * N + n0 + s) * H + i];
                         pr[K - 1] = ar[K - 1];
 #pragma unroll
                         for (int j = K - 2; j >= 0; --j) {
@@ -449,6 +461,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
                             const float q = fmaf(pr[j], qin[0], ql[j]);
+                            if (j == 0 && p.qc_out != nullptr && l == 0 && act) p.qc_out[(map * N + n0 + s) * H + i] = a[0] * q;
                             float gc, du;                                  // gradient along the column recurrence, gradient of u
                             if constexpr (CF) {
                                 gc = q + ga[s][j];
@@ -483,22 +496,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                         for (int v = 0; v < TT; ++v) {
                             if constexpr (!LATEF) {
                                 const int t = tm + v * TMJ;
-                                const int tens = t / PANEL, col = t - tens * PANEL;
+                                const int tens = t / PANEL, lc = t - tens * PANEL, col = p.cb + lc;
                                 if (t < TASKS && col < W) {
-                                    const float sum = sum_partials_fixed<PANEL, NG>(base + tens * (THREADS * K) + lds_colk<LG, K>(col));
+                                    const float sum = sum_partials_fixed<PANEL, NG>(base + tens * (THREADS * K) + lds_colk<LG, K>(lc));
                                     if (tens == 0) {
                                         if constexpr (SP) ddw[ro + col] = sum;  // over the step of this cell, which nobody reads again
                                         else store_elem(ddm + ro + col, sum);
                                     } else {                                    // skip term; exactly +0 under the mask
-                                        const float* cell = prow + lds_colk<LG, K>(col);
+                                        const float* cell = prow + lds_colk<LG, K>(lc);
                                         store_elem(dxm + ro + col, cell[4 * PANEL] != 0.0f ? 0.0f : fmaf(dsk, cell[3 * PANEL], sum));
                                     }
                                 }
                                 continue;
                             }
-                            const int col = tm + v * TMJ;
-                            if (col < PANEL && col < W) {
-                                const int at = lds_colk<LG, K>(col);
+                            const int lc = tm + v * TMJ, col = p.cb + lc;
+                            if (lc < PANEL && col < W) {
+                                const int at = lds_colk<LG, K>(lc);
                                 const float sA = sum_partials_fixed<PANEL, NG>(base + at);
                                 const float sB = sum_partials_fixed<PANEL, NG>(base + THREADS * K + at);
                                 const float* cell = prow + at;                  // dl, xe, dl*xe, dy, mask flag of this cell
@@ -566,7 +579,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
         for (int ch = 0; ch < nch; ++ch) {
 #pragma unroll
             for (int s = 0; s < NW; ++s)
-                p.pA[((size_t)b * p.Dc + c_first + ch) * N + n0 + s] = dAL[((size_t)ch * SLOTS + slot) * NW + s];
+            {
+                float* dst = p.pA + ((size_t)b * p.Dc + c_first + ch) * N + n0 + s;
+                const float v = dAL[((size_t)ch * SLOTS + slot) * NW + s];
+                *dst = p.accum ? *dst + v : v;                     // panels are launched one after the other
+            }
         }
     }
     if (live && tm == 0 && p.pD != nullptr) {
@@ -575,7 +592,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
         for (int ch = 0; ch < nch; ++ch) {
             float acc = 0.0f;
             for (int w = 0; w < WPJ; ++w) acc += dDL[ch * WAVES + w0 + w];
-            p.pD[(size_t)b * p.Dc + c_first + ch] = acc;
+            float* dst = p.pD + (size_t)b * p.Dc + c_first + ch;
+            *dst = p.accum ? *dst + acc : acc;
         }
     }
 }

@@ -433,12 +433,15 @@ def test_backward_shared_producer_variants(s2d, variant, shape, dtype):
 # Maps wider than one lane-group panel (and, beyond 16 states, wider than 256 columns) are swept in panels of 256
 # columns with the row recurrences carried across the panel borders in both directions.
 @pytest.mark.parametrize("shape", [(1, 3, 16, 7, 1500, wl.F32, 0.3), (1, 2, 64, 6, 600, wl.BF16, 0.3), (2, 3, 32, 9, 300, wl.F32, 0.2),
-                                   (1, 2, 16, 3, 1027, wl.BF16, 0.0), (1, 2, 24, 1, 513, wl.F32, 0.3), (1, 5, 16, 5, 2049, wl.F32, 0.3)],
+                                   (1, 2, 16, 3, 1027, wl.BF16, 0.0), (1, 2, 24, 1, 513, wl.F32, 0.3), (1, 5, 16, 5, 2049, wl.F32, 0.3),
+                                   # 16 states: the shared-producer main sweep, several bands, softplus-free plain step
+                                   (2, 3, 16, 21, 520, wl.BF16, 0.3), (1, 9, 16, 13, 400, wl.F32, 0.4), (1, 2, 16, 9, 777, wl.BF16, 0.2)],
                          ids=lambda s: "x".join(map(str, s[:5])) + ("bf16" if s[5] else "f32"))
 def test_backward_of_wide_maps_in_column_panels(s2d, shape):
     Bt, Dc, N, H, W, dtype, mf = shape
     plan = s2d.describe_plan(s2d.Desc(Bt, Dc, H, W, N, dtype, 0), s2d.PASS_BWD)
     assert f"panels={-(-W // 256)} " in plan, plan
+    assert ("form=banded-shared" in plan) == (N == 16), plan
     check_bwd(s2d, wl.Workload("bwide", Bt, Dc, N, H, W, dtype, mask_frac=mf, backward=True), seed=14)
 
 
