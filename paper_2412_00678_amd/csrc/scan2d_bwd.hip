@@ -292,6 +292,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
                                              : bwd_shared_kernels_f32_cf(LG, K, NW, N / NW, waves, W, sp);
         else ks = d->dtype == SCAN2D_BF16 ? bwd_shared_kernels_bf16(LG, K, NW, N / NW, waves, W, sp)
                                           : bwd_shared_kernels_f32(LG, K, NW, N / NW, waves, W, sp);
+        if (pl.panels > 1) ks.main = ks.main_panels;              // column panels: the instantiation that takes them, if any
         if (ks.main != nullptr && (want_shared == 1 || shared_by_default(LG, K, NW))) pl.k = ks;
     }
     if (cf && pl.k.main == nullptr) return false;

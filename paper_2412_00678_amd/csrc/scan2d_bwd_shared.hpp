@@ -23,7 +23,8 @@
 // is accumulated by the producing threads and summed per wavefront: both in a fixed order, so results are
 // bit-reproducible.  K only has to be even here (the scanning lanes load no mask bytes), which allows
 // half-wave groups of 6 columns on 192-wide maps: band state of 96 registers, two waves per SIMD.
-// Column panels (maps wider than LG*K columns, one launch per panel, right to left): p.cb is the panel's first column;
+// MP instantiations - column panels (maps wider than LG*K columns, one launch per panel, right to left; the other
+// instantiations carry none of this code or its registers): p.cb is the panel's first column;
 // the row-scan state entering from the left panel (p.hc_in, left by the checkpoint sweeps) starts lane 0's rebuilt
 // row recurrence, a*q entering from the right panel (p.qc_in) joins the last lane's reverse recurrence, a*q of the
 // panel's first column goes to p.qc_out, and dA / dDskip add to what the panels to the right have left (p.accum).
@@ -118,8 +119,10 @@ __device__ __forceinline__ float from_right_any(float v) {
 // arrays hold v[i-1,j] (in `hprev`) and h[i,j-1] (in `hhl`), the reverse row scan q runs on dy * Cm alone and the
 // reverse column recurrence on its result (gv = q + a[i+1,j] * gv[i+1,j], kept in `ga` as a * gv); the gradient of u
 // is gv, that of the decay gv * v[i-1,j] + q * h[i,j-1]: the same instructions in the other order.
-template <typename T, int LG, int K, int NW, int NG, int WAVES, int RB, bool FAST, bool SP, bool CF = false>
+template <typename T, int LG, int K, int NW, int NG, int WAVES, int RB, bool FAST, bool SP, bool CF = false, bool MP = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const BwdArgs p) {
+    static_assert(!MP || !CF, "column panels: rows first only");
+    const int cb = MP ? p.cb : 0;                         // first column of this launch's panel
     constexpr int THREADS = WAVES * 64, SLOTS = THREADS / LG, JPW = SLOTS / NG, PANEL = LG * K, TMJ = NG * LG;
     static_assert(SLOTS % NG == 0 && JPW >= 1, "whole jobs per workgroup");
     constexpr int CELLS = RB * PANEL, CT = (CELLS + TMJ - 1) / TMJ;     // cells of a band per producing thread
@@ -163,9 +166,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
     const int H = p.H, W = p.W, N = p.N;
     const size_t HW = (size_t)H * W;
     const int n0 = sg * NW;
-    const int col0 = p.cb + l * K;                         // first column of this lane in the map
+    const int col0 = cb + l * K;                         // first column of this lane in the map
     const bool inside = col0 < W;
-    const uint32_t lcol = inside ? (uint32_t)col0 : (uint32_t)p.cb;
+    const uint32_t lcol = inside ? (uint32_t)col0 : (uint32_t)cb;
     const TailRows<T> tl(p.tail, W);
     const bool lastm = b == p.Bt - 1;
     bool lastB[NW];
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
         for (int v = 0; v < CT; ++v) {
             const int i = min(band * RB + cell_r[v], H - 1);
-            const size_t o = (size_t)i * W + (size_t)min(p.cb + cell_c[v], W - 1);
+            const size_t o = (size_t)i * W + (size_t)min(cb + cell_c[v], W - 1);
             rawx[v] = elem_bits(xm + o);
             rawd[v] = elem_bits(dm + o);
             rawy[v] = elem_bits(dym + o);
@@ -264,7 +267,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             float dDb = 0.0f;
 #pragma unroll
             for (int v = 0; v < CT; ++v) {
-                const bool in = cell_ok[v] && act && r0 + cell_r[v] < H && p.cb + cell_c[v] < W;
+                const bool in = cell_ok[v] && act && r0 + cell_r[v] < H && cb + cell_c[v] < W;
                 const bool m = rawm[v] != 0u;
                 const float dl = in ? widen(rawd[v], DT{}) : 0.0f;
                 const float xv = widen(rawx[v], T{});
@@ -346,9 +349,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 hl[0] = dxe[0] * get_elem<T, K>(fB[PF ? (r & 1) : 0][s], 0);
                             }
                             float hcv = 0.0f;                             // state entering from the panel to the left
-                            if (p.hc_in != nullptr && l == 0) {
-                                hcv = p.hc_in[(map * N + n0 + s) * H + i];
-                                hl[0] = fmaf(a[0], hcv, hl[0]);
+                            if constexpr (MP) {
+                                if (p.hc_in != nullptr && l == 0) {
+                                    hcv = p.hc_in[(map * N + n0 + s) * H + i];
+                                    hl[0] = fmaf(a[0], hcv, hl[0]);
+                                }
                             }
                             pl[0] = a[0];
 #pragma unroll
@@ -359,7 +364,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                             float P[1] = {pl[K - 1]}, Hh[1] = {hl[K - 1]}, cin[1];
                             group_scan<LG, 1>(P, Hh, cin);
                             float left = cin[0];                          // hhor[i, j-1] (CF: h[i, j-1])
-                            if (p.hc_in != nullptr && l == 0) left = hcv;
+                            if constexpr (MP) {
+                                if (p.hc_in != nullptr && l == 0) left = hcv;
+                            }
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
@@ -448,8 +455,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                         for (int j = 0; j + 1 < K; ++j) ar[j] = a[j + 1];
                         ar[K - 1] = from_right_any<LG>(a[0]);
                         ql[K - 1] = g[K - 1];
-                        if (p.qc_in != nullptr && l == LG - 1)            // a*q entering from the panel to the right
-                            ql[K - 1] += p.qc_in[(map * N + n0 + s) * H + i];
+                        if constexpr (MP) {
+                            if (p.qc_in != nullptr && l == LG - 1)        // a*q entering from the panel to the right
+                                ql[K - 1] += p.qc_in[(map * N + n0 + s) * H + i];
+                        }
                         pr[K - 1] = ar[K - 1];
 #pragma unroll
                         for (int j = K - 2; j >= 0; --j) {
@@ -461,7 +470,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
                             const float q = fmaf(pr[j], qin[0], ql[j]);
-                            if (j == 0 && p.qc_out != nullptr && l == 0 && act) p.qc_out[(map * N + n0 + s) * H + i] = a[0] * q;
+                            if constexpr (MP) {
+                                if (j == 0 && p.qc_out != nullptr && l == 0 && act) p.qc_out[(map * N + n0 + s) * H + i] = a[0] * q;
+                            }
                             float gc, du;                                  // gradient along the column recurrence, gradient of u
                             if constexpr (CF) {
                                 gc = q + ga[s][j];
@@ -496,7 +507,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                         for (int v = 0; v < TT; ++v) {
                             if constexpr (!LATEF) {
                                 const int t = tm + v * TMJ;
-                                const int tens = t / PANEL, lc = t - tens * PANEL, col = p.cb + lc;
+                                const int tens = t / PANEL, lc = t - tens * PANEL, col = cb + lc;
                                 if (t < TASKS && col < W) {
                                     const float sum = sum_partials_fixed<PANEL, NG>(base + tens * (THREADS * K) + lds_colk<LG, K>(lc));
                                     if (tens == 0) {
@@ -509,7 +520,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 }
                                 continue;
                             }
-                            const int lc = tm + v * TMJ, col = p.cb + lc;
+                            const int lc = tm + v * TMJ, col = cb + lc;
                             if (lc < PANEL && col < W) {
                                 const int at = lds_colk<LG, K>(lc);
                                 const float sA = sum_partials_fixed<PANEL, NG>(base + at);
@@ -582,7 +593,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             {
                 float* dst = p.pA + ((size_t)b * p.Dc + c_first + ch) * N + n0 + s;
                 const float v = dAL[((size_t)ch * SLOTS + slot) * NW + s];
-                *dst = p.accum ? *dst + v : v;                     // panels are launched one after the other
+                *dst = (MP && p.accum) ? *dst + v : v;             // panels are launched one after the other
             }
         }
     }
@@ -593,7 +604,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             float acc = 0.0f;
             for (int w = 0; w < WPJ; ++w) acc += dDL[ch * WAVES + w0 + w];
             float* dst = p.pD + (size_t)b * p.Dc + c_first + ch;
-            *dst = p.accum ? *dst + acc : acc;
+            *dst = (MP && p.accum) ? *dst + acc : acc;
         }
     }
 }

@@ -22,6 +22,7 @@ struct BwdKernels {
     int ckpt_LG = 0, ckpt_waves = 0;      // the checkpoint sweep may use another lane tiling than the main sweep
     bool ckpt_fast = true;                // W is a multiple of the checkpoint sweep's columns per lane
     bool shared = false;                  // main sweep of scan2d_bwd_shared.hpp
+    BwdKernel main_panels = nullptr;      // its instantiation that takes column panels (wave-wide tiling of two states per lane)
     // checkpoint sweep run by the shared-producer forward kernel in its checkpoint mode (FwdArgs), with its tiling
     void (*ckpt_fwd)(const FwdArgs) = nullptr;
     int cf_LG = 0, cf_K = 0, cf_NW = 0, cf_NG = 0, cf_waves = 0, cf_RPB = 0;
@@ -61,6 +62,9 @@ inline BwdKernels lookup_bwd_shared_kernels(int LG, int K, int NW, int NG, int w
         r.main = fast ? scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, true, SP, CF>                 \
                       : scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, false, SP, CF>;               \
         r.RB = rb; r.shared = true;                                                                      \
+        if constexpr (!CF && lg == 64 && k == 4 && nw == 2)                                              \
+            r.main_panels = fast ? scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, true, SP, false, true>      \
+                                 : scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, false, SP, false, true>;    \
         if constexpr (Elem<T>::kBytes == 2) {                                                            \
             r.ckpt_fwd = (W % 2) != 0 ? scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, true, rb, CF>     \
                                       : scan2d_fwd_shared_kernel<T, flg, fk, fnw, fng, fwv, frpb, SP, false, rb, CF>;   \
