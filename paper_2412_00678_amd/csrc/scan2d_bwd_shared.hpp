@@ -109,6 +109,23 @@ __device__ __forceinline__ float from_right_any(float v) {
     }
 }
 
+// Value held by the lane to the left inside the lane group (0 for the group's first lane).
+template <int LG>
+__device__ __forceinline__ float from_left_any(float v) {
+    float r;
+    if constexpr (LG == 16) {
+        asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "=&v"(r) : "v"(v));
+    } else {
+        asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "=&v"(r) : "v"(v));
+        if constexpr (LG == 32) r = (threadIdx.x & 31u) == 0u ? 0.0f : r;
+    }
+    return r;
+}
+
+#ifndef SCAN2D_BWD_RECOMPUTE_HHOR
+#define SCAN2D_BWD_RECOMPUTE_HHOR 1
+#endif
+
 // Dynamic LDS layout (floats), T = workgroup threads, SLOTS = T / LG, JPW = SLOTS / NG:
 //   part [2][2][SLOTS][PANEL]      per-lane partial sums over its states of ddelta and dx (double buffered per row)
 //   pp   [JPW][RB][5][PANEL]       the per-position values of the current (band, channel): dl, xe, dxe, dyv, mask flag
@@ -122,6 +139,12 @@ __device__ __forceinline__ float from_right_any(float v) {
 template <typename T, int LG, int K, int NW, int NG, int WAVES, int RB, bool FAST, bool SP, bool CF = false, bool MP = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const BwdArgs p) {
     static_assert(!MP || !CF, "column panels: rows first only");
+    // RECOMP: the row-scan states hhor[i,j-1] of a band are not kept from the rebuild to the reverse sweep (RB*NW*K
+    // registers) but formed again there from the column states, which are kept anyway: Eq. 6 read backwards,
+    // hhor[i,j] = h[i,j] - a[i,j] * h[i-1,j], one multiply-add per cell and one lane shift per row instead of a register
+    // (in practice: a copy into and out of an accumulation register) per cell.  The difference to the kept value is one
+    // rounding of h[i,j].
+    constexpr bool RECOMP = SCAN2D_BWD_RECOMPUTE_HHOR != 0 && !CF && !MP;
     const int cb = MP ? p.cb : 0;                         // first column of this launch's panel
     constexpr int THREADS = WAVES * 64, SLOTS = THREADS / LG, JPW = SLOTS / NG, PANEL = LG * K, TMJ = NG * LG;
     static_assert(SLOTS % NG == 0 && JPW >= 1, "whole jobs per workgroup");
@@ -289,7 +312,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             __syncthreads();
 
             // ---- scans 1 and 2: rebuild h[i-1,j] and hhor[i,j-1] for the rows of the band
-            float hprev[RB][NW][K], hhl[RB][NW][K];
+            float hprev[RB][NW][K], hhl[RECOMP ? 1 : RB][NW][K];
             float hcur[NW][K];                                 // after scans 1 and 2: the state of the band's bottom row
             {
                 uint32_t fB[NB][NW][XW];
@@ -370,7 +393,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
                             for (int j = 0; j < K; ++j) {
                                 const float hh = (j == K - 1) ? Hh[0] : fmaf(pl[j], cin[0], hl[j]);
-                                hhl[r][s][j] = left;
+                                if constexpr (!RECOMP) hhl[r][s][j] = left;
                                 if constexpr (!CF) {
                                     hprev[r][s][j] = hcur[s][j];
                                     hcur[s][j] = fmaf(a[j], hcur[s][j], hh);
@@ -428,7 +451,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                     for (int j = 0; j < K; ++j) { ddl[j] = 0.0f; dxl[j] = 0.0f; }
 #pragma unroll
                     for (int s = 0; s < NW; ++s) {
-                        float a[K], Bv[K], g[K];
+                        float a[K], Bv[K], g[K], hrow[RECOMP ? K : 1];
 #pragma unroll
                         for (int j = 0; j < K; ++j) {
                             a[j] = __builtin_amdgcn_exp2f(dl[j] * Ap[s]);
@@ -441,6 +464,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 hv = r == RB - 1 ? hcur[s][j] : hprev[r + 1 < RB ? r + 1 : r][s][j];
                             }
                             dCacc[r][s][j] = fmaf(dyv[j], hv, dCacc[r][s][j]);
+                            if constexpr (RECOMP) hrow[j] = fmaf(-a[j], hprev[r][s][j], hv);           // hhor[i,j]
                             const float dyC = dyv[j] * get_elem<T, K>(bC[PF ? (r & 1) : 0][s], j);
                             if constexpr (CF) {
                                 g[j] = dyC;
@@ -448,6 +472,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 g[j] = dyC + ga[s][j];                                                  // scan 3
                                 ga[s][j] = a[j] * g[j];
                             }
+                        }
+                        if constexpr (RECOMP) {                  // hhor[i,j-1]: the left neighbour's last column for j = 0
+                            hhl[0][s][0] = from_left_any<LG>(hrow[K - 1]);
+#pragma unroll
+                            for (int j = 1; j < K; ++j) hhl[0][s][j] = hrow[j - 1];
                         }
                         // scan 4: q[j] = g[j] + a[j+1] * q[j+1]
                         float ar[K], ql[K], pr[K];
@@ -482,7 +511,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 gc = g[j];
                                 du = q;
                             }
-                            const float da = fmaf(gc, hprev[r][s][j], q * hhl[r][s][j]);
+                            const float da = fmaf(gc, hprev[r][s][j], q * hhl[RECOMP ? 0 : r][s][j]);
                             const float t = da * a[j];
                             const float qB = du * Bv[j];
                             dAb[s] = fmaf(t, dl[j], dAb[s]);
