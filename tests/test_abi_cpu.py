@@ -204,3 +204,18 @@ def test_benchmark_configurations_take_the_intended_forms(lib):
     assert f["form"] == "small"                              # many of them: four maps per workgroup, row by row
     b = plan(lib, lib.Desc(4, 512, 128, 192, 16, 0, 0), lib.PASS_BWD)
     assert (b["form"], b["LG"], b["K"], b["NW"]) == ("banded-shared", 16, 12, 1) and b["wgs"] * b["GS"] >= 4 * 512 // 1
+
+
+def test_wide_grids_take_the_shared_producer_forms(lib):
+    # 257 to 1024 columns, 16 states, one map per compute unit: wave-wide groups with 8, 12 or 16 columns per lane
+    for W, K in ((300, 8), (400, 8), (512, 8), (513, 12), (600, 12), (768, 12), (769, 16), (1000, 16), (1024, 16)):
+        for dtype in (0, 1):
+            f = plan(lib, lib.Desc(1, 256, 200, W, 16, dtype, 0), lib.PASS_FWD)
+            assert (f["form"], f["LG"], f["K"], f["panels"]) == ("shared", 64, K, 1) and f["workspace"] == 0, (W, dtype, f)
+    f = plan(lib, lib.Desc(1, 256, 200, 1025, 16, 1, 0), lib.PASS_FWD)
+    assert f["form"] == "general" and f["panels"] > 1
+    # their backward: panels of 256 columns; with 16 states the shared-producer main sweep, two states per lane
+    b = plan(lib, lib.Desc(1, 256, 400, 400, 16, 1, 0), lib.PASS_BWD)
+    assert (b["form"], b["LG"], b["K"], b["NW"], b["waves"], b["panels"]) == ("banded-shared", 64, 4, 2, 8, 2)
+    b = plan(lib, lib.Desc(1, 256, 400, 400, 8, 1, 0), lib.PASS_BWD)
+    assert (b["form"], b["LG"], b["K"], b["panels"]) == ("banded", 64, 4, 2)
