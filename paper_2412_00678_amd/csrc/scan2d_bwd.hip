@@ -304,6 +304,9 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
         pl.k = d->dtype == SCAN2D_BF16 ? bwd_kernels_bf16(LG, K, NW, waves, fast, sp) : bwd_kernels_f32(LG, K, NW, waves, fast, sp);
     if (pl.k.main == nullptr) return false;
     pl.shared = pl.k.shared;
+    // the single-panel shared-producer sweeps apply the softplus and its chain rule themselves (their checkpoint sweep,
+    // the shared-producer forward kernel, computes the step from the raw projection too)
+    if (pl.shared && pl.panels == 1 && pl.k.ckpt_fwd != nullptr && N == pl.k.cf_NG * pl.k.cf_NW) pl.step_outside = false;
     pl.fast = fast && pl.k.ckpt_fast;                        // false: the padded copies of the tensors' last rows are needed
     pl.ck_LG = pl.k.ckpt_LG; pl.ck_waves = pl.k.ckpt_waves;
     pl.LG = LG; pl.K = K; pl.NW = NW; pl.waves = waves; pl.RB = pl.k.RB;

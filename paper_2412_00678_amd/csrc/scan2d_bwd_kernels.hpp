@@ -43,7 +43,7 @@ namespace scan2d {
 struct BwdArgs {
     const void* x; const void* delta; const float* A; const void* Bm; const void* Cm;
     const float* Dskip; const uint8_t* mask; const void* dy;
-    const float* delta_bias;   // [Dc] or null (not read by the sweeps)
+    const float* delta_bias;   // [Dc] or null; read by the single-panel shared-producer sweeps (SP), which apply the softplus themselves
     void* dx; void* ddelta;
     float* ck;           // [maps][nb][N][W]   column state entering each band (band 0 unused)
     int ck_chunked = 0;  // shared-producer sweeps only: rows of LG*K floats in lane order [K/4][LG][4] (see FwdArgs)

@@ -122,6 +122,14 @@ __device__ __forceinline__ float from_left_any(float v) {
     return r;
 }
 
+// d softplus(t) / dt from the softplus value itself: sp = log(1 + e^t), so the logistic function of t is 1 - e^(-sp).
+// Below 1/64 the difference loses digits and the series takes over (next term: sp^4 / 24, under 2e-7 of the value).
+__device__ __forceinline__ float dsoftplus_from_value(float sp) {
+    const float big = 1.0f - __builtin_amdgcn_exp2f(-sp * kLog2e);
+    const float small = sp * (1.0f - sp * (0.5f - sp * (1.0f / 6.0f)));
+    return sp < 0.015625f ? small : big;
+}
+
 #ifndef SCAN2D_BWD_RECOMPUTE_HHOR
 #define SCAN2D_BWD_RECOMPUTE_HHOR 1
 #endif
@@ -155,7 +163,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
     constexpr bool LATEF = 2 * PANEL > TMJ;
     constexpr int TASKS = LATEF ? PANEL : 2 * PANEL, TT = (TASKS + TMJ - 1) / TMJ;
     constexpr int XW = words_of<T, K>();
-    using DT = std::conditional_t<SP, float, T>;                        // element type of the step
+    // SP: p.delta is the raw projection.  Single-panel instantiations (SPIN) apply the softplus where the cells are
+    // produced and the chain rule where ddelta is summed (the logistic factor comes from the step kept in LDS), so
+    // ddelta receives the gradient of the raw projection directly; the column-panel instantiations read the step from a
+    // buffer a kernel of its own has filled (fp32, p.delta) and write the step's gradient back over it.
+    constexpr bool SPIN = SP && !MP;
+    using DT = std::conditional_t<SP && !SPIN, float, T>;               // element type of what p.delta holds
     constexpr int PP_ROW = 5 * PANEL, PP_JOB = RB * PP_ROW;
     // Bm / Cm of the next row are requested before the current row is processed only where the registers allow it
     // (two waves per SIMD hide the latency otherwise)
@@ -273,7 +286,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             const bool act = ch < nch;
             const int c = act ? c_first + ch : c_first;      // idle iterations re-read a valid channel
             const size_t map = (size_t)b * p.Dc + c;
-            float* ddw = SP ? const_cast<float*>(reinterpret_cast<const float*>(p.delta)) + map * HW : nullptr;
+            float* ddw = (SP && !SPIN) ? const_cast<float*>(reinterpret_cast<const float*>(p.delta)) + map * HW : nullptr;
+            const float dbc = (SPIN && p.delta_bias != nullptr) ? p.delta_bias[c] : 0.0f;
             T* dxm = reinterpret_cast<T*>(p.dx) + map * HW;
             T* ddm = reinterpret_cast<T*>(p.ddelta) + map * HW;
             float An[NW], Ap[NW];
@@ -292,7 +306,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             for (int v = 0; v < CT; ++v) {
                 const bool in = cell_ok[v] && act && r0 + cell_r[v] < H && cb + cell_c[v] < W;
                 const bool m = rawm[v] != 0u;
-                const float dl = in ? widen(rawd[v], DT{}) : 0.0f;
+                float dl = widen(rawd[v], DT{});
+                if constexpr (SPIN) dl = softplus_f32(dl + dbc);
+                dl = in ? dl : 0.0f;
                 const float xv = widen(rawx[v], T{});
                 const float xe = (in && !m) ? xv : 0.0f;                 // select: nothing under the mask leaks
                 const float dyv = in ? widen(rawy[v], T{}) : 0.0f;
@@ -540,7 +556,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 if (t < TASKS && col < W) {
                                     const float sum = sum_partials_fixed<PANEL, NG>(base + tens * (THREADS * K) + lds_colk<LG, K>(lc));
                                     if (tens == 0) {
-                                        if constexpr (SP) ddw[ro + col] = sum;  // over the step of this cell, which nobody reads again
+                                        if constexpr (SP && !SPIN) ddw[ro + col] = sum;  // over the step of this cell, which nobody reads again
+                                        else if constexpr (SPIN) store_elem(ddm + ro + col, sum * dsoftplus_from_value(prow[lds_colk<LG, K>(lc)]));
                                         else store_elem(ddm + ro + col, sum);
                                     } else {                                    // skip term; exactly +0 under the mask
                                         const float* cell = prow + lds_colk<LG, K>(lc);
@@ -556,7 +573,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 const float sB = sum_partials_fixed<PANEL, NG>(base + THREADS * K + at);
                                 const float* cell = prow + at;                  // dl, xe, dl*xe, dy, mask flag of this cell
                                 const float dd = fmaf(cell[PANEL], sB, sA);
-                                if constexpr (SP) ddw[ro + col] = dd;           // over the step of this cell, which nobody reads again
+                                if constexpr (SP && !SPIN) ddw[ro + col] = dd;  // over the step of this cell, which nobody reads again
+                                else if constexpr (SPIN) store_elem(ddm + ro + col, dd * dsoftplus_from_value(cell[0]));
                                 else store_elem(ddm + ro + col, dd);
                                 // skip term; exactly +0 under the mask
                                 store_elem(dxm + ro + col, cell[4 * PANEL] != 0.0f ? 0.0f : fmaf(dsk, cell[3 * PANEL], cell[0] * sB));
