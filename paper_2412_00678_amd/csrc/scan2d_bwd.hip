@@ -322,6 +322,7 @@ bool make_plan(const scan2d_desc* d, BwdPlan* out, bool sp = false, bool av = fa
     if (pl.shared) {             // see the LDS layout in scan2d_bwd_shared.hpp
         fixed = 4 * T * K + (T / (size_t)pl.NG / LG) * ((size_t)pl.RB * 5 * LG * K);
         per = T * (size_t)NW * K + (T / LG) * NW + (size_t)waves;
+        if (sp && !pl.step_outside) per += (size_t)waves;     // the bias gradient per wavefront
     }
     const int gs_lds = (int)std::max<size_t>(1, (40960 - std::min<size_t>(fixed, 40960)) / per);
     const int JPW = slots / pl.NG;
@@ -491,6 +492,9 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
     a.ck_chunked = pl.ck_chunked ? 1 : 0;
     a.part_chunked = pl.part_chunked ? 1 : 0;
     a.pAv = A_v == nullptr ? nullptr : (d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pAv) : dA_v);
+    // the sweeps that apply the softplus themselves also add up ddelta_raw per map
+    const bool bias_in_sweep = softplus && ddelta_bias != nullptr && pl.shared && !pl.step_outside && !pl.small;
+    if (bias_in_sweep) a.pBias = d->Bt > 1 ? reinterpret_cast<float*>(ws + pl.off_pb) : ddelta_bias;
 
     const long long maps = (long long)d->Bt * d->Dc;
     if (pl.small) {
@@ -623,6 +627,10 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
         if (ddelta_bias != nullptr && d->Bt > 1)
             hipLaunchKernelGGL(scan2d_bwd_reduce_bias_batch_kernel, dim3((d->Dc + 255) / 256), dim3(256), 0, stream,
                                pb, ddelta_bias, d->Bt, d->Dc);
+    } else if (bias_in_sweep) {
+        if (d->Bt > 1)
+            hipLaunchKernelGGL(scan2d_bwd_reduce_bias_batch_kernel, dim3((d->Dc + 255) / 256), dim3(256), 0, stream,
+                               a.pBias, ddelta_bias, d->Bt, d->Dc);
     } else if (softplus && ddelta_bias != nullptr) {
         launch_bias_sums(d, pl, ddelta, ddelta_bias, ws, stream);
     }

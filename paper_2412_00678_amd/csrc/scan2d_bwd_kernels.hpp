@@ -53,6 +53,7 @@ struct BwdArgs {
     const void* tail;    // padded copies of the rows behind which the tensors end (instantiations without FAST)
     float* pA;           // [Bt][Dc][N]
     float* pD;           // [Bt][Dc]
+    float* pBias = nullptr; // [Bt][Dc] sums of ddelta_raw per map, written by the sweeps that apply the softplus themselves (or null)
     int Bt, Dc, H, W, N;
     int NG;              // lane groups per map
     int GS;              // channels a workgroup handles one after the other

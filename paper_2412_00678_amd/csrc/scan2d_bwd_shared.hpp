@@ -140,6 +140,7 @@ __device__ __forceinline__ float dsoftplus_from_value(float sp) {
 //   gaL  [GS][T][NW*K]             a[i+1,j]*g[i+1,j] of every channel, kept between bands
 //   dAL  [GS][SLOTS][NW]           dA of every channel, accumulated over the bands
 //   dDL  [GS][WAVES]               dDskip of every channel per wavefront, accumulated over the bands
+//   dBL  [GS][WAVES]               (SPIN) the bias gradient, the sum of ddelta_raw, likewise
 // CF: columns first (v = a * v[i-1,j] + u, then h = a * h[i,j-1] + v).  The checkpoints then hold v, the band
 // arrays hold v[i-1,j] (in `hprev`) and h[i,j-1] (in `hhl`), the reverse row scan q runs on dy * Cm alone and the
 // reverse column recurrence on its result (gv = q + a[i+1,j] * gv[i+1,j], kept in `ga` as a * gv); the gradient of u
@@ -184,6 +185,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
     float* const gaL = pp + JPW * PP_JOB;
     float* const dAL = gaL + (size_t)GS * THREADS * NW * K;
     float* const dDL = dAL + (size_t)GS * SLOTS * NW;
+    float* const dBL = dDL + (size_t)GS * WAVES;             // SPIN instantiations only
 
     const int tid = threadIdx.x, slot = tid / LG, l = tid % LG, wave = tid / 64;
     int job_local = slot / NG;
@@ -228,7 +230,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
 #pragma unroll
             for (int s = 0; s < NW; ++s) dAL[((size_t)ch * SLOTS + slot) * NW + s] = 0.0f;
         }
-        if ((tid & 63) == 63) dDL[ch * WAVES + wave] = 0.0f;
+        if ((tid & 63) == 63) {
+            dDL[ch * WAVES + wave] = 0.0f;
+            if constexpr (SPIN) dBL[ch * WAVES + wave] = 0.0f;
+        }
     }
     // gaL entries are private to a thread, dAL entries to the last lane of a lane group, dDL entries to the last
     // lane of a wavefront: no barrier needed for them until the final sums
@@ -301,7 +306,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             // ---- the per-position values of this (band, channel).  The threads that sum the last row of the previous
             // (band, channel) still read its dy and mask flags: wait for them
             __syncthreads();
-            float dDb = 0.0f;
+            float dDb = 0.0f, dBb = 0.0f;                      // dBb (SPIN): sum of the ddelta_raw this thread stores
 #pragma unroll
             for (int v = 0; v < CT; ++v) {
                 const bool in = cell_ok[v] && act && r0 + cell_r[v] < H && cb + cell_c[v] < W;
@@ -557,7 +562,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                     const float sum = sum_partials_fixed<PANEL, NG>(base + tens * (THREADS * K) + lds_colk<LG, K>(lc));
                                     if (tens == 0) {
                                         if constexpr (SP && !SPIN) ddw[ro + col] = sum;  // over the step of this cell, which nobody reads again
-                                        else if constexpr (SPIN) store_elem(ddm + ro + col, sum * dsoftplus_from_value(prow[lds_colk<LG, K>(lc)]));
+                                        else if constexpr (SPIN) {
+                                            const float v = sum * dsoftplus_from_value(prow[lds_colk<LG, K>(lc)]);
+                                            store_elem(ddm + ro + col, v);
+                                            dBb += v;
+                                        }
                                         else store_elem(ddm + ro + col, sum);
                                     } else {                                    // skip term; exactly +0 under the mask
                                         const float* cell = prow + lds_colk<LG, K>(lc);
@@ -574,7 +583,11 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                                 const float* cell = prow + at;                  // dl, xe, dl*xe, dy, mask flag of this cell
                                 const float dd = fmaf(cell[PANEL], sB, sA);
                                 if constexpr (SP && !SPIN) ddw[ro + col] = dd;  // over the step of this cell, which nobody reads again
-                                else if constexpr (SPIN) store_elem(ddm + ro + col, dd * dsoftplus_from_value(cell[0]));
+                                else if constexpr (SPIN) {
+                                    const float v = dd * dsoftplus_from_value(cell[0]);
+                                    store_elem(ddm + ro + col, v);
+                                    dBb += v;
+                                }
                                 else store_elem(ddm + ro + col, dd);
                                 // skip term; exactly +0 under the mask
                                 store_elem(dxm + ro + col, cell[4 * PANEL] != 0.0f ? 0.0f : fmaf(dsk, cell[3 * PANEL], cell[0] * sB));
@@ -594,6 +607,10 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             {
                 const float tot = group_sum_last<64>(dDb);
                 if ((tid & 63) == 63) dDL[ch * WAVES + wave] += tot;
+            }
+            if constexpr (SPIN) {
+                const float tot = group_sum_last<64>(dBb);
+                if ((tid & 63) == 63) dBL[ch * WAVES + wave] += tot;
             }
         }
 
@@ -652,6 +669,17 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
             for (int w = 0; w < WPJ; ++w) acc += dDL[ch * WAVES + w0 + w];
             float* dst = p.pD + (size_t)b * p.Dc + c_first + ch;
             *dst = (MP && p.accum) ? *dst + acc : acc;
+        }
+    }
+    if constexpr (SPIN) {
+        if (live && tm == 0 && p.pBias != nullptr) {
+            constexpr int WPJ = TMJ >= 64 ? TMJ / 64 : 1;
+            const int w0 = (job_slot * TMJ) / 64;
+            for (int ch = 0; ch < nch; ++ch) {
+                float acc = 0.0f;
+                for (int w = 0; w < WPJ; ++w) acc += dBL[ch * WAVES + w0 + w];
+                p.pBias[(size_t)b * p.Dc + c_first + ch] = acc;
+            }
         }
     }
 }
