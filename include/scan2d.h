@@ -186,9 +186,11 @@ int scan2d_fwd_softplus_gated(const scan2d_desc* desc,
 /*
  * Backward of scan2d_fwd_softplus_gated for a given dy = dL/dy (y the gated output).  With s = 1/(1+exp(-z)):
  *     dz[b,c,i,j] = dy * y_scan * s * (1 + z * (1 - s))
- * and every other gradient is that of scan2d_bwd_softplus fed dy * z * s in place of dy.  One element-wise
- * kernel writes dz and that product (rounded to the storage type) into the workspace, then the backward
- * of the scan runs on it.
+ * and every other gradient is that of scan2d_bwd_softplus fed dy * z * s in place of dy.  Where the scan's
+ * backward sweep has an instantiation for it (flags 0, 16 states, at most 256 columns and the other shapes
+ * whose plan reads "banded-shared" with one panel) dz and that product are formed inside the sweep and the
+ * product is never rounded; elsewhere one element-wise kernel writes dz and the product (rounded to the
+ * storage type) into the workspace and the backward of the scan runs on it.
  *   y_scan : as written by the forward (required)
  *   dz     : [Bt][Dc][H][W], dtype, device memory, written
  *   workspace : at least scan2d_workspace_bytes(desc, SCAN2D_PASS_BWD_GATED) bytes

@@ -559,7 +559,8 @@ namespace {
 int bwd_core(const scan2d_desc* desc, const void* x, const void* delta, const float* delta_bias, bool softplus,
              const float* A, const void* Bm, const void* Cm, const float* Dskip, const uint8_t* mask,
              const void* dy, void* dx, void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm,
-             float* dDskip, void* workspace, size_t workspace_bytes, void* stream) {
+             float* dDskip, void* workspace, size_t workspace_bytes, void* stream,
+             const void* z = nullptr, const void* y_scan = nullptr, void* dz = nullptr) {
     int rc = bwd_check(desc, softplus);                                        // nothing is enqueued for a call that will fail
     if (rc != SCAN2D_OK) return rc;
     const size_t sk = skip_bytes(desc);
@@ -576,7 +577,7 @@ int bwd_core(const scan2d_desc* desc, const void* x, const void* delta, const fl
         workspace_bytes = inner;
     }
     rc = bwd_launch(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
-                    dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+                    dDskip, workspace, workspace_bytes, static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, z, y_scan, dz);
     // identity cells: their step is the constant 0, so it has no gradient (with the softplus step the chain
     // rule has already multiplied by the logistic function of -inf, which is 0)
     if (rc == SCAN2D_OK && sk > 0 && mask != nullptr && !softplus)
@@ -635,7 +636,10 @@ int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         if (!aligned16(q)) return SCAN2D_ERR_MISALIGNED;
     rc = check_device();
     if (rc != SCAN2D_OK) return rc;
-    if (z != nullptr) {          // output gate: dz, and dy * SiLU(z) in place of dy
+    // output gate: where the main sweep has an instantiation for it, dz and dy * SiLU(z) are formed where the sweep
+    // produces its cells (nothing rounded in between); otherwise by an element-wise kernel in front of the sweeps
+    const bool gate_in_sweep = z != nullptr && softplus && bwd_gate_in_sweep(desc);
+    if (z != nullptr && !gate_in_sweep) {
         rc = gate_bwd_launch(desc, z, y_scan, dy, dyg, dz, static_cast<hipStream_t>(stream));
         if (rc != SCAN2D_OK) return rc;
         dy = dyg;
@@ -644,7 +648,7 @@ int bwd_impl(const scan2d_desc* desc, const void* x, const void* delta, const fl
         return bwd_columns_first(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm,
                                  dCm, dDskip, workspace, workspace_bytes, stream);
     return bwd_core(desc, x, delta, delta_bias, softplus, A, Bm, Cm, Dskip, mask, dy, dx, ddelta, ddelta_bias, dA, dBm, dCm,
-                    dDskip, workspace, workspace_bytes, stream);
+                    dDskip, workspace, workspace_bytes, stream, gate_in_sweep ? z : nullptr, y_scan, dz);
 }
 }  // namespace
 

@@ -449,6 +449,12 @@ bool bwd_describe(const scan2d_desc* d, char* text, size_t text_bytes) {
     return true;
 }
 
+bool bwd_gate_in_sweep(const scan2d_desc* d) {
+    BwdPlan pl;
+    return d->flags == 0u && make_plan(d, &pl, true, false) && pl.shared && pl.panels == 1 && !pl.step_outside &&
+           pl.k.main_gate != nullptr;
+}
+
 namespace {
 // Sum of ddelta_raw over positions and batch items, per channel (softplus step only).
 void launch_bias_sums(const scan2d_desc* d, const BwdPlan& pl, const void* ddelta_raw, float* dbias, char* ws, hipStream_t stream) {
@@ -471,14 +477,21 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
                const float* A, const void* Bm,
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
                void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
-               size_t workspace_bytes, hipStream_t stream, const float* A_v, float* dA_v, const float* saved) {
+               size_t workspace_bytes, hipStream_t stream, const float* A_v, float* dA_v, const float* saved,
+               const void* z, const void* y_scan, void* dz) {
     BwdPlan pl;
     if (!make_plan(d, &pl, softplus, A_v != nullptr)) return SCAN2D_ERR_BAD_SHAPE;
+    if (z != nullptr) {                                        // the output gate's backward inside the main sweep
+        if (!softplus || y_scan == nullptr || dz == nullptr || !pl.shared || pl.panels != 1 || pl.step_outside || pl.k.main_gate == nullptr)
+            return SCAN2D_ERR_BAD_SHAPE;
+        pl.k.main = pl.k.main_gate;
+    }
     if (pl.total > 0 && (workspace == nullptr || workspace_bytes < pl.total)) return SCAN2D_ERR_WORKSPACE_SMALL;
     char* ws = static_cast<char*>(workspace);
     BwdArgs a;
     a.x = x; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dskip = Dskip; a.mask = mask; a.dy = dy;
     a.dx = dx; a.ddelta = ddelta; a.delta_bias = delta_bias;
+    a.z = z; a.y_scan = y_scan; a.dz = dz;
     if (pl.step_outside) a.delta = ws + pl.off_step;
     a.tail = pl.small ? nullptr : ws + pl.off_tail;
     a.ck = saved != nullptr ? const_cast<float*>(saved) : reinterpret_cast<float*>(ws + pl.off_ck);

@@ -31,6 +31,10 @@ int bwd_launch(const scan2d_desc* d, const void* x, const void* delta, const flo
                const void* Cm, const float* Dskip, const uint8_t* mask, const void* dy, void* dx,
                void* ddelta, float* ddelta_bias, float* dA, float* dBm, float* dCm, float* dDskip, void* workspace,
                size_t workspace_bytes, hipStream_t stream, const float* A_v = nullptr, float* dA_v = nullptr,
-               const float* saved = nullptr);   // saved: the checkpoints left by fwd_saving_launch (no checkpoint sweep then)
+               const float* saved = nullptr,    // saved: the checkpoints left by fwd_saving_launch (no checkpoint sweep then)
+               const void* z = nullptr, const void* y_scan = nullptr, void* dz = nullptr);   // see bwd_gate_in_sweep
+// True where the main sweep has an instantiation that also runs the backward of the output gate (softplus step, no
+// flags): bwd_launch may then be given z, y_scan and dz, with dy the gradient of the GATED output.
+bool bwd_gate_in_sweep(const scan2d_desc* d);
 
 }  // namespace scan2d

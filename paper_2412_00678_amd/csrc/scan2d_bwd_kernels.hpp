@@ -53,6 +53,10 @@ struct BwdArgs {
     const void* tail;    // padded copies of the rows behind which the tensors end (instantiations without FAST)
     float* pA;           // [Bt][Dc][N]
     float* pD;           // [Bt][Dc]
+    // GATE instantiations of the shared-producer sweep only: the block's output gate inside the sweep
+    const void* z = nullptr;        // gate branch, layout of x
+    const void* y_scan = nullptr;   // the stored scan output, layout of x
+    void* dz = nullptr;             // gradient of z, layout of x
     float* pBias = nullptr; // [Bt][Dc] sums of ddelta_raw per map, written by the sweeps that apply the softplus themselves (or null)
     int Bt, Dc, H, W, N;
     int NG;              // lane groups per map

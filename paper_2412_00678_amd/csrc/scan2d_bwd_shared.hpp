@@ -145,9 +145,13 @@ __device__ __forceinline__ float dsoftplus_from_value(float sp) {
 // arrays hold v[i-1,j] (in `hprev`) and h[i,j-1] (in `hhl`), the reverse row scan q runs on dy * Cm alone and the
 // reverse column recurrence on its result (gv = q + a[i+1,j] * gv[i+1,j], kept in `ga` as a * gv); the gradient of u
 // is gv, that of the decay gv * v[i-1,j] + q * h[i,j-1]: the same instructions in the other order.
-template <typename T, int LG, int K, int NW, int NG, int WAVES, int RB, bool FAST, bool SP, bool CF = false, bool MP = false>
+// GATE: the backward of the block's output gate y = y_scan * SiLU(z) where the cells are produced: the thread that
+// produces a cell also loads z and y_scan there, stores dz = dy * y_scan * s (1 + z (1 - s)), s the logistic function of
+// z, and hands dy * SiLU(z), unrounded, to the sweeps in place of dy.
+template <typename T, int LG, int K, int NW, int NG, int WAVES, int RB, bool FAST, bool SP, bool CF = false, bool MP = false, bool GATE = false>
 __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const BwdArgs p) {
     static_assert(!MP || !CF, "column panels: rows first only");
+    static_assert(!GATE || (SP && !MP), "the gate goes with the softplus step, single panel");
     // RECOMP: the row-scan states hhor[i,j-1] of a band are not kept from the rebuild to the reverse sweep (RB*NW*K
     // registers) but formed again there from the column states, which are kept anyway: Eq. 6 read backwards,
     // hhor[i,j] = h[i,j] - a[i,j] * h[i-1,j], one multiply-add per cell and one lane shift per row instead of a register
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
         cell_ok[v] = id < CELLS && live;
         if (!cell_ok[v]) { cell_r[v] = 0; cell_c[v] = 0; }
     }
-    uint32_t rawx[CT], rawd[CT], rawy[CT], rawm[CT];
+    uint32_t rawx[CT], rawd[CT], rawy[CT], rawm[CT], rawz[GATE ? CT : 1], raws[GATE ? CT : 1];
     // Loads of the cells of (band, channel): clamped to a valid element, so that no load sits in a branch; what
     // lies outside the map is zeroed where the cell is produced.
     auto request = [&](int band, int ch) {
@@ -258,10 +262,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
         const T* xm = reinterpret_cast<const T*>(p.x) + map * HW;
         const DT* dm = reinterpret_cast<const DT*>(p.delta) + map * HW;
         const T* dym = reinterpret_cast<const T*>(p.dy) + map * HW;
+        const T* zm = reinterpret_cast<const T*>(p.z) + map * HW;          // GATE only
+        const T* ysm = reinterpret_cast<const T*>(p.y_scan) + map * HW;    // GATE only
 #pragma unroll
         for (int v = 0; v < CT; ++v) {
             const int i = min(band * RB + cell_r[v], H - 1);
             const size_t o = (size_t)i * W + (size_t)min(cb + cell_c[v], W - 1);
+            if constexpr (GATE) { rawz[v] = elem_bits(zm + o); raws[v] = elem_bits(ysm + o); }
             rawx[v] = elem_bits(xm + o);
             rawd[v] = elem_bits(dm + o);
             rawy[v] = elem_bits(dym + o);
@@ -316,7 +323,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan2d_bwd_shared_kernel(const Bwd
                 dl = in ? dl : 0.0f;
                 const float xv = widen(rawx[v], T{});
                 const float xe = (in && !m) ? xv : 0.0f;                 // select: nothing under the mask leaks
-                const float dyv = in ? widen(rawy[v], T{}) : 0.0f;
+                float dyv = in ? widen(rawy[v], T{}) : 0.0f;
+                if constexpr (GATE) {
+                    const float zv = widen(rawz[v], T{}), sg = logistic_f32(zv);
+                    if (in) store_elem(reinterpret_cast<T*>(p.dz) + map * HW + (size_t)(r0 + cell_r[v]) * W + (size_t)(cb + cell_c[v]),
+                                       dyv * widen(raws[v], T{}) * (sg * fmaf(zv, 1.0f - sg, 1.0f)));
+                    dyv *= zv * sg;
+                }
                 if (cell_ok[v]) {
                     float* row = ppj + cell_r[v] * PP_ROW + lds_colk<LG, K>(cell_c[v]);
                     row[0] = dl;

@@ -23,6 +23,7 @@ struct BwdKernels {
     bool ckpt_fast = true;                // W is a multiple of the checkpoint sweep's columns per lane
     bool shared = false;                  // main sweep of scan2d_bwd_shared.hpp
     BwdKernel main_panels = nullptr;      // its instantiation that takes column panels (wave-wide tiling of two states per lane)
+    BwdKernel main_gate = nullptr;        // its instantiation with the output gate's backward inside (softplus step, rows first)
     // checkpoint sweep run by the shared-producer forward kernel in its checkpoint mode (FwdArgs), with its tiling
     void (*ckpt_fwd)(const FwdArgs) = nullptr;
     int cf_LG = 0, cf_K = 0, cf_NW = 0, cf_NG = 0, cf_waves = 0, cf_RPB = 0;
@@ -62,6 +63,9 @@ inline BwdKernels lookup_bwd_shared_kernels(int LG, int K, int NW, int NG, int w
         r.main = fast ? scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, true, SP, CF>                 \
                       : scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, false, SP, CF>;               \
         r.RB = rb; r.shared = true;                                                                      \
+        if constexpr (SP && !CF)                                                                         \
+            r.main_gate = fast ? scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, true, true, false, false, true>       \
+                               : scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, false, true, false, false, true>;     \
         if constexpr (!CF && lg == 64 && k == 4 && nw == 2)                                              \
             r.main_panels = fast ? scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, true, SP, false, true>      \
                                  : scan2d_bwd_shared_kernel<T, lg, k, nw, ng, wv, rb, false, SP, false, true>;    \
