@@ -86,9 +86,12 @@ def test_workspace_query(lib):
     for dt, eb in ((0, 4), (1, 2)):
         d = lib.Desc(2, 8, 20, 40, 16, dt, 0)
         assert lib.workspace_bytes(d, lib.PASS_BWD_GATED) == lib.workspace_bytes(d, lib.PASS_BWD_SOFTPLUS) + ((2 * 8 * 20 * 40 * eb + 255) // 256) * 256
-        # the softplus backward keeps the step in the workspace (one fp32 map-sized buffer)
+        # the shared-producer sweeps (16 states here) apply the softplus themselves: no step buffer
+        assert lib.workspace_bytes(d, lib.PASS_BWD_SOFTPLUS) == lib.workspace_bytes(d, lib.PASS_BWD)
+        # the plain sweeps keep the step in the workspace (one fp32 map-sized buffer)
+        d5 = lib.Desc(2, 8, 20, 40, 5, dt, 0)
         extra = ((2 * 8 * 20 * 40 * 4 + 255) // 256) * 256 + 256      # and room behind it for reads past the last row
-        assert lib.workspace_bytes(d, lib.PASS_BWD_SOFTPLUS) == lib.workspace_bytes(d, lib.PASS_BWD) + extra
+        assert lib.workspace_bytes(d5, lib.PASS_BWD_SOFTPLUS) == lib.workspace_bytes(d5, lib.PASS_BWD) + extra
     assert lib.workspace_bytes(lib.Desc(1, 2, 8, 3000, 4, 0, 0), lib.PASS_BWD_GATED) > 0       # wide maps: column panels
     # columns first inside the kernels (a shared-producer tiling takes the shape): the workspace of the plain call;
     # through transposes otherwise (here: 5 states): the transposed copies (x, delta, y; Bm, Cm; mask) behind the
