@@ -572,6 +572,9 @@ SOFTPLUS_BWD_SHAPES = [
     (2, 5, 16, 14, 14, wl.F32, 0.2), (1, 6, 16, 21, 64, wl.F32, 0.3), (2, 3, 16, 9, 128, wl.BF16, 0.3),
     (1, 9, 16, 13, 192, wl.F32, 0.3), (1, 3, 16, 6, 250, wl.F32, 0.0), (1, 2, 8, 5, 600, wl.F32, 0.3),
     (3, 2, 40, 6, 30, wl.F32, 0.3), (1, 4, 5, 9, 13, wl.BF16, 0.3),
+    # softplus, chain rule and bias gradient inside the shared-producer sweeps: several bands and channels per workgroup,
+    # batch items (bias partials), a ragged 12-column width; and column panels (16 states), which keep the step kernel
+    (3, 20, 16, 23, 190, wl.F32, 0.3), (2, 9, 16, 11, 256, wl.BF16, 0.4), (1, 3, 16, 9, 520, wl.F32, 0.3),
 ]
 
 
@@ -633,6 +636,7 @@ GATED_SHAPES = [
     (1, 4, 5, 7, 45, wl.F32, 0.2),         # ragged last lane group, mask rows off 4-byte boundaries
     (1, 3, 16, 13, 192, wl.F32, 0.0),
     (1, 2, 8, 5, 600, wl.F32, 0.3),        # wider than one panel
+    (1, 3, 16, 9, 400, wl.BF16, 0.3),      # wave-wide groups with 8 columns per lane, gate inside the kernel
     (1, 16, 16, 64, 256, wl.BF16, 0.5),    # one map per workgroup, 4 rows per barrier
     (3, 2, 4, 6, 30, wl.F32, 0.3),
     (2, 3, 64, 11, 40, wl.F32, 0.3),       # all states in one lane: the lane that owns the columns applies the gate
@@ -676,6 +680,9 @@ GATED_BWD_SHAPES = [
     (2, 5, 16, 14, 14, wl.F32, 0.2), (1, 6, 16, 21, 64, wl.F32, 0.3), (2, 3, 16, 9, 128, wl.BF16, 0.3),
     (1, 9, 16, 13, 190, wl.F32, 0.3), (1, 3, 16, 6, 251, wl.F32, 0.0), (3, 2, 40, 6, 30, wl.F32, 0.3),
     (1, 4, 5, 9, 13, wl.BF16, 0.3), (1, 1, 16, 3, 5, wl.F32, 0.0),
+    # the gate's backward inside the shared-producer sweeps: 12-column and wave-wide tilings, several bands, batch items;
+    # and column panels, which keep the element-wise gate kernel
+    (2, 11, 16, 22, 192, wl.F32, 0.3), (2, 5, 16, 9, 250, wl.BF16, 0.3), (1, 3, 16, 7, 400, wl.F32, 0.2),
 ]
 
 
